@@ -1,0 +1,322 @@
+"""CPU oracle of the per-task MAML step over a DLRM-style model (float64, numpy).
+
+TEST INFRASTRUCTURE ONLY.  This file defines what the HIP path must compute; it
+is imported by tests/, by __graft_entry__.smoke() and by bench.py's
+cpu_baseline leg, never by the product package, and it shares no code with it.
+
+What it follows (G-Meta, Algorithm 1, worker i == task t; MAML after Finn et
+al. as the paper adopts it in Section 2):
+  * prefetch of the support and query embedding rows        (Alg. 1, prefetch step)
+  * inner forward L^Sup, local back-propagation on the looked-up rows xi^Sup and
+    on theta with step size alpha                            (Alg. 1, inner steps)
+  * overlap update: query rows that also occur in the support set take the
+    adapted value, all others keep the prefetched one        (Section 2.1.2)
+  * outer forward L^Query with (xi'^Query, theta')           (Alg. 1, outer forward)
+  * gradients of L^Query w.r.t. the META parameters, summed over tasks
+    (Alg. 1, the two global back-propagation steps; Section 2.1.3: the sum of
+    per-task gradients equals the gradient of the sum).
+The beta update itself is not part of the step: the step returns the summed
+gradients.
+
+Model f (the paper says only "embedding layer + dense layers", Section 2.1):
+  x_s = concat_f( sum_{r in bag(s,f)} xi_f[r] ) || dense_s
+  MLP with ReLU on hidden layers, one logit, L = mean over the set's samples of
+  the binary cross-entropy with logits.
+
+Readings where the paper is silent: loss is the MEAN over a set's samples; tasks
+are SUMMED; `inner_steps` repeats the inner update on the whole support set;
+order=1 drops the Hessian term; ReLU'(0) = 0; duplicate indices count with
+multiplicity; an empty bag pools to zero; the sparse output lists every row
+looked up by any support or query sample, ascending by global row id
+(field_base[f] + index).
+
+Pins (tests/test_oracle_*.py): central finite differences of the loss and of
+the meta-objective, K=0 and alpha=0 identities, the K=1 relation
+order2 = (I - alpha*H) order1 with H pinned by differences of the gradient,
+closed-form logistic regression, full-table brute force for the overlap update,
+task additivity, multiplicity, gradient-mass conservation, pure-Python loops on
+a tiny case and a library autograd (double backward) cross-check.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# model description and small helpers
+# --------------------------------------------------------------------------
+@dataclass
+class Model:
+    rows_per_field: Sequence[int]
+    emb_dim: int
+    n_dense: int
+    layer_dims: Sequence[int]          # d_0 .. d_L, d_0 = F*D + n_dense, d_L = 1
+
+    @property
+    def n_fields(self) -> int:
+        return len(self.rows_per_field)
+
+    @property
+    def field_base(self) -> np.ndarray:
+        return np.concatenate([[0], np.cumsum(np.asarray(self.rows_per_field, dtype=np.int64))])
+
+    @property
+    def n_layers(self) -> int:
+        return len(self.layer_dims) - 1
+
+
+def sigmoid(z):
+    return 0.5 * (1.0 + np.tanh(0.5 * z))
+
+
+def bce_with_logits(z, y):
+    """Per-sample binary cross-entropy on a logit, numerically stable form."""
+    return np.maximum(z, 0.0) - y * z + np.log1p(np.exp(-np.abs(z)))
+
+
+def lookup_rows(model: Model, s: Dict[str, np.ndarray], lo: int, hi: int):
+    """Global row id and bag id (relative to sample `lo`) of every lookup of samples [lo, hi)."""
+    F = model.n_fields
+    off = s["bag_offsets"]
+    p0, p1 = int(off[lo * F]), int(off[hi * F])
+    lens = np.diff(off[lo * F: hi * F + 1])
+    bag = np.repeat(np.arange((hi - lo) * F, dtype=np.int64), lens)
+    field = bag % F
+    rows = model.field_base[field] + s["indices"][p0:p1].astype(np.int64)
+    return rows, bag
+
+
+# --------------------------------------------------------------------------
+# the DLRM on one set of samples, with the embedding rows given as a dictionary
+# --------------------------------------------------------------------------
+def pool(model: Model, E: np.ndarray, loc: np.ndarray, bag: np.ndarray, n: int) -> np.ndarray:
+    """e[s,f] = sum over the bag's lookups of E[loc] (multiplicity counted); -> [n, F*D]."""
+    out = np.zeros((n * model.n_fields, model.emb_dim))
+    np.add.at(out, bag, E[loc])
+    return out.reshape(n, model.n_fields * model.emb_dim)
+
+
+def forward(x: np.ndarray, W: List[np.ndarray], b: List[np.ndarray]):
+    """a_0 = x; z_l = a_{l-1} W_l + b_l; a_l = relu(z_l) for l < L.  Returns ([a_0..a_{L-1}], z_L)."""
+    acts = [x]
+    L = len(W)
+    for l in range(L):
+        z = acts[-1] @ W[l] + b[l]
+        if l < L - 1:
+            acts.append(np.where(z > 0.0, z, 0.0))
+    return acts, z[:, 0]
+
+
+def set_loss(z: np.ndarray, y: np.ndarray) -> float:
+    return float(np.mean(bce_with_logits(z, y))) if len(y) else 0.0
+
+
+def backward(acts, z, y, W):
+    """Gradient of the mean BCE w.r.t. W_l, b_l and the input x.  Also returns the deltas."""
+    n = len(y)
+    L = len(W)
+    delta = ((sigmoid(z) - y) / max(n, 1))[:, None]
+    dW, db, deltas = [None] * L, [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        deltas[l] = delta
+        dW[l] = acts[l].T @ delta
+        db[l] = delta.sum(axis=0)
+        da = delta @ W[l].T
+        if l > 0:
+            delta = da * (acts[l] > 0.0)
+    return dW, db, da, deltas
+
+
+def hvp(acts, z, y, W, deltas, vW, vb, vx):
+    """Hessian of the mean BCE (w.r.t. W, b and the input x) times (vW, vb, vx).
+
+    Tangent (forward) pass through the forward AND the backward pass of the
+    network; ReLU has no second-derivative term.  Returns (hW, hb, hx).
+    """
+    n = len(y)
+    L = len(W)
+    sg = sigmoid(z)
+    # tangent of the forward pass
+    ta = [vx]
+    for l in range(L):
+        tz = ta[-1] @ W[l] + acts[l] @ vW[l] + vb[l]
+        if l < L - 1:
+            ta.append(tz * (acts[l + 1] > 0.0))
+    tdelta = (sg * (1.0 - sg) * tz[:, 0] / max(n, 1))[:, None]
+    hW, hb = [None] * L, [None] * L
+    for l in range(L - 1, -1, -1):
+        hW[l] = ta[l].T @ deltas[l] + acts[l].T @ tdelta
+        hb[l] = tdelta.sum(axis=0)
+        tda = tdelta @ W[l].T + deltas[l] @ vW[l].T
+        if l > 0:
+            tdelta = tda * (acts[l] > 0.0)
+    return hW, hb, tda
+
+
+# --------------------------------------------------------------------------
+# one task
+# --------------------------------------------------------------------------
+def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int, order: int,
+                   full_table: bool = False):
+    """MAML for task t.  Returns (L^Query, gW, gb, rows, gxi[rows]) w.r.t. the META parameters.
+
+    full_table=True copies the whole table into the task (brute force: phi_0 is
+    all of xi); the default keeps only the rows the task looks up.  Both must agree.
+    """
+    F, D = model.n_fields, model.emb_dim
+    FD = F * D
+    s_lo, s_hi = int(sup["task_offsets"][t]), int(sup["task_offsets"][t + 1])
+    q_lo, q_hi = int(qry["task_offsets"][t]), int(qry["task_offsets"][t + 1])
+    ns, nq = s_hi - s_lo, q_hi - q_lo
+    rows_s, bag_s = lookup_rows(model, sup, s_lo, s_hi)
+    rows_q, bag_q = lookup_rows(model, qry, q_lo, q_hi)
+    if full_table:
+        rows = np.arange(model.field_base[-1], dtype=np.int64)
+    else:
+        rows = np.unique(np.concatenate([rows_s, rows_q]))
+    loc_s = np.searchsorted(rows, rows_s)
+    loc_q = np.searchsorted(rows, rows_q)
+    ys = sup["labels"][s_lo:s_hi].astype(np.float64)
+    yq = qry["labels"][q_lo:q_hi].astype(np.float64)
+    dense_s = sup["dense"][s_lo:s_hi].astype(np.float64)
+    dense_q = qry["dense"][q_lo:q_hi].astype(np.float64)
+
+    # phi_0 = the meta parameters (task-local copies; the meta table is never written)
+    E = params["emb"][rows].astype(np.float64)
+    W = [w.astype(np.float64) for w in params["W"]]
+    b = [x.astype(np.float64) for x in params["b"]]
+
+    def rows_grad(dx, loc, bag):
+        g = np.zeros_like(E)
+        np.add.at(g, loc, dx[:, :FD].reshape(-1, D)[bag])
+        return g
+
+    # inner loop on the support set
+    tape = []
+    for _ in range(K):
+        x = np.concatenate([pool(model, E, loc_s, bag_s, ns), dense_s], axis=1)
+        acts, z = forward(x, W, b)
+        dW, db, dx, deltas = backward(acts, z, ys, W)
+        tape.append((acts, z, W, deltas))
+        gE = rows_grad(dx, loc_s, bag_s)
+        E = E - alpha * gE
+        W = [w - alpha * g for w, g in zip(W, dW)]
+        b = [v - alpha * g for v, g in zip(b, db)]
+
+    # outer forward/backward on the query set with the adapted parameters
+    xq = np.concatenate([pool(model, E, loc_q, bag_q, nq), dense_q], axis=1)
+    acts, z = forward(xq, W, b)
+    loss_q = set_loss(z, yq)
+    vW, vb, dx, _ = backward(acts, z, yq, W)
+    vE = rows_grad(dx, loc_q, bag_q)
+
+    # chain back through the inner steps: v_k = v_{k+1} - alpha * H_k v_{k+1}
+    if order == 2:
+        for acts_k, z_k, W_k, deltas_k in reversed(tape):
+            vx = np.concatenate([pool(model, vE, loc_s, bag_s, ns), np.zeros_like(dense_s)], axis=1)
+            hW, hb, hx = hvp(acts_k, z_k, ys, W_k, deltas_k, vW, vb, vx)
+            hE = rows_grad(hx, loc_s, bag_s)
+            vW = [v - alpha * h for v, h in zip(vW, hW)]
+            vb = [v - alpha * h for v, h in zip(vb, hb)]
+            vE = vE - alpha * hE
+    elif order != 1:
+        raise ValueError("order must be 1 or 2")
+    if full_table:
+        touched = np.unique(np.concatenate([rows_s, rows_q]))
+        return loss_q, vW, vb, touched, vE[touched]
+    return loss_q, vW, vb, rows, vE
+
+
+# --------------------------------------------------------------------------
+# the whole step
+# --------------------------------------------------------------------------
+def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
+              tasks: Optional[Sequence[int]] = None, full_table: bool = False):
+    """Sum of the per-task meta-gradients (Alg. 1, global back-propagation steps).
+
+    Returns dict(loss, task_loss[T], dW[l], db[l], emb_rows (ascending unique
+    global rows looked up by any sample), emb_grad[len(emb_rows), D]).
+    """
+    T = len(sup["task_offsets"]) - 1
+    tasks = list(range(T)) if tasks is None else list(tasks)
+    L = model.n_layers
+    gW = [np.zeros((model.layer_dims[l], model.layer_dims[l + 1])) for l in range(L)]
+    gb = [np.zeros(model.layer_dims[l + 1]) for l in range(L)]
+    task_loss = np.zeros(len(tasks))
+    parts_rows, parts_grad = [], []
+    for i, t in enumerate(tasks):
+        lq, vW, vb, rows, vE = task_meta_grad(model, params, sup, qry, t, alpha, K, order, full_table)
+        task_loss[i] = lq
+        for l in range(L):
+            gW[l] += vW[l]
+            gb[l] += vb[l]
+        parts_rows.append(rows)
+        parts_grad.append(vE)
+    if parts_rows:
+        all_rows = np.concatenate(parts_rows)
+        emb_rows, inv = np.unique(all_rows, return_inverse=True)
+        emb_grad = np.zeros((len(emb_rows), model.emb_dim))
+        np.add.at(emb_grad, inv, np.concatenate(parts_grad))
+    else:
+        emb_rows, emb_grad = np.zeros(0, np.int64), np.zeros((0, model.emb_dim))
+    return dict(loss=float(task_loss.sum()), task_loss=task_loss, dW=gW, db=gb,
+                emb_rows=emb_rows, emb_grad=emb_grad)
+
+
+# --------------------------------------------------------------------------
+# integer side of the step: what the index preparation must produce, exactly
+# --------------------------------------------------------------------------
+def index_prep(model: Model, sup, qry):
+    """The unique integer structures behind the overlap update and the sparse gradient.
+
+    Per (task, field), in task-major then field order:
+      slot_counts[T*F]    number of distinct rows the task's SUPPORT lookups touch in the field
+      slot_rows           those rows (global ids), ascending within each (task, field)
+      sup_slot[nnz_sup]   for every support lookup, the rank of its row in its (task, field) list
+      qry_slot[nnz_qry]   for every query lookup, that rank if the row is in the task's
+                          support list for the field, else -1   (the overlap join)
+    Over the whole batch:
+      emb_rows            ascending distinct global rows over all support and query lookups
+      seg_counts          number of lookups (support + query, all tasks) of each of them
+    """
+    F = model.n_fields
+    T = len(sup["task_offsets"]) - 1
+    sup_slot = np.zeros(len(sup["indices"]), dtype=np.int32)
+    qry_slot = np.full(len(qry["indices"]), -1, dtype=np.int32)
+    slot_counts = np.zeros(T * F, dtype=np.int64)
+    slot_rows = []
+    all_rows = []
+    for t in range(T):
+        s_lo, s_hi = int(sup["task_offsets"][t]), int(sup["task_offsets"][t + 1])
+        q_lo, q_hi = int(qry["task_offsets"][t]), int(qry["task_offsets"][t + 1])
+        rows_s, bag_s = lookup_rows(model, sup, s_lo, s_hi)
+        rows_q, bag_q = lookup_rows(model, qry, q_lo, q_hi)
+        all_rows += [rows_s, rows_q]
+        ps, pq = int(sup["bag_offsets"][s_lo * F]), int(qry["bag_offsets"][q_lo * F])
+        for f in range(F):
+            ms, mq = (bag_s % F) == f, (bag_q % F) == f
+            u = np.unique(rows_s[ms])
+            slot_counts[t * F + f] = len(u)
+            slot_rows.append(u)
+            sup_slot[ps + np.nonzero(ms)[0]] = np.searchsorted(u, rows_s[ms])
+            if len(u):
+                pos = np.searchsorted(u, rows_q[mq])
+                hit = (pos < len(u)) & (u[np.minimum(pos, len(u) - 1)] == rows_q[mq])
+                qry_slot[pq + np.nonzero(mq)[0]] = np.where(hit, pos, -1)
+    cat = np.concatenate(all_rows) if all_rows else np.zeros(0, np.int64)
+    emb_rows, seg_counts = np.unique(cat, return_counts=True)
+    return dict(slot_counts=slot_counts,
+                slot_rows=np.concatenate(slot_rows) if slot_rows else np.zeros(0, np.int64),
+                sup_slot=sup_slot, qry_slot=qry_slot,
+                emb_rows=emb_rows.astype(np.int64), seg_counts=seg_counts.astype(np.int64))
+
+
+def gather_pool(model: Model, emb: np.ndarray, s) -> np.ndarray:
+    """Pooled model input of every sample of a set: [n, F*D + n_dense] (Alg. 1, prefetch step)."""
+    n = int(s["task_offsets"][-1])
+    rows, bag = lookup_rows(model, s, 0, n)
+    x = pool(model, emb.astype(np.float64), rows, bag, n)
+    return np.concatenate([x, s["dense"].astype(np.float64)], axis=1)
