@@ -1,0 +1,135 @@
+/*
+ * gmeta.h -- C ABI of the MI355X-native per-task MAML step over a DLRM-style model.
+ *
+ * What is computed (G-Meta, Algorithm 1, with "worker i" read as "task t"; MAML as
+ * the paper adopts it in Section 2):
+ *   prefetch of support and query embedding rows in one pass        (Alg. 1, prefetch step; Sec. 2.1.1)
+ *   inner forward L^Sup, local back-propagation on the looked-up
+ *   rows and on theta with step alpha, repeated inner_steps times    (Alg. 1, inner steps)
+ *   overlap update of the query rows that the support set adapted    (Alg. 1, overlap step; Sec. 2.1.2)
+ *   outer forward L^Query with the adapted parameters                (Alg. 1, outer forward)
+ *   gradients of L^Query w.r.t. the META parameters, summed over
+ *   tasks: dense part (theta) and sparse part (xi)                   (Alg. 1, global back-propagation
+ *                                                                     steps; Sec. 2.1.3 sum rule)
+ * The beta update itself is gm_scatter_add (sparse) / the caller's (dense).
+ *
+ * Model: x_s = concat_f( sum_{r in bag(s,f)} xi_f[r] ) || dense_s ; MLP d_0 -> ... -> d_L = 1 with
+ * ReLU on hidden layers; loss = mean over a set's samples of the binary cross-entropy with logits.
+ * Tasks are summed.  order = 1 drops the Hessian-vector term, order = 2 keeps it.
+ *
+ * Pointer convention: every pointer below is marked HOST or DEVICE.  DEVICE memory is allocated
+ * and owned by the caller; the library never frees or reallocates it and never writes to inputs.
+ * All calls of one context are issued on the HIP stream given at gm_create and every entry point
+ * returns after that stream has drained (results are valid on return).
+ * Return value: GM_OK (0) or a negative gm_status; gm_last_error() gives a message.  On error the
+ * outputs are unspecified, but no out-of-bounds access is made: indices, offsets and capacities are
+ * checked on the device before they are used.
+ */
+#ifndef GMETA_H
+#define GMETA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GM_OK = 0,
+    GM_ERR_ARG = -1,        /* null pointer, negative size, unsupported shape, bad order          */
+    GM_ERR_INDEX = -2,      /* an index is outside its table, or offsets are not monotone          */
+    GM_ERR_CAPACITY = -3,   /* emb_rows_capacity too small, or a (task, field) exceeds the limits  */
+    GM_ERR_WORKSPACE = -4,  /* the context's workspace cannot hold even one task                   */
+    GM_ERR_HIP = -5         /* a HIP runtime call failed                                           */
+} gm_status;
+
+typedef struct gm_ctx gm_ctx; /* opaque; owns only its workspace */
+
+/* Model shape.  HOST struct, HOST arrays (copied by gm_create). */
+typedef struct {
+    int32_t n_fields;              /* F sparse fields                                       */
+    const int64_t* rows_per_field; /* HOST [F] rows of each field's table                   */
+    int32_t emb_dim;               /* D, a multiple of 4, at most 256                       */
+    int32_t n_dense;               /* dense features per sample                             */
+    int32_t n_layers;              /* L                                                     */
+    const int32_t* layer_dims;     /* HOST [L+1] d_0..d_L; d_0 = F*D + n_dense, d_L = 1     */
+    int32_t mlp_dtype;             /* 0: fp32 GEMMs; 1: bf16 operands, fp32 accumulation    */
+} gm_model_desc;
+
+/* One set (support or query) of all tasks, CSR over (sample, field) bags. */
+typedef struct {
+    int64_t n_samples;           /* over all tasks                                               */
+    int64_t nnz;                 /* total lookups = bag_offsets[n_samples*F]                     */
+    const int64_t* task_offsets; /* HOST   [T+1] sample range of each task, task_offsets[0] = 0  */
+    const int64_t* bag_offsets;  /* DEVICE [n_samples*F+1], sample-major, field-minor            */
+    const int32_t* indices;      /* DEVICE [nnz] row within its field's table                    */
+    const float* dense;          /* DEVICE [n_samples, n_dense] row-major                        */
+    const float* labels;         /* DEVICE [n_samples] in {0,1}                                  */
+} gm_set;
+
+/* Meta-parameters (never written). */
+typedef struct {
+    const float* emb;       /* DEVICE [sum rows_per_field, D] row-major, tables field after field */
+    const float* const* W;  /* HOST array [L] of DEVICE pointers, W_l is [d_{l-1}, d_l] row-major */
+    const float* const* b;  /* HOST array [L] of DEVICE pointers, b_l is [d_l]                    */
+} gm_params;
+
+/* Outputs of gm_meta_step. */
+typedef struct {
+    float* const* dW;          /* HOST array [L] of DEVICE pointers, same shapes as W            */
+    float* const* db;          /* HOST array [L] of DEVICE pointers, same shapes as b            */
+    int64_t* emb_rows;         /* DEVICE [capacity] ascending distinct global rows (field_base[f]
+                                  + index) looked up by any support or query sample             */
+    float* emb_grad;           /* DEVICE [capacity, D] gradient of the listed rows               */
+    int64_t* n_emb_rows;       /* DEVICE scalar: number of rows listed                           */
+    int64_t emb_rows_capacity; /* rows that emb_rows / emb_grad can hold                         */
+    float* task_loss;          /* DEVICE [T] per-task L^Query, or NULL                           */
+} gm_grads;
+
+/* Creates a context on `device` that enqueues on `hip_stream` (a hipStream_t, or NULL for the
+ * default stream) and owns a workspace of `workspace_bytes` (see gm_workspace_bytes). */
+int gm_create(gm_ctx** ctx, const gm_model_desc* model, int device, void* hip_stream,
+              size_t workspace_bytes);
+void gm_destroy(gm_ctx* ctx);
+const char* gm_last_error(const gm_ctx* ctx);
+
+/* Workspace that lets a batch of this size run in ONE wave of tasks.  A smaller workspace is
+ * legal: gm_meta_step then processes the tasks in several waves (Alg. 1 treats tasks independently). */
+size_t gm_workspace_bytes(const gm_model_desc* model, int32_t n_tasks, int64_t n_support,
+                          int64_t n_query, int64_t nnz_support, int64_t nnz_query,
+                          int32_t inner_steps, int32_t order);
+
+/* The whole step (Alg. 1 from the prefetch step to the two global back-propagation steps, without
+ * the beta update).  loss: DEVICE scalar = sum_t L^Query_t.  order in {1,2}; inner_steps >= 0. */
+int gm_meta_step(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_set* query,
+                 const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
+                 float* loss, gm_grads* out);
+
+/* table[rows[i], :] += scale * grad[i, :]  (Alg. 1, global back-propagation on xi, on one shard,
+ * with scale = -beta).  rows must be distinct (as gm_meta_step emits them).  All DEVICE. */
+int gm_scatter_add(gm_ctx* ctx, float* table, const int64_t* rows, const float* grad,
+                   int64_t n_rows, float scale);
+
+/* The prefetch step alone: pooled model input of every sample of `set`,
+ * x[s, :] = [ sum-pooled rows of field 0 | ... | field F-1 | dense_s ], DEVICE [n_samples, d_0]. */
+int gm_gather_pool(gm_ctx* ctx, int32_t n_tasks, const gm_set* set, const float* emb, float* x);
+
+/* The integer side of the step alone (the overlap join of Sec. 2.1.2 and the row routing of the
+ * sparse gradient), for exact comparison.  All outputs DEVICE, sized by the caller:
+ *   slot_counts [T*F]       distinct rows of the task's SUPPORT lookups in the field
+ *   slot_rows   [nnz_sup]   those rows (global ids) ascending per (task, field), packed in
+ *                           (task, field) order; first sum(slot_counts) entries are valid
+ *   sup_slot    [nnz_sup]   rank of each support lookup's row in its (task, field) list
+ *   qry_slot    [nnz_qry]   that rank for query lookups whose row is in the list, else -1
+ *   emb_rows    [capacity], seg_counts [capacity], n_emb_rows: ascending distinct global rows over
+ *                           all lookups, and how many lookups hit each */
+int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_set* query,
+                  int64_t* slot_counts, int64_t* slot_rows, int32_t* sup_slot, int32_t* qry_slot,
+                  int64_t* emb_rows, int64_t* seg_counts, int64_t* n_emb_rows,
+                  int64_t emb_rows_capacity);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GMETA_H */

@@ -1,0 +1,224 @@
+"""ctypes binding of libgmeta.so: argument marshalling only.
+
+Every step of the MAML-DLRM path runs inside the library's HIP kernels; PyTorch
+is used here for device memory (torch.empty on the GPU) and nothing else.
+There is no CPU fallback: if the shared library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgmeta.so")
+
+GM_OK, GM_ERR_ARG, GM_ERR_INDEX, GM_ERR_CAPACITY, GM_ERR_WORKSPACE, GM_ERR_HIP = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ["gm_create", "gm_destroy", "gm_last_error", "gm_workspace_bytes", "gm_meta_step",
+           "gm_scatter_add", "gm_gather_pool", "gm_index_prep"]
+
+
+class gm_model_desc(C.Structure):
+    _fields_ = [("n_fields", C.c_int32), ("rows_per_field", C.POINTER(C.c_int64)),
+                ("emb_dim", C.c_int32), ("n_dense", C.c_int32), ("n_layers", C.c_int32),
+                ("layer_dims", C.POINTER(C.c_int32)), ("mlp_dtype", C.c_int32)]
+
+
+class gm_set(C.Structure):
+    _fields_ = [("n_samples", C.c_int64), ("nnz", C.c_int64), ("task_offsets", C.POINTER(C.c_int64)),
+                ("bag_offsets", C.c_void_p), ("indices", C.c_void_p), ("dense", C.c_void_p),
+                ("labels", C.c_void_p)]
+
+
+class gm_params(C.Structure):
+    _fields_ = [("emb", C.c_void_p), ("W", C.POINTER(C.c_void_p)), ("b", C.POINTER(C.c_void_p))]
+
+
+class gm_grads(C.Structure):
+    _fields_ = [("dW", C.POINTER(C.c_void_p)), ("db", C.POINTER(C.c_void_p)), ("emb_rows", C.c_void_p),
+                ("emb_grad", C.c_void_p), ("n_emb_rows", C.c_void_p), ("emb_rows_capacity", C.c_int64),
+                ("task_loss", C.c_void_p)]
+
+
+class GMetaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"gmeta error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libgmeta.so (built in-tree by paper_2401_04338_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is not built; run `python -m paper_2401_04338_amd.build` (there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    lib.gm_create.restype = C.c_int
+    lib.gm_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(gm_model_desc), C.c_int, C.c_void_p, C.c_size_t]
+    lib.gm_destroy.restype = None
+    lib.gm_destroy.argtypes = [C.c_void_p]
+    lib.gm_last_error.restype = C.c_char_p
+    lib.gm_last_error.argtypes = [C.c_void_p]
+    lib.gm_workspace_bytes.restype = C.c_size_t
+    lib.gm_workspace_bytes.argtypes = [C.POINTER(gm_model_desc), C.c_int32, C.c_int64, C.c_int64, C.c_int64,
+                                       C.c_int64, C.c_int32, C.c_int32]
+    lib.gm_meta_step.restype = C.c_int
+    lib.gm_meta_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set),
+                                 C.POINTER(gm_params), C.c_float, C.c_int32, C.c_int32, C.c_void_p,
+                                 C.POINTER(gm_grads)]
+    lib.gm_scatter_add.restype = C.c_int
+    lib.gm_scatter_add.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float]
+    lib.gm_gather_pool.restype = C.c_int
+    lib.gm_gather_pool.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.c_void_p, C.c_void_p]
+    lib.gm_index_prep.restype = C.c_int
+    lib.gm_index_prep.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set)] + [C.c_void_p] * 7 + [C.c_int64]
+    _lib = lib
+    return lib
+
+
+def _model_desc(n_fields, rows_per_field, emb_dim, n_dense, layer_dims, mlp_dtype):
+    rows = (C.c_int64 * max(n_fields, 1))(*[int(r) for r in rows_per_field])
+    dims = (C.c_int32 * len(layer_dims))(*[int(d) for d in layer_dims])
+    m = gm_model_desc(n_fields, rows, emb_dim, n_dense, len(layer_dims) - 1, dims, mlp_dtype)
+    m._keep = (rows, dims)
+    return m
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _set_struct(s) -> gm_set:
+    """s: an object with task_offsets (host numpy int64), bag_offsets, indices, dense, labels (device tensors)."""
+    toff = np.ascontiguousarray(np.asarray(s.task_offsets, dtype=np.int64))
+    st = gm_set(int(toff[-1]), int(s.indices.numel()), toff.ctypes.data_as(C.POINTER(C.c_int64)),
+                _ptr(s.bag_offsets), _ptr(s.indices), _ptr(s.dense), _ptr(s.labels))
+    st._keep = (toff, s)
+    return st
+
+
+class GMeta:
+    """One context of the library: model shape + workspace on one GPU."""
+
+    def __init__(self, n_fields: int, rows_per_field: Sequence[int], emb_dim: int, n_dense: int,
+                 layer_dims: Sequence[int], mlp_dtype: int = 0, device: int = 0,
+                 workspace_bytes: int = 1 << 30, stream: Optional[int] = None):
+        self.lib = load_library()
+        self.n_fields, self.emb_dim, self.n_dense = n_fields, emb_dim, n_dense
+        self.layer_dims = list(layer_dims)
+        self.rows_per_field = list(rows_per_field)
+        self.device = torch.device("cuda", device)
+        self._desc = _model_desc(n_fields, rows_per_field, emb_dim, n_dense, layer_dims, mlp_dtype)
+        self._ctx = C.c_void_p()
+        rc = self.lib.gm_create(C.byref(self._ctx), C.byref(self._desc), device,
+                                C.c_void_p(stream) if stream else None, workspace_bytes)
+        if rc != GM_OK:
+            msg = self.lib.gm_last_error(self._ctx).decode() if self._ctx else "gm_create failed"
+            if self._ctx:
+                self.lib.gm_destroy(self._ctx)
+                self._ctx = C.c_void_p()
+            raise GMetaError(rc, msg)
+
+    @classmethod
+    def from_config(cls, cfg, device: int = 0, workspace_bytes: int = 1 << 30, stream=None, mlp_dtype=None):
+        return cls(cfg.n_fields, [cfg.rows_per_field] * cfg.n_fields, cfg.emb_dim, cfg.n_dense, cfg.layer_dims,
+                   cfg.mlp_dtype if mlp_dtype is None else mlp_dtype, device, workspace_bytes, stream)
+
+    def workspace_bytes(self, n_tasks, n_support, n_query, nnz_support, nnz_query, inner_steps, order) -> int:
+        return int(self.lib.gm_workspace_bytes(C.byref(self._desc), n_tasks, n_support, n_query, nnz_support,
+                                               nnz_query, inner_steps, order))
+
+    def close(self):
+        if getattr(self, "_ctx", None):
+            self.lib.gm_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != GM_OK:
+            raise GMetaError(rc, self.lib.gm_last_error(self._ctx).decode())
+
+    # ------------------------------------------------------------------ entry points
+    def alloc_outputs(self, n_tasks: int, emb_rows_capacity: int) -> Dict[str, object]:
+        dev, L = self.device, len(self.layer_dims) - 1
+        return dict(
+            loss=torch.empty(1, dtype=torch.float32, device=dev),
+            task_loss=torch.empty(max(n_tasks, 1), dtype=torch.float32, device=dev),
+            dW=[torch.empty(self.layer_dims[l], self.layer_dims[l + 1], dtype=torch.float32, device=dev) for l in range(L)],
+            db=[torch.empty(self.layer_dims[l + 1], dtype=torch.float32, device=dev) for l in range(L)],
+            emb_rows=torch.empty(max(emb_rows_capacity, 1), dtype=torch.int64, device=dev),
+            emb_grad=torch.empty(max(emb_rows_capacity, 1), self.emb_dim, dtype=torch.float32, device=dev),
+            n_emb_rows=torch.zeros(1, dtype=torch.int64, device=dev),
+            capacity=emb_rows_capacity)
+
+    def meta_step(self, support, query, params, inner_lr: float, inner_steps: int, order: int,
+                  out: Optional[Dict[str, object]] = None, emb_rows_capacity: Optional[int] = None):
+        """gm_meta_step.  support/query: SetData-like; params: object with emb, W[], b[] device tensors."""
+        n_tasks = len(support.task_offsets) - 1
+        if out is None:
+            cap = emb_rows_capacity
+            if cap is None:
+                cap = min(int(support.indices.numel() + query.indices.numel()), int(sum(self.rows_per_field)))
+            out = self.alloc_outputs(n_tasks, cap)
+        L = len(self.layer_dims) - 1
+        ss, qs = _set_struct(support), _set_struct(query)
+        Wp = (C.c_void_p * L)(*[w.data_ptr() for w in params.W])
+        bp = (C.c_void_p * L)(*[x.data_ptr() for x in params.b])
+        ps = gm_params(_ptr(params.emb), Wp, bp)
+        dWp = (C.c_void_p * L)(*[w.data_ptr() for w in out["dW"]])
+        dbp = (C.c_void_p * L)(*[x.data_ptr() for x in out["db"]])
+        gs = gm_grads(dWp, dbp, _ptr(out["emb_rows"]), _ptr(out["emb_grad"]), _ptr(out["n_emb_rows"]),
+                      int(out["capacity"]), _ptr(out["task_loss"]))
+        rc = self.lib.gm_meta_step(self._ctx, n_tasks, C.byref(ss), C.byref(qs), C.byref(ps), float(inner_lr),
+                                   int(inner_steps), int(order), _ptr(out["loss"]), C.byref(gs))
+        self._check(rc)
+        return out
+
+    def gather_pool(self, set_, emb: torch.Tensor) -> torch.Tensor:
+        n_tasks = len(set_.task_offsets) - 1
+        st = _set_struct(set_)
+        x = torch.empty(max(st.n_samples, 1), self.layer_dims[0], dtype=torch.float32, device=self.device)
+        self._check(self.lib.gm_gather_pool(self._ctx, n_tasks, C.byref(st), _ptr(emb), _ptr(x)))
+        return x[: st.n_samples]
+
+    def index_prep(self, support, query, emb_rows_capacity: Optional[int] = None):
+        n_tasks = len(support.task_offsets) - 1
+        ss, qs = _set_struct(support), _set_struct(query)
+        dev, F = self.device, self.n_fields
+        cap = emb_rows_capacity
+        if cap is None:
+            cap = min(ss.nnz + qs.nnz, int(sum(self.rows_per_field)))
+        o = dict(slot_counts=torch.zeros(max(n_tasks * F, 1), dtype=torch.int64, device=dev),
+                 slot_rows=torch.zeros(max(ss.nnz, 1), dtype=torch.int64, device=dev),
+                 sup_slot=torch.zeros(max(ss.nnz, 1), dtype=torch.int32, device=dev),
+                 qry_slot=torch.zeros(max(qs.nnz, 1), dtype=torch.int32, device=dev),
+                 emb_rows=torch.zeros(max(cap, 1), dtype=torch.int64, device=dev),
+                 seg_counts=torch.zeros(max(cap, 1), dtype=torch.int64, device=dev),
+                 n_emb_rows=torch.zeros(1, dtype=torch.int64, device=dev))
+        rc = self.lib.gm_index_prep(self._ctx, n_tasks, C.byref(ss), C.byref(qs), _ptr(o["slot_counts"]),
+                                    _ptr(o["slot_rows"]), _ptr(o["sup_slot"]), _ptr(o["qry_slot"]),
+                                    _ptr(o["emb_rows"]), _ptr(o["seg_counts"]), _ptr(o["n_emb_rows"]), cap)
+        self._check(rc)
+        n = int(o["n_emb_rows"].item())
+        ns = int(o["slot_counts"][: n_tasks * F].sum().item())
+        return dict(slot_counts=o["slot_counts"][: n_tasks * F], slot_rows=o["slot_rows"][:ns],
+                    sup_slot=o["sup_slot"][: ss.nnz], qry_slot=o["qry_slot"][: qs.nnz],
+                    emb_rows=o["emb_rows"][:n], seg_counts=o["seg_counts"][:n])
+
+    def scatter_add(self, table: torch.Tensor, rows: torch.Tensor, grad: torch.Tensor, scale: float):
+        self._check(self.lib.gm_scatter_add(self._ctx, _ptr(table), _ptr(rows), _ptr(grad), int(rows.numel()),
+                                            float(scale)))

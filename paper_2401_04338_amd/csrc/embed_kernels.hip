@@ -1,0 +1,244 @@
+// Embedding side of the MAML step (G-Meta Alg. 1): the one-pass prefetch of support and query rows
+// with sum pooling (prefetch step, Sec. 2.1.1), the task-local row updates and the overlap update
+// (inner steps on xi^Sup, Sec. 2.1.2), and the segment reduction that coalesces the sparse
+// meta-gradient (global back-propagation on xi).  All HBM-bound: rows are read as float4 by groups of
+// D/4 lanes so that one wavefront keeps several independent row reads in flight.
+#include "gm_internal.h"
+
+__device__ __forceinline__ bf16_t f2bf(float x) {  // round to nearest even
+    u32 u = __builtin_bit_cast(u32, x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ void store_bf4(bf16_t* dst, float4 v) {
+    uint2 o;
+    o.x = (u32)f2bf(v.x) | ((u32)f2bf(v.y) << 16);
+    o.y = (u32)f2bf(v.z) | ((u32)f2bf(v.w) << 16);
+    *reinterpret_cast<uint2*>(dst) = o;
+}
+
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+
+// ------------------------------------------------------------------------------------------------
+// prefetch + sum pooling: x[s, f*D:(f+1)*D] = sum over bag(s,f) of emb[field_base[f] + index]
+// ------------------------------------------------------------------------------------------------
+__global__ void gather_pool_kernel(int F, int D, int LG, const int64_t* __restrict__ field_base,
+                                   const int64_t* __restrict__ bag_offsets, const int32_t* __restrict__ indices,
+                                   const float* __restrict__ emb, int64_t sample0, int64_t n_bags, float* x, int ldx,
+                                   bf16_t* x_bf) {
+    const int groups_per_block = blockDim.x / LG;
+    const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
+    if (g_in_block >= groups_per_block) return;
+    const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
+    const float4* emb4 = reinterpret_cast<const float4*>(emb);
+    for (int64_t bag = (int64_t)blockIdx.x * groups_per_block + g_in_block; bag < n_bags; bag += n_groups) {
+        const int64_t s = bag / F;
+        const int f = (int)(bag - s * F);
+        const int64_t gb = sample0 * F + bag;
+        const int64_t p0 = bag_offsets[gb], p1 = bag_offsets[gb + 1];
+        const int64_t fb = field_base[f];
+        float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
+        int64_t p = p0;
+        for (; p + 4 <= p1; p += 4) {
+            const int64_t r0 = fb + indices[p], r1 = fb + indices[p + 1], r2 = fb + indices[p + 2], r3 = fb + indices[p + 3];
+            const float4 v0 = emb4[r0 * LG + l], v1 = emb4[r1 * LG + l], v2 = emb4[r2 * LG + l], v3 = emb4[r3 * LG + l];
+            acc0 = add4(add4(acc0, v0), v1);   // fixed order: the bag's lookups left to right in two lanes of sums
+            acc1 = add4(add4(acc1, v2), v3);
+        }
+        for (; p < p1; ++p) acc0 = add4(acc0, emb4[(fb + indices[p]) * LG + l]);
+        const float4 acc = add4(acc0, acc1);
+        const int64_t o = s * ldx + (int64_t)f * D + l * 4;
+        *reinterpret_cast<float4*>(x + o) = acc;
+        if (x_bf) store_bf4(x_bf + o, acc);
+    }
+}
+
+// dense features and zero padding behind the pooled fields
+__global__ void dense_tail_kernel(int FD, int n_dense, const float* __restrict__ dense, int64_t sample0,
+                                  int64_t n_samples, float* x, int ldx, bf16_t* x_bf) {
+    const int tail = ldx - FD;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_samples * tail) return;
+    const int64_t s = i / tail;
+    const int c = (int)(i - s * tail);
+    const float v = (dense && c < n_dense) ? dense[(sample0 + s) * n_dense + c] : 0.f;
+    x[s * ldx + FD + c] = v;
+    if (x_bf) x_bf[s * ldx + FD + c] = f2bf(v);
+}
+
+static inline unsigned pool_grid(int64_t n_bags, int groups_per_block) {
+    int64_t nb = (n_bags + groups_per_block - 1) / groups_per_block;
+    const int64_t cap = 256 * 32;  // grid-stride beyond 32 blocks per CU
+    if (nb > cap) nb = cap;
+    if (nb < 1) nb = 1;
+    return (unsigned)nb;
+}
+
+void launch_gather_pool(hipStream_t st, int F, int D, int n_dense, const int64_t* field_base,
+                        const int64_t* bag_offsets, const int32_t* indices, const float* dense, const float* emb,
+                        int64_t sample0, int64_t n_samples, float* x, int ldx, bf16_t* x_bf) {
+    if (n_samples <= 0) return;
+    const int LG = D / 4;
+    const int64_t n_bags = n_samples * F;
+    if (n_bags > 0)
+        hipLaunchKernelGGL(gather_pool_kernel, dim3(pool_grid(n_bags, 256 / LG)), dim3(256), 0, st, F, D, LG, field_base,
+                           bag_offsets, indices, emb, sample0, n_bags, x, ldx, x_bf);
+    const int64_t nt = n_samples * (ldx - F * D);
+    if (nt > 0)
+        hipLaunchKernelGGL(dense_tail_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, st, F * D, n_dense, dense,
+                           sample0, n_samples, x, ldx, x_bf);
+}
+
+// ------------------------------------------------------------------------------------------------
+// pooling over a task-local slot table (row deltas, or a direction's row part)
+// ------------------------------------------------------------------------------------------------
+__global__ void pool_slots_kernel(int F, int D, int LG, const int64_t* __restrict__ bag_offsets, int64_t sample0,
+                                  int64_t lookup0, int64_t n_bags, const int32_t* __restrict__ sample_task,
+                                  const int32_t* __restrict__ slot_of_lookup, const u32* __restrict__ tf_base,
+                                  const float* __restrict__ table, const float* x_base, float* x_out, int ldx,
+                                  bf16_t* x_bf) {
+    const int groups_per_block = blockDim.x / LG;
+    const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
+    if (g_in_block >= groups_per_block) return;
+    const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
+    const float4* tab4 = reinterpret_cast<const float4*>(table);
+    for (int64_t bag = (int64_t)blockIdx.x * groups_per_block + g_in_block; bag < n_bags; bag += n_groups) {
+        const int64_t s = bag / F;
+        const int f = (int)(bag - s * F);
+        const int64_t gb = sample0 * F + bag;
+        const int64_t p0 = bag_offsets[gb] - lookup0, p1 = bag_offsets[gb + 1] - lookup0;
+        const int64_t base = tf_base[(int64_t)sample_task[s] * F + f];
+        const int64_t o = s * ldx + (int64_t)f * D + l * 4;
+        float4 acc = x_base ? *reinterpret_cast<const float4*>(x_base + o) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int64_t p = p0; p < p1; ++p) {
+            const int32_t slot = slot_of_lookup[p];
+            if (slot >= 0) acc = add4(acc, tab4[(base + slot) * LG + l]);
+        }
+        if (x_out) *reinterpret_cast<float4*>(x_out + o) = acc;
+        if (x_bf) store_bf4(x_bf + o, acc);
+    }
+}
+
+__global__ void copy_tail_kernel(int FD, const float* x_base, int64_t n_samples, float* x_out, int ldx, bf16_t* x_bf) {
+    const int tail = ldx - FD;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_samples * tail) return;
+    const int64_t s = i / tail;
+    const int c = (int)(i - s * tail);
+    const float v = x_base ? x_base[s * ldx + FD + c] : 0.f;
+    if (x_out) x_out[s * ldx + FD + c] = v;
+    if (x_bf) x_bf[s * ldx + FD + c] = f2bf(v);
+}
+
+void launch_pool_slots(hipStream_t st, int F, int D, const int64_t* bag_offsets, int64_t sample0, int64_t lookup0,
+                       int64_t n_samples, const int32_t* sample_task, const int32_t* slot_of_lookup,
+                       const u32* tf_base, const float* table, const float* x_base, float* x_out, int ldx,
+                       bf16_t* x_bf) {
+    if (n_samples <= 0) return;
+    const int LG = D / 4;
+    const int64_t n_bags = n_samples * F;
+    if (n_bags > 0)
+        hipLaunchKernelGGL(pool_slots_kernel, dim3(pool_grid(n_bags, 256 / LG)), dim3(256), 0, st, F, D, LG, bag_offsets,
+                           sample0, lookup0, n_bags, sample_task, slot_of_lookup, tf_base, table, x_base, x_out, ldx, x_bf);
+    const int64_t nt = n_samples * (ldx - F * D);
+    if (nt > 0 && x_base != x_out)
+        hipLaunchKernelGGL(copy_tail_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, st, F * D, x_base,
+                           n_samples, x_out, ldx, x_bf);
+}
+
+// ------------------------------------------------------------------------------------------------
+// per-task segment sum: table[slot] = c0*table[slot] + c1 * sum over the slot's lookups of src[sample, f]
+// The lookups of a slot are consecutive in the (row, sample, position)-sorted list, so the order of the
+// sum is fixed.
+// ------------------------------------------------------------------------------------------------
+__global__ void slot_segsum_kernel(int F, int D, int LG, const u32* __restrict__ tf_base, const u32* __restrict__ n_slots,
+                                   const int32_t* __restrict__ seg_lo, const int32_t* __restrict__ seg_hi,
+                                   int seg_tf_stride, const int32_t* __restrict__ sorted_sample,
+                                   const float* __restrict__ src, int ld_src, float* table, float c0, float c1) {
+    const int tf = blockIdx.x;
+    const int f = tf % F;
+    const int groups = blockDim.x / LG;
+    const int g = threadIdx.x / LG, l = threadIdx.x % LG;
+    if (g >= groups) return;
+    const int64_t B = tf_base[tf];
+    const int nu = (int)n_slots[tf];
+    const int64_t sb = B + (int64_t)tf * seg_tf_stride;
+    for (int u = g; u < nu; u += groups) {
+        const int lo = seg_lo[sb + u], hi = seg_hi[sb + u];
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = lo; i < hi; ++i) {
+            const int64_t s = sorted_sample[i];
+            acc = add4(acc, *reinterpret_cast<const float4*>(src + s * ld_src + (int64_t)f * D + l * 4));
+        }
+        float4* dst = reinterpret_cast<float4*>(table + (B + u) * D + l * 4);
+        float4 o;
+        if (c0 != 0.f) {
+            const float4 old = *dst;
+            o = make_float4(c0 * old.x + c1 * acc.x, c0 * old.y + c1 * acc.y, c0 * old.z + c1 * acc.z, c0 * old.w + c1 * acc.w);
+        } else {
+            o = make_float4(c1 * acc.x, c1 * acc.y, c1 * acc.z, c1 * acc.w);
+        }
+        *dst = o;
+    }
+}
+
+void launch_slot_segsum(hipStream_t st, int F, int D, int n_tf, const u32* tf_base, const u32* n_slots,
+                        const int32_t* seg_lo, const int32_t* seg_hi, int seg_tf_stride, const int32_t* sorted_sample,
+                        const float* src, int ld_src, float* table, float c0, float c1) {
+    if (n_tf <= 0) return;
+    hipLaunchKernelGGL(slot_segsum_kernel, dim3(n_tf), dim3(256), 0, st, F, D, D / 4, tf_base, n_slots, seg_lo, seg_hi,
+                       seg_tf_stride, sorted_sample, src, ld_src, table, c0, c1);
+}
+
+// ------------------------------------------------------------------------------------------------
+// global segment reduction: emb_grad[seg] = sum over the segment's lookups (stable (field,row) order) of
+// gx[bag id], gx laid out [all samples (support then query), F, D]
+// ------------------------------------------------------------------------------------------------
+__global__ void seg_reduce_kernel(int D, int LG, const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
+                                  int64_t capacity, const u32* __restrict__ sorted_vals, const float* __restrict__ gx,
+                                  float* emb_grad) {
+    const int groups_per_block = blockDim.x / LG;
+    const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
+    if (g_in_block >= groups_per_block) return;
+    const int64_t n = min(*n_rows, capacity);
+    const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
+    const float4* gx4 = reinterpret_cast<const float4*>(gx);
+    for (int64_t seg = (int64_t)blockIdx.x * groups_per_block + g_in_block; seg < n; seg += n_groups) {
+        const u32 lo = seg_start[seg], hi = seg_start[seg + 1];
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (u32 i = lo; i < hi; ++i) acc = add4(acc, gx4[(int64_t)sorted_vals[i] * LG + l]);
+        *reinterpret_cast<float4*>(emb_grad + seg * D + l * 4) = acc;
+    }
+}
+
+void launch_seg_reduce(hipStream_t st, int D, const u32* seg_start, const int64_t* n_rows, int64_t capacity,
+                       int64_t max_rows, const u32* sorted_vals, const float* gx, float* emb_grad) {
+    if (max_rows <= 0) return;
+    const int LG = D / 4;
+    hipLaunchKernelGGL(seg_reduce_kernel, dim3(pool_grid(max_rows, 256 / LG)), dim3(256), 0, st, D, LG, seg_start,
+                       n_rows, capacity, sorted_vals, gx, emb_grad);
+}
+
+__global__ void scatter_add_kernel(int D, int LG, float* table, const int64_t* __restrict__ rows,
+                                   const float* __restrict__ grad, int64_t n_rows, float scale) {
+    const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = gt / LG;
+    const int l = (int)(gt % LG);
+    if (i >= n_rows) return;
+    float4* dst = reinterpret_cast<float4*>(table + rows[i] * D + l * 4);
+    const float4 g = *reinterpret_cast<const float4*>(grad + i * D + l * 4);
+    float4 o = *dst;
+    o.x += scale * g.x; o.y += scale * g.y; o.z += scale * g.z; o.w += scale * g.w;
+    *dst = o;
+}
+
+void launch_scatter_add(hipStream_t st, int D, float* table, const int64_t* rows, const float* grad, int64_t n_rows,
+                        float scale) {
+    if (n_rows <= 0) return;
+    const int LG = D / 4;
+    const int64_t nt = n_rows * LG;
+    hipLaunchKernelGGL(scatter_add_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, st, D, LG, table, rows, grad,
+                       n_rows, scale);
+}

@@ -1,0 +1,142 @@
+// Internal declarations shared by the kernel files and the host orchestration.
+// Nothing here is visible across the C ABI (see include/gmeta.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+// Device-side status word indices (ctx->d_status).
+enum { ST_BAD_INDEX = 0, ST_CAPACITY = 1, ST_MAX_TF = 2, ST_NROWS = 3, ST_WORDS = 8 };
+
+// ------------------------------------------------------------------ index kernels
+// Per-wave geometry handed to the index kernels (all device pointers).
+struct SetView {
+    const int64_t* bag_offsets;  // whole set
+    const int32_t* indices;      // whole set
+    const int64_t* task_offsets; // device copy, whole set
+    int64_t sample0;             // first sample of the wave in the set
+    int64_t lookup0;             // first lookup of the wave in the set
+    int64_t n_samples;           // samples of the whole set
+};
+
+void launch_tf_count(hipStream_t st, int F, int t0, int Tw, SetView sup, SetView qry, const int64_t* field_base,
+                     int64_t nnz_sup, int64_t nnz_qry, u32* cnt_sup, u32* cnt_qry, u32* status);
+void launch_scan_u32(hipStream_t st, const u32* in, u32* out, int64_t n, u32* tmp /* >= n/1024+2048 */,
+                     u32* total /* may be null */);
+size_t scan_tmp_words(int64_t n);
+
+struct TfSortArgs {
+    int F, t0, Tw;
+    SetView sup, qry;
+    const int64_t* field_base;      // [F+1] device
+    const u32* cnt_sup;             // [Tw*F]
+    const u32* base_sup;            // exclusive scan of cnt_sup
+    const u32* cnt_qry;
+    const u32* base_qry;
+    // outputs (wave-local lookup numbering)
+    u32* n_slots;                   // [Tw*F]
+    u32* slot_rows;                 // [nnz_sup_w]       at base_sup[tf] + slot
+    int32_t* slot_start;            // [nnz_sup_w+Tw*F]  at base_sup[tf] + tf + slot: first position of the slot in
+                                    //                   the sorted list (absolute); sentinel at +n_slots
+    int32_t* sup_sorted_sample;     // [nnz_sup_w]       wave-local support sample of sorted lookup
+    int32_t* sup_slot;              // [nnz_sup_w]       by lookup
+    int32_t* qry_slot;              // [nnz_qry_w]       by lookup, -1 when not in support
+    int32_t* qry_sorted_sample;     // [nnz_qry_w]       (may be null: then query segments are skipped)
+    int32_t* qseg_lo;               // [nnz_sup_w]       at base_sup[tf] + slot : range in the sorted query list
+    int32_t* qseg_hi;
+    u32* status;
+};
+void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int cap);
+int tf_sort_max_cap();
+
+void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
+                       const int32_t* indices, int64_t n_bags, u32 bag_id0, u32* keys, u32* vals, u32* status);
+// Stable LSD radix sort of (key, val) pairs on the low `bits` bits; result ends in (keys, vals).
+void launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n,
+                       int bits, u32* hist /* 256*nblk + scan tmp */);
+size_t radix_hist_words(int64_t n);
+void launch_segments(hipStream_t st, const u32* sorted_keys, int64_t n, u32* flags_scan, u32* scan_tmp,
+                     int64_t* emb_rows, u32* seg_start, int64_t* seg_counts /* may be null */,
+                     int64_t capacity, int64_t* n_rows_out, u32* status);
+
+// ------------------------------------------------------------------ embedding kernels
+void launch_gather_pool(hipStream_t st, int F, int D, int n_dense, const int64_t* field_base,
+                        const int64_t* bag_offsets, const int32_t* indices, const float* dense,
+                        const float* emb, int64_t sample0, int64_t n_samples, float* x, int ldx,
+                        bf16_t* x_bf /* may be null */);
+// x_out[s, f*D:] = x_base[s, f*D:] + sum over the bag's lookups with slot >= 0 of table[base[tf]+slot]
+// (x_base null: start from zero; dense and pad columns copied from x_base or zeroed).
+void launch_pool_slots(hipStream_t st, int F, int D, const int64_t* bag_offsets, int64_t sample0,
+                       int64_t lookup0, int64_t n_samples, const int32_t* sample_task,
+                       const int32_t* slot_of_lookup, const u32* tf_base, const float* table,
+                       const float* x_base, float* x_out, int ldx, bf16_t* x_bf);
+// table[base+slot] = c0*table[base+slot] + c1 * sum_{i in segment} src[sample_i, f*D:]
+void launch_slot_segsum(hipStream_t st, int F, int D, int n_tf, const u32* tf_base, const u32* n_slots,
+                        const int32_t* seg_lo, const int32_t* seg_hi, int seg_tf_stride,
+                        const int32_t* sorted_sample, const float* src, int ld_src, float* table, float c0,
+                        float c1);
+void launch_seg_reduce(hipStream_t st, int D, const u32* seg_start, const int64_t* n_rows, int64_t capacity,
+                       int64_t max_rows, const u32* sorted_vals, const float* gx, float* emb_grad);
+void launch_scatter_add(hipStream_t st, int D, float* table, const int64_t* rows, const float* grad,
+                        int64_t n_rows, float scale);
+
+// ------------------------------------------------------------------ MLP kernels
+enum { EPI_NONE = 0, EPI_BIAS_RELU = 1, EPI_BIAS_MASK = 2, EPI_MASK = 3, EPI_AXPBY = 4 };
+
+struct GemmArgs {
+    // up to two products accumulated: C = A1*B1 (+ A2*B2)
+    const float* A[2];
+    const float* B[2];
+    int64_t sAm[2], sAk[2], gA[2];   // element (m,k) of group g: A + g*gA + r0(g)*rA + m*sAm + k*sAk
+    int64_t sBk[2], sBn[2], gB[2];
+    int64_t rA[2], rB[2];            // multiplier of the group's first row r0(g)
+    int n_pairs;
+    float* C;
+    int64_t ldc, gC, rC;             // element (m,n): C + g*gC + r0(g)*rC + m*ldc + n
+    int M, N, K;                     // fixed extents; -1 means "rows of the group" (variable)
+    const int32_t* row_offsets;      // [G+1] device: first row of each group
+    int G;
+    // tiles over variable M: per m-tile the group and its first row inside the group
+    const int32_t* tile_group;       // [n_mtiles] (null when M is fixed)
+    const int32_t* tile_m0;
+    int n_mtiles;
+    int epi;
+    const float* bias; int64_t gBias;           // bias + g*gBias + n
+    const float* mask; int64_t ld_mask;         // mask + (r0+m)*ld_mask + n
+    const float* Cin; int64_t gCin;             // Cin + g*gCin + m*ldc + n   (EPI_AXPBY)
+    float c0, c1;
+};
+void launch_gemm_f32(hipStream_t st, const GemmArgs& a);
+
+// out[g*g_out + n] = c0*in[g*g_in + n] + c1 * sum_{s in group g} (X1[s,n]*w1[s] + X2[s,n]*w2[s])
+void launch_task_colsum(hipStream_t st, int G, const int32_t* row_offsets, int N, const float* X1,
+                        const float* w1, const float* X2, const float* w2, int64_t ldx, float* out,
+                        int64_t g_out, const float* in, int64_t g_in, float c0, float c1);
+// z[s] = a[s,:].w_g + b_g (+ ta[s,:].w_g + a[s,:].tw_g + tb_g when tangent)
+struct LastFwdArgs {
+    int64_t n; int N; int64_t ld;
+    const int32_t* sample_task; const int32_t* row_offsets;
+    const float* a; const float* ta;                 // ta null: plain forward
+    const float* w; int64_t gW; const float* b;      // w + g*gW [N], b + g*gW scalar
+    const float* tw; int64_t gTW; const float* tb;
+    const float* labels; const float* z_in;          // tangent: z of the primal pass
+    float* z_out; float* delta_out; float* loss_out; // plain: z, (sigma-y)/N_g, bce/N_g
+                                                     // tangent: delta_out = sigma'(z) * tz / N_g
+};
+void launch_last_fwd(hipStream_t st, const LastFwdArgs& a);
+// d[s,n] = (dl[s]*w_g[n] (+ dl2[s]*w2_g[n])) * (act[s,n] > 0)   (act null: no mask)
+void launch_last_bwd(hipStream_t st, int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* sample_task,
+                     const float* dl, const float* w, int64_t gW, const float* dl2, const float* w2,
+                     int64_t gW2, const float* act, float* d);
+void launch_reduce_tasks(hipStream_t st, const float* v, int64_t ld, int G, int64_t n, float* out, int accumulate);
+void launch_fill_sample_task(hipStream_t st, const int32_t* row_offsets, int G, int32_t* sample_task);
+void launch_pack_weights(hipStream_t st, const float* W, int din, int dout, int ld_in, int ld_out, float* dst);
+void launch_unpack_weights(hipStream_t st, const float* src, int din, int dout, int ld_out, float* W);
+void launch_axpy(hipStream_t st, int64_t n, float a, const float* x, float* y);  // y += a*x
+void launch_sum_to_scalar(hipStream_t st, const float* x, int n, float* out, int accumulate);
+void launch_fill_u32(hipStream_t st, u32* p, int64_t n, u32 v);
+void launch_fill_f32(hipStream_t st, float* p, int64_t n, float v);

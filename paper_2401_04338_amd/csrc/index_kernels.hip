@@ -1,0 +1,534 @@
+// Integer side of the MAML step (G-Meta Alg. 1): the per-(task, field) row dictionaries behind the
+// inner-loop row update and the overlap join of Sec. 2.1.2, and the global (field,row) ordering that
+// routes the sparse meta-gradient (Alg. 1, global back-propagation on xi).  Everything here has exactly
+// one correct answer and is compared bit-exactly with the CPU oracle.
+#include "gm_internal.h"
+
+#define WAVE 64
+
+// ------------------------------------------------------------------------------------------------
+// small helpers
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int wave_incl_scan(int v) {
+    const int lane = threadIdx.x & (WAVE - 1);
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        int o = __shfl_up(v, d, WAVE);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Exclusive scan of one int per thread over the block; `sh` holds >= blockDim/64 + 1 ints.
+__device__ __forceinline__ int block_excl_scan(int v, int* sh, int* total) {
+    const int lane = threadIdx.x & (WAVE - 1), wid = threadIdx.x / WAVE, nw = blockDim.x / WAVE;
+    int incl = wave_incl_scan(v);
+    __syncthreads();
+    if (lane == WAVE - 1) sh[wid] = incl;
+    __syncthreads();
+    if (wid == 0) {
+        int x = lane < nw ? sh[lane] : 0;
+        int xi = wave_incl_scan(x);
+        if (lane < nw) sh[lane] = xi - x;
+        if (lane == nw - 1) sh[nw] = xi;
+    }
+    __syncthreads();
+    int r = sh[wid] + incl - v;
+    *total = sh[nw];
+    return r;
+}
+
+// ------------------------------------------------------------------------------------------------
+// validation + per-(task, field) lookup counts
+// ------------------------------------------------------------------------------------------------
+__global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const int64_t* field_base,
+                                int64_t nnz_sup, int64_t nnz_qry, u32* cnt_sup, u32* cnt_qry, u32* status) {
+    extern __shared__ u32 sh_cnt[];  // [2F]
+    const int t = blockIdx.x;
+    for (int i = threadIdx.x; i < 2 * F; i += blockDim.x) sh_cnt[i] = 0;
+    __syncthreads();
+    bool bad = false;
+    for (int set = 0; set < 2; ++set) {
+        const SetView& v = set ? qry : sup;
+        const int64_t nnz = set ? nnz_qry : nnz_sup;
+        const int64_t s_lo = v.task_offsets[t0 + t], s_hi = v.task_offsets[t0 + t + 1];
+        if (s_hi - s_lo > 65536) bad = true;
+        const int64_t n = (s_hi - s_lo) * F;
+        for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
+            const int64_t bag = s_lo * F + i;
+            const int f = (int)(i % F);
+            const int64_t p0 = v.bag_offsets[bag], p1 = v.bag_offsets[bag + 1];
+            if (p0 < 0 || p1 < p0 || p1 > nnz || p1 - p0 > 65535) {
+                bad = true;
+                continue;
+            }
+            const int64_t R = field_base[f + 1] - field_base[f];
+            for (int64_t p = p0; p < p1; ++p) {
+                const int32_t r = v.indices[p];
+                if (r < 0 || r >= R) bad = true;
+            }
+            atomicAdd(&sh_cnt[set * F + f], (u32)(p1 - p0));
+        }
+    }
+    if (t == 0 && threadIdx.x == 0) {  // the ends of both offset arrays
+        if (sup.bag_offsets[0] != 0 || sup.bag_offsets[sup.n_samples * F] != nnz_sup) bad = true;
+        if (qry.bag_offsets[0] != 0 || qry.bag_offsets[qry.n_samples * F] != nnz_qry) bad = true;
+    }
+    __syncthreads();
+    u32 mx = 0;
+    for (int i = threadIdx.x; i < 2 * F; i += blockDim.x) {
+        const u32 c = sh_cnt[i];
+        if (i < F) cnt_sup[(size_t)t * F + i] = c;
+        else cnt_qry[(size_t)t * F + (i - F)] = c;
+        mx = max(mx, c);
+    }
+    if (mx) atomicMax(&status[ST_MAX_TF], mx);
+    if (bad) atomicOr(&status[ST_BAD_INDEX], 1u);
+}
+
+void launch_tf_count(hipStream_t st, int F, int t0, int Tw, SetView sup, SetView qry, const int64_t* field_base,
+                     int64_t nnz_sup, int64_t nnz_qry, u32* cnt_sup, u32* cnt_qry, u32* status) {
+    if (Tw <= 0) return;
+    hipLaunchKernelGGL(tf_count_kernel, dim3(Tw), dim3(256), 2 * F * sizeof(u32), st, F, t0, sup, qry, field_base,
+                       nnz_sup, nnz_qry, cnt_sup, cnt_qry, status);
+}
+
+// ------------------------------------------------------------------------------------------------
+// device-wide exclusive scan of u32 (three-phase, recursive on the block sums)
+// ------------------------------------------------------------------------------------------------
+#define SCAN_NT 256
+#define SCAN_ITEMS 8
+#define SCAN_TILE (SCAN_NT * SCAN_ITEMS)
+
+__global__ void scan_block_kernel(const u32* in, u32* out, int64_t n, u32* block_sums) {
+    __shared__ int sh[SCAN_NT / WAVE + 2];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    u32 v[SCAN_ITEMS];
+    u32 sum = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        v[i] = (base + i < n) ? in[base + i] : 0u;
+        sum += v[i];
+    }
+    int total;
+    u32 run = (u32)block_excl_scan((int)sum, sh, &total);
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        if (base + i < n) out[base + i] = run;
+        run += v[i];
+    }
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = (u32)total;
+}
+
+__global__ void scan_add_kernel(u32* out, int64_t n, const u32* block_offsets) {
+    const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    const u32 o = block_offsets[blockIdx.x];
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i)
+        if (base + i < n) out[base + i] += o;
+}
+
+__global__ void copy_u32_kernel(const u32* src, u32* dst) { *dst = *src; }
+
+size_t scan_tmp_words(int64_t n) {
+    size_t w = 0;
+    while (true) {
+        int64_t nb = (n + SCAN_TILE - 1) / SCAN_TILE;
+        if (nb < 1) nb = 1;
+        w += (size_t)((nb + 63) / 64 * 64);
+        if (nb <= 1) break;
+        n = nb;
+    }
+    return w + 64;
+}
+
+void launch_scan_u32(hipStream_t st, const u32* in, u32* out, int64_t n, u32* tmp, u32* total) {
+    if (n <= 0) {
+        if (total) launch_fill_u32(st, total, 1, 0);
+        return;
+    }
+    const int64_t nb = (n + SCAN_TILE - 1) / SCAN_TILE;
+    hipLaunchKernelGGL(scan_block_kernel, dim3((unsigned)nb), dim3(SCAN_NT), 0, st, in, out, n, tmp);
+    if (nb == 1) {
+        if (total) hipLaunchKernelGGL(copy_u32_kernel, dim3(1), dim3(1), 0, st, tmp, total);
+        return;
+    }
+    u32* next = tmp + (nb + 63) / 64 * 64;
+    launch_scan_u32(st, tmp, tmp, nb, next, total);
+    hipLaunchKernelGGL(scan_add_kernel, dim3((unsigned)nb), dim3(SCAN_NT), 0, st, out, n, tmp);
+}
+
+// ------------------------------------------------------------------------------------------------
+// per-(task, field) dictionaries: LDS sort of the support lookups, then the query join
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void bitonic_sort_lds(u64* keys, int n2) {
+    for (int k = 2; k <= n2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int p = threadIdx.x; p < (n2 >> 1); p += blockDim.x) {
+                const int i = ((p & ~(j - 1)) << 1) | (p & (j - 1));
+                const int ixj = i + j;
+                const bool asc = (i & k) == 0;
+                const u64 a = keys[i], b = keys[ixj];
+                if ((a > b) == asc) {
+                    keys[i] = b;
+                    keys[ixj] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__device__ __forceinline__ int load_tf_keys(u64* keys, int* sh_fill, const SetView& v, int F, int f, int64_t s_lo,
+                                            int64_t s_hi, u32 fb) {
+    if (threadIdx.x == 0) *sh_fill = 0;
+    __syncthreads();
+    const int ns = (int)(s_hi - s_lo);
+    for (int s = threadIdx.x; s < ns; s += blockDim.x) {
+        const int64_t bag = (s_lo + s) * F + f;
+        const int64_t p0 = v.bag_offsets[bag];
+        const int len = (int)(v.bag_offsets[bag + 1] - p0);
+        if (len > 0) {
+            const int base = atomicAdd(sh_fill, len);
+            for (int j = 0; j < len; ++j)
+                keys[base + j] = ((u64)(fb + (u32)v.indices[p0 + j]) << 32) | ((u64)s << 16) | (u64)j;
+        }
+    }
+    __syncthreads();
+    return *sh_fill;
+}
+
+template <bool LDS_UNIQ>
+__global__ void tf_sort_kernel(TfSortArgs a, int cap) {
+    extern __shared__ u64 sh_keys[];  // [cap] (+ u32 uniq[cap] when LDS_UNIQ)
+    __shared__ int sh_scan[20];
+    __shared__ int sh_fill;
+    const int f = blockIdx.x, t = blockIdx.y;
+    const size_t tf = (size_t)t * a.F + f;
+    const u32 fb = (u32)a.field_base[f];
+    const u32 n = a.cnt_sup[tf], B = a.base_sup[tf];
+    const u32 nq = a.cnt_qry[tf], Bq = a.base_qry[tf];
+    u32* uniq = LDS_UNIQ ? (u32*)(sh_keys + cap) : (a.slot_rows + B);
+    int n_unique = 0;
+
+    // ---- phase A: support lookups sorted by (row, sample, position in bag)
+    const int64_t s_lo = a.sup.task_offsets[a.t0 + t], s_hi = a.sup.task_offsets[a.t0 + t + 1];
+    if (n > 0) {
+        load_tf_keys(sh_keys, &sh_fill, a.sup, a.F, f, s_lo, s_hi, fb);
+        int n2 = 1;
+        while (n2 < (int)n) n2 <<= 1;
+        for (int i = n + threadIdx.x; i < n2; i += blockDim.x) sh_keys[i] = ~0ull;
+        __syncthreads();
+        bitonic_sort_lds(sh_keys, n2);
+        const int chunk = ((int)n + blockDim.x - 1) / blockDim.x;
+        const int i0 = min((int)n, (int)threadIdx.x * chunk), i1 = min((int)n, i0 + chunk);
+        int c = 0;
+        for (int i = i0; i < i1; ++i) c += (i == 0) || ((sh_keys[i] >> 32) != (sh_keys[i - 1] >> 32));
+        int slot = block_excl_scan(c, sh_scan, &n_unique) - 1;
+        for (int i = i0; i < i1; ++i) {
+            const u64 key = sh_keys[i];
+            const u32 row = (u32)(key >> 32);
+            const bool head = (i == 0) || (row != (u32)(sh_keys[i - 1] >> 32));
+            if (head) {
+                ++slot;
+                a.slot_start[B + tf + slot] = (int32_t)(B + i);
+                a.slot_rows[B + slot] = row;
+                if (LDS_UNIQ) uniq[slot] = row;
+            }
+            const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
+            const int64_t p = a.sup.bag_offsets[(s_lo + s) * a.F + f] + j;
+            a.sup_slot[p - a.sup.lookup0] = slot;
+            a.sup_sorted_sample[B + i] = (int32_t)(s_lo + s - a.sup.sample0);
+        }
+    }
+    if (threadIdx.x == 0) {
+        a.slot_start[B + tf + n_unique] = (int32_t)(B + n);
+        a.n_slots[tf] = (u32)n_unique;
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // ---- phase B: query lookups sorted the same way, joined against the support rows
+    if (nq == 0) {
+        for (int u = threadIdx.x; u < n_unique; u += blockDim.x) {
+            a.qseg_lo[B + u] = (int32_t)Bq;
+            a.qseg_hi[B + u] = (int32_t)Bq;
+        }
+        return;
+    }
+    const int64_t q_lo = a.qry.task_offsets[a.t0 + t], q_hi = a.qry.task_offsets[a.t0 + t + 1];
+    load_tf_keys(sh_keys, &sh_fill, a.qry, a.F, f, q_lo, q_hi, fb);
+    int n2 = 1;
+    while (n2 < (int)nq) n2 <<= 1;
+    for (int i = nq + threadIdx.x; i < n2; i += blockDim.x) sh_keys[i] = ~0ull;
+    __syncthreads();
+    bitonic_sort_lds(sh_keys, n2);
+    for (int i = threadIdx.x; i < (int)nq; i += blockDim.x) {
+        const u64 key = sh_keys[i];
+        const u32 row = (u32)(key >> 32);
+        int lo = 0, hi = n_unique;  // first slot with uniq >= row
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (uniq[mid] < row) lo = mid + 1;
+            else hi = mid;
+        }
+        const int slot = (lo < n_unique && uniq[lo] == row) ? lo : -1;
+        const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
+        const int64_t p = a.qry.bag_offsets[(q_lo + s) * a.F + f] + j;
+        a.qry_slot[p - a.qry.lookup0] = slot;
+        a.qry_sorted_sample[Bq + i] = (int32_t)(q_lo + s - a.qry.sample0);
+    }
+    for (int u = threadIdx.x; u < n_unique; u += blockDim.x) {
+        const u64 klo = (u64)uniq[u] << 32, khi = ((u64)uniq[u] + 1) << 32;
+        int lo = 0, hi = (int)nq;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (sh_keys[mid] < klo) lo = mid + 1;
+            else hi = mid;
+        }
+        int lo2 = lo, hi2 = (int)nq;
+        while (lo2 < hi2) {
+            const int mid = (lo2 + hi2) >> 1;
+            if (sh_keys[mid] < khi) lo2 = mid + 1;
+            else hi2 = mid;
+        }
+        a.qseg_lo[B + u] = (int32_t)(Bq + lo);
+        a.qseg_hi[B + u] = (int32_t)(Bq + lo2);
+    }
+}
+
+int tf_sort_max_cap() { return 16384; }
+
+void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int cap) {
+    if (a.Tw <= 0 || a.F <= 0) return;
+    const bool lds_uniq = cap <= 8192;
+    const size_t shmem = (size_t)cap * (lds_uniq ? 12 : 8);
+    const int nt = cap <= 1024 ? 256 : (cap <= 4096 ? 512 : 1024);
+    dim3 grid(a.F, a.Tw);
+    if (lds_uniq) {
+        hipFuncSetAttribute((const void*)tf_sort_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+        hipLaunchKernelGGL(tf_sort_kernel<true>, grid, dim3(nt), shmem, st, a, cap);
+    } else {
+        hipFuncSetAttribute((const void*)tf_sort_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+        hipLaunchKernelGGL(tf_sort_kernel<false>, grid, dim3(nt), shmem, st, a, cap);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// global (field,row) ordering of all lookups: keys, stable LSD radix sort, segments
+// ------------------------------------------------------------------------------------------------
+__global__ void build_keys_kernel(int F, const int64_t* field_base, const int64_t* bag_offsets,
+                                  const int32_t* indices, int64_t n_bags, u32 bag_id0, u32* keys, u32* vals) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= n_bags) return;
+    const u32 fb = (u32)field_base[b % F];
+    const int64_t p0 = bag_offsets[b], p1 = bag_offsets[b + 1];
+    for (int64_t p = p0; p < p1; ++p) {
+        keys[p] = fb + (u32)indices[p];
+        vals[p] = bag_id0 + (u32)b;
+    }
+}
+
+void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
+                       const int32_t* indices, int64_t n_bags, u32 bag_id0, u32* keys, u32* vals, u32* status) {
+    (void)status;
+    if (n_bags <= 0) return;
+    hipLaunchKernelGGL(build_keys_kernel, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, st, F, field_base,
+                       bag_offsets, indices, n_bags, bag_id0, keys, vals);
+}
+
+#define RS_NT 256
+#define RS_ITEMS 16
+#define RS_TILE (RS_NT * RS_ITEMS)
+#define RS_WAVES (RS_NT / WAVE)
+
+__global__ void radix_hist_kernel(const u32* keys, int64_t n, int shift, u32* hist, int nblk) {
+    __shared__ u32 h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * RS_TILE;
+#pragma unroll
+    for (int i = 0; i < RS_ITEMS; ++i) {
+        const int64_t idx = base + i * RS_NT + threadIdx.x;
+        if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[(size_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+
+// Stable scatter: every wave owns a contiguous 1/4 of the tile and ranks its keys round by round (64
+// consecutive keys per round) with ballot matching, so equal digits keep their input order.
+__global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, u32* vout, const u32* gofs,
+                                     int64_t n, int shift, int nblk) {
+    __shared__ u32 cnt[RS_WAVES][256];
+    __shared__ u32 digstart[256];
+    __shared__ u32 skeys[RS_TILE];
+    __shared__ u32 svals[RS_TILE];
+    __shared__ int sh_scan[RS_WAVES + 2];
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    for (int i = threadIdx.x; i < RS_WAVES * 256; i += RS_NT) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    const int64_t tile0 = (int64_t)blockIdx.x * RS_TILE;
+    u32 key[RS_ITEMS], val[RS_ITEMS], rank[RS_ITEMS];
+    const u64 lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+    for (int r = 0; r < RS_ITEMS; ++r) {
+        const int64_t idx = tile0 + (int64_t)w * (WAVE * RS_ITEMS) + r * WAVE + lane;
+        const bool valid = idx < n;
+        key[r] = valid ? kin[idx] : 0xFFFFFFFFu;
+        val[r] = valid ? vin[idx] : 0u;
+        const u32 d = (key[r] >> shift) & 255u;
+        u64 peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (d >> b) & 1u;
+            const u64 m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        const int leader = valid ? (__ffsll((unsigned long long)peers) - 1) : lane;
+        u32 old = 0;
+        if (valid && lane == leader) {
+            old = cnt[w][d];
+            cnt[w][d] = old + (u32)__popcll(peers);
+        }
+        old = __shfl(old, leader, WAVE);
+        rank[r] = old + (u32)__popcll(peers & lt_mask);
+        __syncthreads();
+    }
+    // per-digit: exclusive prefix over the waves, block total, start of each digit inside the tile
+    u32 total = 0;
+    {
+        const int d = threadIdx.x;
+#pragma unroll
+        for (int ww = 0; ww < RS_WAVES; ++ww) {
+            const u32 c = cnt[ww][d];
+            cnt[ww][d] = total;
+            total += c;
+        }
+    }
+    int tile_count;
+    const int ds = block_excl_scan((int)total, sh_scan, &tile_count);
+    digstart[threadIdx.x] = (u32)ds;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RS_ITEMS; ++r) {
+        const int64_t idx = tile0 + (int64_t)w * (WAVE * RS_ITEMS) + r * WAVE + lane;
+        if (idx < n) {
+            const u32 d = (key[r] >> shift) & 255u;
+            const u32 pos = digstart[d] + cnt[w][d] + rank[r];
+            skeys[pos] = key[r];
+            svals[pos] = val[r];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < RS_ITEMS; ++i) {
+        const int pos = i * RS_NT + threadIdx.x;
+        if (pos < tile_count) {
+            const u32 k = skeys[pos];
+            const u32 d = (k >> shift) & 255u;
+            const size_t dst = (size_t)gofs[(size_t)d * nblk + blockIdx.x] + (pos - digstart[d]);
+            kout[dst] = k;
+            vout[dst] = svals[pos];
+        }
+    }
+}
+
+size_t radix_hist_words(int64_t n) {
+    const int64_t nblk = (n + RS_TILE - 1) / RS_TILE;
+    return (size_t)(256 * nblk + 64) + scan_tmp_words(256 * nblk);
+}
+
+void launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n, int bits,
+                       u32* hist) {
+    if (n <= 0) return;
+    const int nblk = (int)((n + RS_TILE - 1) / RS_TILE);
+    u32* scan_tmp = hist + ((size_t)256 * nblk + 63) / 64 * 64;
+    int passes = (bits + 7) / 8;
+    if (passes < 1) passes = 1;
+    if (passes & 1) ++passes;  // even number of passes: the result lands in (keys, vals)
+    u32 *ki = keys, *vi = vals, *ko = keys_tmp, *vo = vals_tmp;
+    for (int p = 0; p < passes; ++p) {
+        const int shift = 8 * p;
+        if (shift >= 32) {  // nothing left to sort on: plain copy keeps the pairing of buffers
+            hipMemcpyAsync(ko, ki, n * sizeof(u32), hipMemcpyDeviceToDevice, st);
+            hipMemcpyAsync(vo, vi, n * sizeof(u32), hipMemcpyDeviceToDevice, st);
+        } else {
+            hipLaunchKernelGGL(radix_hist_kernel, dim3(nblk), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
+            launch_scan_u32(st, hist, hist, (int64_t)256 * nblk, scan_tmp, nullptr);
+            hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblk), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift,
+                               nblk);
+        }
+        u32* t = ki; ki = ko; ko = t;
+        t = vi; vi = vo; vo = t;
+    }
+}
+
+__global__ void seg_flags_kernel(const u32* keys, int64_t n, u32* flags) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) flags[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
+}
+
+__global__ void seg_emit_kernel(const u32* keys, int64_t n, const u32* scan, int64_t* emb_rows, u32* seg_start,
+                                int64_t capacity, int64_t* n_rows_out, u32* status) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const bool head = (i == 0 || keys[i] != keys[i - 1]);
+    const u32 seg = scan[i];
+    if (head && (int64_t)seg < capacity) {
+        emb_rows[seg] = (int64_t)keys[i];
+        seg_start[seg] = (u32)i;
+    }
+    if (i == n - 1) {
+        const int64_t total = (int64_t)seg + (head ? 1 : 0);
+        *n_rows_out = total;
+        status[ST_NROWS] = (u32)total;
+        if (total > capacity) atomicOr(&status[ST_CAPACITY], 1u);
+        else seg_start[total] = (u32)n;
+    }
+}
+
+__global__ void seg_counts_kernel(const u32* seg_start, const int64_t* n_rows, int64_t capacity, int64_t* counts) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t n = min(*n_rows, capacity);
+    if (i < n) counts[i] = (int64_t)seg_start[i + 1] - (int64_t)seg_start[i];
+}
+
+__global__ void zero_rows_kernel(int64_t* n_rows_out, u32* status) {
+    *n_rows_out = 0;
+    status[ST_NROWS] = 0;
+}
+
+void launch_segments(hipStream_t st, const u32* sorted_keys, int64_t n, u32* flags_scan, u32* scan_tmp,
+                     int64_t* emb_rows, u32* seg_start, int64_t* seg_counts, int64_t capacity,
+                     int64_t* n_rows_out, u32* status) {
+    if (n <= 0) {
+        hipLaunchKernelGGL(zero_rows_kernel, dim3(1), dim3(1), 0, st, n_rows_out, status);
+        return;
+    }
+    const unsigned nb = (unsigned)((n + 255) / 256);
+    hipLaunchKernelGGL(seg_flags_kernel, dim3(nb), dim3(256), 0, st, sorted_keys, n, flags_scan);
+    launch_scan_u32(st, flags_scan, flags_scan, n, scan_tmp, nullptr);
+    hipLaunchKernelGGL(seg_emit_kernel, dim3(nb), dim3(256), 0, st, sorted_keys, n, flags_scan, emb_rows, seg_start,
+                       capacity, n_rows_out, status);
+    if (seg_counts) {
+        const int64_t m = capacity < n ? capacity : n;
+        hipLaunchKernelGGL(seg_counts_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, st, seg_start,
+                           n_rows_out, capacity, seg_counts);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ void fill_u32_kernel(u32* p, int64_t n, u32 v) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+void launch_fill_u32(hipStream_t st, u32* p, int64_t n, u32 v) {
+    if (n <= 0) return;
+    int64_t nb = (n + 255) / 256;
+    if (nb > 65536) nb = 65536;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)nb), dim3(256), 0, st, p, n, v);
+}
+void launch_fill_f32(hipStream_t st, float* p, int64_t n, float v) {
+    launch_fill_u32(st, (u32*)p, n, __builtin_bit_cast(u32, v));
+}

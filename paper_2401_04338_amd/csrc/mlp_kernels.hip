@@ -1,0 +1,295 @@
+// Dense side of the MAML step (G-Meta Alg. 1): inner forward / local back-propagation on theta, outer
+// forward with the task's adapted theta', and the tangent passes of the second-order term.  Every
+// product is a GROUPED GEMM: one group per task, each group with its own rows and (when theta has been
+// adapted) its own weights.
+#include "gm_internal.h"
+
+// ------------------------------------------------------------------------------------------------
+// fp32 grouped GEMM (vector FMA), C = A1*B1 (+ A2*B2) with generic strides and a fused epilogue
+// ------------------------------------------------------------------------------------------------
+#define GB_M 64
+#define GB_N 64
+#define GB_K 16
+
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a, int n_ntiles, int mt_per_group) {
+    __shared__ float As[GB_K][GB_M + 4];
+    __shared__ float Bs[GB_K][GB_N + 4];
+    const int ntile = blockIdx.x % n_ntiles;
+    const int mtile = blockIdx.x / n_ntiles;
+    int g, m0;
+    if (a.tile_group) {
+        g = a.tile_group[mtile];
+        m0 = a.tile_m0[mtile];
+    } else {
+        g = mtile / mt_per_group;
+        m0 = (mtile % mt_per_group) * GB_M;
+    }
+    const int64_t r0 = a.row_offsets ? a.row_offsets[g] : 0;
+    const int rows_g = a.row_offsets ? (int)(a.row_offsets[g + 1] - r0) : 0;
+    const int M = a.M < 0 ? rows_g : a.M;
+    const int K = a.K < 0 ? rows_g : a.K;
+    const int N = a.N;
+    const int n0 = ntile * GB_N;
+    const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+    for (int pr = 0; pr < a.n_pairs; ++pr) {
+        const float* A = a.A[pr] + (int64_t)g * a.gA[pr] + r0 * a.rA[pr];
+        const float* B = a.B[pr] + (int64_t)g * a.gB[pr] + r0 * a.rB[pr];
+        const int64_t sAm = a.sAm[pr], sAk = a.sAk[pr], sBk = a.sBk[pr], sBn = a.sBn[pr];
+        for (int k0 = 0; k0 < K; k0 += GB_K) {
+#pragma unroll
+            for (int e = threadIdx.x; e < GB_M * GB_K; e += 256) {
+                int m, k;
+                if (sAk == 1) { m = e / GB_K; k = e % GB_K; } else { m = e % GB_M; k = e / GB_M; }
+                const int gm = m0 + m, gk = k0 + k;
+                As[k][m] = (gm < M && gk < K) ? A[gm * sAm + gk * sAk] : 0.f;
+            }
+#pragma unroll
+            for (int e = threadIdx.x; e < GB_N * GB_K; e += 256) {
+                int n, k;
+                if (sBk == 1) { n = e / GB_K; k = e % GB_K; } else { n = e % GB_N; k = e / GB_N; }
+                const int gn = n0 + n, gk = k0 + k;
+                Bs[k][n] = (gn < N && gk < K) ? B[gk * sBk + gn * sBn] : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < GB_K; ++k) {
+                float av[4], bv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) av[i] = As[k][ty * 4 + i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bv[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+            }
+            __syncthreads();
+        }
+    }
+
+    float* C = a.C + (int64_t)g * a.gC + r0 * a.rC;
+    const float* bias = a.bias ? a.bias + (int64_t)g * a.gBias : nullptr;
+    const float* mask = a.mask ? a.mask + r0 * a.ld_mask : nullptr;
+    const float* Cin = a.Cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n >= N) continue;
+            float v = acc[i][j];
+            switch (a.epi) {
+                case EPI_BIAS_RELU: v = fmaxf(v + bias[n], 0.f); break;
+                case EPI_BIAS_MASK: v = (mask[(int64_t)m * a.ld_mask + n] > 0.f) ? v + bias[n] : 0.f; break;
+                case EPI_MASK: v = (mask[(int64_t)m * a.ld_mask + n] > 0.f) ? v : 0.f; break;
+                case EPI_AXPBY: v = a.c1 * v + (Cin ? a.c0 * Cin[(int64_t)m * a.ldc + n] : 0.f); break;
+                default: break;
+            }
+            C[(int64_t)m * a.ldc + n] = v;
+        }
+    }
+}
+
+void launch_gemm_f32(hipStream_t st, const GemmArgs& a) {
+    const int n_ntiles = (a.N + GB_N - 1) / GB_N;
+    int64_t n_mtiles;
+    int mt_per_group = 1;
+    if (a.tile_group) {
+        n_mtiles = a.n_mtiles;
+    } else {
+        mt_per_group = (a.M + GB_M - 1) / GB_M;
+        n_mtiles = (int64_t)mt_per_group * a.G;
+    }
+    if (n_mtiles <= 0 || n_ntiles <= 0) return;
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((unsigned)(n_mtiles * n_ntiles)), dim3(256), 0, st, a, n_ntiles,
+                       mt_per_group);
+}
+
+// ------------------------------------------------------------------------------------------------
+// per-task column sums (bias gradients, last-layer weight gradient, per-task mean loss)
+// out[g,n] = c0*in[g,n] + c1 * sum_{s in g} ( X1[s,n]*w1[s] + X2[s,n]*w2[s] ), rows summed in order
+// ------------------------------------------------------------------------------------------------
+__global__ void task_colsum_kernel(const int32_t* __restrict__ row_offsets, int N, const float* __restrict__ X1,
+                                   const float* __restrict__ w1, const float* __restrict__ X2,
+                                   const float* __restrict__ w2, int64_t ldx, float* out, int64_t g_out,
+                                   const float* in, int64_t g_in, float c0, float c1) {
+    const int g = blockIdx.y;
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    const int64_t r0 = row_offsets[g], r1 = row_offsets[g + 1];
+    float acc = 0.f;
+    for (int64_t s = r0; s < r1; ++s) {
+        float v = X1[s * ldx + n] * (w1 ? w1[s] : 1.f);
+        if (X2) v += X2[s * ldx + n] * (w2 ? w2[s] : 1.f);
+        acc += v;
+    }
+    const float o = c1 * acc + (in ? c0 * in[(int64_t)g * g_in + n] : 0.f);
+    out[(int64_t)g * g_out + n] = o;
+}
+
+void launch_task_colsum(hipStream_t st, int G, const int32_t* row_offsets, int N, const float* X1, const float* w1,
+                        const float* X2, const float* w2, int64_t ldx, float* out, int64_t g_out, const float* in,
+                        int64_t g_in, float c0, float c1) {
+    if (G <= 0 || N <= 0) return;
+    const int nt = N >= 256 ? 256 : 64;
+    for (int g0 = 0; g0 < G; g0 += 32768) {
+        const int gc = (G - g0) < 32768 ? (G - g0) : 32768;
+        hipLaunchKernelGGL(task_colsum_kernel, dim3((N + nt - 1) / nt, gc), dim3(nt), 0, st, row_offsets + g0, N, X1, w1,
+                           X2, w2, ldx, out + (int64_t)g0 * g_out, g_out, in ? in + (int64_t)g0 * g_in : nullptr, g_in,
+                           c0, c1);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// last layer (d_L = 1) fused with the sigmoid / binary cross-entropy: one wavefront per sample
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+__global__ void last_fwd_kernel(LastFwdArgs a) {
+    const int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 64;
+    const int lane = threadIdx.x & 63;
+    if (s >= a.n) return;
+    const int g = a.sample_task[s];
+    const float* w = a.w + (int64_t)g * a.gW;
+    const float* x = a.a + s * a.ld;
+    float acc = 0.f;
+    if (!a.ta) {
+        for (int n = lane; n < a.N; n += 64) acc = fmaf(x[n], w[n], acc);
+    } else {
+        const float* tx = a.ta + s * a.ld;
+        const float* tw = a.tw + (int64_t)g * a.gTW;
+        for (int n = lane; n < a.N; n += 64) acc += tx[n] * w[n] + x[n] * tw[n];
+    }
+    acc = wave_sum(acc);
+    if (lane != 0) return;
+    const float inv_n = 1.f / (float)(a.row_offsets[g + 1] - a.row_offsets[g]);
+    if (!a.ta) {
+        const float z = acc + a.b[(int64_t)g * a.gW];
+        const float y = a.labels[s];
+        const float e = __expf(-fabsf(z));
+        const float sig = z >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+        if (a.z_out) a.z_out[s] = z;
+        a.delta_out[s] = (sig - y) * inv_n;
+        if (a.loss_out) a.loss_out[s] = (fmaxf(z, 0.f) - y * z + log1pf(e)) * inv_n;
+    } else {
+        const float tz = acc + a.tb[(int64_t)g * a.gTW];
+        const float z = a.z_in[s];
+        const float e = __expf(-fabsf(z));
+        const float sig = z >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+        a.delta_out[s] = sig * (1.f - sig) * tz * inv_n;
+    }
+}
+
+void launch_last_fwd(hipStream_t st, const LastFwdArgs& a) {
+    if (a.n <= 0) return;
+    hipLaunchKernelGGL(last_fwd_kernel, dim3((unsigned)((a.n * 64 + 255) / 256)), dim3(256), 0, st, a);
+}
+
+__global__ void last_bwd_kernel(int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* __restrict__ sample_task,
+                                const float* __restrict__ dl, const float* __restrict__ w, int64_t gW,
+                                const float* __restrict__ dl2, const float* __restrict__ w2, int64_t gW2,
+                                const float* __restrict__ act, float* d) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n * N) return;
+    const int64_t s = i / N;
+    const int c = (int)(i - s * N);
+    const int g = sample_task[s];
+    float v = dl[s] * w[(int64_t)g * gW + c];
+    if (dl2) v += dl2[s] * w2[(int64_t)g * gW2 + c];
+    d[s * ld_d + c] = (!act || act[s * ld_a + c] > 0.f) ? v : 0.f;
+}
+
+void launch_last_bwd(hipStream_t st, int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* sample_task, const float* dl,
+                     const float* w, int64_t gW, const float* dl2, const float* w2, int64_t gW2, const float* act,
+                     float* d) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(last_bwd_kernel, dim3((unsigned)((n * N + 255) / 256)), dim3(256), 0, st, n, N, ld_a, ld_d,
+                       sample_task, dl, w, gW, dl2, w2, gW2, act, d);
+}
+
+// ------------------------------------------------------------------------------------------------
+// cross-task reduction of the dense meta-gradient (Alg. 1, global back-propagation on theta; Sec. 2.1.3):
+// out[j] (+)= sum_g v[g, j], tasks added in task order
+// ------------------------------------------------------------------------------------------------
+__global__ void reduce_tasks_kernel(const float* __restrict__ v, int64_t ld, int G, int64_t n, float* out,
+                                    int accumulate) {
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    float acc = accumulate ? out[j] : 0.f;
+    for (int g = 0; g < G; ++g) acc += v[(int64_t)g * ld + j];
+    out[j] = acc;
+}
+
+void launch_reduce_tasks(hipStream_t st, const float* v, int64_t ld, int G, int64_t n, float* out, int accumulate) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(reduce_tasks_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, v, ld, G, n, out,
+                       accumulate);
+}
+
+__global__ void fill_sample_task_kernel(const int32_t* row_offsets, int32_t* sample_task) {
+    const int g = blockIdx.x;
+    for (int s = row_offsets[g] + threadIdx.x; s < row_offsets[g + 1]; s += blockDim.x) sample_task[s] = g;
+}
+void launch_fill_sample_task(hipStream_t st, const int32_t* row_offsets, int G, int32_t* sample_task) {
+    if (G <= 0) return;
+    hipLaunchKernelGGL(fill_sample_task_kernel, dim3(G), dim3(256), 0, st, row_offsets, sample_task);
+}
+
+// W [din, dout] row-major  <->  padded [ld_in, ld_out] (pad rows / columns zero)
+__global__ void pack_weights_kernel(const float* W, int din, int dout, int ld_in, int ld_out, float* dst) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)ld_in * ld_out) return;
+    const int r = (int)(i / ld_out), c = (int)(i % ld_out);
+    dst[i] = (r < din && c < dout) ? W[(int64_t)r * dout + c] : 0.f;
+}
+void launch_pack_weights(hipStream_t st, const float* W, int din, int dout, int ld_in, int ld_out, float* dst) {
+    const int64_t n = (int64_t)ld_in * ld_out;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, W, din, dout, ld_in,
+                       ld_out, dst);
+}
+__global__ void unpack_weights_kernel(const float* src, int din, int dout, int ld_out, float* W) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)din * dout) return;
+    const int r = (int)(i / dout), c = (int)(i % dout);
+    W[i] = src[(int64_t)r * ld_out + c];
+}
+void launch_unpack_weights(hipStream_t st, const float* src, int din, int dout, int ld_out, float* W) {
+    const int64_t n = (int64_t)din * dout;
+    if (n <= 0) return;
+    hipLaunchKernelGGL(unpack_weights_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src, din, dout,
+                       ld_out, W);
+}
+
+__global__ void axpy_kernel(int64_t n, float a, const float* __restrict__ x, float* y) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        y[i] += a * x[i];
+}
+void launch_axpy(hipStream_t st, int64_t n, float a, const float* x, float* y) {
+    if (n <= 0) return;
+    int64_t nb = (n + 255) / 256;
+    if (nb > 65536) nb = 65536;
+    hipLaunchKernelGGL(axpy_kernel, dim3((unsigned)nb), dim3(256), 0, st, n, a, x, y);
+}
+
+__global__ void sum_to_scalar_kernel(const float* x, int n, float* out, int accumulate) {
+    // one wavefront, fixed order: lanes stride the array, then a butterfly
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < n; i += 64) acc += x[i];
+    acc = wave_sum(acc);
+    if (threadIdx.x == 0) *out = accumulate ? *out + acc : acc;
+}
+void launch_sum_to_scalar(hipStream_t st, const float* x, int n, float* out, int accumulate) {
+    hipLaunchKernelGGL(sum_to_scalar_kernel, dim3(1), dim3(64), 0, st, x, n, out, accumulate);
+}

@@ -1,0 +1,226 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Bar: integers (slots, row lists, segment sizes) bit-exact; fp32 path 1e-4 relative
+(L2 and max-abs relative to the reference's max-abs) on losses and gradients.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import maml_dlrm as O
+from synth import SMALL, TINY, make_batch, make_params
+from tests.helpers import oracle_model, rel_err, small_cfg
+
+pytestmark = pytest.mark.gpu
+
+TOL_FP32 = 1e-4
+
+
+@pytest.fixture(scope="module")
+def gm():
+    from paper_2401_04338_amd import GMeta
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return GMeta
+
+
+def _to_dev(sd, dev):
+    from synth.generate import SetData
+    return SetData(sd.task_offsets, sd.bag_offsets.to(dev), sd.indices.to(dev), sd.dense.to(dev), sd.labels.to(dev))
+
+
+def _inputs(cfg, emb_std=0.05, tasks=None):
+    sup, qry = make_batch(cfg, 0, "cpu", tasks)
+    params = make_params(cfg, "cpu", emb_std=emb_std)
+    return sup, qry, params
+
+
+def _params_dev(params, dev):
+    from synth.generate import Params
+    return Params(params.emb.to(dev), [w.to(dev) for w in params.W], [b.to(dev) for b in params.b])
+
+
+def _compare_step(cfg, ctx, sup, qry, params, K, order, tol, label):
+    dev = ctx.device
+    out = ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, K, order)
+    ref = O.meta_step(oracle_model(cfg), params.numpy(), sup.numpy(), qry.numpy(), cfg.inner_lr, K, order)
+    n = int(out["n_emb_rows"].item())
+    assert n == len(ref["emb_rows"]), label
+    assert np.array_equal(out["emb_rows"][:n].cpu().numpy(), ref["emb_rows"]), label
+    errs = {}
+    errs["loss"] = abs(float(out["loss"].item()) - ref["loss"]) / abs(ref["loss"])
+    T = cfg.n_tasks if len(sup.task_offsets) - 1 == cfg.n_tasks else len(sup.task_offsets) - 1
+    errs["task_loss"] = max(rel_err(out["task_loss"][:T].cpu().numpy(), ref["task_loss"]))
+    for l in range(len(ref["dW"])):
+        errs[f"dW{l}"] = max(rel_err(out["dW"][l].cpu().numpy(), ref["dW"][l]))
+        errs[f"db{l}"] = max(rel_err(out["db"][l].cpu().numpy(), ref["db"][l]))
+    errs["emb_grad"] = max(rel_err(out["emb_grad"][:n].cpu().numpy(), ref["emb_grad"]))
+    print(label, {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= tol, (label, k, v)
+    return out, ref
+
+
+# ---------------------------------------------------------------- a0: integer structures
+@pytest.mark.parametrize("cfg", [small_cfg(n_tasks=5, rows_per_field=12, bag_max=5),
+                                 TINY, SMALL.with_(n_tasks=6)], ids=["mini", "tiny", "small6"])
+def test_index_prep_bit_exact(gm, cfg):
+    print("index_prep", cfg.name, flush=True)
+    sup, qry, _ = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+    got = ctx.index_prep(_to_dev(sup, ctx.device), _to_dev(qry, ctx.device))
+    ref = O.index_prep(oracle_model(cfg), sup.numpy(), qry.numpy())
+    for k in ("slot_counts", "slot_rows", "sup_slot", "qry_slot", "emb_rows", "seg_counts"):
+        assert np.array_equal(got[k].cpu().numpy(), ref[k]), k
+    ctx.close()
+
+
+# ---------------------------------------------------------------- a1: gather + sum-pool
+@pytest.mark.parametrize("cfg", [small_cfg(n_tasks=5), TINY, SMALL.with_(n_tasks=6)], ids=["mini", "tiny", "small6"])
+def test_gather_pool(gm, cfg):
+    print("gather_pool", cfg.name, flush=True)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
+    x = ctx.gather_pool(_to_dev(sup, ctx.device), params.emb.to(ctx.device)).cpu().numpy()
+    ref = O.gather_pool(oracle_model(cfg), params.emb.numpy(), sup.numpy())
+    assert x.shape == ref.shape
+    # bag size 1 (Tiny): a pure gather, exact
+    if cfg.bag_max == 1:
+        assert np.array_equal(x, ref.astype(np.float32))
+    assert max(rel_err(x, ref)) <= 1e-6
+    ctx.close()
+
+
+# ---------------------------------------------------------------- the whole step
+@pytest.mark.parametrize("K,order", [(0, 1), (1, 1), (1, 2), (2, 1), (2, 2), (3, 2)])
+def test_meta_step_mini(gm, K, order):
+    cfg = small_cfg(n_tasks=5, inner_lr=0.3)
+    sup, qry, params = _inputs(cfg, emb_std=0.3)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
+    _compare_step(cfg, ctx, sup, qry, params, K, order, TOL_FP32, f"mini K={K} order={order}")
+    ctx.close()
+
+
+@pytest.mark.parametrize("order", [1, 2])
+def test_meta_step_tiny_config(gm, order):
+    """configs[0] at full size."""
+    cfg = TINY
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
+    _compare_step(cfg, ctx, sup, qry, params, cfg.inner_steps, order, TOL_FP32, f"tiny order={order}")
+    ctx.close()
+
+
+def test_meta_step_small_config_subset(gm):
+    """configs[1] shape (26 fields x 100k rows x 32, multi-hot Zipf bags, MLP 845-256-128-1), 8 tasks."""
+    cfg = SMALL.with_(n_tasks=8)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=2 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, 1, 2, TOL_FP32, "small8 K=1 order=2")
+    _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_FP32, "small8 K=2 order=2")
+    ctx.close()
+
+
+def test_waves_give_the_same_result(gm):
+    """A workspace too small for one wave splits the tasks; results agree with the single-wave run."""
+    cfg = SMALL.with_(n_tasks=8)
+    sup, qry, params = _inputs(cfg)
+    big = gm.from_config(cfg, workspace_bytes=2 << 30)
+    need = big.workspace_bytes(8, sup.n_samples, qry.n_samples, sup.nnz, qry.nnz, 2, 2)
+    small = gm.from_config(cfg, workspace_bytes=int(need * 0.45))
+    dev = big.device
+    a = big.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), 0.01, 2, 2)
+    b = small.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), 0.01, 2, 2)
+    n = int(a["n_emb_rows"].item())
+    assert n == int(b["n_emb_rows"].item())
+    assert torch.equal(a["emb_rows"][:n], b["emb_rows"][:n])
+    assert torch.equal(a["task_loss"], b["task_loss"])
+    assert max(rel_err(b["emb_grad"][:n].cpu().numpy(), a["emb_grad"][:n].cpu().numpy())) < 1e-6
+    for l in range(3):
+        assert max(rel_err(b["dW"][l].cpu().numpy(), a["dW"][l].cpu().numpy())) < 1e-5
+    big.close()
+    small.close()
+
+
+def test_determinism(gm):
+    cfg = SMALL.with_(n_tasks=4)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+    dev = ctx.device
+    a = ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), 0.01, 1, 2)
+    b = ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), 0.01, 1, 2)
+    n = int(a["n_emb_rows"].item())
+    assert torch.equal(a["emb_grad"][:n], b["emb_grad"][:n])
+    assert torch.equal(a["loss"], b["loss"])
+    for l in range(3):
+        assert torch.equal(a["dW"][l], b["dW"][l])
+    ctx.close()
+
+
+# ---------------------------------------------------------------- edge cases and error paths
+def test_ragged_and_empty_tasks(gm):
+    """Variable task sizes including a task with no support samples and empty bags."""
+    from synth.generate import SetData
+    cfg = small_cfg(n_tasks=4, inner_lr=0.2)
+    sup, qry, params = _inputs(cfg, emb_std=0.3)
+
+    def drop_task_samples(sd, t):   # remove all samples of task t
+        F = cfg.n_fields
+        lo, hi = int(sd.task_offsets[t]), int(sd.task_offsets[t + 1])
+        p0, p1 = int(sd.bag_offsets[lo * F]), int(sd.bag_offsets[hi * F])
+        offs = torch.cat([sd.bag_offsets[: lo * F], sd.bag_offsets[hi * F:] - (p1 - p0)])
+        toff = sd.task_offsets.copy()
+        toff[t + 1:] -= hi - lo
+        keep = torch.ones(sd.n_samples, dtype=torch.bool)
+        keep[lo:hi] = False
+        return SetData(toff, offs, torch.cat([sd.indices[:p0], sd.indices[p1:]]), sd.dense[keep], sd.labels[keep])
+
+    sup2 = drop_task_samples(sup, 1)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
+    _compare_step(cfg, ctx, sup2, qry, params, 2, 2, TOL_FP32, "empty-support-task")
+    ctx.close()
+
+
+def test_error_paths(gm):
+    from paper_2401_04338_amd import GMetaError
+    cfg = small_cfg(n_tasks=3)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
+    dev = ctx.device
+    p = _params_dev(params, dev)
+    bad = _to_dev(sup, dev)
+    bad.indices = bad.indices.clone()
+    bad.indices[3] = cfg.rows_per_field        # out of range
+    with pytest.raises(GMetaError) as e:
+        ctx.meta_step(bad, _to_dev(qry, dev), p, 0.1, 1, 2)
+    assert e.value.code == -2
+    bad2 = _to_dev(sup, dev)
+    bad2.bag_offsets = bad2.bag_offsets.clone()
+    bad2.bag_offsets[5] = bad2.bag_offsets[6] + 1   # not monotone
+    with pytest.raises(GMetaError) as e:
+        ctx.meta_step(bad2, _to_dev(qry, dev), p, 0.1, 1, 2)
+    assert e.value.code == -2
+    with pytest.raises(GMetaError) as e:
+        ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), p, 0.1, 1, 2, emb_rows_capacity=3)
+    assert e.value.code == -3
+    with pytest.raises(GMetaError) as e:
+        ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), p, 0.1, 1, 3)
+    assert e.value.code == -1
+    # the context still works after errors
+    _compare_step(cfg, ctx, sup, qry, params, 1, 2, TOL_FP32, "after-errors")
+    ctx.close()
+
+
+def test_scatter_add_is_the_outer_update(gm):
+    cfg = small_cfg(n_tasks=3)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
+    dev = ctx.device
+    out = ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), 0.1, 1, 2)
+    n = int(out["n_emb_rows"].item())
+    table = params.emb.to(dev).clone()
+    ctx.scatter_add(table, out["emb_rows"][:n], out["emb_grad"][:n], -0.5)
+    want = params.emb.clone()
+    want[out["emb_rows"][:n].cpu()] -= 0.5 * out["emb_grad"][:n].cpu()
+    assert torch.equal(table.cpu(), want)
+    ctx.close()
