@@ -129,6 +129,13 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
                   int64_t* emb_rows, int64_t* seg_counts, int64_t* n_emb_rows,
                   int64_t emb_rows_capacity);
 
+/* Kernel timing for measurement harnesses (not part of the method): while enabled, every kernel family
+ * launched by later calls is bracketed by HIP events on the context's stream.  gm_profile_report returns
+ * HOST text owned by the context, one line per family: "name launches total_ms algorithmic_bytes
+ * algorithmic_flops".  Enabling clears the accumulated figures. */
+int gm_profile(gm_ctx* ctx, int enable);
+const char* gm_profile_report(gm_ctx* ctx);
+
 #ifdef __cplusplus
 }
 #endif

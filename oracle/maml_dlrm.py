@@ -30,6 +30,19 @@ multiplicity; an empty bag pools to zero; the sparse output lists every row
 looked up by any support or query sample, ascending by global row id
 (field_base[f] + index).
 
+Operand precision.  By default everything is float64.  With operand="bf16" the
+operands of the hidden-layer matrix products -- the model input x, the weights
+W_l (l < L), the activations a_l, the deltas delta_l (l < L), and their tangent
+counterparts -- are rounded to bfloat16 (round to nearest even) at the points
+where a mixed-precision kernel would store them; sums, biases, the last layer,
+the loss, the SGD updates and the embedding-row arithmetic stay float64.  This
+exists because a ReLU mask is a yes/no decision taken on a floating-point
+value: a path that stores bf16 activations decides it on the rounded operands,
+and a float64 oracle compared with it would differ by whole gradient terms
+wherever a pre-activation sits within rounding distance of zero.  Both sides
+must take that decision in the same precision; the rounding below is the only
+place where the oracle departs from float64, and q = identity recovers it.
+
 Pins (tests/test_oracle_*.py): central finite differences of the loss and of
 the meta-objective, K=0 and alpha=0 identities, the K=1 relation
 order2 = (I - alpha*H) order1 with H pinned by differences of the gradient,
@@ -68,6 +81,26 @@ class Model:
         return len(self.layer_dims) - 1
 
 
+def round_bf16(x):
+    """Round float values to the nearest bfloat16 (ties to even), returned as float64."""
+    a = np.ascontiguousarray(np.asarray(x, dtype=np.float64).astype(np.float32))
+    u = a.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+def _identity(x):
+    return x
+
+
+def quantizer(operand: str):
+    if operand == "fp64":
+        return _identity
+    if operand == "bf16":
+        return round_bf16
+    raise ValueError("operand must be 'fp64' or 'bf16'")
+
+
 def sigmoid(z):
     return 0.5 * (1.0 + np.tanh(0.5 * z))
 
@@ -99,14 +132,19 @@ def pool(model: Model, E: np.ndarray, loc: np.ndarray, bag: np.ndarray, n: int) 
     return out.reshape(n, model.n_fields * model.emb_dim)
 
 
-def forward(x: np.ndarray, W: List[np.ndarray], b: List[np.ndarray]):
+def _w(W, l, q):
+    """Weights of layer l as the matrix product reads them: rounded for hidden layers, exact for the last."""
+    return q(W[l]) if l < len(W) - 1 else W[l]
+
+
+def forward(x: np.ndarray, W: List[np.ndarray], b: List[np.ndarray], q=_identity):
     """a_0 = x; z_l = a_{l-1} W_l + b_l; a_l = relu(z_l) for l < L.  Returns ([a_0..a_{L-1}], z_L)."""
-    acts = [x]
+    acts = [q(x)]
     L = len(W)
     for l in range(L):
-        z = acts[-1] @ W[l] + b[l]
+        z = acts[-1] @ _w(W, l, q) + b[l]
         if l < L - 1:
-            acts.append(np.where(z > 0.0, z, 0.0))
+            acts.append(q(np.where(z > 0.0, z, 0.0)))
     return acts, z[:, 0]
 
 
@@ -114,7 +152,7 @@ def set_loss(z: np.ndarray, y: np.ndarray) -> float:
     return float(np.mean(bce_with_logits(z, y))) if len(y) else 0.0
 
 
-def backward(acts, z, y, W):
+def backward(acts, z, y, W, q=_identity):
     """Gradient of the mean BCE w.r.t. W_l, b_l and the input x.  Also returns the deltas."""
     n = len(y)
     L = len(W)
@@ -124,13 +162,13 @@ def backward(acts, z, y, W):
         deltas[l] = delta
         dW[l] = acts[l].T @ delta
         db[l] = delta.sum(axis=0)
-        da = delta @ W[l].T
+        da = delta @ _w(W, l, q).T
         if l > 0:
-            delta = da * (acts[l] > 0.0)
+            delta = q(da * (acts[l] > 0.0))
     return dW, db, da, deltas
 
 
-def hvp(acts, z, y, W, deltas, vW, vb, vx):
+def hvp(acts, z, y, W, deltas, vW, vb, vx, q=_identity):
     """Hessian of the mean BCE (w.r.t. W, b and the input x) times (vW, vb, vx).
 
     Tangent (forward) pass through the forward AND the backward pass of the
@@ -140,19 +178,19 @@ def hvp(acts, z, y, W, deltas, vW, vb, vx):
     L = len(W)
     sg = sigmoid(z)
     # tangent of the forward pass
-    ta = [vx]
+    ta = [q(vx)]
     for l in range(L):
-        tz = ta[-1] @ W[l] + acts[l] @ vW[l] + vb[l]
+        tz = ta[-1] @ _w(W, l, q) + acts[l] @ _w(vW, l, q) + vb[l]
         if l < L - 1:
-            ta.append(tz * (acts[l + 1] > 0.0))
+            ta.append(q(tz * (acts[l + 1] > 0.0)))
     tdelta = (sg * (1.0 - sg) * tz[:, 0] / max(n, 1))[:, None]
     hW, hb = [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
         hW[l] = ta[l].T @ deltas[l] + acts[l].T @ tdelta
         hb[l] = tdelta.sum(axis=0)
-        tda = tdelta @ W[l].T + deltas[l] @ vW[l].T
+        tda = tdelta @ _w(W, l, q).T + deltas[l] @ _w(vW, l, q).T
         if l > 0:
-            tdelta = tda * (acts[l] > 0.0)
+            tdelta = q(tda * (acts[l] > 0.0))
     return hW, hb, tda
 
 
@@ -160,7 +198,7 @@ def hvp(acts, z, y, W, deltas, vW, vb, vx):
 # one task
 # --------------------------------------------------------------------------
 def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int, order: int,
-                   full_table: bool = False):
+                   full_table: bool = False, operand: str = "fp64"):
     """MAML for task t.  Returns (L^Query, gW, gb, rows, gxi[rows]) w.r.t. the META parameters.
 
     full_table=True copies the whole table into the task (brute force: phi_0 is
@@ -168,6 +206,7 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
     """
     F, D = model.n_fields, model.emb_dim
     FD = F * D
+    q = quantizer(operand)
     s_lo, s_hi = int(sup["task_offsets"][t]), int(sup["task_offsets"][t + 1])
     q_lo, q_hi = int(qry["task_offsets"][t]), int(qry["task_offsets"][t + 1])
     ns, nq = s_hi - s_lo, q_hi - q_lo
@@ -198,8 +237,8 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
     tape = []
     for _ in range(K):
         x = np.concatenate([pool(model, E, loc_s, bag_s, ns), dense_s], axis=1)
-        acts, z = forward(x, W, b)
-        dW, db, dx, deltas = backward(acts, z, ys, W)
+        acts, z = forward(x, W, b, q)
+        dW, db, dx, deltas = backward(acts, z, ys, W, q)
         tape.append((acts, z, W, deltas))
         gE = rows_grad(dx, loc_s, bag_s)
         E = E - alpha * gE
@@ -208,16 +247,16 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
 
     # outer forward/backward on the query set with the adapted parameters
     xq = np.concatenate([pool(model, E, loc_q, bag_q, nq), dense_q], axis=1)
-    acts, z = forward(xq, W, b)
+    acts, z = forward(xq, W, b, q)
     loss_q = set_loss(z, yq)
-    vW, vb, dx, _ = backward(acts, z, yq, W)
+    vW, vb, dx, _ = backward(acts, z, yq, W, q)
     vE = rows_grad(dx, loc_q, bag_q)
 
     # chain back through the inner steps: v_k = v_{k+1} - alpha * H_k v_{k+1}
     if order == 2:
         for acts_k, z_k, W_k, deltas_k in reversed(tape):
             vx = np.concatenate([pool(model, vE, loc_s, bag_s, ns), np.zeros_like(dense_s)], axis=1)
-            hW, hb, hx = hvp(acts_k, z_k, ys, W_k, deltas_k, vW, vb, vx)
+            hW, hb, hx = hvp(acts_k, z_k, ys, W_k, deltas_k, vW, vb, vx, q)
             hE = rows_grad(hx, loc_s, bag_s)
             vW = [v - alpha * h for v, h in zip(vW, hW)]
             vb = [v - alpha * h for v, h in zip(vb, hb)]
@@ -234,7 +273,7 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
 # the whole step
 # --------------------------------------------------------------------------
 def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
-              tasks: Optional[Sequence[int]] = None, full_table: bool = False):
+              tasks: Optional[Sequence[int]] = None, full_table: bool = False, operand: str = "fp64"):
     """Sum of the per-task meta-gradients (Alg. 1, global back-propagation steps).
 
     Returns dict(loss, task_loss[T], dW[l], db[l], emb_rows (ascending unique
@@ -248,7 +287,7 @@ def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
     task_loss = np.zeros(len(tasks))
     parts_rows, parts_grad = [], []
     for i, t in enumerate(tasks):
-        lq, vW, vb, rows, vE = task_meta_grad(model, params, sup, qry, t, alpha, K, order, full_table)
+        lq, vW, vb, rows, vE = task_meta_grad(model, params, sup, qry, t, alpha, K, order, full_table, operand)
         task_loss[i] = lq
         for l in range(L):
             gW[l] += vW[l]

@@ -5,13 +5,6 @@
 // D/4 lanes so that one wavefront keeps several independent row reads in flight.
 #include "gm_internal.h"
 
-__device__ __forceinline__ bf16_t f2bf(float x) {  // round to nearest even
-    u32 u = __builtin_bit_cast(u32, x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
-}
-
 __device__ __forceinline__ void store_bf4(bf16_t* dst, float4 v) {
     uint2 o;
     o.x = (u32)f2bf(v.x) | ((u32)f2bf(v.y) << 16);
@@ -26,7 +19,8 @@ __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(
 // ------------------------------------------------------------------------------------------------
 __global__ void gather_pool_kernel(int F, int D, int LG, const int64_t* __restrict__ field_base,
                                    const int64_t* __restrict__ bag_offsets, const int32_t* __restrict__ indices,
-                                   const float* __restrict__ emb, int64_t sample0, int64_t n_bags, float* x, int ldx,
+                                   const float* __restrict__ emb, int64_t sample0, int64_t n_bags,
+                                   const int32_t* __restrict__ row_map, int32_t row_base, float* x, int ldx,
                                    bf16_t* x_bf) {
     const int groups_per_block = blockDim.x / LG;
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
@@ -49,23 +43,25 @@ __global__ void gather_pool_kernel(int F, int D, int LG, const int64_t* __restri
         }
         for (; p < p1; ++p) acc0 = add4(acc0, emb4[(fb + indices[p]) * LG + l]);
         const float4 acc = add4(acc0, acc1);
-        const int64_t o = s * ldx + (int64_t)f * D + l * 4;
-        *reinterpret_cast<float4*>(x + o) = acc;
+        const int64_t o = (int64_t)(row_map[s] - row_base) * ldx + (int64_t)f * D + l * 4;
+        if (x) *reinterpret_cast<float4*>(x + o) = acc;
         if (x_bf) store_bf4(x_bf + o, acc);
     }
 }
 
 // dense features and zero padding behind the pooled fields
 __global__ void dense_tail_kernel(int FD, int n_dense, const float* __restrict__ dense, int64_t sample0,
-                                  int64_t n_samples, float* x, int ldx, bf16_t* x_bf) {
+                                  int64_t n_samples, const int32_t* __restrict__ row_map, int32_t row_base, float* x,
+                                  int ldx, bf16_t* x_bf) {
     const int tail = ldx - FD;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_samples * tail) return;
     const int64_t s = i / tail;
     const int c = (int)(i - s * tail);
     const float v = (dense && c < n_dense) ? dense[(sample0 + s) * n_dense + c] : 0.f;
-    x[s * ldx + FD + c] = v;
-    if (x_bf) x_bf[s * ldx + FD + c] = f2bf(v);
+    const int64_t o = (int64_t)(row_map[s] - row_base) * ldx + FD + c;
+    if (x) x[o] = v;
+    if (x_bf) x_bf[o] = f2bf(v);
 }
 
 static inline unsigned pool_grid(int64_t n_bags, int groups_per_block) {
@@ -78,17 +74,18 @@ static inline unsigned pool_grid(int64_t n_bags, int groups_per_block) {
 
 void launch_gather_pool(hipStream_t st, int F, int D, int n_dense, const int64_t* field_base,
                         const int64_t* bag_offsets, const int32_t* indices, const float* dense, const float* emb,
-                        int64_t sample0, int64_t n_samples, float* x, int ldx, bf16_t* x_bf) {
+                        int64_t sample0, int64_t n_samples, const int32_t* row_map, int32_t row_base, float* x, int ldx,
+                        bf16_t* x_bf) {
     if (n_samples <= 0) return;
     const int LG = D / 4;
     const int64_t n_bags = n_samples * F;
     if (n_bags > 0)
         hipLaunchKernelGGL(gather_pool_kernel, dim3(pool_grid(n_bags, 256 / LG)), dim3(256), 0, st, F, D, LG, field_base,
-                           bag_offsets, indices, emb, sample0, n_bags, x, ldx, x_bf);
+                           bag_offsets, indices, emb, sample0, n_bags, row_map, row_base, x, ldx, x_bf);
     const int64_t nt = n_samples * (ldx - F * D);
     if (nt > 0)
         hipLaunchKernelGGL(dense_tail_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, st, F * D, n_dense, dense,
-                           sample0, n_samples, x, ldx, x_bf);
+                           sample0, n_samples, row_map, row_base, x, ldx, x_bf);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -97,8 +94,8 @@ void launch_gather_pool(hipStream_t st, int F, int D, int n_dense, const int64_t
 __global__ void pool_slots_kernel(int F, int D, int LG, const int64_t* __restrict__ bag_offsets, int64_t sample0,
                                   int64_t lookup0, int64_t n_bags, const int32_t* __restrict__ sample_task,
                                   const int32_t* __restrict__ slot_of_lookup, const u32* __restrict__ tf_base,
-                                  const float* __restrict__ table, const float* x_base, float* x_out, int ldx,
-                                  bf16_t* x_bf) {
+                                  const float* __restrict__ table, const int32_t* __restrict__ row_map,
+                                  int32_t row_base, const float* x_base, float* x_out, int ldx, bf16_t* x_bf) {
     const int groups_per_block = blockDim.x / LG;
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
     if (g_in_block >= groups_per_block) return;
@@ -110,7 +107,7 @@ __global__ void pool_slots_kernel(int F, int D, int LG, const int64_t* __restric
         const int64_t gb = sample0 * F + bag;
         const int64_t p0 = bag_offsets[gb] - lookup0, p1 = bag_offsets[gb + 1] - lookup0;
         const int64_t base = tf_base[(int64_t)sample_task[s] * F + f];
-        const int64_t o = s * ldx + (int64_t)f * D + l * 4;
+        const int64_t o = (int64_t)(row_map[s] - row_base) * ldx + (int64_t)f * D + l * 4;
         float4 acc = x_base ? *reinterpret_cast<const float4*>(x_base + o) : make_float4(0.f, 0.f, 0.f, 0.f);
         for (int64_t p = p0; p < p1; ++p) {
             const int32_t slot = slot_of_lookup[p];
@@ -121,10 +118,11 @@ __global__ void pool_slots_kernel(int F, int D, int LG, const int64_t* __restric
     }
 }
 
-__global__ void copy_tail_kernel(int FD, const float* x_base, int64_t n_samples, float* x_out, int ldx, bf16_t* x_bf) {
+// dense and pad columns of every (padded) row: copied from x_base, or zero
+__global__ void copy_tail_kernel(int FD, const float* x_base, int64_t n_rows, float* x_out, int ldx, bf16_t* x_bf) {
     const int tail = ldx - FD;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_samples * tail) return;
+    if (i >= n_rows * tail) return;
     const int64_t s = i / tail;
     const int c = (int)(i - s * tail);
     const float v = x_base ? x_base[s * ldx + FD + c] : 0.f;
@@ -134,18 +132,19 @@ __global__ void copy_tail_kernel(int FD, const float* x_base, int64_t n_samples,
 
 void launch_pool_slots(hipStream_t st, int F, int D, const int64_t* bag_offsets, int64_t sample0, int64_t lookup0,
                        int64_t n_samples, const int32_t* sample_task, const int32_t* slot_of_lookup,
-                       const u32* tf_base, const float* table, const float* x_base, float* x_out, int ldx,
-                       bf16_t* x_bf) {
+                       const u32* tf_base, const float* table, const int32_t* row_map, int32_t row_base, int64_t n_rows,
+                       const float* x_base, float* x_out, int ldx, bf16_t* x_bf) {
     if (n_samples <= 0) return;
     const int LG = D / 4;
     const int64_t n_bags = n_samples * F;
     if (n_bags > 0)
         hipLaunchKernelGGL(pool_slots_kernel, dim3(pool_grid(n_bags, 256 / LG)), dim3(256), 0, st, F, D, LG, bag_offsets,
-                           sample0, lookup0, n_bags, sample_task, slot_of_lookup, tf_base, table, x_base, x_out, ldx, x_bf);
-    const int64_t nt = n_samples * (ldx - F * D);
-    if (nt > 0 && x_base != x_out)
+                           sample0, lookup0, n_bags, sample_task, slot_of_lookup, tf_base, table, row_map, row_base, x_base, x_out,
+                           ldx, x_bf);
+    const int64_t nt = n_rows * (ldx - F * D);
+    if (nt > 0 && (x_base != x_out || x_bf))
         hipLaunchKernelGGL(copy_tail_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, st, F * D, x_base,
-                           n_samples, x_out, ldx, x_bf);
+                           n_rows, x_out, ldx, x_bf);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -1,0 +1,235 @@
+// Grouped bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+//
+// One form serves every dense product of the MAML step (G-Meta Alg. 1: inner forward, local
+// back-propagation, outer forward, and the tangent passes of the second-order term):
+//     C_g[M, N] = sum_p  A_p,g[M, K] * Bt_p,g[N, K]^T          (p = 1 or 2 products)
+// with BOTH operands stored contraction-contiguous, so that a lane's 8 consecutive k values are one
+// 16-byte LDS read.  The caller picks pointers and strides:
+//   forward      A = activations [rows, d_in],        Bt = W^T  [d_out, d_in]
+//   backward dA  A = deltas      [rows, d_out],       Bt = W    [d_in, d_out]
+//   weight grad  A = activations^T [d_in, rows],      Bt = deltas^T [d_out, rows]   (K = rows of the task)
+// A group is a task: its rows are [row_offsets[g], row_offsets[g+1]) and, once theta has been adapted,
+// its weights are its own (group stride != 0).
+#include "gm_internal.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+#define GK 64          // k extent of one LDS tile
+#define GLD (GK + 8)   // LDS row stride in elements: 144 bytes, an odd number of 16-byte units
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group) {
+    constexpr int MI = BM / 64, NI = BN / 64;  // 32x32 blocks per wave in each direction (2x2 waves)
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t* As = smem;                 // [BM][GLD]
+    bf16_t* Bs = smem + BM * GLD;      // [BN][GLD]
+
+    const int ntile = blockIdx.x % n_ntiles;
+    const int mtile = blockIdx.x / n_ntiles;
+    int g, m0;
+    if (a.tile_group) {
+        g = a.tile_group[mtile];
+        m0 = a.tile_m0[mtile];
+    } else {
+        g = mtile / mt_per_group;
+        m0 = (mtile % mt_per_group) * BM;
+    }
+    const int64_t r0 = a.row_offsets[g];
+    const int rows_g = (int)(a.row_offsets[g + 1] - r0);
+    const int M = a.M < 0 ? rows_g : a.M;
+    const int K = a.K < 0 ? rows_g : a.K;
+    const int N = a.N;
+    const int n0 = ntile * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // global -> register staging: 16-byte chunks, 8 chunks per tile row
+    constexpr int CA = BM * 8 / 256, CB = BN * 8 / 256;  // chunks per thread
+    uint4 ra[CA], rb[CB];
+    const int crow = tid >> 3, ccol = (tid & 7) * 8;     // chunk c = tid + 256*i: row = crow + 32*i, k = ccol
+
+    const int total_kt_pair[2] = {(K + GK - 1) / GK, (K + GK - 1) / GK};
+    const int n_kt = total_kt_pair[0] * a.n_pairs;
+
+    auto load_tile = [&](int kt) {
+        const int pr = kt / total_kt_pair[0];
+        const int k0 = (kt - pr * total_kt_pair[0]) * GK;
+        const bf16_t* A = a.A[pr] + (int64_t)g * a.gA[pr] + r0 * a.rA[pr];
+        const bf16_t* B = a.B[pr] + (int64_t)g * a.gB[pr] + r0 * a.rB[pr];
+        const int64_t lda = a.lda[pr], ldb = a.ldb[pr];
+        const bool kok = k0 + ccol < K;
+#pragma unroll
+        for (int i = 0; i < CA; ++i) {
+            const int m = m0 + crow + 32 * i;
+            ra[i] = (kok && m < M) ? *reinterpret_cast<const uint4*>(A + (int64_t)m * lda + k0 + ccol) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            const int n = n0 + crow + 32 * i;
+            rb[i] = (kok && n < N) ? *reinterpret_cast<const uint4*>(B + (int64_t)n * ldb + k0 + ccol) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4*>(As + (crow + 32 * i) * GLD + ccol) = ra[i];
+#pragma unroll
+        for (int i = 0; i < CB; ++i) *reinterpret_cast<uint4*>(Bs + (crow + 32 * i) * GLD + ccol) = rb[i];
+    };
+
+    if (n_kt > 0) load_tile(0);
+    for (int kt = 0; kt < n_kt; ++kt) {
+        __syncthreads();  // previous tile fully consumed
+        store_tile();
+        __syncthreads();
+        if (kt + 1 < n_kt) load_tile(kt + 1);  // overlaps with the MFMAs below
+#pragma unroll
+        for (int kk = 0; kk < GK / 16; ++kk) {
+            bf16x8 af[MI], bfr[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                af[i] = *reinterpret_cast<const bf16x8*>(As + (wm0 + i * 32 + l32) * GLD + kk * 16 + lhi * 8);
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + (wn0 + j * 32 + l32) * GLD + kk * 16 + lhi * 8);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // epilogue: lane holds column n = l32 of each 32x32 block and rows 8*(v/4) + 4*lhi + v%4
+    const float* bias = a.bias ? a.bias + (int64_t)g * a.gBias : nullptr;
+    const bf16_t* mask = a.mask ? a.mask + r0 * a.ld_mask : nullptr;
+    const float* Cin = a.Cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
+    float* Cf = a.Cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
+    bf16_t* Cb = a.Cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
+    bf16_t* CbT = a.CbT ? a.CbT + (int64_t)g * a.gCbT + r0 * a.rCbT : nullptr;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int n = n0 + wn0 + j * 32 + l32;
+            if (n >= N) continue;
+            const float bn = bias ? bias[n] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm0 + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
+                if (m >= M) continue;
+                float x = acc[i][j][v];
+                switch (a.epi) {
+                    case EPI_BIAS_RELU: x = fmaxf(x + bn, 0.f); break;
+                    case EPI_BIAS_MASK: x = (bf2f(mask[(int64_t)m * a.ld_mask + n]) > 0.f) ? x + bn : 0.f; break;
+                    case EPI_MASK: x = (bf2f(mask[(int64_t)m * a.ld_mask + n]) > 0.f) ? x : 0.f; break;
+                    case EPI_AXPBY: x = a.c1 * x + (Cin ? a.c0 * Cin[(int64_t)m * a.ldcf + n] : 0.f); break;
+                    default: break;
+                }
+                if (Cf) Cf[(int64_t)m * a.ldcf + n] = x;
+                if (Cb) Cb[(int64_t)m * a.ldcb + n] = f2bf(x);
+                if (CbT) CbT[(int64_t)n * a.ldcbT + m] = f2bf(x);
+            }
+        }
+    }
+}
+
+template <int BM, int BN>
+static void launch_variant(hipStream_t st, const GemmBArgs& a) {
+    const int n_ntiles = (a.N + BN - 1) / BN;
+    int64_t n_mtiles;
+    int mt_per_group = 1;
+    if (a.tile_group) {
+        n_mtiles = a.n_mtiles;
+    } else {
+        mt_per_group = (a.M + BM - 1) / BM;
+        n_mtiles = (int64_t)mt_per_group * a.G;
+    }
+    if (n_mtiles <= 0 || n_ntiles <= 0) return;
+    const size_t shmem = (size_t)(BM + BN) * GLD * sizeof(bf16_t);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN>), dim3((unsigned)(n_mtiles * n_ntiles)), dim3(256), shmem, st, a,
+                       n_ntiles, mt_per_group);
+}
+
+// bm: row tile the caller built its (tile_group, tile_m0) lists for (64 or 128)
+void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm) {
+    if (bm == 64) launch_variant<64, 128>(st, a);
+    else launch_variant<128, 128>(st, a);
+}
+
+// ------------------------------------------------------------------------------------------------
+// grouped transpose of a bf16 matrix: src [P, ld] -> dst [ld, ldT]  (dst[c, r] = src[r, c])
+// ------------------------------------------------------------------------------------------------
+__global__ void transpose_bf16_kernel(const bf16_t* __restrict__ src, int64_t P, int ld, bf16_t* dst, int64_t ldT,
+                                      int64_t g_src, int64_t g_dst) {
+    __shared__ bf16_t tile[64][66];
+    src += (int64_t)blockIdx.z * g_src;
+    dst += (int64_t)blockIdx.z * g_dst;
+    const int64_t r0 = (int64_t)blockIdx.y * 64;
+    const int c0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 256 threads: 4 rows at a time
+    for (int i = ty; i < 64; i += 4) {
+        const int64_t r = r0 + i;
+        const int c = c0 + tx;
+        tile[i][tx] = (r < P && c < ld) ? src[r * ld + c] : (bf16_t)0;
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int c = c0 + i;
+        const int64_t r = r0 + tx;
+        if (c < ld && r < P) dst[(int64_t)c * ldT + r] = tile[tx][i];
+    }
+}
+
+void launch_transpose_bf16(hipStream_t st, const bf16_t* src, int64_t P, int ld, bf16_t* dst, int64_t ldT, int G,
+                           int64_t g_src, int64_t g_dst) {
+    if (P <= 0 || ld <= 0 || G <= 0) return;
+    for (int g0 = 0; g0 < G; g0 += 32768) {
+        const int gc = (G - g0) < 32768 ? (G - g0) : 32768;
+        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((ld + 63) / 64, (unsigned)((P + 63) / 64), gc), dim3(256), 0, st,
+                           src + (int64_t)g0 * g_src, P, ld, dst + (int64_t)g0 * g_dst, ldT, g_src, g_dst);
+    }
+}
+
+// fp32 padded weights [rows, cols] -> bf16 W [rows, cols] and W^T [cols, rows], per group
+__global__ void convert_weights_kernel(const float* __restrict__ src, int64_t g_src, int rows, int cols, bf16_t* w,
+                                       bf16_t* wT, int64_t g_dst) {
+    __shared__ float tile[32][33];
+    const int g = blockIdx.z;
+    const float* s = src + (int64_t)g * g_src;
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 256 threads: 8 rows at a time
+    for (int i = ty; i < 32; i += 8) {
+        const int r = r0 + i, c = c0 + tx;
+        const float v = (r < rows && c < cols) ? s[(int64_t)r * cols + c] : 0.f;
+        tile[i][tx] = v;
+        if (w && r < rows && c < cols) w[(int64_t)g * g_dst + (int64_t)r * cols + c] = f2bf(v);
+    }
+    __syncthreads();
+    if (!wT) return;
+    for (int i = ty; i < 32; i += 8) {
+        const int c = c0 + i, r = r0 + tx;
+        if (c < cols && r < rows) wT[(int64_t)g * g_dst + (int64_t)c * rows + r] = f2bf(tile[tx][i]);
+    }
+}
+
+void launch_convert_weights(hipStream_t st, const float* src, int64_t g_src, int G, int rows, int cols, bf16_t* w,
+                            bf16_t* wT, int64_t g_dst) {
+    if (G <= 0 || rows <= 0 || cols <= 0) return;
+    for (int g0 = 0; g0 < G; g0 += 32768) {
+        const int gc = (G - g0) < 32768 ? (G - g0) : 32768;
+        hipLaunchKernelGGL(convert_weights_kernel, dim3((cols + 31) / 32, (rows + 31) / 32, gc), dim3(256), 0, st,
+                           src + (int64_t)g0 * g_src, g_src, rows, cols, w ? w + (int64_t)g0 * g_dst : nullptr,
+                           wT ? wT + (int64_t)g0 * g_dst : nullptr, g_dst);
+    }
+}

@@ -9,6 +9,16 @@ typedef uint32_t u32;
 typedef uint64_t u64;
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 
+#ifdef __HIPCC__
+__device__ __forceinline__ bf16_t f2bf(float x) {  // round to nearest even; NaN stays NaN
+    u32 u = __builtin_bit_cast(u32, x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(bf16_t h) { return __builtin_bit_cast(float, (u32)h << 16); }
+#endif
+
 // Device-side status word indices (ctx->d_status).
 enum { ST_BAD_INDEX = 0, ST_CAPACITY = 1, ST_MAX_TF = 2, ST_NROWS = 3, ST_WORDS = 8 };
 
@@ -48,13 +58,17 @@ struct TfSortArgs {
     int32_t* qry_sorted_sample;     // [nnz_qry_w]       (may be null: then query segments are skipped)
     int32_t* qseg_lo;               // [nnz_sup_w]       at base_sup[tf] + slot : range in the sorted query list
     int32_t* qseg_hi;
+    // row of every sample (whole set) in the activation buffers, and the wave's first row
+    const int32_t* sup_rows; int32_t sup_row_base;
+    const int32_t* qry_rows; int32_t qry_row_base;
     u32* status;
 };
 void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int cap);
 int tf_sort_max_cap();
 
 void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
-                       const int32_t* indices, int64_t n_bags, u32 bag_id0, u32* keys, u32* vals, u32* status);
+                       const int32_t* indices, int64_t n_bags, const int32_t* row_map, u32 row0, u32* keys,
+                       u32* vals);
 // Stable LSD radix sort of (key, val) pairs on the low `bits` bits; result ends in (keys, vals).
 void launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n,
                        int bits, u32* hist /* 256*nblk + scan tmp */);
@@ -66,14 +80,15 @@ void launch_segments(hipStream_t st, const u32* sorted_keys, int64_t n, u32* fla
 // ------------------------------------------------------------------ embedding kernels
 void launch_gather_pool(hipStream_t st, int F, int D, int n_dense, const int64_t* field_base,
                         const int64_t* bag_offsets, const int32_t* indices, const float* dense,
-                        const float* emb, int64_t sample0, int64_t n_samples, float* x, int ldx,
-                        bf16_t* x_bf /* may be null */);
+                        const float* emb, int64_t sample0, int64_t n_samples, const int32_t* row_map,
+                        int32_t row_base, float* x /* may be null */, int ldx, bf16_t* x_bf /* may be null */);
 // x_out[s, f*D:] = x_base[s, f*D:] + sum over the bag's lookups with slot >= 0 of table[base[tf]+slot]
 // (x_base null: start from zero; dense and pad columns copied from x_base or zeroed).
 void launch_pool_slots(hipStream_t st, int F, int D, const int64_t* bag_offsets, int64_t sample0,
                        int64_t lookup0, int64_t n_samples, const int32_t* sample_task,
                        const int32_t* slot_of_lookup, const u32* tf_base, const float* table,
-                       const float* x_base, float* x_out, int ldx, bf16_t* x_bf);
+                       const int32_t* row_map, int32_t row_base, int64_t n_rows, const float* x_base, float* x_out,
+                       int ldx, bf16_t* x_bf);
 // table[base+slot] = c0*table[base+slot] + c1 * sum_{i in segment} src[sample_i, f*D:]
 void launch_slot_segsum(hipStream_t st, int F, int D, int n_tf, const u32* tf_base, const u32* n_slots,
                         const int32_t* seg_lo, const int32_t* seg_hi, int seg_tf_stride,
@@ -112,15 +127,50 @@ struct GemmArgs {
 };
 void launch_gemm_f32(hipStream_t st, const GemmArgs& a);
 
+// bf16 operands, both stored contraction-contiguous: C[M,N] = sum_p A_p[M,K] * Bt_p[N,K]^T
+struct GemmBArgs {
+    const bf16_t* A[2];
+    const bf16_t* B[2];
+    int64_t lda[2], gA[2], rA[2];   // element (m,k) of group g: A + g*gA + r0(g)*rA + m*lda + k
+    int64_t ldb[2], gB[2], rB[2];   // element (n,k) of group g: B + g*gB + r0(g)*rB + n*ldb + k
+    int n_pairs;
+    int M, N, K;                    // -1: rows of the group
+    const int32_t* row_offsets;     // [G+1]
+    int G;
+    const int32_t* tile_group;      // per m-tile (null: fixed M, tiles enumerated per group)
+    const int32_t* tile_m0;
+    int n_mtiles;
+    int epi;
+    const float* bias; int64_t gBias;
+    const bf16_t* mask; int64_t ld_mask;   // mask + (r0+m)*ld_mask + n
+    const float* Cin; int64_t gCin;        // Cin + g*gCin + m*ldcf + n (EPI_AXPBY)
+    float c0, c1;
+    float* Cf; int64_t ldcf, gCf, rCf;     // fp32 output        (any of the three may be null)
+    bf16_t* Cb; int64_t ldcb, gCb, rCb;    // bf16 output
+    bf16_t* CbT; int64_t ldcbT, gCbT, rCbT;  // bf16 output, transposed: CbT + ... + n*ldcbT + m
+};
+void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm);
+// dst[g][c, r] = src[g][r, c] for r < P, c < ld  (src row stride ld, dst row stride ldT)
+void launch_transpose_bf16(hipStream_t st, const bf16_t* src, int64_t P, int ld, bf16_t* dst, int64_t ldT, int G,
+                           int64_t g_src, int64_t g_dst);
+void launch_convert_weights(hipStream_t st, const float* src, int64_t g_src, int G, int rows, int cols, bf16_t* w,
+                            bf16_t* wT, int64_t g_dst);
+
 // out[g*g_out + n] = c0*in[g*g_in + n] + c1 * sum_{s in group g} (X1[s,n]*w1[s] + X2[s,n]*w2[s])
 void launch_task_colsum(hipStream_t st, int G, const int32_t* row_offsets, int N, const float* X1,
                         const float* w1, const float* X2, const float* w2, int64_t ldx, float* out,
                         int64_t g_out, const float* in, int64_t g_in, float c0, float c1);
+void launch_task_colsum_bf(hipStream_t st, int G, const int32_t* row_offsets, int N, const bf16_t* X1,
+                           const float* w1, const bf16_t* X2, const float* w2, int64_t ldx, float* out,
+                           int64_t g_out, const float* in, int64_t g_in, float c0, float c1);
 // z[s] = a[s,:].w_g + b_g (+ ta[s,:].w_g + a[s,:].tw_g + tb_g when tangent)
 struct LastFwdArgs {
-    int64_t n; int N; int64_t ld;
-    const int32_t* sample_task; const int32_t* row_offsets;
-    const float* a; const float* ta;                 // ta null: plain forward
+    int64_t n; int N; int64_t ld;       // rows (padded), width of the last hidden layer, its leading dimension
+    int bf16;                           // activations a / ta are bf16 (else fp32)
+    const int32_t* row_task;            // [n] task of every row
+    const int32_t* row_offsets;         // [G+1] first (padded) row of each task
+    const int32_t* real_offsets;        // [G+1] first sample of each task (labels are indexed by sample)
+    const void* a; const void* ta;      // ta null: plain forward
     const float* w; int64_t gW; const float* b;      // w + g*gW [N], b + g*gW scalar
     const float* tw; int64_t gTW; const float* tb;
     const float* labels; const float* z_in;          // tangent: z of the primal pass
@@ -128,10 +178,9 @@ struct LastFwdArgs {
                                                      // tangent: delta_out = sigma'(z) * tz / N_g
 };
 void launch_last_fwd(hipStream_t st, const LastFwdArgs& a);
-// d[s,n] = (dl[s]*w_g[n] (+ dl2[s]*w2_g[n])) * (act[s,n] > 0)   (act null: no mask)
-void launch_last_bwd(hipStream_t st, int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* sample_task,
-                     const float* dl, const float* w, int64_t gW, const float* dl2, const float* w2,
-                     int64_t gW2, const float* act, float* d);
+void launch_last_bwd(hipStream_t st, int bf16, int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* row_task,
+                     const float* dl, const float* w, int64_t gW, const float* dl2, const float* w2, int64_t gW2,
+                     const void* act, void* d, float* d_f32);
 void launch_reduce_tasks(hipStream_t st, const float* v, int64_t ld, int G, int64_t n, float* out, int accumulate);
 void launch_fill_sample_task(hipStream_t st, const int32_t* row_offsets, int G, int32_t* sample_task);
 void launch_pack_weights(hipStream_t st, const float* W, int din, int dout, int ld_in, int ld_out, float* dst);

@@ -1,16 +1,28 @@
 // Host side of the library: the C ABI of include/gmeta.h and the orchestration of one MAML step
 // (G-Meta Alg. 1 with "worker" read as "task") as a fixed sequence of kernel launches on one stream.
+//
+// Data layout in HBM (per wave of tasks; a wave is as many tasks as the workspace holds):
+//   activations  [rows, ld]   rows = samples of the wave, each task's rows padded to a multiple of
+//                             `row_pad` (1 for fp32, 8 for bf16: 16-byte aligned task slices in the
+//                             transposed copies); ld = width rounded up to 32
+//   theta        [Tw, n_theta] fp32, per task once adapted; layer l at offW[l] ([ld_{l-1}, ld_l],
+//                             zero padded) and offb[l]
+//   bf16 mode    every GEMM operand also lives as bf16, activations in both orientations
+//                ([rows, ld] and [ld, rows]) and weights as W and W^T, so that every product reads
+//                both operands contraction-contiguous
+//   slot tables  [lookups of the wave's support set, D] fp32: task-local row deltas / directions,
+//                addressed base[task, field] + rank of the row in the (task, field) dictionary
 #include <algorithm>
+#include <chrono>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <string>
 #include <vector>
 
 #include "../../include/gmeta.h"
 #include "gm_internal.h"
-
-#define GEMM_BM 64
 
 struct Arena {
     char* base = nullptr;
@@ -30,13 +42,24 @@ struct Arena {
     }
 };
 
+struct ProfEntry {
+    int64_t launches = 0;
+    double ms = 0, bytes = 0, flops = 0;
+};
+struct ProfPending {
+    std::string name;
+    hipEvent_t e0, e1;
+    double bytes, flops;
+};
+
 struct gm_ctx {
     int F = 0, D = 0, n_dense = 0, L = 0, mlp_dtype = 0;
     std::vector<int64_t> rows, field_base;
     std::vector<int> dims, ld;
-    std::vector<int64_t> offW, offb;
-    int64_t n_theta = 0;
-    int FD = 0;
+    std::vector<int64_t> offW, offb;    // fp32 theta layout
+    std::vector<int64_t> offWb, offWTb; // bf16 theta layout: W_l and W_l^T, l = 1..L-1
+    int64_t n_theta = 0, n_theta_b = 0;
+    int FD = 0, row_pad = 1;
     int device = 0;
     hipStream_t stream = nullptr;
     char* ws = nullptr;
@@ -45,6 +68,12 @@ struct gm_ctx {
     int64_t* d_field_base = nullptr;
     u32* d_status = nullptr;
     std::string err;
+    // optional kernel timing
+    bool prof_on = false;
+    std::vector<ProfPending> prof_pending;
+    std::vector<hipEvent_t> prof_free;
+    std::map<std::string, ProfEntry> prof;
+    std::string prof_text;
 };
 
 static int fail(gm_ctx* c, int code, const char* fmt, ...) {
@@ -57,13 +86,60 @@ static int fail(gm_ctx* c, int code, const char* fmt, ...) {
     return code;
 }
 
-#define HIPCHK(c, call)                                                                              \
-    do {                                                                                             \
-        hipError_t e_ = (call);                                                                      \
-        if (e_ != hipSuccess) return fail(c, GM_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_));   \
+#define HIPCHK(c, call)                                                                            \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) return fail(c, GM_ERR_HIP, "%s: %s", #call, hipGetErrorString(e_)); \
     } while (0)
 
+// Brackets the launches issued during its lifetime with two events on the context's stream.
+struct Prof {
+    gm_ctx* c;
+    ProfPending p;
+    bool on;
+    Prof(gm_ctx* c_, const char* name, double bytes, double flops) : c(c_), on(c_->prof_on) {
+        if (!on) return;
+        p.name = name;
+        p.bytes = bytes;
+        p.flops = flops;
+        for (hipEvent_t* e : {&p.e0, &p.e1}) {
+            if (!c->prof_free.empty()) {
+                *e = c->prof_free.back();
+                c->prof_free.pop_back();
+            } else if (hipEventCreate(e) != hipSuccess) {
+                on = false;
+                return;
+            }
+        }
+        (void)hipEventRecord(p.e0, c->stream);
+    }
+    ~Prof() {
+        if (!on) return;
+        (void)hipEventRecord(p.e1, c->stream);
+        c->prof_pending.push_back(p);
+    }
+};
+
+static void prof_drain(gm_ctx* c) {  // after the stream has been synchronised
+    for (ProfPending& p : c->prof_pending) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.e0, p.e1) == hipSuccess) {
+            ProfEntry& e = c->prof[p.name];
+            e.launches += 1;
+            e.ms += ms;
+            e.bytes += p.bytes;
+            e.flops += p.flops;
+        }
+        c->prof_free.push_back(p.e0);
+        c->prof_free.push_back(p.e1);
+    }
+    c->prof_pending.clear();
+}
+
+static void zero_bf16(hipStream_t st, bf16_t* p, int64_t n) { launch_fill_u32(st, reinterpret_cast<u32*>(p), (n + 1) / 2, 0u); }
+
 static int round_up(int x, int m) { return (x + m - 1) / m * m; }
+static int64_t round_up64(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 static int model_layout(gm_ctx* c, const gm_model_desc* m) {
     if (!m || m->n_fields < 0 || m->n_layers < 1 || !m->layer_dims || (m->n_fields > 0 && !m->rows_per_field))
@@ -76,6 +152,7 @@ static int model_layout(gm_ctx* c, const gm_model_desc* m) {
     c->n_dense = m->n_dense;
     c->L = m->n_layers;
     c->mlp_dtype = m->mlp_dtype;
+    c->row_pad = m->mlp_dtype ? 8 : 1;
     c->FD = c->F * D;
     c->rows.assign(m->rows_per_field, m->rows_per_field + c->F);
     c->field_base.assign(c->F + 1, 0);
@@ -85,74 +162,127 @@ static int model_layout(gm_ctx* c, const gm_model_desc* m) {
     }
     if (c->field_base[c->F] >= (int64_t)1 << 32) return fail(c, GM_ERR_ARG, "more than 2^32 rows in total");
     c->dims.assign(m->layer_dims, m->layer_dims + c->L + 1);
-    if (c->dims[0] != c->FD + c->n_dense || c->dims[c->L] != 1 || c->n_dense < 0)
+    if (c->n_dense < 0 || c->dims[0] != c->FD + c->n_dense || c->dims[c->L] != 1)
         return fail(c, GM_ERR_ARG, "layer_dims must start at F*D+n_dense and end at 1");
     c->ld.resize(c->L + 1);
     for (int l = 0; l <= c->L; ++l) {
         if (c->dims[l] <= 0) return fail(c, GM_ERR_ARG, "layer_dims must be positive");
         c->ld[l] = l == c->L ? 1 : round_up(c->dims[l], 32);
     }
-    c->offW.resize(c->L + 1);
-    c->offb.resize(c->L + 1);
-    int64_t o = 0;
+    c->offW.assign(c->L + 1, 0);
+    c->offb.assign(c->L + 1, 0);
+    c->offWb.assign(c->L + 1, 0);
+    c->offWTb.assign(c->L + 1, 0);
+    int64_t o = 0, ob = 0;
     for (int l = 1; l <= c->L; ++l) {
         c->offW[l] = o;
-        o += (int64_t)c->ld[l - 1] * c->ld[l];
-        o = (o + 31) / 32 * 32;
+        o += round_up64((int64_t)c->ld[l - 1] * c->ld[l], 32);
         c->offb[l] = o;
         o += round_up(c->ld[l], 32);
+        if (l < c->L) {
+            c->offWb[l] = ob;
+            ob += (int64_t)c->ld[l - 1] * c->ld[l];
+            c->offWTb[l] = ob;
+            ob += (int64_t)c->ld[l - 1] * c->ld[l];
+        }
     }
     c->n_theta = o;
+    c->n_theta_b = std::max<int64_t>(ob, 32);
     return GM_OK;
 }
 
 // ------------------------------------------------------------------------------------------------
-// buffers
+// handles
 // ------------------------------------------------------------------------------------------------
+struct Act {  // one activation-shaped buffer [rows, ld] in the type(s) the GEMMs read
+    float* f = nullptr;    // fp32 mode
+    bf16_t* b = nullptr;   // bf16 mode: [rows, ld]
+    bf16_t* bT = nullptr;  // bf16 mode: [ld, rows]
+    int ld = 0;
+};
+struct Theta {  // parameters as the GEMMs read them; stride 0 = shared by all tasks
+    float* f = nullptr;
+    int64_t sf = 0;
+    bf16_t* b = nullptr;
+    int64_t sb = 0;
+};
+
 struct StepState {  // what one inner step leaves behind for the second-order pass
-    float* X = nullptr;                 // a_0 of the step [Ss, ld0]
-    std::vector<float*> A, Dl;          // [1..L-1]
-    float *dL = nullptr, *zL = nullptr; // [Ss]
-    float* theta = nullptr;             // parameters the step was taken at
-    int64_t theta_stride = 0;
+    Act X;
+    std::vector<Act> A, Dl;  // [1..L-1]
+    float *dL = nullptr, *zL = nullptr;
+    Theta th;                // parameters the step was taken at (GEMM operands)
+    const float* wL = nullptr;  // last-layer weights of the step, fp32
+    int64_t wL_stride = 0;
+    float* wL_copy = nullptr;   // bf16 mode: copy of the last-layer weights (the master is updated in place)
 };
 
 struct WaveBufs {
-    int32_t *row_off_s, *row_off_q, *sample_task_s, *sample_task_q;
+    int32_t *row_off_s, *row_off_q, *real_off_s, *real_off_q;
+    int32_t *sample_task_s, *sample_task_q, *row_task_s, *row_task_q;
     int32_t *tile_g_s, *tile_m_s, *tile_g_q, *tile_m_q;
     u32 *cnt_s, *base_s, *cnt_q, *base_q, *n_slots, *scan_tmp;
     u32* slot_rows;
     int32_t *slot_start, *sup_sorted_sample, *sup_slot, *qry_slot, *qry_sorted_sample, *qseg_lo, *qseg_hi;
-    float *Xs0, *Xq0, *Xs_scratch, *Delta, *vXi, *dX, *v_theta, *loss_q;
+    float *Xs0, *Xq0, *Delta, *vXi, *dX, *loss_q;
+    Theta v;  // direction / query gradient w.r.t. theta'
+    Act Xs_scratch;
     std::vector<StepState> steps;
-    std::vector<float*> thetas;  // theta^(1..K)
-    // query pass
-    float* Xq;
-    std::vector<float*> Aq, Dq;
+    std::vector<Theta> thetas;
+    Act Xq;
+    std::vector<Act> Aq, Dq;
     float *dLq, *zq;
-    // tangent temporaries
-    float* TX;
-    std::vector<float*> TA, TD;
+    Act TX;
+    std::vector<Act> TA, TD;
     float* tdL;
 };
 
 struct WaveDims {
     int Tw;
-    int64_t Ss, Sq, nnz_s, nnz_q;
+    int64_t Ss, Sq, Ps, Pq, nnz_s, nnz_q;  // real samples, padded rows, lookups
     int mt_s, mt_q;
 };
 
+static Act alloc_act(const gm_ctx* c, Arena& ar, int64_t rows, int ld, bool transposed = true) {
+    Act a;
+    a.ld = ld;
+    if (c->mlp_dtype == 0) {
+        a.f = ar.get<float>(rows * ld);
+    } else {
+        a.b = ar.get<bf16_t>(rows * ld + 8);
+        if (transposed) a.bT = ar.get<bf16_t>(rows * ld + 8);
+    }
+    return a;
+}
+static Theta alloc_theta(const gm_ctx* c, Arena& ar, int Tw, bool need_f) {
+    Theta t;
+    if (need_f) {
+        t.f = ar.get<float>((int64_t)Tw * c->n_theta);
+        t.sf = c->n_theta;
+    }
+    if (c->mlp_dtype) {
+        t.b = ar.get<bf16_t>((int64_t)Tw * c->n_theta_b);
+        t.sb = c->n_theta_b;
+    }
+    return t;
+}
+
 static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& d, int K, int order) {
     const int L = c->L, F = c->F, D = c->D;
+    const bool bf = c->mlp_dtype != 0;
     const int64_t TF = (int64_t)d.Tw * F;
     w.row_off_s = ar.get<int32_t>(d.Tw + 1);
     w.row_off_q = ar.get<int32_t>(d.Tw + 1);
-    w.sample_task_s = ar.get<int32_t>(d.Ss);
-    w.sample_task_q = ar.get<int32_t>(d.Sq);
-    w.tile_g_s = ar.get<int32_t>(d.mt_s);
-    w.tile_m_s = ar.get<int32_t>(d.mt_s);
-    w.tile_g_q = ar.get<int32_t>(d.mt_q);
-    w.tile_m_q = ar.get<int32_t>(d.mt_q);
+    w.real_off_s = ar.get<int32_t>(d.Tw + 1);
+    w.real_off_q = ar.get<int32_t>(d.Tw + 1);
+    w.sample_task_s = ar.get<int32_t>(d.Ss + 1);
+    w.sample_task_q = ar.get<int32_t>(d.Sq + 1);
+    w.row_task_s = ar.get<int32_t>(d.Ps + 1);
+    w.row_task_q = ar.get<int32_t>(d.Pq + 1);
+    w.tile_g_s = ar.get<int32_t>(d.mt_s + 1);
+    w.tile_m_s = ar.get<int32_t>(d.mt_s + 1);
+    w.tile_g_q = ar.get<int32_t>(d.mt_q + 1);
+    w.tile_m_q = ar.get<int32_t>(d.mt_q + 1);
     w.cnt_s = ar.get<u32>(TF + 1);
     w.base_s = ar.get<u32>(TF + 1);
     w.cnt_q = ar.get<u32>(TF + 1);
@@ -168,99 +298,114 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
     w.qseg_lo = ar.get<int32_t>(d.nnz_s + 1);
     w.qseg_hi = ar.get<int32_t>(d.nnz_s + 1);
     const int ld0 = c->ld[0];
-    w.Xs0 = ar.get<float>(d.Ss * ld0);
-    w.Xq0 = ar.get<float>(d.Sq * ld0);
+    w.Xs0 = ar.get<float>(d.Ps * ld0);
+    w.Xq0 = ar.get<float>(d.Pq * ld0);
     w.Delta = K > 0 ? ar.get<float>((d.nnz_s + 1) * D) : nullptr;
     const bool second = order == 2 && K > 0;
-    w.Xs_scratch = (K > 1 && !second) ? ar.get<float>(d.Ss * ld0) : nullptr;
     w.vXi = second ? ar.get<float>((d.nnz_s + 1) * D) : nullptr;
-    w.dX = ar.get<float>(std::max(d.Ss, d.Sq) * (int64_t)std::max(c->FD, 1));
-    w.v_theta = ar.get<float>((int64_t)d.Tw * c->n_theta);
-    w.loss_q = ar.get<float>(d.Sq + 1);
+    w.dX = ar.get<float>(std::max(d.Ps, d.Pq) * (int64_t)std::max(c->FD, 1) + 4);
+    w.loss_q = ar.get<float>(d.Pq + 1);
+    w.v = alloc_theta(c, ar, d.Tw, true);
+    if (!second) w.v.b = nullptr;  // the direction is a GEMM operand only in the second-order pass
+    w.Xs_scratch = Act();
+    if (K > 1 && !second) {
+        w.Xs_scratch = alloc_act(c, ar, d.Ps, ld0);
+    }
     const int kept = second ? K : (K > 0 ? 1 : 0);
     w.steps.assign(kept, StepState());
     for (int k = 0; k < kept; ++k) {
         StepState& s = w.steps[k];
-        s.X = (k == 0) ? w.Xs0 : ar.get<float>(d.Ss * ld0);
-        s.A.assign(L, nullptr);
-        s.Dl.assign(L, nullptr);
+        // fp32: step 0 reads Xs0 itself; later steps (second order) keep their own input
+        if (bf) s.X = alloc_act(c, ar, d.Ps, ld0);
+        else if (k > 0) s.X = alloc_act(c, ar, d.Ps, ld0);
+        s.X.ld = ld0;
+        s.A.assign(L, Act());
+        s.Dl.assign(L, Act());
         for (int l = 1; l < L; ++l) {
-            s.A[l] = ar.get<float>(d.Ss * c->ld[l]);
-            s.Dl[l] = ar.get<float>(d.Ss * c->ld[l]);
+            s.A[l] = alloc_act(c, ar, d.Ps, c->ld[l]);
+            s.Dl[l] = alloc_act(c, ar, d.Ps, c->ld[l]);
         }
-        s.dL = ar.get<float>(d.Ss + 1);
-        s.zL = ar.get<float>(d.Ss + 1);
+        s.dL = ar.get<float>(d.Ps + 1);
+        s.zL = ar.get<float>(d.Ps + 1);
+        s.wL_copy = (bf && second && k > 0) ? ar.get<float>((int64_t)d.Tw * c->ld[L - 1]) : nullptr;
     }
-    const int n_theta_bufs = second ? K : (K > 0 ? 1 : 0);
-    w.thetas.assign(n_theta_bufs, nullptr);
-    for (int k = 0; k < n_theta_bufs; ++k) w.thetas[k] = ar.get<float>((int64_t)d.Tw * c->n_theta);
-    w.Xq = K > 0 ? ar.get<float>(d.Sq * ld0) : w.Xq0;
-    w.Aq.assign(L, nullptr);
-    w.Dq.assign(L, nullptr);
+    // theta^(k+1), k = 0..K-1.  fp32: one buffer per kept step (the second-order pass needs them all), or one
+    // updated in place.  bf16: ONE fp32 master updated in place, and bf16 operand copies per kept step.
+    const int n_bufs = second ? K : (K > 0 ? 1 : 0);
+    w.thetas.assign(n_bufs, Theta());
+    for (int k = 0; k < n_bufs; ++k) {
+        if (bf) {
+            w.thetas[k] = alloc_theta(c, ar, d.Tw, k == 0);
+            if (k > 0) { w.thetas[k].f = w.thetas[0].f; w.thetas[k].sf = w.thetas[0].sf; }
+        } else {
+            w.thetas[k] = alloc_theta(c, ar, d.Tw, true);
+        }
+    }
+    w.Xq = alloc_act(c, ar, d.Pq, ld0);
+    if (!bf && K == 0) { /* fp32 without adaptation reads Xq0 directly */ }
+    w.Aq.assign(L, Act());
+    w.Dq.assign(L, Act());
     for (int l = 1; l < L; ++l) {
-        w.Aq[l] = ar.get<float>(d.Sq * c->ld[l]);
-        w.Dq[l] = ar.get<float>(d.Sq * c->ld[l]);
+        w.Aq[l] = alloc_act(c, ar, d.Pq, c->ld[l]);
+        w.Dq[l] = alloc_act(c, ar, d.Pq, c->ld[l]);
     }
-    w.dLq = ar.get<float>(d.Sq + 1);
-    w.zq = ar.get<float>(d.Sq + 1);
-    w.TX = nullptr;
-    w.TA.assign(L, nullptr);
-    w.TD.assign(L, nullptr);
+    w.dLq = ar.get<float>(d.Pq + 1);
+    w.zq = ar.get<float>(d.Pq + 1);
+    w.TX = Act();
+    w.TA.assign(L, Act());
+    w.TD.assign(L, Act());
     w.tdL = nullptr;
     if (second) {
-        w.TX = ar.get<float>(d.Ss * ld0);
+        w.TX = alloc_act(c, ar, d.Ps, ld0);
         for (int l = 1; l < L; ++l) {
-            w.TA[l] = ar.get<float>(d.Ss * c->ld[l]);
-            w.TD[l] = ar.get<float>(d.Ss * c->ld[l]);
+            w.TA[l] = alloc_act(c, ar, d.Ps, c->ld[l]);
+            w.TD[l] = alloc_act(c, ar, d.Ps, c->ld[l]);
         }
-        w.tdL = ar.get<float>(d.Ss + 1);
+        w.tdL = ar.get<float>(d.Ps + 1);
     }
 }
 
 struct BatchBufs {
     int64_t *toff_s, *toff_q;
-    float *GX, *theta0, *g_theta, *task_loss;
+    int32_t *prow_s, *prow_q, *prow_off_s, *prow_off_q;
+    float *GX, *g_theta, *task_loss;
+    Theta theta0;
     u32 *keys, *vals, *keys_tmp, *vals_tmp, *hist, *scan_tmp, *seg_start;
 };
 
-static void alloc_batch(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t Ss, int64_t Sq, int64_t nnz,
-                        int64_t capacity, bool need_gx) {
+static void alloc_batch(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t Ss, int64_t Sq, int64_t Ps, int64_t Pq,
+                        int64_t nnz, int64_t capacity, bool need_gx) {
     b.toff_s = ar.get<int64_t>(T + 1);
     b.toff_q = ar.get<int64_t>(T + 1);
-    b.GX = need_gx ? ar.get<float>((Ss + Sq) * (int64_t)std::max(c->FD, 1) + 4) : nullptr;
-    b.theta0 = ar.get<float>(c->n_theta);
+    b.prow_off_s = ar.get<int32_t>(T + 1);
+    b.prow_off_q = ar.get<int32_t>(T + 1);
+    b.prow_s = ar.get<int32_t>(Ss + 1);
+    b.prow_q = ar.get<int32_t>(Sq + 1);
+    b.GX = need_gx ? ar.get<float>((Ps + Pq) * (int64_t)std::max(c->FD, 1) + 4) : nullptr;
+    b.theta0 = Theta();
+    b.theta0.f = ar.get<float>(c->n_theta);
+    if (c->mlp_dtype) b.theta0.b = ar.get<bf16_t>(c->n_theta_b);
     b.g_theta = ar.get<float>(c->n_theta);
     b.task_loss = ar.get<float>(T + 1);
     b.keys = ar.get<u32>(nnz + 1);
     b.vals = ar.get<u32>(nnz + 1);
     b.keys_tmp = ar.get<u32>(nnz + 1);
     b.vals_tmp = ar.get<u32>(nnz + 1);
-    b.hist = ar.get<u32>(radix_hist_words(nnz));
+    b.hist = ar.get<u32>(radix_hist_words(nnz) + 2 * (size_t)(T + 1) * 2);
     b.scan_tmp = ar.get<u32>(scan_tmp_words(nnz));
     b.seg_start = ar.get<u32>(std::min(nnz, capacity) + 2);
 }
 
-static int count_mtiles(const int64_t* toff, int t0, int t1) {
-    int64_t n = 0;
-    for (int t = t0; t < t1; ++t) n += (toff[t + 1] - toff[t] + GEMM_BM - 1) / GEMM_BM;
-    return (int)n;
-}
-
 // ------------------------------------------------------------------------------------------------
-// ABI: create / destroy / sizes
+// ABI: create / destroy / sizes / timing
 // ------------------------------------------------------------------------------------------------
 extern "C" int gm_create(gm_ctx** out, const gm_model_desc* model, int device, void* hip_stream,
                          size_t workspace_bytes) {
     if (!out) return GM_ERR_ARG;
-    *out = nullptr;
     gm_ctx* c = new gm_ctx();
+    *out = c;  // kept on failure too, so that the message can be read; gm_destroy frees it
     int rc = model_layout(c, model);
-    if (rc != GM_OK) {
-        // keep the context so that the message can be read
-        *out = c;
-        return rc;
-    }
-    *out = c;
+    if (rc != GM_OK) return rc;
     c->device = device;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
     HIPCHK(c, hipSetDevice(device));
@@ -279,13 +424,39 @@ extern "C" int gm_create(gm_ctx** out, const gm_model_desc* model, int device, v
 extern "C" void gm_destroy(gm_ctx* c) {
     if (!c) return;
     if (c->ws) {
-        hipSetDevice(c->device);
-        hipFree(c->ws);
+        (void)hipSetDevice(c->device);
+        for (ProfPending& p : c->prof_pending) {
+            (void)hipEventDestroy(p.e0);
+            (void)hipEventDestroy(p.e1);
+        }
+        for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
+        (void)hipFree(c->ws);
     }
     delete c;
 }
 
 extern "C" const char* gm_last_error(const gm_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+extern "C" int gm_profile(gm_ctx* c, int enable) {
+    if (!c) return GM_ERR_ARG;
+    c->prof_on = enable != 0;
+    if (enable) c->prof.clear();
+    return GM_OK;
+}
+
+extern "C" const char* gm_profile_report(gm_ctx* c) {
+    if (!c) return "";
+    c->prof_text.clear();
+    char line[256];
+    for (auto& kv : c->prof) {
+        snprintf(line, sizeof line, "%s %lld %.6f %.6e %.6e\n", kv.first.c_str(), (long long)kv.second.launches,
+                 kv.second.ms, kv.second.bytes, kv.second.flops);
+        c->prof_text += line;
+    }
+    return c->prof_text.c_str();
+}
+
+static int64_t padded_upper(const gm_ctx* c, int64_t n, int T) { return n + (int64_t)T * (c->row_pad - 1); }
 
 extern "C" size_t gm_workspace_bytes(const gm_model_desc* model, int32_t n_tasks, int64_t n_support, int64_t n_query,
                                      int64_t nnz_support, int64_t nnz_query, int32_t inner_steps, int32_t order) {
@@ -297,17 +468,16 @@ extern "C" size_t gm_workspace_bytes(const gm_model_desc* model, int32_t n_tasks
     ar.get<u32>(ST_WORDS);
     BatchBufs b;
     const int64_t total_rows = c.field_base[c.F];
-    alloc_batch(&c, ar, b, n_tasks, n_support, n_query, nnz_support + nnz_query,
+    const int64_t Ps = padded_upper(&c, n_support, n_tasks), Pq = padded_upper(&c, n_query, n_tasks);
+    alloc_batch(&c, ar, b, n_tasks, n_support, n_query, Ps, Pq, nnz_support + nnz_query,
                 std::min(total_rows, nnz_support + nnz_query), true);
     WaveBufs w;
     WaveDims d;
     d.Tw = n_tasks;
-    d.Ss = n_support;
-    d.Sq = n_query;
-    d.nnz_s = nnz_support;
-    d.nnz_q = nnz_query;
-    d.mt_s = (int)(n_support / GEMM_BM + n_tasks + 1);  // upper bound on m-tiles
-    d.mt_q = (int)(n_query / GEMM_BM + n_tasks + 1);
+    d.Ss = n_support; d.Sq = n_query; d.Ps = Ps; d.Pq = Pq;
+    d.nnz_s = nnz_support; d.nnz_q = nnz_query;
+    d.mt_s = (int)(Ps / 64 + n_tasks + 1);  // upper bound on m-tiles
+    d.mt_q = (int)(Pq / 64 + n_tasks + 1);
     alloc_wave(&c, ar, w, d, inner_steps, order);
     return ar.off + (1 << 20);
 }
@@ -326,7 +496,7 @@ static int check_set(gm_ctx* c, const gm_set* s, int T, const char* name) {
         return fail(c, GM_ERR_ARG, "%s: null array", name);
     if (s->nnz > 0 && !s->indices) return fail(c, GM_ERR_ARG, "%s: null indices", name);
     if (s->n_samples == 0 && s->nnz != 0) return fail(c, GM_ERR_ARG, "%s: nnz without samples", name);
-    if (s->n_samples * (int64_t)std::max(c->F, 1) >= ((int64_t)1 << 31) || s->nnz >= ((int64_t)1 << 31))
+    if ((s->n_samples + (int64_t)T * 8) * (int64_t)std::max(c->F, 1) >= ((int64_t)1 << 31) || s->nnz >= ((int64_t)1 << 31))
         return fail(c, GM_ERR_ARG, "%s: more than 2^31 bags or lookups in one call", name);
     return GM_OK;
 }
@@ -349,188 +519,265 @@ static int read_status(gm_ctx* c, u32* host) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// GEMM argument builders
+// dense operators on handles (fp32: vector-FMA GEMM; bf16: MFMA GEMM + the transposed copies)
 // ------------------------------------------------------------------------------------------------
-struct Grp {  // the grouping of one set's samples by task inside the wave
-    const int32_t* row_off;
+struct Grp {  // grouping of one set's rows by task inside the wave
+    const int32_t *row_off, *real_off, *row_task;
     const int32_t *tile_g, *tile_m;
-    int n_mtiles, G;
+    int n_mtiles, G, bm;
+    int64_t rows;  // padded rows of the set in the wave
 };
 
-static GemmArgs gemm_base(const Grp& g) {
-    GemmArgs a;
-    memset(&a, 0, sizeof a);
-    a.row_offsets = g.row_off;
-    a.G = g.G;
-    a.n_pairs = 1;
-    return a;
+static void transpose_act(gm_ctx* c, const Act& a, int64_t rows) {
+    if (a.b && a.bT) {
+        Prof p(c, "transpose_act", 4.0 * rows * a.ld, 0);
+        launch_transpose_bf16(c->stream, a.b, rows, a.ld, a.bT, rows, 1, 0, 0);
+    }
 }
 
-// C[rows, N] = sum_p A_p[rows, K] * W_p[K, N]   (W row-major [K, ldw])
-static void set_pair_nn(GemmArgs& a, int p, const float* A, int lda, const float* W, int ldw, int64_t w_stride) {
-    a.A[p] = A; a.sAm[p] = lda; a.sAk[p] = 1; a.gA[p] = 0; a.rA[p] = lda;
-    a.B[p] = W; a.sBk[p] = ldw; a.sBn[p] = 1; a.gB[p] = w_stride; a.rB[p] = 0;
+// out[rows, ld_l] = epi( sum_p in_p[rows, ld_{l-1}] * W_p,l + bias )
+static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, const Theta* th0, const Act* in1,
+                     const Theta* th1, const float* bias, int64_t bias_stride, const Act* mask, int epi, Act& out) {
+    const int K = c->ld[l - 1], N = c->ld[l];
+    Prof p(c, "gemm_fwd", 0, 2.0 * g.rows * N * K * np);
+    const Act* ins[2] = {in0, in1};
+    const Theta* ths[2] = {th0, th1};
+    if (c->mlp_dtype == 0) {
+        GemmArgs a;
+        memset(&a, 0, sizeof a);
+        a.row_offsets = g.row_off; a.G = g.G; a.n_pairs = np;
+        for (int i = 0; i < np; ++i) {
+            a.A[i] = ins[i]->f; a.sAm[i] = K; a.sAk[i] = 1; a.rA[i] = K;
+            a.B[i] = ths[i]->f + c->offW[l]; a.sBk[i] = N; a.sBn[i] = 1; a.gB[i] = ths[i]->sf;
+        }
+        a.C = out.f; a.ldc = N; a.rC = N; a.M = -1; a.N = N; a.K = K;
+        a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
+        a.epi = epi; a.bias = bias; a.gBias = bias_stride;
+        if (mask) { a.mask = mask->f; a.ld_mask = mask->ld; }
+        launch_gemm_f32(c->stream, a);
+    } else {
+        GemmBArgs a;
+        memset(&a, 0, sizeof a);
+        a.row_offsets = g.row_off; a.G = g.G; a.n_pairs = np;
+        for (int i = 0; i < np; ++i) {
+            a.A[i] = ins[i]->b; a.lda[i] = K; a.rA[i] = K;
+            a.B[i] = ths[i]->b + c->offWTb[l]; a.ldb[i] = K; a.gB[i] = ths[i]->sb;
+        }
+        a.Cb = out.b; a.ldcb = N; a.rCb = N; a.M = -1; a.N = N; a.K = K;
+        a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
+        a.epi = epi; a.bias = bias; a.gBias = bias_stride;
+        if (mask) { a.mask = mask->b; a.ld_mask = mask->ld; }
+        launch_gemm_bf16(c->stream, a, g.bm);
+    }
+    transpose_act(c, out, g.rows);
 }
-// C[rows, N] = sum_p A_p[rows, K] * W_p^T   (W row-major [N, ldw], K = ldw's extent)
-static void set_pair_nt(GemmArgs& a, int p, const float* A, int lda, const float* W, int ldw, int64_t w_stride) {
-    a.A[p] = A; a.sAm[p] = lda; a.sAk[p] = 1; a.gA[p] = 0; a.rA[p] = lda;
-    a.B[p] = W; a.sBk[p] = 1; a.sBn[p] = ldw; a.gB[p] = w_stride; a.rB[p] = 0;
+
+// out[rows, ld_{l-1}] = mask .* sum_p d_p[rows, ld_l] * W_p,l^T ; for l == 1: dX[rows, FD] fp32, no mask
+static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, const Theta* th0, const Act* d1,
+                     const Theta* th1, const Act* mask, Act* out, float* dX) {
+    const int K = c->ld[l], N = dX ? c->FD : c->ld[l - 1];
+    if (N <= 0) return;
+    Prof p(c, "gemm_bwd", 0, 2.0 * g.rows * N * K * np);
+    const Act* ds[2] = {d0, d1};
+    const Theta* ths[2] = {th0, th1};
+    if (c->mlp_dtype == 0) {
+        GemmArgs a;
+        memset(&a, 0, sizeof a);
+        a.row_offsets = g.row_off; a.G = g.G; a.n_pairs = np;
+        for (int i = 0; i < np; ++i) {
+            a.A[i] = ds[i]->f; a.sAm[i] = K; a.sAk[i] = 1; a.rA[i] = K;
+            a.B[i] = ths[i]->f + c->offW[l]; a.sBk[i] = 1; a.sBn[i] = K; a.gB[i] = ths[i]->sf;
+        }
+        a.M = -1; a.N = N; a.K = K;
+        a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
+        if (dX) { a.C = dX; a.ldc = N; a.rC = N; a.epi = EPI_NONE; }
+        else { a.C = out->f; a.ldc = N; a.rC = N; a.epi = EPI_MASK; a.mask = mask->f; a.ld_mask = mask->ld; }
+        launch_gemm_f32(c->stream, a);
+    } else {
+        GemmBArgs a;
+        memset(&a, 0, sizeof a);
+        a.row_offsets = g.row_off; a.G = g.G; a.n_pairs = np;
+        for (int i = 0; i < np; ++i) {
+            a.A[i] = ds[i]->b; a.lda[i] = K; a.rA[i] = K;
+            a.B[i] = ths[i]->b + c->offWb[l]; a.ldb[i] = K; a.gB[i] = ths[i]->sb;
+        }
+        a.M = -1; a.N = N; a.K = K;
+        a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
+        if (dX) { a.Cf = dX; a.ldcf = N; a.rCf = N; a.epi = EPI_NONE; }
+        else { a.Cb = out->b; a.ldcb = N; a.rCb = N; a.epi = EPI_MASK; a.mask = mask->b; a.ld_mask = mask->ld; }
+        launch_gemm_bf16(c->stream, a, g.bm);
+    }
+    if (!dX) transpose_act(c, *out, g.rows);
 }
-// C_g[M, N] = sum_p A_p[rows_g, M]^T * B_p[rows_g, N]
-static void set_pair_tn(GemmArgs& a, int p, const float* A, int lda, const float* B, int ldb) {
-    a.A[p] = A; a.sAm[p] = 1; a.sAk[p] = lda; a.gA[p] = 0; a.rA[p] = lda;
-    a.B[p] = B; a.sBk[p] = ldb; a.sBn[p] = 1; a.gB[p] = 0; a.rB[p] = ldb;
+
+// out_g[ld_{l-1}, ld_l] = c0*in_g + c1 * sum_p a_p[rows_g, ld_{l-1}]^T d_p[rows_g, ld_l]  (and its bf16 copies)
+static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, const Act* d0, const Act* a1, const Act* d1,
+                     Theta& out, const float* in, int64_t in_stride, float c0, float c1) {
+    const int M = c->ld[l - 1], N = c->ld[l];
+    const Act* as[2] = {a0, a1};
+    const Act* ds[2] = {d0, d1};
+    {
+        Prof p(c, "gemm_wgrad", 0, 2.0 * g.rows * N * M * np);
+        if (c->mlp_dtype == 0) {
+            GemmArgs a;
+            memset(&a, 0, sizeof a);
+            a.row_offsets = g.row_off; a.G = g.G; a.n_pairs = np;
+            for (int i = 0; i < np; ++i) {
+                a.A[i] = as[i]->f; a.sAm[i] = 1; a.sAk[i] = M; a.rA[i] = M;
+                a.B[i] = ds[i]->f; a.sBk[i] = N; a.sBn[i] = 1; a.rB[i] = N;
+            }
+            a.C = out.f + c->offW[l]; a.ldc = N; a.gC = out.sf; a.M = M; a.N = N; a.K = -1;
+            a.epi = EPI_AXPBY; a.Cin = in ? in + c->offW[l] : nullptr; a.gCin = in_stride; a.c0 = c0; a.c1 = c1;
+            launch_gemm_f32(c->stream, a);
+        } else {
+            GemmBArgs a;
+            memset(&a, 0, sizeof a);
+            a.row_offsets = g.row_off; a.G = g.G; a.n_pairs = np;
+            for (int i = 0; i < np; ++i) {
+                a.A[i] = as[i]->bT; a.lda[i] = g.rows; a.rA[i] = 1;
+                a.B[i] = ds[i]->bT; a.ldb[i] = g.rows; a.rB[i] = 1;
+            }
+            a.Cf = out.f + c->offW[l]; a.ldcf = N; a.gCf = out.sf; a.M = M; a.N = N; a.K = -1;
+            if (out.b) { a.Cb = out.b + c->offWb[l]; a.ldcb = N; a.gCb = out.sb; }
+            a.epi = EPI_AXPBY; a.Cin = in ? in + c->offW[l] : nullptr; a.gCin = in_stride; a.c0 = c0; a.c1 = c1;
+            launch_gemm_bf16(c->stream, a, 128);
+        }
+    }
+    if (c->mlp_dtype && out.b) {
+        Prof p(c, "transpose_w", 4.0 * g.G * M * N, 0);
+        launch_transpose_bf16(c->stream, out.b + c->offWb[l], M, N, out.b + c->offWTb[l], M, g.G, out.sb, out.sb);
+    }
 }
-static void rows_out(GemmArgs& a, const Grp& g, float* C, int ldc, int N, int K) {
-    a.C = C; a.ldc = ldc; a.gC = 0; a.rC = ldc;
-    a.M = -1; a.N = N; a.K = K;
-    a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
+
+static void colsum(gm_ctx* c, const Grp& g, int N, const Act* X1, const float* w1, const Act* X2, const float* w2,
+                   float* out, int64_t g_out, const float* in, int64_t g_in, float c0, float c1) {
+    Prof p(c, "task_colsum", 0, 0);
+    if (c->mlp_dtype == 0)
+        launch_task_colsum(c->stream, g.G, g.row_off, N, X1->f, w1, X2 ? X2->f : nullptr, w2, X1->ld, out, g_out, in, g_in,
+                           c0, c1);
+    else
+        launch_task_colsum_bf(c->stream, g.G, g.row_off, N, X1->b, w1, X2 ? X2->b : nullptr, w2, X1->ld, out, g_out, in,
+                              g_in, c0, c1);
 }
-static void theta_out(GemmArgs& a, float* C, int64_t stride, int M, int N, const float* Cin, int64_t cin_stride,
-                      float c0, float c1) {
-    a.C = C; a.ldc = N; a.gC = stride; a.rC = 0;
-    a.M = M; a.N = N; a.K = -1;
-    a.tile_group = nullptr;
-    a.epi = EPI_AXPBY; a.Cin = Cin; a.gCin = cin_stride; a.c0 = c0; a.c1 = c1;
+static void colsum_f32(gm_ctx* c, const Grp& g, int N, const float* X1, int64_t ldx, float* out, int64_t g_out,
+                       const float* in, int64_t g_in, float c0, float c1) {
+    Prof p(c, "task_colsum", 0, 0);
+    launch_task_colsum(c->stream, g.G, g.row_off, N, X1, nullptr, nullptr, nullptr, ldx, out, g_out, in, g_in, c0, c1);
 }
+
+static const void* act_ptr(const gm_ctx* c, const Act& a) { return c->mlp_dtype ? (const void*)a.b : (const void*)a.f; }
+static void* act_ptr(const gm_ctx* c, Act& a) { return c->mlp_dtype ? (void*)a.b : (void*)a.f; }
 
 struct Pass {  // activations of one forward/backward pass over one set
-    float* X; int64_t n;
-    std::vector<float*>*A, *Dl;
+    Act* X;
+    std::vector<Act>*A, *Dl;
     float *dL, *zL;
 };
 
-// forward with parameters theta (stride 0: shared by all tasks), loss and delta_L; then backward to the
-// deltas of every layer and, when dX is given, to the pooled-input gradient [n, FD].
-static void forward_backward(gm_ctx* c, const Grp& g, const int32_t* sample_task, const float* labels,
-                             const Pass& p, const float* theta, int64_t ts, float* loss_out, float* dX) {
+// forward with parameters th (GEMM operands) / thf (fp32: biases and the last layer), loss and delta_L; then
+// backward to the deltas of every layer and, when dX is given, to the pooled-input gradient [rows, FD].
+static void forward_backward(gm_ctx* c, const Grp& g, const float* labels, const Pass& p, const Theta& th,
+                             const float* thf, int64_t thf_stride, float* loss_out, float* dX) {
     hipStream_t st = c->stream;
     const int L = c->L;
-    const float* prev = p.X;
+    const Act* prev = p.X;
     for (int l = 1; l < L; ++l) {
-        GemmArgs a = gemm_base(g);
-        set_pair_nn(a, 0, prev, c->ld[l - 1], theta + c->offW[l], c->ld[l], ts);
-        rows_out(a, g, (*p.A)[l], c->ld[l], c->ld[l], c->ld[l - 1]);
-        a.epi = EPI_BIAS_RELU; a.bias = theta + c->offb[l]; a.gBias = ts;
-        launch_gemm_f32(st, a);
-        prev = (*p.A)[l];
+        dense_nn(c, g, l, 1, prev, &th, nullptr, nullptr, thf + c->offb[l], thf_stride, nullptr, EPI_BIAS_RELU, (*p.A)[l]);
+        prev = &(*p.A)[l];
     }
-    LastFwdArgs f;
-    memset(&f, 0, sizeof f);
-    f.n = p.n; f.N = c->ld[L - 1]; f.ld = c->ld[L - 1];
-    f.sample_task = sample_task; f.row_offsets = g.row_off;
-    f.a = prev; f.w = theta + c->offW[L]; f.gW = ts; f.b = theta + c->offb[L];
-    f.labels = labels; f.z_out = p.zL; f.delta_out = p.dL; f.loss_out = loss_out;
-    launch_last_fwd(st, f);
-    // backward
-    if (L == 1) {
-        if (dX) launch_last_bwd(st, p.n, c->FD, c->ld[0], c->FD, sample_task, p.dL, theta + c->offW[L], ts, nullptr,
-                                nullptr, 0, nullptr, dX);
-        return;
-    }
-    launch_last_bwd(st, p.n, c->ld[L - 1], c->ld[L - 1], c->ld[L - 1], sample_task, p.dL, theta + c->offW[L], ts,
-                    nullptr, nullptr, 0, (*p.A)[L - 1], (*p.Dl)[L - 1]);
-    for (int l = L - 1; l >= 1; --l) {
-        if (l == 1 && !dX) break;
-        GemmArgs a = gemm_base(g);
-        set_pair_nt(a, 0, (*p.Dl)[l], c->ld[l], theta + c->offW[l], c->ld[l], ts);
-        if (l == 1) {
-            rows_out(a, g, dX, c->FD, c->FD, c->ld[l]);
-            a.epi = EPI_NONE;
-        } else {
-            rows_out(a, g, (*p.Dl)[l - 1], c->ld[l - 1], c->ld[l - 1], c->ld[l]);
-            a.epi = EPI_MASK; a.mask = (*p.A)[l - 1]; a.ld_mask = c->ld[l - 1];
+    const float* wL = thf + c->offW[L];
+    {
+        Prof pr(c, "last_layer", 0, 0);
+        LastFwdArgs f;
+        memset(&f, 0, sizeof f);
+        f.n = g.rows; f.N = c->ld[L - 1]; f.ld = c->ld[L - 1]; f.bf16 = c->mlp_dtype;
+        f.row_task = g.row_task; f.row_offsets = g.row_off; f.real_offsets = g.real_off;
+        f.a = act_ptr(c, *prev); f.w = wL; f.gW = thf_stride; f.b = thf + c->offb[L];
+        f.labels = labels; f.z_out = p.zL; f.delta_out = p.dL; f.loss_out = loss_out;
+        launch_last_fwd(st, f);
+        if (L == 1) {
+            if (dX) launch_last_bwd(st, 0, g.rows, c->FD, c->ld[0], c->FD, g.row_task, p.dL, wL, thf_stride, nullptr, nullptr,
+                                    0, nullptr, nullptr, dX);
+            return;
         }
-        launch_gemm_f32(st, a);
+        launch_last_bwd(st, c->mlp_dtype, g.rows, c->ld[L - 1], c->ld[L - 1], c->ld[L - 1], g.row_task, p.dL, wL,
+                        thf_stride, nullptr, nullptr, 0, act_ptr(c, (*p.A)[L - 1]), act_ptr(c, (*p.Dl)[L - 1]), nullptr);
+    }
+    transpose_act(c, (*p.Dl)[L - 1], g.rows);
+    for (int l = L - 1; l >= 1; --l) {
+        if (l == 1) {
+            if (dX) dense_nt(c, g, l, 1, &(*p.Dl)[l], &th, nullptr, nullptr, nullptr, nullptr, dX);
+        } else {
+            dense_nt(c, g, l, 1, &(*p.Dl)[l], &th, nullptr, nullptr, &(*p.A)[l - 1], &(*p.Dl)[l - 1], nullptr);
+        }
     }
 }
 
-// out = c0*in + c1 * (gradient of the pass w.r.t. theta), per task
-static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, float* out, const float* in, int64_t in_stride, float c0,
-                       float c1) {
-    hipStream_t st = c->stream;
+// out = c0*in + c1 * (gradient of the pass w.r.t. theta), per task; out.b (if any) gets the bf16 operand copies
+static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, Theta& out, const float* in, int64_t in_stride, float c0,
+                       float c1, float* wL_copy) {
     const int L = c->L;
-    const int64_t nt = c->n_theta;
+    const int64_t nt = out.sf;
     for (int l = 1; l < L; ++l) {
-        const float* prev = l == 1 ? p.X : (*p.A)[l - 1];
-        GemmArgs a = gemm_base(g);
-        set_pair_tn(a, 0, prev, c->ld[l - 1], (*p.Dl)[l], c->ld[l]);
-        theta_out(a, out + c->offW[l], nt, c->ld[l - 1], c->ld[l], in ? in + c->offW[l] : nullptr, in_stride, c0, c1);
-        launch_gemm_f32(st, a);
-        launch_task_colsum(st, g.G, g.row_off, c->ld[l], (*p.Dl)[l], nullptr, nullptr, nullptr, c->ld[l],
-                           out + c->offb[l], nt, in ? in + c->offb[l] : nullptr, in_stride, c0, c1);
+        const Act* prev = l == 1 ? p.X : &(*p.A)[l - 1];
+        dense_tn(c, g, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, out, in, in_stride, c0, c1);
+        colsum(c, g, c->ld[l], &(*p.Dl)[l], nullptr, nullptr, nullptr, out.f + c->offb[l], nt, in ? in + c->offb[l] : nullptr,
+               in_stride, c0, c1);
     }
-    const float* prev = L == 1 ? p.X : (*p.A)[L - 1];
-    launch_task_colsum(st, g.G, g.row_off, c->ld[L - 1], prev, p.dL, nullptr, nullptr, c->ld[L - 1], out + c->offW[L],
-                       nt, in ? in + c->offW[L] : nullptr, in_stride, c0, c1);
-    launch_task_colsum(st, g.G, g.row_off, 1, p.dL, nullptr, nullptr, nullptr, 1, out + c->offb[L], nt,
-                       in ? in + c->offb[L] : nullptr, in_stride, c0, c1);
+    const Act* prev = L == 1 ? p.X : &(*p.A)[L - 1];
+    colsum(c, g, c->ld[L - 1], prev, p.dL, nullptr, nullptr, out.f + c->offW[L], nt, in ? in + c->offW[L] : nullptr,
+           in_stride, c0, c1);
+    colsum_f32(c, g, 1, p.dL, 1, out.f + c->offb[L], nt, in ? in + c->offb[L] : nullptr, in_stride, c0, c1);
+    if (wL_copy)
+        (void)hipMemcpy2DAsync(wL_copy, c->ld[L - 1] * sizeof(float), out.f + c->offW[L], nt * sizeof(float),
+                               c->ld[L - 1] * sizeof(float), g.G, hipMemcpyDeviceToDevice, c->stream);
 }
 
-// v_theta <- v_theta - alpha * H_theta,. v ;  tdx [Ss, FD] <- (H v)'s pooled-input part
-// (tangent pass through the forward and the backward pass of step `s`, direction (v_theta, TX))
-static void hvp_step(gm_ctx* c, const Grp& g, const int32_t* sample_task, const StepState& s, int64_t n, WaveBufs& w,
-                     float alpha) {
+// v <- v - alpha * (H v)_theta ;  w.dX [rows, FD] <- (H v)'s pooled-input part
+// (tangent pass through the forward and the backward pass of step s, direction (v, TX))
+static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, float alpha, bool refresh_v_copies) {
     hipStream_t st = c->stream;
     const int L = c->L;
-    const int64_t nt = c->n_theta;
-    float* v = w.v_theta;
-    const float* tprev = w.TX;
-    const float* prev = s.X;
+    Theta& v = w.v;
+    const int64_t nt = v.sf;
+    const Act* tprev = &w.TX;
+    const Act* prev = &s.X;
     for (int l = 1; l < L; ++l) {
-        GemmArgs a = gemm_base(g);
-        a.n_pairs = 2;
-        set_pair_nn(a, 0, tprev, c->ld[l - 1], s.theta + c->offW[l], c->ld[l], s.theta_stride);
-        set_pair_nn(a, 1, prev, c->ld[l - 1], v + c->offW[l], c->ld[l], nt);
-        rows_out(a, g, w.TA[l], c->ld[l], c->ld[l], c->ld[l - 1]);
-        a.epi = EPI_BIAS_MASK; a.bias = v + c->offb[l]; a.gBias = nt; a.mask = s.A[l]; a.ld_mask = c->ld[l];
-        launch_gemm_f32(st, a);
-        tprev = w.TA[l];
-        prev = s.A[l];
+        dense_nn(c, g, l, 2, tprev, &s.th, prev, &v, v.f + c->offb[l], nt, &s.A[l], EPI_BIAS_MASK, w.TA[l]);
+        tprev = &w.TA[l];
+        prev = &s.A[l];
     }
-    LastFwdArgs f;
-    memset(&f, 0, sizeof f);
-    f.n = n; f.N = c->ld[L - 1]; f.ld = c->ld[L - 1];
-    f.sample_task = sample_task; f.row_offsets = g.row_off;
-    f.a = prev; f.ta = tprev; f.w = s.theta + c->offW[L]; f.gW = s.theta_stride; f.b = s.theta + c->offb[L];
-    f.tw = v + c->offW[L]; f.gTW = nt; f.tb = v + c->offb[L];
-    f.z_in = s.zL; f.delta_out = w.tdL;
-    launch_last_fwd(st, f);
-    // tangent of the backward pass, top layer first; each layer's direction is consumed before it is updated
-    if (L == 1) {
-        launch_last_bwd(st, n, c->FD, c->ld[0], c->FD, sample_task, w.tdL, s.theta + c->offW[L], s.theta_stride, s.dL,
-                        v + c->offW[L], nt, nullptr, w.dX);
-    } else {
-        launch_last_bwd(st, n, c->ld[L - 1], c->ld[L - 1], c->ld[L - 1], sample_task, w.tdL, s.theta + c->offW[L],
-                        s.theta_stride, s.dL, v + c->offW[L], nt, s.A[L - 1], w.TD[L - 1]);
+    const float* vwL = v.f + c->offW[L];
+    {
+        Prof pr(c, "last_layer", 0, 0);
+        LastFwdArgs f;
+        memset(&f, 0, sizeof f);
+        f.n = g.rows; f.N = c->ld[L - 1]; f.ld = c->ld[L - 1]; f.bf16 = c->mlp_dtype;
+        f.row_task = g.row_task; f.row_offsets = g.row_off; f.real_offsets = g.real_off;
+        f.a = act_ptr(c, *prev); f.ta = act_ptr(c, *tprev); f.w = s.wL; f.gW = s.wL_stride; f.b = nullptr;
+        f.tw = vwL; f.gTW = nt; f.tb = v.f + c->offb[L];
+        f.z_in = s.zL; f.delta_out = w.tdL;
+        launch_last_fwd(st, f);
+        // tangent of the backward pass, top layer first; each layer's direction is consumed before it is updated
+        if (L == 1)
+            launch_last_bwd(st, 0, g.rows, c->FD, c->ld[0], c->FD, g.row_task, w.tdL, s.wL, s.wL_stride, s.dL, vwL, nt,
+                            nullptr, nullptr, w.dX);
+        else
+            launch_last_bwd(st, c->mlp_dtype, g.rows, c->ld[L - 1], c->ld[L - 1], c->ld[L - 1], g.row_task, w.tdL, s.wL,
+                            s.wL_stride, s.dL, vwL, nt, act_ptr(c, s.A[L - 1]), act_ptr(c, w.TD[L - 1]), nullptr);
     }
-    launch_task_colsum(st, g.G, g.row_off, c->ld[L - 1], tprev, s.dL, prev, w.tdL, c->ld[L - 1], v + c->offW[L], nt,
-                       v + c->offW[L], nt, 1.f, -alpha);
-    launch_task_colsum(st, g.G, g.row_off, 1, w.tdL, nullptr, nullptr, nullptr, 1, v + c->offb[L], nt, v + c->offb[L],
-                       nt, 1.f, -alpha);
+    if (L > 1) transpose_act(c, w.TD[L - 1], g.rows);
+    colsum(c, g, c->ld[L - 1], tprev, s.dL, prev, w.tdL, v.f + c->offW[L], nt, v.f + c->offW[L], nt, 1.f, -alpha);
+    colsum_f32(c, g, 1, w.tdL, 1, v.f + c->offb[L], nt, v.f + c->offb[L], nt, 1.f, -alpha);
+    Theta vout = v;
+    if (!refresh_v_copies) vout.b = nullptr;
     for (int l = L - 1; l >= 1; --l) {
-        GemmArgs a = gemm_base(g);
-        a.n_pairs = 2;
-        set_pair_nt(a, 0, w.TD[l], c->ld[l], s.theta + c->offW[l], c->ld[l], s.theta_stride);
-        set_pair_nt(a, 1, s.Dl[l], c->ld[l], v + c->offW[l], c->ld[l], nt);
-        if (l == 1) {
-            rows_out(a, g, w.dX, c->FD, c->FD, c->ld[l]);
-            a.epi = EPI_NONE;
-        } else {
-            rows_out(a, g, w.TD[l - 1], c->ld[l - 1], c->ld[l - 1], c->ld[l]);
-            a.epi = EPI_MASK; a.mask = s.A[l - 1]; a.ld_mask = c->ld[l - 1];
-        }
-        if (c->FD > 0 || l > 1) launch_gemm_f32(st, a);
-        const float* ta_prev = l == 1 ? w.TX : w.TA[l - 1];
-        const float* a_prev = l == 1 ? s.X : s.A[l - 1];
-        GemmArgs b = gemm_base(g);
-        b.n_pairs = 2;
-        set_pair_tn(b, 0, ta_prev, c->ld[l - 1], s.Dl[l], c->ld[l]);
-        set_pair_tn(b, 1, a_prev, c->ld[l - 1], w.TD[l], c->ld[l]);
-        theta_out(b, v + c->offW[l], nt, c->ld[l - 1], c->ld[l], v + c->offW[l], nt, 1.f, -alpha);
-        launch_gemm_f32(st, b);
-        launch_task_colsum(st, g.G, g.row_off, c->ld[l], w.TD[l], nullptr, nullptr, nullptr, c->ld[l], v + c->offb[l],
-                           nt, v + c->offb[l], nt, 1.f, -alpha);
+        if (l == 1) dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, nullptr, nullptr, w.dX);
+        else dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, &s.A[l - 1], &w.TD[l - 1], nullptr);
+        const Act* ta_prev = l == 1 ? &w.TX : &w.TA[l - 1];
+        const Act* a_prev = l == 1 ? &s.X : &s.A[l - 1];
+        dense_tn(c, g, l, 2, ta_prev, &s.Dl[l], a_prev, &w.TD[l], vout, v.f, nt, 1.f, -alpha);
+        colsum(c, g, c->ld[l], &w.TD[l], nullptr, nullptr, nullptr, v.f + c->offb[l], nt, v.f + c->offb[l], nt, 1.f, -alpha);
     }
 }
 
@@ -539,8 +786,9 @@ static void hvp_step(gm_ctx* c, const Grp& g, const int32_t* sample_task, const 
 // ------------------------------------------------------------------------------------------------
 struct WavePlan {
     int t0, t1;
-    int64_t s0, s1, q0, q1;          // sample ranges
-    int64_t ls0, ls1, lq0, lq1;      // lookup ranges
+    int64_t s0, s1, q0, q1;      // sample ranges
+    int64_t ps0, ps1, pq0, pq1;  // padded row ranges
+    int64_t ls0, ls1, lq0, lq1;  // lookup ranges
 };
 
 __global__ void gather_task_lookup_offsets(const int64_t* toff, const int64_t* bag_offsets, int F, int T, int64_t* out) {
@@ -548,19 +796,26 @@ __global__ void gather_task_lookup_offsets(const int64_t* toff, const int64_t* b
     if (t <= T) out[t] = bag_offsets[toff[t] * F];
 }
 
-static void build_tiles(const int64_t* toff, int t0, int t1, std::vector<int32_t>& row_off, std::vector<int32_t>& tg,
-                        std::vector<int32_t>& tm) {
+// prow[s] = padded row of sample s (whole set): prow_off[t] + (s - toff[t])
+__global__ void fill_prow_kernel(const int64_t* toff, const int32_t* prow_off, int32_t* prow) {
+    const int t = blockIdx.x;
+    const int64_t lo = toff[t], hi = toff[t + 1];
+    for (int64_t s = lo + threadIdx.x; s < hi; s += blockDim.x) prow[s] = prow_off[t] + (int32_t)(s - lo);
+}
+
+static void build_tiles(const std::vector<int64_t>& poff, int t0, int t1, int bm, std::vector<int32_t>& row_off,
+                        std::vector<int32_t>& tg, std::vector<int32_t>& tm) {
     row_off.clear(); tg.clear(); tm.clear();
-    const int64_t base = toff[t0];
+    const int64_t base = poff[t0];
     for (int t = t0; t < t1; ++t) {
-        row_off.push_back((int32_t)(toff[t] - base));
-        const int n = (int)(toff[t + 1] - toff[t]);
-        for (int m = 0; m < n; m += GEMM_BM) {
+        row_off.push_back((int32_t)(poff[t] - base));
+        const int n = (int)(poff[t + 1] - poff[t]);
+        for (int m = 0; m < n; m += bm) {
             tg.push_back(t - t0);
             tm.push_back(m);
         }
     }
-    row_off.push_back((int32_t)(toff[t1] - base));
+    row_off.push_back((int32_t)(poff[t1] - base));
 }
 
 static int upload_i32(gm_ctx* c, int32_t* dst, const std::vector<int32_t>& v) {
@@ -569,15 +824,25 @@ static int upload_i32(gm_ctx* c, int32_t* dst, const std::vector<int32_t>& v) {
     return GM_OK;
 }
 
-static int run_index_wave(gm_ctx* c, const gm_set* sup, const gm_set* qry, const BatchBufs& b, const WavePlan& wp,
-                          WaveBufs& w) {
+struct Batch {  // host-side description of one call
+    int T;
+    const gm_set *sup, *qry;
+    std::vector<int64_t> poff_s, poff_q;  // padded row offsets per task, whole batch
+    std::vector<int64_t> ls, lq;          // lookup offsets per task (filled when several waves are needed)
+    BatchBufs b;
+};
+
+static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBufs& w) {
     hipStream_t st = c->stream;
     const int F = c->F, Tw = wp.t1 - wp.t0;
     if (F == 0 || Tw == 0) return GM_OK;
     const int64_t TF = (int64_t)Tw * F;
-    SetView vs = make_view(sup, b.toff_s, wp.s0, wp.ls0), vq = make_view(qry, b.toff_q, wp.q0, wp.lq0);
+    SetView vs = make_view(B.sup, B.b.toff_s, wp.s0, wp.ls0), vq = make_view(B.qry, B.b.toff_q, wp.q0, wp.lq0);
     launch_fill_u32(st, c->d_status, ST_WORDS, 0);
-    launch_tf_count(st, F, wp.t0, Tw, vs, vq, c->d_field_base, sup->nnz, qry->nnz, w.cnt_s, w.cnt_q, c->d_status);
+    {
+        Prof p(c, "tf_count", 8.0 * ((wp.s1 - wp.s0) + (wp.q1 - wp.q0)) * F + 4.0 * ((wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0)), 0);
+        launch_tf_count(st, F, wp.t0, Tw, vs, vq, c->d_field_base, B.sup->nnz, B.qry->nnz, w.cnt_s, w.cnt_q, c->d_status);
+    }
     u32 hs[ST_WORDS];
     int rc = read_status(c, hs);
     if (rc != GM_OK) return rc;
@@ -595,20 +860,28 @@ static int run_index_wave(gm_ctx* c, const gm_set* sup, const gm_set* qry, const
     a.n_slots = w.n_slots; a.slot_rows = w.slot_rows; a.slot_start = w.slot_start;
     a.sup_sorted_sample = w.sup_sorted_sample; a.sup_slot = w.sup_slot; a.qry_slot = w.qry_slot;
     a.qry_sorted_sample = w.qry_sorted_sample; a.qseg_lo = w.qseg_lo; a.qseg_hi = w.qseg_hi; a.status = c->d_status;
-    launch_tf_sort(st, a, cap);
+    a.sup_rows = B.b.prow_s; a.sup_row_base = (int32_t)wp.ps0;
+    a.qry_rows = B.b.prow_q; a.qry_row_base = (int32_t)wp.pq0;
+    {
+        Prof p(c, "tf_sort", 12.0 * ((wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0)), 0);
+        launch_tf_sort(st, a, cap);
+    }
     return GM_OK;
 }
 
-static int global_order(gm_ctx* c, const gm_set* sup, const gm_set* qry, const BatchBufs& b, int64_t* emb_rows,
-                        int64_t* seg_counts, int64_t capacity, int64_t* n_rows) {
+static int global_order(gm_ctx* c, const Batch& B, int64_t* emb_rows, int64_t* seg_counts, int64_t capacity,
+                        int64_t* n_rows) {
     hipStream_t st = c->stream;
     const int F = c->F;
+    const gm_set *sup = B.sup, *qry = B.qry;
+    const BatchBufs& b = B.b;
     const int64_t nnz = sup->nnz + qry->nnz;
+    Prof p(c, "global_sort", 0, 0);
     if (F > 0) {
-        launch_build_keys(st, F, c->d_field_base, sup->bag_offsets, sup->indices, sup->n_samples * F, 0u, b.keys, b.vals,
-                          c->d_status);
-        launch_build_keys(st, F, c->d_field_base, qry->bag_offsets, qry->indices, qry->n_samples * F,
-                          (u32)(sup->n_samples * F), b.keys + sup->nnz, b.vals + sup->nnz, c->d_status);
+        launch_build_keys(st, F, c->d_field_base, sup->bag_offsets, sup->indices, sup->n_samples * F, b.prow_s, 0u, b.keys,
+                          b.vals);
+        launch_build_keys(st, F, c->d_field_base, qry->bag_offsets, qry->indices, qry->n_samples * F, b.prow_q,
+                          (u32)B.poff_s[B.T], b.keys + sup->nnz, b.vals + sup->nnz);
     }
     int bits = 1;
     while (((int64_t)1 << bits) < c->field_base[c->F]) ++bits;
@@ -618,36 +891,46 @@ static int global_order(gm_ctx* c, const gm_set* sup, const gm_set* qry, const B
     return GM_OK;
 }
 
-// validates the lookups of the whole batch on the device (offsets monotone and inside nnz, indices inside
-// their tables) before any kernel trusts them
-static int plan_waves(gm_ctx* c, int T, const gm_set* sup, const gm_set* qry, const BatchBufs& b, size_t avail, int K,
-                      int order, std::vector<WavePlan>& plans) {
-    const int F = c->F;
-    std::vector<int64_t> ls(T + 1, 0), lq(T + 1, 0);
+static WaveDims wave_dims(const Batch& B, const WavePlan& p, int bm) {
+    WaveDims d;
+    d.Tw = p.t1 - p.t0;
+    d.Ss = p.s1 - p.s0; d.Sq = p.q1 - p.q0; d.Ps = p.ps1 - p.ps0; d.Pq = p.pq1 - p.pq0;
+    d.nnz_s = p.ls1 - p.ls0; d.nnz_q = p.lq1 - p.lq0;
+    int64_t ms = 0, mq = 0;
+    for (int t = p.t0; t < p.t1; ++t) {
+        ms += (B.poff_s[t + 1] - B.poff_s[t] + bm - 1) / bm;
+        mq += (B.poff_q[t + 1] - B.poff_q[t] + bm - 1) / bm;
+    }
+    d.mt_s = (int)ms; d.mt_q = (int)mq;
+    return d;
+}
+
+static int pick_bm(const gm_ctx* c, const Batch& B) {
+    if (B.T == 0) return 64;
+    const int64_t avg = (B.poff_s[B.T] + B.poff_q[B.T]) / (2 * (int64_t)B.T);
+    return (c->mlp_dtype && avg >= 96) ? 128 : 64;
+}
+
+// splits the tasks into waves that fit `avail` bytes of workspace
+static int plan_waves(gm_ctx* c, Batch& B, size_t avail, int K, int order, int bm, std::vector<WavePlan>& plans) {
+    const int F = c->F, T = B.T;
+    const gm_set *sup = B.sup, *qry = B.qry;
+    B.ls.assign(T + 1, 0);
+    B.lq.assign(T + 1, 0);
     bool have_offsets = false;
     auto fetch = [&]() -> int {
         if (have_offsets || F == 0) return GM_OK;
-        // lookup offset of every task boundary, read back once
-        // the two small arrays reuse the radix-sort histogram scratch
-        int64_t* d = reinterpret_cast<int64_t*>(b.hist);
-        const size_t need = 2 * (size_t)(T + 1) * sizeof(int64_t);
-        if (radix_hist_words(sup->nnz + qry->nnz) * sizeof(u32) < need) {
-            // tiny batches: hist may be too small; fall back to per-element copies
-            for (int t = 0; t <= T; ++t) {
-                HIPCHK(c, hipMemcpy(&ls[t], sup->bag_offsets + sup->task_offsets[t] * F, sizeof(int64_t), hipMemcpyDeviceToHost));
-                HIPCHK(c, hipMemcpy(&lq[t], qry->bag_offsets + qry->task_offsets[t] * F, sizeof(int64_t), hipMemcpyDeviceToHost));
-            }
-        } else {
-            hipLaunchKernelGGL(gather_task_lookup_offsets, dim3((T + 256) / 256), dim3(256), 0, c->stream, b.toff_s,
-                               sup->bag_offsets, F, T, d);
-            hipLaunchKernelGGL(gather_task_lookup_offsets, dim3((T + 256) / 256), dim3(256), 0, c->stream, b.toff_q,
-                               qry->bag_offsets, F, T, d + T + 1);
-            HIPCHK(c, hipMemcpyAsync(ls.data(), d, (T + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, c->stream));
-            HIPCHK(c, hipMemcpyAsync(lq.data(), d + T + 1, (T + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, c->stream));
-            HIPCHK(c, hipStreamSynchronize(c->stream));
-        }
+        int64_t* d = reinterpret_cast<int64_t*>(B.b.hist);  // scratch: the histogram area is free until the global sort
+        hipLaunchKernelGGL(gather_task_lookup_offsets, dim3((T + 256) / 256), dim3(256), 0, c->stream, B.b.toff_s,
+                           sup->bag_offsets, F, T, d);
+        hipLaunchKernelGGL(gather_task_lookup_offsets, dim3((T + 256) / 256), dim3(256), 0, c->stream, B.b.toff_q,
+                           qry->bag_offsets, F, T, d + T + 1);
+        HIPCHK(c, hipMemcpyAsync(B.ls.data(), d, (T + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipMemcpyAsync(B.lq.data(), d + T + 1, (T + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
         for (int t = 0; t <= T; ++t)
-            if (ls[t] < 0 || ls[t] > sup->nnz || lq[t] < 0 || lq[t] > qry->nnz || (t && (ls[t] < ls[t - 1] || lq[t] < lq[t - 1])))
+            if (B.ls[t] < 0 || B.ls[t] > sup->nnz || B.lq[t] < 0 || B.lq[t] > qry->nnz ||
+                (t && (B.ls[t] < B.ls[t - 1] || B.lq[t] < B.lq[t - 1])))
                 return fail(c, GM_ERR_INDEX, "bag_offsets not monotone / beyond nnz at a task boundary");
         have_offsets = true;
         return GM_OK;
@@ -660,8 +943,8 @@ static int plan_waves(gm_ctx* c, int T, const gm_set* sup, const gm_set* qry, co
             int rc = fetch();
             if (rc != GM_OK) return rc;
         } else {
-            ls[T] = sup->nnz;
-            lq[T] = qry->nnz;
+            B.ls[T] = sup->nnz;
+            B.lq[T] = qry->nnz;
         }
         for (int t0 = 0; t0 < T || (T == 0 && plans.empty()); t0 += per) {
             WavePlan p;
@@ -669,16 +952,13 @@ static int plan_waves(gm_ctx* c, int T, const gm_set* sup, const gm_set* qry, co
             p.t1 = std::min(T, t0 + per);
             p.s0 = sup->task_offsets[p.t0]; p.s1 = sup->task_offsets[p.t1];
             p.q0 = qry->task_offsets[p.t0]; p.q1 = qry->task_offsets[p.t1];
-            p.ls0 = ls[p.t0]; p.ls1 = ls[p.t1]; p.lq0 = lq[p.t0]; p.lq1 = lq[p.t1];
+            p.ps0 = B.poff_s[p.t0]; p.ps1 = B.poff_s[p.t1]; p.pq0 = B.poff_q[p.t0]; p.pq1 = B.poff_q[p.t1];
+            p.ls0 = B.ls[p.t0]; p.ls1 = B.ls[p.t1]; p.lq0 = B.lq[p.t0]; p.lq1 = B.lq[p.t1];
             plans.push_back(p);
             Arena ar;
             ar.cap = avail;
             WaveBufs w;
-            WaveDims d;
-            d.Tw = p.t1 - p.t0; d.Ss = p.s1 - p.s0; d.Sq = p.q1 - p.q0; d.nnz_s = p.ls1 - p.ls0; d.nnz_q = p.lq1 - p.lq0;
-            d.mt_s = count_mtiles(sup->task_offsets, p.t0, p.t1);
-            d.mt_q = count_mtiles(qry->task_offsets, p.t0, p.t1);
-            alloc_wave(c, ar, w, d, K, order);
+            alloc_wave(c, ar, w, wave_dims(B, p, bm), K, order);
             if (ar.overflow) { fits = false; break; }
             if (T == 0) break;
         }
@@ -688,11 +968,64 @@ static int plan_waves(gm_ctx* c, int T, const gm_set* sup, const gm_set* qry, co
     }
 }
 
+// batch-level set-up shared by gm_meta_step and gm_index_prep
+static int begin_batch(gm_ctx* c, Batch& B, Arena& ar, int64_t capacity, bool need_gx) {
+    const int T = B.T, pad = c->row_pad;
+    B.poff_s.assign(T + 1, 0);
+    B.poff_q.assign(T + 1, 0);
+    for (int t = 0; t < T; ++t) {
+        B.poff_s[t + 1] = B.poff_s[t] + round_up64(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t], pad);
+        B.poff_q[t + 1] = B.poff_q[t] + round_up64(B.qry->task_offsets[t + 1] - B.qry->task_offsets[t], pad);
+    }
+    if ((B.poff_s[T] + B.poff_q[T]) * (int64_t)std::max(c->F, 1) >= ((int64_t)1 << 32))
+        return fail(c, GM_ERR_ARG, "more than 2^32 (row, field) pairs in one call");
+    alloc_batch(c, ar, B.b, T, B.sup->n_samples, B.qry->n_samples, B.poff_s[T], B.poff_q[T], B.sup->nnz + B.qry->nnz,
+                capacity, need_gx);
+    if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "workspace too small for the batch-level buffers (%zu needed)", ar.off);
+    hipStream_t st = c->stream;
+    HIPCHK(c, hipMemcpyAsync(B.b.toff_s, B.sup->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    HIPCHK(c, hipMemcpyAsync(B.b.toff_q, B.qry->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    std::vector<int32_t> ps(B.poff_s.begin(), B.poff_s.end()), pq(B.poff_q.begin(), B.poff_q.end());
+    int rc;
+    if ((rc = upload_i32(c, B.b.prow_off_s, ps)) || (rc = upload_i32(c, B.b.prow_off_q, pq))) return rc;
+    if (T > 0) {
+        hipLaunchKernelGGL(fill_prow_kernel, dim3(T), dim3(256), 0, st, B.b.toff_s, B.b.prow_off_s, B.b.prow_s);
+        hipLaunchKernelGGL(fill_prow_kernel, dim3(T), dim3(256), 0, st, B.b.toff_q, B.b.prow_off_q, B.b.prow_q);
+    }
+    HIPCHK(c, hipStreamSynchronize(st));  // the host vectors above go out of scope
+    return GM_OK;
+}
+
+static int setup_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, int bm, WaveBufs& w, const WaveDims& d, Grp& gs,
+                      Grp& gq) {
+    hipStream_t st = c->stream;
+    std::vector<int32_t> ro_s, tg_s, tm_s, ro_q, tg_q, tm_q, re_s, re_q;
+    build_tiles(B.poff_s, wp.t0, wp.t1, bm, ro_s, tg_s, tm_s);
+    build_tiles(B.poff_q, wp.t0, wp.t1, bm, ro_q, tg_q, tm_q);
+    for (int t = wp.t0; t <= wp.t1; ++t) {
+        re_s.push_back((int32_t)(B.sup->task_offsets[t] - wp.s0));
+        re_q.push_back((int32_t)(B.qry->task_offsets[t] - wp.q0));
+    }
+    int rc;
+    if ((rc = upload_i32(c, w.row_off_s, ro_s)) || (rc = upload_i32(c, w.row_off_q, ro_q)) ||
+        (rc = upload_i32(c, w.real_off_s, re_s)) || (rc = upload_i32(c, w.real_off_q, re_q)) ||
+        (rc = upload_i32(c, w.tile_g_s, tg_s)) || (rc = upload_i32(c, w.tile_m_s, tm_s)) ||
+        (rc = upload_i32(c, w.tile_g_q, tg_q)) || (rc = upload_i32(c, w.tile_m_q, tm_q)))
+        return rc;
+    launch_fill_sample_task(st, w.real_off_s, d.Tw, w.sample_task_s);
+    launch_fill_sample_task(st, w.real_off_q, d.Tw, w.sample_task_q);
+    launch_fill_sample_task(st, w.row_off_s, d.Tw, w.row_task_s);
+    launch_fill_sample_task(st, w.row_off_q, d.Tw, w.row_task_q);
+    HIPCHK(c, hipStreamSynchronize(st));  // host vectors go out of scope
+    gs = Grp{w.row_off_s, w.real_off_s, w.row_task_s, w.tile_g_s, w.tile_m_s, d.mt_s, d.Tw, bm, d.Ps};
+    gq = Grp{w.row_off_q, w.real_off_q, w.row_task_q, w.tile_g_q, w.tile_m_q, d.mt_q, d.Tw, bm, d.Pq};
+    return GM_OK;
+}
+
 extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set* qry, const gm_params* params,
                             float alpha, int32_t K, int32_t order, float* loss, gm_grads* out) {
     if (!c) return GM_ERR_ARG;
     if (T < 0 || K < 0 || (order != 1 && order != 2)) return fail(c, GM_ERR_ARG, "bad n_tasks / inner_steps / order");
-    if (c->mlp_dtype != 0) return fail(c, GM_ERR_ARG, "mlp_dtype 1 is not available in this build");
     int rc = check_set(c, sup, T, "support");
     if (rc != GM_OK) return rc;
     rc = check_set(c, qry, T, "query");
@@ -706,29 +1039,35 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     HIPCHK(c, hipSetDevice(c->device));
     hipStream_t st = c->stream;
     const int F = c->F, D = c->D, L = c->L, FD = c->FD, ld0 = c->ld[0];
+    const bool bf = c->mlp_dtype != 0;
     const int64_t nt = c->n_theta;
-    const int64_t Ss = sup->n_samples, Sq = qry->n_samples, nnz = sup->nnz + qry->nnz;
+    const int64_t nnz = sup->nnz + qry->nnz;
     const int64_t capacity = out->emb_rows_capacity;
 
     Arena ar;
     ar.base = c->ws; ar.cap = c->ws_bytes; ar.off = c->persistent;
-    BatchBufs b;
-    alloc_batch(c, ar, b, T, Ss, Sq, nnz, capacity, true);
-    if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "workspace too small for the batch-level buffers (%zu needed)", ar.off);
-    HIPCHK(c, hipMemcpyAsync(b.toff_s, sup->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    HIPCHK(c, hipMemcpyAsync(b.toff_q, qry->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    Batch B;
+    B.T = T; B.sup = sup; B.qry = qry;
+    rc = begin_batch(c, B, ar, capacity, true);
+    if (rc != GM_OK) return rc;
+    BatchBufs& b = B.b;
+    const int64_t Ps_tot = B.poff_s[T];
+    const int bm = pick_bm(c, B);
     std::vector<WavePlan> plans;
-    rc = plan_waves(c, T, sup, qry, b, c->ws_bytes - ar.off, K, order, plans);
+    rc = plan_waves(c, B, c->ws_bytes - ar.off, K, order, bm, plans);
     if (rc != GM_OK) return rc;
     const size_t wave_mark = ar.off;
 
-    // meta theta in the padded internal layout; accumulators
+    // meta theta in the padded internal layout (and its bf16 operand copies); accumulators
     for (int l = 1; l <= L; ++l) {
-        launch_pack_weights(st, params->W[l - 1], c->dims[l - 1], c->dims[l], c->ld[l - 1], c->ld[l], b.theta0 + c->offW[l]);
-        launch_pack_weights(st, params->b[l - 1], 1, c->dims[l], 1, (int)(l == L ? 32 : c->ld[l]), b.theta0 + c->offb[l]);
+        launch_pack_weights(st, params->W[l - 1], c->dims[l - 1], c->dims[l], c->ld[l - 1], c->ld[l], b.theta0.f + c->offW[l]);
+        launch_pack_weights(st, params->b[l - 1], 1, c->dims[l], 1, (int)(l == L ? 32 : c->ld[l]), b.theta0.f + c->offb[l]);
+        if (bf && l < L)
+            launch_convert_weights(st, b.theta0.f + c->offW[l], 0, 1, c->ld[l - 1], c->ld[l], b.theta0.b + c->offWb[l],
+                                   b.theta0.b + c->offWTb[l], 0);
     }
     launch_fill_f32(st, b.g_theta, nt, 0.f);
-    if (b.GX) launch_fill_f32(st, b.GX, (Ss + Sq) * (int64_t)FD, 0.f);
+    if (FD > 0) launch_fill_f32(st, b.GX, (Ps_tot + B.poff_q[T]) * (int64_t)FD, 0.f);
     float* task_loss = out->task_loss ? out->task_loss : b.task_loss;
 
     for (const WavePlan& wp : plans) {
@@ -736,100 +1075,151 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         const int Tw = wp.t1 - wp.t0;
         if (Tw == 0) continue;
         WaveBufs w;
-        WaveDims d;
-        d.Tw = Tw; d.Ss = wp.s1 - wp.s0; d.Sq = wp.q1 - wp.q0; d.nnz_s = wp.ls1 - wp.ls0; d.nnz_q = wp.lq1 - wp.lq0;
-        std::vector<int32_t> ro_s, tg_s, tm_s, ro_q, tg_q, tm_q;
-        build_tiles(sup->task_offsets, wp.t0, wp.t1, ro_s, tg_s, tm_s);
-        build_tiles(qry->task_offsets, wp.t0, wp.t1, ro_q, tg_q, tm_q);
-        d.mt_s = (int)tg_s.size(); d.mt_q = (int)tg_q.size();
+        const WaveDims d = wave_dims(B, wp, bm);
         alloc_wave(c, ar, w, d, K, order);
         if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "internal: wave does not fit");
-        if ((rc = upload_i32(c, w.row_off_s, ro_s)) || (rc = upload_i32(c, w.row_off_q, ro_q)) ||
-            (rc = upload_i32(c, w.tile_g_s, tg_s)) || (rc = upload_i32(c, w.tile_m_s, tm_s)) ||
-            (rc = upload_i32(c, w.tile_g_q, tg_q)) || (rc = upload_i32(c, w.tile_m_q, tm_q)))
-            return rc;
-        launch_fill_sample_task(st, w.row_off_s, Tw, w.sample_task_s);
-        launch_fill_sample_task(st, w.row_off_q, Tw, w.sample_task_q);
-        Grp gs{w.row_off_s, w.tile_g_s, w.tile_m_s, d.mt_s, Tw}, gq{w.row_off_q, w.tile_g_q, w.tile_m_q, d.mt_q, Tw};
+        Grp gs, gq;
+        if ((rc = setup_wave(c, B, wp, bm, w, d, gs, gq))) return rc;
 
         // a0: row dictionaries and the overlap join
-        rc = run_index_wave(c, sup, qry, b, wp, w);
+        rc = run_index_wave(c, B, wp, w);
         if (rc != GM_OK) return rc;
         const int n_tf = Tw * F;
+        const int32_t* rows_s = b.prow_s + wp.s0;
+        const int32_t* rows_q = b.prow_q + wp.q0;
+        const int32_t rb_s = (int32_t)wp.ps0, rb_q = (int32_t)wp.pq0;
+        const bool second = order == 2 && K > 0;
 
-        // a1: one prefetch pass for both sets
-        launch_gather_pool(st, F, D, c->n_dense, c->d_field_base, sup->bag_offsets, sup->indices, sup->dense, params->emb,
-                           wp.s0, d.Ss, w.Xs0, ld0, nullptr);
-        launch_gather_pool(st, F, D, c->n_dense, c->d_field_base, qry->bag_offsets, qry->indices, qry->dense, params->emb,
-                           wp.q0, d.Sq, w.Xq0, ld0, nullptr);
+        // a1: one prefetch pass for both sets (pad rows stay zero)
+        if (c->row_pad > 1) {
+            launch_fill_f32(st, w.Xs0, d.Ps * ld0, 0.f);
+            launch_fill_f32(st, w.Xq0, d.Pq * ld0, 0.f);
+        }
+        Act X0s;  // step-0 support input
+        X0s.ld = ld0;
+        if (bf) X0s = K > 0 ? w.steps[0].X : Act();
+        else X0s.f = w.Xs0;
+        {
+            const double lookups = (double)(d.nnz_s + d.nnz_q), bags = (double)(d.Ss + d.Sq) * F;
+            Prof p(c, "gather_pool", lookups * (4.0 * D + 4) + bags * (4.0 * D + 8 + (bf ? 2.0 * D : 0)), 0);
+            if (bf && X0s.b) zero_bf16(st, X0s.b, d.Ps * ld0);
+            if (bf) zero_bf16(st, w.Xq.b, d.Pq * ld0);
+            launch_gather_pool(st, F, D, c->n_dense, c->d_field_base, sup->bag_offsets, sup->indices, sup->dense,
+                               params->emb, wp.s0, d.Ss, rows_s, rb_s, w.Xs0, ld0, bf ? X0s.b : nullptr);
+            launch_gather_pool(st, F, D, c->n_dense, c->d_field_base, qry->bag_offsets, qry->indices, qry->dense,
+                               params->emb, wp.q0, d.Sq, rows_q, rb_q, w.Xq0, ld0, (bf && K == 0) ? w.Xq.b : nullptr);
+        }
+        if (bf && X0s.b) transpose_act(c, X0s, d.Ps);
         if (K > 0 && F > 0) launch_fill_f32(st, w.Delta, (d.nnz_s + 1) * D, 0.f);
+        if (second && c->row_pad > 1) {
+            if (w.TX.b) zero_bf16(st, w.TX.b, d.Ps * ld0);
+            if (w.TX.f) launch_fill_f32(st, w.TX.f, d.Ps * ld0, 0.f);
+        }
 
         // inner loop on the support set
         const float* labels_s = sup->labels + wp.s0;
         const float* labels_q = qry->labels + wp.q0;
-        const bool second = order == 2 && K > 0;
-        const float* theta = b.theta0;
-        int64_t ts = 0;
+        Theta th = b.theta0;        // GEMM operands of the current step
+        const float* thf = b.theta0.f;  // fp32 view (biases, last layer)
+        int64_t thf_stride = 0;
         for (int k = 0; k < K; ++k) {
             StepState& s = w.steps[second ? k : 0];
-            if (k > 0 && F > 0) {
+            if (k == 0) {
+                s.X = X0s;
+            } else if (F > 0) {
                 // support input of step k: meta rows plus the task's accumulated row deltas
-                float* Xk = second ? s.X : w.Xs_scratch;
+                Act Xk = second ? s.X : w.Xs_scratch;
+                Prof p(c, "pool_slots", (double)d.nnz_s * (4.0 * D + 4) + (double)d.Ss * F * 8.0 * D, 0);
+                if (bf && c->row_pad > 1) zero_bf16(st, Xk.b, d.Ps * ld0);
                 launch_pool_slots(st, F, D, sup->bag_offsets, wp.s0, wp.ls0, d.Ss, w.sample_task_s, w.sup_slot, w.base_s,
-                                  w.Delta, w.Xs0, Xk, ld0, nullptr);
+                                  w.Delta, rows_s, rb_s, d.Ps, w.Xs0, bf ? nullptr : Xk.f, ld0, bf ? Xk.b : nullptr);
                 s.X = Xk;
             } else {
-                s.X = w.Xs0;
+                s.X = X0s;
             }
-            s.theta = const_cast<float*>(theta);
-            s.theta_stride = ts;
-            Pass p{s.X, d.Ss, &s.A, &s.Dl, s.dL, s.zL};
-            forward_backward(c, gs, w.sample_task_s, labels_s, p, theta, ts, nullptr, F > 0 ? w.dX : nullptr);
+            if (k > 0 && F > 0) transpose_act(c, s.X, d.Ps);
+            s.th = th;
+            s.wL = thf + c->offW[L];
+            s.wL_stride = thf_stride;
+            Pass p{&s.X, &s.A, &s.Dl, s.dL, s.zL};
+            forward_backward(c, gs, labels_s, p, th, thf, thf_stride, nullptr, F > 0 ? w.dX : nullptr);
             // local back-propagation: theta' = theta - alpha dtheta (per task), rows' = rows - alpha drows
-            float* theta_next = w.thetas[second ? k : 0];
-            theta_grad(c, gs, p, theta_next, theta, ts, 1.f, -alpha);
-            theta = theta_next;
-            ts = nt;
-            if (F > 0)
+            Theta& next = w.thetas[second ? k : 0];
+            float* wl_copy = (bf && second && k + 1 < K) ? w.steps[k + 1].wL_copy : nullptr;
+            theta_grad(c, gs, p, next, thf, thf_stride, 1.f, -alpha, wl_copy);
+            th = next;
+            thf = next.f;
+            thf_stride = nt;
+            if (F > 0) {
+                Prof pp(c, "slot_segsum", (double)d.nnz_s * (4.0 * D + 4) + (double)d.nnz_s * 4.0 * D, 0);
                 launch_slot_segsum(st, F, D, n_tf, w.base_s, w.n_slots, w.slot_start, w.slot_start + 1, 1,
                                    w.sup_sorted_sample, w.dX, FD, w.Delta, 1.f, -alpha);
+            }
         }
+        // bf16 second order with K > 1: steps k >= 1 read their last-layer weights from the copies taken above
+        if (bf && second)
+            for (int k = 1; k < K; ++k) {
+                w.steps[k].wL = w.steps[k].wL_copy;
+                w.steps[k].wL_stride = c->ld[L - 1];
+            }
 
         // overlap update + outer forward/backward on the query set
-        if (K > 0 && F > 0)
+        Act Xq = w.Xq;
+        if (!bf && !(K > 0 && F > 0)) Xq.f = w.Xq0;
+        if (K > 0 && F > 0) {
+            Prof p(c, "pool_slots", (double)d.nnz_q * (4.0 * D + 4) + (double)d.Sq * F * 8.0 * D, 0);
+            if (bf && c->row_pad > 1) zero_bf16(st, Xq.b, d.Pq * ld0);
             launch_pool_slots(st, F, D, qry->bag_offsets, wp.q0, wp.lq0, d.Sq, w.sample_task_q, w.qry_slot, w.base_s,
-                              w.Delta, w.Xq0, w.Xq, ld0, nullptr);
-        float* gxq = b.GX + (Ss + wp.q0) * (int64_t)FD;
-        float* gxs = b.GX + wp.s0 * (int64_t)FD;
-        Pass pq{K > 0 && F > 0 ? w.Xq : w.Xq0, d.Sq, &w.Aq, &w.Dq, w.dLq, w.zq};
-        forward_backward(c, gq, w.sample_task_q, labels_q, pq, theta, ts, w.loss_q, F > 0 ? gxq : nullptr);
-        launch_task_colsum(st, Tw, w.row_off_q, 1, w.loss_q, nullptr, nullptr, nullptr, 1, task_loss + wp.t0, 1, nullptr,
-                           0, 0.f, 1.f);
-        theta_grad(c, gq, pq, w.v_theta, nullptr, 0, 0.f, 1.f);
+                              w.Delta, rows_q, rb_q, d.Pq, w.Xq0, bf ? nullptr : Xq.f, ld0, bf ? Xq.b : nullptr);
+        } else if (bf && K > 0) {  // no sparse fields: the query input is the prefetched one
+            Prof p(c, "pool_slots", 0, 0);
+            launch_pool_slots(st, 0, D, qry->bag_offsets, wp.q0, wp.lq0, d.Sq, w.sample_task_q, w.qry_slot, w.base_s,
+                              nullptr, rows_q, rb_q, d.Pq, w.Xq0, nullptr, ld0, Xq.b);
+        }
+        transpose_act(c, Xq, d.Pq);
+        float* gxq = b.GX + (Ps_tot + wp.pq0) * (int64_t)FD;
+        float* gxs = b.GX + wp.ps0 * (int64_t)FD;
+        Pass pq{&Xq, &w.Aq, &w.Dq, w.dLq, w.zq};
+        forward_backward(c, gq, labels_q, pq, th, thf, thf_stride, w.loss_q, F > 0 ? gxq : nullptr);
+        colsum_f32(c, gq, 1, w.loss_q, 1, task_loss + wp.t0, 1, nullptr, 0, 0.f, 1.f);
+        theta_grad(c, gq, pq, w.v, nullptr, 0, 0.f, 1.f, nullptr);
 
         // second-order chain back through the inner steps
         if (second) {
-            if (F > 0)
+            if (F > 0) {
+                Prof p(c, "slot_segsum", (double)d.nnz_q * (4.0 * D + 4) + (double)d.nnz_s * 4.0 * D, 0);
                 launch_slot_segsum(st, F, D, n_tf, w.base_s, w.n_slots, w.qseg_lo, w.qseg_hi, 0, w.qry_sorted_sample, gxq,
                                    FD, w.vXi, 0.f, 1.f);
+            }
             for (int k = K - 1; k >= 0; --k) {
                 const StepState& s = w.steps[k];
-                if (F > 0)
-                    launch_pool_slots(st, F, D, sup->bag_offsets, wp.s0, wp.ls0, d.Ss, w.sample_task_s, w.sup_slot,
-                                      w.base_s, w.vXi, nullptr, w.TX, ld0, nullptr);
-                else
-                    launch_fill_f32(st, w.TX, d.Ss * ld0, 0.f);
-                hvp_step(c, gs, w.sample_task_s, s, d.Ss, w, alpha);
                 if (F > 0) {
-                    launch_axpy(st, d.Ss * (int64_t)FD, -alpha, w.dX, gxs);
-                    if (k > 0)
+                    Prof p(c, "pool_slots", (double)d.nnz_s * (4.0 * D + 4) + (double)d.Ss * F * 4.0 * D, 0);
+                    launch_pool_slots(st, F, D, sup->bag_offsets, wp.s0, wp.ls0, d.Ss, w.sample_task_s, w.sup_slot,
+                                      w.base_s, w.vXi, rows_s, rb_s, d.Ps, nullptr, w.TX.f, ld0, w.TX.b);
+                } else if (w.TX.f) {
+                    launch_fill_f32(st, w.TX.f, d.Ps * ld0, 0.f);
+                }
+                transpose_act(c, w.TX, d.Ps);
+                hvp_step(c, gs, s, w, alpha, k > 0);
+                if (F > 0) {
+                    {
+                        Prof p(c, "axpy_gx", 12.0 * d.Ps * FD, 0);
+                        launch_axpy(st, d.Ps * (int64_t)FD, -alpha, w.dX, gxs);
+                    }
+                    if (k > 0) {
+                        Prof p(c, "slot_segsum", (double)d.nnz_s * (4.0 * D + 4) + (double)d.nnz_s * 8.0 * D, 0);
                         launch_slot_segsum(st, F, D, n_tf, w.base_s, w.n_slots, w.slot_start, w.slot_start + 1, 1,
                                            w.sup_sorted_sample, w.dX, FD, w.vXi, 1.f, -alpha);
+                    }
                 }
             }
         }
         // cross-task reduction of the dense part (tasks of the wave in order, waves in order)
-        launch_reduce_tasks(st, w.v_theta, nt, Tw, nt, b.g_theta, 1);
+        {
+            Prof p(c, "reduce_tasks", 4.0 * Tw * nt, 0);
+            launch_reduce_tasks(st, w.v.f, nt, Tw, nt, b.g_theta, 1);
+        }
     }
 
     // outputs: dense meta-gradient, loss, coalesced sparse meta-gradient
@@ -839,14 +1229,17 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     }
     launch_sum_to_scalar(st, task_loss, T, loss, 0);
     launch_fill_u32(st, c->d_status, ST_WORDS, 0);
-    global_order(c, sup, qry, b, out->emb_rows, nullptr, capacity, out->n_emb_rows);
-    if (F > 0)
+    global_order(c, B, out->emb_rows, nullptr, capacity, out->n_emb_rows);
+    if (F > 0) {
+        Prof p(c, "seg_reduce", (double)nnz * (4.0 * D + 4), 0);
         launch_seg_reduce(st, D, b.seg_start, out->n_emb_rows, capacity, std::min(nnz, capacity), b.vals, b.GX,
                           out->emb_grad);
+    }
     u32 hs[ST_WORDS];
     rc = read_status(c, hs);
     if (rc != GM_OK) return rc;
     HIPCHK(c, hipGetLastError());
+    prof_drain(c);
     if (hs[ST_CAPACITY])
         return fail(c, GM_ERR_CAPACITY, "emb_rows_capacity %lld is smaller than the %u rows touched", (long long)capacity,
                     hs[ST_NROWS]);
@@ -870,6 +1263,10 @@ __global__ void strip_pad_kernel(const float* src, int64_t n, int ld, int d, flo
     if (i >= n * d) return;
     const int64_t s = i / d;
     dst[i] = src[s * ld + (i - s * d)];
+}
+__global__ void iota_i32_kernel(int32_t* p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = (int32_t)i;
 }
 
 extern "C" int gm_gather_pool(gm_ctx* c, int32_t T, const gm_set* set, const float* emb, float* x) {
@@ -899,19 +1296,24 @@ extern "C" int gm_gather_pool(gm_ctx* c, int32_t T, const gm_set* set, const flo
     const size_t mark = ar.off;
     const int ld0 = c->ld[0], d0 = c->dims[0];
     const size_t avail = c->ws_bytes - mark;
-    int64_t chunk = (int64_t)(avail / ((size_t)ld0 * sizeof(float))) - 8;
+    int64_t chunk = (int64_t)(avail / ((size_t)(ld0 + 1) * sizeof(float))) - 128;
     if (chunk < 1) return fail(c, GM_ERR_WORKSPACE, "workspace too small");
+    chunk = std::min<int64_t>(chunk, (int64_t)1 << 30);
     for (int64_t s0 = 0; s0 < set->n_samples; s0 += chunk) {
         const int64_t n = std::min(chunk, set->n_samples - s0);
         ar.off = mark;
         float* xp = ar.get<float>(n * ld0);
+        int32_t* ident = ar.get<int32_t>(n);
+        hipLaunchKernelGGL(iota_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, ident, n);
+        Prof p(c, "gather_pool", 0, 0);
         launch_gather_pool(st, c->F, c->D, c->n_dense, c->d_field_base, set->bag_offsets, set->indices, set->dense, emb, s0,
-                           n, xp, ld0, nullptr);
+                           n, ident, 0, xp, ld0, nullptr);
         hipLaunchKernelGGL(strip_pad_kernel, dim3((unsigned)((n * d0 + 255) / 256)), dim3(256), 0, st, xp, n, ld0, d0,
                            x + s0 * d0);
     }
     HIPCHK(c, hipStreamSynchronize(st));
     HIPCHK(c, hipGetLastError());
+    prof_drain(c);
     return GM_OK;
 }
 
@@ -942,13 +1344,12 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
     const int F = c->F;
     Arena ar;
     ar.base = c->ws; ar.cap = c->ws_bytes; ar.off = c->persistent;
-    BatchBufs b;
-    alloc_batch(c, ar, b, T, 0, 0, sup->nnz + qry->nnz, capacity, false);
-    if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "workspace too small");
-    HIPCHK(c, hipMemcpyAsync(b.toff_s, sup->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    HIPCHK(c, hipMemcpyAsync(b.toff_q, qry->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    Batch B;
+    B.T = T; B.sup = sup; B.qry = qry;
+    rc = begin_batch(c, B, ar, capacity, false);
+    if (rc != GM_OK) return rc;
     std::vector<WavePlan> plans;
-    rc = plan_waves(c, T, sup, qry, b, c->ws_bytes - ar.off, 1, 2, plans);
+    rc = plan_waves(c, B, c->ws_bytes - ar.off, 1, 2, 64, plans);
     if (rc != GM_OK) return rc;
     const size_t mark = ar.off;
     int64_t packed0 = 0;
@@ -957,12 +1358,9 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
         const int Tw = wp.t1 - wp.t0;
         if (Tw == 0 || F == 0) continue;
         WaveBufs w;
-        WaveDims d;
-        d.Tw = Tw; d.Ss = wp.s1 - wp.s0; d.Sq = wp.q1 - wp.q0; d.nnz_s = wp.ls1 - wp.ls0; d.nnz_q = wp.lq1 - wp.lq0;
-        d.mt_s = count_mtiles(sup->task_offsets, wp.t0, wp.t1);
-        d.mt_q = count_mtiles(qry->task_offsets, wp.t0, wp.t1);
+        const WaveDims d = wave_dims(B, wp, 64);
         alloc_wave(c, ar, w, d, 1, 2);
-        rc = run_index_wave(c, sup, qry, b, wp, w);
+        rc = run_index_wave(c, B, wp, w);
         if (rc != GM_OK) return rc;
         const int64_t TF = (int64_t)Tw * F;
         hipLaunchKernelGGL(widen_u32_kernel, dim3((unsigned)((TF + 255) / 256)), dim3(256), 0, st, w.n_slots, TF,
@@ -979,11 +1377,12 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
         packed0 += h_total;
     }
     launch_fill_u32(st, c->d_status, ST_WORDS, 0);
-    global_order(c, sup, qry, b, emb_rows, seg_counts, capacity, n_emb_rows);
+    global_order(c, B, emb_rows, seg_counts, capacity, n_emb_rows);
     u32 hs[ST_WORDS];
     rc = read_status(c, hs);
     if (rc != GM_OK) return rc;
     HIPCHK(c, hipGetLastError());
+    prof_drain(c);
     if (hs[ST_CAPACITY])
         return fail(c, GM_ERR_CAPACITY, "emb_rows_capacity %lld is smaller than the %u rows touched", (long long)capacity,
                     hs[ST_NROWS]);

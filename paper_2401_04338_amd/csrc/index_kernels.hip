@@ -238,7 +238,7 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap) {
             const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
             const int64_t p = a.sup.bag_offsets[(s_lo + s) * a.F + f] + j;
             a.sup_slot[p - a.sup.lookup0] = slot;
-            a.sup_sorted_sample[B + i] = (int32_t)(s_lo + s - a.sup.sample0);
+            a.sup_sorted_sample[B + i] = a.sup_rows[s_lo + s] - a.sup_row_base;
         }
     }
     if (threadIdx.x == 0) {
@@ -276,7 +276,7 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap) {
         const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
         const int64_t p = a.qry.bag_offsets[(q_lo + s) * a.F + f] + j;
         a.qry_slot[p - a.qry.lookup0] = slot;
-        a.qry_sorted_sample[Bq + i] = (int32_t)(q_lo + s - a.qry.sample0);
+        a.qry_sorted_sample[Bq + i] = a.qry_rows[q_lo + s] - a.qry_row_base;
     }
     for (int u = threadIdx.x; u < n_unique; u += blockDim.x) {
         const u64 klo = (u64)uniq[u] << 32, khi = ((u64)uniq[u] + 1) << 32;
@@ -318,23 +318,25 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int cap) {
 // global (field,row) ordering of all lookups: keys, stable LSD radix sort, segments
 // ------------------------------------------------------------------------------------------------
 __global__ void build_keys_kernel(int F, const int64_t* field_base, const int64_t* bag_offsets,
-                                  const int32_t* indices, int64_t n_bags, u32 bag_id0, u32* keys, u32* vals) {
+                                  const int32_t* indices, int64_t n_bags, const int32_t* __restrict__ row_map,
+                                  u32 row0, u32* keys, u32* vals) {
     const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= n_bags) return;
-    const u32 fb = (u32)field_base[b % F];
+    const int f = (int)(b % F);
+    const u32 fb = (u32)field_base[f];
+    const u32 val = (row0 + (u32)row_map[b / F]) * (u32)F + (u32)f;  // (row of the sample, field) in the gradient buffer
     const int64_t p0 = bag_offsets[b], p1 = bag_offsets[b + 1];
     for (int64_t p = p0; p < p1; ++p) {
         keys[p] = fb + (u32)indices[p];
-        vals[p] = bag_id0 + (u32)b;
+        vals[p] = val;
     }
 }
 
 void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
-                       const int32_t* indices, int64_t n_bags, u32 bag_id0, u32* keys, u32* vals, u32* status) {
-    (void)status;
+                       const int32_t* indices, int64_t n_bags, const int32_t* row_map, u32 row0, u32* keys, u32* vals) {
     if (n_bags <= 0) return;
     hipLaunchKernelGGL(build_keys_kernel, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, st, F, field_base,
-                       bag_offsets, indices, n_bags, bag_id0, keys, vals);
+                       bag_offsets, indices, n_bags, row_map, row0, keys, vals);
 }
 
 #define RS_NT 256

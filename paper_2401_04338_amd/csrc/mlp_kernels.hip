@@ -114,11 +114,20 @@ void launch_gemm_f32(hipStream_t st, const GemmArgs& a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// element access in either activation type
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float ldf(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float ldf(const bf16_t* p, int64_t i) { return bf2f(p[i]); }
+__device__ __forceinline__ void stf(float* p, int64_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void stf(bf16_t* p, int64_t i, float v) { p[i] = f2bf(v); }
+
+// ------------------------------------------------------------------------------------------------
 // per-task column sums (bias gradients, last-layer weight gradient, per-task mean loss)
 // out[g,n] = c0*in[g,n] + c1 * sum_{s in g} ( X1[s,n]*w1[s] + X2[s,n]*w2[s] ), rows summed in order
 // ------------------------------------------------------------------------------------------------
-__global__ void task_colsum_kernel(const int32_t* __restrict__ row_offsets, int N, const float* __restrict__ X1,
-                                   const float* __restrict__ w1, const float* __restrict__ X2,
+template <typename T>
+__global__ void task_colsum_kernel(const int32_t* __restrict__ row_offsets, int N, const T* __restrict__ X1,
+                                   const float* __restrict__ w1, const T* __restrict__ X2,
                                    const float* __restrict__ w2, int64_t ldx, float* out, int64_t g_out,
                                    const float* in, int64_t g_in, float c0, float c1) {
     const int g = blockIdx.y;
@@ -127,29 +136,42 @@ __global__ void task_colsum_kernel(const int32_t* __restrict__ row_offsets, int 
     const int64_t r0 = row_offsets[g], r1 = row_offsets[g + 1];
     float acc = 0.f;
     for (int64_t s = r0; s < r1; ++s) {
-        float v = X1[s * ldx + n] * (w1 ? w1[s] : 1.f);
-        if (X2) v += X2[s * ldx + n] * (w2 ? w2[s] : 1.f);
+        float v = ldf(X1, s * ldx + n) * (w1 ? w1[s] : 1.f);
+        if (X2) v += ldf(X2, s * ldx + n) * (w2 ? w2[s] : 1.f);
         acc += v;
     }
     const float o = c1 * acc + (in ? c0 * in[(int64_t)g * g_in + n] : 0.f);
     out[(int64_t)g * g_out + n] = o;
 }
 
-void launch_task_colsum(hipStream_t st, int G, const int32_t* row_offsets, int N, const float* X1, const float* w1,
-                        const float* X2, const float* w2, int64_t ldx, float* out, int64_t g_out, const float* in,
-                        int64_t g_in, float c0, float c1) {
+template <typename T>
+static void task_colsum_t(hipStream_t st, int G, const int32_t* row_offsets, int N, const T* X1, const float* w1,
+                          const T* X2, const float* w2, int64_t ldx, float* out, int64_t g_out, const float* in,
+                          int64_t g_in, float c0, float c1) {
     if (G <= 0 || N <= 0) return;
     const int nt = N >= 256 ? 256 : 64;
     for (int g0 = 0; g0 < G; g0 += 32768) {
         const int gc = (G - g0) < 32768 ? (G - g0) : 32768;
-        hipLaunchKernelGGL(task_colsum_kernel, dim3((N + nt - 1) / nt, gc), dim3(nt), 0, st, row_offsets + g0, N, X1, w1,
-                           X2, w2, ldx, out + (int64_t)g0 * g_out, g_out, in ? in + (int64_t)g0 * g_in : nullptr, g_in,
-                           c0, c1);
+        hipLaunchKernelGGL(task_colsum_kernel<T>, dim3((N + nt - 1) / nt, gc), dim3(nt), 0, st, row_offsets + g0, N, X1,
+                           w1, X2, w2, ldx, out + (int64_t)g0 * g_out, g_out, in ? in + (int64_t)g0 * g_in : nullptr,
+                           g_in, c0, c1);
     }
+}
+void launch_task_colsum(hipStream_t st, int G, const int32_t* row_offsets, int N, const float* X1, const float* w1,
+                        const float* X2, const float* w2, int64_t ldx, float* out, int64_t g_out, const float* in,
+                        int64_t g_in, float c0, float c1) {
+    task_colsum_t<float>(st, G, row_offsets, N, X1, w1, X2, w2, ldx, out, g_out, in, g_in, c0, c1);
+}
+void launch_task_colsum_bf(hipStream_t st, int G, const int32_t* row_offsets, int N, const bf16_t* X1, const float* w1,
+                           const bf16_t* X2, const float* w2, int64_t ldx, float* out, int64_t g_out, const float* in,
+                           int64_t g_in, float c0, float c1) {
+    task_colsum_t<bf16_t>(st, G, row_offsets, N, X1, w1, X2, w2, ldx, out, g_out, in, g_in, c0, c1);
 }
 
 // ------------------------------------------------------------------------------------------------
-// last layer (d_L = 1) fused with the sigmoid / binary cross-entropy: one wavefront per sample
+// last layer (d_L = 1) fused with the sigmoid / binary cross-entropy: one wavefront per row.
+// Rows may be padded per task: row r of task g is sample real_offsets[g] + (r - row_offsets[g]) when that
+// is below real_offsets[g+1]; pad rows get delta = 0 and loss = 0.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -157,27 +179,38 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+template <typename T>
 __global__ void last_fwd_kernel(LastFwdArgs a) {
     const int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 64;
     const int lane = threadIdx.x & 63;
     if (s >= a.n) return;
-    const int g = a.sample_task[s];
+    const int g = a.row_task[s];
+    const int r_in = (int)(s - a.row_offsets[g]);
+    const int n_real = a.real_offsets[g + 1] - a.real_offsets[g];
+    if (r_in >= n_real) {  // pad row
+        if (lane == 0) {
+            a.delta_out[s] = 0.f;
+            if (a.z_out) a.z_out[s] = 0.f;
+            if (a.loss_out) a.loss_out[s] = 0.f;
+        }
+        return;
+    }
     const float* w = a.w + (int64_t)g * a.gW;
-    const float* x = a.a + s * a.ld;
+    const T* x = reinterpret_cast<const T*>(a.a) + s * a.ld;
     float acc = 0.f;
     if (!a.ta) {
-        for (int n = lane; n < a.N; n += 64) acc = fmaf(x[n], w[n], acc);
+        for (int n = lane; n < a.N; n += 64) acc = fmaf(ldf(x, n), w[n], acc);
     } else {
-        const float* tx = a.ta + s * a.ld;
+        const T* tx = reinterpret_cast<const T*>(a.ta) + s * a.ld;
         const float* tw = a.tw + (int64_t)g * a.gTW;
-        for (int n = lane; n < a.N; n += 64) acc += tx[n] * w[n] + x[n] * tw[n];
+        for (int n = lane; n < a.N; n += 64) acc += ldf(tx, n) * w[n] + ldf(x, n) * tw[n];
     }
     acc = wave_sum(acc);
     if (lane != 0) return;
-    const float inv_n = 1.f / (float)(a.row_offsets[g + 1] - a.row_offsets[g]);
+    const float inv_n = 1.f / (float)n_real;
     if (!a.ta) {
         const float z = acc + a.b[(int64_t)g * a.gW];
-        const float y = a.labels[s];
+        const float y = a.labels[a.real_offsets[g] + r_in];
         const float e = __expf(-fabsf(z));
         const float sig = z >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
         if (a.z_out) a.z_out[s] = z;
@@ -194,29 +227,41 @@ __global__ void last_fwd_kernel(LastFwdArgs a) {
 
 void launch_last_fwd(hipStream_t st, const LastFwdArgs& a) {
     if (a.n <= 0) return;
-    hipLaunchKernelGGL(last_fwd_kernel, dim3((unsigned)((a.n * 64 + 255) / 256)), dim3(256), 0, st, a);
+    const dim3 grid((unsigned)((a.n * 64 + 255) / 256));
+    if (a.bf16) hipLaunchKernelGGL(last_fwd_kernel<bf16_t>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(last_fwd_kernel<float>, grid, dim3(256), 0, st, a);
 }
 
-__global__ void last_bwd_kernel(int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* __restrict__ sample_task,
+template <typename T>
+__global__ void last_bwd_kernel(int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* __restrict__ row_task,
                                 const float* __restrict__ dl, const float* __restrict__ w, int64_t gW,
                                 const float* __restrict__ dl2, const float* __restrict__ w2, int64_t gW2,
-                                const float* __restrict__ act, float* d) {
+                                const T* __restrict__ act, T* d, float* d_f32) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n * N) return;
     const int64_t s = i / N;
     const int c = (int)(i - s * N);
-    const int g = sample_task[s];
+    const int g = row_task[s];
     float v = dl[s] * w[(int64_t)g * gW + c];
     if (dl2) v += dl2[s] * w2[(int64_t)g * gW2 + c];
-    d[s * ld_d + c] = (!act || act[s * ld_a + c] > 0.f) ? v : 0.f;
+    if (act && !(ldf(act, s * ld_a + c) > 0.f)) v = 0.f;
+    if (d) stf(d, s * ld_d + c, v);
+    if (d_f32) d_f32[s * ld_d + c] = v;
 }
 
-void launch_last_bwd(hipStream_t st, int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* sample_task, const float* dl,
-                     const float* w, int64_t gW, const float* dl2, const float* w2, int64_t gW2, const float* act,
-                     float* d) {
-    if (n <= 0) return;
-    hipLaunchKernelGGL(last_bwd_kernel, dim3((unsigned)((n * N + 255) / 256)), dim3(256), 0, st, n, N, ld_a, ld_d,
-                       sample_task, dl, w, gW, dl2, w2, gW2, act, d);
+// d[s,n] = (dl[s]*w_g[n] (+ dl2[s]*w2_g[n])) * (act[s,n] > 0); act null: no mask.  Output in the
+// activation type (d) and/or fp32 (d_f32).
+void launch_last_bwd(hipStream_t st, int bf16, int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* row_task,
+                     const float* dl, const float* w, int64_t gW, const float* dl2, const float* w2, int64_t gW2,
+                     const void* act, void* d, float* d_f32) {
+    if (n <= 0 || N <= 0) return;
+    const dim3 grid((unsigned)((n * N + 255) / 256));
+    if (bf16)
+        hipLaunchKernelGGL(last_bwd_kernel<bf16_t>, grid, dim3(256), 0, st, n, N, ld_a, ld_d, row_task, dl, w, gW, dl2,
+                           w2, gW2, (const bf16_t*)act, (bf16_t*)d, d_f32);
+    else
+        hipLaunchKernelGGL(last_bwd_kernel<float>, grid, dim3(256), 0, st, n, N, ld_a, ld_d, row_task, dl, w, gW, dl2, w2,
+                           gW2, (const float*)act, (float*)d, d_f32);
 }
 
 // ------------------------------------------------------------------------------------------------

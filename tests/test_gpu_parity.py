@@ -40,10 +40,19 @@ def _params_dev(params, dev):
     return Params(params.emb.to(dev), [w.to(dev) for w in params.W], [b.to(dev) for b in params.b])
 
 
-def _compare_step(cfg, ctx, sup, qry, params, K, order, tol, label):
+def _compare_step(cfg, ctx, sup, qry, params, K, order, tol, label, operand="fp64"):
+    """operand="bf16": the oracle rounds the hidden-layer GEMM operands where the kernels store bf16, so that
+    both sides decide every ReLU mask on the same values; the loss is also held against the float64 oracle."""
     dev = ctx.device
     out = ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, K, order)
-    ref = O.meta_step(oracle_model(cfg), params.numpy(), sup.numpy(), qry.numpy(), cfg.inner_lr, K, order)
+    ref = O.meta_step(oracle_model(cfg), params.numpy(), sup.numpy(), qry.numpy(), cfg.inner_lr, K, order,
+                      operand=operand)
+    if operand != "fp64":
+        ref64 = O.meta_step(oracle_model(cfg), params.numpy(), sup.numpy(), qry.numpy(), cfg.inner_lr, K, order)
+        e64 = abs(float(out["loss"].item()) - ref64["loss"]) / abs(ref64["loss"])
+        g64 = max(rel_err(out["dW"][0].cpu().numpy(), ref64["dW"][0]))
+        print(label, f"vs float64 oracle: loss {e64:.2e}, dW0 {g64:.2e} (mask flips included)", flush=True)
+        assert e64 <= tol, (label, "loss vs float64", e64)
     n = int(out["n_emb_rows"].item())
     assert n == len(ref["emb_rows"]), label
     assert np.array_equal(out["emb_rows"][:n].cpu().numpy(), ref["emb_rows"]), label
@@ -223,4 +232,37 @@ def test_scatter_add_is_the_outer_update(gm):
     want = params.emb.clone()
     want[out["emb_rows"][:n].cpu()] -= 0.5 * out["emb_grad"][:n].cpu()
     assert torch.equal(table.cpu(), want)
+    ctx.close()
+
+
+# ---------------------------------------------------------------- bf16 GEMM path (MFMA), fp32 everything else
+TOL_BF16 = 2e-2
+
+
+@pytest.mark.parametrize("K,order", [(0, 1), (1, 1), (1, 2), (2, 2), (3, 1), (3, 2)])
+def test_meta_step_bf16_small_shape(gm, K, order):
+    """configs[1]'s model shape with bf16 operands; 6 tasks of ragged size so that the row padding is exercised."""
+    cfg = SMALL.with_(n_tasks=6, n_support=50, n_query=37, mlp_dtype=1, rows_per_field=5000, inner_lr=0.05)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=2 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, K, order, TOL_BF16, f"bf16 small K={K} order={order}", operand="bf16")
+    ctx.close()
+
+
+def test_meta_step_bf16_tiny_config(gm):
+    cfg = TINY.with_(mlp_dtype=1)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
+    _compare_step(cfg, ctx, sup, qry, params, 1, 2, TOL_BF16, "bf16 tiny", operand="bf16")
+    ctx.close()
+
+
+def test_meta_step_bf16_medium_shape_subset(gm):
+    """configs[2]'s model (MLP 1677-512-256-1, D=64, bags up to 20, Zipf 1.1, 3 inner steps), 4 tasks, smaller tables."""
+    from synth import MEDIUM
+    cfg = MEDIUM.with_(n_tasks=4, rows_per_field=20000)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=3 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, 3, 2, TOL_BF16, "bf16 medium4 K=3 order=2", operand="bf16")
+    _compare_step(cfg, ctx, sup, qry, params, 3, 1, TOL_BF16, "bf16 medium4 K=3 order=1", operand="bf16")
     ctx.close()

@@ -11,17 +11,17 @@ from tests.helpers import small_cfg
 from tests.test_oracle_pins import _fd_check
 
 
-def _drop_cross_term(acts, z, y, W, deltas, vW, vb, vx):
+def _drop_cross_term(acts, z, y, W, deltas, vW, vb, vx, q=None):
     hW, hb, hx = _ORIG(acts, z, y, W, deltas, vW, vb, vx)
     return hW, hb, hx * 0.0 + (hx - deltas[0] @ vW[0].T)      # drop delta * vW^T at the input
 
 
-def _wrong_sign(acts, z, y, W, deltas, vW, vb, vx):
+def _wrong_sign(acts, z, y, W, deltas, vW, vb, vx, q=None):
     hW, hb, hx = _ORIG(acts, z, y, W, deltas, vW, vb, vx)
     return [-h for h in hW], hb, hx
 
 
-def _no_bias_tangent(acts, z, y, W, deltas, vW, vb, vx):
+def _no_bias_tangent(acts, z, y, W, deltas, vW, vb, vx, q=None):
     return _ORIG(acts, z, y, W, deltas, vW, [np.zeros_like(v) for v in vb], vx)
 
 

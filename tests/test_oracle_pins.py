@@ -412,3 +412,43 @@ def test_index_prep_against_sets():
     assert list(ip["seg_counts"]) == [rows_seen[r] for r in sorted(rows_seen)]
     out = O.meta_step(model, params, sup, qry, 0.1, 1, 2)
     assert np.array_equal(out["emb_rows"], ip["emb_rows"])
+
+
+# ---------------------------------------------------------------- bf16 operand rounding
+def test_round_bf16_matches_library_conversion():
+    import torch
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.normal(size=4000) * 10.0 ** rng.integers(-20, 20, size=4000),
+                        np.array([0.0, -0.0, 1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 3.3895314e38])]).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(O.round_bf16(x), want)
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert O.round_bf16(np.float32(1.0 + 2.0 ** -8)) == 1.0
+    assert O.round_bf16(np.float32(1.0 + 3 * 2.0 ** -8)) == 1.0 + 2.0 ** -6
+
+
+def test_bf16_operands_with_representable_inputs_change_nothing_in_a_linear_model():
+    """L = 1 has no rounded operand except x; with x exactly representable the two modes coincide."""
+    rng = np.random.default_rng(2)
+    d, n = 8, 12
+    model = O.Model(rows_per_field=[], emb_dim=4, n_dense=d, layer_dims=[d, 1])
+    params = dict(emb=np.zeros((0, 4)), W=[rng.normal(size=(d, 1))], b=[rng.normal(size=1)])
+
+    def mkset():
+        return dict(task_offsets=np.array([0, n]), bag_offsets=np.zeros(1, np.int64), indices=np.zeros(0, np.int32),
+                    dense=O.round_bf16(rng.normal(size=(n, d))), labels=(rng.random(n) < 0.4).astype(np.float64))
+    sup, qry = mkset(), mkset()
+    a = O.meta_step(model, params, sup, qry, 0.3, 2, 2, operand="fp64")
+    b = O.meta_step(model, params, sup, qry, 0.3, 2, 2, operand="bf16")
+    assert a["loss"] == b["loss"] and np.array_equal(a["dW"][0], b["dW"][0])
+
+
+def test_bf16_operands_stay_close_to_float64_where_no_mask_decides():
+    """Loss (no yes/no decision downstream of it that could amplify) moves by rounding noise only."""
+    cfg = small_cfg(inner_lr=0.1)
+    model, params, sup, qry = oracle_inputs(cfg, emb_std=0.3)
+    a = O.meta_step(model, params, sup, qry, 0.1, 2, 2, operand="fp64")
+    b = O.meta_step(model, params, sup, qry, 0.1, 2, 2, operand="bf16")
+    assert abs(a["loss"] - b["loss"]) / a["loss"] < 5e-3
+    assert abs(a["loss"] - b["loss"]) > 0.0
+    assert np.array_equal(a["emb_rows"], b["emb_rows"])
