@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of gm_meta_step on one MI355X: meta-train samples/sec (support + query).
+
+A step is one whole pass of the hot path (index preparation, prefetch + pooling, inner loop,
+overlap update, outer forward, meta-gradient with the second-order chain, cross-task reduction,
+coalesced sparse gradient) over one synthetic batch that is already resident in HBM.
+
+Prints ONE JSON line: metric/value/unit, ms_per_step, config.workload, plus
+  "roofline":     the dominant kernel family of the step against the chip's published peak
+                  (durations measured live with HIP events on the library's stream),
+  "cpu_baseline": the CPU oracle timed on a bounded task subset of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "fp32": (157.3, "TFLOP/s")}
+HBM_FAMILIES = {"gather_pool", "pool_slots", "slot_segsum", "seg_reduce", "global_sort", "tf_sort", "tf_count",
+                "transpose_act", "transpose_w", "reduce_tasks", "axpy_gx"}
+GEMM_FAMILIES = {"gemm_fwd", "gemm_bwd", "gemm_wgrad"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="c3_medium", help="c1_tiny | c2_small | c3_medium | c4_coldstart")
+    ap.add_argument("--order", type=int, default=None)
+    ap.add_argument("--workspace-gib", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--batches", type=int, default=2, help="distinct pre-generated batches cycled through")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures ONE GPU: this build has no multi-GPU path (every box has one GPU); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from synth import CONFIGS, make_batch, make_params
+    from paper_2401_04338_amd import GMeta
+
+    cfg = CONFIGS[args.config]
+    order = cfg.order if args.order is None else args.order
+    K = cfg.inner_steps
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    params = make_params(cfg, dev)
+    batches = [make_batch(cfg, it, dev) for it in range(max(1, args.batches))]
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    sup0, qry0 = batches[0]
+    S = sup0.n_samples + qry0.n_samples
+    nnz = sup0.nnz + qry0.nnz
+
+    probe = GMeta.from_config(cfg, workspace_bytes=1 << 20)
+    need = max(probe.workspace_bytes(cfg.n_tasks, s.n_samples, q.n_samples, s.nnz, q.nnz, K, order) for s, q in batches)
+    probe.close()
+    free_b, _total = torch.cuda.mem_get_info()
+    cap_rows = min(nnz, cfg.total_rows)
+    out_bytes = cap_rows * (cfg.emb_dim * 4 + 8)
+    ws = int(need * 1.02)
+    if args.workspace_gib is not None:
+        ws = int(args.workspace_gib * 2 ** 30)
+    ws = min(ws, int(free_b - out_bytes - (4 << 30)))
+    ctx = GMeta.from_config(cfg, workspace_bytes=ws)
+    out = ctx.alloc_outputs(cfg.n_tasks, cap_rows)
+
+    def step(i):
+        s, q = batches[i % len(batches)]
+        return ctx.meta_step(s, q, params, cfg.inner_lr, K, order, out=out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = S * args.steps / dt
+    loss = float(out["loss"].item())
+
+    # kernel families, timed live with HIP events on the library's stream (separate, untimed pass)
+    ctx.profile(True)
+    n_prof = 2
+    for i in range(n_prof):
+        step(i)
+    ctx.profile(False)
+    rep = ctx.profile_report()
+    fams = []
+    for name, r in rep.items():
+        if name in GEMM_FAMILIES:
+            bound, work = "mfma", r["flops"]
+            peak, unit = PEAK["mfma_bf16"] if cfg.mlp_dtype else PEAK["fp32"]
+            ach = work / (r["ms"] * 1e-3) / 1e12 if r["ms"] > 0 else 0.0
+        else:
+            bound, work = "hbm", r["bytes"]
+            peak, unit = PEAK["hbm"]
+            ach = work / (r["ms"] * 1e-3) / 1e9 if r["ms"] > 0 else 0.0
+        fams.append(dict(kernel=name, bound=bound, launches=r["launches"] // n_prof, ms_per_step=r["ms"] / n_prof,
+                         avg_launch_ms=r["ms"] / max(r["launches"], 1), achieved=ach, peak=peak, unit=unit,
+                         frac=ach / peak if work > 0 else None))
+    fams.sort(key=lambda f: -f["ms_per_step"])
+    # dominant family: all GEMM launches are one kernel (same code, three operand set-ups)
+    gemm_ms = sum(f["ms_per_step"] for f in fams if f["kernel"] in GEMM_FAMILIES)
+    gemm_flops = sum(rep[n]["flops"] for n in GEMM_FAMILIES if n in rep)
+    gemm_launches = sum(rep[n]["launches"] for n in GEMM_FAMILIES if n in rep)
+    top_hbm = next((f for f in fams if f["bound"] == "hbm" and f["frac"] is not None), None)
+    peak_m, unit_m = PEAK["mfma_bf16"] if cfg.mlp_dtype else PEAK["fp32"]
+    gemm_ach = gemm_flops / n_prof / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    roof_gemm = dict(kernel="gemm_bf16_kernel" if cfg.mlp_dtype else "gemm_f32_kernel",
+                     bound="mfma" if cfg.mlp_dtype else "alu", achieved=gemm_ach, peak=peak_m, unit=unit_m,
+                     frac=gemm_ach / peak_m, traffic=None, ms_per_step=gemm_ms,
+                     avg_launch_ms=gemm_ms * n_prof / max(gemm_launches, 1))
+    roof = roof_gemm
+    if top_hbm is not None and top_hbm["ms_per_step"] > gemm_ms:
+        roof = dict(kernel=top_hbm["kernel"], bound="hbm", achieved=top_hbm["achieved"], peak=top_hbm["peak"],
+                    unit=top_hbm["unit"], frac=top_hbm["frac"], traffic=None, ms_per_step=top_hbm["ms_per_step"],
+                    avg_launch_ms=top_hbm["avg_launch_ms"])
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, K, order, args.cpu_seconds, params.numpy())
+
+    line = {
+        "metric": "meta-train samples/sec (support+query) on 1 GPU", "value": value, "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.mlp_dtype else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "n_tasks": cfg.n_tasks, "samples_per_step": S, "lookups_per_step": nnz,
+                   "n_fields": cfg.n_fields, "rows_per_field": cfg.rows_per_field, "emb_dim": cfg.emb_dim,
+                   "mlp": list(cfg.layer_dims), "inner_steps": K, "order": order, "inner_lr": cfg.inner_lr,
+                   "workspace_gib": ws / 2 ** 30, "batches_cycled": len(batches), "loss": loss,
+                   "input_generation_s": gen_s},
+        "roofline": roof,
+        "roofline_gemm": roof_gemm,
+        "roofline_hbm": top_hbm,
+        "kernels": fams,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(cfg, K, order, budget_s, params):
+    """The CPU oracle, as it stands, on a task subset of the same workload (about budget_s of CPU work)."""
+    import numpy as np
+    from oracle import maml_dlrm as O
+    from synth import make_batch
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    model = O.Model(rows_per_field=[cfg.rows_per_field] * cfg.n_fields, emb_dim=cfg.emb_dim, n_dense=cfg.n_dense,
+                    layer_dims=list(cfg.layer_dims))
+    operand = "bf16" if cfg.mlp_dtype else "fp64"
+    done, spent, samples, n = 0, 0.0, 0, 1
+    t_all = time.perf_counter()
+    while done < cfg.n_tasks and spent < budget_s:
+        tasks = list(range(done, min(cfg.n_tasks, done + n)))
+        sup, qry = make_batch(cfg, 0, "cpu", tasks)
+        t0 = time.perf_counter()
+        O.meta_step(model, params, sup.numpy(), qry.numpy(), cfg.inner_lr, K, order, operand=operand)
+        dt = time.perf_counter() - t0
+        spent += dt
+        samples += sup.n_samples + qry.n_samples
+        done += len(tasks)
+        per_task = spent / done
+        n = max(1, min(cfg.n_tasks - done, int((budget_s - spent) / max(per_task, 1e-6) / 2)))
+    return {"value": samples / spent, "unit": "samples/s", "cores": cores, "kind": "oracle",
+            "sample": f"tasks 0..{done - 1} of {cfg.n_tasks} ({samples} samples, {spent:.1f} s of oracle time, "
+                      f"float64 numpy, operand rounding {operand})"}
+
+
+if __name__ == "__main__":
+    main()

@@ -193,31 +193,106 @@ void launch_slot_segsum(hipStream_t st, int F, int D, int n_tf, const u32* tf_ba
 
 // ------------------------------------------------------------------------------------------------
 // global segment reduction: emb_grad[seg] = sum over the segment's lookups (stable (field,row) order) of
-// gx[bag id], gx laid out [all samples (support then query), F, D]
+// gx[(row of the sample, field)], gx laid out [rows (support then query), F, D].
+//
+// Under Zipf skew a hot row's segment holds a large share of all lookups, so segments are not the unit
+// of work: the sorted lookup list is cut into fixed chunks of SEG_CH positions, one lane group walks one
+// chunk, a segment that lies inside one chunk is written directly, and a segment that crosses chunk
+// borders leaves one partial sum per chunk that a second pass adds in chunk order.  The cutting depends
+// only on positions, so the order of every sum is fixed.
 // ------------------------------------------------------------------------------------------------
-__global__ void seg_reduce_kernel(int D, int LG, const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
-                                  int64_t capacity, const u32* __restrict__ sorted_vals, const float* __restrict__ gx,
-                                  float* emb_grad) {
+#define SEG_CH 64
+
+__global__ void seg_reduce_chunks_kernel(int D, int LG, const u32* __restrict__ keys, const u32* __restrict__ scan,
+                                         const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
+                                         int64_t capacity, int64_t n, const u32* __restrict__ sorted_vals,
+                                         const float* __restrict__ gx, float* emb_grad, float* partial) {
     const int groups_per_block = blockDim.x / LG;
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
     if (g_in_block >= groups_per_block) return;
-    const int64_t n = min(*n_rows, capacity);
+    const int64_t n_valid = min(*n_rows, capacity);
+    const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
     const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
     const float4* gx4 = reinterpret_cast<const float4*>(gx);
-    for (int64_t seg = (int64_t)blockIdx.x * groups_per_block + g_in_block; seg < n; seg += n_groups) {
-        const u32 lo = seg_start[seg], hi = seg_start[seg + 1];
+    for (int64_t c = (int64_t)blockIdx.x * groups_per_block + g_in_block; c < n_chunks; c += n_groups) {
+        const int64_t cb = c * SEG_CH, ce = min(n, cb + SEG_CH);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (u32 i = lo; i < hi; ++i) acc = add4(acc, gx4[(int64_t)sorted_vals[i] * LG + l]);
+        int64_t run_begin = cb;
+        int64_t cur = -1;
+        auto flush = [&](int64_t seg, int64_t a, int64_t b) {
+            if (seg < 0 || seg >= n_valid) return;
+            const int64_t s0 = seg_start[seg], s1 = seg_start[seg + 1];
+            float* dst;
+            if (a == s0 && b == s1) dst = emb_grad + seg * D;                       // whole segment in this chunk
+            else if (s0 < a) dst = partial + (c * 2 + 0) * D;                       // began in an earlier chunk
+            else dst = partial + (c * 2 + 1) * D;                                   // continues in a later chunk
+            *reinterpret_cast<float4*>(dst + l * 4) = acc;
+        };
+        for (int64_t i0 = cb; i0 < ce; i0 += 4) {
+            u32 v[4];
+            int64_t sg[4];
+            float4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = i0 + u;
+                if (i < ce) {
+                    v[u] = sorted_vals[i];
+                    const bool head = (i == 0) || (keys[i] != keys[i - 1]);
+                    sg[u] = (int64_t)scan[i] + (head ? 1 : 0) - 1;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + u < ce) x[u] = gx4[(int64_t)v[u] * LG + l];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = i0 + u;
+                if (i >= ce) break;
+                if (sg[u] != cur) {
+                    flush(cur, run_begin, i);
+                    cur = sg[u];
+                    run_begin = i;
+                    acc = x[u];
+                } else {
+                    acc = add4(acc, x[u]);
+                }
+            }
+        }
+        flush(cur, run_begin, ce);
+    }
+}
+
+__global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
+                                       int64_t capacity, const float* __restrict__ partial, float* emb_grad) {
+    const int groups_per_block = blockDim.x / LG;
+    const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
+    if (g_in_block >= groups_per_block) return;
+    const int64_t n_valid = min(*n_rows, capacity);
+    const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
+    for (int64_t seg = (int64_t)blockIdx.x * groups_per_block + g_in_block; seg < n_valid; seg += n_groups) {
+        const int64_t s0 = seg_start[seg], s1 = seg_start[seg + 1];
+        const int64_t c0 = s0 / SEG_CH, c1 = (s1 - 1) / SEG_CH;
+        if (c0 == c1) continue;
+        // first chunk: the part that starts in it (slot 1); every later chunk: the part that began earlier (slot 0)
+        float4 acc = *reinterpret_cast<const float4*>(partial + (c0 * 2 + 1) * D + l * 4);
+        for (int64_t c = c0 + 1; c <= c1; ++c)
+            acc = add4(acc, *reinterpret_cast<const float4*>(partial + (c * 2 + 0) * D + l * 4));
         *reinterpret_cast<float4*>(emb_grad + seg * D + l * 4) = acc;
     }
 }
 
-void launch_seg_reduce(hipStream_t st, int D, const u32* seg_start, const int64_t* n_rows, int64_t capacity,
-                       int64_t max_rows, const u32* sorted_vals, const float* gx, float* emb_grad) {
-    if (max_rows <= 0) return;
+size_t seg_reduce_partial_floats(int64_t n, int D) { return (size_t)((n + SEG_CH - 1) / SEG_CH) * 2 * D + 16; }
+
+void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const u32* seg_start,
+                       const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
+                       float* emb_grad, float* partial) {
+    if (n <= 0 || capacity <= 0) return;
     const int LG = D / 4;
-    hipLaunchKernelGGL(seg_reduce_kernel, dim3(pool_grid(max_rows, 256 / LG)), dim3(256), 0, st, D, LG, seg_start,
-                       n_rows, capacity, sorted_vals, gx, emb_grad);
+    const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
+    hipLaunchKernelGGL(seg_reduce_chunks_kernel, dim3(pool_grid(n_chunks, 256 / LG)), dim3(256), 0, st, D, LG, keys, scan,
+                       seg_start, n_rows, capacity, n, sorted_vals, gx, emb_grad, partial);
+    hipLaunchKernelGGL(seg_reduce_join_kernel, dim3(pool_grid(capacity < n ? capacity : n, 256 / LG)), dim3(256), 0, st,
+                       D, LG, seg_start, n_rows, capacity, partial, emb_grad);
 }
 
 __global__ void scatter_add_kernel(int D, int LG, float* table, const int64_t* __restrict__ rows,

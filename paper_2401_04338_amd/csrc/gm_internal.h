@@ -94,8 +94,11 @@ void launch_slot_segsum(hipStream_t st, int F, int D, int n_tf, const u32* tf_ba
                         const int32_t* seg_lo, const int32_t* seg_hi, int seg_tf_stride,
                         const int32_t* sorted_sample, const float* src, int ld_src, float* table, float c0,
                         float c1);
-void launch_seg_reduce(hipStream_t st, int D, const u32* seg_start, const int64_t* n_rows, int64_t capacity,
-                       int64_t max_rows, const u32* sorted_vals, const float* gx, float* emb_grad);
+// keys: the sorted row keys; scan: exclusive scan of their segment-head flags (both as launch_segments left them)
+void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const u32* seg_start,
+                       const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
+                       float* emb_grad, float* partial /* seg_reduce_partial_floats(n, D) */);
+size_t seg_reduce_partial_floats(int64_t n, int D);
 void launch_scatter_add(hipStream_t st, int D, float* table, const int64_t* rows, const float* grad,
                         int64_t n_rows, float scale);
 

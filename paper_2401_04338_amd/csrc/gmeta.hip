@@ -371,6 +371,7 @@ struct BatchBufs {
     float *GX, *g_theta, *task_loss;
     Theta theta0;
     u32 *keys, *vals, *keys_tmp, *vals_tmp, *hist, *scan_tmp, *seg_start;
+    float* seg_partial;
 };
 
 static void alloc_batch(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t Ss, int64_t Sq, int64_t Ps, int64_t Pq,
@@ -394,6 +395,7 @@ static void alloc_batch(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t
     b.hist = ar.get<u32>(radix_hist_words(nnz) + 2 * (size_t)(T + 1) * 2);
     b.scan_tmp = ar.get<u32>(scan_tmp_words(nnz));
     b.seg_start = ar.get<u32>(std::min(nnz, capacity) + 2);
+    b.seg_partial = need_gx ? ar.get<float>(seg_reduce_partial_floats(nnz, c->D)) : nullptr;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1232,8 +1234,9 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     global_order(c, B, out->emb_rows, nullptr, capacity, out->n_emb_rows);
     if (F > 0) {
         Prof p(c, "seg_reduce", (double)nnz * (4.0 * D + 4), 0);
-        launch_seg_reduce(st, D, b.seg_start, out->n_emb_rows, capacity, std::min(nnz, capacity), b.vals, b.GX,
-                          out->emb_grad);
+        // the second sort buffer is free after the sort: it holds the partial sums of chunk-crossing segments
+        launch_seg_reduce(st, D, b.keys, b.keys_tmp, b.seg_start, out->n_emb_rows, capacity, nnz, b.vals, b.GX,
+                          out->emb_grad, b.seg_partial);
     }
     u32 hs[ST_WORDS];
     rc = read_status(c, hs);
