@@ -1,6 +1,6 @@
 // Embedding side of the MAML step (G-Meta Alg. 1): the one-pass prefetch of support and query rows
 // with sum pooling (prefetch step, Sec. 2.1.1), the task-local row updates and the overlap update
-// (inner steps on xi^Sup, Sec. 2.1.2), and the segment reduction that coalesces the sparse
+// (their dense and pad columns; the row arithmetic itself is in twohop_kernels.hip), and the segment reduction that coalesces the sparse
 // meta-gradient (global back-propagation on xi).  All HBM-bound: rows are read as float4 by groups of
 // D/4 lanes so that one wavefront keeps several independent row reads in flight.
 #include "gm_internal.h"
@@ -88,36 +88,6 @@ void launch_gather_pool(hipStream_t st, int F, int D, int n_dense, const int64_t
                            sample0, n_samples, row_map, row_base, x, ldx, x_bf);
 }
 
-// ------------------------------------------------------------------------------------------------
-// pooling over a task-local slot table (row deltas, or a direction's row part)
-// ------------------------------------------------------------------------------------------------
-__global__ void pool_slots_kernel(int F, int D, int LG, const int64_t* __restrict__ bag_offsets, int64_t sample0,
-                                  int64_t lookup0, int64_t n_bags, const int32_t* __restrict__ sample_task,
-                                  const int32_t* __restrict__ slot_of_lookup, const u32* __restrict__ tf_base,
-                                  const float* __restrict__ table, const int32_t* __restrict__ row_map,
-                                  int32_t row_base, const float* x_base, float* x_out, int ldx, bf16_t* x_bf) {
-    const int groups_per_block = blockDim.x / LG;
-    const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
-    if (g_in_block >= groups_per_block) return;
-    const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
-    const float4* tab4 = reinterpret_cast<const float4*>(table);
-    for (int64_t bag = (int64_t)blockIdx.x * groups_per_block + g_in_block; bag < n_bags; bag += n_groups) {
-        const int64_t s = bag / F;
-        const int f = (int)(bag - s * F);
-        const int64_t gb = sample0 * F + bag;
-        const int64_t p0 = bag_offsets[gb] - lookup0, p1 = bag_offsets[gb + 1] - lookup0;
-        const int64_t base = tf_base[(int64_t)sample_task[s] * F + f];
-        const int64_t o = (int64_t)(row_map[s] - row_base) * ldx + (int64_t)f * D + l * 4;
-        float4 acc = x_base ? *reinterpret_cast<const float4*>(x_base + o) : make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int64_t p = p0; p < p1; ++p) {
-            const int32_t slot = slot_of_lookup[p];
-            if (slot >= 0) acc = add4(acc, tab4[(base + slot) * LG + l]);
-        }
-        if (x_out) *reinterpret_cast<float4*>(x_out + o) = acc;
-        if (x_bf) store_bf4(x_bf + o, acc);
-    }
-}
-
 // dense and pad columns of every (padded) row: copied from x_base, or zero
 __global__ void copy_tail_kernel(int FD, const float* x_base, int64_t n_rows, float* x_out, int ldx, bf16_t* x_bf) {
     const int tail = ldx - FD;
@@ -130,65 +100,11 @@ __global__ void copy_tail_kernel(int FD, const float* x_base, int64_t n_rows, fl
     if (x_bf) x_bf[s * ldx + FD + c] = f2bf(v);
 }
 
-void launch_pool_slots(hipStream_t st, int F, int D, const int64_t* bag_offsets, int64_t sample0, int64_t lookup0,
-                       int64_t n_samples, const int32_t* sample_task, const int32_t* slot_of_lookup,
-                       const u32* tf_base, const float* table, const int32_t* row_map, int32_t row_base, int64_t n_rows,
-                       const float* x_base, float* x_out, int ldx, bf16_t* x_bf) {
-    if (n_samples <= 0) return;
-    const int LG = D / 4;
-    const int64_t n_bags = n_samples * F;
-    if (n_bags > 0)
-        hipLaunchKernelGGL(pool_slots_kernel, dim3(pool_grid(n_bags, 256 / LG)), dim3(256), 0, st, F, D, LG, bag_offsets,
-                           sample0, lookup0, n_bags, sample_task, slot_of_lookup, tf_base, table, row_map, row_base, x_base, x_out,
-                           ldx, x_bf);
-    const int64_t nt = n_rows * (ldx - F * D);
-    if (nt > 0 && (x_base != x_out || x_bf))
-        hipLaunchKernelGGL(copy_tail_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, st, F * D, x_base,
-                           n_rows, x_out, ldx, x_bf);
-}
-
-// ------------------------------------------------------------------------------------------------
-// per-task segment sum: table[slot] = c0*table[slot] + c1 * sum over the slot's lookups of src[sample, f]
-// The lookups of a slot are consecutive in the (row, sample, position)-sorted list, so the order of the
-// sum is fixed.
-// ------------------------------------------------------------------------------------------------
-__global__ void slot_segsum_kernel(int F, int D, int LG, const u32* __restrict__ tf_base, const u32* __restrict__ n_slots,
-                                   const int32_t* __restrict__ seg_lo, const int32_t* __restrict__ seg_hi,
-                                   int seg_tf_stride, const int32_t* __restrict__ sorted_sample,
-                                   const float* __restrict__ src, int ld_src, float* table, float c0, float c1) {
-    const int tf = blockIdx.x;
-    const int f = tf % F;
-    const int groups = blockDim.x / LG;
-    const int g = threadIdx.x / LG, l = threadIdx.x % LG;
-    if (g >= groups) return;
-    const int64_t B = tf_base[tf];
-    const int nu = (int)n_slots[tf];
-    const int64_t sb = B + (int64_t)tf * seg_tf_stride;
-    for (int u = g; u < nu; u += groups) {
-        const int lo = seg_lo[sb + u], hi = seg_hi[sb + u];
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int i = lo; i < hi; ++i) {
-            const int64_t s = sorted_sample[i];
-            acc = add4(acc, *reinterpret_cast<const float4*>(src + s * ld_src + (int64_t)f * D + l * 4));
-        }
-        float4* dst = reinterpret_cast<float4*>(table + (B + u) * D + l * 4);
-        float4 o;
-        if (c0 != 0.f) {
-            const float4 old = *dst;
-            o = make_float4(c0 * old.x + c1 * acc.x, c0 * old.y + c1 * acc.y, c0 * old.z + c1 * acc.z, c0 * old.w + c1 * acc.w);
-        } else {
-            o = make_float4(c1 * acc.x, c1 * acc.y, c1 * acc.z, c1 * acc.w);
-        }
-        *dst = o;
-    }
-}
-
-void launch_slot_segsum(hipStream_t st, int F, int D, int n_tf, const u32* tf_base, const u32* n_slots,
-                        const int32_t* seg_lo, const int32_t* seg_hi, int seg_tf_stride, const int32_t* sorted_sample,
-                        const float* src, int ld_src, float* table, float c0, float c1) {
-    if (n_tf <= 0) return;
-    hipLaunchKernelGGL(slot_segsum_kernel, dim3(n_tf), dim3(256), 0, st, F, D, D / 4, tf_base, n_slots, seg_lo, seg_hi,
-                       seg_tf_stride, sorted_sample, src, ld_src, table, c0, c1);
+void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_rows, float* x_out, int ldx, bf16_t* x_bf) {
+    const int64_t nt = n_rows * (ldx - FD);
+    if (nt > 0)
+        hipLaunchKernelGGL(copy_tail_kernel, dim3((unsigned)((nt + 255) / 256)), dim3(256), 0, st, FD, x_base, n_rows,
+                           x_out, ldx, x_bf);
 }
 
 // ------------------------------------------------------------------------------------------------

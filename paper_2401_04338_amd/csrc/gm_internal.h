@@ -52,10 +52,10 @@ struct TfSortArgs {
     u32* slot_rows;                 // [nnz_sup_w]       at base_sup[tf] + slot
     int32_t* slot_start;            // [nnz_sup_w+Tw*F]  at base_sup[tf] + tf + slot: first position of the slot in
                                     //                   the sorted list (absolute); sentinel at +n_slots
-    int32_t* sup_sorted_sample;     // [nnz_sup_w]       wave-local support sample of sorted lookup
+    int2* sup_sorted;               // [nnz_sup_w]       {row of the sample, slot} of every support lookup in sorted order
     int32_t* sup_slot;              // [nnz_sup_w]       by lookup
     int32_t* qry_slot;              // [nnz_qry_w]       by lookup, -1 when not in support
-    int32_t* qry_sorted_sample;     // [nnz_qry_w]       (may be null: then query segments are skipped)
+    int2* qry_sorted;               // [nnz_qry_w]       {row of the sample, slot or -1} of every query lookup, sorted
     int32_t* qseg_lo;               // [nnz_sup_w]       at base_sup[tf] + slot : range in the sorted query list
     int32_t* qseg_hi;
     // row of every sample (whole set) in the activation buffers, and the wave's first row
@@ -82,18 +82,37 @@ void launch_gather_pool(hipStream_t st, int F, int D, int n_dense, const int64_t
                         const int64_t* bag_offsets, const int32_t* indices, const float* dense,
                         const float* emb, int64_t sample0, int64_t n_samples, const int32_t* row_map,
                         int32_t row_base, float* x /* may be null */, int ldx, bf16_t* x_bf /* may be null */);
-// x_out[s, f*D:] = x_base[s, f*D:] + sum over the bag's lookups with slot >= 0 of table[base[tf]+slot]
-// (x_base null: start from zero; dense and pad columns copied from x_base or zeroed).
-void launch_pool_slots(hipStream_t st, int F, int D, const int64_t* bag_offsets, int64_t sample0,
-                       int64_t lookup0, int64_t n_samples, const int32_t* sample_task,
-                       const int32_t* slot_of_lookup, const u32* tf_base, const float* table,
-                       const int32_t* row_map, int32_t row_base, int64_t n_rows, const float* x_base, float* x_out,
-                       int ldx, bf16_t* x_bf);
-// table[base+slot] = c0*table[base+slot] + c1 * sum_{i in segment} src[sample_i, f*D:]
-void launch_slot_segsum(hipStream_t st, int F, int D, int n_tf, const u32* tf_base, const u32* n_slots,
-                        const int32_t* seg_lo, const int32_t* seg_hi, int seg_tf_stride,
-                        const int32_t* sorted_sample, const float* src, int ld_src, float* table, float c0,
-                        float c1);
+// Two-hop row arithmetic per (task, field): G[slot] = sum of Z over the slot's lookups (hop 1), then
+// y_out[bag] = y_in[bag] + c * sum over the bag's lookups of G[slot] (hop 2), for up to two sets of bags.
+struct TwoHopOut {
+    int enabled;
+    const int64_t* bag_offsets;     // the set's CSR (whole set)
+    int64_t sample0, lookup0;       // the wave's first sample / lookup in the set
+    const int32_t* real_offsets;    // [Tw+1] first sample of each task, relative to sample0
+    const int32_t* slot_of_lookup;  // [lookups of the wave] slot of each lookup, -1 when its row is not in the support set
+    const int32_t* row_map;         // row of each sample of the wave in the activation buffers
+    int32_t row_base;
+    const float* y_in;              // null: start from zero
+    float* y_out;                   // may alias y_in; may be null
+    bf16_t* y_bf;                   // may be null
+    int64_t ld;
+    float c;
+};
+struct TwoHopArgs {
+    int F, D, dc, range, bag0;      // dc (columns per slice), range and bag0 are set by the launcher
+    const u32 *tf_base, *n_slots;   // per (task, field): base of its slot / lookup lists, number of slots
+    const int32_t *in_seg_lo, *in_seg_hi;  // lookups of slot u: positions [lo, hi) of in_sorted_row, at base + tf*stride + u
+    int in_seg_tf_stride;
+    const int2* in_sorted;          // {row of Z, slot or -1} of every lookup in slot order
+    const int32_t* in_row_offsets;  // [Tw+1] first row (of Z) of each task
+    int max_in_rows;                // largest number of rows of Z any task has
+    const float* Z;                 // [rows, ldz], the (field f) block at column f*D
+    int64_t ldz;
+    TwoHopOut out[2];
+};
+void launch_two_hop(hipStream_t st, TwoHopArgs a, int n_tasks, int max_bags);
+void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_rows, float* x_out, int ldx, bf16_t* x_bf);
+
 // keys: the sorted row keys; scan: exclusive scan of their segment-head flags (both as launch_segments left them)
 void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const u32* seg_start,
                        const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,

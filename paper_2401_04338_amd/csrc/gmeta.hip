@@ -223,8 +223,9 @@ struct WaveBufs {
     int32_t *tile_g_s, *tile_m_s, *tile_g_q, *tile_m_q;
     u32 *cnt_s, *base_s, *cnt_q, *base_q, *n_slots, *scan_tmp;
     u32* slot_rows;
-    int32_t *slot_start, *sup_sorted_sample, *sup_slot, *qry_slot, *qry_sorted_sample, *qseg_lo, *qseg_hi;
-    float *Xs0, *Xq0, *Delta, *vXi, *dX, *loss_q;
+    int32_t *slot_start, *sup_slot, *qry_slot, *qseg_lo, *qseg_hi;
+    int2 *sup_sorted, *qry_sorted;
+    float *Xs0, *Xq0, *TXf, *dX, *loss_q;
     Theta v;  // direction / query gradient w.r.t. theta'
     Act Xs_scratch;
     std::vector<StepState> steps;
@@ -291,18 +292,17 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
     w.scan_tmp = ar.get<u32>(scan_tmp_words(TF + 1));
     w.slot_rows = ar.get<u32>(d.nnz_s + 1);
     w.slot_start = ar.get<int32_t>(d.nnz_s + TF + 1);
-    w.sup_sorted_sample = ar.get<int32_t>(d.nnz_s + 1);
+    w.sup_sorted = ar.get<int2>(d.nnz_s + 1);
     w.sup_slot = ar.get<int32_t>(d.nnz_s + 1);
     w.qry_slot = ar.get<int32_t>(d.nnz_q + 1);
-    w.qry_sorted_sample = ar.get<int32_t>(d.nnz_q + 1);
+    w.qry_sorted = ar.get<int2>(d.nnz_q + 1);
     w.qseg_lo = ar.get<int32_t>(d.nnz_s + 1);
     w.qseg_hi = ar.get<int32_t>(d.nnz_s + 1);
     const int ld0 = c->ld[0];
     w.Xs0 = ar.get<float>(d.Ps * ld0);
     w.Xq0 = ar.get<float>(d.Pq * ld0);
-    w.Delta = K > 0 ? ar.get<float>((d.nnz_s + 1) * D) : nullptr;
     const bool second = order == 2 && K > 0;
-    w.vXi = second ? ar.get<float>((d.nnz_s + 1) * D) : nullptr;
+    w.TXf = (second && bf) ? ar.get<float>(d.Ps * ld0) : nullptr;
     w.dX = ar.get<float>(std::max(d.Ps, d.Pq) * (int64_t)std::max(c->FD, 1) + 4);
     w.loss_q = ar.get<float>(d.Pq + 1);
     w.v = alloc_theta(c, ar, d.Tw, true);
@@ -860,8 +860,8 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
     a.F = F; a.t0 = wp.t0; a.Tw = Tw; a.sup = vs; a.qry = vq; a.field_base = c->d_field_base;
     a.cnt_sup = w.cnt_s; a.base_sup = w.base_s; a.cnt_qry = w.cnt_q; a.base_qry = w.base_q;
     a.n_slots = w.n_slots; a.slot_rows = w.slot_rows; a.slot_start = w.slot_start;
-    a.sup_sorted_sample = w.sup_sorted_sample; a.sup_slot = w.sup_slot; a.qry_slot = w.qry_slot;
-    a.qry_sorted_sample = w.qry_sorted_sample; a.qseg_lo = w.qseg_lo; a.qseg_hi = w.qseg_hi; a.status = c->d_status;
+    a.sup_sorted = w.sup_sorted; a.sup_slot = w.sup_slot; a.qry_slot = w.qry_slot;
+    a.qry_sorted = w.qry_sorted; a.qseg_lo = w.qseg_lo; a.qseg_hi = w.qseg_hi; a.status = c->d_status;
     a.sup_rows = B.b.prow_s; a.sup_row_base = (int32_t)wp.ps0;
     a.qry_rows = B.b.prow_q; a.qry_row_base = (int32_t)wp.pq0;
     {
@@ -1112,11 +1112,56 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                                params->emb, wp.q0, d.Sq, rows_q, rb_q, w.Xq0, ld0, (bf && K == 0) ? w.Xq.b : nullptr);
         }
         if (bf && X0s.b) transpose_act(c, X0s, d.Ps);
-        if (K > 0 && F > 0) launch_fill_f32(st, w.Delta, (d.nnz_s + 1) * D, 0.f);
         if (second && c->row_pad > 1) {
             if (w.TX.b) zero_bf16(st, w.TX.b, d.Ps * ld0);
             if (w.TX.f) launch_fill_f32(st, w.TX.f, d.Ps * ld0, 0.f);
         }
+        if (second && w.TXf) launch_fill_f32(st, w.TXf, d.Ps * ld0, 0.f);
+        if (second && c->row_pad == 1 && w.TX.f) launch_fill_f32(st, w.TX.f, d.Ps * ld0, 0.f);
+
+        // row arithmetic of one (task, field) at a time, through LDS (no row table in HBM)
+        int max_bags = 0;
+        for (int t = wp.t0; t < wp.t1; ++t)
+            max_bags = std::max<int>(max_bags, (int)std::max(sup->task_offsets[t + 1] - sup->task_offsets[t],
+                                                               qry->task_offsets[t + 1] - qry->task_offsets[t]));
+        int max_prows = 0;
+        for (int t = wp.t0; t < wp.t1; ++t)
+            max_prows = std::max<int>(max_prows, (int)std::max(B.poff_s[t + 1] - B.poff_s[t], B.poff_q[t + 1] - B.poff_q[t]));
+        if (K > 0 && F > 0 && max_prows > 2048)
+            return fail(c, GM_ERR_CAPACITY, "a task has %d samples in one set; the limit with inner steps is 2048", max_prows);
+        auto hop_out = [&](bool support, const float* y_in, float* y_out, bf16_t* y_bf, float cc) {
+            TwoHopOut o;
+            memset(&o, 0, sizeof o);
+            o.enabled = 1;
+            o.bag_offsets = support ? sup->bag_offsets : qry->bag_offsets;
+            o.sample0 = support ? wp.s0 : wp.q0;
+            o.lookup0 = support ? wp.ls0 : wp.lq0;
+            o.real_offsets = support ? w.real_off_s : w.real_off_q;
+            o.slot_of_lookup = support ? w.sup_slot : w.qry_slot;
+            o.row_map = support ? rows_s : rows_q;
+            o.row_base = support ? rb_s : rb_q;
+            o.y_in = y_in; o.y_out = y_out; o.y_bf = y_bf; o.ld = ld0; o.c = cc;
+            return o;
+        };
+        auto two_hop = [&](bool in_support, const float* Z, const TwoHopOut* o0, const TwoHopOut* o1) {
+            TwoHopArgs a;
+            memset(&a, 0, sizeof a);
+            a.F = F; a.D = D;
+            a.tf_base = w.base_s; a.n_slots = w.n_slots;
+            if (in_support) { a.in_seg_lo = w.slot_start; a.in_seg_hi = w.slot_start + 1; a.in_seg_tf_stride = 1; a.in_sorted = w.sup_sorted; }
+            else { a.in_seg_lo = w.qseg_lo; a.in_seg_hi = w.qseg_hi; a.in_seg_tf_stride = 0; a.in_sorted = w.qry_sorted; }
+            a.Z = Z; a.ldz = FD;
+            a.in_row_offsets = in_support ? w.row_off_s : w.row_off_q;
+            a.max_in_rows = max_prows;
+            if (o0) a.out[0] = *o0;
+            if (o1) a.out[1] = *o1;
+            const double bags = (o0 ? (double)d.Ss : 0.0) + (o1 ? (double)d.Sq : 0.0);
+            const double in_l = in_support ? (double)d.nnz_s : (double)d.nnz_q;
+            const double out_l = (o0 ? (double)d.nnz_s : 0.0) + (o1 ? (double)d.nnz_q : 0.0);
+            // algorithmic bytes: Z once per (sample, field), Y read + written per (sample, field), 4 B per lookup and hop
+            Prof p(c, "two_hop", 4.0 * D * F * (in_support ? d.Ss : d.Sq) + bags * F * (8.0 * D + (bf ? 2.0 * D : 0)) + 4.0 * (in_l + out_l), 0);
+            launch_two_hop(st, a, Tw, max_bags);
+        };
 
         // inner loop on the support set
         const float* labels_s = sup->labels + wp.s0;
@@ -1124,38 +1169,50 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         Theta th = b.theta0;        // GEMM operands of the current step
         const float* thf = b.theta0.f;  // fp32 view (biases, last layer)
         int64_t thf_stride = 0;
+        const float* xs_cur = w.Xs0;    // fp32 support input of the current step
+        Act Xq = w.Xq;                  // query input as the GEMMs read it
+        if (!bf) Xq.f = w.Xq0;          // fp32: the prefetched buffer, updated in place by the overlap update
         for (int k = 0; k < K; ++k) {
             StepState& s = w.steps[second ? k : 0];
-            if (k == 0) {
-                s.X = X0s;
-            } else if (F > 0) {
-                // support input of step k: meta rows plus the task's accumulated row deltas
-                Act Xk = second ? s.X : w.Xs_scratch;
-                Prof p(c, "pool_slots", (double)d.nnz_s * (4.0 * D + 4) + (double)d.Ss * F * 8.0 * D, 0);
-                if (bf && c->row_pad > 1) zero_bf16(st, Xk.b, d.Ps * ld0);
-                launch_pool_slots(st, F, D, sup->bag_offsets, wp.s0, wp.ls0, d.Ss, w.sample_task_s, w.sup_slot, w.base_s,
-                                  w.Delta, rows_s, rb_s, d.Ps, w.Xs0, bf ? nullptr : Xk.f, ld0, bf ? Xk.b : nullptr);
-                s.X = Xk;
-            } else {
-                s.X = X0s;
-            }
-            if (k > 0 && F > 0) transpose_act(c, s.X, d.Ps);
+            if (k == 0) s.X = X0s;
             s.th = th;
             s.wL = thf + c->offW[L];
             s.wL_stride = thf_stride;
             Pass p{&s.X, &s.A, &s.Dl, s.dL, s.zL};
             forward_backward(c, gs, labels_s, p, th, thf, thf_stride, nullptr, F > 0 ? w.dX : nullptr);
-            // local back-propagation: theta' = theta - alpha dtheta (per task), rows' = rows - alpha drows
+            // local back-propagation: theta' = theta - alpha dtheta (per task)
             Theta& next = w.thetas[second ? k : 0];
             float* wl_copy = (bf && second && k + 1 < K) ? w.steps[k + 1].wL_copy : nullptr;
             theta_grad(c, gs, p, next, thf, thf_stride, 1.f, -alpha, wl_copy);
             th = next;
             thf = next.f;
             thf_stride = nt;
+            // rows' = rows - alpha drows, seen through the pooled inputs: the support input of the next step and
+            // (overlap update) the query input; a query row that the support set does not touch keeps its meta value
+            const bool more = k + 1 < K;
+            Act Xn;  // support input of step k+1
+            if (more) Xn = second ? w.steps[k + 1].X : w.Xs_scratch;
             if (F > 0) {
-                Prof pp(c, "slot_segsum", (double)d.nnz_s * (4.0 * D + 4) + (double)d.nnz_s * 4.0 * D, 0);
-                launch_slot_segsum(st, F, D, n_tf, w.base_s, w.n_slots, w.slot_start, w.slot_start + 1, 1,
-                                   w.sup_sorted_sample, w.dX, FD, w.Delta, 1.f, -alpha);
+                float* xs_next = nullptr;
+                if (more) {
+                    xs_next = bf ? w.Xs0 : Xn.f;  // bf16: the fp32 master is updated in place
+                    if (bf && c->row_pad > 1) zero_bf16(st, Xn.b, d.Ps * ld0);
+                }
+                const bool last = !more;
+                TwoHopOut os = hop_out(true, xs_cur, xs_next, more && bf ? Xn.b : nullptr, -alpha);
+                TwoHopOut oq = hop_out(false, w.Xq0, w.Xq0, (bf && last) ? Xq.b : nullptr, -alpha);
+                if (bf && last && c->row_pad > 1) zero_bf16(st, Xq.b, d.Pq * ld0);
+                two_hop(true, w.dX, more ? &os : nullptr, &oq);
+                if (more) {
+                    launch_copy_tail(st, FD, xs_cur, d.Ps, bf ? nullptr : (xs_next != xs_cur ? xs_next : nullptr), ld0, bf ? Xn.b : nullptr);
+                    xs_cur = xs_next;
+                }
+            } else if (more) {  // no sparse fields: every step reads the same input
+                Xn = s.X;
+            }
+            if (more) {
+                if (F > 0) transpose_act(c, Xn, d.Ps);
+                w.steps[second ? k + 1 : 0].X = Xn;
             }
         }
         // bf16 second order with K > 1: steps k >= 1 read their last-layer weights from the copies taken above
@@ -1165,19 +1222,8 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                 w.steps[k].wL_stride = c->ld[L - 1];
             }
 
-        // overlap update + outer forward/backward on the query set
-        Act Xq = w.Xq;
-        if (!bf && !(K > 0 && F > 0)) Xq.f = w.Xq0;
-        if (K > 0 && F > 0) {
-            Prof p(c, "pool_slots", (double)d.nnz_q * (4.0 * D + 4) + (double)d.Sq * F * 8.0 * D, 0);
-            if (bf && c->row_pad > 1) zero_bf16(st, Xq.b, d.Pq * ld0);
-            launch_pool_slots(st, F, D, qry->bag_offsets, wp.q0, wp.lq0, d.Sq, w.sample_task_q, w.qry_slot, w.base_s,
-                              w.Delta, rows_q, rb_q, d.Pq, w.Xq0, bf ? nullptr : Xq.f, ld0, bf ? Xq.b : nullptr);
-        } else if (bf && K > 0) {  // no sparse fields: the query input is the prefetched one
-            Prof p(c, "pool_slots", 0, 0);
-            launch_pool_slots(st, 0, D, qry->bag_offsets, wp.q0, wp.lq0, d.Sq, w.sample_task_q, w.qry_slot, w.base_s,
-                              nullptr, rows_q, rb_q, d.Pq, w.Xq0, nullptr, ld0, Xq.b);
-        }
+        // outer forward/backward on the query set with the adapted parameters
+        if (bf && K > 0) launch_copy_tail(st, F > 0 ? FD : 0, w.Xq0, d.Pq, nullptr, ld0, Xq.b);
         transpose_act(c, Xq, d.Pq);
         float* gxq = b.GX + (Ps_tot + wp.pq0) * (int64_t)FD;
         float* gxs = b.GX + wp.ps0 * (int64_t)FD;
@@ -1186,22 +1232,16 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         colsum_f32(c, gq, 1, w.loss_q, 1, task_loss + wp.t0, 1, nullptr, 0, 0.f, 1.f);
         theta_grad(c, gq, pq, w.v, nullptr, 0, 0.f, 1.f, nullptr);
 
-        // second-order chain back through the inner steps
+        // second-order chain back through the inner steps: v_k = v_{k+1} - alpha H_k v_{k+1}
         if (second) {
+            float* txf = bf ? w.TXf : w.TX.f;  // fp32 pooled direction (support rows); TX.b is its GEMM operand copy
             if (F > 0) {
-                Prof p(c, "slot_segsum", (double)d.nnz_q * (4.0 * D + 4) + (double)d.nnz_s * 4.0 * D, 0);
-                launch_slot_segsum(st, F, D, n_tf, w.base_s, w.n_slots, w.qseg_lo, w.qseg_hi, 0, w.qry_sorted_sample, gxq,
-                                   FD, w.vXi, 0.f, 1.f);
+                // direction on the support rows = query gradient routed through the rows both sets share
+                TwoHopOut os = hop_out(true, nullptr, txf, w.TX.b, 1.f);
+                two_hop(false, gxq, &os, nullptr);
             }
             for (int k = K - 1; k >= 0; --k) {
                 const StepState& s = w.steps[k];
-                if (F > 0) {
-                    Prof p(c, "pool_slots", (double)d.nnz_s * (4.0 * D + 4) + (double)d.Ss * F * 4.0 * D, 0);
-                    launch_pool_slots(st, F, D, sup->bag_offsets, wp.s0, wp.ls0, d.Ss, w.sample_task_s, w.sup_slot,
-                                      w.base_s, w.vXi, rows_s, rb_s, d.Ps, nullptr, w.TX.f, ld0, w.TX.b);
-                } else if (w.TX.f) {
-                    launch_fill_f32(st, w.TX.f, d.Ps * ld0, 0.f);
-                }
                 transpose_act(c, w.TX, d.Ps);
                 hvp_step(c, gs, s, w, alpha, k > 0);
                 if (F > 0) {
@@ -1210,9 +1250,8 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                         launch_axpy(st, d.Ps * (int64_t)FD, -alpha, w.dX, gxs);
                     }
                     if (k > 0) {
-                        Prof p(c, "slot_segsum", (double)d.nnz_s * (4.0 * D + 4) + (double)d.nnz_s * 8.0 * D, 0);
-                        launch_slot_segsum(st, F, D, n_tf, w.base_s, w.n_slots, w.slot_start, w.slot_start + 1, 1,
-                                           w.sup_sorted_sample, w.dX, FD, w.vXi, 1.f, -alpha);
+                        TwoHopOut os = hop_out(true, txf, txf, w.TX.b, -alpha);
+                        two_hop(true, w.dX, &os, nullptr);
                     }
                 }
             }

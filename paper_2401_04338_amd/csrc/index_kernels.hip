@@ -238,7 +238,7 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap) {
             const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
             const int64_t p = a.sup.bag_offsets[(s_lo + s) * a.F + f] + j;
             a.sup_slot[p - a.sup.lookup0] = slot;
-            a.sup_sorted_sample[B + i] = a.sup_rows[s_lo + s] - a.sup_row_base;
+            a.sup_sorted[B + i] = make_int2(a.sup_rows[s_lo + s] - a.sup_row_base, slot);
         }
     }
     if (threadIdx.x == 0) {
@@ -276,7 +276,7 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap) {
         const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
         const int64_t p = a.qry.bag_offsets[(q_lo + s) * a.F + f] + j;
         a.qry_slot[p - a.qry.lookup0] = slot;
-        a.qry_sorted_sample[Bq + i] = a.qry_rows[q_lo + s] - a.qry_row_base;
+        a.qry_sorted[Bq + i] = make_int2(a.qry_rows[q_lo + s] - a.qry_row_base, slot);
     }
     for (int u = threadIdx.x; u < n_unique; u += blockDim.x) {
         const u64 klo = (u64)uniq[u] << 32, khi = ((u64)uniq[u] + 1) << 32;
