@@ -110,36 +110,81 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
         }
     }
 
-    // epilogue: lane holds column n = l32 of each 32x32 block and rows 8*(v/4) + 4*lhi + v%4
+    // epilogue.  A lane holds column l32 of each 32x32 block and rows 8*(v/4) + 4*lhi + v%4, which would give
+    // 2-byte scattered stores; instead every wave passes its accumulators through LDS one 32 x 64 strip at
+    // a time, applies the fused operation on 4 consecutive columns per lane and writes whole 128/256-byte
+    // row segments.  The transposed bf16 copy is read back from the same strip column-wise, 8 rows = 16 B.
     const float* bias = a.bias ? a.bias + (int64_t)g * a.gBias : nullptr;
     const bf16_t* mask = a.mask ? a.mask + r0 * a.ld_mask : nullptr;
     const float* Cin = a.Cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
     float* Cf = a.Cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
     bf16_t* Cb = a.Cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
     bf16_t* CbT = a.CbT ? a.CbT + (int64_t)g * a.gCbT + r0 * a.rCbT : nullptr;
+    constexpr int ELD = 64 + 4;
+    float* E = reinterpret_cast<float*>(smem) + wave * (32 * ELD);
+    const int er = lane >> 4, ec = (lane & 15) * 4;
+    __syncthreads();  // every wave is done with the operand tiles
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int n = n0 + wn0 + j * 32 + l32;
-            if (n >= N) continue;
-            const float bn = bias ? bias[n] : 0.f;
+        for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm0 + i * 32 + 8 * (v >> 2) + 4 * lhi + (v & 3);
-                if (m >= M) continue;
-                float x = acc[i][j][v];
-                switch (a.epi) {
-                    case EPI_BIAS_RELU: x = fmaxf(x + bn, 0.f); break;
-                    case EPI_BIAS_MASK: x = (bf2f(mask[(int64_t)m * a.ld_mask + n]) > 0.f) ? x + bn : 0.f; break;
-                    case EPI_MASK: x = (bf2f(mask[(int64_t)m * a.ld_mask + n]) > 0.f) ? x : 0.f; break;
-                    case EPI_AXPBY: x = a.c1 * x + (Cin ? a.c0 * Cin[(int64_t)m * a.ldcf + n] : 0.f); break;
-                    default: break;
+            for (int v = 0; v < 16; ++v) E[(8 * (v >> 2) + 4 * lhi + (v & 3)) * ELD + j * 32 + l32] = acc[i][j][v];
+        __syncthreads();
+        const int n = n0 + wn0 + ec;
+        const bool nok = n < N;
+        float4 bn = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (bias && nok) bn = *reinterpret_cast<const float4*>(bias + n);
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int rr = it * 4 + er;
+            const int m = m0 + wm0 + i * 32 + rr;
+            if (!nok || m >= M) continue;
+            float4 x = *reinterpret_cast<const float4*>(E + rr * ELD + ec);
+            if (a.epi == EPI_BIAS_RELU) {
+                x = make_float4(fmaxf(x.x + bn.x, 0.f), fmaxf(x.y + bn.y, 0.f), fmaxf(x.z + bn.z, 0.f), fmaxf(x.w + bn.w, 0.f));
+            } else if (a.epi == EPI_BIAS_MASK || a.epi == EPI_MASK) {
+                const uint2 mk = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
+                if (a.epi == EPI_BIAS_MASK) x = make_float4(x.x + bn.x, x.y + bn.y, x.z + bn.z, x.w + bn.w);
+                // a bf16 is positive iff it is neither zero nor has its sign bit set
+                const u32 h0 = mk.x & 0xffffu, h1 = mk.x >> 16, h2 = mk.y & 0xffffu, h3 = mk.y >> 16;
+                x.x = (h0 != 0 && h0 < 0x8000u) ? x.x : 0.f;
+                x.y = (h1 != 0 && h1 < 0x8000u) ? x.y : 0.f;
+                x.z = (h2 != 0 && h2 < 0x8000u) ? x.z : 0.f;
+                x.w = (h3 != 0 && h3 < 0x8000u) ? x.w : 0.f;
+            } else if (a.epi == EPI_AXPBY) {
+                x = make_float4(a.c1 * x.x, a.c1 * x.y, a.c1 * x.z, a.c1 * x.w);
+                if (Cin) {
+                    const float4 ci = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
+                    x = make_float4(x.x + a.c0 * ci.x, x.y + a.c0 * ci.y, x.z + a.c0 * ci.z, x.w + a.c0 * ci.w);
                 }
-                if (Cf) Cf[(int64_t)m * a.ldcf + n] = x;
-                if (Cb) Cb[(int64_t)m * a.ldcb + n] = f2bf(x);
-                if (CbT) CbT[(int64_t)n * a.ldcbT + m] = f2bf(x);
             }
+            if (Cf) *reinterpret_cast<float4*>(Cf + (int64_t)m * a.ldcf + n) = x;
+            if (Cb) {
+                uint2 pk;
+                pk.x = (u32)f2bf(x.x) | ((u32)f2bf(x.y) << 16);
+                pk.y = (u32)f2bf(x.z) | ((u32)f2bf(x.w) << 16);
+                *reinterpret_cast<uint2*>(Cb + (int64_t)m * a.ldcb + n) = pk;
+            }
+            if (CbT) *reinterpret_cast<float4*>(E + rr * ELD + ec) = x;
+        }
+        __syncthreads();
+        if (CbT) {
+            const int nT = n0 + wn0 + lane;   // one column per lane, 8 rows per 16-byte store
+            if (nT < N) {
+#pragma unroll
+                for (int r8 = 0; r8 < 32; r8 += 8) {
+                    const int m = m0 + wm0 + i * 32 + r8;
+                    if (m >= M) continue;     // M is a multiple of 8 on this path
+                    uint4 pk;
+                    pk.x = (u32)f2bf(E[(r8 + 0) * ELD + lane]) | ((u32)f2bf(E[(r8 + 1) * ELD + lane]) << 16);
+                    pk.y = (u32)f2bf(E[(r8 + 2) * ELD + lane]) | ((u32)f2bf(E[(r8 + 3) * ELD + lane]) << 16);
+                    pk.z = (u32)f2bf(E[(r8 + 4) * ELD + lane]) | ((u32)f2bf(E[(r8 + 5) * ELD + lane]) << 16);
+                    pk.w = (u32)f2bf(E[(r8 + 6) * ELD + lane]) | ((u32)f2bf(E[(r8 + 7) * ELD + lane]) << 16);
+                    *reinterpret_cast<uint4*>(CbT + (int64_t)nT * a.ldcbT + m) = pk;
+                }
+            }
+            __syncthreads();
         }
     }
 }
@@ -156,7 +201,8 @@ static void launch_variant(hipStream_t st, const GemmBArgs& a) {
         n_mtiles = (int64_t)mt_per_group * a.G;
     }
     if (n_mtiles <= 0 || n_ntiles <= 0) return;
-    const size_t shmem = (size_t)(BM + BN) * GLD * sizeof(bf16_t);
+    size_t shmem = (size_t)(BM + BN) * GLD * sizeof(bf16_t);
+    if (shmem < 4 * 32 * 68 * sizeof(float)) shmem = 4 * 32 * 68 * sizeof(float);  // the epilogue's strips
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN>), dim3((unsigned)(n_mtiles * n_ntiles)), dim3(256), shmem, st, a,
                        n_ntiles, mt_per_group);
 }

@@ -165,7 +165,7 @@ struct GemmBArgs {
     int epi;
     const float* bias; int64_t gBias;
     const bf16_t* mask; int64_t ld_mask;   // mask + (r0+m)*ld_mask + n
-    const float* Cin; int64_t gCin;        // Cin + g*gCin + m*ldcf + n (EPI_AXPBY)
+    const float* Cin; int64_t gCin, ldcin; // Cin + g*gCin + m*ldcin + n (EPI_AXPBY)
     float c0, c1;
     float* Cf; int64_t ldcf, gCf, rCf;     // fp32 output        (any of the three may be null)
     bf16_t* Cb; int64_t ldcb, gCb, rCb;    // bf16 output

@@ -566,12 +566,12 @@ static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, con
             a.B[i] = ths[i]->b + c->offWTb[l]; a.ldb[i] = K; a.gB[i] = ths[i]->sb;
         }
         a.Cb = out.b; a.ldcb = N; a.rCb = N; a.M = -1; a.N = N; a.K = K;
+        if (out.bT) { a.CbT = out.bT; a.ldcbT = g.rows; a.rCbT = 1; }  // [ld, rows]: the task's rows are a column range
         a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
         a.epi = epi; a.bias = bias; a.gBias = bias_stride;
         if (mask) { a.mask = mask->b; a.ld_mask = mask->ld; }
         launch_gemm_bf16(c->stream, a, g.bm);
     }
-    transpose_act(c, out, g.rows);
 }
 
 // out[rows, ld_{l-1}] = mask .* sum_p d_p[rows, ld_l] * W_p,l^T ; for l == 1: dX[rows, FD] fp32, no mask
@@ -606,15 +606,17 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
         a.M = -1; a.N = N; a.K = K;
         a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
         if (dX) { a.Cf = dX; a.ldcf = N; a.rCf = N; a.epi = EPI_NONE; }
-        else { a.Cb = out->b; a.ldcb = N; a.rCb = N; a.epi = EPI_MASK; a.mask = mask->b; a.ld_mask = mask->ld; }
+        else {
+            a.Cb = out->b; a.ldcb = N; a.rCb = N; a.epi = EPI_MASK; a.mask = mask->b; a.ld_mask = mask->ld;
+            if (out->bT) { a.CbT = out->bT; a.ldcbT = g.rows; a.rCbT = 1; }
+        }
         launch_gemm_bf16(c->stream, a, g.bm);
     }
-    if (!dX) transpose_act(c, *out, g.rows);
 }
 
 // out_g[ld_{l-1}, ld_l] = c0*in_g + c1 * sum_p a_p[rows_g, ld_{l-1}]^T d_p[rows_g, ld_l]  (and its bf16 copies)
 static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, const Act* d0, const Act* a1, const Act* d1,
-                     Theta& out, const float* in, int64_t in_stride, float c0, float c1) {
+                     Theta& out, const float* in, int64_t in_stride, float c0, float c1, bool write_f32 = true) {
     const int M = c->ld[l - 1], N = c->ld[l];
     const Act* as[2] = {a0, a1};
     const Act* ds[2] = {d0, d1};
@@ -639,15 +641,15 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
                 a.A[i] = as[i]->bT; a.lda[i] = g.rows; a.rA[i] = 1;
                 a.B[i] = ds[i]->bT; a.ldb[i] = g.rows; a.rB[i] = 1;
             }
-            a.Cf = out.f + c->offW[l]; a.ldcf = N; a.gCf = out.sf; a.M = M; a.N = N; a.K = -1;
-            if (out.b) { a.Cb = out.b + c->offWb[l]; a.ldcb = N; a.gCb = out.sb; }
-            a.epi = EPI_AXPBY; a.Cin = in ? in + c->offW[l] : nullptr; a.gCin = in_stride; a.c0 = c0; a.c1 = c1;
+            if (write_f32 || !out.b) { a.Cf = out.f + c->offW[l]; a.ldcf = N; a.gCf = out.sf; }
+            a.M = M; a.N = N; a.K = -1;
+            if (out.b) {  // operand copies: W and W^T
+                a.Cb = out.b + c->offWb[l]; a.ldcb = N; a.gCb = out.sb;
+                a.CbT = out.b + c->offWTb[l]; a.ldcbT = M; a.gCbT = out.sb;
+            }
+            a.epi = EPI_AXPBY; a.Cin = in ? in + c->offW[l] : nullptr; a.gCin = in_stride; a.ldcin = N; a.c0 = c0; a.c1 = c1;
             launch_gemm_bf16(c->stream, a, 128);
         }
-    }
-    if (c->mlp_dtype && out.b) {
-        Prof p(c, "transpose_w", 4.0 * g.G * M * N, 0);
-        launch_transpose_bf16(c->stream, out.b + c->offWb[l], M, N, out.b + c->offWTb[l], M, g.G, out.sb, out.sb);
     }
 }
 
@@ -717,12 +719,12 @@ static void forward_backward(gm_ctx* c, const Grp& g, const float* labels, const
 
 // out = c0*in + c1 * (gradient of the pass w.r.t. theta), per task; out.b (if any) gets the bf16 operand copies
 static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, Theta& out, const float* in, int64_t in_stride, float c0,
-                       float c1, float* wL_copy) {
+                       float c1, float* wL_copy, bool write_f32 = true) {
     const int L = c->L;
     const int64_t nt = out.sf;
     for (int l = 1; l < L; ++l) {
         const Act* prev = l == 1 ? p.X : &(*p.A)[l - 1];
-        dense_tn(c, g, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, out, in, in_stride, c0, c1);
+        dense_tn(c, g, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, out, in, in_stride, c0, c1, write_f32);
         colsum(c, g, c->ld[l], &(*p.Dl)[l], nullptr, nullptr, nullptr, out.f + c->offb[l], nt, in ? in + c->offb[l] : nullptr,
                in_stride, c0, c1);
     }
@@ -1183,7 +1185,8 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             // local back-propagation: theta' = theta - alpha dtheta (per task)
             Theta& next = w.thetas[second ? k : 0];
             float* wl_copy = (bf && second && k + 1 < K) ? w.steps[k + 1].wL_copy : nullptr;
-            theta_grad(c, gs, p, next, thf, thf_stride, 1.f, -alpha, wl_copy);
+            // bf16: after the last inner step only the operand copies of W' are read again, not its fp32 master
+            theta_grad(c, gs, p, next, thf, thf_stride, 1.f, -alpha, wl_copy, !(bf && k + 1 == K));
             th = next;
             thf = next.f;
             thf_stride = nt;
