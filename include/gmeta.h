@@ -50,7 +50,7 @@ typedef struct gm_ctx gm_ctx; /* opaque; owns only its workspace */
 typedef struct {
     int32_t n_fields;              /* F sparse fields                                       */
     const int64_t* rows_per_field; /* HOST [F] rows of each field's table                   */
-    int32_t emb_dim;               /* D, a multiple of 4, at most 256                       */
+    int32_t emb_dim;               /* D, a power of two in 4..256                           */
     int32_t n_dense;               /* dense features per sample                             */
     int32_t n_layers;              /* L                                                     */
     const int32_t* layer_dims;     /* HOST [L+1] d_0..d_L; d_0 = F*D + n_dense, d_L = 1     */
