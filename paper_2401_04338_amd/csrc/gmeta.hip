@@ -939,7 +939,7 @@ static int plan_waves(gm_ctx* c, Batch& B, size_t avail, int K, int order, int b
         have_offsets = true;
         return GM_OK;
     };
-    int per = std::max(T, 1);
+    int per = std::min(std::max(T, 1), 32768);  // a wave's tasks are one grid dimension of several kernels
     while (true) {
         plans.clear();
         bool fits = true;
