@@ -18,15 +18,20 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 #define GK 64          // k extent of one LDS tile
 #define GLD (GK + 8)   // LDS row stride in elements: 144 bytes, an odd number of 16-byte units
 
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group) {
+template <int BM, int BN, bool DB>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
     constexpr int MI = BM / 64, NI = BN / 64;  // 32x32 blocks per wave in each direction (2x2 waves)
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    bf16_t* As = smem;                 // [BM][GLD]
-    bf16_t* Bs = smem + BM * GLD;      // [BN][GLD]
+    constexpr int TILE = (BM + BN) * GLD;      // elements of one operand stage: A [BM][GLD] then B [BN][GLD]
 
-    const int ntile = blockIdx.x % n_ntiles;
-    const int mtile = blockIdx.x / n_ntiles;
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Re-number them so that
+    // consecutive tiles -- the n-tiles of one row block, then the next row block of the same task, which
+    // read the same rows and the same weights -- run on the same XCD.
+    const int per_xcd = gridDim.x >> 3;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= n_tiles) return;
+    const int ntile = tile % n_ntiles;
+    const int mtile = tile / n_ntiles;
     int g, m0;
     if (a.tile_group) {
         g = a.tile_group[mtile];
@@ -59,12 +64,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     uint4 ra[CA], rb[CB];
     const int crow = tid >> 3, ccol = (tid & 7) * 8;     // chunk c = tid + 256*i: row = crow + 32*i, k = ccol
 
-    const int total_kt_pair[2] = {(K + GK - 1) / GK, (K + GK - 1) / GK};
-    const int n_kt = total_kt_pair[0] * a.n_pairs;
+    const int kt_per_pair = (K + GK - 1) / GK;
+    const int n_kt = kt_per_pair * a.n_pairs;
 
     auto load_tile = [&](int kt) {
-        const int pr = kt / total_kt_pair[0];
-        const int k0 = (kt - pr * total_kt_pair[0]) * GK;
+        const int pr = kt / kt_per_pair;
+        const int k0 = (kt - pr * kt_per_pair) * GK;
         const bf16_t* A = a.A[pr] + (int64_t)g * a.gA[pr] + r0 * a.rA[pr];
         const bf16_t* B = a.B[pr] + (int64_t)g * a.gB[pr] + r0 * a.rB[pr];
         const int64_t lda = a.lda[pr], ldb = a.ldb[pr];
@@ -80,19 +85,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
             rb[i] = (kok && n < N) ? *reinterpret_cast<const uint4*>(B + (int64_t)n * ldb + k0 + ccol) : make_uint4(0, 0, 0, 0);
         }
     };
-    auto store_tile = [&]() {
+    auto store_tile = [&](bf16_t* stage) {
 #pragma unroll
-        for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4*>(As + (crow + 32 * i) * GLD + ccol) = ra[i];
+        for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4*>(stage + (crow + 32 * i) * GLD + ccol) = ra[i];
 #pragma unroll
-        for (int i = 0; i < CB; ++i) *reinterpret_cast<uint4*>(Bs + (crow + 32 * i) * GLD + ccol) = rb[i];
+        for (int i = 0; i < CB; ++i) *reinterpret_cast<uint4*>(stage + BM * GLD + (crow + 32 * i) * GLD + ccol) = rb[i];
     };
-
-    if (n_kt > 0) load_tile(0);
-    for (int kt = 0; kt < n_kt; ++kt) {
-        __syncthreads();  // previous tile fully consumed
-        store_tile();
-        __syncthreads();
-        if (kt + 1 < n_kt) load_tile(kt + 1);  // overlaps with the MFMAs below
+    auto compute = [&](const bf16_t* stage) {
+        const bf16_t* As = stage;
+        const bf16_t* Bs = stage + BM * GLD;
 #pragma unroll
         for (int kk = 0; kk < GK / 16; ++kk) {
             bf16x8 af[MI], bfr[NI];
@@ -108,22 +109,49 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
                 for (int j = 0; j < NI; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
+    };
+
+    if (DB) {
+        // two LDS stages: the next tile is fetched to registers while this one feeds the MFMAs and is parked in the
+        // other stage afterwards; one barrier per tile
+        if (n_kt > 0) {
+            load_tile(0);
+            store_tile(smem);
+        }
+        __syncthreads();
+        for (int kt = 0; kt < n_kt; ++kt) {
+            const bool more = kt + 1 < n_kt;
+            if (more) load_tile(kt + 1);
+            compute(smem + (kt & 1) * TILE);
+            if (more) store_tile(smem + ((kt + 1) & 1) * TILE);
+            __syncthreads();
+        }
+    } else {
+        if (n_kt > 0) load_tile(0);
+        for (int kt = 0; kt < n_kt; ++kt) {
+            __syncthreads();  // previous tile fully consumed
+            store_tile(smem);
+            __syncthreads();
+            if (kt + 1 < n_kt) load_tile(kt + 1);  // overlaps with the MFMAs below
+            compute(smem);
+        }
+        __syncthreads();  // every wave is done with the operand tiles
     }
 
     // epilogue.  A lane holds column l32 of each 32x32 block and rows 8*(v/4) + 4*lhi + v%4, which would give
-    // 2-byte scattered stores; instead every wave passes its accumulators through LDS one 32 x 64 strip at
-    // a time, applies the fused operation on 4 consecutive columns per lane and writes whole 128/256-byte
-    // row segments.  The transposed bf16 copy is read back from the same strip column-wise, 8 rows = 16 B.
+    // 2-byte scattered stores; instead every wave passes its accumulators through LDS one 32-row strip at a
+    // time, applies the fused operation on 4 consecutive columns per lane and writes whole row segments.
+    // The transposed bf16 copy is read back from the same strip column-wise, 8 rows = 16 bytes.
     const float* bias = a.bias ? a.bias + (int64_t)g * a.gBias : nullptr;
     const bf16_t* mask = a.mask ? a.mask + r0 * a.ld_mask : nullptr;
     const float* Cin = a.Cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
     float* Cf = a.Cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
     bf16_t* Cb = a.Cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
     bf16_t* CbT = a.CbT ? a.CbT + (int64_t)g * a.gCbT + r0 * a.rCbT : nullptr;
-    constexpr int ELD = 64 + 4;
+    constexpr int SW = NI * 32, ELD = SW + 4;      // strip width, LDS row stride (floats)
+    constexpr int LPR = SW / 4, RPI = 64 / LPR;    // lanes per strip row, rows per pass
     float* E = reinterpret_cast<float*>(smem) + wave * (32 * ELD);
-    const int er = lane >> 4, ec = (lane & 15) * 4;
-    __syncthreads();  // every wave is done with the operand tiles
+    const int er = lane / LPR, ec = (lane % LPR) * 4;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -136,8 +164,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
         float4 bn = make_float4(0.f, 0.f, 0.f, 0.f);
         if (bias && nok) bn = *reinterpret_cast<const float4*>(bias + n);
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const int rr = it * 4 + er;
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int rr = it * RPI + er;
             const int m = m0 + wm0 + i * 32 + rr;
             if (!nok || m >= M) continue;
             float4 x = *reinterpret_cast<const float4*>(E + rr * ELD + ec);
@@ -170,18 +198,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
         }
         __syncthreads();
         if (CbT) {
-            const int nT = n0 + wn0 + lane;   // one column per lane, 8 rows per 16-byte store
-            if (nT < N) {
 #pragma unroll
-                for (int r8 = 0; r8 < 32; r8 += 8) {
-                    const int m = m0 + wm0 + i * 32 + r8;
-                    if (m >= M) continue;     // M is a multiple of 8 on this path
-                    uint4 pk;
-                    pk.x = (u32)f2bf(E[(r8 + 0) * ELD + lane]) | ((u32)f2bf(E[(r8 + 1) * ELD + lane]) << 16);
-                    pk.y = (u32)f2bf(E[(r8 + 2) * ELD + lane]) | ((u32)f2bf(E[(r8 + 3) * ELD + lane]) << 16);
-                    pk.z = (u32)f2bf(E[(r8 + 4) * ELD + lane]) | ((u32)f2bf(E[(r8 + 5) * ELD + lane]) << 16);
-                    pk.w = (u32)f2bf(E[(r8 + 6) * ELD + lane]) | ((u32)f2bf(E[(r8 + 7) * ELD + lane]) << 16);
-                    *reinterpret_cast<uint4*>(CbT + (int64_t)nT * a.ldcbT + m) = pk;
+            for (int c = 0; c < SW; c += 64) {
+                const int col = c + lane;         // one column per lane, 8 rows per 16-byte store
+                const int nT = n0 + wn0 + col;
+                if (col < SW && nT < N) {
+#pragma unroll
+                    for (int r8 = 0; r8 < 32; r8 += 8) {
+                        const int m = m0 + wm0 + i * 32 + r8;
+                        if (m >= M) continue;     // M is a multiple of 8 on this path
+                        uint4 pk;
+                        pk.x = (u32)f2bf(E[(r8 + 0) * ELD + col]) | ((u32)f2bf(E[(r8 + 1) * ELD + col]) << 16);
+                        pk.y = (u32)f2bf(E[(r8 + 2) * ELD + col]) | ((u32)f2bf(E[(r8 + 3) * ELD + col]) << 16);
+                        pk.z = (u32)f2bf(E[(r8 + 4) * ELD + col]) | ((u32)f2bf(E[(r8 + 5) * ELD + col]) << 16);
+                        pk.w = (u32)f2bf(E[(r8 + 6) * ELD + col]) | ((u32)f2bf(E[(r8 + 7) * ELD + col]) << 16);
+                        *reinterpret_cast<uint4*>(CbT + (int64_t)nT * a.ldcbT + m) = pk;
+                    }
                 }
             }
             __syncthreads();
@@ -189,7 +221,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool DB>
 static void launch_variant(hipStream_t st, const GemmBArgs& a) {
     const int n_ntiles = (a.N + BN - 1) / BN;
     int64_t n_mtiles;
@@ -201,16 +233,24 @@ static void launch_variant(hipStream_t st, const GemmBArgs& a) {
         n_mtiles = (int64_t)mt_per_group * a.G;
     }
     if (n_mtiles <= 0 || n_ntiles <= 0) return;
-    size_t shmem = (size_t)(BM + BN) * GLD * sizeof(bf16_t);
-    if (shmem < 4 * 32 * 68 * sizeof(float)) shmem = 4 * 32 * 68 * sizeof(float);  // the epilogue's strips
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN>), dim3((unsigned)(n_mtiles * n_ntiles)), dim3(256), shmem, st, a,
-                       n_ntiles, mt_per_group);
+    const int64_t n_tiles = n_mtiles * n_ntiles;
+    size_t shmem = (size_t)(BM + BN) * GLD * sizeof(bf16_t) * (DB ? 2 : 1);
+    const size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);  // the epilogue's strips
+    if (shmem < epi) shmem = epi;
+    auto kern = gemm_bf16_kernel<BM, BN, DB>;
+    if (shmem > 48 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
 }
 
-// bm: row tile the caller built its (tile_group, tile_m0) lists for (64 or 128)
+// bm: row tile the caller built its (tile_group, tile_m0) lists for (64, 128 or 256).  Measured on the
+// benchmark shapes: one LDS stage with register prefetch beats two stages (occupancy), and 256x128 beats
+// 128x128 and 256x256 when a task has enough rows; the weight-gradient set-up (fixed M, K = rows of a
+// task) is bound by the theta' it writes and keeps 128x128.
 void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm) {
-    if (bm == 64) launch_variant<64, 128>(st, a);
-    else launch_variant<128, 128>(st, a);
+    if (bm == 64) launch_variant<64, 128, false>(st, a);
+    else if (bm == 256) launch_variant<256, 128, false>(st, a);
+    else launch_variant<128, 128, false>(st, a);
 }
 
 // ------------------------------------------------------------------------------------------------

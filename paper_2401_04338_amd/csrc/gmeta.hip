@@ -912,7 +912,8 @@ static WaveDims wave_dims(const Batch& B, const WavePlan& p, int bm) {
 static int pick_bm(const gm_ctx* c, const Batch& B) {
     if (B.T == 0) return 64;
     const int64_t avg = (B.poff_s[B.T] + B.poff_q[B.T]) / (2 * (int64_t)B.T);
-    return (c->mlp_dtype && avg >= 96) ? 128 : 64;
+    if (!c->mlp_dtype) return 64;
+    return avg >= 192 ? 256 : (avg >= 96 ? 128 : 64);
 }
 
 // splits the tasks into waves that fit `avail` bytes of workspace
