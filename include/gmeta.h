@@ -94,8 +94,9 @@ int gm_create(gm_ctx** ctx, const gm_model_desc* model, int device, void* hip_st
 void gm_destroy(gm_ctx* ctx);
 const char* gm_last_error(const gm_ctx* ctx);
 
-/* Workspace that lets a batch of this size run in ONE wave of tasks.  A smaller workspace is
- * legal: gm_meta_step then processes the tasks in several waves (Alg. 1 treats tasks independently). */
+/* Workspace that lets a batch of this size, with tasks of equal size, run in ONE wave of tasks.  A
+ * smaller workspace is legal (and very uneven tasks may need more): gm_meta_step then processes the
+ * tasks in several waves (Alg. 1 treats tasks independently). */
 size_t gm_workspace_bytes(const gm_model_desc* model, int32_t n_tasks, int64_t n_support,
                           int64_t n_query, int64_t nnz_support, int64_t nnz_query,
                           int32_t inner_steps, int32_t order);
@@ -128,6 +129,15 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
                   int64_t* slot_counts, int64_t* slot_rows, int32_t* sup_slot, int32_t* qry_slot,
                   int64_t* emb_rows, int64_t* seg_counts, int64_t* n_emb_rows,
                   int64_t emb_rows_capacity);
+
+/* Implementation choices that change results by rounding order only (for measurement and tests).
+ *   "row_path": how the task-local row arithmetic (inner-loop row update, overlap update of Sec. 2.1.2 and
+ *               their tangents) is carried out: 0 = chosen per wave of tasks (default); 1 = always the
+ *               sparse two-hop kernel; 2 = always per-(task, field) pair-count matrices on the matrix
+ *               cores (gm_meta_step then returns GM_ERR_CAPACITY when a wave exceeds that path's limits:
+ *               bags of at most 255 lookups, pair counts of at most 255, 8192 lookups per task, field and set).
+ * Unknown keys or values give GM_ERR_ARG. */
+int gm_configure(gm_ctx* ctx, const char* key, int64_t value);
 
 /* Kernel timing for measurement harnesses (not part of the method): while enabled, every kernel family
  * launched by later calls is bracketed by HIP events on the context's stream.  gm_profile_report returns

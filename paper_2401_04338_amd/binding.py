@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libgmeta.so")
 GM_OK, GM_ERR_ARG, GM_ERR_INDEX, GM_ERR_CAPACITY, GM_ERR_WORKSPACE, GM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["gm_create", "gm_destroy", "gm_last_error", "gm_workspace_bytes", "gm_meta_step",
-           "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_profile", "gm_profile_report"]
+           "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report"]
 
 
 class gm_model_desc(C.Structure):
@@ -81,6 +81,8 @@ def load_library() -> C.CDLL:
     lib.gm_gather_pool.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.c_void_p, C.c_void_p]
     lib.gm_index_prep.restype = C.c_int
     lib.gm_index_prep.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set)] + [C.c_void_p] * 7 + [C.c_int64]
+    lib.gm_configure.restype = C.c_int
+    lib.gm_configure.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
     lib.gm_profile.restype = C.c_int
     lib.gm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.gm_profile_report.restype = C.c_char_p
@@ -222,6 +224,9 @@ class GMeta:
         return dict(slot_counts=o["slot_counts"][: n_tasks * F], slot_rows=o["slot_rows"][:ns],
                     sup_slot=o["sup_slot"][: ss.nnz], qry_slot=o["qry_slot"][: qs.nnz],
                     emb_rows=o["emb_rows"][:n], seg_counts=o["seg_counts"][:n])
+
+    def configure(self, key: str, value: int):
+        self._check(self.lib.gm_configure(self._ctx, key.encode(), int(value)))
 
     def profile(self, enable: bool):
         self._check(self.lib.gm_profile(self._ctx, 1 if enable else 0))

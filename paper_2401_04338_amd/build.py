@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgmeta.so")
-SOURCES = ["gmeta.hip", "index_kernels.hip", "embed_kernels.hip", "mlp_kernels.hip", "gemm_bf16.hip", "twohop_kernels.hip"]
+SOURCES = ["gmeta.hip", "index_kernels.hip", "embed_kernels.hip", "mlp_kernels.hip", "gemm_bf16.hip", "twohop_kernels.hip", "pairhop_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-Wno-unused-value", "-Wno-unknown-warning-option"]

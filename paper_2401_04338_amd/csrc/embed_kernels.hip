@@ -178,21 +178,38 @@ __global__ void seg_reduce_chunks_kernel(int D, int LG, const u32* __restrict__ 
     }
 }
 
-__global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
-                                       int64_t capacity, const float* __restrict__ partial, float* emb_grad) {
+// One lane group per CHUNK: if a segment starts inside the chunk and runs past its end, this group adds its
+// partial sums in chunk order (every such segment is the last one of exactly one chunk).
+__global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ keys, const u32* __restrict__ scan,
+                                       const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
+                                       int64_t capacity, int64_t n, const float* __restrict__ partial, float* emb_grad) {
     const int groups_per_block = blockDim.x / LG;
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
     if (g_in_block >= groups_per_block) return;
     const int64_t n_valid = min(*n_rows, capacity);
+    const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
     const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
-    for (int64_t seg = (int64_t)blockIdx.x * groups_per_block + g_in_block; seg < n_valid; seg += n_groups) {
+    for (int64_t c = (int64_t)blockIdx.x * groups_per_block + g_in_block; c + 1 < n_chunks; c += n_groups) {
+        const int64_t cb = c * SEG_CH, ce = cb + SEG_CH;   // not the last chunk, so it is full
+        const int64_t i = ce - 1;
+        const bool head = (i == 0) || (keys[i] != keys[i - 1]);
+        const int64_t seg = (int64_t)scan[i] + (head ? 1 : 0) - 1;
+        if (seg >= n_valid) continue;
         const int64_t s0 = seg_start[seg], s1 = seg_start[seg + 1];
-        const int64_t c0 = s0 / SEG_CH, c1 = (s1 - 1) / SEG_CH;
-        if (c0 == c1) continue;
-        // first chunk: the part that starts in it (slot 1); every later chunk: the part that began earlier (slot 0)
-        float4 acc = *reinterpret_cast<const float4*>(partial + (c0 * 2 + 1) * D + l * 4);
-        for (int64_t c = c0 + 1; c <= c1; ++c)
-            acc = add4(acc, *reinterpret_cast<const float4*>(partial + (c * 2 + 0) * D + l * 4));
+        if (s0 < cb || s1 <= ce) continue;                 // began earlier, or ends inside this chunk
+        const int64_t c1 = (s1 - 1) / SEG_CH;
+        float4 acc = *reinterpret_cast<const float4*>(partial + (c * 2 + 1) * D + l * 4);
+        // a hot row's segment spans thousands of chunks: keep 8 independent loads in flight, add in chunk order
+        int64_t cc = c + 1;
+        for (; cc + 8 <= c1 + 1; cc += 8) {
+            float4 x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = *reinterpret_cast<const float4*>(partial + ((cc + u) * 2 + 0) * D + l * 4);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = add4(acc, x[u]);
+        }
+        for (; cc <= c1; ++cc)
+            acc = add4(acc, *reinterpret_cast<const float4*>(partial + (cc * 2 + 0) * D + l * 4));
         *reinterpret_cast<float4*>(emb_grad + seg * D + l * 4) = acc;
     }
 }
@@ -207,8 +224,8 @@ void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, 
     const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
     hipLaunchKernelGGL(seg_reduce_chunks_kernel, dim3(pool_grid(n_chunks, 256 / LG)), dim3(256), 0, st, D, LG, keys, scan,
                        seg_start, n_rows, capacity, n, sorted_vals, gx, emb_grad, partial);
-    hipLaunchKernelGGL(seg_reduce_join_kernel, dim3(pool_grid(capacity < n ? capacity : n, 256 / LG)), dim3(256), 0, st,
-                       D, LG, seg_start, n_rows, capacity, partial, emb_grad);
+    hipLaunchKernelGGL(seg_reduce_join_kernel, dim3(pool_grid(n_chunks, 256 / LG)), dim3(256), 0, st, D, LG, keys, scan,
+                       seg_start, n_rows, capacity, n, partial, emb_grad);
 }
 
 __global__ void scatter_add_kernel(int D, int LG, float* table, const int64_t* __restrict__ rows,

@@ -20,7 +20,7 @@ __device__ __forceinline__ float bf2f(bf16_t h) { return __builtin_bit_cast(floa
 #endif
 
 // Device-side status word indices (ctx->d_status).
-enum { ST_BAD_INDEX = 0, ST_CAPACITY = 1, ST_MAX_TF = 2, ST_NROWS = 3, ST_WORDS = 8 };
+enum { ST_BAD_INDEX = 0, ST_CAPACITY = 1, ST_MAX_TF = 2, ST_NROWS = 3, ST_MAX_BAG = 4, ST_PAIR_OVF = 5, ST_WORDS = 8 };
 
 // ------------------------------------------------------------------ index kernels
 // Per-wave geometry handed to the index kernels (all device pointers).
@@ -111,6 +111,46 @@ struct TwoHopArgs {
     TwoHopOut out[2];
 };
 void launch_two_hop(hipStream_t st, TwoHopArgs a, int n_tasks, int max_bags);
+
+// The same row arithmetic as a dense product: per (task, field) the pair-count matrix
+// M[i][j] = number of (lookup of out-bag i, lookup of in-bag j) pairs on one row of the task's support set,
+// stored as bytes, [pad64(n_out)][pad64(n_in)] per field, fields of a task back to back.
+#define PAIR_TILE_BYTES (136 * 1024)
+#define PAIR_MAX_CAP 8192        // lookups of one (task, field) and set that the counting kernel stages
+#define PAIR_MAX_BAG 255         // longest bag for which the 16-bit counters cannot wrap
+struct PairCountArgs {
+    int F;
+    const int32_t *real_off_s, *real_off_q;   // [Tw+1] first sample of each task (relative to the wave)
+    const int32_t *row_off_s, *row_off_q;     // [Tw+1] first row of each task in the activation buffers
+    const u32 *base_s, *base_q, *cnt_q, *n_slots;   // per (task, field)
+    const int32_t *slot_start, *qseg_lo, *qseg_hi;
+    const int2 *sup_sorted, *qry_sorted;
+    const int64_t *off_ss, *off_qs, *off_sq;  // [Tw] byte offset of the task's first matrix of each kind
+    uint8_t* mat;
+    int want_ss, want_sq;
+    int tile_bytes;                           // set by the launcher
+    u32* status;
+};
+void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap);
+struct PairHopOut {
+    int enabled;
+    const int64_t* mat_off;                   // [Tw]
+    const int32_t *real_off, *row_off;        // the out set
+    const float* y_in;                        // null: start from zero
+    float* y_out;                             // may alias y_in; may be null
+    bf16_t* y_bf;                             // may be null
+    int64_t ld;
+    float c;
+};
+struct PairHopArgs {
+    int F, D, row_blocks;                     // row_blocks is set by the launcher
+    const uint8_t* mat;
+    const int32_t *in_real_off, *in_row_off;  // the in set
+    const float* Z;                           // [rows, ldz], the (field f) block at column f*D
+    int64_t ldz;
+    PairHopOut out[2];
+};
+void launch_pair_hop(hipStream_t st, PairHopArgs a, int Tw, int max_out_rows);
 void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_rows, float* x_out, int ldx, bf16_t* x_bf);
 
 // keys: the sorted row keys; scan: exclusive scan of their segment-head flags (both as launch_segments left them)

@@ -68,6 +68,7 @@ struct gm_ctx {
     int64_t* d_field_base = nullptr;
     u32* d_status = nullptr;
     std::string err;
+    int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
     // optional kernel timing
     bool prof_on = false;
     std::vector<ProfPending> prof_pending;
@@ -236,12 +237,18 @@ struct WaveBufs {
     Act TX;
     std::vector<Act> TA, TD;
     float* tdL;
+    // pair-count matrices of the wave (null when the sparse kernel does the row arithmetic)
+    uint8_t* pair_mat;
+    int64_t *pair_off_ss, *pair_off_qs, *pair_off_sq;
 };
 
 struct WaveDims {
     int Tw;
     int64_t Ss, Sq, Ps, Pq, nnz_s, nnz_q;  // real samples, padded rows, lookups
     int mt_s, mt_q;
+    bool pair = false;                     // pair-count matrices are allocated for the wave
+    bool pair_ss = false, pair_sq = false; // which kinds besides query x support
+    int64_t pair_bytes = 0;
 };
 
 static Act alloc_act(const gm_ctx* c, Arena& ar, int64_t rows, int ld, bool transposed = true) {
@@ -363,6 +370,14 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
         }
         w.tdL = ar.get<float>(d.Ps + 1);
     }
+    w.pair_mat = nullptr;
+    w.pair_off_ss = w.pair_off_qs = w.pair_off_sq = nullptr;
+    if (d.pair) {
+        w.pair_off_ss = ar.get<int64_t>(d.Tw + 1);
+        w.pair_off_qs = ar.get<int64_t>(d.Tw + 1);
+        w.pair_off_sq = ar.get<int64_t>(d.Tw + 1);
+        w.pair_mat = ar.get<uint8_t>(d.pair_bytes + 64);
+    }
 }
 
 struct BatchBufs {
@@ -439,6 +454,17 @@ extern "C" void gm_destroy(gm_ctx* c) {
 
 extern "C" const char* gm_last_error(const gm_ctx* c) { return c ? c->err.c_str() : "null context"; }
 
+extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
+    if (!c) return GM_ERR_ARG;
+    if (!key) return fail(c, GM_ERR_ARG, "null key");
+    if (!strcmp(key, "row_path")) {
+        if (value < 0 || value > 2) return fail(c, GM_ERR_ARG, "row_path must be 0, 1 or 2");
+        c->row_path = (int)value;
+        return GM_OK;
+    }
+    return fail(c, GM_ERR_ARG, "unknown key '%s'", key);
+}
+
 extern "C" int gm_profile(gm_ctx* c, int enable) {
     if (!c) return GM_ERR_ARG;
     c->prof_on = enable != 0;
@@ -480,6 +506,17 @@ extern "C" size_t gm_workspace_bytes(const gm_model_desc* model, int32_t n_tasks
     d.nnz_s = nnz_support; d.nnz_q = nnz_query;
     d.mt_s = (int)(Ps / 64 + n_tasks + 1);  // upper bound on m-tiles
     d.mt_q = (int)(Pq / 64 + n_tasks + 1);
+    // pair-count matrices, for tasks of equal size (a batch of uneven tasks may need more and then runs in waves)
+    if (n_tasks > 0 && inner_steps > 0 && c.F > 0 && c.D % 32 == 0) {
+        const int64_t ns = (n_support + n_tasks - 1) / n_tasks, nq = (n_query + n_tasks - 1) / n_tasks;
+        if (std::max(ns, nq) > 0 && std::max(ns, nq) <= 512) {
+            const int64_t ps = (ns + 63) & ~(int64_t)63, pq = (nq + 63) & ~(int64_t)63;
+            d.pair = true;
+            d.pair_ss = inner_steps >= 2;
+            d.pair_sq = order == 2;
+            d.pair_bytes = (int64_t)n_tasks * c.F * ((d.pair_ss ? ps * ps : 0) + pq * ps * (d.pair_sq ? 2 : 1));
+        }
+    }
     alloc_wave(&c, ar, w, d, inner_steps, order);
     return ar.off + (1 << 20);
 }
@@ -836,7 +873,8 @@ struct Batch {  // host-side description of one call
     BatchBufs b;
 };
 
-static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBufs& w) {
+static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBufs& w, int* cap_out = nullptr,
+                          int* max_bag_out = nullptr) {
     hipStream_t st = c->stream;
     const int F = c->F, Tw = wp.t1 - wp.t0;
     if (F == 0 || Tw == 0) return GM_OK;
@@ -853,6 +891,8 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
     if (hs[ST_BAD_INDEX]) return fail(c, GM_ERR_INDEX, "index outside its table, or bag_offsets not monotone / beyond nnz");
     int cap = 1024;
     while (cap < (int)hs[ST_MAX_TF]) cap <<= 1;
+    if (cap_out) *cap_out = cap;
+    if (max_bag_out) *max_bag_out = (int)hs[ST_MAX_BAG];
     if (cap > tf_sort_max_cap())
         return fail(c, GM_ERR_CAPACITY, "a (task, field) has %u lookups in one set; the limit is %d", hs[ST_MAX_TF],
                     tf_sort_max_cap());
@@ -895,8 +935,46 @@ static int global_order(gm_ctx* c, const Batch& B, int64_t* emb_rows, int64_t* s
     return GM_OK;
 }
 
-static WaveDims wave_dims(const Batch& B, const WavePlan& p, int bm) {
+static inline int64_t pad64(int64_t n) { return (n + 63) & ~(int64_t)63; }
+
+// Byte offsets of every task's pair-count matrices (kind by kind, fields back to back); returns the total.
+static int64_t pair_layout(const gm_ctx* c, const Batch& B, const WavePlan& p, bool ss, bool sq, std::vector<int64_t>* off_ss,
+                           std::vector<int64_t>* off_qs, std::vector<int64_t>* off_sq) {
+    int64_t acc = 0;
+    for (int t = p.t0; t < p.t1; ++t) {
+        const int64_t ns = pad64(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t]);
+        const int64_t nq = pad64(B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]);
+        if (off_ss) off_ss->push_back(acc);
+        if (ss) acc += c->F * ns * ns;
+        if (off_qs) off_qs->push_back(acc);
+        acc += c->F * nq * ns;
+        if (off_sq) off_sq->push_back(acc);
+        if (sq) acc += c->F * ns * nq;
+    }
+    return acc;
+}
+
+// Whether the wave's row arithmetic should go through pair-count matrices: the product costs
+// n_out * n_in * D per (task, field) against lookups * D for the sparse kernel, on units that are far
+// faster, so it pays while tasks are moderately small.
+static bool pair_path_wanted(const gm_ctx* c, const Batch& B, const WavePlan& p, int K) {
+    if (c->row_path == 1 || K <= 0 || c->F == 0 || c->D % 32 != 0) return false;
+    int64_t mx = 0;
+    for (int t = p.t0; t < p.t1; ++t) {
+        mx = std::max(mx, B.sup->task_offsets[t + 1] - B.sup->task_offsets[t]);
+        mx = std::max(mx, B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]);
+    }
+    return mx > 0 && mx <= (c->row_path == 2 ? 1024 : 512);
+}
+
+static WaveDims wave_dims(const gm_ctx* c, const Batch& B, const WavePlan& p, int bm, int K, int order) {
     WaveDims d;
+    if (pair_path_wanted(c, B, p, K)) {
+        d.pair = true;
+        d.pair_ss = K >= 2;
+        d.pair_sq = order == 2;
+        d.pair_bytes = pair_layout(c, B, p, d.pair_ss, d.pair_sq, nullptr, nullptr, nullptr);
+    }
     d.Tw = p.t1 - p.t0;
     d.Ss = p.s1 - p.s0; d.Sq = p.q1 - p.q0; d.Ps = p.ps1 - p.ps0; d.Pq = p.pq1 - p.pq0;
     d.nnz_s = p.ls1 - p.ls0; d.nnz_q = p.lq1 - p.lq0;
@@ -963,7 +1041,7 @@ static int plan_waves(gm_ctx* c, Batch& B, size_t avail, int K, int order, int b
             Arena ar;
             ar.cap = avail;
             WaveBufs w;
-            alloc_wave(c, ar, w, wave_dims(B, p, bm), K, order);
+            alloc_wave(c, ar, w, wave_dims(c, B, p, bm, K, order), K, order);
             if (ar.overflow) { fits = false; break; }
             if (T == 0) break;
         }
@@ -1017,6 +1095,13 @@ static int setup_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, int bm, Wav
         (rc = upload_i32(c, w.tile_g_s, tg_s)) || (rc = upload_i32(c, w.tile_m_s, tm_s)) ||
         (rc = upload_i32(c, w.tile_g_q, tg_q)) || (rc = upload_i32(c, w.tile_m_q, tm_q)))
         return rc;
+    std::vector<int64_t> po_ss, po_qs, po_sq;
+    if (d.pair) {
+        pair_layout(c, B, wp, d.pair_ss, d.pair_sq, &po_ss, &po_qs, &po_sq);
+        HIPCHK(c, hipMemcpyAsync(w.pair_off_ss, po_ss.data(), po_ss.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+        HIPCHK(c, hipMemcpyAsync(w.pair_off_qs, po_qs.data(), po_qs.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+        HIPCHK(c, hipMemcpyAsync(w.pair_off_sq, po_sq.data(), po_sq.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    }
     launch_fill_sample_task(st, w.real_off_s, d.Tw, w.sample_task_s);
     launch_fill_sample_task(st, w.real_off_q, d.Tw, w.sample_task_q);
     launch_fill_sample_task(st, w.row_off_s, d.Tw, w.row_task_s);
@@ -1080,15 +1165,38 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         const int Tw = wp.t1 - wp.t0;
         if (Tw == 0) continue;
         WaveBufs w;
-        const WaveDims d = wave_dims(B, wp, bm);
+        const WaveDims d = wave_dims(c, B, wp, bm, K, order);
         alloc_wave(c, ar, w, d, K, order);
         if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "internal: wave does not fit");
         Grp gs, gq;
         if ((rc = setup_wave(c, B, wp, bm, w, d, gs, gq))) return rc;
 
         // a0: row dictionaries and the overlap join
-        rc = run_index_wave(c, B, wp, w);
+        int tf_cap = 0, max_bag = 0;
+        rc = run_index_wave(c, B, wp, w, &tf_cap, &max_bag);
         if (rc != GM_OK) return rc;
+        // pair-count matrices, when the wave qualifies and every count fits a byte
+        bool pair = d.pair && tf_cap <= PAIR_MAX_CAP && max_bag <= PAIR_MAX_BAG;
+        if (pair) {
+            PairCountArgs pa;
+            memset(&pa, 0, sizeof pa);
+            pa.F = F;
+            pa.real_off_s = w.real_off_s; pa.real_off_q = w.real_off_q; pa.row_off_s = w.row_off_s; pa.row_off_q = w.row_off_q;
+            pa.base_s = w.base_s; pa.base_q = w.base_q; pa.cnt_q = w.cnt_q; pa.n_slots = w.n_slots;
+            pa.slot_start = w.slot_start; pa.qseg_lo = w.qseg_lo; pa.qseg_hi = w.qseg_hi;
+            pa.sup_sorted = w.sup_sorted; pa.qry_sorted = w.qry_sorted;
+            pa.off_ss = w.pair_off_ss; pa.off_qs = w.pair_off_qs; pa.off_sq = w.pair_off_sq;
+            pa.mat = w.pair_mat; pa.want_ss = d.pair_ss; pa.want_sq = d.pair_sq; pa.status = c->d_status;
+            {
+                Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0);
+                launch_pair_count(st, pa, Tw, tf_cap);
+            }
+            u32 hs[ST_WORDS];
+            if ((rc = read_status(c, hs))) return rc;
+            if (hs[ST_PAIR_OVF]) pair = false;   // a count above 255: the sparse kernel takes the wave
+        }
+        if (c->row_path == 2 && d.pair && !pair)
+            return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a count, bag or (task, field) exceeds its limits");
         const int n_tf = Tw * F;
         const int32_t* rows_s = b.prow_s + wp.s0;
         const int32_t* rows_q = b.prow_q + wp.q0;
@@ -1147,6 +1255,31 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             return o;
         };
         auto two_hop = [&](bool in_support, const float* Z, const TwoHopOut* o0, const TwoHopOut* o1) {
+            const double bags_ = (o0 ? (double)d.Ss : 0.0) + (o1 ? (double)d.Sq : 0.0);
+            const double in_l_ = in_support ? (double)d.nnz_s : (double)d.nnz_q;
+            const double out_l_ = (o0 ? (double)d.nnz_s : 0.0) + (o1 ? (double)d.nnz_q : 0.0);
+            // algorithmic bytes: Z once per (sample, field), Y read + written per (sample, field), 4 B per lookup and hop
+            const double alg_bytes = 4.0 * D * F * (in_support ? d.Ss : d.Sq) + bags_ * F * (8.0 * D + (bf ? 2.0 * D : 0)) + 4.0 * (in_l_ + out_l_);
+            if (pair) {   // o0 is always the support side, o1 the query side
+                PairHopArgs pa;
+                memset(&pa, 0, sizeof pa);
+                pa.F = F; pa.D = D; pa.mat = w.pair_mat;
+                pa.in_real_off = in_support ? w.real_off_s : w.real_off_q;
+                pa.in_row_off = in_support ? w.row_off_s : w.row_off_q;
+                pa.Z = Z; pa.ldz = FD;
+                auto fill = [&](PairHopOut& po, const TwoHopOut& o, bool out_support) {
+                    po.enabled = 1;
+                    po.mat_off = out_support ? (in_support ? w.pair_off_ss : w.pair_off_sq) : w.pair_off_qs;
+                    po.real_off = out_support ? w.real_off_s : w.real_off_q;
+                    po.row_off = out_support ? w.row_off_s : w.row_off_q;
+                    po.y_in = o.y_in; po.y_out = o.y_out; po.y_bf = o.y_bf; po.ld = o.ld; po.c = o.c;
+                };
+                if (o0) fill(pa.out[0], *o0, true);
+                if (o1) fill(pa.out[1], *o1, false);
+                Prof p(c, "pair_hop", alg_bytes, 0);
+                launch_pair_hop(st, pa, Tw, max_bags);
+                return;
+            }
             TwoHopArgs a;
             memset(&a, 0, sizeof a);
             a.F = F; a.D = D;
@@ -1158,11 +1291,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             a.max_in_rows = max_prows;
             if (o0) a.out[0] = *o0;
             if (o1) a.out[1] = *o1;
-            const double bags = (o0 ? (double)d.Ss : 0.0) + (o1 ? (double)d.Sq : 0.0);
-            const double in_l = in_support ? (double)d.nnz_s : (double)d.nnz_q;
-            const double out_l = (o0 ? (double)d.nnz_s : 0.0) + (o1 ? (double)d.nnz_q : 0.0);
-            // algorithmic bytes: Z once per (sample, field), Y read + written per (sample, field), 4 B per lookup and hop
-            Prof p(c, "two_hop", 4.0 * D * F * (in_support ? d.Ss : d.Sq) + bags * F * (8.0 * D + (bf ? 2.0 * D : 0)) + 4.0 * (in_l + out_l), 0);
+            Prof p(c, "two_hop", alg_bytes, 0);
             launch_two_hop(st, a, Tw, max_bags);
         };
 
@@ -1404,7 +1533,7 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
         const int Tw = wp.t1 - wp.t0;
         if (Tw == 0 || F == 0) continue;
         WaveBufs w;
-        const WaveDims d = wave_dims(B, wp, 64);
+        const WaveDims d = wave_dims(c, B, wp, 64, 0, 1);
         alloc_wave(c, ar, w, d, 1, 2);
         rc = run_index_wave(c, B, wp, w);
         if (rc != GM_OK) return rc;

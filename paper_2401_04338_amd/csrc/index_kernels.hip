@@ -48,6 +48,7 @@ __global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const i
     for (int i = threadIdx.x; i < 2 * F; i += blockDim.x) sh_cnt[i] = 0;
     __syncthreads();
     bool bad = false;
+    u32 longest = 0;
     for (int set = 0; set < 2; ++set) {
         const SetView& v = set ? qry : sup;
         const int64_t nnz = set ? nnz_qry : nnz_sup;
@@ -68,6 +69,7 @@ __global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const i
                 if (r < 0 || r >= R) bad = true;
             }
             atomicAdd(&sh_cnt[set * F + f], (u32)(p1 - p0));
+            longest = max(longest, (u32)(p1 - p0));
         }
     }
     if (t == 0 && threadIdx.x == 0) {  // the ends of both offset arrays
@@ -83,6 +85,7 @@ __global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const i
         mx = max(mx, c);
     }
     if (mx) atomicMax(&status[ST_MAX_TF], mx);
+    if (longest) atomicMax(&status[ST_MAX_BAG], longest);
     if (bad) atomicOr(&status[ST_BAD_INDEX], 1u);
 }
 

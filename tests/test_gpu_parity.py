@@ -266,3 +266,61 @@ def test_meta_step_bf16_medium_shape_subset(gm):
     _compare_step(cfg, ctx, sup, qry, params, 3, 2, TOL_BF16, "bf16 medium4 K=3 order=2", operand="bf16")
     _compare_step(cfg, ctx, sup, qry, params, 3, 1, TOL_BF16, "bf16 medium4 K=3 order=1", operand="bf16")
     ctx.close()
+
+
+# ---------------------------------------------------------------- the two row-arithmetic paths
+def _row_path_ctx(gm, cfg, path, ws):
+    ctx = gm.from_config(cfg, workspace_bytes=ws)
+    ctx.configure("row_path", path)
+    return ctx
+
+
+@pytest.mark.parametrize("path", [1, 2], ids=["sparse", "pairs"])
+def test_row_paths_fp32_small_shape(gm, path):
+    """configs[1]'s shape (D=32, fp32): the sparse two-hop kernel and the pair-count matrices, each against the oracle."""
+    cfg = SMALL.with_(n_tasks=8)
+    sup, qry, params = _inputs(cfg)
+    ctx = _row_path_ctx(gm, cfg, path, 2 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, 1, 2, TOL_FP32, f"small8 path={path} K=1 order=2")
+    _compare_step(cfg, ctx, sup, qry, params, 3, 2, TOL_FP32, f"small8 path={path} K=3 order=2")
+    _compare_step(cfg, ctx, sup, qry, params, 2, 1, TOL_FP32, f"small8 path={path} K=2 order=1")
+    ctx.close()
+
+
+@pytest.mark.parametrize("path", [1, 2], ids=["sparse", "pairs"])
+def test_row_paths_ragged_sizes(gm, path):
+    """Task sizes that are no multiple of any tile (50 / 37 samples; 300 / 270 samples: several row blocks, two
+    count tiles), D=64, fp32 GEMMs so that the bar is the fp32 one."""
+    for ns, nq, nt in ((50, 37, 5), (300, 270, 3)):
+        cfg = SMALL.with_(n_tasks=nt, n_support=ns, n_query=nq, n_fields=6, emb_dim=64, rows_per_field=3000,
+                          layer_dims=(6 * 64 + 13, 64, 32, 1), inner_lr=0.05)
+        sup, qry, params = _inputs(cfg)
+        ctx = _row_path_ctx(gm, cfg, path, 2 << 30)
+        _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_FP32, f"ragged {ns}/{nq} path={path}")
+        ctx.close()
+
+
+@pytest.mark.parametrize("path", [1, 2], ids=["sparse", "pairs"])
+def test_row_paths_bf16_medium_shape(gm, path):
+    from synth import MEDIUM
+    cfg = MEDIUM.with_(n_tasks=4, rows_per_field=20000)
+    sup, qry, params = _inputs(cfg)
+    ctx = _row_path_ctx(gm, cfg, path, 3 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, 3, 2, TOL_BF16, f"bf16 medium4 path={path}", operand="bf16")
+    ctx.close()
+
+
+def test_pair_counts_above_a_byte_fall_back(gm):
+    """One row per table: every pair of bags shares all its lookups, so counts reach bag_i * bag_j > 255.  The default
+    choice must fall back to the sparse kernel (and still match the oracle); the forced pair path must refuse."""
+    from paper_2401_04338_amd.binding import GMetaError
+    cfg = SMALL.with_(n_tasks=3, n_support=40, n_query=30, n_fields=4, emb_dim=32, rows_per_field=1, bag_max=24,
+                      layer_dims=(4 * 32 + 13, 32, 16, 1), inner_lr=0.01)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_FP32, "pair overflow, auto")
+    ctx.configure("row_path", 2)
+    dev = ctx.device
+    with pytest.raises(GMetaError):
+        ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, 2, 2)
+    ctx.close()
