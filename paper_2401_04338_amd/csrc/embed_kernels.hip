@@ -7,8 +7,8 @@
 
 __device__ __forceinline__ void store_bf4(bf16_t* dst, float4 v) {
     uint2 o;
-    o.x = (u32)f2bf(v.x) | ((u32)f2bf(v.y) << 16);
-    o.y = (u32)f2bf(v.z) | ((u32)f2bf(v.w) << 16);
+    o.x = f2bf2(v.x, v.y);
+    o.y = f2bf2(v.z, v.w);
     *reinterpret_cast<uint2*>(dst) = o;
 }
 

@@ -190,8 +190,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
             if (Cf) *reinterpret_cast<float4*>(Cf + (int64_t)m * a.ldcf + n) = x;
             if (Cb) {
                 uint2 pk;
-                pk.x = (u32)f2bf(x.x) | ((u32)f2bf(x.y) << 16);
-                pk.y = (u32)f2bf(x.z) | ((u32)f2bf(x.w) << 16);
+                pk.x = f2bf2(x.x, x.y);
+                pk.y = f2bf2(x.z, x.w);
                 *reinterpret_cast<uint2*>(Cb + (int64_t)m * a.ldcb + n) = pk;
             }
             if (CbT) *reinterpret_cast<float4*>(E + rr * ELD + ec) = x;
@@ -208,10 +208,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
                         const int m = m0 + wm0 + i * 32 + r8;
                         if (m >= M) continue;     // M is a multiple of 8 on this path
                         uint4 pk;
-                        pk.x = (u32)f2bf(E[(r8 + 0) * ELD + col]) | ((u32)f2bf(E[(r8 + 1) * ELD + col]) << 16);
-                        pk.y = (u32)f2bf(E[(r8 + 2) * ELD + col]) | ((u32)f2bf(E[(r8 + 3) * ELD + col]) << 16);
-                        pk.z = (u32)f2bf(E[(r8 + 4) * ELD + col]) | ((u32)f2bf(E[(r8 + 5) * ELD + col]) << 16);
-                        pk.w = (u32)f2bf(E[(r8 + 6) * ELD + col]) | ((u32)f2bf(E[(r8 + 7) * ELD + col]) << 16);
+                        pk.x = f2bf2(E[(r8 + 0) * ELD + col], E[(r8 + 1) * ELD + col]);
+                        pk.y = f2bf2(E[(r8 + 2) * ELD + col], E[(r8 + 3) * ELD + col]);
+                        pk.z = f2bf2(E[(r8 + 4) * ELD + col], E[(r8 + 5) * ELD + col]);
+                        pk.w = f2bf2(E[(r8 + 6) * ELD + col], E[(r8 + 7) * ELD + col]);
                         *reinterpret_cast<uint4*>(CbT + (int64_t)nT * a.ldcbT + m) = pk;
                     }
                 }

@@ -10,11 +10,13 @@ typedef uint64_t u64;
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 
 #ifdef __HIPCC__
-__device__ __forceinline__ bf16_t f2bf(float x) {  // round to nearest even; NaN stays NaN
-    u32 u = __builtin_bit_cast(u32, x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// fp32 -> bf16, round to nearest even: the gfx950 conversion instruction (two values per instruction)
+__device__ __forceinline__ bf16_t f2bf(float x) { return __builtin_bit_cast(bf16_t, (__bf16)x); }
+__device__ __forceinline__ u32 f2bf2(float lo, float hi) {  // {bf16(hi), bf16(lo)}
+    typedef float gm_f2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 gm_b2 __attribute__((ext_vector_type(2)));
+    const gm_f2 v = {lo, hi};
+    return __builtin_bit_cast(u32, __builtin_convertvector(v, gm_b2));
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __builtin_bit_cast(float, (u32)h << 16); }
 #endif
@@ -115,8 +117,8 @@ void launch_two_hop(hipStream_t st, TwoHopArgs a, int n_tasks, int max_bags);
 // The same row arithmetic as a dense product: per (task, field) the pair-count matrix
 // M[i][j] = number of (lookup of out-bag i, lookup of in-bag j) pairs on one row of the task's support set,
 // stored as bytes, [pad64(n_out)][pad64(n_in)] per field, fields of a task back to back.
-#define PAIR_TILE_BYTES (136 * 1024)
-#define PAIR_MAX_CAP 8192        // lookups of one (task, field) and set that the counting kernel stages
+#define PAIR_LDS_BYTES (152 * 1024)   // LDS of the counting kernel: a tile of 16-bit cells and two dense count blocks
+#define PAIR_MAX_CAP 8192        // lookups of one (task, field) and set (the hot-row list shares the tile's LDS)
 #define PAIR_MAX_BAG 255         // longest bag for which the 16-bit counters cannot wrap
 struct PairCountArgs {
     int F;
@@ -131,7 +133,7 @@ struct PairCountArgs {
     int tile_bytes;                           // set by the launcher
     u32* status;
 };
-void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap);
+void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw);
 struct PairHopOut {
     int enabled;
     const int64_t* mat_off;                   // [Tw]

@@ -226,8 +226,8 @@ __global__ __launch_bounds__(NT) void two_hop_kernel(TwoHopArgs a) {
             if (out.y_out) *reinterpret_cast<float4*>(out.y_out + off) = y;
             if (out.y_bf) {
                 uint2 pk;
-                pk.x = (u32)f2bf(y.x) | ((u32)f2bf(y.y) << 16);
-                pk.y = (u32)f2bf(y.z) | ((u32)f2bf(y.w) << 16);
+                pk.x = f2bf2(y.x, y.y);
+                pk.y = f2bf2(y.z, y.w);
                 *reinterpret_cast<uint2*>(out.y_bf + off) = pk;
             }
         }
