@@ -152,17 +152,32 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     constexpr int LPR = SW / 4, RPI = 64 / LPR;    // lanes per strip row, rows per pass
     float* E = reinterpret_cast<float*>(smem) + wave * (32 * ELD);
     const int er = lane / LPR, ec = (lane % LPR) * 4;
+    const int n = n0 + wn0 + ec;
+    const bool nok = n < N;
+    float4 bn = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (bias && nok) bn = *reinterpret_cast<const float4*>(bias + n);
+    const bool has_mask = a.epi == EPI_BIAS_MASK || a.epi == EPI_MASK;
+    const bool has_cin = a.epi == EPI_AXPBY && Cin;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
+        // What the strip reads from memory is requested before anything of it is stored: the outputs may alias
+        // the inputs (an in-place update), which would otherwise chain every load behind the previous store.
+        uint2 mk_all[32 / RPI];
+        float4 ci_all[32 / RPI];
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int m = m0 + wm0 + i * 32 + it * RPI + er;
+            const bool ok = nok && m < M;
+            mk_all[it] = make_uint2(0u, 0u);
+            ci_all[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ok && has_mask) mk_all[it] = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
+            if (ok && has_cin) ci_all[it] = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
+        }
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) E[(8 * (v >> 2) + 4 * lhi + (v & 3)) * ELD + j * 32 + l32] = acc[i][j][v];
         __syncthreads();
-        const int n = n0 + wn0 + ec;
-        const bool nok = n < N;
-        float4 bn = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (bias && nok) bn = *reinterpret_cast<const float4*>(bias + n);
 #pragma unroll
         for (int it = 0; it < 32 / RPI; ++it) {
             const int rr = it * RPI + er;
@@ -171,8 +186,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
             float4 x = *reinterpret_cast<const float4*>(E + rr * ELD + ec);
             if (a.epi == EPI_BIAS_RELU) {
                 x = make_float4(fmaxf(x.x + bn.x, 0.f), fmaxf(x.y + bn.y, 0.f), fmaxf(x.z + bn.z, 0.f), fmaxf(x.w + bn.w, 0.f));
-            } else if (a.epi == EPI_BIAS_MASK || a.epi == EPI_MASK) {
-                const uint2 mk = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
+            } else if (has_mask) {
+                const uint2 mk = mk_all[it];
                 if (a.epi == EPI_BIAS_MASK) x = make_float4(x.x + bn.x, x.y + bn.y, x.z + bn.z, x.w + bn.w);
                 // a bf16 is positive iff it is neither zero nor has its sign bit set
                 const u32 h0 = mk.x & 0xffffu, h1 = mk.x >> 16, h2 = mk.y & 0xffffu, h3 = mk.y >> 16;
@@ -183,7 +198,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
             } else if (a.epi == EPI_AXPBY) {
                 x = make_float4(a.c1 * x.x, a.c1 * x.y, a.c1 * x.z, a.c1 * x.w);
                 if (Cin) {
-                    const float4 ci = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
+                    const float4 ci = ci_all[it];
                     x = make_float4(x.x + a.c0 * ci.x, x.y + a.c0 * ci.y, x.z + a.c0 * ci.z, x.w + a.c0 * ci.w);
                 }
             }

@@ -117,9 +117,9 @@ void launch_two_hop(hipStream_t st, TwoHopArgs a, int n_tasks, int max_bags);
 // The same row arithmetic as a dense product: per (task, field) the pair-count matrix
 // M[i][j] = number of (lookup of out-bag i, lookup of in-bag j) pairs on one row of the task's support set,
 // stored as bytes, [pad64(n_out)][pad64(n_in)] per field, fields of a task back to back.
-#define PAIR_LDS_BYTES (152 * 1024)   // LDS of the counting kernel: a tile of 16-bit cells and two dense count blocks
-#define PAIR_MAX_CAP 8192        // lookups of one (task, field) and set (the hot-row list shares the tile's LDS)
-#define PAIR_MAX_BAG 255         // longest bag for which the 16-bit counters cannot wrap
+#define PAIR_LDS_BYTES (144 * 1024)   // LDS of the counting kernel: a tile of byte cells, two dense count blocks, the lists
+#define PAIR_MAX_CAP 8192        // lookups of one (task, field) and set that the counting kernel stages
+#define PAIR_MAX_BAG 255         // longest bag for which the 16-bit counts of one row cannot wrap
 struct PairCountArgs {
     int F;
     const int32_t *real_off_s, *real_off_q;   // [Tw+1] first sample of each task (relative to the wave)
@@ -130,10 +130,10 @@ struct PairCountArgs {
     const int64_t *off_ss, *off_qs, *off_sq;  // [Tw] byte offset of the task's first matrix of each kind
     uint8_t* mat;
     int want_ss, want_sq;
-    int tile_bytes;                           // set by the launcher
+    int lds_bytes, cap;                       // set by the launcher
     u32* status;
 };
-void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw);
+void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap);
 struct PairHopOut {
     int enabled;
     const int64_t* mat_off;                   // [Tw]

@@ -1189,7 +1189,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             pa.mat = w.pair_mat; pa.want_ss = d.pair_ss; pa.want_sq = d.pair_sq; pa.status = c->d_status;
             {
                 Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0);
-                launch_pair_count(st, pa, Tw);
+                launch_pair_count(st, pa, Tw, tf_cap);
             }
             u32 hs[ST_WORDS];
             if ((rc = read_status(c, hs))) return rc;

@@ -39,9 +39,8 @@ __device__ __forceinline__ int pad64(int n) { return (n + 63) & ~63; }
 // ------------------------------------------------------------------------------------------------
 #define PC_NT 1024
 #define PC_TPW (64 / (PC_NT / 64))   // MFMA tiles per wave: at most 64 tiles per row tile
-#define PC_HB 16     // hot rows per matrix-core batch (the contraction length of one MFMA)
+#define PC_HB 32     // hot rows per matrix-core batch (two MFMA contraction steps)
 #define PC_HOT 4     // a row is hot when one of the two sets looks it up at least this often
-#define PC_CLAMP 60000.f
 
 __device__ __forceinline__ ph_short8 pc_counts_to_bf16(uint4 q) {  // eight 16-bit counts -> eight bf16 (exact up to 256)
     u32 w[4];
@@ -69,24 +68,35 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     const u32 B = a.base_s[tf], Bq = a.base_q[tf];
     const int nu = (int)a.n_slots[tf];
     const int n_in_entries = a.slot_start[B + tf + nu] - (int)B;
-    const int2* in_list = a.sup_sorted + B;                           // {row, slot}, slot-sorted
-    const int2* out_list = qs ? a.qry_sorted + Bq : a.sup_sorted + B;
-    const int in_row0 = a.row_off_s[t], out_row0 = qs ? a.row_off_q[t] : a.row_off_s[t];
-    // positions [lo, hi) of row u's lookups in the in / out list
+    const int n_out_entries = qs ? (int)a.cnt_q[tf] : n_in_entries;
+    const int2* in_list = a.sup_sorted + B;   // {row, slot}, slot-sorted
+    // positions [lo, hi) of row u's lookups in the slot-sorted in / out list
     auto in_seg = [&](int u, int& lo, int& hi) { lo = a.slot_start[B + tf + u] - (int)B; hi = a.slot_start[B + tf + u + 1] - (int)B; };
     auto out_seg = [&](int u, int& lo, int& hi) {
         if (qs) { lo = a.qseg_lo[B + u] - (int)Bq; hi = a.qseg_hi[B + u] - (int)Bq; }
         else in_seg(u, lo, hi);
     };
-    // LDS: tile of R out-rows, 16-bit cells, row stride colsP + 2 (an odd number of words); then the two dense
-    // count blocks of a batch, [R][16] and [colsP][16] 16-bit counts.  At most 64 MFMA tiles per row tile.
-    const int lds_ld = colsP + 2;
-    int R = rowsP;
-    while (R > 32 && ((size_t)R * lds_ld * 2 + (size_t)(R + colsP) * PC_HB * 2 > (size_t)a.tile_bytes || R * colsP > 65536)) R -= 32;
-    uint16_t* tile = reinterpret_cast<uint16_t*>(pc_lds);
-    u32* c_out = pc_lds + (R * lds_ld) / 2;            // R * lds_ld * 2 bytes is a multiple of 16
-    u32* c_in = c_out + R * PC_HB / 2;
-    u32* hot_list = pc_lds;                            // lives in the tile area until the hot part is stored
+    // LDS, from the end: the bag of every in / out lookup (16 bits each, slot-sorted) and the list of hot rows
+    // (a hot row has >= PC_HOT lookups in one set: at most cap / 2 of them).  From the start: the tile of R
+    // out-rows, TRANSPOSED, one byte per cell: cell (i, j) at j * ldT + i with ldT = R + 4 (an odd number of
+    // words: the MFMA result, the transposed read-out and the atomics all spread over the banks); then the
+    // two dense count blocks of a batch, [R][PC_HB] and [colsP][PC_HB] 16-bit counts.
+    uint16_t* in_rows = reinterpret_cast<uint16_t*>(pc_lds) + (a.lds_bytes / 2 - 2 * a.cap);
+    uint16_t* out_rows = in_rows + a.cap;
+    u32* hot_list = reinterpret_cast<u32*>(in_rows) - a.cap / 2;
+    {
+        const int2* out_list = qs ? a.qry_sorted + Bq : a.sup_sorted + B;
+        const int in_row0 = a.row_off_s[t], out_row0 = qs ? a.row_off_q[t] : a.row_off_s[t];
+        for (int e = threadIdx.x; e < n_in_entries; e += PC_NT) in_rows[e] = (uint16_t)(in_list[e].x - in_row0);
+        for (int e = threadIdx.x; e < n_out_entries; e += PC_NT) out_rows[e] = (uint16_t)(out_list[e].x - out_row0);
+    }
+    const size_t budget = (size_t)a.lds_bytes - 6 * (size_t)a.cap;
+    int R = rowsP;   // at most 64 MFMA tiles per row tile
+    while (R > 32 && ((size_t)colsP * (R + 4) + (size_t)(R + colsP) * PC_HB * 2 > budget || R * colsP > 65536)) R -= 32;
+    const int ldT = R + 4;
+    uint8_t* tile = reinterpret_cast<uint8_t*>(pc_lds);
+    uint16_t* c_out = reinterpret_cast<uint16_t*>(tile + (size_t)colsP * ldT);   // colsP * ldT is a multiple of 16
+    uint16_t* c_in = c_out + R * PC_HB;
     uint8_t* M = a.mat + (qs ? a.off_qs[t] : a.off_ss[t]) + (size_t)f * rowsP * colsP;
     uint8_t* Mt = (qs && a.want_sq) ? a.mat + a.off_sq[t] + (size_t)f * colsP * rowsP : nullptr;  // [colsP rows][rowsP cols]
     const int tiles_c = colsP / 32;
@@ -96,7 +106,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
         const int n_tiles = (rows_here / 32) * tiles_c;
         // ---- the hot rows of this (task, field)
         if (threadIdx.x == 0) sh_nhot = 0;
-        __syncthreads();
+        __syncthreads();   // also: the lists are staged, the previous tile has been read out
         for (int u = threadIdx.x; u < nu; u += PC_NT) {
             int lo, hi, lo2, hi2;
             in_seg(u, lo, hi);
@@ -105,6 +115,13 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
         }
         __syncthreads();
         const int nhot = sh_nhot;
+        int my_tr[PC_TPW], my_tc[PC_TPW];
+#pragma unroll
+        for (int q = 0; q < PC_TPW; ++q) {
+            const int tt = wv * PC_TPW + q;
+            my_tr[q] = tt < n_tiles ? tt / tiles_c : -1;
+            my_tc[q] = tt - (tt / tiles_c) * tiles_c;
+        }
         ph_float16 acc[PC_TPW];
 #pragma unroll
         for (int q = 0; q < PC_TPW; ++q)
@@ -119,85 +136,86 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
                 const u32 inc = 1u << (16 * (hx & 1));
                 int lo, hi;
                 in_seg(u, lo, hi);
-                for (int e = lo + lane; e < hi; e += 64) {
-                    const int j = in_list[e].x - in_row0;
-                    atomicAdd(&c_in[(j * PC_HB + hx) >> 1], inc);
-                }
+                for (int e = lo + lane; e < hi; e += 64)
+                    atomicAdd(reinterpret_cast<u32*>(c_in) + (((int)in_rows[e] * PC_HB + hx) >> 1), inc);
                 out_seg(u, lo, hi);
                 for (int e = lo + lane; e < hi; e += 64) {
-                    const int i = out_list[e].x - out_row0 - i0;
-                    if ((unsigned)i < (unsigned)rows_here) atomicAdd(&c_out[(i * PC_HB + hx) >> 1], inc);
+                    const int i = (int)out_rows[e] - i0;
+                    if ((unsigned)i < (unsigned)rows_here) atomicAdd(reinterpret_cast<u32*>(c_out) + ((i * PC_HB + hx) >> 1), inc);
                 }
             }
             __syncthreads();
 #pragma unroll
             for (int q = 0; q < PC_TPW; ++q) {
-                const int tt = wv * PC_TPW + q;
-                if (tt < n_tiles) {
-                    const int tr = tt / tiles_c, tc = tt - tr * tiles_c;
-                    const uint4 qa = *reinterpret_cast<const uint4*>(c_out + ((tr * 32 + ln) * PC_HB + h * 8) / 2);
-                    const uint4 qb = *reinterpret_cast<const uint4*>(c_in + ((tc * 32 + ln) * PC_HB + h * 8) / 2);
-                    acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pc_counts_to_bf16(qa), pc_counts_to_bf16(qb), acc[q], 0, 0, 0);
+                if (my_tr[q] >= 0) {
+#pragma unroll
+                    for (int ks = 0; ks < PC_HB / 16; ++ks) {
+                        const uint4 qa = *reinterpret_cast<const uint4*>(c_out + (my_tr[q] * 32 + ln) * PC_HB + ks * 16 + h * 8);
+                        const uint4 qb = *reinterpret_cast<const uint4*>(c_in + (my_tc[q] * 32 + ln) * PC_HB + ks * 16 + h * 8);
+                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pc_counts_to_bf16(qa), pc_counts_to_bf16(qb), acc[q], 0, 0, 0);
+                    }
                 }
             }
             __syncthreads();
         }
-        // ---- the hot part becomes the tile's initial content (every cell of the tile's rows is written)
+        // ---- the hot part becomes the tile's initial content (every cell of the tile's rows is written); a lane
+        //      holds four consecutive rows of one column: one word of the transposed tile.  255 stands for
+        //      "255 or more" and is reported when the tile is read out.
 #pragma unroll
         for (int q = 0; q < PC_TPW; ++q) {
-            const int tt = wv * PC_TPW + q;
-            if (tt < n_tiles) {
-                const int tr = tt / tiles_c, tc = tt - tr * tiles_c;
+            if (my_tr[q] >= 0) {
+                uint8_t* col = tile + (size_t)(my_tc[q] * 32 + ln) * ldT + my_tr[q] * 32 + 4 * h;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int i = tr * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                    tile[i * lds_ld + tc * 32 + ln] = (uint16_t)fminf(acc[q][v], PC_CLAMP);
+                for (int g = 0; g < 4; ++g) {
+                    const u32 b0 = (u32)fminf(acc[q][4 * g + 0], 255.f), b1 = (u32)fminf(acc[q][4 * g + 1], 255.f);
+                    const u32 b2 = (u32)fminf(acc[q][4 * g + 2], 255.f), b3 = (u32)fminf(acc[q][4 * g + 3], 255.f);
+                    *reinterpret_cast<u32*>(col + 8 * g) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
                 }
             }
         }
         __syncthreads();
-        // ---- the other rows, pair by pair (a lookup of the in-set walks the row's few lookups of the out-set)
+        // ---- the other rows, pair by pair (a lookup of the in-set walks the row's few lookups of the out-set);
+        //      a cell that was at 254 or more before an increment may have wrapped: reported
         for (int p = threadIdx.x; p < n_in_entries; p += PC_NT) {
-            const int2 e = in_list[p];
-            const int u = e.y, j = e.x - in_row0;
+            const int u = in_list[p].y, j = (int)in_rows[p];
             int lo, hi, lo2, hi2;
             in_seg(u, lo, hi);
             out_seg(u, lo2, hi2);
             if (hi - lo >= PC_HOT || hi2 - lo2 >= PC_HOT) continue;
-            const u32 inc = 1u << (16 * (j & 1));
             for (int x = lo2; x < hi2; ++x) {
-                const int i = out_list[x].x - out_row0 - i0;
-                if ((unsigned)i < (unsigned)rows_here) atomicAdd(&pc_lds[(i * lds_ld + j) >> 1], inc);
+                const int i = (int)out_rows[x] - i0;
+                if ((unsigned)i < (unsigned)rows_here) {
+                    const int sh = 8 * (i & 3);
+                    const u32 old = atomicAdd(&pc_lds[(j * ldT + i) >> 2], 1u << sh);
+                    ovf |= ((old >> sh) & 0xFFu) >= 254u;
+                }
             }
         }
         __syncthreads();
-        // ---- rows [i0, i0 + rows_here) of M, four counts per store
+        // ---- rows [i0, i0 + rows_here) of M: a thread gathers four consecutive columns of one row
         const int wpr = colsP / 4;
         for (int w = threadIdx.x; w < rows_here * wpr; w += PC_NT) {
             const int i = w / wpr, j4 = (w - i * wpr) * 4;
-            const u32 lo2 = *reinterpret_cast<const u32*>(tile + i * lds_ld + j4);
-            const u32 hi2 = *reinterpret_cast<const u32*>(tile + i * lds_ld + j4 + 2);
-            const u32 c0 = lo2 & 0xFFFFu, c1 = lo2 >> 16, c2 = hi2 & 0xFFFFu, c3 = hi2 >> 16;
-            ovf |= (c0 | c1 | c2 | c3) > 255u;
+            const u32 c0 = tile[(j4 + 0) * ldT + i], c1 = tile[(j4 + 1) * ldT + i];
+            const u32 c2 = tile[(j4 + 2) * ldT + i], c3 = tile[(j4 + 3) * ldT + i];
+            ovf |= (c0 == 255u) | (c1 == 255u) | (c2 == 255u) | (c3 == 255u);
             *reinterpret_cast<u32*>(M + (size_t)(i0 + i) * colsP + j4) = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
         }
-        if (Mt) {  // the transpose: row j of it holds columns [i0, i0 + rows_here)
+        if (Mt) {  // the transpose is the tile as it lies: row j holds columns [i0, i0 + rows_here)
             const int gpr = rows_here / 4;
             for (int w = threadIdx.x; w < colsP * gpr; w += PC_NT) {
                 const int j = w / gpr, i4 = (w - j * gpr) * 4;
-                const u32 c0 = tile[(i4 + 0) * lds_ld + j], c1 = tile[(i4 + 1) * lds_ld + j];
-                const u32 c2 = tile[(i4 + 2) * lds_ld + j], c3 = tile[(i4 + 3) * lds_ld + j];
-                *reinterpret_cast<u32*>(Mt + (size_t)j * rowsP + i0 + i4) = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+                *reinterpret_cast<u32*>(Mt + (size_t)j * rowsP + i0 + i4) = *reinterpret_cast<const u32*>(tile + j * ldT + i4);
             }
         }
-        __syncthreads();
     }
     if (ovf) a.status[ST_PAIR_OVF] = 1u;
 }
 
-void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw) {
+void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap) {
     if (Tw <= 0 || a.F <= 0) return;
-    a.tile_bytes = PAIR_LDS_BYTES;
+    a.lds_bytes = PAIR_LDS_BYTES;
+    a.cap = cap;
     (void)hipFuncSetAttribute((const void*)pair_count_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, PAIR_LDS_BYTES);
     hipLaunchKernelGGL(pair_count_kernel, dim3(a.F, Tw, 2), dim3(PC_NT), PAIR_LDS_BYTES, st, a);
 }
@@ -231,11 +249,11 @@ __device__ __forceinline__ void ph_cvt4(u32 x, u32& lo, u32& hi) {
 __device__ __forceinline__ int ph_key(int col) { return ((col >> 1) + (col >> 4)) & 7; }
 
 template <int DS>
-__global__ __launch_bounds__(256) void pair_hop_kernel(PairHopArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void pair_hop_kernel(PairHopArgs a) {
     constexpr int NCT = DS / 32;      // 32-column tiles
     constexpr int CG = DS / 4;        // float4 column groups of a row of Z
     constexpr int RPT = CG / 4;       // rows of the 64-row chunk staged per thread (256 threads)
-    __shared__ __attribute__((aligned(16))) bf16_t zs[3 * DS * PH_KC];
+    __shared__ __attribute__((aligned(16))) bf16_t zs[2 * 3 * DS * PH_KC];
     const int nsl = a.D / DS;
     const int f = blockIdx.x / nsl, sl = blockIdx.x - f * nsl, t = blockIdx.y;
     const int o = blockIdx.z / a.row_blocks, rb = blockIdx.z - o * a.row_blocks;
@@ -276,9 +294,9 @@ __global__ __launch_bounds__(256) void pair_hop_kernel(PairHopArgs a) {
     uint4 araw[2][2], anext[2][2];
     auto load_z = [&](int kc) {
 #pragma unroll
-        for (int r = 0; r < RPT; ++r) {
+        for (int r = 0; r < RPT; ++r) {   // branch-free: a row beyond the task reads the task's last row and is zeroed
             const int row = kc + rg * RPT + r;
-            z[r] = row < n_in ? *reinterpret_cast<const float4*>(Zt + (int64_t)row * a.ldz) : make_float4(0.f, 0.f, 0.f, 0.f);
+            z[r] = *reinterpret_cast<const float4*>(Zt + (int64_t)min(row, n_in - 1) * a.ldz);
         }
     };
     auto load_a = [&](int kc, uint4 (&dst)[2][2]) {
@@ -289,47 +307,53 @@ __global__ __launch_bounds__(256) void pair_hop_kernel(PairHopArgs a) {
             dst[s][1] = src[1];
         }
     };
+    // splits the staged rows into their three bf16 pieces and writes them into one LDS buffer
+    auto stage = [&](bf16_t* buf, int kc) {
+        u32 p0[4][RPT], p1[4][RPT], p2[4][RPT];  // [column][row]: the three pieces as fp32 bit patterns
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) {
+            const float keep = kc + rg * RPT + r < n_in ? 1.f : 0.f;
+            const float zz[4] = {z[r].x * keep, z[r].y * keep, z[r].z * keep, z[r].w * keep};
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                const u32 u0 = __builtin_bit_cast(u32, zz[cc]);
+                const float r1 = zz[cc] - __builtin_bit_cast(float, u0 & 0xFFFF0000u);
+                const u32 u1 = __builtin_bit_cast(u32, r1);
+                const float r2 = r1 - __builtin_bit_cast(float, u1 & 0xFFFF0000u);
+                p0[cc][r] = u0; p1[cc][r] = u1; p2[cc][r] = __builtin_bit_cast(u32, r2);
+            }
+        }
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            bf16_t* d0 = buf + wr_off[cc];
+            bf16_t* d1 = d0 + DS * PH_KC;
+            bf16_t* d2 = d1 + DS * PH_KC;
+            if constexpr (RPT == 4) {
+                *reinterpret_cast<uint2*>(d0) = make_uint2(ph_pack_hi(p0[cc][0], p0[cc][1]), ph_pack_hi(p0[cc][2], p0[cc][3]));
+                *reinterpret_cast<uint2*>(d1) = make_uint2(ph_pack_hi(p1[cc][0], p1[cc][1]), ph_pack_hi(p1[cc][2], p1[cc][3]));
+                *reinterpret_cast<uint2*>(d2) = make_uint2(ph_pack_hi(p2[cc][0], p2[cc][1]), ph_pack_hi(p2[cc][2], p2[cc][3]));
+            } else {
+                *reinterpret_cast<u32*>(d0) = ph_pack_hi(p0[cc][0], p0[cc][1]);
+                *reinterpret_cast<u32*>(d1) = ph_pack_hi(p1[cc][0], p1[cc][1]);
+                *reinterpret_cast<u32*>(d2) = ph_pack_hi(p2[cc][0], p2[cc][1]);
+            }
+        }
+    };
+    // Two LDS buffers: while chunk c is multiplied out of one, chunk c+1 (loaded during the multiplication) is
+    // split into the other; one barrier per chunk.
     if (colsP > 0) {
         load_z(0);
         load_a(0, araw);
+        stage(zs, 0);
     }
+    __syncthreads();
+    int cur = 0;
     for (int kc = 0; kc < colsP; kc += PH_KC) {
-        __syncthreads();  // the previous chunk's fragments have been read
-        {
-            u32 p0[4][RPT], p1[4][RPT], p2[4][RPT];  // [column][row]: the three pieces as fp32 bit patterns
-#pragma unroll
-            for (int r = 0; r < RPT; ++r) {
-                const float zz[4] = {z[r].x, z[r].y, z[r].z, z[r].w};
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    const u32 u0 = __builtin_bit_cast(u32, zz[cc]);
-                    const float r1 = zz[cc] - __builtin_bit_cast(float, u0 & 0xFFFF0000u);
-                    const u32 u1 = __builtin_bit_cast(u32, r1);
-                    const float r2 = r1 - __builtin_bit_cast(float, u1 & 0xFFFF0000u);
-                    p0[cc][r] = u0; p1[cc][r] = u1; p2[cc][r] = __builtin_bit_cast(u32, r2);
-                }
-            }
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-                bf16_t* d0 = zs + wr_off[cc];
-                bf16_t* d1 = d0 + DS * PH_KC;
-                bf16_t* d2 = d1 + DS * PH_KC;
-                if constexpr (RPT == 4) {
-                    *reinterpret_cast<uint2*>(d0) = make_uint2(ph_pack_hi(p0[cc][0], p0[cc][1]), ph_pack_hi(p0[cc][2], p0[cc][3]));
-                    *reinterpret_cast<uint2*>(d1) = make_uint2(ph_pack_hi(p1[cc][0], p1[cc][1]), ph_pack_hi(p1[cc][2], p1[cc][3]));
-                    *reinterpret_cast<uint2*>(d2) = make_uint2(ph_pack_hi(p2[cc][0], p2[cc][1]), ph_pack_hi(p2[cc][2], p2[cc][3]));
-                } else {
-                    *reinterpret_cast<u32*>(d0) = ph_pack_hi(p0[cc][0], p0[cc][1]);
-                    *reinterpret_cast<u32*>(d1) = ph_pack_hi(p1[cc][0], p1[cc][1]);
-                    *reinterpret_cast<u32*>(d2) = ph_pack_hi(p2[cc][0], p2[cc][1]);
-                }
-            }
-        }
-        __syncthreads();
-        // the next chunk's loads fly while this one is multiplied (the last chunk loads itself again)
-        const int kn = kc + PH_KC < colsP ? kc + PH_KC : kc;
+        const int kn = kc + PH_KC < colsP ? kc + PH_KC : kc;   // the last chunk loads itself again: no branches
         load_z(kn);
         load_a(kn, anext);
+        __builtin_amdgcn_sched_barrier(0);   // the loads above are consumed only after the multiplication below
+        const bf16_t* zb = zs + cur * (3 * DS * PH_KC);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             ph_short8 af[2];
@@ -343,20 +367,27 @@ __global__ __launch_bounds__(256) void pair_hop_kernel(PairHopArgs a) {
                 const uint4 packed = make_uint4(w0, w1, w2, w3);
                 af[s] = __builtin_bit_cast(ph_short8, packed);
             }
+            ph_short8 bfrag[NCT][3];
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
-                const bf16_t* src = zs + (ct * 32 + ln) * PH_KC + (((h * 4 + ks) ^ rd_key[ct]) << 3);
+                const bf16_t* src = zb + (ct * 32 + ln) * PH_KC + (((h * 4 + ks) ^ rd_key[ct]) << 3);
 #pragma unroll
-                for (int sp = 2; sp >= 0; --sp) {  // smallest pieces first
-                    const ph_short8 bfrag = *reinterpret_cast<const ph_short8*>(src + sp * DS * PH_KC);
+                for (int sp = 0; sp < 3; ++sp) bfrag[ct][sp] = *reinterpret_cast<const ph_short8*>(src + sp * DS * PH_KC);
+            }
+#pragma unroll
+            for (int sp = 2; sp >= 0; --sp)  // smallest pieces first
+#pragma unroll
+                for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
                     for (int s = 0; s < 2; ++s)
-                        acc[s][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s], bfrag, acc[s][ct], 0, 0, 0);
-                }
-            }
+                        acc[s][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s], bfrag[ct][sp], acc[s][ct], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        cur ^= 1;
+        stage(zs + cur * (3 * DS * PH_KC), kn);
 #pragma unroll
         for (int s = 0; s < 2; ++s) { araw[s][0] = anext[s][0]; araw[s][1] = anext[s][1]; }
+        __syncthreads();
     }
     if (!wave_on) return;
     // D layout of the 32x32 tile: register v of lane (ln, h) is row 8*(v/4) + 4*h + v%4, column ln
@@ -366,16 +397,23 @@ __global__ __launch_bounds__(256) void pair_hop_kernel(PairHopArgs a) {
     bf16_t* ybf = out.y_bf ? out.y_bf + base : nullptr;
     const int ldo = (int)out.ld;
     const float cc = out.c;
+    // y_in may be y_out: the loads of a 32x32 tile are issued together, ahead of its stores
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rl = s * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (row_w + rl >= n_out) continue;
+        for (int ct = 0; ct < NCT; ++ct) {
+            float yv[16];
 #pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) {
+            for (int v = 0; v < 16; ++v) {
+                const int rl = s * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                yv[v] = (yin && row_w + rl < n_out) ? yin[rl * ldo + ct * 32] : 0.f;
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rl = s * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (row_w + rl >= n_out) continue;
                 const int idx = rl * ldo + ct * 32;
-                const float y = (yin ? yin[idx] : 0.f) + cc * acc[s][ct][v];
+                const float y = yv[v] + cc * acc[s][ct][v];
                 if (yout) yout[idx] = y;
                 if (ybf) ybf[idx] = f2bf(y);
             }
