@@ -123,25 +123,90 @@ __device__ __forceinline__ void stf(bf16_t* p, int64_t i, float v) { p[i] = f2bf
 
 // ------------------------------------------------------------------------------------------------
 // per-task column sums (bias gradients, last-layer weight gradient, per-task mean loss)
-// out[g,n] = c0*in[g,n] + c1 * sum_{s in g} ( X1[s,n]*w1[s] + X2[s,n]*w2[s] ), rows summed in order
+// out[g,n] = c0*in[g,n] + c1 * sum_{s in g} ( X1[s,n]*w1[s] + X2[s,n]*w2[s] ), rows summed in a fixed order
 // ------------------------------------------------------------------------------------------------
+// One workgroup of 4 waves per (task, block of columns): a lane owns 16 bytes of columns (8 bf16 or 4 fp32), the
+// waves take the task's rows round-robin in batches of 8 independent loads, and the four partial sums are
+// added in wave order.  The partition depends only on the shapes: results are reproducible.
 template <typename T>
-__global__ void task_colsum_kernel(const int32_t* __restrict__ row_offsets, int N, const T* __restrict__ X1,
-                                   const float* __restrict__ w1, const T* __restrict__ X2,
-                                   const float* __restrict__ w2, int64_t ldx, float* out, int64_t g_out,
-                                   const float* in, int64_t g_in, float c0, float c1) {
-    const int g = blockIdx.y;
-    const int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= N) return;
-    const int64_t r0 = row_offsets[g], r1 = row_offsets[g + 1];
-    float acc = 0.f;
-    for (int64_t s = r0; s < r1; ++s) {
-        float v = ldf(X1, s * ldx + n) * (w1 ? w1[s] : 1.f);
-        if (X2) v += ldf(X2, s * ldx + n) * (w2 ? w2[s] : 1.f);
-        acc += v;
+struct ColVec;
+template <>
+struct ColVec<float> {
+    static constexpr int N = 4;
+    __device__ static void load(const float* p, float (&v)[4]) {
+        const float4 x = *reinterpret_cast<const float4*>(p);
+        v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
     }
-    const float o = c1 * acc + (in ? c0 * in[(int64_t)g * g_in + n] : 0.f);
-    out[(int64_t)g * g_out + n] = o;
+};
+template <>
+struct ColVec<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static void load(const bf16_t* p, float (&v)[8]) {
+        const uint4 x = *reinterpret_cast<const uint4*>(p);
+        const u32 w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[2 * k] = __builtin_bit_cast(float, w[k] << 16);
+            v[2 * k + 1] = __builtin_bit_cast(float, w[k] & 0xFFFF0000u);
+        }
+    }
+};
+
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void task_colsum_kernel(const int32_t* __restrict__ row_offsets, int N,
+                                                          const T* __restrict__ X1, const float* __restrict__ w1,
+                                                          const T* __restrict__ X2, const float* __restrict__ w2,
+                                                          int64_t ldx, float* out, int64_t g_out, const float* in,
+                                                          int64_t g_in, float c0, float c1) {
+    constexpr int V = VEC ? ColVec<T>::N : 1;
+    __shared__ float part[3][64 * V];
+    const int g = blockIdx.y;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int n = (blockIdx.x * 64 + lane) * V;
+    const int64_t r0 = row_offsets[g], r1 = row_offsets[g + 1];
+    float acc[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) acc[k] = 0.f;
+    if (n < N) {
+        constexpr int UB = 8;
+        for (int64_t s0 = r0 + wv * UB; s0 < r1; s0 += 4 * UB) {
+            float x1[UB][V], x2[UB][V], f1[UB], f2[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int64_t s = s0 + u;
+                const bool ok = s < r1;
+                const int64_t sc = ok ? s : r0;
+                if constexpr (VEC) ColVec<T>::load(X1 + sc * ldx + n, x1[u]);
+                else x1[u][0] = ldf(X1, sc * ldx + n);
+                f1[u] = ok ? (w1 ? w1[sc] : 1.f) : 0.f;
+                if (X2) {
+                    if constexpr (VEC) ColVec<T>::load(X2 + sc * ldx + n, x2[u]);
+                    else x2[u][0] = ldf(X2, sc * ldx + n);
+                    f2[u] = ok ? (w2 ? w2[sc] : 1.f) : 0.f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+#pragma unroll
+                for (int k = 0; k < V; ++k) {
+                    float v = x1[u][k] * f1[u];
+                    if (X2) v += x2[u][k] * f2[u];
+                    acc[k] += v;
+                }
+        }
+    }
+    if (wv > 0) {
+#pragma unroll
+        for (int k = 0; k < V; ++k) part[wv - 1][lane * V + k] = acc[k];
+    }
+    __syncthreads();
+    if (wv == 0 && n < N) {
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const float sum = ((acc[k] + part[0][lane * V + k]) + part[1][lane * V + k]) + part[2][lane * V + k];
+            if (n + k < N) out[(int64_t)g * g_out + n + k] = c1 * sum + (in ? c0 * in[(int64_t)g * g_in + n + k] : 0.f);
+        }
+    }
 }
 
 template <typename T>
@@ -149,12 +214,20 @@ static void task_colsum_t(hipStream_t st, int G, const int32_t* row_offsets, int
                           const T* X2, const float* w2, int64_t ldx, float* out, int64_t g_out, const float* in,
                           int64_t g_in, float c0, float c1) {
     if (G <= 0 || N <= 0) return;
-    const int nt = N >= 256 ? 256 : 64;
+    // 16-byte loads need aligned rows and whole vectors inside the row
+    constexpr int V = ColVec<T>::N;
+    const bool vec = N >= 64 && ldx % V == 0 && (reinterpret_cast<uintptr_t>(X1) % 16 == 0) &&
+                     (!X2 || reinterpret_cast<uintptr_t>(X2) % 16 == 0) && ((N + V - 1) / V * V <= ldx);
+    const int cols = 64 * (vec ? V : 1);
     for (int g0 = 0; g0 < G; g0 += 32768) {
         const int gc = (G - g0) < 32768 ? (G - g0) : 32768;
-        hipLaunchKernelGGL(task_colsum_kernel<T>, dim3((N + nt - 1) / nt, gc), dim3(nt), 0, st, row_offsets + g0, N, X1,
-                           w1, X2, w2, ldx, out + (int64_t)g0 * g_out, g_out, in ? in + (int64_t)g0 * g_in : nullptr,
-                           g_in, c0, c1);
+        const dim3 grid((N + cols - 1) / cols, gc);
+        if (vec)
+            hipLaunchKernelGGL((task_colsum_kernel<T, true>), grid, dim3(256), 0, st, row_offsets + g0, N, X1, w1, X2, w2, ldx,
+                               out + (int64_t)g0 * g_out, g_out, in ? in + (int64_t)g0 * g_in : nullptr, g_in, c0, c1);
+        else
+            hipLaunchKernelGGL((task_colsum_kernel<T, false>), grid, dim3(256), 0, st, row_offsets + g0, N, X1, w1, X2, w2, ldx,
+                               out + (int64_t)g0 * g_out, g_out, in ? in + (int64_t)g0 * g_in : nullptr, g_in, c0, c1);
     }
 }
 void launch_task_colsum(hipStream_t st, int G, const int32_t* row_offsets, int N, const float* X1, const float* w1,
