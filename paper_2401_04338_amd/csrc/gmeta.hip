@@ -578,7 +578,14 @@ static void transpose_act(gm_ctx* c, const Act& a, int64_t rows) {
 static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, const Theta* th0, const Act* in1,
                      const Theta* th1, const float* bias, int64_t bias_stride, const Act* mask, int epi, Act& out) {
     const int K = c->ld[l - 1], N = c->ld[l];
-    Prof p(c, "gemm_fwd", 0, 2.0 * g.rows * N * K * np);
+    // algorithmic bytes: operands once (per-task weights once per task), every output once
+    const double esz = c->mlp_dtype ? 2.0 : 4.0;
+    double by = (double)g.rows * N * esz * ((c->mlp_dtype && out.bT) ? 2 : 1) + (mask ? (double)g.rows * N * esz : 0.0);
+    for (int i = 0; i < np; ++i) {
+        const Theta* t = i ? th1 : th0;
+        by += (double)g.rows * K * esz + (double)((c->mlp_dtype ? t->sb : t->sf) ? g.G : 1) * K * N * esz;
+    }
+    Prof p(c, "gemm_fwd", by, 2.0 * g.rows * N * K * np);
     const Act* ins[2] = {in0, in1};
     const Theta* ths[2] = {th0, th1};
     if (c->mlp_dtype == 0) {
@@ -616,7 +623,14 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
                      const Theta* th1, const Act* mask, Act* out, float* dX) {
     const int K = c->ld[l], N = dX ? c->FD : c->ld[l - 1];
     if (N <= 0) return;
-    Prof p(c, "gemm_bwd", 0, 2.0 * g.rows * N * K * np);
+    const double esz = c->mlp_dtype ? 2.0 : 4.0;
+    double by = dX ? (double)g.rows * N * 4.0 : (double)g.rows * N * esz * ((c->mlp_dtype && out && out->bT) ? 2 : 1);
+    if (mask) by += (double)g.rows * N * esz;
+    for (int i = 0; i < np; ++i) {
+        const Theta* t = i ? th1 : th0;
+        by += (double)g.rows * K * esz + (double)((c->mlp_dtype ? t->sb : t->sf) ? g.G : 1) * K * N * esz;
+    }
+    Prof p(c, "gemm_bwd", by, 2.0 * g.rows * N * K * np);
     const Act* ds[2] = {d0, d1};
     const Theta* ths[2] = {th0, th1};
     if (c->mlp_dtype == 0) {
@@ -658,7 +672,10 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
     const Act* as[2] = {a0, a1};
     const Act* ds[2] = {d0, d1};
     {
-        Prof p(c, "gemm_wgrad", 0, 2.0 * g.rows * N * M * np);
+        const double esz = c->mlp_dtype ? 2.0 : 4.0;
+        const double out_b = c->mlp_dtype ? ((write_f32 || !out.b) ? 4.0 : 0.0) + (out.b ? 4.0 : 0.0) : 4.0;
+        const double by = (double)np * g.rows * (M + N) * esz + (double)g.G * M * N * (out_b + ((in && in_stride) ? 4.0 : 0.0));
+        Prof p(c, "gemm_wgrad", by, 2.0 * g.rows * N * M * np);
         if (c->mlp_dtype == 0) {
             GemmArgs a;
             memset(&a, 0, sizeof a);
