@@ -32,8 +32,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="c3_medium", help="c1_tiny | c2_small | c3_medium | c4_coldstart")
+    ap.add_argument("--config", default="c3_medium", help="c1_tiny | c2_small | c3_medium | c4_coldstart | c5_large (with --tasks)")
     ap.add_argument("--order", type=int, default=None)
+    ap.add_argument("--tasks", type=int, default=None,
+                    help="run only the first N tasks of the config (same per-task data; a share of a config too large for one call)")
     ap.add_argument("--workspace-gib", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -51,7 +53,12 @@ def main():
     from synth import CONFIGS, make_batch, make_params
     from paper_2401_04338_amd import GMeta
 
-    cfg = CONFIGS[args.config]
+    cfg = cfg_gen = CONFIGS[args.config]
+    task_ids = None
+    if args.tasks is not None and args.tasks < cfg.n_tasks:
+        # inputs are generated from the full config's streams, so the share holds exactly the full batch's values
+        task_ids = list(range(args.tasks))
+        cfg = cfg.with_(n_tasks=args.tasks, name=f"{cfg.name}[first {args.tasks} of {cfg.n_tasks} tasks]")
     order = cfg.order if args.order is None else args.order
     K = cfg.inner_steps
     dev = torch.device("cuda", 0)
@@ -59,7 +66,7 @@ def main():
 
     t0 = time.time()
     params = make_params(cfg, dev)
-    batches = [make_batch(cfg, it, dev) for it in range(max(1, args.batches))]
+    batches = [make_batch(cfg_gen, it, dev, task_ids) for it in range(max(1, args.batches))]
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     sup0, qry0 = batches[0]
@@ -155,7 +162,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, K, order, args.cpu_seconds, params.numpy())
+        cpu = cpu_baseline(cfg, cfg_gen, K, order, args.cpu_seconds, params.numpy())
 
     line = {
         "metric": "meta-train samples/sec (support+query) on 1 GPU", "value": value, "unit": "samples/s",
@@ -187,7 +194,7 @@ def measured_traffic(workload, family):
         return None
 
 
-def cpu_baseline(cfg, K, order, budget_s, params):
+def cpu_baseline(cfg, cfg_gen, K, order, budget_s, params):
     """The CPU oracle, as it stands, on a task subset of the same workload (about budget_s of CPU work)."""
     import numpy as np
     from oracle import maml_dlrm as O
@@ -204,7 +211,7 @@ def cpu_baseline(cfg, K, order, budget_s, params):
     t_all = time.perf_counter()
     while done < cfg.n_tasks and spent < budget_s:
         tasks = list(range(done, min(cfg.n_tasks, done + n)))
-        sup, qry = make_batch(cfg, 0, "cpu", tasks)
+        sup, qry = make_batch(cfg_gen, 0, "cpu", tasks)
         t0 = time.perf_counter()
         O.meta_step(model, params, sup.numpy(), qry.numpy(), cfg.inner_lr, K, order, operand=operand)
         dt = time.perf_counter() - t0
