@@ -111,6 +111,7 @@ struct TwoHopArgs {
     const float* Z;                 // [rows, ldz], the (field f) block at column f*D
     int64_t ldz;
     TwoHopOut out[2];
+    const u32* task_path;           // [Tw] tasks flagged 1 are left to the pair-count kernels (null: none is)
 };
 void launch_two_hop(hipStream_t st, TwoHopArgs a, int n_tasks, int max_bags);
 
@@ -131,6 +132,7 @@ struct PairCountArgs {
     uint8_t* mat;
     int want_ss, want_sq;
     int lds_bytes, cap;                       // set by the launcher
+    u32* task_path;                           // [Tw] only tasks flagged 1 are counted; cleared when a count exceeds 254
     u32* status;
 };
 void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap);
@@ -151,6 +153,7 @@ struct PairHopArgs {
     const float* Z;                           // [rows, ldz], the (field f) block at column f*D
     int64_t ldz;
     PairHopOut out[2];
+    const u32* task_path;                     // [Tw] only tasks flagged 1 are touched
 };
 void launch_pair_hop(hipStream_t st, PairHopArgs a, int Tw, int max_out_rows);
 void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_rows, float* x_out, int ldx, bf16_t* x_bf);

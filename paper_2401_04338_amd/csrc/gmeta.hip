@@ -240,13 +240,15 @@ struct WaveBufs {
     // pair-count matrices of the wave (null when the sparse kernel does the row arithmetic)
     uint8_t* pair_mat;
     int64_t *pair_off_ss, *pair_off_qs, *pair_off_sq;
+    u32* task_path;   // [Tw] 1: pair-count path, 0: sparse kernel (the counting kernel clears it on overflow)
 };
 
 struct WaveDims {
     int Tw;
     int64_t Ss, Sq, Ps, Pq, nnz_s, nnz_q;  // real samples, padded rows, lookups
     int mt_s, mt_q;
-    bool pair = false;                     // pair-count matrices are allocated for the wave
+    bool pair = false;                     // some task of the wave takes the pair-count path (matrices are allocated)
+    bool any_sparse = false;               // some task of the wave takes the sparse kernel
     bool pair_ss = false, pair_sq = false; // which kinds besides query x support
     int64_t pair_bytes = 0;
 };
@@ -372,6 +374,7 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
     }
     w.pair_mat = nullptr;
     w.pair_off_ss = w.pair_off_qs = w.pair_off_sq = nullptr;
+    w.task_path = ar.get<u32>(d.Tw + 1);
     if (d.pair) {
         w.pair_off_ss = ar.get<int64_t>(d.Tw + 1);
         w.pair_off_qs = ar.get<int64_t>(d.Tw + 1);
@@ -954,13 +957,26 @@ static int global_order(gm_ctx* c, const Batch& B, int64_t* emb_rows, int64_t* s
 
 static inline int64_t pad64(int64_t n) { return (n + 63) & ~(int64_t)63; }
 
-// Byte offsets of every task's pair-count matrices (kind by kind, fields back to back); returns the total.
-static int64_t pair_layout(const gm_ctx* c, const Batch& B, const WavePlan& p, bool ss, bool sq, std::vector<int64_t>* off_ss,
-                           std::vector<int64_t>* off_qs, std::vector<int64_t>* off_sq) {
+// Whether a task's row arithmetic should go through pair-count matrices: the product costs
+// n_out * n_in * D per (task, field) against lookups * D for the sparse kernel, on units that are far
+// faster, so it pays while the task is moderately small.
+static bool task_pair_ok(const gm_ctx* c, const Batch& B, int t, int K) {
+    if (c->row_path == 1 || K <= 0 || c->F == 0 || c->D % 32 != 0) return false;
+    const int64_t mx = std::max(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t], B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]);
+    return mx > 0 && mx <= (c->row_path == 2 ? 1024 : 512);
+}
+
+// Byte offsets of every task's pair-count matrices (kind by kind, fields back to back; nothing for a task
+// that takes the sparse kernel); returns the total.
+static int64_t pair_layout(const gm_ctx* c, const Batch& B, const WavePlan& p, int K, bool ss, bool sq,
+                           std::vector<int64_t>* off_ss, std::vector<int64_t>* off_qs, std::vector<int64_t>* off_sq,
+                           std::vector<u32>* path) {
     int64_t acc = 0;
     for (int t = p.t0; t < p.t1; ++t) {
-        const int64_t ns = pad64(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t]);
-        const int64_t nq = pad64(B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]);
+        const bool ok = task_pair_ok(c, B, t, K);
+        const int64_t ns = ok ? pad64(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t]) : 0;
+        const int64_t nq = ok ? pad64(B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]) : 0;
+        if (path) path->push_back(ok ? 1u : 0u);
         if (off_ss) off_ss->push_back(acc);
         if (ss) acc += c->F * ns * ns;
         if (off_qs) off_qs->push_back(acc);
@@ -971,26 +987,16 @@ static int64_t pair_layout(const gm_ctx* c, const Batch& B, const WavePlan& p, b
     return acc;
 }
 
-// Whether the wave's row arithmetic should go through pair-count matrices: the product costs
-// n_out * n_in * D per (task, field) against lookups * D for the sparse kernel, on units that are far
-// faster, so it pays while tasks are moderately small.
-static bool pair_path_wanted(const gm_ctx* c, const Batch& B, const WavePlan& p, int K) {
-    if (c->row_path == 1 || K <= 0 || c->F == 0 || c->D % 32 != 0) return false;
-    int64_t mx = 0;
-    for (int t = p.t0; t < p.t1; ++t) {
-        mx = std::max(mx, B.sup->task_offsets[t + 1] - B.sup->task_offsets[t]);
-        mx = std::max(mx, B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]);
-    }
-    return mx > 0 && mx <= (c->row_path == 2 ? 1024 : 512);
-}
-
 static WaveDims wave_dims(const gm_ctx* c, const Batch& B, const WavePlan& p, int bm, int K, int order) {
     WaveDims d;
-    if (pair_path_wanted(c, B, p, K)) {
-        d.pair = true;
+    for (int t = p.t0; t < p.t1; ++t) {
+        if (task_pair_ok(c, B, t, K)) d.pair = true;
+        else d.any_sparse = true;
+    }
+    if (d.pair) {
         d.pair_ss = K >= 2;
         d.pair_sq = order == 2;
-        d.pair_bytes = pair_layout(c, B, p, d.pair_ss, d.pair_sq, nullptr, nullptr, nullptr);
+        d.pair_bytes = pair_layout(c, B, p, K, d.pair_ss, d.pair_sq, nullptr, nullptr, nullptr, nullptr);
     }
     d.Tw = p.t1 - p.t0;
     d.Ss = p.s1 - p.s0; d.Sq = p.q1 - p.q0; d.Ps = p.ps1 - p.ps0; d.Pq = p.pq1 - p.pq0;
@@ -1096,7 +1102,7 @@ static int begin_batch(gm_ctx* c, Batch& B, Arena& ar, int64_t capacity, bool ne
     return GM_OK;
 }
 
-static int setup_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, int bm, WaveBufs& w, const WaveDims& d, Grp& gs,
+static int setup_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, int bm, int K, WaveBufs& w, const WaveDims& d, Grp& gs,
                       Grp& gq) {
     hipStream_t st = c->stream;
     std::vector<int32_t> ro_s, tg_s, tm_s, ro_q, tg_q, tm_q, re_s, re_q;
@@ -1113,8 +1119,11 @@ static int setup_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, int bm, Wav
         (rc = upload_i32(c, w.tile_g_q, tg_q)) || (rc = upload_i32(c, w.tile_m_q, tm_q)))
         return rc;
     std::vector<int64_t> po_ss, po_qs, po_sq;
+    std::vector<u32> path;
+    pair_layout(c, B, wp, K, d.pair_ss, d.pair_sq, &po_ss, &po_qs, &po_sq, &path);
+    if (!path.empty())
+        HIPCHK(c, hipMemcpyAsync(w.task_path, path.data(), path.size() * sizeof(u32), hipMemcpyHostToDevice, st));
     if (d.pair) {
-        pair_layout(c, B, wp, d.pair_ss, d.pair_sq, &po_ss, &po_qs, &po_sq);
         HIPCHK(c, hipMemcpyAsync(w.pair_off_ss, po_ss.data(), po_ss.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
         HIPCHK(c, hipMemcpyAsync(w.pair_off_qs, po_qs.data(), po_qs.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
         HIPCHK(c, hipMemcpyAsync(w.pair_off_sq, po_sq.data(), po_sq.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
@@ -1186,14 +1195,17 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         alloc_wave(c, ar, w, d, K, order);
         if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "internal: wave does not fit");
         Grp gs, gq;
-        if ((rc = setup_wave(c, B, wp, bm, w, d, gs, gq))) return rc;
+        if ((rc = setup_wave(c, B, wp, bm, K, w, d, gs, gq))) return rc;
 
         // a0: row dictionaries and the overlap join
         int tf_cap = 0, max_bag = 0;
         rc = run_index_wave(c, B, wp, w, &tf_cap, &max_bag);
         if (rc != GM_OK) return rc;
-        // pair-count matrices, when the wave qualifies and every count fits a byte
+        // pair-count matrices for the tasks that qualify, when the wave's bags and (task, field)s are within the
+        // counting kernel's limits; a task with a count that does not fit a byte is handed to the sparse kernel
         bool pair = d.pair && tf_cap <= PAIR_MAX_CAP && max_bag <= PAIR_MAX_BAG;
+        bool any_sparse = d.any_sparse || (d.pair && !pair);
+        if (d.pair && !pair) launch_fill_u32(st, w.task_path, Tw, 0u);
         if (pair) {
             PairCountArgs pa;
             memset(&pa, 0, sizeof pa);
@@ -1204,16 +1216,17 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             pa.sup_sorted = w.sup_sorted; pa.qry_sorted = w.qry_sorted;
             pa.off_ss = w.pair_off_ss; pa.off_qs = w.pair_off_qs; pa.off_sq = w.pair_off_sq;
             pa.mat = w.pair_mat; pa.want_ss = d.pair_ss; pa.want_sq = d.pair_sq; pa.status = c->d_status;
+            pa.task_path = w.task_path;
             {
                 Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0);
                 launch_pair_count(st, pa, Tw, tf_cap);
             }
             u32 hs[ST_WORDS];
             if ((rc = read_status(c, hs))) return rc;
-            if (hs[ST_PAIR_OVF]) pair = false;   // a count above 255: the sparse kernel takes the wave
+            if (hs[ST_PAIR_OVF]) any_sparse = true;   // some task's flag was cleared on the device
         }
-        if (c->row_path == 2 && d.pair && !pair)
-            return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a count, bag or (task, field) exceeds its limits");
+        if (c->row_path == 2 && any_sparse)
+            return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a task, count, bag or (task, field) exceeds its limits");
         const int n_tf = Tw * F;
         const int32_t* rows_s = b.prow_s + wp.s0;
         const int32_t* rows_q = b.prow_q + wp.q0;
@@ -1280,7 +1293,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             if (pair) {   // o0 is always the support side, o1 the query side
                 PairHopArgs pa;
                 memset(&pa, 0, sizeof pa);
-                pa.F = F; pa.D = D; pa.mat = w.pair_mat;
+                pa.F = F; pa.D = D; pa.mat = w.pair_mat; pa.task_path = w.task_path;
                 pa.in_real_off = in_support ? w.real_off_s : w.real_off_q;
                 pa.in_row_off = in_support ? w.row_off_s : w.row_off_q;
                 pa.Z = Z; pa.ldz = FD;
@@ -1295,15 +1308,15 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                 if (o1) fill(pa.out[1], *o1, false);
                 Prof p(c, "pair_hop", alg_bytes, 0);
                 launch_pair_hop(st, pa, Tw, max_bags);
-                return;
             }
+            if (!any_sparse) return;
             TwoHopArgs a;
             memset(&a, 0, sizeof a);
             a.F = F; a.D = D;
             a.tf_base = w.base_s; a.n_slots = w.n_slots;
             if (in_support) { a.in_seg_lo = w.slot_start; a.in_seg_hi = w.slot_start + 1; a.in_seg_tf_stride = 1; a.in_sorted = w.sup_sorted; }
             else { a.in_seg_lo = w.qseg_lo; a.in_seg_hi = w.qseg_hi; a.in_seg_tf_stride = 0; a.in_sorted = w.qry_sorted; }
-            a.Z = Z; a.ldz = FD;
+            a.Z = Z; a.ldz = FD; a.task_path = w.task_path;
             a.in_row_offsets = in_support ? w.row_off_s : w.row_off_q;
             a.max_in_rows = max_prows;
             if (o0) a.out[0] = *o0;

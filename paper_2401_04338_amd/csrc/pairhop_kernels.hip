@@ -59,6 +59,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     const int f = blockIdx.x, t = blockIdx.y;
     const bool qs = blockIdx.z == 1;   // 0: support x support, 1: query x support (and its transpose)
     if (!qs && !a.want_ss) return;
+    if (!a.task_path[t]) return;
     const size_t tf = (size_t)t * a.F + f;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, ln = lane & 31, h = lane >> 5;
     const int ns = a.real_off_s[t + 1] - a.real_off_s[t], nq = a.real_off_q[t + 1] - a.real_off_q[t];
@@ -209,7 +210,10 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
             }
         }
     }
-    if (ovf) a.status[ST_PAIR_OVF] = 1u;
+    if (ovf) {   // this task goes to the sparse kernel
+        a.task_path[t] = 0u;
+        a.status[ST_PAIR_OVF] = 1u;
+    }
 }
 
 void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap) {
@@ -260,7 +264,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const PairHopOut& out = a.out[o];
     const int n_in = a.in_real_off[t + 1] - a.in_real_off[t];
     const int n_out = out.real_off[t + 1] - out.real_off[t];
-    if (rb * 256 >= n_out) return;
+    if (rb * 256 >= n_out || !a.task_path[t]) return;
     const int colsP = pad64(n_in), rowsP = pad64(n_out);
     const uint8_t* M = a.mat + out.mat_off[t] + (size_t)f * rowsP * colsP;
     const int wv = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, h = lane >> 5;

@@ -33,6 +33,7 @@ __global__ __launch_bounds__(NT) void two_hop_kernel(TwoHopArgs a) {
     int* rec_slot = reinterpret_cast<int*>(rec_vec + (size_t)groups * 2 * D);  // [groups*2]
     float* Zs = reinterpret_cast<float*>(rec_slot + groups * 2);               // [rows of the task][D]: this slice of Z
     const int f = blockIdx.x, t = blockIdx.y;
+    if (a.task_path && a.task_path[t]) return;   // the pair-count kernels own this task
     const int tf = t * F + f;
     const int g = threadIdx.x / LG, l = threadIdx.x % LG;
     const int lane = threadIdx.x & 63, gbase = lane & ~(LG - 1);

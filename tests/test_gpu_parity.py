@@ -324,3 +324,19 @@ def test_pair_counts_above_a_byte_fall_back(gm):
     with pytest.raises(GMetaError):
         ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, 2, 2)
     ctx.close()
+
+
+def test_mixed_row_paths_in_one_wave(gm):
+    """configs[3]'s size mix in miniature (log-normal task sizes, task-private rows in the first fields): tasks above
+    512 samples per set take the sparse kernel, the others the pair-count kernels, inside one wave of tasks."""
+    from synth import COLDSTART
+    from synth.generate import task_sizes
+    cfg = COLDSTART.with_(n_tasks=7, n_fields=5, rows_per_field=40000, layer_dims=(5 * 64 + 13, 64, 32, 1), mlp_dtype=0,
+                          size_median=600, size_sigma=1.2, size_max=3000, n_private_fields=2, inner_lr=0.05, seed=5)
+    ns = task_sizes(cfg)[:, 0]
+    print("support samples per task", list(ns), flush=True)
+    assert max(ns) > 512 and min(ns) <= 512, "the case must mix both paths"
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=3 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_FP32, "mixed paths K=2 order=2")
+    ctx.close()
