@@ -71,9 +71,10 @@ int tf_sort_max_cap();
 void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
                        const int32_t* indices, int64_t n_bags, const int32_t* row_map, u32 row0, u32* keys,
                        u32* vals);
-// Stable LSD radix sort of (key, val) pairs on the low `bits` bits; result ends in (keys, vals).
-void launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n,
-                       int bits, u32* hist /* 256*nblk + scan tmp */);
+// Stable LSD radix sort of (key, val) pairs on the low `bits` bits.  Returns the number of passes: after an odd
+// number the result is in (keys_tmp, vals_tmp), else in (keys, vals).
+int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n,
+                      int bits, u32* hist /* radix_hist_words(n) */);
 size_t radix_hist_words(int64_t n);
 void launch_segments(hipStream_t st, const u32* sorted_keys, int64_t n, u32* flags_scan, u32* scan_tmp,
                      int64_t* emb_rows, u32* seg_start, int64_t* seg_counts /* may be null */,

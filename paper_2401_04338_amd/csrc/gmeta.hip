@@ -933,12 +933,12 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
     return GM_OK;
 }
 
-static int global_order(gm_ctx* c, const Batch& B, int64_t* emb_rows, int64_t* seg_counts, int64_t capacity,
+static int global_order(gm_ctx* c, Batch& B, int64_t* emb_rows, int64_t* seg_counts, int64_t capacity,
                         int64_t* n_rows) {
     hipStream_t st = c->stream;
     const int F = c->F;
     const gm_set *sup = B.sup, *qry = B.qry;
-    const BatchBufs& b = B.b;
+    BatchBufs& b = B.b;
     const int64_t nnz = sup->nnz + qry->nnz;
     Prof p(c, "global_sort", 0, 0);
     if (F > 0) {
@@ -949,7 +949,10 @@ static int global_order(gm_ctx* c, const Batch& B, int64_t* emb_rows, int64_t* s
     }
     int bits = 1;
     while (((int64_t)1 << bits) < c->field_base[c->F]) ++bits;
-    launch_radix_sort(st, b.keys, b.vals, b.keys_tmp, b.vals_tmp, nnz, bits, b.hist);
+    if (launch_radix_sort(st, b.keys, b.vals, b.keys_tmp, b.vals_tmp, nnz, bits, b.hist) & 1) {
+        std::swap(b.keys, b.keys_tmp);   // an odd number of passes leaves the result in the second pair of buffers
+        std::swap(b.vals, b.vals_tmp);
+    }
     launch_segments(st, b.keys, nnz, b.keys_tmp, b.scan_tmp, emb_rows, b.seg_start, seg_counts, capacity, n_rows,
                     c->d_status);
     return GM_OK;

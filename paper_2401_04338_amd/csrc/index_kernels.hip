@@ -320,18 +320,28 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int cap) {
 // ------------------------------------------------------------------------------------------------
 // global (field,row) ordering of all lookups: keys, stable LSD radix sort, segments
 // ------------------------------------------------------------------------------------------------
-__global__ void build_keys_kernel(int F, const int64_t* field_base, const int64_t* bag_offsets,
-                                  const int32_t* indices, int64_t n_bags, const int32_t* __restrict__ row_map,
-                                  u32 row0, u32* keys, u32* vals) {
-    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= n_bags) return;
-    const int f = (int)(b % F);
-    const u32 fb = (u32)field_base[f];
-    const u32 val = (row0 + (u32)row_map[b / F]) * (u32)F + (u32)f;  // (row of the sample, field) in the gradient buffer
-    const int64_t p0 = bag_offsets[b], p1 = bag_offsets[b + 1];
-    for (int64_t p = p0; p < p1; ++p) {
-        keys[p] = fb + (u32)indices[p];
-        vals[p] = val;
+// One workgroup per 256 consecutive bags: their lookups are one contiguous range, walked by all lanes with
+// coalesced reads and writes; the bag of a lookup is found by bisection of the 257 staged offsets.
+__global__ __launch_bounds__(256) void build_keys_kernel(int F, const int64_t* field_base, const int64_t* bag_offsets,
+                                                         const int32_t* indices, int64_t n_bags,
+                                                         const int32_t* __restrict__ row_map, u32 row0, u32* keys, u32* vals) {
+    __shared__ int64_t offs[257];
+    const int64_t b0 = (int64_t)blockIdx.x * 256;
+    const int nb = (int)min<int64_t>(256, n_bags - b0);
+    for (int i = threadIdx.x; i <= nb; i += 256) offs[i] = bag_offsets[b0 + i];
+    __syncthreads();
+    const int64_t p0 = offs[0], p1 = offs[nb];
+    for (int64_t p = p0 + threadIdx.x; p < p1; p += 256) {
+        int lo = 0, hi = nb;   // last bag with offs[bag] <= p
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (offs[mid] <= p) lo = mid;
+            else hi = mid;
+        }
+        const int64_t b = b0 + lo;
+        const int f = (int)(b % F);
+        keys[p] = (u32)field_base[f] + (u32)indices[p];
+        vals[p] = (row0 + (u32)row_map[b / F]) * (u32)F + (u32)f;  // (row of the sample, field) in the gradient buffer
     }
 }
 
@@ -347,31 +357,36 @@ void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const i
 #define RS_TILE (RS_NT * RS_ITEMS)
 #define RS_WAVES (RS_NT / WAVE)
 
+// Digits are BITS wide (8 or 9): 25-bit row keys sort in three 9-bit passes instead of four 8-bit ones.
+template <int BITS>
 __global__ void radix_hist_kernel(const u32* keys, int64_t n, int shift, u32* hist, int nblk) {
-    __shared__ u32 h[256];
-    h[threadIdx.x] = 0;
+    constexpr int NB = 1 << BITS;
+    __shared__ u32 h[NB];
+    for (int i = threadIdx.x; i < NB; i += RS_NT) h[i] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * RS_TILE;
 #pragma unroll
     for (int i = 0; i < RS_ITEMS; ++i) {
         const int64_t idx = base + i * RS_NT + threadIdx.x;
-        if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & 255u], 1u);
+        if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & (NB - 1)], 1u);
     }
     __syncthreads();
-    hist[(size_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+    for (int i = threadIdx.x; i < NB; i += RS_NT) hist[(size_t)i * nblk + blockIdx.x] = h[i];
 }
 
 // Stable scatter: every wave owns a contiguous 1/4 of the tile and ranks its keys round by round (64
 // consecutive keys per round) with ballot matching, so equal digits keep their input order.
+template <int BITS>
 __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, u32* vout, const u32* gofs,
                                      int64_t n, int shift, int nblk) {
-    __shared__ u32 cnt[RS_WAVES][256];
-    __shared__ u32 digstart[256];
+    constexpr int NB = 1 << BITS, DPT = NB / RS_NT;   // digits per thread in the per-digit phase
+    __shared__ u32 cnt[RS_WAVES][NB];
+    __shared__ u32 digstart[NB];
     __shared__ u32 skeys[RS_TILE];
     __shared__ u32 svals[RS_TILE];
     __shared__ int sh_scan[RS_WAVES + 2];
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
-    for (int i = threadIdx.x; i < RS_WAVES * 256; i += RS_NT) (&cnt[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < RS_WAVES * NB; i += RS_NT) (&cnt[0][0])[i] = 0;
     __syncthreads();
     const int64_t tile0 = (int64_t)blockIdx.x * RS_TILE;
     u32 key[RS_ITEMS], val[RS_ITEMS], rank[RS_ITEMS];
@@ -382,10 +397,10 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
         const bool valid = idx < n;
         key[r] = valid ? kin[idx] : 0xFFFFFFFFu;
         val[r] = valid ? vin[idx] : 0u;
-        const u32 d = (key[r] >> shift) & 255u;
+        const u32 d = (key[r] >> shift) & (NB - 1);
         u64 peers = __ballot(valid);
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
+        for (int b = 0; b < BITS; ++b) {
             const bool bit = (d >> b) & 1u;
             const u64 m = __ballot(bit);
             peers &= bit ? m : ~m;
@@ -400,26 +415,35 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
         rank[r] = old + (u32)__popcll(peers & lt_mask);
         __syncthreads();
     }
-    // per-digit: exclusive prefix over the waves, block total, start of each digit inside the tile
-    u32 total = 0;
-    {
-        const int d = threadIdx.x;
+    // per digit: exclusive prefix over the waves, block total, start of each digit inside the tile
+    u32 total[DPT];
+    u32 mine = 0;
+#pragma unroll
+    for (int k = 0; k < DPT; ++k) {
+        const int d = threadIdx.x * DPT + k;
+        u32 t = 0;
 #pragma unroll
         for (int ww = 0; ww < RS_WAVES; ++ww) {
             const u32 c = cnt[ww][d];
-            cnt[ww][d] = total;
-            total += c;
+            cnt[ww][d] = t;
+            t += c;
         }
+        total[k] = t;
+        mine += t;
     }
     int tile_count;
-    const int ds = block_excl_scan((int)total, sh_scan, &tile_count);
-    digstart[threadIdx.x] = (u32)ds;
+    u32 ds = (u32)block_excl_scan((int)mine, sh_scan, &tile_count);
+#pragma unroll
+    for (int k = 0; k < DPT; ++k) {
+        digstart[threadIdx.x * DPT + k] = ds;
+        ds += total[k];
+    }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < RS_ITEMS; ++r) {
         const int64_t idx = tile0 + (int64_t)w * (WAVE * RS_ITEMS) + r * WAVE + lane;
         if (idx < n) {
-            const u32 d = (key[r] >> shift) & 255u;
+            const u32 d = (key[r] >> shift) & (NB - 1);
             const u32 pos = digstart[d] + cnt[w][d] + rank[r];
             skeys[pos] = key[r];
             svals[pos] = val[r];
@@ -431,7 +455,7 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
         const int pos = i * RS_NT + threadIdx.x;
         if (pos < tile_count) {
             const u32 k = skeys[pos];
-            const u32 d = (k >> shift) & 255u;
+            const u32 d = (k >> shift) & (NB - 1);
             const size_t dst = (size_t)gofs[(size_t)d * nblk + blockIdx.x] + (pos - digstart[d]);
             kout[dst] = k;
             vout[dst] = svals[pos];
@@ -441,32 +465,35 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
 
 size_t radix_hist_words(int64_t n) {
     const int64_t nblk = (n + RS_TILE - 1) / RS_TILE;
-    return (size_t)(256 * nblk + 64) + scan_tmp_words(256 * nblk);
+    return (size_t)(512 * nblk + 64) + scan_tmp_words(512 * nblk);
 }
 
-void launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n, int bits,
-                       u32* hist) {
-    if (n <= 0) return;
+// Returns the number of passes made: after an odd number the result is in (keys_tmp, vals_tmp).
+int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n, int bits,
+                      u32* hist) {
+    if (n <= 0) return 0;
     const int nblk = (int)((n + RS_TILE - 1) / RS_TILE);
-    u32* scan_tmp = hist + ((size_t)256 * nblk + 63) / 64 * 64;
-    int passes = (bits + 7) / 8;
-    if (passes < 1) passes = 1;
-    if (passes & 1) ++passes;  // even number of passes: the result lands in (keys, vals)
+    u32* scan_tmp = hist + ((size_t)512 * nblk + 63) / 64 * 64;
+    if (bits < 1) bits = 1;
+    if (bits > 32) bits = 32;
+    const int p8 = (bits + 7) / 8, p9 = (bits + 8) / 9;
+    const int width = p9 < p8 ? 9 : 8, passes = p9 < p8 ? p9 : p8;
     u32 *ki = keys, *vi = vals, *ko = keys_tmp, *vo = vals_tmp;
     for (int p = 0; p < passes; ++p) {
-        const int shift = 8 * p;
-        if (shift >= 32) {  // nothing left to sort on: plain copy keeps the pairing of buffers
-            hipMemcpyAsync(ko, ki, n * sizeof(u32), hipMemcpyDeviceToDevice, st);
-            hipMemcpyAsync(vo, vi, n * sizeof(u32), hipMemcpyDeviceToDevice, st);
+        const int shift = width * p;
+        if (width == 9) {
+            hipLaunchKernelGGL(radix_hist_kernel<9>, dim3(nblk), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
+            launch_scan_u32(st, hist, hist, (int64_t)512 * nblk, scan_tmp, nullptr);
+            hipLaunchKernelGGL(radix_scatter_kernel<9>, dim3(nblk), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk);
         } else {
-            hipLaunchKernelGGL(radix_hist_kernel, dim3(nblk), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
+            hipLaunchKernelGGL(radix_hist_kernel<8>, dim3(nblk), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
             launch_scan_u32(st, hist, hist, (int64_t)256 * nblk, scan_tmp, nullptr);
-            hipLaunchKernelGGL(radix_scatter_kernel, dim3(nblk), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift,
-                               nblk);
+            hipLaunchKernelGGL(radix_scatter_kernel<8>, dim3(nblk), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk);
         }
         u32* t = ki; ki = ko; ko = t;
         t = vi; vi = vo; vo = t;
     }
+    return passes;
 }
 
 __global__ void seg_flags_kernel(const u32* keys, int64_t n, u32* flags) {
