@@ -1236,8 +1236,10 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         const int32_t rb_s = (int32_t)wp.ps0, rb_q = (int32_t)wp.pq0;
         const bool second = order == 2 && K > 0;
 
-        // a1: one prefetch pass for both sets (pad rows stay zero)
-        if (c->row_pad > 1) {
+        // a1: one prefetch pass for both sets (pad rows stay zero; without pad rows nothing needs clearing: every
+        // real row is written whole, pooled fields by the gather and dense / pad columns by the tail kernels)
+        const bool padded = d.Ps != d.Ss || d.Pq != d.Sq;
+        if (padded) {
             launch_fill_f32(st, w.Xs0, d.Ps * ld0, 0.f);
             launch_fill_f32(st, w.Xq0, d.Pq * ld0, 0.f);
         }
@@ -1248,20 +1250,22 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         {
             const double lookups = (double)(d.nnz_s + d.nnz_q), bags = (double)(d.Ss + d.Sq) * F;
             Prof p(c, "gather_pool", lookups * (4.0 * D + 4) + bags * (4.0 * D + 8 + (bf ? 2.0 * D : 0)), 0);
-            if (bf && X0s.b) zero_bf16(st, X0s.b, d.Ps * ld0);
-            if (bf) zero_bf16(st, w.Xq.b, d.Pq * ld0);
+            if (bf && X0s.b && padded) zero_bf16(st, X0s.b, d.Ps * ld0);
+            if (bf && padded) zero_bf16(st, w.Xq.b, d.Pq * ld0);
             launch_gather_pool(st, F, D, c->n_dense, c->d_field_base, sup->bag_offsets, sup->indices, sup->dense,
                                params->emb, wp.s0, d.Ss, rows_s, rb_s, w.Xs0, ld0, bf ? X0s.b : nullptr);
             launch_gather_pool(st, F, D, c->n_dense, c->d_field_base, qry->bag_offsets, qry->indices, qry->dense,
                                params->emb, wp.q0, d.Sq, rows_q, rb_q, w.Xq0, ld0, (bf && K == 0) ? w.Xq.b : nullptr);
         }
         if (bf && X0s.b) transpose_act(c, X0s, d.Ps);
-        if (second && c->row_pad > 1) {
+        // the pooled direction: its dense and pad columns are zero (dense features are not parameters)
+        if (second && padded) {
             if (w.TX.b) zero_bf16(st, w.TX.b, d.Ps * ld0);
             if (w.TX.f) launch_fill_f32(st, w.TX.f, d.Ps * ld0, 0.f);
+            if (w.TXf) launch_fill_f32(st, w.TXf, d.Ps * ld0, 0.f);
+        } else if (second) {
+            launch_copy_tail(st, FD, nullptr, d.Ps, bf ? w.TXf : w.TX.f, ld0, w.TX.b);
         }
-        if (second && w.TXf) launch_fill_f32(st, w.TXf, d.Ps * ld0, 0.f);
-        if (second && c->row_pad == 1 && w.TX.f) launch_fill_f32(st, w.TX.f, d.Ps * ld0, 0.f);
 
         // row arithmetic of one (task, field) at a time, through LDS (no row table in HBM)
         int max_bags = 0;
@@ -1362,12 +1366,12 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                 float* xs_next = nullptr;
                 if (more) {
                     xs_next = bf ? w.Xs0 : Xn.f;  // bf16: the fp32 master is updated in place
-                    if (bf && c->row_pad > 1) zero_bf16(st, Xn.b, d.Ps * ld0);
+                    if (bf && padded) zero_bf16(st, Xn.b, d.Ps * ld0);
                 }
                 const bool last = !more;
                 TwoHopOut os = hop_out(true, xs_cur, xs_next, more && bf ? Xn.b : nullptr, -alpha);
                 TwoHopOut oq = hop_out(false, w.Xq0, w.Xq0, (bf && last) ? Xq.b : nullptr, -alpha);
-                if (bf && last && c->row_pad > 1) zero_bf16(st, Xq.b, d.Pq * ld0);
+                if (bf && last && padded) zero_bf16(st, Xq.b, d.Pq * ld0);
                 two_hop(true, w.dX, more ? &os : nullptr, &oq);
                 if (more) {
                     launch_copy_tail(st, FD, xs_cur, d.Ps, bf ? nullptr : (xs_next != xs_cur ? xs_next : nullptr), ld0, bf ? Xn.b : nullptr);
