@@ -119,8 +119,8 @@ void launch_two_hop(hipStream_t st, TwoHopArgs a, int n_tasks, int max_bags);
 // The same row arithmetic as a dense product: per (task, field) the pair-count matrix
 // M[i][j] = number of (lookup of out-bag i, lookup of in-bag j) pairs on one row of the task's support set,
 // stored as bytes, [pad64(n_out)][pad64(n_in)] per field, fields of a task back to back.
-#define PAIR_LDS_BYTES (144 * 1024)   // LDS of the counting kernel: a tile of byte cells, two dense count blocks, the lists
-#define PAIR_MAX_CAP 8192        // lookups of one (task, field) and set that the counting kernel stages
+#define PAIR_LDS_BYTES (159 * 1024)   // LDS of the counting kernel: a tile of byte cells, two dense count blocks, the lists
+#define PAIR_MAX_CAP 16384       // lookups of one (task, field) and set that the counting kernel stages
 #define PAIR_MAX_BAG 255         // longest bag for which the 16-bit counts of one row cannot wrap
 struct PairCountArgs {
     int F;

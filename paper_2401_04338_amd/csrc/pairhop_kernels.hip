@@ -77,21 +77,20 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
         if (qs) { lo = a.qseg_lo[B + u] - (int)Bq; hi = a.qseg_hi[B + u] - (int)Bq; }
         else in_seg(u, lo, hi);
     };
-    // LDS, from the end: the bag of every in / out lookup (16 bits each, slot-sorted) and the list of hot rows
-    // (a hot row has >= PC_HOT lookups in one set: at most cap / 2 of them).  From the start: the tile of R
+    // LDS, from the end: the bag of every out lookup (16 bits each, slot-sorted) and the list of hot rows (16 bits
+    // each; a hot row has >= PC_HOT lookups in one set: at most cap / 2 of them).  From the start: the tile of R
     // out-rows, TRANSPOSED, one byte per cell: cell (i, j) at j * ldT + i with ldT = R + 4 (an odd number of
     // words: the MFMA result, the transposed read-out and the atomics all spread over the banks); then the
     // two dense count blocks of a batch, [R][PC_HB] and [colsP][PC_HB] 16-bit counts.
-    uint16_t* in_rows = reinterpret_cast<uint16_t*>(pc_lds) + (a.lds_bytes / 2 - 2 * a.cap);
-    uint16_t* out_rows = in_rows + a.cap;
-    u32* hot_list = reinterpret_cast<u32*>(in_rows) - a.cap / 2;
+    uint16_t* out_rows = reinterpret_cast<uint16_t*>(pc_lds) + (a.lds_bytes / 2 - a.cap);
+    uint16_t* hot_list = out_rows - a.cap / 2;
+    const int in_row0 = a.row_off_s[t];
     {
         const int2* out_list = qs ? a.qry_sorted + Bq : a.sup_sorted + B;
-        const int in_row0 = a.row_off_s[t], out_row0 = qs ? a.row_off_q[t] : a.row_off_s[t];
-        for (int e = threadIdx.x; e < n_in_entries; e += PC_NT) in_rows[e] = (uint16_t)(in_list[e].x - in_row0);
+        const int out_row0 = qs ? a.row_off_q[t] : a.row_off_s[t];
         for (int e = threadIdx.x; e < n_out_entries; e += PC_NT) out_rows[e] = (uint16_t)(out_list[e].x - out_row0);
     }
-    const size_t budget = (size_t)a.lds_bytes - 6 * (size_t)a.cap;
+    const size_t budget = (size_t)a.lds_bytes - 3 * (size_t)a.cap;
     int R = rowsP;   // at most 64 MFMA tiles per row tile
     while (R > 32 && ((size_t)colsP * (R + 4) + (size_t)(R + colsP) * PC_HB * 2 > budget || R * colsP > 65536)) R -= 32;
     const int ldT = R + 4;
@@ -112,7 +111,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
             int lo, hi, lo2, hi2;
             in_seg(u, lo, hi);
             out_seg(u, lo2, hi2);
-            if (hi - lo >= PC_HOT || hi2 - lo2 >= PC_HOT) hot_list[atomicAdd(&sh_nhot, 1)] = (u32)u;
+            if (hi - lo >= PC_HOT || hi2 - lo2 >= PC_HOT) hot_list[atomicAdd(&sh_nhot, 1)] = (uint16_t)u;
         }
         __syncthreads();
         const int nhot = sh_nhot;
@@ -138,7 +137,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
                 int lo, hi;
                 in_seg(u, lo, hi);
                 for (int e = lo + lane; e < hi; e += 64)
-                    atomicAdd(reinterpret_cast<u32*>(c_in) + (((int)in_rows[e] * PC_HB + hx) >> 1), inc);
+                    atomicAdd(reinterpret_cast<u32*>(c_in) + (((in_list[e].x - in_row0) * PC_HB + hx) >> 1), inc);
                 out_seg(u, lo, hi);
                 for (int e = lo + lane; e < hi; e += 64) {
                     const int i = (int)out_rows[e] - i0;
@@ -178,7 +177,8 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
         // ---- the other rows, pair by pair (a lookup of the in-set walks the row's few lookups of the out-set);
         //      a cell that was at 254 or more before an increment may have wrapped: reported
         for (int p = threadIdx.x; p < n_in_entries; p += PC_NT) {
-            const int u = in_list[p].y, j = (int)in_rows[p];
+            const int2 ent = in_list[p];
+            const int u = ent.y, j = ent.x - in_row0;
             int lo, hi, lo2, hi2;
             in_seg(u, lo, hi);
             out_seg(u, lo2, hi2);
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
 void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap) {
     if (Tw <= 0 || a.F <= 0) return;
     a.lds_bytes = PAIR_LDS_BYTES;
-    a.cap = cap;
+    a.cap = cap;   // a power of two >= 1024
     (void)hipFuncSetAttribute((const void*)pair_count_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, PAIR_LDS_BYTES);
     hipLaunchKernelGGL(pair_count_kernel, dim3(a.F, Tw, 2), dim3(PC_NT), PAIR_LDS_BYTES, st, a);
 }
