@@ -8,6 +8,11 @@
 //   forward      A = activations [rows, d_in],        Bt = W^T  [d_out, d_in]
 //   backward dA  A = deltas      [rows, d_out],       Bt = W    [d_in, d_out]
 //   weight grad  A = activations^T [d_in, rows],      Bt = deltas^T [d_out, rows]   (K = rows of the task)
+// The weight gradient reads its operands as they are stored (KM = true: activations [rows, d_in] and deltas
+// [rows, d_out], contraction index slowest): the tiles go to LDS row by row and a lane collects its 8 values
+// with eight 2-byte LDS reads.  That is eight times the LDS instructions of the other form, affordable
+// exactly here: the contraction is only as long as a task has rows, and the kernel is bound by the
+// per-task weights it writes.  No transposed copy of any activation exists.
 // A group is a task: its rows are [row_offsets[g], row_offsets[g+1]) and, once theta has been adapted,
 // its weights are its own (group stride != 0).
 #include "gm_internal.h"
@@ -18,11 +23,12 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 #define GK 64          // k extent of one LDS tile
 #define GLD (GK + 8)   // LDS row stride in elements: 144 bytes, an odd number of 16-byte units
 
-template <int BM, int BN, bool DB>
+template <int BM, int BN, bool DB, bool KM>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
     constexpr int MI = BM / 64, NI = BN / 64;  // 32x32 blocks per wave in each direction (2x2 waves)
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    constexpr int TILE = (BM + BN) * GLD;      // elements of one operand stage: A [BM][GLD] then B [BN][GLD]
+    constexpr int LDA_K = BM + 8, LDB_K = BN + 8;  // KM: LDS row strides of the [GK][BM] and [GK][BN] tiles
+    constexpr int TILE = KM ? GK * (LDA_K + LDB_K) : (BM + BN) * GLD;  // elements of one operand stage
 
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Re-number them so that
     // consecutive tiles -- the n-tiles of one row block, then the next row block of the same task, which
@@ -73,6 +79,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
         const bf16_t* A = a.A[pr] + (int64_t)g * a.gA[pr] + r0 * a.rA[pr];
         const bf16_t* B = a.B[pr] + (int64_t)g * a.gB[pr] + r0 * a.rB[pr];
         const int64_t lda = a.lda[pr], ldb = a.ldb[pr];
+        if constexpr (KM) {  // 16-byte chunks along m / n: chunk c = tid + 256*i of row c / (BM/8)
+#pragma unroll
+            for (int i = 0; i < CA; ++i) {
+                const int ch = tid + 256 * i, kr = ch / (BM / 8), mc = (ch % (BM / 8)) * 8;
+                ra[i] = (k0 + kr < K && m0 + mc < M) ? *reinterpret_cast<const uint4*>(A + (int64_t)(k0 + kr) * lda + m0 + mc)
+                                                     : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < CB; ++i) {
+                const int ch = tid + 256 * i, kr = ch / (BN / 8), nc = (ch % (BN / 8)) * 8;
+                rb[i] = (k0 + kr < K && n0 + nc < N) ? *reinterpret_cast<const uint4*>(B + (int64_t)(k0 + kr) * ldb + n0 + nc)
+                                                     : make_uint4(0, 0, 0, 0);
+            }
+            return;
+        }
         const bool kok = k0 + ccol < K;
 #pragma unroll
         for (int i = 0; i < CA; ++i) {
@@ -86,12 +107,50 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
         }
     };
     auto store_tile = [&](bf16_t* stage) {
+        if constexpr (KM) {
+#pragma unroll
+            for (int i = 0; i < CA; ++i) {
+                const int ch = tid + 256 * i;
+                *reinterpret_cast<uint4*>(stage + (ch / (BM / 8)) * LDA_K + (ch % (BM / 8)) * 8) = ra[i];
+            }
+#pragma unroll
+            for (int i = 0; i < CB; ++i) {
+                const int ch = tid + 256 * i;
+                *reinterpret_cast<uint4*>(stage + GK * LDA_K + (ch / (BN / 8)) * LDB_K + (ch % (BN / 8)) * 8) = rb[i];
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4*>(stage + (crow + 32 * i) * GLD + ccol) = ra[i];
 #pragma unroll
         for (int i = 0; i < CB; ++i) *reinterpret_cast<uint4*>(stage + BM * GLD + (crow + 32 * i) * GLD + ccol) = rb[i];
     };
     auto compute = [&](const bf16_t* stage) {
+        if constexpr (KM) {
+            const bf16_t* As = stage + wm0 + l32;
+            const bf16_t* Bs = stage + GK * LDA_K + wn0 + l32;
+            auto frag = [&](const bf16_t* col, int ld, int k) {  // 8 contraction values of one column, two per register
+                u32 w[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    w[jj] = (u32)col[(k + 2 * jj) * ld] | ((u32)col[(k + 2 * jj + 1) * ld] << 16);
+                return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            };
+#pragma unroll
+            for (int kk = 0; kk < GK / 16; ++kk) {
+                bf16x8 af[MI], bfr[NI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) af[i] = frag(As + i * 32, LDA_K, kk * 16 + lhi * 8);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) bfr[j] = frag(Bs + j * 32, LDB_K, kk * 16 + lhi * 8);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            }
+            return;
+        }
         const bf16_t* As = stage;
         const bf16_t* Bs = stage + BM * GLD;
 #pragma unroll
@@ -236,7 +295,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     }
 }
 
-template <int BM, int BN, bool DB>
+template <int BM, int BN, bool DB, bool KM = false>
 static void launch_variant(hipStream_t st, const GemmBArgs& a) {
     const int n_ntiles = (a.N + BN - 1) / BN;
     int64_t n_mtiles;
@@ -249,10 +308,10 @@ static void launch_variant(hipStream_t st, const GemmBArgs& a) {
     }
     if (n_mtiles <= 0 || n_ntiles <= 0) return;
     const int64_t n_tiles = n_mtiles * n_ntiles;
-    size_t shmem = (size_t)(BM + BN) * GLD * sizeof(bf16_t) * (DB ? 2 : 1);
+    size_t shmem = (KM ? (size_t)GK * (BM + BN + 16) : (size_t)(BM + BN) * GLD) * sizeof(bf16_t) * (DB ? 2 : 1);
     const size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);  // the epilogue's strips
     if (shmem < epi) shmem = epi;
-    auto kern = gemm_bf16_kernel<BM, BN, DB>;
+    auto kern = gemm_bf16_kernel<BM, BN, DB, KM>;
     if (shmem > 48 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
@@ -267,6 +326,9 @@ void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm) {
     else if (bm == 256) launch_variant<256, 128, false>(st, a);
     else launch_variant<128, 128, false>(st, a);
 }
+
+// Weight-gradient form: both operands stored with the contraction index slowest (A [K, M], B [K, N]).
+void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a) { launch_variant<128, 128, false, true>(st, a); }
 
 // ------------------------------------------------------------------------------------------------
 // grouped transpose of a bf16 matrix: src [P, ld] -> dst [ld, ldT]  (dst[c, r] = src[r, c])

@@ -253,7 +253,7 @@ struct WaveDims {
     int64_t pair_bytes = 0;
 };
 
-static Act alloc_act(const gm_ctx* c, Arena& ar, int64_t rows, int ld, bool transposed = true) {
+static Act alloc_act(const gm_ctx* c, Arena& ar, int64_t rows, int ld, bool transposed = false) {
     Act a;
     a.ld = ld;
     if (c->mlp_dtype == 0) {
@@ -694,9 +694,9 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
             GemmBArgs a;
             memset(&a, 0, sizeof a);
             a.row_offsets = g.row_off; a.G = g.G; a.n_pairs = np;
-            for (int i = 0; i < np; ++i) {
-                a.A[i] = as[i]->bT; a.lda[i] = g.rows; a.rA[i] = 1;
-                a.B[i] = ds[i]->bT; a.ldb[i] = g.rows; a.rB[i] = 1;
+            for (int i = 0; i < np; ++i) {   // activations and deltas as they are stored: [rows, width]
+                a.A[i] = as[i]->b; a.lda[i] = M; a.rA[i] = M;
+                a.B[i] = ds[i]->b; a.ldb[i] = N; a.rB[i] = N;
             }
             if (write_f32 || !out.b) { a.Cf = out.f + c->offW[l]; a.ldcf = N; a.gCf = out.sf; }
             a.M = M; a.N = N; a.K = -1;
@@ -705,7 +705,7 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
                 a.CbT = out.b + c->offWTb[l]; a.ldcbT = M; a.gCbT = out.sb;
             }
             a.epi = EPI_AXPBY; a.Cin = in ? in + c->offW[l] : nullptr; a.gCin = in_stride; a.ldcin = N; a.c0 = c0; a.c1 = c1;
-            launch_gemm_bf16(c->stream, a, 128);
+            launch_gemm_bf16_kmajor(c->stream, a);
         }
     }
 }
