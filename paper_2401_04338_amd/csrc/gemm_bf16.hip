@@ -23,12 +23,12 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 #define GK 64          // k extent of one LDS tile
 #define GLD (GK + 8)   // LDS row stride in elements: 144 bytes, an odd number of 16-byte units
 
-template <int BM, int BN, bool DB, bool KM>
+template <int BM, int BN, bool DB, bool KA, bool KB>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
     constexpr int MI = BM / 64, NI = BN / 64;  // 32x32 blocks per wave in each direction (2x2 waves)
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     constexpr int LDA_K = BM + 8, LDB_K = BN + 8;  // KM: LDS row strides of the [GK][BM] and [GK][BN] tiles
-    constexpr int TILE = KM ? GK * (LDA_K + LDB_K) : (BM + BN) * GLD;  // elements of one operand stage
+    constexpr int TILE = (KA ? GK * LDA_K : BM * GLD) + (KB ? GK * LDB_K : BN * GLD);  // elements of one operand stage
 
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Re-number them so that
     // consecutive tiles -- the n-tiles of one row block, then the next row block of the same task, which
@@ -73,95 +73,80 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     const int kt_per_pair = (K + GK - 1) / GK;
     const int n_kt = kt_per_pair * a.n_pairs;
 
+    constexpr int A_ELEMS = KA ? GK * LDA_K : BM * GLD;   // LDS elements of the A tile; the B tile follows
     auto load_tile = [&](int kt) {
         const int pr = kt / kt_per_pair;
         const int k0 = (kt - pr * kt_per_pair) * GK;
         const bf16_t* A = a.A[pr] + (int64_t)g * a.gA[pr] + r0 * a.rA[pr];
         const bf16_t* B = a.B[pr] + (int64_t)g * a.gB[pr] + r0 * a.rB[pr];
         const int64_t lda = a.lda[pr], ldb = a.ldb[pr];
-        if constexpr (KM) {  // 16-byte chunks along m / n: chunk c = tid + 256*i of row c / (BM/8)
+        const bool kok = k0 + ccol < K;
+        if constexpr (KA) {  // contraction slowest: 16-byte chunks along m, chunk c = tid + 256*i of row c / (BM/8)
 #pragma unroll
             for (int i = 0; i < CA; ++i) {
                 const int ch = tid + 256 * i, kr = ch / (BM / 8), mc = (ch % (BM / 8)) * 8;
                 ra[i] = (k0 + kr < K && m0 + mc < M) ? *reinterpret_cast<const uint4*>(A + (int64_t)(k0 + kr) * lda + m0 + mc)
                                                      : make_uint4(0, 0, 0, 0);
             }
+        } else {
+#pragma unroll
+            for (int i = 0; i < CA; ++i) {
+                const int m = m0 + crow + 32 * i;
+                ra[i] = (kok && m < M) ? *reinterpret_cast<const uint4*>(A + (int64_t)m * lda + k0 + ccol) : make_uint4(0, 0, 0, 0);
+            }
+        }
+        if constexpr (KB) {
 #pragma unroll
             for (int i = 0; i < CB; ++i) {
                 const int ch = tid + 256 * i, kr = ch / (BN / 8), nc = (ch % (BN / 8)) * 8;
                 rb[i] = (k0 + kr < K && n0 + nc < N) ? *reinterpret_cast<const uint4*>(B + (int64_t)(k0 + kr) * ldb + n0 + nc)
                                                      : make_uint4(0, 0, 0, 0);
             }
-            return;
-        }
-        const bool kok = k0 + ccol < K;
+        } else {
 #pragma unroll
-        for (int i = 0; i < CA; ++i) {
-            const int m = m0 + crow + 32 * i;
-            ra[i] = (kok && m < M) ? *reinterpret_cast<const uint4*>(A + (int64_t)m * lda + k0 + ccol) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < CB; ++i) {
-            const int n = n0 + crow + 32 * i;
-            rb[i] = (kok && n < N) ? *reinterpret_cast<const uint4*>(B + (int64_t)n * ldb + k0 + ccol) : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < CB; ++i) {
+                const int n = n0 + crow + 32 * i;
+                rb[i] = (kok && n < N) ? *reinterpret_cast<const uint4*>(B + (int64_t)n * ldb + k0 + ccol) : make_uint4(0, 0, 0, 0);
+            }
         }
     };
     auto store_tile = [&](bf16_t* stage) {
-        if constexpr (KM) {
 #pragma unroll
-            for (int i = 0; i < CA; ++i) {
-                const int ch = tid + 256 * i;
-                *reinterpret_cast<uint4*>(stage + (ch / (BM / 8)) * LDA_K + (ch % (BM / 8)) * 8) = ra[i];
-            }
-#pragma unroll
-            for (int i = 0; i < CB; ++i) {
-                const int ch = tid + 256 * i;
-                *reinterpret_cast<uint4*>(stage + GK * LDA_K + (ch / (BN / 8)) * LDB_K + (ch % (BN / 8)) * 8) = rb[i];
-            }
-            return;
+        for (int i = 0; i < CA; ++i) {
+            const int ch = tid + 256 * i;
+            if constexpr (KA) *reinterpret_cast<uint4*>(stage + (ch / (BM / 8)) * LDA_K + (ch % (BM / 8)) * 8) = ra[i];
+            else *reinterpret_cast<uint4*>(stage + (crow + 32 * i) * GLD + ccol) = ra[i];
         }
 #pragma unroll
-        for (int i = 0; i < CA; ++i) *reinterpret_cast<uint4*>(stage + (crow + 32 * i) * GLD + ccol) = ra[i];
+        for (int i = 0; i < CB; ++i) {
+            const int ch = tid + 256 * i;
+            if constexpr (KB) *reinterpret_cast<uint4*>(stage + A_ELEMS + (ch / (BN / 8)) * LDB_K + (ch % (BN / 8)) * 8) = rb[i];
+            else *reinterpret_cast<uint4*>(stage + A_ELEMS + (crow + 32 * i) * GLD + ccol) = rb[i];
+        }
+    };
+    // 8 contraction values of one column of a contraction-slowest tile, two per register
+    auto frag = [&](const bf16_t* col, int ld, int k) {
+        u32 w[4];
 #pragma unroll
-        for (int i = 0; i < CB; ++i) *reinterpret_cast<uint4*>(stage + BM * GLD + (crow + 32 * i) * GLD + ccol) = rb[i];
+        for (int jj = 0; jj < 4; ++jj) w[jj] = (u32)col[(k + 2 * jj) * ld] | ((u32)col[(k + 2 * jj + 1) * ld] << 16);
+        return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
     };
     auto compute = [&](const bf16_t* stage) {
-        if constexpr (KM) {
-            const bf16_t* As = stage + wm0 + l32;
-            const bf16_t* Bs = stage + GK * LDA_K + wn0 + l32;
-            auto frag = [&](const bf16_t* col, int ld, int k) {  // 8 contraction values of one column, two per register
-                u32 w[4];
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    w[jj] = (u32)col[(k + 2 * jj) * ld] | ((u32)col[(k + 2 * jj + 1) * ld] << 16);
-                return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
-            };
-#pragma unroll
-            for (int kk = 0; kk < GK / 16; ++kk) {
-                bf16x8 af[MI], bfr[NI];
-#pragma unroll
-                for (int i = 0; i < MI; ++i) af[i] = frag(As + i * 32, LDA_K, kk * 16 + lhi * 8);
-#pragma unroll
-                for (int j = 0; j < NI; ++j) bfr[j] = frag(Bs + j * 32, LDB_K, kk * 16 + lhi * 8);
-#pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-            }
-            return;
-        }
         const bf16_t* As = stage;
-        const bf16_t* Bs = stage + BM * GLD;
+        const bf16_t* Bs = stage + A_ELEMS;
 #pragma unroll
         for (int kk = 0; kk < GK / 16; ++kk) {
             bf16x8 af[MI], bfr[NI];
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(As + (wm0 + i * 32 + l32) * GLD + kk * 16 + lhi * 8);
+            for (int i = 0; i < MI; ++i) {
+                if constexpr (KA) af[i] = frag(As + wm0 + i * 32 + l32, LDA_K, kk * 16 + lhi * 8);
+                else af[i] = *reinterpret_cast<const bf16x8*>(As + (wm0 + i * 32 + l32) * GLD + kk * 16 + lhi * 8);
+            }
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + (wn0 + j * 32 + l32) * GLD + kk * 16 + lhi * 8);
+            for (int j = 0; j < NI; ++j) {
+                if constexpr (KB) bfr[j] = frag(Bs + wn0 + j * 32 + l32, LDB_K, kk * 16 + lhi * 8);
+                else bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + (wn0 + j * 32 + l32) * GLD + kk * 16 + lhi * 8);
+            }
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -295,7 +280,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     }
 }
 
-template <int BM, int BN, bool DB, bool KM = false>
+template <int BM, int BN, bool DB, bool KA = false, bool KB = false>
 static void launch_variant(hipStream_t st, const GemmBArgs& a) {
     const int n_ntiles = (a.N + BN - 1) / BN;
     int64_t n_mtiles;
@@ -308,10 +293,10 @@ static void launch_variant(hipStream_t st, const GemmBArgs& a) {
     }
     if (n_mtiles <= 0 || n_ntiles <= 0) return;
     const int64_t n_tiles = n_mtiles * n_ntiles;
-    size_t shmem = (KM ? (size_t)GK * (BM + BN + 16) : (size_t)(BM + BN) * GLD) * sizeof(bf16_t) * (DB ? 2 : 1);
+    size_t shmem = ((KA ? (size_t)GK * (BM + 8) : (size_t)BM * GLD) + (KB ? (size_t)GK * (BN + 8) : (size_t)BN * GLD)) * sizeof(bf16_t) * (DB ? 2 : 1);
     const size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);  // the epilogue's strips
     if (shmem < epi) shmem = epi;
-    auto kern = gemm_bf16_kernel<BM, BN, DB, KM>;
+    auto kern = gemm_bf16_kernel<BM, BN, DB, KA, KB>;
     if (shmem > 48 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
@@ -328,7 +313,14 @@ void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm) {
 }
 
 // Weight-gradient form: both operands stored with the contraction index slowest (A [K, M], B [K, N]).
-void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a) { launch_variant<128, 128, false, true>(st, a); }
+void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a) { launch_variant<128, 128, false, true, true>(st, a); }
+
+// Forward form with the weights as they are stored (B [K, N] = W [d_in, d_out]): no transposed copy of theta.
+void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm) {
+    if (bm == 64) launch_variant<64, 128, false, false, true>(st, a);
+    else if (bm == 256) launch_variant<256, 128, false, false, true>(st, a);
+    else launch_variant<128, 128, false, false, true>(st, a);
+}
 
 // ------------------------------------------------------------------------------------------------
 // grouped transpose of a bf16 matrix: src [P, ld] -> dst [ld, ldT]  (dst[c, r] = src[r, c])

@@ -221,6 +221,8 @@ void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm);
 // same product with both operands stored contraction-slowest: A_p element (k, m) at A + g*gA + r0*rA + k*lda + m,
 // B_p element (k, n) at B + g*gB + r0*rB + k*ldb + n
 void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a);
+// A contraction-contiguous as in launch_gemm_bf16, B stored contraction-slowest (element (k, n) at ... + k*ldb + n)
+void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm);
 // dst[g][c, r] = src[g][r, c] for r < P, c < ld  (src row stride ld, dst row stride ldT)
 void launch_transpose_bf16(hipStream_t st, const bf16_t* src, int64_t P, int ld, bf16_t* dst, int64_t ldT, int G,
                            int64_t g_src, int64_t g_dst);

@@ -57,7 +57,7 @@ struct gm_ctx {
     std::vector<int64_t> rows, field_base;
     std::vector<int> dims, ld;
     std::vector<int64_t> offW, offb;    // fp32 theta layout
-    std::vector<int64_t> offWb, offWTb; // bf16 theta layout: W_l and W_l^T, l = 1..L-1
+    std::vector<int64_t> offWb;         // bf16 theta layout: W_l as stored ([d_in, d_out]), l = 1..L-1
     int64_t n_theta = 0, n_theta_b = 0;
     int FD = 0, row_pad = 1;
     int device = 0;
@@ -173,7 +173,6 @@ static int model_layout(gm_ctx* c, const gm_model_desc* m) {
     c->offW.assign(c->L + 1, 0);
     c->offb.assign(c->L + 1, 0);
     c->offWb.assign(c->L + 1, 0);
-    c->offWTb.assign(c->L + 1, 0);
     int64_t o = 0, ob = 0;
     for (int l = 1; l <= c->L; ++l) {
         c->offW[l] = o;
@@ -182,8 +181,6 @@ static int model_layout(gm_ctx* c, const gm_model_desc* m) {
         o += round_up(c->ld[l], 32);
         if (l < c->L) {
             c->offWb[l] = ob;
-            ob += (int64_t)c->ld[l - 1] * c->ld[l];
-            c->offWTb[l] = ob;
             ob += (int64_t)c->ld[l - 1] * c->ld[l];
         }
     }
@@ -608,16 +605,16 @@ static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, con
         GemmBArgs a;
         memset(&a, 0, sizeof a);
         a.row_offsets = g.row_off; a.G = g.G; a.n_pairs = np;
-        for (int i = 0; i < np; ++i) {
+        for (int i = 0; i < np; ++i) {   // W as stored, [d_in, d_out]: the contraction index is its slow one
             a.A[i] = ins[i]->b; a.lda[i] = K; a.rA[i] = K;
-            a.B[i] = ths[i]->b + c->offWTb[l]; a.ldb[i] = K; a.gB[i] = ths[i]->sb;
+            a.B[i] = ths[i]->b + c->offWb[l]; a.ldb[i] = N; a.gB[i] = ths[i]->sb;
         }
         a.Cb = out.b; a.ldcb = N; a.rCb = N; a.M = -1; a.N = N; a.K = K;
         if (out.bT) { a.CbT = out.bT; a.ldcbT = g.rows; a.rCbT = 1; }  // [ld, rows]: the task's rows are a column range
         a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
         a.epi = epi; a.bias = bias; a.gBias = bias_stride;
         if (mask) { a.mask = mask->b; a.ld_mask = mask->ld; }
-        launch_gemm_bf16(c->stream, a, g.bm);
+        launch_gemm_bf16_bkmajor(c->stream, a, g.bm);
     }
 }
 
@@ -676,7 +673,7 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
     const Act* ds[2] = {d0, d1};
     {
         const double esz = c->mlp_dtype ? 2.0 : 4.0;
-        const double out_b = c->mlp_dtype ? ((write_f32 || !out.b) ? 4.0 : 0.0) + (out.b ? 4.0 : 0.0) : 4.0;
+        const double out_b = c->mlp_dtype ? ((write_f32 || !out.b) ? 4.0 : 0.0) + (out.b ? 2.0 : 0.0) : 4.0;
         const double by = (double)np * g.rows * (M + N) * esz + (double)g.G * M * N * (out_b + ((in && in_stride) ? 4.0 : 0.0));
         Prof p(c, "gemm_wgrad", by, 2.0 * g.rows * N * M * np);
         if (c->mlp_dtype == 0) {
@@ -700,9 +697,8 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
             }
             if (write_f32 || !out.b) { a.Cf = out.f + c->offW[l]; a.ldcf = N; a.gCf = out.sf; }
             a.M = M; a.N = N; a.K = -1;
-            if (out.b) {  // operand copies: W and W^T
+            if (out.b) {  // the bf16 operand copy of W
                 a.Cb = out.b + c->offWb[l]; a.ldcb = N; a.gCb = out.sb;
-                a.CbT = out.b + c->offWTb[l]; a.ldcbT = M; a.gCbT = out.sb;
             }
             a.epi = EPI_AXPBY; a.Cin = in ? in + c->offW[l] : nullptr; a.gCin = in_stride; a.ldcin = N; a.c0 = c0; a.c1 = c1;
             launch_gemm_bf16_kmajor(c->stream, a);
@@ -1183,7 +1179,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         launch_pack_weights(st, params->b[l - 1], 1, c->dims[l], 1, (int)(l == L ? 32 : c->ld[l]), b.theta0.f + c->offb[l]);
         if (bf && l < L)
             launch_convert_weights(st, b.theta0.f + c->offW[l], 0, 1, c->ld[l - 1], c->ld[l], b.theta0.b + c->offWb[l],
-                                   b.theta0.b + c->offWTb[l], 0);
+                                   nullptr, 0);
     }
     launch_fill_f32(st, b.g_theta, nt, 0.f);
     if (FD > 0) launch_fill_f32(st, b.GX, (Ps_tot + B.poff_q[T]) * (int64_t)FD, 0.f);
