@@ -252,6 +252,20 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+__device__ __forceinline__ void load8(const bf16_t* p, float (&v)[8]) {
+    const uint4 x = *reinterpret_cast<const uint4*>(p);
+    const u32 w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        v[2 * k] = __builtin_bit_cast(float, w[k] << 16);
+        v[2 * k + 1] = __builtin_bit_cast(float, w[k] & 0xFFFF0000u);
+    }
+}
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
 template <typename T>
 __global__ void last_fwd_kernel(LastFwdArgs a) {
     const int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 64;
@@ -271,7 +285,29 @@ __global__ void last_fwd_kernel(LastFwdArgs a) {
     const float* w = a.w + (int64_t)g * a.gW;
     const T* x = reinterpret_cast<const T*>(a.a) + s * a.ld;
     float acc = 0.f;
-    if (!a.ta) {
+    // bf16 rows whose width and stride are multiples of 8: 16-byte loads (pad columns hold zeros on both sides)
+    const bool vec = sizeof(T) == 2 && (a.N % 8 == 0) && (a.ld % 8 == 0) && (a.gW % 4 == 0) && (!a.ta || a.gTW % 4 == 0) &&
+                     reinterpret_cast<uintptr_t>(a.w) % 16 == 0 && (!a.ta || reinterpret_cast<uintptr_t>(a.tw) % 16 == 0);
+    if (vec) {
+        const bf16_t* xb = reinterpret_cast<const bf16_t*>(x);
+        const bf16_t* txb = a.ta ? reinterpret_cast<const bf16_t*>(a.ta) + s * a.ld : nullptr;
+        const float* tw = a.ta ? a.tw + (int64_t)g * a.gTW : nullptr;
+        for (int n = lane * 8; n < a.N; n += 512) {
+            float xv[8], wv[8];
+            load8(xb + n, xv);
+            load8(w + n, wv);
+            if (!a.ta) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) acc = fmaf(xv[k], wv[k], acc);
+            } else {
+                float tv[8], twv[8];
+                load8(txb + n, tv);
+                load8(tw + n, twv);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) acc += tv[k] * wv[k] + xv[k] * twv[k];
+            }
+        }
+    } else if (!a.ta) {
         for (int n = lane; n < a.N; n += 64) acc = fmaf(ldf(x, n), w[n], acc);
     } else {
         const T* tx = reinterpret_cast<const T*>(a.ta) + s * a.ld;
@@ -322,6 +358,42 @@ __global__ void last_bwd_kernel(int64_t n, int N, int64_t ld_a, int64_t ld_d, co
     if (d_f32) d_f32[s * ld_d + c] = v;
 }
 
+// bf16 rows, 8 columns per thread (N, strides and the weight strides allow 16-byte accesses)
+__global__ void last_bwd_vec_kernel(int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* __restrict__ row_task,
+                                    const float* __restrict__ dl, const float* __restrict__ w, int64_t gW,
+                                    const float* __restrict__ dl2, const float* __restrict__ w2, int64_t gW2,
+                                    const bf16_t* __restrict__ act, bf16_t* d, float* d_f32) {
+    const int per_row = N / 8;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n * per_row) return;
+    const int64_t s = i / per_row;
+    const int c = (int)(i - s * per_row) * 8;
+    const int g = row_task[s];
+    float wv[8], v[8];
+    load8(w + (int64_t)g * gW + c, wv);
+    const float a1 = dl[s];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = a1 * wv[k];
+    if (dl2) {
+        load8(w2 + (int64_t)g * gW2 + c, wv);
+        const float a2 = dl2[s];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] += a2 * wv[k];
+    }
+    if (act) {
+        float av[8];
+        load8(act + s * ld_a + c, av);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (!(av[k] > 0.f)) v[k] = 0.f;
+    }
+    if (d) *reinterpret_cast<uint4*>(d + s * ld_d + c) = make_uint4(f2bf2(v[0], v[1]), f2bf2(v[2], v[3]), f2bf2(v[4], v[5]), f2bf2(v[6], v[7]));
+    if (d_f32) {
+        *reinterpret_cast<float4*>(d_f32 + s * ld_d + c) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(d_f32 + s * ld_d + c + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+}
+
 // d[s,n] = (dl[s]*w_g[n] (+ dl2[s]*w2_g[n])) * (act[s,n] > 0); act null: no mask.  Output in the
 // activation type (d) and/or fp32 (d_f32).
 void launch_last_bwd(hipStream_t st, int bf16, int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* row_task,
@@ -329,7 +401,11 @@ void launch_last_bwd(hipStream_t st, int bf16, int64_t n, int N, int64_t ld_a, i
                      const void* act, void* d, float* d_f32) {
     if (n <= 0 || N <= 0) return;
     const dim3 grid((unsigned)((n * N + 255) / 256));
-    if (bf16)
+    if (bf16 && N % 8 == 0 && ld_a % 8 == 0 && ld_d % 8 == 0 && gW % 4 == 0 && (!dl2 || gW2 % 4 == 0) &&
+        reinterpret_cast<uintptr_t>(w) % 16 == 0 && (!w2 || reinterpret_cast<uintptr_t>(w2) % 16 == 0))
+        hipLaunchKernelGGL(last_bwd_vec_kernel, dim3((unsigned)((n * (N / 8) + 255) / 256)), dim3(256), 0, st, n, N, ld_a, ld_d,
+                           row_task, dl, w, gW, dl2, w2, gW2, (const bf16_t*)act, (bf16_t*)d, d_f32);
+    else if (bf16)
         hipLaunchKernelGGL(last_bwd_kernel<bf16_t>, grid, dim3(256), 0, st, n, N, ld_a, ld_d, row_task, dl, w, gW, dl2,
                            w2, gW2, (const bf16_t*)act, (bf16_t*)d, d_f32);
     else
