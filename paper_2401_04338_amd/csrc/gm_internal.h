@@ -65,7 +65,7 @@ struct TfSortArgs {
     const int32_t* qry_rows; int32_t qry_row_base;
     u32* status;
 };
-void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int cap);
+void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set_rows);
 int tf_sort_max_cap();
 
 void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,

@@ -924,7 +924,11 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
     a.qry_rows = B.b.prow_q; a.qry_row_base = (int32_t)wp.pq0;
     {
         Prof p(c, "tf_sort", 12.0 * ((wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0)), 0);
-        launch_tf_sort(st, a, cap);
+        int64_t max_set_rows = 0;
+        for (int t = wp.t0; t < wp.t1; ++t)
+            max_set_rows = std::max(max_set_rows, std::max(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t],
+                                                           B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]));
+        launch_tf_sort(st, a, (int)hs[ST_MAX_TF], (int)std::min<int64_t>(max_set_rows, 1 << 30));
     }
     return GM_OK;
 }

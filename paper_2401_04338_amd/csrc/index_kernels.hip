@@ -201,33 +201,174 @@ __device__ __forceinline__ int load_tf_keys(u64* keys, int* sh_fill, const SetVi
     return *sh_fill;
 }
 
-template <bool LDS_UNIQ>
-__global__ void tf_sort_kernel(TfSortArgs a, int cap) {
-    extern __shared__ u64 sh_keys[];  // [cap] (+ u32 uniq[cap] when LDS_UNIQ)
+// The same keys in (row, sample, position) order by a stable LSD radix sort inside LDS: the keys are written in
+// (sample, position) order first (an exclusive scan of the bag lengths places every bag), so only the row bits
+// have to be sorted, in passes of at most 8 bits.  Per pass every wave ranks a contiguous share of the keys, 64 at
+// a time, with ballot matching (equal digits keep their order), and the per-(digit, wave) counts are turned into
+// positions.  Returns the buffer (one of the two) that holds the result.  At most TFR_ROUNDS * 64 keys per wave
+// and TFR_MAXS bags per task and set.
+#define TFR_ROUNDS 8
+#define TFR_MAXS 2048
+struct TfRadixLds {
+    u64 *buf_a, *buf_b;     // [cap] each
+    u32 *sbase, *sp0;       // [ms + 1], [ms]: first key / first lookup (relative to the wave's) of every bag
+    uint16_t* cnt;          // [waves][256]
+    u32* digstart;          // [256]
+    int* sh_scan;
+};
+__device__ __forceinline__ u64* tf_radix_sorted(const TfRadixLds& L, const SetView& v, int F, int f, int64_t s_lo,
+                                                int64_t s_hi, u32 fb, int bits, int n) {
+    const int NT = blockDim.x, W = NT / WAVE, lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
+    const int ns = (int)(s_hi - s_lo);
+    // bag lengths -> first key of every bag
+    {
+        const int per = (ns + NT - 1) / NT;
+        const int b0 = min(ns, (int)threadIdx.x * per), b1 = min(ns, b0 + per);
+        int sum = 0;
+        for (int sidx = b0; sidx < b1; ++sidx) {
+            const int64_t bag = (s_lo + sidx) * F + f;
+            sum += (int)(v.bag_offsets[bag + 1] - v.bag_offsets[bag]);
+        }
+        int total;
+        int run = block_excl_scan(sum, L.sh_scan, &total);
+        for (int sidx = b0; sidx < b1; ++sidx) {
+            const int64_t bag = (s_lo + sidx) * F + f;
+            const int64_t p0 = v.bag_offsets[bag];
+            L.sbase[sidx] = (u32)run;
+            L.sp0[sidx] = (u32)(p0 - v.lookup0);
+            run += (int)(v.bag_offsets[bag + 1] - p0);
+        }
+        if (threadIdx.x == 0) L.sbase[ns] = (u32)n;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < n; e += NT) {
+        int lo = 0, hi = ns;   // last bag whose first key is <= e (empty bags share their successor's first key)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (L.sbase[mid] <= (u32)e) lo = mid;
+            else hi = mid;
+        }
+        const int j = e - (int)L.sbase[lo];
+        const u32 idx = (u32)v.indices[v.lookup0 + L.sp0[lo] + j];
+        L.buf_a[e] = ((u64)(fb + idx) << 32) | ((u64)lo << 16) | (u64)j;
+    }
+    const int passes = (bits + 7) / 8 > 0 ? (bits + 7) / 8 : 1;
+    const int width = (bits + passes - 1) / passes > 0 ? (bits + passes - 1) / passes : 1;
+    const int NB = 1 << width;
+    const int chunk = ((n + W * WAVE - 1) / (W * WAVE)) * WAVE;   // keys per wave, a multiple of 64
+    const int rounds = chunk / WAVE;
+    const u64 lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    u64* in = L.buf_a;
+    u64* out = L.buf_b;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int shift = pass * width;
+        for (int i = threadIdx.x; i < W * NB; i += NT) L.cnt[i] = 0;
+        __syncthreads();   // also: the keys of the previous step are in place
+        u64 key[TFR_ROUNDS];
+        u32 rank[TFR_ROUNDS];
+        const int w_end = min(n, (wv + 1) * chunk);
+#pragma unroll
+        for (int r = 0; r < TFR_ROUNDS; ++r) {
+            if (r < rounds) {
+                const int i = wv * chunk + r * WAVE + lane;
+                const bool valid = i < w_end;
+                key[r] = valid ? in[i] : ~0ull;
+                const u32 d = (((u32)(key[r] >> 32) - fb) >> shift) & (u32)(NB - 1);
+                u64 peers = __ballot(valid);
+                for (int b = 0; b < width; ++b) {
+                    const bool bit = (d >> b) & 1u;
+                    const u64 m = __ballot(bit);
+                    peers &= bit ? m : ~m;
+                }
+                const int leader = valid ? (__ffsll((unsigned long long)peers) - 1) : lane;
+                u32 old = 0;
+                if (valid && lane == leader) {
+                    old = L.cnt[wv * NB + d];
+                    L.cnt[wv * NB + d] = (uint16_t)(old + (u32)__popcll(peers));
+                }
+                old = __shfl(old, leader, WAVE);
+                rank[r] = old + (u32)__popcll(peers & lt_mask);
+            }
+        }
+        __syncthreads();
+        u32 total = 0;
+        if ((int)threadIdx.x < NB) {
+            for (int ww = 0; ww < W; ++ww) {
+                const u32 cc = L.cnt[ww * NB + threadIdx.x];
+                L.cnt[ww * NB + threadIdx.x] = (uint16_t)total;
+                total += cc;
+            }
+        }
+        int tile_count;
+        const int ds = block_excl_scan((int)total, L.sh_scan, &tile_count);
+        if ((int)threadIdx.x < NB) L.digstart[threadIdx.x] = (u32)ds;
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < TFR_ROUNDS; ++r) {
+            if (r < rounds) {
+                const int i = wv * chunk + r * WAVE + lane;
+                if (i < w_end) {
+                    const u32 d = (((u32)(key[r] >> 32) - fb) >> shift) & (u32)(NB - 1);
+                    out[L.digstart[d] + L.cnt[wv * NB + d] + rank[r]] = key[r];
+                }
+            }
+        }
+        u64* tmp = in; in = out; out = tmp;
+        __syncthreads();   // every wave has placed its keys and is done with the counters
+    }
+    return in;
+}
+
+// cap: key capacity of an LDS buffer (bitonic: a power of two); ms: most samples a task has in one set (radix)
+template <bool LDS_UNIQ, bool RADIX>
+__global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms) {
+    extern __shared__ u64 sh_dyn[];  // bitonic: keys [cap] (+ u32 uniq[cap]); radix: two key buffers, uniq, bag tables, counters
     __shared__ int sh_scan[20];
     __shared__ int sh_fill;
+    __shared__ u32 sh_digstart[256];
+    u64* sh_keys = sh_dyn;
+    TfRadixLds L;
+    if (RADIX) {
+        L.buf_a = sh_dyn;
+        L.buf_b = sh_dyn + cap;
+        u32* w32 = reinterpret_cast<u32*>(sh_dyn + 2 * cap) + (LDS_UNIQ ? cap : 0);
+        L.sbase = w32;
+        L.sp0 = w32 + (ms + 1);
+        L.cnt = reinterpret_cast<uint16_t*>(w32 + 2 * ms + 2);
+        L.digstart = sh_digstart;
+        L.sh_scan = sh_scan;
+    }
     const int f = blockIdx.x, t = blockIdx.y;
     const size_t tf = (size_t)t * a.F + f;
     const u32 fb = (u32)a.field_base[f];
     const u32 n = a.cnt_sup[tf], B = a.base_sup[tf];
     const u32 nq = a.cnt_qry[tf], Bq = a.base_qry[tf];
-    u32* uniq = LDS_UNIQ ? (u32*)(sh_keys + cap) : (a.slot_rows + B);
+    u32* uniq = LDS_UNIQ ? (u32*)(sh_dyn + (RADIX ? 2 : 1) * cap) : (a.slot_rows + B);
+    int bits = 1;
+    while (((int64_t)1 << bits) < a.field_base[f + 1] - a.field_base[f]) ++bits;
     int n_unique = 0;
 
     // ---- phase A: support lookups sorted by (row, sample, position in bag)
     const int64_t s_lo = a.sup.task_offsets[a.t0 + t], s_hi = a.sup.task_offsets[a.t0 + t + 1];
     if (n > 0) {
-        load_tf_keys(sh_keys, &sh_fill, a.sup, a.F, f, s_lo, s_hi, fb);
-        int n2 = 1;
-        while (n2 < (int)n) n2 <<= 1;
-        for (int i = n + threadIdx.x; i < n2; i += blockDim.x) sh_keys[i] = ~0ull;
-        __syncthreads();
-        bitonic_sort_lds(sh_keys, n2);
+        if (RADIX) {
+            sh_keys = tf_radix_sorted(L, a.sup, a.F, f, s_lo, s_hi, fb, bits, (int)n);
+        } else {
+            load_tf_keys(sh_keys, &sh_fill, a.sup, a.F, f, s_lo, s_hi, fb);
+            int n2 = 1;
+            while (n2 < (int)n) n2 <<= 1;
+            for (int i = n + threadIdx.x; i < n2; i += blockDim.x) sh_keys[i] = ~0ull;
+            __syncthreads();
+            bitonic_sort_lds(sh_keys, n2);
+        }
         const int chunk = ((int)n + blockDim.x - 1) / blockDim.x;
         const int i0 = min((int)n, (int)threadIdx.x * chunk), i1 = min((int)n, i0 + chunk);
         int c = 0;
         for (int i = i0; i < i1; ++i) c += (i == 0) || ((sh_keys[i] >> 32) != (sh_keys[i - 1] >> 32));
         int slot = block_excl_scan(c, sh_scan, &n_unique) - 1;
+        // radix: the slot of every key goes to the idle key buffer first, so that the second sweep below has
+        // independent iterations and reads only LDS (the bag tables of the sort give every lookup's position)
+        uint16_t* slot_of = RADIX ? reinterpret_cast<uint16_t*>(sh_keys == L.buf_a ? L.buf_b : L.buf_a) : nullptr;
         for (int i = i0; i < i1; ++i) {
             const u64 key = sh_keys[i];
             const u32 row = (u32)(key >> 32);
@@ -238,10 +379,25 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap) {
                 a.slot_rows[B + slot] = row;
                 if (LDS_UNIQ) uniq[slot] = row;
             }
-            const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
-            const int64_t p = a.sup.bag_offsets[(s_lo + s) * a.F + f] + j;
-            a.sup_slot[p - a.sup.lookup0] = slot;
-            a.sup_sorted[B + i] = make_int2(a.sup_rows[s_lo + s] - a.sup_row_base, slot);
+            if (RADIX) {
+                slot_of[i] = (uint16_t)slot;
+            } else {
+                const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
+                const int64_t p = a.sup.bag_offsets[(s_lo + s) * a.F + f] + j;
+                a.sup_slot[p - a.sup.lookup0] = slot;
+                a.sup_sorted[B + i] = make_int2(a.sup_rows[s_lo + s] - a.sup_row_base, slot);
+            }
+        }
+        if (RADIX) {
+            __syncthreads();
+            const int prow0 = a.sup_rows[s_lo] - a.sup_row_base;   // rows of a task are consecutive
+            for (int i = threadIdx.x; i < (int)n; i += blockDim.x) {
+                const u64 key = sh_keys[i];
+                const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
+                const int sl = (int)slot_of[i];
+                a.sup_slot[L.sp0[s] + j] = sl;
+                a.sup_sorted[B + i] = make_int2(prow0 + s, sl);
+            }
         }
     }
     if (threadIdx.x == 0) {
@@ -260,12 +416,18 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap) {
         return;
     }
     const int64_t q_lo = a.qry.task_offsets[a.t0 + t], q_hi = a.qry.task_offsets[a.t0 + t + 1];
-    load_tf_keys(sh_keys, &sh_fill, a.qry, a.F, f, q_lo, q_hi, fb);
-    int n2 = 1;
-    while (n2 < (int)nq) n2 <<= 1;
-    for (int i = nq + threadIdx.x; i < n2; i += blockDim.x) sh_keys[i] = ~0ull;
-    __syncthreads();
-    bitonic_sort_lds(sh_keys, n2);
+    if (RADIX) {
+        sh_keys = tf_radix_sorted(L, a.qry, a.F, f, q_lo, q_hi, fb, bits, (int)nq);
+    } else {
+        sh_keys = sh_dyn;
+        load_tf_keys(sh_keys, &sh_fill, a.qry, a.F, f, q_lo, q_hi, fb);
+        int n2 = 1;
+        while (n2 < (int)nq) n2 <<= 1;
+        for (int i = nq + threadIdx.x; i < n2; i += blockDim.x) sh_keys[i] = ~0ull;
+        __syncthreads();
+        bitonic_sort_lds(sh_keys, n2);
+    }
+    const int qprow0 = a.qry_rows[q_lo] - a.qry_row_base;
     for (int i = threadIdx.x; i < (int)nq; i += blockDim.x) {
         const u64 key = sh_keys[i];
         const u32 row = (u32)(key >> 32);
@@ -277,9 +439,14 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap) {
         }
         const int slot = (lo < n_unique && uniq[lo] == row) ? lo : -1;
         const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
-        const int64_t p = a.qry.bag_offsets[(q_lo + s) * a.F + f] + j;
-        a.qry_slot[p - a.qry.lookup0] = slot;
-        a.qry_sorted[Bq + i] = make_int2(a.qry_rows[q_lo + s] - a.qry_row_base, slot);
+        if (RADIX) {
+            a.qry_slot[L.sp0[s] + j] = slot;
+            a.qry_sorted[Bq + i] = make_int2(qprow0 + s, slot);
+        } else {
+            const int64_t p = a.qry.bag_offsets[(q_lo + s) * a.F + f] + j;
+            a.qry_slot[p - a.qry.lookup0] = slot;
+            a.qry_sorted[Bq + i] = make_int2(a.qry_rows[q_lo + s] - a.qry_row_base, slot);
+        }
     }
     for (int u = threadIdx.x; u < n_unique; u += blockDim.x) {
         const u64 klo = (u64)uniq[u] << 32, khi = ((u64)uniq[u] + 1) << 32;
@@ -302,18 +469,38 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap) {
 
 int tf_sort_max_cap() { return 16384; }
 
-void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int cap) {
+// max_tf: the largest number of lookups any (task, field) of the wave has in one set; max_set_rows: the largest
+// number of samples any task of the wave has in one set
+void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set_rows) {
     if (a.Tw <= 0 || a.F <= 0) return;
+    dim3 grid(a.F, a.Tw);
+    int cap = 1024;
+    while (cap < max_tf) cap <<= 1;
+    if (cap <= 8192 && max_set_rows <= TFR_MAXS) {   // radix sort in LDS
+        const int kcap = (max_tf + 63) / 64 * 64 + 64;                // keys per buffer
+        const int ms = max_set_rows > 0 ? max_set_rows : 1;
+        const int nt = cap / 8 < 256 ? 256 : cap / 8;                 // at most TFR_ROUNDS rounds of 64 keys per wave
+        const size_t fixed = (size_t)(2 * ms + 2) * 4 + (size_t)(nt / WAVE) * 256 * 2;
+        const bool lds_uniq = (size_t)kcap * 20 + fixed <= 80 * 1024;   // the row list in LDS while two workgroups fit a compute unit
+        const size_t shmem = (size_t)kcap * 16 + (lds_uniq ? (size_t)kcap * 4 : 0) + fixed;
+        if (lds_uniq) {
+            hipFuncSetAttribute((const void*)tf_sort_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+            hipLaunchKernelGGL((tf_sort_kernel<true, true>), grid, dim3(nt), shmem, st, a, kcap, ms);
+        } else {
+            hipFuncSetAttribute((const void*)tf_sort_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+            hipLaunchKernelGGL((tf_sort_kernel<false, true>), grid, dim3(nt), shmem, st, a, kcap, ms);
+        }
+        return;
+    }
     const bool lds_uniq = cap <= 8192;
     const size_t shmem = (size_t)cap * (lds_uniq ? 12 : 8);
     const int nt = cap <= 1024 ? 256 : (cap <= 4096 ? 512 : 1024);
-    dim3 grid(a.F, a.Tw);
     if (lds_uniq) {
-        hipFuncSetAttribute((const void*)tf_sort_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-        hipLaunchKernelGGL(tf_sort_kernel<true>, grid, dim3(nt), shmem, st, a, cap);
+        hipFuncSetAttribute((const void*)tf_sort_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+        hipLaunchKernelGGL((tf_sort_kernel<true, false>), grid, dim3(nt), shmem, st, a, cap, 0);
     } else {
-        hipFuncSetAttribute((const void*)tf_sort_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-        hipLaunchKernelGGL(tf_sort_kernel<false>, grid, dim3(nt), shmem, st, a, cap);
+        hipFuncSetAttribute((const void*)tf_sort_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+        hipLaunchKernelGGL((tf_sort_kernel<false, false>), grid, dim3(nt), shmem, st, a, cap, 0);
     }
 }
 
