@@ -1,18 +1,17 @@
 // Grouped bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
-// One form serves every dense product of the MAML step (G-Meta Alg. 1: inner forward, local
+// One kernel serves every dense product of the MAML step (G-Meta Alg. 1: inner forward, local
 // back-propagation, outer forward, and the tangent passes of the second-order term):
-//     C_g[M, N] = sum_p  A_p,g[M, K] * Bt_p,g[N, K]^T          (p = 1 or 2 products)
-// with BOTH operands stored contraction-contiguous, so that a lane's 8 consecutive k values are one
-// 16-byte LDS read.  The caller picks pointers and strides:
-//   forward      A = activations [rows, d_in],        Bt = W^T  [d_out, d_in]
-//   backward dA  A = deltas      [rows, d_out],       Bt = W    [d_in, d_out]
-//   weight grad  A = activations^T [d_in, rows],      Bt = deltas^T [d_out, rows]   (K = rows of the task)
-// The weight gradient reads its operands as they are stored (KM = true: activations [rows, d_in] and deltas
-// [rows, d_out], contraction index slowest): the tiles go to LDS row by row and a lane collects its 8 values
-// with eight 2-byte LDS reads.  That is eight times the LDS instructions of the other form, affordable
-// exactly here: the contraction is only as long as a task has rows, and the kernel is bound by the
-// per-task weights it writes.  No transposed copy of any activation exists.
+//     C_g[M, N] = sum_p  A_p,g[M, K] * B_p,g[K, N]          (p = 1 or 2 products)
+// A lane's MFMA fragment is 8 consecutive contraction values.  An operand stored contraction-contiguous
+// delivers them as one 16-byte LDS read; an operand stored with the contraction index slowest (template
+// flags KA / KB) goes to LDS row by row as it lies in memory and the lane collects its 8 values with eight
+// 2-byte LDS reads.  Every matrix therefore exists once, in the orientation it was produced in:
+//   forward      A = activations [rows, d_in]  (contiguous),  B = W [d_in, d_out]          (KB)
+//   backward dA  A = deltas      [rows, d_out] (contiguous),  B = W [d_in, d_out] read as [n][k] (contiguous)
+//   weight grad  A = activations [rows, d_in]  (KA),          B = deltas [rows, d_out]     (KB), K = rows of the task
+// The eightfold LDS instruction count of the slow-index form is affordable where it is used: the forward
+// product and the weight gradient are bound by the per-task weights they stream, not by LDS issue.
 // A group is a task: its rows are [row_offsets[g], row_offsets[g+1]) and, once theta has been adapted,
 // its weights are its own (group stride != 0).
 #include "gm_internal.h"
@@ -185,13 +184,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     // epilogue.  A lane holds column l32 of each 32x32 block and rows 8*(v/4) + 4*lhi + v%4, which would give
     // 2-byte scattered stores; instead every wave passes its accumulators through LDS one 32-row strip at a
     // time, applies the fused operation on 4 consecutive columns per lane and writes whole row segments.
-    // The transposed bf16 copy is read back from the same strip column-wise, 8 rows = 16 bytes.
     const float* bias = a.bias ? a.bias + (int64_t)g * a.gBias : nullptr;
     const bf16_t* mask = a.mask ? a.mask + r0 * a.ld_mask : nullptr;
     const float* Cin = a.Cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
     float* Cf = a.Cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
     bf16_t* Cb = a.Cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
-    bf16_t* CbT = a.CbT ? a.CbT + (int64_t)g * a.gCbT + r0 * a.rCbT : nullptr;
     constexpr int SW = NI * 32, ELD = SW + 4;      // strip width, LDS row stride (floats)
     constexpr int LPR = SW / 4, RPI = 64 / LPR;    // lanes per strip row, rows per pass
     float* E = reinterpret_cast<float*>(smem) + wave * (32 * ELD);
@@ -253,30 +250,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
                 pk.y = f2bf2(x.z, x.w);
                 *reinterpret_cast<uint2*>(Cb + (int64_t)m * a.ldcb + n) = pk;
             }
-            if (CbT) *reinterpret_cast<float4*>(E + rr * ELD + ec) = x;
         }
         __syncthreads();
-        if (CbT) {
-#pragma unroll
-            for (int c = 0; c < SW; c += 64) {
-                const int col = c + lane;         // one column per lane, 8 rows per 16-byte store
-                const int nT = n0 + wn0 + col;
-                if (col < SW && nT < N) {
-#pragma unroll
-                    for (int r8 = 0; r8 < 32; r8 += 8) {
-                        const int m = m0 + wm0 + i * 32 + r8;
-                        if (m >= M) continue;     // M is a multiple of 8 on this path
-                        uint4 pk;
-                        pk.x = f2bf2(E[(r8 + 0) * ELD + col], E[(r8 + 1) * ELD + col]);
-                        pk.y = f2bf2(E[(r8 + 2) * ELD + col], E[(r8 + 3) * ELD + col]);
-                        pk.z = f2bf2(E[(r8 + 4) * ELD + col], E[(r8 + 5) * ELD + col]);
-                        pk.w = f2bf2(E[(r8 + 6) * ELD + col], E[(r8 + 7) * ELD + col]);
-                        *reinterpret_cast<uint4*>(CbT + (int64_t)nT * a.ldcbT + m) = pk;
-                    }
-                }
-            }
-            __syncthreads();
-        }
     }
 }
 
@@ -320,40 +295,6 @@ void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm) {
     if (bm == 64) launch_variant<64, 128, false, false, true>(st, a);
     else if (bm == 256) launch_variant<256, 128, false, false, true>(st, a);
     else launch_variant<128, 128, false, false, true>(st, a);
-}
-
-// ------------------------------------------------------------------------------------------------
-// grouped transpose of a bf16 matrix: src [P, ld] -> dst [ld, ldT]  (dst[c, r] = src[r, c])
-// ------------------------------------------------------------------------------------------------
-__global__ void transpose_bf16_kernel(const bf16_t* __restrict__ src, int64_t P, int ld, bf16_t* dst, int64_t ldT,
-                                      int64_t g_src, int64_t g_dst) {
-    __shared__ bf16_t tile[64][66];
-    src += (int64_t)blockIdx.z * g_src;
-    dst += (int64_t)blockIdx.z * g_dst;
-    const int64_t r0 = (int64_t)blockIdx.y * 64;
-    const int c0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 256 threads: 4 rows at a time
-    for (int i = ty; i < 64; i += 4) {
-        const int64_t r = r0 + i;
-        const int c = c0 + tx;
-        tile[i][tx] = (r < P && c < ld) ? src[r * ld + c] : (bf16_t)0;
-    }
-    __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        const int c = c0 + i;
-        const int64_t r = r0 + tx;
-        if (c < ld && r < P) dst[(int64_t)c * ldT + r] = tile[tx][i];
-    }
-}
-
-void launch_transpose_bf16(hipStream_t st, const bf16_t* src, int64_t P, int ld, bf16_t* dst, int64_t ldT, int G,
-                           int64_t g_src, int64_t g_dst) {
-    if (P <= 0 || ld <= 0 || G <= 0) return;
-    for (int g0 = 0; g0 < G; g0 += 32768) {
-        const int gc = (G - g0) < 32768 ? (G - g0) : 32768;
-        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((ld + 63) / 64, (unsigned)((P + 63) / 64), gc), dim3(256), 0, st,
-                           src + (int64_t)g0 * g_src, P, ld, dst + (int64_t)g0 * g_dst, ldT, g_src, g_dst);
-    }
 }
 
 // fp32 padded weights [rows, cols] -> bf16 W [rows, cols] and W^T [cols, rows], per group

@@ -213,9 +213,8 @@ struct GemmBArgs {
     const bf16_t* mask; int64_t ld_mask;   // mask + (r0+m)*ld_mask + n
     const float* Cin; int64_t gCin, ldcin; // Cin + g*gCin + m*ldcin + n (EPI_AXPBY)
     float c0, c1;
-    float* Cf; int64_t ldcf, gCf, rCf;     // fp32 output        (any of the three may be null)
+    float* Cf; int64_t ldcf, gCf, rCf;     // fp32 output        (either may be null)
     bf16_t* Cb; int64_t ldcb, gCb, rCb;    // bf16 output
-    bf16_t* CbT; int64_t ldcbT, gCbT, rCbT;  // bf16 output, transposed: CbT + ... + n*ldcbT + m
 };
 void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm);
 // same product with both operands stored contraction-slowest: A_p element (k, m) at A + g*gA + r0*rA + k*lda + m,
@@ -223,9 +222,6 @@ void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm);
 void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a);
 // A contraction-contiguous as in launch_gemm_bf16, B stored contraction-slowest (element (k, n) at ... + k*ldb + n)
 void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm);
-// dst[g][c, r] = src[g][r, c] for r < P, c < ld  (src row stride ld, dst row stride ldT)
-void launch_transpose_bf16(hipStream_t st, const bf16_t* src, int64_t P, int ld, bf16_t* dst, int64_t ldT, int G,
-                           int64_t g_src, int64_t g_dst);
 void launch_convert_weights(hipStream_t st, const float* src, int64_t g_src, int G, int rows, int cols, bf16_t* w,
                             bf16_t* wT, int64_t g_dst);
 

@@ -3,15 +3,14 @@
 //
 // Data layout in HBM (per wave of tasks; a wave is as many tasks as the workspace holds):
 //   activations  [rows, ld]   rows = samples of the wave, each task's rows padded to a multiple of
-//                             `row_pad` (1 for fp32, 8 for bf16: 16-byte aligned task slices in the
-//                             transposed copies); ld = width rounded up to 32
+//                             `row_pad` (1 for fp32, 8 for bf16); ld = width rounded up to 32
 //   theta        [Tw, n_theta] fp32, per task once adapted; layer l at offW[l] ([ld_{l-1}, ld_l],
 //                             zero padded) and offb[l]
-//   bf16 mode    every GEMM operand also lives as bf16, activations in both orientations
-//                ([rows, ld] and [ld, rows]) and weights as W and W^T, so that every product reads
-//                both operands contraction-contiguous
-//   slot tables  [lookups of the wave's support set, D] fp32: task-local row deltas / directions,
-//                addressed base[task, field] + rank of the row in the (task, field) dictionary
+//   bf16 mode    every GEMM operand also lives as bf16, once, in the orientation it is produced in
+//                (activations and deltas [rows, ld], weights [ld_{l-1}, ld_l]); the GEMMs read an operand
+//                whose contraction index is the slow one through LDS
+//   row arithmetic: no row table in HBM; per (task, field) either byte matrices of pair counts or sorted
+//                {row, slot} lists (see pairhop_kernels.hip / twohop_kernels.hip)
 #include <algorithm>
 #include <chrono>
 #include <cstdarg>
@@ -195,7 +194,6 @@ static int model_layout(gm_ctx* c, const gm_model_desc* m) {
 struct Act {  // one activation-shaped buffer [rows, ld] in the type(s) the GEMMs read
     float* f = nullptr;    // fp32 mode
     bf16_t* b = nullptr;   // bf16 mode: [rows, ld]
-    bf16_t* bT = nullptr;  // bf16 mode: [ld, rows]
     int ld = 0;
 };
 struct Theta {  // parameters as the GEMMs read them; stride 0 = shared by all tasks
@@ -250,14 +248,13 @@ struct WaveDims {
     int64_t pair_bytes = 0;
 };
 
-static Act alloc_act(const gm_ctx* c, Arena& ar, int64_t rows, int ld, bool transposed = false) {
+static Act alloc_act(const gm_ctx* c, Arena& ar, int64_t rows, int ld) {
     Act a;
     a.ld = ld;
     if (c->mlp_dtype == 0) {
         a.f = ar.get<float>(rows * ld);
     } else {
         a.b = ar.get<bf16_t>(rows * ld + 8);
-        if (transposed) a.bT = ar.get<bf16_t>(rows * ld + 8);
     }
     return a;
 }
@@ -558,7 +555,7 @@ static int read_status(gm_ctx* c, u32* host) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// dense operators on handles (fp32: vector-FMA GEMM; bf16: MFMA GEMM + the transposed copies)
+// dense operators on handles (fp32: vector-FMA GEMM; bf16: MFMA GEMM)
 // ------------------------------------------------------------------------------------------------
 struct Grp {  // grouping of one set's rows by task inside the wave
     const int32_t *row_off, *real_off, *row_task;
@@ -567,12 +564,6 @@ struct Grp {  // grouping of one set's rows by task inside the wave
     int64_t rows;  // padded rows of the set in the wave
 };
 
-static void transpose_act(gm_ctx* c, const Act& a, int64_t rows) {
-    if (a.b && a.bT) {
-        Prof p(c, "transpose_act", 4.0 * rows * a.ld, 0);
-        launch_transpose_bf16(c->stream, a.b, rows, a.ld, a.bT, rows, 1, 0, 0);
-    }
-}
 
 // out[rows, ld_l] = epi( sum_p in_p[rows, ld_{l-1}] * W_p,l + bias )
 static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, const Theta* th0, const Act* in1,
@@ -580,7 +571,7 @@ static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, con
     const int K = c->ld[l - 1], N = c->ld[l];
     // algorithmic bytes: operands once (per-task weights once per task), every output once
     const double esz = c->mlp_dtype ? 2.0 : 4.0;
-    double by = (double)g.rows * N * esz * ((c->mlp_dtype && out.bT) ? 2 : 1) + (mask ? (double)g.rows * N * esz : 0.0);
+    double by = (double)g.rows * N * esz + (mask ? (double)g.rows * N * esz : 0.0);
     for (int i = 0; i < np; ++i) {
         const Theta* t = i ? th1 : th0;
         by += (double)g.rows * K * esz + (double)((c->mlp_dtype ? t->sb : t->sf) ? g.G : 1) * K * N * esz;
@@ -610,7 +601,6 @@ static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, con
             a.B[i] = ths[i]->b + c->offWb[l]; a.ldb[i] = N; a.gB[i] = ths[i]->sb;
         }
         a.Cb = out.b; a.ldcb = N; a.rCb = N; a.M = -1; a.N = N; a.K = K;
-        if (out.bT) { a.CbT = out.bT; a.ldcbT = g.rows; a.rCbT = 1; }  // [ld, rows]: the task's rows are a column range
         a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
         a.epi = epi; a.bias = bias; a.gBias = bias_stride;
         if (mask) { a.mask = mask->b; a.ld_mask = mask->ld; }
@@ -624,7 +614,7 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
     const int K = c->ld[l], N = dX ? c->FD : c->ld[l - 1];
     if (N <= 0) return;
     const double esz = c->mlp_dtype ? 2.0 : 4.0;
-    double by = dX ? (double)g.rows * N * 4.0 : (double)g.rows * N * esz * ((c->mlp_dtype && out && out->bT) ? 2 : 1);
+    double by = dX ? (double)g.rows * N * 4.0 : (double)g.rows * N * esz;
     if (mask) by += (double)g.rows * N * esz;
     for (int i = 0; i < np; ++i) {
         const Theta* t = i ? th1 : th0;
@@ -659,7 +649,6 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
         if (dX) { a.Cf = dX; a.ldcf = N; a.rCf = N; a.epi = EPI_NONE; }
         else {
             a.Cb = out->b; a.ldcb = N; a.rCb = N; a.epi = EPI_MASK; a.mask = mask->b; a.ld_mask = mask->ld;
-            if (out->bT) { a.CbT = out->bT; a.ldcbT = g.rows; a.rCbT = 1; }
         }
         launch_gemm_bf16(c->stream, a, g.bm);
     }
@@ -760,7 +749,6 @@ static void forward_backward(gm_ctx* c, const Grp& g, const float* labels, const
         launch_last_bwd(st, c->mlp_dtype, g.rows, c->ld[L - 1], c->ld[L - 1], c->ld[L - 1], g.row_task, p.dL, wL,
                         thf_stride, nullptr, nullptr, 0, act_ptr(c, (*p.A)[L - 1]), act_ptr(c, (*p.Dl)[L - 1]), nullptr);
     }
-    transpose_act(c, (*p.Dl)[L - 1], g.rows);
     for (int l = L - 1; l >= 1; --l) {
         if (l == 1) {
             if (dX) dense_nt(c, g, l, 1, &(*p.Dl)[l], &th, nullptr, nullptr, nullptr, nullptr, dX);
@@ -823,7 +811,6 @@ static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, f
             launch_last_bwd(st, c->mlp_dtype, g.rows, c->ld[L - 1], c->ld[L - 1], c->ld[L - 1], g.row_task, w.tdL, s.wL,
                             s.wL_stride, s.dL, vwL, nt, act_ptr(c, s.A[L - 1]), act_ptr(c, w.TD[L - 1]), nullptr);
     }
-    if (L > 1) transpose_act(c, w.TD[L - 1], g.rows);
     colsum(c, g, c->ld[L - 1], tprev, s.dL, prev, w.tdL, v.f + c->offW[L], nt, v.f + c->offW[L], nt, 1.f, -alpha);
     colsum_f32(c, g, 1, w.tdL, 1, v.f + c->offb[L], nt, v.f + c->offb[L], nt, 1.f, -alpha);
     Theta vout = v;
@@ -1257,7 +1244,6 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             launch_gather_pool(st, F, D, c->n_dense, c->d_field_base, qry->bag_offsets, qry->indices, qry->dense,
                                params->emb, wp.q0, d.Sq, rows_q, rb_q, w.Xq0, ld0, (bf && K == 0) ? w.Xq.b : nullptr);
         }
-        if (bf && X0s.b) transpose_act(c, X0s, d.Ps);
         // the pooled direction: its dense and pad columns are zero (dense features are not parameters)
         if (second && padded) {
             if (w.TX.b) zero_bf16(st, w.TX.b, d.Ps * ld0);
@@ -1381,7 +1367,6 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                 Xn = s.X;
             }
             if (more) {
-                if (F > 0) transpose_act(c, Xn, d.Ps);
                 w.steps[second ? k + 1 : 0].X = Xn;
             }
         }
@@ -1394,7 +1379,6 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
 
         // outer forward/backward on the query set with the adapted parameters
         if (bf && K > 0) launch_copy_tail(st, F > 0 ? FD : 0, w.Xq0, d.Pq, nullptr, ld0, Xq.b);
-        transpose_act(c, Xq, d.Pq);
         float* gxq = b.GX + (Ps_tot + wp.pq0) * (int64_t)FD;
         float* gxs = b.GX + wp.ps0 * (int64_t)FD;
         Pass pq{&Xq, &w.Aq, &w.Dq, w.dLq, w.zq};
@@ -1412,7 +1396,6 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             }
             for (int k = K - 1; k >= 0; --k) {
                 const StepState& s = w.steps[k];
-                transpose_act(c, w.TX, d.Ps);
                 hvp_step(c, gs, s, w, alpha, k > 0);
                 if (F > 0) {
                     {
