@@ -28,9 +28,10 @@ FAMILIES = {
     "task_colsum": ["task_colsum_kernel"],
     "reduce_tasks": ["reduce_tasks_kernel"],
     "axpy_gx": ["axpy_kernel"],
-    # the weight-gradient GEMM always runs 128x128 tiles; forward / backward run 256x128 when tasks have >= 192 rows
-    "gemm_wgrad": ["gemm_bf16_kernel<128, 128"],
-    "gemm_fwd+gemm_bwd": ["gemm_bf16_kernel<256, 128", "gemm_bf16_kernel<64, 128"],
+    # template flags of gemm_bf16_kernel<BM, BN, DB, KA, KB>: which operand is read contraction-slowest
+    "gemm_wgrad": ["false, true, true>"],
+    "gemm_fwd": ["false, false, true>"],
+    "gemm_bwd": ["false, false, false>"],
     "gemm_f32 (all launches)": ["gemm_f32_kernel"],
 }
 

@@ -19,9 +19,9 @@ def summarize(db_path: str, top_n: int = 40) -> str:
         else:
             ours.append((name.split("(")[0].replace("void ", ""), calls, total, avg))
     tot = sum(r[2] for r in ours)
-    lines = ["kernel                                   calls   total_us     avg_us   share_of_library_time"]
+    lines = [f"{'kernel':56s} {'calls':>6s} {'total_us':>10s} {'avg_us':>10s}   share_of_library_time"]
     for name, calls, total, avg in ours[:top_n]:
-        lines.append(f"{name[:40]:40s} {calls:6d} {total:10.1f} {avg:10.2f} {100.0 * total / tot:8.2f}%")
+        lines.append(f"{name[:56]:56s} {calls:6d} {total:10.1f} {avg:10.2f} {100.0 * total / tot:8.2f}%")
     lines.append(f"(input generation and other framework kernels: {other_calls} calls, {other_ns:.1f} us)")
     return "\n".join(lines)
 
