@@ -340,3 +340,54 @@ def test_mixed_row_paths_in_one_wave(gm):
     ctx = gm.from_config(cfg, workspace_bytes=3 << 30)
     _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_FP32, "mixed paths K=2 order=2")
     ctx.close()
+
+
+# ---------------------------------------------------------------- the benchmark configurations at full size
+def test_small_config_full_size(gm):
+    """configs[1] whole (64 tasks x (128 + 128) samples, 26 fields x 100k rows x 32, fp32, K=1, second order): every
+    output against the oracle."""
+    cfg = SMALL
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=4 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, cfg.inner_steps, cfg.order, TOL_FP32, "c2_small full size")
+    ctx.close()
+
+
+def test_medium_config_full_size_sampled_tasks(gm):
+    """configs[2] whole, as bench.py launches it (512 tasks, 26 fields x 1M rows x 64, bf16 operands, K=3, second
+    order).  The oracle cannot run the whole batch in the test budget, but tasks are independent (Alg. 1): the loss of
+    a sampled task from the full-size run must equal the oracle's for that task alone.  Over all tasks: the loss is
+    the sum of the task losses, and the listed rows are exactly the distinct rows looked up, ascending."""
+    from synth import MEDIUM
+    cfg = MEDIUM
+    dev = torch.device("cuda", 0)
+    sup, qry = make_batch(cfg, 0, dev)
+    params = make_params(cfg, dev)
+    probe = gm.from_config(cfg, workspace_bytes=1 << 20)   # the workspace that holds one wave, as the benchmark does
+    need = probe.workspace_bytes(cfg.n_tasks, sup.n_samples, qry.n_samples, sup.nnz, qry.nnz, cfg.inner_steps, cfg.order)
+    probe.close()
+    ctx = gm.from_config(cfg, workspace_bytes=int(need * 1.02))
+    out = ctx.meta_step(sup, qry, params, cfg.inner_lr, cfg.inner_steps, cfg.order)
+    task_loss = out["task_loss"][: cfg.n_tasks].double().cpu().numpy()
+    loss = float(out["loss"].item())
+    assert abs(task_loss.sum() - loss) <= 1e-5 * abs(loss)
+    n = int(out["n_emb_rows"].item())
+    rows = out["emb_rows"][:n]
+    F = cfg.n_fields
+    want = []
+    for sd in (sup, qry):
+        lens = sd.bag_offsets[1:] - sd.bag_offsets[:-1]
+        field = (torch.arange(lens.numel(), device=dev) % F).repeat_interleave(lens)
+        want.append(sd.indices.long() + field * cfg.rows_per_field)
+    want = torch.unique(torch.cat(want))
+    assert n == want.numel() and torch.equal(rows, want), "listed rows != distinct rows looked up"
+    assert torch.isfinite(out["emb_grad"][:n]).all()
+    params_np = make_params(cfg, "cpu").numpy()
+    for t in (0, 257, 511):
+        s1, q1 = make_batch(cfg, 0, "cpu", [t])
+        ref = O.meta_step(oracle_model(cfg), params_np, s1.numpy(), q1.numpy(), cfg.inner_lr, cfg.inner_steps, cfg.order,
+                          operand="bf16")
+        e = abs(task_loss[t] - ref["loss"]) / abs(ref["loss"])
+        print(f"c3 full size, task {t}: loss {task_loss[t]:.6f} vs oracle {ref['loss']:.6f} ({e:.2e})", flush=True)
+        assert e <= TOL_BF16
+    ctx.close()
