@@ -148,7 +148,7 @@ struct PairHopOut {
     float c;
 };
 struct PairHopArgs {
-    int F, D, row_blocks;                     // row_blocks is set by the launcher
+    int F, D, row_blocks, n_out, n_work;      // row_blocks, n_out (enabled out sets) and n_work (workgroups) are set by the launcher
     const uint8_t* mat;
     const int32_t *in_real_off, *in_row_off;  // the in set
     const float* Z;                           // [rows, ldz], the (field f) block at column f*D

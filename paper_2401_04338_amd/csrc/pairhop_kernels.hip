@@ -258,9 +258,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     constexpr int CG = DS / 4;        // float4 column groups of a row of Z
     constexpr int RPT = CG / 4;       // rows of the 64-row chunk staged per thread (256 threads)
     __shared__ __attribute__((aligned(16))) bf16_t zs[2 * 3 * DS * PH_KC];
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): re-number them so that the
+    // workgroups of one (task, field, column slice) -- both out sets, all row blocks: they read the same rows of
+    // Z -- are consecutive on one XCD.
     const int nsl = a.D / DS;
-    const int f = blockIdx.x / nsl, sl = blockIdx.x - f * nsl, t = blockIdx.y;
-    const int o = blockIdx.z / a.row_blocks, rb = blockIdx.z - o * a.row_blocks;
+    const int per_xcd = gridDim.x >> 3;
+    const int wid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (wid >= a.n_work) return;
+    const int nz = a.n_out * a.row_blocks, fx = a.F * nsl;
+    const int zi = wid % nz, rest = wid / nz;
+    const int fs = rest % fx, t = rest / fx;
+    const int f = fs / nsl, sl = fs - f * nsl;
+    const int o = zi / a.row_blocks, rb = zi - o * a.row_blocks;
     const PairHopOut& out = a.out[o];
     const int n_in = a.in_real_off[t + 1] - a.in_real_off[t];
     const int n_out = out.real_off[t + 1] - out.real_off[t];
@@ -433,8 +442,12 @@ void launch_pair_hop(hipStream_t st, PairHopArgs a, int Tw, int max_out_rows) {
     if (n_out == 0) return;
     for (int o = 0; o < n_out; ++o) a.out[o] = packed[o];
     a.row_blocks = (max_out_rows + 255) / 256;
-    if (a.D % 64 == 0)
-        hipLaunchKernelGGL(pair_hop_kernel<64>, dim3(a.F * (a.D / 64), Tw, n_out * a.row_blocks), dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL(pair_hop_kernel<32>, dim3(a.F * (a.D / 32), Tw, n_out * a.row_blocks), dim3(256), 0, st, a);
+    a.n_out = n_out;
+    const int ds = a.D % 64 == 0 ? 64 : 32;
+    const int64_t n_work = (int64_t)a.F * (a.D / ds) * Tw * n_out * a.row_blocks;
+    if (n_work >= ((int64_t)1 << 31) - 8) return;   // cannot happen within the library's own limits on a call
+    a.n_work = (int)n_work;
+    const unsigned grid = (unsigned)((n_work + 7) / 8 * 8);
+    if (ds == 64) hipLaunchKernelGGL(pair_hop_kernel<64>, dim3(grid), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(pair_hop_kernel<32>, dim3(grid), dim3(256), 0, st, a);
 }
