@@ -188,6 +188,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     const bf16_t* mask = a.mask ? a.mask + r0 * a.ld_mask : nullptr;
     const float* Cin = a.Cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
     float* Cf = a.Cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
+    float* Cacc = a.Cacc ? a.Cacc + r0 * a.rCacc : nullptr;
     bf16_t* Cb = a.Cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
     constexpr int SW = NI * 32, ELD = SW + 4;      // strip width, LDS row stride (floats)
     constexpr int LPR = SW / 4, RPI = 64 / LPR;    // lanes per strip row, rows per pass
@@ -199,6 +200,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     if (bias && nok) bn = *reinterpret_cast<const float4*>(bias + n);
     const bool has_mask = a.epi == EPI_BIAS_MASK || a.epi == EPI_MASK;
     const bool has_cin = a.epi == EPI_AXPBY && Cin;
+    const bool has_acc = Cacc && !has_cin;   // the accumulate-into output shares the registers of Cin
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
         // What the strip reads from memory is requested before anything of it is stored: the outputs may alias
@@ -213,6 +215,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
             ci_all[it] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (ok && has_mask) mk_all[it] = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
             if (ok && has_cin) ci_all[it] = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
+            if (ok && has_acc) ci_all[it] = *reinterpret_cast<const float4*>(Cacc + (int64_t)m * a.ldcacc + n);
         }
 #pragma unroll
         for (int j = 0; j < NI; ++j)
@@ -244,6 +247,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
                 }
             }
             if (Cf) *reinterpret_cast<float4*>(Cf + (int64_t)m * a.ldcf + n) = x;
+            if (has_acc) {
+                const float4 ci = ci_all[it];
+                *reinterpret_cast<float4*>(Cacc + (int64_t)m * a.ldcacc + n) =
+                    make_float4(ci.x + a.cacc * x.x, ci.y + a.cacc * x.y, ci.z + a.cacc * x.z, ci.w + a.cacc * x.w);
+            }
             if (Cb) {
                 uint2 pk;
                 pk.x = f2bf2(x.x, x.y);

@@ -609,12 +609,15 @@ static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, con
 }
 
 // out[rows, ld_{l-1}] = mask .* sum_p d_p[rows, ld_l] * W_p,l^T ; for l == 1: dX[rows, FD] fp32, no mask
+// dX (layer 1 only): the fp32 gradient w.r.t. the pooled input.  bf16 mode can also accumulate it, scaled, into
+// gx_acc (gx_acc += gx_scale * dX) in the same pass; with write_dx = false only that accumulation is stored.
 static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, const Theta* th0, const Act* d1,
-                     const Theta* th1, const Act* mask, Act* out, float* dX) {
+                     const Theta* th1, const Act* mask, Act* out, float* dX, float* gx_acc = nullptr, float gx_scale = 0.f,
+                     bool write_dx = true) {
     const int K = c->ld[l], N = dX ? c->FD : c->ld[l - 1];
     if (N <= 0) return;
     const double esz = c->mlp_dtype ? 2.0 : 4.0;
-    double by = dX ? (double)g.rows * N * 4.0 : (double)g.rows * N * esz;
+    double by = dX ? (double)g.rows * N * 4.0 * ((write_dx ? 1 : 0) + (gx_acc ? 2 : 0)) : (double)g.rows * N * esz;
     if (mask) by += (double)g.rows * N * esz;
     for (int i = 0; i < np; ++i) {
         const Theta* t = i ? th1 : th0;
@@ -646,8 +649,11 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
         }
         a.M = -1; a.N = N; a.K = K;
         a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
-        if (dX) { a.Cf = dX; a.ldcf = N; a.rCf = N; a.epi = EPI_NONE; }
-        else {
+        if (dX) {
+            if (write_dx) { a.Cf = dX; a.ldcf = N; a.rCf = N; }
+            a.epi = EPI_NONE;
+            if (gx_acc) { a.Cacc = gx_acc; a.ldcacc = N; a.rCacc = N; a.cacc = gx_scale; }
+        } else {
             a.Cb = out->b; a.ldcb = N; a.rCb = N; a.epi = EPI_MASK; a.mask = mask->b; a.ld_mask = mask->ld;
         }
         launch_gemm_bf16(c->stream, a, g.bm);
@@ -780,7 +786,10 @@ static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, Theta& out, const
 
 // v <- v - alpha * (H v)_theta ;  w.dX [rows, FD] <- (H v)'s pooled-input part
 // (tangent pass through the forward and the backward pass of step s, direction (v, TX))
-static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, float alpha, bool refresh_v_copies) {
+// gx_acc (bf16 mode): the support rows of the sparse-gradient buffer, which take -alpha * (tangent of dX) in the
+// layer-1 product itself; need_dx: the tangent of dX is also wanted in w.dX (for the row arithmetic of the next step)
+static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, float alpha, bool refresh_v_copies,
+                     float* gx_acc, bool need_dx) {
     hipStream_t st = c->stream;
     const int L = c->L;
     Theta& v = w.v;
@@ -816,7 +825,7 @@ static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, f
     Theta vout = v;
     if (!refresh_v_copies) vout.b = nullptr;
     for (int l = L - 1; l >= 1; --l) {
-        if (l == 1) dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, nullptr, nullptr, w.dX);
+        if (l == 1) dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, nullptr, nullptr, w.dX, gx_acc, -alpha, need_dx || !gx_acc);
         else dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, &s.A[l - 1], &w.TD[l - 1], nullptr);
         const Act* ta_prev = l == 1 ? &w.TX : &w.TA[l - 1];
         const Act* a_prev = l == 1 ? &s.X : &s.A[l - 1];
@@ -1396,9 +1405,11 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             }
             for (int k = K - 1; k >= 0; --k) {
                 const StepState& s = w.steps[k];
-                hvp_step(c, gs, s, w, alpha, k > 0);
+                // bf16 with hidden layers: the layer-1 product adds -alpha * dX to the gradient buffer itself
+                const bool fused_gx = bf && L > 1 && F > 0;
+                hvp_step(c, gs, s, w, alpha, k > 0, fused_gx ? gxs : nullptr, k > 0);
                 if (F > 0) {
-                    {
+                    if (!fused_gx) {
                         Prof p(c, "axpy_gx", 12.0 * d.Ps * FD, 0);
                         launch_axpy(st, d.Ps * (int64_t)FD, -alpha, w.dX, gxs);
                     }
