@@ -85,6 +85,15 @@ typedef struct {
     int64_t* n_emb_rows;       /* DEVICE scalar: number of rows listed                           */
     int64_t emb_rows_capacity; /* rows that emb_rows / emb_grad can hold                         */
     float* task_loss;          /* DEVICE [T] per-task L^Query, or NULL                           */
+    float* emb_grad_table;     /* NULL, or DEVICE [sum rows_per_field, D] (the shape of params->emb):
+                                  the sparse meta-gradient is ADDED to it row by row (the summation
+                                  over tasks of Alg. 1's global back-propagation on xi, landing in a
+                                  caller-owned accumulator) and no list is produced: emb_rows,
+                                  emb_grad and emb_rows_capacity are ignored and *n_emb_rows = 0.
+                                  Every wave of tasks orders and reduces its own lookups, so the
+                                  call may hold more than 2^31 lookups per set; a row's sum is taken
+                                  in a fixed order for a given workspace size.  Must not alias
+                                  params->emb.                                                    */
 } gm_grads;
 
 /* Creates a context on `device` that enqueues on `hip_stream` (a hipStream_t, or NULL for the

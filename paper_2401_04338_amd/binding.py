@@ -41,7 +41,7 @@ class gm_params(C.Structure):
 class gm_grads(C.Structure):
     _fields_ = [("dW", C.POINTER(C.c_void_p)), ("db", C.POINTER(C.c_void_p)), ("emb_rows", C.c_void_p),
                 ("emb_grad", C.c_void_p), ("n_emb_rows", C.c_void_p), ("emb_rows_capacity", C.c_int64),
-                ("task_loss", C.c_void_p)]
+                ("task_loss", C.c_void_p), ("emb_grad_table", C.c_void_p)]
 
 
 class GMetaError(RuntimeError):
@@ -172,12 +172,22 @@ class GMeta:
             capacity=emb_rows_capacity)
 
     def meta_step(self, support, query, params, inner_lr: float, inner_steps: int, order: int,
-                  out: Optional[Dict[str, object]] = None, emb_rows_capacity: Optional[int] = None):
-        """gm_meta_step.  support/query: SetData-like; params: object with emb, W[], b[] device tensors."""
+                  out: Optional[Dict[str, object]] = None, emb_rows_capacity: Optional[int] = None,
+                  emb_grad_table: Optional[torch.Tensor] = None):
+        """gm_meta_step.  support/query: SetData-like; params: object with emb, W[], b[] device tensors.
+        emb_grad_table: a float32 device tensor shaped like params.emb that the sparse gradient is added to
+        (then no row list is produced)."""
         n_tasks = len(support.task_offsets) - 1
+        if emb_grad_table is not None:
+            if (emb_grad_table.dtype != torch.float32 or not emb_grad_table.is_contiguous()
+                    or tuple(emb_grad_table.shape) != (int(sum(self.rows_per_field)), self.emb_dim)
+                    or emb_grad_table.device != params.emb.device):
+                raise ValueError("emb_grad_table must be a contiguous float32 [sum rows_per_field, emb_dim] device tensor")
         if out is None:
             cap = emb_rows_capacity
-            if cap is None:
+            if emb_grad_table is not None:
+                cap = 0
+            elif cap is None:
                 cap = min(int(support.indices.numel() + query.indices.numel()), int(sum(self.rows_per_field)))
             out = self.alloc_outputs(n_tasks, cap)
         L = len(self.layer_dims) - 1
@@ -188,7 +198,8 @@ class GMeta:
         dWp = (C.c_void_p * L)(*[w.data_ptr() for w in out["dW"]])
         dbp = (C.c_void_p * L)(*[x.data_ptr() for x in out["db"]])
         gs = gm_grads(dWp, dbp, _ptr(out["emb_rows"]), _ptr(out["emb_grad"]), _ptr(out["n_emb_rows"]),
-                      int(out["capacity"]), _ptr(out["task_loss"]))
+                      int(out["capacity"]), _ptr(out["task_loss"]),
+                      _ptr(emb_grad_table) if emb_grad_table is not None else None)
         rc = self.lib.gm_meta_step(self._ctx, n_tasks, C.byref(ss), C.byref(qs), C.byref(ps), float(inner_lr),
                                    int(inner_steps), int(order), _ptr(out["loss"]), C.byref(gs))
         self._check(rc)

@@ -122,7 +122,7 @@ void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_row
 __global__ void seg_reduce_chunks_kernel(int D, int LG, const u32* __restrict__ keys, const u32* __restrict__ scan,
                                          const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
                                          int64_t capacity, int64_t n, const u32* __restrict__ sorted_vals,
-                                         const float* __restrict__ gx, float* emb_grad, float* partial) {
+                                         const float* __restrict__ gx, float* emb_grad, float* partial, float* table) {
     const int groups_per_block = blockDim.x / LG;
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
     if (g_in_block >= groups_per_block) return;
@@ -139,8 +139,14 @@ __global__ void seg_reduce_chunks_kernel(int D, int LG, const u32* __restrict__ 
             if (seg < 0 || seg >= n_valid) return;
             const int64_t s0 = seg_start[seg], s1 = seg_start[seg + 1];
             float* dst;
-            if (a == s0 && b == s1) dst = emb_grad + seg * D;                       // whole segment in this chunk
-            else if (s0 < a) dst = partial + (c * 2 + 0) * D;                       // began in an earlier chunk
+            if (a == s0 && b == s1) {                                               // whole segment in this chunk
+                if (table) {   // table-shaped output: added to the segment's row (rows of one call are distinct)
+                    float4* tp = reinterpret_cast<float4*>(table + (int64_t)keys[s0] * D + l * 4);
+                    *tp = add4(*tp, acc);
+                    return;
+                }
+                dst = emb_grad + seg * D;
+            } else if (s0 < a) dst = partial + (c * 2 + 0) * D;                     // began in an earlier chunk
             else dst = partial + (c * 2 + 1) * D;                                   // continues in a later chunk
             *reinterpret_cast<float4*>(dst + l * 4) = acc;
         };
@@ -182,7 +188,8 @@ __global__ void seg_reduce_chunks_kernel(int D, int LG, const u32* __restrict__ 
 // partial sums in chunk order (every such segment is the last one of exactly one chunk).
 __global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ keys, const u32* __restrict__ scan,
                                        const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
-                                       int64_t capacity, int64_t n, const float* __restrict__ partial, float* emb_grad) {
+                                       int64_t capacity, int64_t n, const float* __restrict__ partial, float* emb_grad,
+                                       float* table) {
     const int groups_per_block = blockDim.x / LG;
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
     if (g_in_block >= groups_per_block) return;
@@ -210,7 +217,12 @@ __global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ ke
         }
         for (; cc <= c1; ++cc)
             acc = add4(acc, *reinterpret_cast<const float4*>(partial + (cc * 2 + 0) * D + l * 4));
-        *reinterpret_cast<float4*>(emb_grad + seg * D + l * 4) = acc;
+        if (table) {
+            float4* tp = reinterpret_cast<float4*>(table + (int64_t)keys[s0] * D + l * 4);
+            *tp = add4(*tp, acc);
+        } else {
+            *reinterpret_cast<float4*>(emb_grad + seg * D + l * 4) = acc;
+        }
     }
 }
 
@@ -218,14 +230,14 @@ size_t seg_reduce_partial_floats(int64_t n, int D) { return (size_t)((n + SEG_CH
 
 void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const u32* seg_start,
                        const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
-                       float* emb_grad, float* partial) {
+                       float* emb_grad, float* partial, float* table) {
     if (n <= 0 || capacity <= 0) return;
     const int LG = D / 4;
     const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
     hipLaunchKernelGGL(seg_reduce_chunks_kernel, dim3(pool_grid(n_chunks, 256 / LG)), dim3(256), 0, st, D, LG, keys, scan,
-                       seg_start, n_rows, capacity, n, sorted_vals, gx, emb_grad, partial);
+                       seg_start, n_rows, capacity, n, sorted_vals, gx, emb_grad, partial, table);
     hipLaunchKernelGGL(seg_reduce_join_kernel, dim3(pool_grid(n_chunks, 256 / LG)), dim3(256), 0, st, D, LG, keys, scan,
-                       seg_start, n_rows, capacity, n, partial, emb_grad);
+                       seg_start, n_rows, capacity, n, partial, emb_grad, table);
 }
 
 __global__ void scatter_add_kernel(int D, int LG, float* table, const int64_t* __restrict__ rows,

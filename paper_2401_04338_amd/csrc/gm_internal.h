@@ -69,7 +69,7 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set
 int tf_sort_max_cap();
 
 void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
-                       const int32_t* indices, int64_t n_bags, const int32_t* row_map, u32 row0, u32* keys,
+                       const int32_t* indices, int64_t n_bags, int64_t lookup0, const int32_t* row_map, u32 row0, u32* keys,
                        u32* vals);
 // Stable LSD radix sort of (key, val) pairs on the low `bits` bits.  Returns the number of passes: after an odd
 // number the result is in (keys_tmp, vals_tmp), else in (keys, vals).
@@ -162,7 +162,8 @@ void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_row
 // keys: the sorted row keys; scan: exclusive scan of their segment-head flags (both as launch_segments left them)
 void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const u32* seg_start,
                        const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
-                       float* emb_grad, float* partial /* seg_reduce_partial_floats(n, D) */);
+                       float* emb_grad, float* partial /* seg_reduce_partial_floats(n, D) */,
+                       float* table /* null, or [all rows, D]: every segment is ADDED to its row instead of listed */);
 size_t seg_reduce_partial_floats(int64_t n, int D);
 void launch_scatter_add(hipStream_t st, int D, float* table, const int64_t* rows, const float* grad,
                         int64_t n_rows, float scale);

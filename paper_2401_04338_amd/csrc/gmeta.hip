@@ -213,6 +213,13 @@ struct StepState {  // what one inner step leaves behind for the second-order pa
     float* wL_copy = nullptr;   // bf16 mode: copy of the last-layer weights (the master is updated in place)
 };
 
+// buffers of one sort + segment reduction of (row key, gradient-buffer slot) pairs
+struct SortBufs {
+    u32 *keys = nullptr, *vals = nullptr, *keys_tmp = nullptr, *vals_tmp = nullptr, *hist = nullptr, *scan_tmp = nullptr,
+        *seg_start = nullptr;
+    float* seg_partial = nullptr;
+};
+
 struct WaveBufs {
     int32_t *row_off_s, *row_off_q, *real_off_s, *real_off_q;
     int32_t *sample_task_s, *sample_task_q, *row_task_s, *row_task_q;
@@ -236,6 +243,10 @@ struct WaveBufs {
     uint8_t* pair_mat;
     int64_t *pair_off_ss, *pair_off_qs, *pair_off_sq;
     u32* task_path;   // [Tw] 1: pair-count path, 0: sparse kernel (the counting kernel clears it on overflow)
+    // table-shaped sparse output only: the wave's own gradient buffer (support rows, then query rows) and sort
+    float* GX = nullptr;
+    int64_t* n_rows = nullptr;
+    SortBufs so;
 };
 
 struct WaveDims {
@@ -246,6 +257,7 @@ struct WaveDims {
     bool any_sparse = false;               // some task of the wave takes the sparse kernel
     bool pair_ss = false, pair_sq = false; // which kinds besides query x support
     int64_t pair_bytes = 0;
+    bool table = false;                    // the sparse gradient is reduced wave by wave into a table-shaped output
 };
 
 static Act alloc_act(const gm_ctx* c, Arena& ar, int64_t rows, int ld) {
@@ -269,6 +281,18 @@ static Theta alloc_theta(const gm_ctx* c, Arena& ar, int Tw, bool need_f) {
         t.sb = c->n_theta_b;
     }
     return t;
+}
+
+static void alloc_sort(const gm_ctx* c, Arena& ar, SortBufs& so, int64_t nnz, int64_t max_segs, size_t extra_hist_words,
+                       bool need_gx) {
+    so.keys = ar.get<u32>(nnz + 1);
+    so.vals = ar.get<u32>(nnz + 1);
+    so.keys_tmp = ar.get<u32>(nnz + 1);
+    so.vals_tmp = ar.get<u32>(nnz + 1);
+    so.hist = ar.get<u32>(radix_hist_words(nnz) + extra_hist_words);
+    so.scan_tmp = ar.get<u32>(scan_tmp_words(nnz));
+    so.seg_start = ar.get<u32>(std::min(nnz, max_segs) + 2);
+    so.seg_partial = need_gx ? ar.get<float>(seg_reduce_partial_floats(nnz, c->D)) : nullptr;
 }
 
 static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& d, int K, int order) {
@@ -375,6 +399,11 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
         w.pair_off_sq = ar.get<int64_t>(d.Tw + 1);
         w.pair_mat = ar.get<uint8_t>(d.pair_bytes + 64);
     }
+    if (d.table) {
+        w.GX = ar.get<float>((d.Ps + d.Pq) * (int64_t)std::max(c->FD, 1) + 4);
+        w.n_rows = ar.get<int64_t>(2);
+        alloc_sort(c, ar, w.so, d.nnz_s + d.nnz_q, c->field_base[c->F], 0, true);
+    }
 }
 
 struct BatchBufs {
@@ -382,8 +411,7 @@ struct BatchBufs {
     int32_t *prow_s, *prow_q, *prow_off_s, *prow_off_q;
     float *GX, *g_theta, *task_loss;
     Theta theta0;
-    u32 *keys, *vals, *keys_tmp, *vals_tmp, *hist, *scan_tmp, *seg_start;
-    float* seg_partial;
+    SortBufs so;
 };
 
 static void alloc_batch(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t Ss, int64_t Sq, int64_t Ps, int64_t Pq,
@@ -400,14 +428,8 @@ static void alloc_batch(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t
     if (c->mlp_dtype) b.theta0.b = ar.get<bf16_t>(c->n_theta_b);
     b.g_theta = ar.get<float>(c->n_theta);
     b.task_loss = ar.get<float>(T + 1);
-    b.keys = ar.get<u32>(nnz + 1);
-    b.vals = ar.get<u32>(nnz + 1);
-    b.keys_tmp = ar.get<u32>(nnz + 1);
-    b.vals_tmp = ar.get<u32>(nnz + 1);
-    b.hist = ar.get<u32>(radix_hist_words(nnz) + 2 * (size_t)(T + 1) * 2);
-    b.scan_tmp = ar.get<u32>(scan_tmp_words(nnz));
-    b.seg_start = ar.get<u32>(std::min(nnz, capacity) + 2);
-    b.seg_partial = need_gx ? ar.get<float>(seg_reduce_partial_floats(nnz, c->D)) : nullptr;
+    // the histogram area doubles as the scratch of the per-task lookup offsets (2 (T+1) 64-bit words) before any sort
+    alloc_sort(c, ar, b.so, nnz, capacity, 2 * (size_t)(T + 1) * 2, need_gx);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -521,7 +543,7 @@ extern "C" size_t gm_workspace_bytes(const gm_model_desc* model, int32_t n_tasks
 // ------------------------------------------------------------------------------------------------
 // argument checks shared by the entry points
 // ------------------------------------------------------------------------------------------------
-static int check_set(gm_ctx* c, const gm_set* s, int T, const char* name) {
+static int check_set(gm_ctx* c, const gm_set* s, int T, const char* name, bool any_nnz = false) {
     if (!s || !s->task_offsets) return fail(c, GM_ERR_ARG, "%s: null set or task_offsets", name);
     if (s->n_samples < 0 || s->nnz < 0) return fail(c, GM_ERR_ARG, "%s: negative size", name);
     if (s->task_offsets[0] != 0 || s->task_offsets[T] != s->n_samples)
@@ -532,7 +554,9 @@ static int check_set(gm_ctx* c, const gm_set* s, int T, const char* name) {
         return fail(c, GM_ERR_ARG, "%s: null array", name);
     if (s->nnz > 0 && !s->indices) return fail(c, GM_ERR_ARG, "%s: null indices", name);
     if (s->n_samples == 0 && s->nnz != 0) return fail(c, GM_ERR_ARG, "%s: nnz without samples", name);
-    if ((s->n_samples + (int64_t)T * 8) * (int64_t)std::max(c->F, 1) >= ((int64_t)1 << 31) || s->nnz >= ((int64_t)1 << 31))
+    // any_nnz: the call orders lookups wave by wave, so only a wave's lookups must number below 2^31
+    if ((s->n_samples + (int64_t)T * 8) * (int64_t)std::max(c->F, 1) >= ((int64_t)1 << 31) ||
+        (!any_nnz && s->nnz >= ((int64_t)1 << 31)))
         return fail(c, GM_ERR_ARG, "%s: more than 2^31 bags or lookups in one call", name);
     return GM_OK;
 }
@@ -882,6 +906,7 @@ struct Batch {  // host-side description of one call
     const gm_set *sup, *qry;
     std::vector<int64_t> poff_s, poff_q;  // padded row offsets per task, whole batch
     std::vector<int64_t> ls, lq;          // lookup offsets per task (filled when several waves are needed)
+    bool table = false;                   // table-shaped sparse output: every wave sorts and reduces its own lookups
     BatchBufs b;
 };
 
@@ -929,29 +954,41 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
     return GM_OK;
 }
 
-static int global_order(gm_ctx* c, Batch& B, int64_t* emb_rows, int64_t* seg_counts, int64_t capacity,
-                        int64_t* n_rows) {
+// The lookups of samples [s0, s1) of the support set and [q0, q1) of the query set, ordered by global row and cut into
+// one segment per distinct row.  Gradient-buffer rows are row0_* + the batch-wide padded row of the sample (mod 2^32).
+struct SortRange {
+    int64_t s0, s1, q0, q1;      // samples
+    int64_t ls0, ls1, lq0, lq1;  // their lookups
+    u32 row0_s, row0_q;
+};
+
+static int global_order(gm_ctx* c, Batch& B, SortBufs& so, const SortRange& r, int64_t* emb_rows, int64_t* seg_counts,
+                        int64_t capacity, int64_t* n_rows) {
     hipStream_t st = c->stream;
     const int F = c->F;
     const gm_set *sup = B.sup, *qry = B.qry;
     BatchBufs& b = B.b;
-    const int64_t nnz = sup->nnz + qry->nnz;
+    const int64_t n_s = r.ls1 - r.ls0, nnz = n_s + (r.lq1 - r.lq0);
     Prof p(c, "global_sort", 0, 0);
     if (F > 0) {
-        launch_build_keys(st, F, c->d_field_base, sup->bag_offsets, sup->indices, sup->n_samples * F, b.prow_s, 0u, b.keys,
-                          b.vals);
-        launch_build_keys(st, F, c->d_field_base, qry->bag_offsets, qry->indices, qry->n_samples * F, b.prow_q,
-                          (u32)B.poff_s[B.T], b.keys + sup->nnz, b.vals + sup->nnz);
+        launch_build_keys(st, F, c->d_field_base, sup->bag_offsets + r.s0 * F, sup->indices, (r.s1 - r.s0) * F, r.ls0,
+                          b.prow_s + r.s0, r.row0_s, so.keys, so.vals);
+        launch_build_keys(st, F, c->d_field_base, qry->bag_offsets + r.q0 * F, qry->indices, (r.q1 - r.q0) * F, r.lq0,
+                          b.prow_q + r.q0, r.row0_q, so.keys + n_s, so.vals + n_s);
     }
     int bits = 1;
     while (((int64_t)1 << bits) < c->field_base[c->F]) ++bits;
-    if (launch_radix_sort(st, b.keys, b.vals, b.keys_tmp, b.vals_tmp, nnz, bits, b.hist) & 1) {
-        std::swap(b.keys, b.keys_tmp);   // an odd number of passes leaves the result in the second pair of buffers
-        std::swap(b.vals, b.vals_tmp);
+    if (launch_radix_sort(st, so.keys, so.vals, so.keys_tmp, so.vals_tmp, nnz, bits, so.hist) & 1) {
+        std::swap(so.keys, so.keys_tmp);   // an odd number of passes leaves the result in the second pair of buffers
+        std::swap(so.vals, so.vals_tmp);
     }
-    launch_segments(st, b.keys, nnz, b.keys_tmp, b.scan_tmp, emb_rows, b.seg_start, seg_counts, capacity, n_rows,
+    launch_segments(st, so.keys, nnz, so.keys_tmp, so.scan_tmp, emb_rows, so.seg_start, seg_counts, capacity, n_rows,
                     c->d_status);
     return GM_OK;
+}
+
+static SortRange whole_batch_range(const Batch& B) {
+    return SortRange{0, B.sup->n_samples, 0, B.qry->n_samples, 0, B.sup->nnz, 0, B.qry->nnz, 0u, (u32)B.poff_s[B.T]};
 }
 
 static inline int64_t pad64(int64_t n) { return (n + 63) & ~(int64_t)63; }
@@ -988,6 +1025,7 @@ static int64_t pair_layout(const gm_ctx* c, const Batch& B, const WavePlan& p, i
 
 static WaveDims wave_dims(const gm_ctx* c, const Batch& B, const WavePlan& p, int bm, int K, int order) {
     WaveDims d;
+    d.table = B.table;
     for (int t = p.t0; t < p.t1; ++t) {
         if (task_pair_ok(c, B, t, K)) d.pair = true;
         else d.any_sparse = true;
@@ -1025,7 +1063,7 @@ static int plan_waves(gm_ctx* c, Batch& B, size_t avail, int K, int order, int b
     bool have_offsets = false;
     auto fetch = [&]() -> int {
         if (have_offsets || F == 0) return GM_OK;
-        int64_t* d = reinterpret_cast<int64_t*>(B.b.hist);  // scratch: the histogram area is free until the global sort
+        int64_t* d = reinterpret_cast<int64_t*>(B.b.so.hist);  // scratch: the histogram area is free until the global sort
         hipLaunchKernelGGL(gather_task_lookup_offsets, dim3((T + 256) / 256), dim3(256), 0, c->stream, B.b.toff_s,
                            sup->bag_offsets, F, T, d);
         hipLaunchKernelGGL(gather_task_lookup_offsets, dim3((T + 256) / 256), dim3(256), 0, c->stream, B.b.toff_q,
@@ -1060,6 +1098,8 @@ static int plan_waves(gm_ctx* c, Batch& B, size_t avail, int K, int order, int b
             p.ps0 = B.poff_s[p.t0]; p.ps1 = B.poff_s[p.t1]; p.pq0 = B.poff_q[p.t0]; p.pq1 = B.poff_q[p.t1];
             p.ls0 = B.ls[p.t0]; p.ls1 = B.ls[p.t1]; p.lq0 = B.lq[p.t0]; p.lq1 = B.lq[p.t1];
             plans.push_back(p);
+            // a wave's lookups are numbered in 32 bits
+            if ((p.ls1 - p.ls0) + (p.lq1 - p.lq0) >= ((int64_t)1 << 31)) { fits = false; break; }
             Arena ar;
             ar.cap = avail;
             WaveBufs w;
@@ -1141,15 +1181,17 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                             float alpha, int32_t K, int32_t order, float* loss, gm_grads* out) {
     if (!c) return GM_ERR_ARG;
     if (T < 0 || K < 0 || (order != 1 && order != 2)) return fail(c, GM_ERR_ARG, "bad n_tasks / inner_steps / order");
-    int rc = check_set(c, sup, T, "support");
+    if (!out) return fail(c, GM_ERR_ARG, "null outputs");
+    float* const table = c->F > 0 ? out->emb_grad_table : nullptr;
+    int rc = check_set(c, sup, T, "support", table != nullptr);
     if (rc != GM_OK) return rc;
-    rc = check_set(c, qry, T, "query");
+    rc = check_set(c, qry, T, "query", table != nullptr);
     if (rc != GM_OK) return rc;
     if (!params || !params->W || !params->b || (c->F > 0 && !params->emb)) return fail(c, GM_ERR_ARG, "null params");
-    if (!loss || !out || !out->dW || !out->db || !out->n_emb_rows) return fail(c, GM_ERR_ARG, "null outputs");
+    if (!loss || !out->dW || !out->db || !out->n_emb_rows) return fail(c, GM_ERR_ARG, "null outputs");
     for (int l = 0; l < c->L; ++l)
         if (!params->W[l] || !params->b[l] || !out->dW[l] || !out->db[l]) return fail(c, GM_ERR_ARG, "null layer pointer");
-    if (out->emb_rows_capacity < 0 || (out->emb_rows_capacity > 0 && (!out->emb_rows || !out->emb_grad)))
+    if (!table && (out->emb_rows_capacity < 0 || (out->emb_rows_capacity > 0 && (!out->emb_rows || !out->emb_grad))))
         return fail(c, GM_ERR_ARG, "bad sparse output buffers");
     HIPCHK(c, hipSetDevice(c->device));
     hipStream_t st = c->stream;
@@ -1157,13 +1199,14 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     const bool bf = c->mlp_dtype != 0;
     const int64_t nt = c->n_theta;
     const int64_t nnz = sup->nnz + qry->nnz;
-    const int64_t capacity = out->emb_rows_capacity;
+    const int64_t capacity = table ? 0 : out->emb_rows_capacity;
 
     Arena ar;
     ar.base = c->ws; ar.cap = c->ws_bytes; ar.off = c->persistent;
     Batch B;
     B.T = T; B.sup = sup; B.qry = qry;
-    rc = begin_batch(c, B, ar, capacity, true);
+    B.table = table != nullptr;
+    rc = begin_batch(c, B, ar, capacity, !B.table);
     if (rc != GM_OK) return rc;
     BatchBufs& b = B.b;
     const int64_t Ps_tot = B.poff_s[T];
@@ -1182,7 +1225,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                                    nullptr, 0);
     }
     launch_fill_f32(st, b.g_theta, nt, 0.f);
-    if (FD > 0) launch_fill_f32(st, b.GX, (Ps_tot + B.poff_q[T]) * (int64_t)FD, 0.f);
+    if (FD > 0 && !table) launch_fill_f32(st, b.GX, (Ps_tot + B.poff_q[T]) * (int64_t)FD, 0.f);
     float* task_loss = out->task_loss ? out->task_loss : b.task_loss;
 
     for (const WavePlan& wp : plans) {
@@ -1388,8 +1431,10 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
 
         // outer forward/backward on the query set with the adapted parameters
         if (bf && K > 0) launch_copy_tail(st, F > 0 ? FD : 0, w.Xq0, d.Pq, nullptr, ld0, Xq.b);
-        float* gxq = b.GX + (Ps_tot + wp.pq0) * (int64_t)FD;
-        float* gxs = b.GX + wp.ps0 * (int64_t)FD;
+        // gradient w.r.t. the pooled inputs: the wave's rows of the batch-wide buffer, or the wave's own buffer
+        float* gxs = table ? w.GX : b.GX + wp.ps0 * (int64_t)FD;
+        float* gxq = table ? w.GX + d.Ps * (int64_t)FD : b.GX + (Ps_tot + wp.pq0) * (int64_t)FD;
+        if (table && FD > 0) launch_fill_f32(st, w.GX, (d.Ps + d.Pq) * (int64_t)FD, 0.f);
         Pass pq{&Xq, &w.Aq, &w.Dq, w.dLq, w.zq};
         forward_backward(c, gq, labels_q, pq, th, thf, thf_stride, w.loss_q, F > 0 ? gxq : nullptr);
         colsum_f32(c, gq, 1, w.loss_q, 1, task_loss + wp.t0, 1, nullptr, 0, 0.f, 1.f);
@@ -1425,6 +1470,17 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             Prof p(c, "reduce_tasks", 4.0 * Tw * nt, 0);
             launch_reduce_tasks(st, w.v.f, nt, Tw, nt, b.g_theta, 1);
         }
+        // table-shaped sparse output: the wave's lookups are ordered by row and every row's sum is added to its row of
+        // the table (rows are distinct within a wave; waves follow each other on the stream)
+        if (table) {
+            const SortRange r{wp.s0, wp.s1, wp.q0, wp.q1, wp.ls0, wp.ls1, wp.lq0, wp.lq1,
+                              (u32)(0 - (uint64_t)wp.ps0), (u32)((uint64_t)d.Ps - (uint64_t)wp.pq0)};
+            const int64_t nw = d.nnz_s + d.nnz_q;
+            global_order(c, B, w.so, r, nullptr, nullptr, nw, w.n_rows);
+            Prof p(c, "seg_reduce", (double)nw * (4.0 * D + 4), 0);
+            launch_seg_reduce(st, D, w.so.keys, w.so.keys_tmp, w.so.seg_start, w.n_rows, nw, nw, w.so.vals, w.GX, nullptr,
+                              w.so.seg_partial, table);
+        }
     }
 
     // outputs: dense meta-gradient, loss, coalesced sparse meta-gradient
@@ -1434,12 +1490,15 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     }
     launch_sum_to_scalar(st, task_loss, T, loss, 0);
     launch_fill_u32(st, c->d_status, ST_WORDS, 0);
-    global_order(c, B, out->emb_rows, nullptr, capacity, out->n_emb_rows);
-    if (F > 0) {
-        Prof p(c, "seg_reduce", (double)nnz * (4.0 * D + 4), 0);
-        // the second sort buffer is free after the sort: it holds the partial sums of chunk-crossing segments
-        launch_seg_reduce(st, D, b.keys, b.keys_tmp, b.seg_start, out->n_emb_rows, capacity, nnz, b.vals, b.GX,
-                          out->emb_grad, b.seg_partial);
+    if (table) {
+        launch_fill_u32(st, reinterpret_cast<u32*>(out->n_emb_rows), 2, 0u);
+    } else {
+        global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows);
+        if (F > 0) {
+            Prof p(c, "seg_reduce", (double)nnz * (4.0 * D + 4), 0);
+            launch_seg_reduce(st, D, b.so.keys, b.so.keys_tmp, b.so.seg_start, out->n_emb_rows, capacity, nnz, b.so.vals,
+                              b.GX, out->emb_grad, b.so.seg_partial, nullptr);
+        }
     }
     u32 hs[ST_WORDS];
     rc = read_status(c, hs);
@@ -1583,7 +1642,7 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
         packed0 += h_total;
     }
     launch_fill_u32(st, c->d_status, ST_WORDS, 0);
-    global_order(c, B, emb_rows, seg_counts, capacity, n_emb_rows);
+    global_order(c, B, B.b.so, whole_batch_range(B), emb_rows, seg_counts, capacity, n_emb_rows);
     u32 hs[ST_WORDS];
     rc = read_status(c, hs);
     if (rc != GM_OK) return rc;

@@ -510,7 +510,7 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set
 // One workgroup per 256 consecutive bags: their lookups are one contiguous range, walked by all lanes with
 // coalesced reads and writes; the bag of a lookup is found by bisection of the 257 staged offsets.
 __global__ __launch_bounds__(256) void build_keys_kernel(int F, const int64_t* field_base, const int64_t* bag_offsets,
-                                                         const int32_t* indices, int64_t n_bags,
+                                                         const int32_t* indices, int64_t n_bags, int64_t lookup0,
                                                          const int32_t* __restrict__ row_map, u32 row0, u32* keys, u32* vals) {
     __shared__ int64_t offs[257];
     const int64_t b0 = (int64_t)blockIdx.x * 256;
@@ -527,16 +527,19 @@ __global__ __launch_bounds__(256) void build_keys_kernel(int F, const int64_t* f
         }
         const int64_t b = b0 + lo;
         const int f = (int)(b % F);
-        keys[p] = (u32)field_base[f] + (u32)indices[p];
-        vals[p] = (row0 + (u32)row_map[b / F]) * (u32)F + (u32)f;  // (row of the sample, field) in the gradient buffer
+        keys[p - lookup0] = (u32)field_base[f] + (u32)indices[p];
+        vals[p - lookup0] = (row0 + (u32)row_map[b / F]) * (u32)F + (u32)f;  // (row of the sample, field) in the gradient buffer
     }
 }
 
+// bag_offsets / row_map point at the first bag / sample of the range (a multiple of F bags); lookup0 is the range's first
+// lookup: keys and vals are numbered from it
 void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
-                       const int32_t* indices, int64_t n_bags, const int32_t* row_map, u32 row0, u32* keys, u32* vals) {
+                       const int32_t* indices, int64_t n_bags, int64_t lookup0, const int32_t* row_map, u32 row0, u32* keys,
+                       u32* vals) {
     if (n_bags <= 0) return;
     hipLaunchKernelGGL(build_keys_kernel, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, st, F, field_base,
-                       bag_offsets, indices, n_bags, row_map, row0, keys, vals);
+                       bag_offsets, indices, n_bags, lookup0, row_map, row0, keys, vals);
 }
 
 #define RS_NT 256
@@ -695,7 +698,7 @@ __global__ void seg_emit_kernel(const u32* keys, int64_t n, const u32* scan, int
     const bool head = (i == 0 || keys[i] != keys[i - 1]);
     const u32 seg = scan[i];
     if (head && (int64_t)seg < capacity) {
-        emb_rows[seg] = (int64_t)keys[i];
+        if (emb_rows) emb_rows[seg] = (int64_t)keys[i];
         seg_start[seg] = (u32)i;
     }
     if (i == n - 1) {

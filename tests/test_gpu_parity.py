@@ -151,6 +151,44 @@ def test_waves_give_the_same_result(gm):
     small.close()
 
 
+@pytest.mark.parametrize("waves", [1, 3], ids=["one_wave", "several_waves"])
+def test_table_shaped_sparse_gradient(gm, waves):
+    """emb_grad_table: the sparse meta-gradient is added into a caller-owned table, wave by wave.  Held against the
+    oracle's row list scattered into a table; with one wave it is bit for bit the listed gradient."""
+    cfg = SMALL.with_(n_tasks=8)
+    sup, qry, params = _inputs(cfg)
+    big = gm.from_config(cfg, workspace_bytes=2 << 30)
+    dev = big.device
+    ctx = big
+    if waves > 1:
+        need = big.workspace_bytes(8, sup.n_samples, qry.n_samples, sup.nnz, qry.nnz, 2, 2)
+        ctx = gm.from_config(cfg, workspace_bytes=int(need * 0.3))
+    ds, dq, dp = _to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev)
+    listed = big.meta_step(ds, dq, dp, cfg.inner_lr, 2, 2)
+    n = int(listed["n_emb_rows"].item())
+    table = torch.zeros_like(dp.emb)
+    out = ctx.meta_step(ds, dq, dp, cfg.inner_lr, 2, 2, emb_grad_table=table)
+    assert int(out["n_emb_rows"].item()) == 0
+    assert torch.equal(out["task_loss"], listed["task_loss"])
+    want = torch.zeros_like(table)
+    want[listed["emb_rows"][:n]] = listed["emb_grad"][:n]
+    if waves == 1:
+        assert torch.equal(table, want)
+        assert torch.equal(out["dW"][0], listed["dW"][0])
+    ref = O.meta_step(oracle_model(cfg), params.numpy(), sup.numpy(), qry.numpy(), cfg.inner_lr, 2, 2)
+    got = table.cpu().numpy()
+    assert np.all(np.isin(np.flatnonzero(np.abs(got).sum(1) > 0), ref["emb_rows"]))   # no other row is written
+    e = max(rel_err(got[ref["emb_rows"]], ref["emb_grad"]))
+    print("table mode", waves, f"emb_grad {e:.2e}", flush=True)
+    assert e <= TOL_FP32
+    # a second call keeps accumulating
+    ctx.meta_step(ds, dq, dp, cfg.inner_lr, 2, 2, emb_grad_table=table)
+    assert max(rel_err(table.cpu().numpy()[ref["emb_rows"]], 2.0 * ref["emb_grad"])) <= TOL_FP32
+    if ctx is not big:
+        ctx.close()
+    big.close()
+
+
 def test_determinism(gm):
     cfg = SMALL.with_(n_tasks=4)
     sup, qry, params = _inputs(cfg)
