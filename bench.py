@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--tasks", type=int, default=None,
                     help="run only the first N tasks of the config (same per-task data; a share of a config too large for one call)")
     ap.add_argument("--workspace-gib", type=float, default=None)
+    ap.add_argument("--sparse-out", choices=("list", "table"), default=None,
+                    help="list: coalesced (rows, gradient) lists; table: added into a table-shaped accumulator wave by wave "
+                         "(default: list while the call has fewer than 2^31 lookups per set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--batches", type=int, default=2, help="distinct pre-generated batches cycled through")
@@ -76,8 +79,10 @@ def main():
     probe = GMeta.from_config(cfg, workspace_bytes=1 << 20)
     need = max(probe.workspace_bytes(cfg.n_tasks, s.n_samples, q.n_samples, s.nnz, q.nnz, K, order) for s, q in batches)
     probe.close()
+    sparse_out = args.sparse_out or ("table" if max(sup0.nnz, qry0.nnz) >= 2 ** 31 else "list")
+    table = torch.zeros_like(params.emb) if sparse_out == "table" else None
     free_b, _total = torch.cuda.mem_get_info()
-    cap_rows = min(nnz, cfg.total_rows)
+    cap_rows = 0 if table is not None else min(nnz, cfg.total_rows)
     out_bytes = cap_rows * (cfg.emb_dim * 4 + 8)
     ws = int(need * 1.02)
     if args.workspace_gib is not None:
@@ -88,7 +93,7 @@ def main():
 
     def step(i):
         s, q = batches[i % len(batches)]
-        return ctx.meta_step(s, q, params, cfg.inner_lr, K, order, out=out)
+        return ctx.meta_step(s, q, params, cfg.inner_lr, K, order, out=out, emb_grad_table=table)
 
     for i in range(args.warmup):
         step(i)
@@ -172,7 +177,7 @@ def main():
         "config": {"workload": cfg.name, "n_tasks": cfg.n_tasks, "samples_per_step": S, "lookups_per_step": nnz,
                    "n_fields": cfg.n_fields, "rows_per_field": cfg.rows_per_field, "emb_dim": cfg.emb_dim,
                    "mlp": list(cfg.layer_dims), "inner_steps": K, "order": order, "inner_lr": cfg.inner_lr,
-                   "workspace_gib": ws / 2 ** 30, "batches_cycled": len(batches), "loss": loss,
+                   "sparse_out": sparse_out, "workspace_gib": ws / 2 ** 30, "batches_cycled": len(batches), "loss": loss,
                    "input_generation_s": gen_s},
         "roofline": roof,
         "roofline_gemm": roof_gemm,

@@ -1124,8 +1124,9 @@ static int begin_batch(gm_ctx* c, Batch& B, Arena& ar, int64_t capacity, bool ne
     }
     if ((B.poff_s[T] + B.poff_q[T]) * (int64_t)std::max(c->F, 1) >= ((int64_t)1 << 32))
         return fail(c, GM_ERR_ARG, "more than 2^32 (row, field) pairs in one call");
-    alloc_batch(c, ar, B.b, T, B.sup->n_samples, B.qry->n_samples, B.poff_s[T], B.poff_q[T], B.sup->nnz + B.qry->nnz,
-                capacity, need_gx);
+    // (no batch-wide sort when every wave reduces its own lookups into a table)
+    alloc_batch(c, ar, B.b, T, B.sup->n_samples, B.qry->n_samples, B.poff_s[T], B.poff_q[T],
+                B.table ? 0 : B.sup->nnz + B.qry->nnz, capacity, need_gx);
     if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "workspace too small for the batch-level buffers (%zu needed)", ar.off);
     hipStream_t st = c->stream;
     HIPCHK(c, hipMemcpyAsync(B.b.toff_s, B.sup->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
