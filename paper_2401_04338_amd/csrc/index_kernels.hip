@@ -207,10 +207,10 @@ __device__ __forceinline__ int load_tf_keys(u64* keys, int* sh_fill, const SetVi
 // a time, with ballot matching (equal digits keep their order), and the per-(digit, wave) counts are turned into
 // positions.  Returns the buffer (one of the two) that holds the result.  At most TFR_ROUNDS * 64 keys per wave
 // and TFR_MAXS bags per task and set.
-#define TFR_ROUNDS 8
+#define TFR_ROUNDS 16
 #define TFR_MAXS 2048
 struct TfRadixLds {
-    u64 *buf_a, *buf_b;     // [cap] each
+    u64* buf;               // [cap]: every pass holds all keys in registers between its read and its write
     u32 *sbase, *sp0;       // [ms + 1], [ms]: first key / first lookup (relative to the wave's) of every bag
     uint16_t* cnt;          // [waves][256]
     u32* digstart;          // [256]
@@ -250,7 +250,7 @@ __device__ __forceinline__ u64* tf_radix_sorted(const TfRadixLds& L, const SetVi
         }
         const int j = e - (int)L.sbase[lo];
         const u32 idx = (u32)v.indices[v.lookup0 + L.sp0[lo] + j];
-        L.buf_a[e] = ((u64)(fb + idx) << 32) | ((u64)lo << 16) | (u64)j;
+        L.buf[e] = ((u64)(fb + idx) << 32) | ((u64)lo << 16) | (u64)j;
     }
     const int passes = (bits + 7) / 8 > 0 ? (bits + 7) / 8 : 1;
     const int width = (bits + passes - 1) / passes > 0 ? (bits + passes - 1) / passes : 1;
@@ -258,8 +258,8 @@ __device__ __forceinline__ u64* tf_radix_sorted(const TfRadixLds& L, const SetVi
     const int chunk = ((n + W * WAVE - 1) / (W * WAVE)) * WAVE;   // keys per wave, a multiple of 64
     const int rounds = chunk / WAVE;
     const u64 lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    u64* in = L.buf_a;
-    u64* out = L.buf_b;
+    u64* const in = L.buf;
+    u64* const out = L.buf;   // in place: the barriers between ranking and placing separate the last read from the first write
     for (int pass = 0; pass < passes; ++pass) {
         const int shift = pass * width;
         for (int i = threadIdx.x; i < W * NB; i += NT) L.cnt[i] = 0;
@@ -313,10 +313,9 @@ __device__ __forceinline__ u64* tf_radix_sorted(const TfRadixLds& L, const SetVi
                 }
             }
         }
-        u64* tmp = in; in = out; out = tmp;
         __syncthreads();   // every wave has placed its keys and is done with the counters
     }
-    return in;
+    return L.buf;
 }
 
 // cap: key capacity of an LDS buffer (bitonic: a power of two); ms: most samples a task has in one set (radix)
@@ -329,9 +328,8 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms) {
     u64* sh_keys = sh_dyn;
     TfRadixLds L;
     if (RADIX) {
-        L.buf_a = sh_dyn;
-        L.buf_b = sh_dyn + cap;
-        u32* w32 = reinterpret_cast<u32*>(sh_dyn + 2 * cap) + (LDS_UNIQ ? cap : 0);
+        L.buf = sh_dyn;
+        u32* w32 = reinterpret_cast<u32*>(sh_dyn + cap) + (LDS_UNIQ ? cap : 0);
         L.sbase = w32;
         L.sp0 = w32 + (ms + 1);
         L.cnt = reinterpret_cast<uint16_t*>(w32 + 2 * ms + 2);
@@ -343,7 +341,7 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms) {
     const u32 fb = (u32)a.field_base[f];
     const u32 n = a.cnt_sup[tf], B = a.base_sup[tf];
     const u32 nq = a.cnt_qry[tf], Bq = a.base_qry[tf];
-    u32* uniq = LDS_UNIQ ? (u32*)(sh_dyn + (RADIX ? 2 : 1) * cap) : (a.slot_rows + B);
+    u32* uniq = LDS_UNIQ ? (u32*)(sh_dyn + cap) : (a.slot_rows + B);
     int bits = 1;
     while (((int64_t)1 << bits) < a.field_base[f + 1] - a.field_base[f]) ++bits;
     int n_unique = 0;
@@ -364,15 +362,18 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms) {
         const int chunk = ((int)n + blockDim.x - 1) / blockDim.x;
         const int i0 = min((int)n, (int)threadIdx.x * chunk), i1 = min((int)n, i0 + chunk);
         int c = 0;
+        // row of the key before this thread's range, read before any key is rewritten below
+        const u32 row_before = i0 > 0 && i0 < (int)n ? (u32)(sh_keys[i0 - 1] >> 32) : ~0u;
         for (int i = i0; i < i1; ++i) c += (i == 0) || ((sh_keys[i] >> 32) != (sh_keys[i - 1] >> 32));
         int slot = block_excl_scan(c, sh_scan, &n_unique) - 1;
-        // radix: the slot of every key goes to the idle key buffer first, so that the second sweep below has
-        // independent iterations and reads only LDS (the bag tables of the sort give every lookup's position)
-        uint16_t* slot_of = RADIX ? reinterpret_cast<uint16_t*>(sh_keys == L.buf_a ? L.buf_b : L.buf_a) : nullptr;
+        // radix: the slot of every key replaces its row first, so that the second sweep below has independent
+        // iterations and reads only LDS (the bag tables of the sort give every lookup's position)
+        u32 prev = row_before;
         for (int i = i0; i < i1; ++i) {
             const u64 key = sh_keys[i];
             const u32 row = (u32)(key >> 32);
-            const bool head = (i == 0) || (row != (u32)(sh_keys[i - 1] >> 32));
+            const bool head = RADIX ? (i == 0 || row != prev) : ((i == 0) || (row != (u32)(sh_keys[i - 1] >> 32)));
+            prev = row;
             if (head) {
                 ++slot;
                 a.slot_start[B + tf + slot] = (int32_t)(B + i);
@@ -380,7 +381,7 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms) {
                 if (LDS_UNIQ) uniq[slot] = row;
             }
             if (RADIX) {
-                slot_of[i] = (uint16_t)slot;
+                sh_keys[i] = ((u64)(u32)slot << 32) | (key & 0xFFFFFFFFull);
             } else {
                 const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
                 const int64_t p = a.sup.bag_offsets[(s_lo + s) * a.F + f] + j;
@@ -394,7 +395,7 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms) {
             for (int i = threadIdx.x; i < (int)n; i += blockDim.x) {
                 const u64 key = sh_keys[i];
                 const int s = (int)((key >> 16) & 0xFFFF), j = (int)(key & 0xFFFF);
-                const int sl = (int)slot_of[i];
+                const int sl = (int)(key >> 32);
                 a.sup_slot[L.sp0[s] + j] = sl;
                 a.sup_sorted[B + i] = make_int2(prow0 + s, sl);
             }
@@ -476,13 +477,14 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set
     dim3 grid(a.F, a.Tw);
     int cap = 1024;
     while (cap < max_tf) cap <<= 1;
-    if (cap <= 8192 && max_set_rows <= TFR_MAXS) {   // radix sort in LDS
-        const int kcap = (max_tf + 63) / 64 * 64 + 64;                // keys per buffer
+    if (max_set_rows <= TFR_MAXS) {   // radix sort in LDS
+        const int kcap = (max_tf + 63) / 64 * 64 + 64;                // keys in the buffer
         const int ms = max_set_rows > 0 ? max_set_rows : 1;
-        const int nt = cap / 8 < 256 ? 256 : cap / 8;                 // at most TFR_ROUNDS rounds of 64 keys per wave
+        int nt = cap / 8;                                             // at most 8 rounds of 64 keys per wave while the block
+        nt = nt < 256 ? 256 : (nt > 1024 ? 1024 : nt);                // allows (TFR_ROUNDS = 16 at the largest capacity)
         const size_t fixed = (size_t)(2 * ms + 2) * 4 + (size_t)(nt / WAVE) * 256 * 2;
-        const bool lds_uniq = (size_t)kcap * 20 + fixed <= 80 * 1024;   // the row list in LDS while two workgroups fit a compute unit
-        const size_t shmem = (size_t)kcap * 16 + (lds_uniq ? (size_t)kcap * 4 : 0) + fixed;
+        const bool lds_uniq = (size_t)kcap * 12 + fixed <= 80 * 1024;   // the row list in LDS while two workgroups fit a compute unit
+        const size_t shmem = (size_t)kcap * 8 + (lds_uniq ? (size_t)kcap * 4 : 0) + fixed;
         if (lds_uniq) {
             hipFuncSetAttribute((const void*)tf_sort_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
             hipLaunchKernelGGL((tf_sort_kernel<true, true>), grid, dim3(nt), shmem, st, a, kcap, ms);
