@@ -550,20 +550,29 @@ void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const i
 #define RS_WAVES (RS_NT / WAVE)
 
 // Digits are BITS wide (8 or 9): 25-bit row keys sort in three 9-bit passes instead of four 8-bit ones.
+// Tiles are dealt to workgroups so that every XCD (workgroups are spread over the 8 XCDs round-robin) walks one
+// contiguous range of tiles: the pieces that neighbouring tiles write into a digit's output range then meet in one L2.
+__device__ __forceinline__ int rs_tile_of_block(int nblk) {
+    const int per = (nblk + 7) >> 3;
+    return (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+}
+
 template <int BITS>
 __global__ void radix_hist_kernel(const u32* keys, int64_t n, int shift, u32* hist, int nblk) {
     constexpr int NB = 1 << BITS;
     __shared__ u32 h[NB];
+    const int tile = rs_tile_of_block(nblk);
+    if (tile >= nblk) return;
     for (int i = threadIdx.x; i < NB; i += RS_NT) h[i] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * RS_TILE;
+    const int64_t base = (int64_t)tile * RS_TILE;
 #pragma unroll
     for (int i = 0; i < RS_ITEMS; ++i) {
         const int64_t idx = base + i * RS_NT + threadIdx.x;
         if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & (NB - 1)], 1u);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < NB; i += RS_NT) hist[(size_t)i * nblk + blockIdx.x] = h[i];
+    for (int i = threadIdx.x; i < NB; i += RS_NT) hist[(size_t)i * nblk + tile] = h[i];
 }
 
 // Stable scatter: every wave owns a contiguous 1/4 of the tile and ranks its keys round by round (64
@@ -578,9 +587,11 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
     __shared__ u32 svals[RS_TILE];
     __shared__ int sh_scan[RS_WAVES + 2];
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    const int tile = rs_tile_of_block(nblk);
+    if (tile >= nblk) return;
     for (int i = threadIdx.x; i < RS_WAVES * NB; i += RS_NT) (&cnt[0][0])[i] = 0;
     __syncthreads();
-    const int64_t tile0 = (int64_t)blockIdx.x * RS_TILE;
+    const int64_t tile0 = (int64_t)tile * RS_TILE;
     u32 key[RS_ITEMS], val[RS_ITEMS], rank[RS_ITEMS];
     const u64 lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
@@ -604,9 +615,9 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
             cnt[w][d] = old + (u32)__popcll(peers);
         }
         old = __shfl(old, leader, WAVE);
-        rank[r] = old + (u32)__popcll(peers & lt_mask);
-        __syncthreads();
+        rank[r] = old + (u32)__popcll(peers & lt_mask);   // (a wave's counters are its own: no barrier between rounds)
     }
+    __syncthreads();
     // per digit: exclusive prefix over the waves, block total, start of each digit inside the tile
     u32 total[DPT];
     u32 mine = 0;
@@ -648,7 +659,7 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
         if (pos < tile_count) {
             const u32 k = skeys[pos];
             const u32 d = (k >> shift) & (NB - 1);
-            const size_t dst = (size_t)gofs[(size_t)d * nblk + blockIdx.x] + (pos - digstart[d]);
+            const size_t dst = (size_t)gofs[(size_t)d * nblk + tile] + (pos - digstart[d]);
             kout[dst] = k;
             vout[dst] = svals[pos];
         }
@@ -674,13 +685,13 @@ int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* 
     for (int p = 0; p < passes; ++p) {
         const int shift = width * p;
         if (width == 9) {
-            hipLaunchKernelGGL(radix_hist_kernel<9>, dim3(nblk), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
+            hipLaunchKernelGGL(radix_hist_kernel<9>, dim3((nblk + 7) / 8 * 8), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
             launch_scan_u32(st, hist, hist, (int64_t)512 * nblk, scan_tmp, nullptr);
-            hipLaunchKernelGGL(radix_scatter_kernel<9>, dim3(nblk), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk);
+            hipLaunchKernelGGL(radix_scatter_kernel<9>, dim3((nblk + 7) / 8 * 8), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk);
         } else {
-            hipLaunchKernelGGL(radix_hist_kernel<8>, dim3(nblk), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
+            hipLaunchKernelGGL(radix_hist_kernel<8>, dim3((nblk + 7) / 8 * 8), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
             launch_scan_u32(st, hist, hist, (int64_t)256 * nblk, scan_tmp, nullptr);
-            hipLaunchKernelGGL(radix_scatter_kernel<8>, dim3(nblk), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk);
+            hipLaunchKernelGGL(radix_scatter_kernel<8>, dim3((nblk + 7) / 8 * 8), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk);
         }
         u32* t = ki; ki = ko; ko = t;
         t = vi; vi = vo; vo = t;
