@@ -391,6 +391,29 @@ def test_small_config_full_size(gm):
     ctx.close()
 
 
+def test_large_config_shape(gm):
+    """configs[4]'s shapes on two of its tasks (64 fields, bags of 1-32, 512 + 512 samples per task, MLP
+    4109-1024-512-256-1, bf16 operands, K=1, second order) over smaller tables (2^16 rows per field, so that the oracle's
+    copy fits the test): more than 8192 lookups per (task, field, set), 512-row pair-count matrices, and the widest
+    grouped GEMMs; every output against the oracle, in both shapes of the sparse output."""
+    from synth import LARGE
+    cfg = LARGE.with_(n_tasks=2, rows_per_field=1 << 16)
+    ctx = gm.from_config(cfg, workspace_bytes=6 << 30)
+    dev = ctx.device
+    sup, qry = (_to_dev(sd, "cpu") for sd in make_batch(cfg, 0, dev))   # the same streams, drawn faster on the device
+    params = make_params(cfg, "cpu")
+    out, ref = _compare_step(cfg, ctx, sup, qry, params, cfg.inner_steps, cfg.order, TOL_BF16, "c5 shape, 2 tasks",
+                             operand="bf16")
+    table = torch.zeros(cfg.total_rows, cfg.emb_dim, dtype=torch.float32, device=dev)
+    ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, cfg.inner_steps, cfg.order,
+                  emb_grad_table=table)
+    n = int(out["n_emb_rows"].item())
+    want = torch.zeros_like(table)
+    want[out["emb_rows"][:n]] = out["emb_grad"][:n]
+    assert torch.equal(table, want)
+    ctx.close()
+
+
 def test_medium_config_full_size_sampled_tasks(gm):
     """configs[2] whole, as bench.py launches it (512 tasks, 26 fields x 1M rows x 64, bf16 operands, K=3, second
     order).  The oracle cannot run the whole batch in the test budget, but tasks are independent (Alg. 1): the loss of
