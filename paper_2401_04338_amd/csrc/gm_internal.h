@@ -132,11 +132,11 @@ struct PairCountArgs {
     const int64_t *off_ss, *off_qs, *off_sq;  // [Tw] byte offset of the task's first matrix of each kind
     uint8_t* mat;
     int want_ss, want_sq;
-    int lds_bytes, cap;                       // set by the launcher
+    int lds_bytes, n_max, max_tile_rows;      // set by the launcher
     u32* task_path;                           // [Tw] only tasks flagged 1 are counted; cleared when a count exceeds 254
     u32* status;
 };
-void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap);
+void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int max_tf, int max_rows, int max_tile_rows);
 struct PairHopOut {
     int enabled;
     const int64_t* mat_off;                   // [Tw]

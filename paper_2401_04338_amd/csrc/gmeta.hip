@@ -67,6 +67,7 @@ struct gm_ctx {
     int64_t* d_field_base = nullptr;
     u32* d_status = nullptr;
     std::string err;
+    int pair_tile_rows = 0;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
     // optional kernel timing
     bool prof_on = false;
@@ -476,6 +477,11 @@ extern "C" const char* gm_last_error(const gm_ctx* c) { return c ? c->err.c_str(
 extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
     if (!c) return GM_ERR_ARG;
     if (!key) return fail(c, GM_ERR_ARG, "null key");
+    if (!strcmp(key, "pair_tile_rows")) {   // most out-rows of a pair-count matrix counted at a time (0: as many as fit)
+        if (value < 0 || value > 1024) return fail(c, GM_ERR_ARG, "pair_tile_rows must be in [0, 1024]");
+        c->pair_tile_rows = (int)value;
+        return GM_OK;
+    }
     if (!strcmp(key, "row_path")) {
         if (value < 0 || value > 2) return fail(c, GM_ERR_ARG, "row_path must be 0, 1 or 2");
         c->row_path = (int)value;
@@ -911,7 +917,7 @@ struct Batch {  // host-side description of one call
 };
 
 static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBufs& w, int* cap_out = nullptr,
-                          int* max_bag_out = nullptr) {
+                          int* max_bag_out = nullptr, int* max_tf_out = nullptr) {
     hipStream_t st = c->stream;
     const int F = c->F, Tw = wp.t1 - wp.t0;
     if (F == 0 || Tw == 0) return GM_OK;
@@ -930,6 +936,7 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
     while (cap < (int)hs[ST_MAX_TF]) cap <<= 1;
     if (cap_out) *cap_out = cap;
     if (max_bag_out) *max_bag_out = (int)hs[ST_MAX_BAG];
+    if (max_tf_out) *max_tf_out = (int)hs[ST_MAX_TF];
     if (cap > tf_sort_max_cap())
         return fail(c, GM_ERR_CAPACITY, "a (task, field) has %u lookups in one set; the limit is %d", hs[ST_MAX_TF],
                     tf_sort_max_cap());
@@ -1241,8 +1248,8 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         if ((rc = setup_wave(c, B, wp, bm, K, w, d, gs, gq))) return rc;
 
         // a0: row dictionaries and the overlap join
-        int tf_cap = 0, max_bag = 0;
-        rc = run_index_wave(c, B, wp, w, &tf_cap, &max_bag);
+        int tf_cap = 0, max_bag = 0, max_tf = 0;
+        rc = run_index_wave(c, B, wp, w, &tf_cap, &max_bag, &max_tf);
         if (rc != GM_OK) return rc;
         // pair-count matrices for the tasks that qualify, when the wave's bags and (task, field)s are within the
         // counting kernel's limits; a task with a count that does not fit a byte is handed to the sparse kernel
@@ -1262,7 +1269,12 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             pa.task_path = w.task_path;
             {
                 Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0);
-                launch_pair_count(st, pa, Tw, tf_cap);
+                int max_rows = 0;
+                for (int t = wp.t0; t < wp.t1; ++t)
+                    if (task_pair_ok(c, B, t, K))
+                        max_rows = std::max<int>(max_rows, (int)std::max(sup->task_offsets[t + 1] - sup->task_offsets[t],
+                                                                         qry->task_offsets[t + 1] - qry->task_offsets[t]));
+                launch_pair_count(st, pa, Tw, max_tf, max_rows, c->pair_tile_rows);
             }
             u32 hs[ST_WORDS];
             if ((rc = read_status(c, hs))) return rc;

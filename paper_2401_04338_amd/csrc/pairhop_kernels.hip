@@ -22,7 +22,7 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 ph_short8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float ph_float16;
 
-__device__ __forceinline__ int pad64(int n) { return (n + 63) & ~63; }
+__host__ __device__ __forceinline__ int pad64(int n) { return (n + 63) & ~63; }
 
 // ------------------------------------------------------------------------------------------------
 // counting: M[i][j] for one (task, field) and one pair of sets, in tiles of out-rows held in LDS
@@ -30,32 +30,40 @@ __device__ __forceinline__ int pad64(int n) { return (n + 63) & ~63; }
 // M = sum over the rows u of the task's support set of  c_out(:, u) (x) c_in(:, u),  with c_set(b, u) the
 // number of times bag b looks row u up.  Under a skewed row distribution a few hot rows carry nearly all
 // of the pairs (a row looked up a times by one set and b times by the other adds a*b of them), and LDS
-// atomics retire only about one lane per cycle, so the hot rows do not go through atomics: sixteen hot
-// rows at a time, their count vectors are laid out densely ([bags, 16], a few thousand atomics) and
-// multiplied on the matrix cores (counts up to 255 are exact in bf16, sums exact in fp32).  Only the
-// remaining rows (fewer than PC_HOT lookups from either set, at most 9 pairs each) are counted pair by
-// pair with atomics on 16-bit cells, on top of the stored hot part.  Everything is integer arithmetic:
-// the result does not depend on any order.
+// atomics retire only about one lane per cycle, so the hot rows do not go through pair-by-pair atomics:
+// PC_HB hot rows at a time, their count vectors are laid out densely ([bags, PC_HB] bytes, one atomic per
+// lookup) and multiplied on the matrix cores (counts up to 255 are exact in bf16, sums exact in fp32).
+// Only the remaining rows (fewer than PC_HOT lookups from either set, at most 9 pairs each) are counted
+// pair by pair with atomics on the byte cells, on top of the stored hot part.  Everything is integer
+// arithmetic: the result does not depend on any order.
+//
+// The kernel is bound by latency, not by arithmetic, so everything it walks more than once is staged in
+// LDS when the workgroup starts: the bag of every lookup of both lists (16 bits each) and one record per
+// row with pairs (hot: the bounds of its two lookup ranges; cold: packed starts and sizes).  After that
+// only LDS is read until the matrix is written out.
 // ------------------------------------------------------------------------------------------------
 #define PC_NT 1024
 #define PC_TPW (64 / (PC_NT / 64))   // MFMA tiles per wave: at most 64 tiles per row tile
 #define PC_HB 32     // hot rows per matrix-core batch (two MFMA contraction steps)
+#define PC_HBS 40    // bytes per bag in a count block: 10 words, so that the 8-byte fragment reads of 32 bags spread over the banks
 #define PC_HOT 4     // a row is hot when one of the two sets looks it up at least this often
 
-__device__ __forceinline__ ph_short8 pc_counts_to_bf16(uint4 q) {  // eight 16-bit counts -> eight bf16 (exact up to 256)
+__device__ __forceinline__ ph_short8 pc_counts_to_bf16(uint2 q) {  // eight byte counts -> eight bf16 (exact)
     u32 w[4];
-    const u32 x[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const float lo = (float)(x[k] & 0xFFFFu), hi = (float)(x[k] >> 16);
-        w[k] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, hi), __builtin_bit_cast(u32, lo), 0x07060302u);
-    }
+    const float f0 = (float)(q.x & 0xFFu), f1 = (float)((q.x >> 8) & 0xFFu);   // (byte-to-float conversions)
+    const float f2 = (float)((q.x >> 16) & 0xFFu), f3 = (float)(q.x >> 24);
+    const float f4 = (float)(q.y & 0xFFu), f5 = (float)((q.y >> 8) & 0xFFu);
+    const float f6 = (float)((q.y >> 16) & 0xFFu), f7 = (float)(q.y >> 24);
+    w[0] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, f1), __builtin_bit_cast(u32, f0), 0x07060302u);
+    w[1] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, f3), __builtin_bit_cast(u32, f2), 0x07060302u);
+    w[2] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, f5), __builtin_bit_cast(u32, f4), 0x07060302u);
+    w[3] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, f7), __builtin_bit_cast(u32, f6), 0x07060302u);
     return __builtin_bit_cast(ph_short8, make_uint4(w[0], w[1], w[2], w[3]));
 }
 
 __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     extern __shared__ __attribute__((aligned(16))) u32 pc_lds[];
-    __shared__ int sh_nhot;
+    __shared__ int sh_nhot, sh_ncold;
     const int f = blockIdx.x, t = blockIdx.y;
     const bool qs = blockIdx.z == 1;   // 0: support x support, 1: query x support (and its transpose)
     if (!qs && !a.want_ss) return;
@@ -70,33 +78,69 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     const int nu = (int)a.n_slots[tf];
     const int n_in_entries = a.slot_start[B + tf + nu] - (int)B;
     const int n_out_entries = qs ? (int)a.cnt_q[tf] : n_in_entries;
-    const int2* in_list = a.sup_sorted + B;   // {row, slot}, slot-sorted
-    // positions [lo, hi) of row u's lookups in the slot-sorted in / out list
-    auto in_seg = [&](int u, int& lo, int& hi) { lo = a.slot_start[B + tf + u] - (int)B; hi = a.slot_start[B + tf + u + 1] - (int)B; };
-    auto out_seg = [&](int u, int& lo, int& hi) {
-        if (qs) { lo = a.qseg_lo[B + u] - (int)Bq; hi = a.qseg_hi[B + u] - (int)Bq; }
-        else in_seg(u, lo, hi);
-    };
-    // LDS, from the end: the bag of every out lookup (16 bits each, slot-sorted) and the list of hot rows (16 bits
-    // each; a hot row has >= PC_HOT lookups in one set: at most cap / 2 of them).  From the start: the tile of R
-    // out-rows, TRANSPOSED, one byte per cell: cell (i, j) at j * ldT + i with ldT = R + 4 (an odd number of
-    // words: the MFMA result, the transposed read-out and the atomics all spread over the banks); then the
-    // two dense count blocks of a batch, [R][PC_HB] and [colsP][PC_HB] 16-bit counts.
-    uint16_t* out_rows = reinterpret_cast<uint16_t*>(pc_lds) + (a.lds_bytes / 2 - a.cap);
-    uint16_t* hot_list = out_rows - a.cap / 2;
-    const int in_row0 = a.row_off_s[t];
+    // LDS, from the end (6 * n_max bytes): the bag of every out lookup and of every in lookup (16 bits each, in the
+    // order of the row-sorted lists; one array when both sets are the support set), then the records: hot rows
+    // from the front (two words: in range, out range), cold rows with pairs from the back (one word).
+    // From the start: the tile of R out-rows, TRANSPOSED, one byte per cell: cell (i, j) at j * ldT + i with
+    // ldT = R + 4 (an odd number of words: the MFMA result, the transposed read-out and the atomics all spread
+    // over the banks); then the two dense count blocks of a batch, [R] and [colsP] bags of PC_HBS bytes.
+    const int nmax = a.n_max;                                  // a multiple of 8
+    uint16_t* out_rows = reinterpret_cast<uint16_t*>(pc_lds) + (a.lds_bytes / 2 - nmax);
+    uint16_t* in_rows = qs ? out_rows - nmax : out_rows;
+    const int RW = qs ? nmax / 2 : nmax;                       // record words
+    u32* recs = reinterpret_cast<u32*>(in_rows) - RW;
+    if (threadIdx.x == 0) { sh_nhot = 0; sh_ncold = 0; }
     {
-        const int2* out_list = qs ? a.qry_sorted + Bq : a.sup_sorted + B;
-        const int out_row0 = qs ? a.row_off_q[t] : a.row_off_s[t];
-        for (int e = threadIdx.x; e < n_out_entries; e += PC_NT) out_rows[e] = (uint16_t)(out_list[e].x - out_row0);
+        const int2* in_list = a.sup_sorted + B;   // {row, slot}, slot-sorted
+        const int in_row0 = a.row_off_s[t];
+        for (int e = threadIdx.x; e < n_in_entries; e += PC_NT) in_rows[e] = (uint16_t)(in_list[e].x - in_row0);
+        if (qs) {
+            const int2* out_list = a.qry_sorted + Bq;
+            const int out_row0 = a.row_off_q[t];
+            for (int e = threadIdx.x; e < n_out_entries; e += PC_NT) out_rows[e] = (uint16_t)(out_list[e].x - out_row0);
+        }
     }
-    const size_t budget = (size_t)a.lds_bytes - 3 * (size_t)a.cap;
-    int R = rowsP;   // at most 64 MFMA tiles per row tile
-    while (R > 32 && ((size_t)colsP * (R + 4) + (size_t)(R + colsP) * PC_HB * 2 > budget || R * colsP > 65536)) R -= 32;
+    __syncthreads();
+    for (int u = threadIdx.x; u < nu; u += PC_NT) {
+        const int lo = a.slot_start[B + tf + u] - (int)B, hi = a.slot_start[B + tf + u + 1] - (int)B;
+        int lo2 = lo, hi2 = hi;
+        if (qs) { lo2 = a.qseg_lo[B + u] - (int)Bq; hi2 = a.qseg_hi[B + u] - (int)Bq; }
+        const int na = hi - lo, nb = hi2 - lo2;
+        if (na <= 0 || nb <= 0) continue;
+        if (na >= PC_HOT || nb >= PC_HOT) {
+            const int k = atomicAdd(&sh_nhot, 1);
+            if (2 * k + 1 < RW) {
+                recs[2 * k] = (u32)lo | ((u32)hi << 16);
+                recs[2 * k + 1] = (u32)lo2 | ((u32)hi2 << 16);
+            }
+        } else {
+            const int k = atomicAdd(&sh_ncold, 1);
+            if (k < RW) recs[RW - 1 - k] = (u32)lo | ((u32)lo2 << 14) | ((u32)na << 28) | ((u32)nb << 30);
+        }
+    }
+    __syncthreads();
+    const int nhot = sh_nhot, ncold = sh_ncold;
+    if (2 * nhot + ncold > RW) {   // the records do not fit (they may have overwritten each other): sparse kernel
+        if (threadIdx.x == 0) {
+            a.task_path[t] = 0u;
+            a.status[ST_PAIR_OVF] = 1u;
+        }
+        return;
+    }
+    const size_t budget = (size_t)a.lds_bytes - 6 * (size_t)nmax;
+    int R = min(rowsP, a.max_tile_rows);   // at most 64 MFMA tiles per row tile
+    while (R > 32 && ((size_t)colsP * (R + 4) + (size_t)(R + colsP) * PC_HBS > budget || R * colsP > 65536)) R -= 32;
+    if ((size_t)colsP * (R + 4) + (size_t)(R + colsP) * PC_HBS > budget) {   // not even 32 rows fit: sparse kernel
+        if (threadIdx.x == 0) {
+            a.task_path[t] = 0u;
+            a.status[ST_PAIR_OVF] = 1u;
+        }
+        return;
+    }
     const int ldT = R + 4;
     uint8_t* tile = reinterpret_cast<uint8_t*>(pc_lds);
-    uint16_t* c_out = reinterpret_cast<uint16_t*>(tile + (size_t)colsP * ldT);   // colsP * ldT is a multiple of 16
-    uint16_t* c_in = c_out + R * PC_HB;
+    uint8_t* c_out = tile + (size_t)colsP * ldT;   // colsP * ldT is a multiple of 16
+    uint8_t* c_in = c_out + R * PC_HBS;
     uint8_t* M = a.mat + (qs ? a.off_qs[t] : a.off_ss[t]) + (size_t)f * rowsP * colsP;
     uint8_t* Mt = (qs && a.want_sq) ? a.mat + a.off_sq[t] + (size_t)f * colsP * rowsP : nullptr;  // [colsP rows][rowsP cols]
     const int tiles_c = colsP / 32;
@@ -104,17 +148,6 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     for (int i0 = 0; i0 < rowsP; i0 += R) {
         const int rows_here = min(R, rowsP - i0);
         const int n_tiles = (rows_here / 32) * tiles_c;
-        // ---- the hot rows of this (task, field)
-        if (threadIdx.x == 0) sh_nhot = 0;
-        __syncthreads();   // also: the lists are staged, the previous tile has been read out
-        for (int u = threadIdx.x; u < nu; u += PC_NT) {
-            int lo, hi, lo2, hi2;
-            in_seg(u, lo, hi);
-            out_seg(u, lo2, hi2);
-            if (hi - lo >= PC_HOT || hi2 - lo2 >= PC_HOT) hot_list[atomicAdd(&sh_nhot, 1)] = (uint16_t)u;
-        }
-        __syncthreads();
-        const int nhot = sh_nhot;
         int my_tr[PC_TPW], my_tc[PC_TPW];
 #pragma unroll
         for (int q = 0; q < PC_TPW; ++q) {
@@ -128,20 +161,18 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
         for (int hb = 0; hb < nhot; hb += PC_HB) {
-            for (int i = threadIdx.x; i < (R + colsP) * PC_HB / 8; i += PC_NT)   // both count blocks, contiguous
+            __syncthreads();   // the previous batch's fragments (or the previous tile) have been read
+            for (int i = threadIdx.x; i < (R + colsP) * PC_HBS / 16; i += PC_NT)   // both count blocks, contiguous
                 reinterpret_cast<uint4*>(c_out)[i] = make_uint4(0u, 0u, 0u, 0u);
             __syncthreads();
             for (int hx = wv; hx < PC_HB && hb + hx < nhot; hx += PC_NT / 64) {
-                const int u = (int)hot_list[hb + hx];
-                const u32 inc = 1u << (16 * (hx & 1));
-                int lo, hi;
-                in_seg(u, lo, hi);
-                for (int e = lo + lane; e < hi; e += 64)
-                    atomicAdd(reinterpret_cast<u32*>(c_in) + (((in_list[e].x - in_row0) * PC_HB + hx) >> 1), inc);
-                out_seg(u, lo, hi);
-                for (int e = lo + lane; e < hi; e += 64) {
+                const u32 r0 = recs[2 * (hb + hx)], r1 = recs[2 * (hb + hx) + 1];
+                const u32 inc = 1u << (8 * (hx & 3));
+                for (int e = (int)(r0 & 0xFFFFu) + lane; e < (int)(r0 >> 16); e += 64)
+                    atomicAdd(reinterpret_cast<u32*>(c_in) + (((int)in_rows[e] * PC_HBS + hx) >> 2), inc);
+                for (int e = (int)(r1 & 0xFFFFu) + lane; e < (int)(r1 >> 16); e += 64) {
                     const int i = (int)out_rows[e] - i0;
-                    if ((unsigned)i < (unsigned)rows_here) atomicAdd(reinterpret_cast<u32*>(c_out) + ((i * PC_HB + hx) >> 1), inc);
+                    if ((unsigned)i < (unsigned)rows_here) atomicAdd(reinterpret_cast<u32*>(c_out) + ((i * PC_HBS + hx) >> 2), inc);
                 }
             }
             __syncthreads();
@@ -150,17 +181,17 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
                 if (my_tr[q] >= 0) {
 #pragma unroll
                     for (int ks = 0; ks < PC_HB / 16; ++ks) {
-                        const uint4 qa = *reinterpret_cast<const uint4*>(c_out + (my_tr[q] * 32 + ln) * PC_HB + ks * 16 + h * 8);
-                        const uint4 qb = *reinterpret_cast<const uint4*>(c_in + (my_tc[q] * 32 + ln) * PC_HB + ks * 16 + h * 8);
+                        const uint2 qa = *reinterpret_cast<const uint2*>(c_out + (my_tr[q] * 32 + ln) * PC_HBS + ks * 16 + h * 8);
+                        const uint2 qb = *reinterpret_cast<const uint2*>(c_in + (my_tc[q] * 32 + ln) * PC_HBS + ks * 16 + h * 8);
                         acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pc_counts_to_bf16(qa), pc_counts_to_bf16(qb), acc[q], 0, 0, 0);
                     }
                 }
             }
-            __syncthreads();
         }
         // ---- the hot part becomes the tile's initial content (every cell of the tile's rows is written); a lane
         //      holds four consecutive rows of one column: one word of the transposed tile.  255 stands for
         //      "255 or more" and is reported when the tile is read out.
+        __syncthreads();   // the previous tile has been read out
 #pragma unroll
         for (int q = 0; q < PC_TPW; ++q) {
             if (my_tr[q] >= 0) {
@@ -174,19 +205,17 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
             }
         }
         __syncthreads();
-        // ---- the other rows, pair by pair (a lookup of the in-set walks the row's few lookups of the out-set);
-        //      a cell that was at 254 or more before an increment may have wrapped: reported
-        for (int p = threadIdx.x; p < n_in_entries; p += PC_NT) {
-            const int2 ent = in_list[p];
-            const int u = ent.y, j = ent.x - in_row0;
-            int lo, hi, lo2, hi2;
-            in_seg(u, lo, hi);
-            out_seg(u, lo2, hi2);
-            if (hi - lo >= PC_HOT || hi2 - lo2 >= PC_HOT) continue;
-            for (int x = lo2; x < hi2; ++x) {
-                const int i = (int)out_rows[x] - i0;
-                if ((unsigned)i < (unsigned)rows_here) {
-                    const int sh = 8 * (i & 3);
+        // ---- the other rows, pair by pair; a cell that was at 254 or more before an increment may have
+        //      wrapped: reported
+        for (int k = threadIdx.x; k < ncold; k += PC_NT) {
+            const u32 r = recs[RW - 1 - k];
+            const int lo = (int)(r & 0x3FFFu), lo2 = (int)((r >> 14) & 0x3FFFu), na = (int)((r >> 28) & 3u), nb = (int)(r >> 30);
+            for (int y = 0; y < nb; ++y) {
+                const int i = (int)out_rows[lo2 + y] - i0;
+                if ((unsigned)i >= (unsigned)rows_here) continue;
+                const int sh = 8 * (i & 3);
+                for (int x = 0; x < na; ++x) {
+                    const int j = (int)in_rows[lo + x];
                     const u32 old = atomicAdd(&pc_lds[(j * ldT + i) >> 2], 1u << sh);
                     ovf |= ((old >> sh) & 0xFFu) >= 254u;
                 }
@@ -216,12 +245,20 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     }
 }
 
-void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int cap) {
+// max_tf: the most lookups any (task, field) of the wave has in one set; max_rows: the most samples any
+// counted task has in one set
+void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int max_tf, int max_rows, int max_tile_rows) {
     if (Tw <= 0 || a.F <= 0) return;
-    a.lds_bytes = PAIR_LDS_BYTES;
-    a.cap = cap;   // a power of two >= 1024
+    a.n_max = (max_tf + 7) / 8 * 8 + 8;
+    a.max_tile_rows = max_tile_rows > 0 ? (max_tile_rows + 31) / 32 * 32 : 1 << 20;
+    // LDS: what the largest (task, field) needs for one tile of all its rows, or all there is
+    const size_t P = (size_t)pad64(max_rows > 0 ? max_rows : 1);
+    const size_t R = P < (size_t)a.max_tile_rows ? P : (size_t)a.max_tile_rows;
+    size_t need = 6 * (size_t)a.n_max + P * (R + 4) + (R + P) * PC_HBS + 64;
+    if (need > PAIR_LDS_BYTES) need = PAIR_LDS_BYTES;
+    a.lds_bytes = (int)(need / 16 * 16);
     (void)hipFuncSetAttribute((const void*)pair_count_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, PAIR_LDS_BYTES);
-    hipLaunchKernelGGL(pair_count_kernel, dim3(a.F, Tw, 2), dim3(PC_NT), PAIR_LDS_BYTES, st, a);
+    hipLaunchKernelGGL(pair_count_kernel, dim3(a.F, Tw, 2), dim3(PC_NT), (size_t)a.lds_bytes, st, a);
 }
 
 // ------------------------------------------------------------------------------------------------
