@@ -144,7 +144,7 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               their tangents) is carried out: 0 = chosen per wave of tasks (default); 1 = always the
  *               sparse two-hop kernel; 2 = always per-(task, field) pair-count matrices on the matrix
  *               cores (gm_meta_step then returns GM_ERR_CAPACITY when a wave exceeds that path's limits:
- *               bags of at most 255 lookups, pair counts of at most 254, 16384 lookups per task, field and set).
+ *               bags of at most 127 lookups, pair counts of at most 254, 16384 lookups per task, field and set).
  * Unknown keys or values give GM_ERR_ARG. */
 int gm_configure(gm_ctx* ctx, const char* key, int64_t value);
 

@@ -121,7 +121,7 @@ void launch_two_hop(hipStream_t st, TwoHopArgs a, int n_tasks, int max_bags);
 // stored as bytes, [pad64(n_out)][pad64(n_in)] per field, fields of a task back to back.
 #define PAIR_LDS_BYTES (159 * 1024)   // LDS of the counting kernel: a tile of byte cells, two dense count blocks, the lists
 #define PAIR_MAX_CAP 16384       // lookups of one (task, field) and set that the counting kernel stages
-#define PAIR_MAX_BAG 255         // longest bag for which the 16-bit counts of one row cannot wrap
+#define PAIR_MAX_BAG 127         // longest bag for which a (bag, row) count is a non-negative 8-bit integer
 struct PairCountArgs {
     int F;
     const int32_t *real_off_s, *real_off_q;   // [Tw+1] first sample of each task (relative to the wave)

@@ -32,7 +32,8 @@ __host__ __device__ __forceinline__ int pad64(int n) { return (n + 63) & ~63; }
 // of the pairs (a row looked up a times by one set and b times by the other adds a*b of them), and LDS
 // atomics retire only about one lane per cycle, so the hot rows do not go through pair-by-pair atomics:
 // PC_HB hot rows at a time, their count vectors are laid out densely ([bags, PC_HB] bytes, one atomic per
-// lookup) and multiplied on the matrix cores (counts up to 255 are exact in bf16, sums exact in fp32).
+// lookup) and multiplied on the matrix cores as 8-bit integers (v_mfma_i32_32x32x32_i8: a count is at
+// most the bag's length, which this path limits to 127; sums are exact in 32 bits).
 // Only the remaining rows (fewer than PC_HOT lookups from either set, at most 9 pairs each) are counted
 // pair by pair with atomics on the byte cells, on top of the stored hot part.  Everything is integer
 // arithmetic: the result does not depend on any order.
@@ -44,22 +45,12 @@ __host__ __device__ __forceinline__ int pad64(int n) { return (n + 63) & ~63; }
 // ------------------------------------------------------------------------------------------------
 #define PC_NT 1024
 #define PC_TPW (64 / (PC_NT / 64))   // MFMA tiles per wave: at most 64 tiles per row tile
-#define PC_HB 32     // hot rows per matrix-core batch (two MFMA contraction steps)
-#define PC_HBS 40    // bytes per bag in a count block: 10 words, so that the 8-byte fragment reads of 32 bags spread over the banks
+#define PC_HB 32     // hot rows per matrix-core batch (one MFMA contraction step)
+#define PC_HBS 48    // bytes per bag in a count block (16-byte fragment reads; 12 words spread them over the banks)
 #define PC_HOT 4     // a row is hot when one of the two sets looks it up at least this often
 
-__device__ __forceinline__ ph_short8 pc_counts_to_bf16(uint2 q) {  // eight byte counts -> eight bf16 (exact)
-    u32 w[4];
-    const float f0 = (float)(q.x & 0xFFu), f1 = (float)((q.x >> 8) & 0xFFu);   // (byte-to-float conversions)
-    const float f2 = (float)((q.x >> 16) & 0xFFu), f3 = (float)(q.x >> 24);
-    const float f4 = (float)(q.y & 0xFFu), f5 = (float)((q.y >> 8) & 0xFFu);
-    const float f6 = (float)((q.y >> 16) & 0xFFu), f7 = (float)(q.y >> 24);
-    w[0] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, f1), __builtin_bit_cast(u32, f0), 0x07060302u);
-    w[1] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, f3), __builtin_bit_cast(u32, f2), 0x07060302u);
-    w[2] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, f5), __builtin_bit_cast(u32, f4), 0x07060302u);
-    w[3] = __builtin_amdgcn_perm(__builtin_bit_cast(u32, f7), __builtin_bit_cast(u32, f6), 0x07060302u);
-    return __builtin_bit_cast(ph_short8, make_uint4(w[0], w[1], w[2], w[3]));
-}
+typedef int pc_int4 __attribute__((ext_vector_type(4)));
+typedef int pc_int16 __attribute__((ext_vector_type(16)));
 
 __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     extern __shared__ __attribute__((aligned(16))) u32 pc_lds[];
@@ -90,6 +81,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     const int RW = qs ? nmax / 2 : nmax;                       // record words
     u32* recs = reinterpret_cast<u32*>(in_rows) - RW;
     if (threadIdx.x == 0) { sh_nhot = 0; sh_ncold = 0; }
+    __syncthreads();
     {
         const int2* in_list = a.sup_sorted + B;   // {row, slot}, slot-sorted
         const int in_row0 = a.row_off_s[t];
@@ -100,7 +92,6 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
             for (int e = threadIdx.x; e < n_out_entries; e += PC_NT) out_rows[e] = (uint16_t)(out_list[e].x - out_row0);
         }
     }
-    __syncthreads();
     for (int u = threadIdx.x; u < nu; u += PC_NT) {
         const int lo = a.slot_start[B + tf + u] - (int)B, hi = a.slot_start[B + tf + u + 1] - (int)B;
         int lo2 = lo, hi2 = hi;
@@ -155,16 +146,17 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
             my_tr[q] = tt < n_tiles ? tt / tiles_c : -1;
             my_tc[q] = tt - (tt / tiles_c) * tiles_c;
         }
-        ph_float16 acc[PC_TPW];
+        pc_int16 acc[PC_TPW];
 #pragma unroll
         for (int q = 0; q < PC_TPW; ++q)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[q][v] = 0;
         for (int hb = 0; hb < nhot; hb += PC_HB) {
             __syncthreads();   // the previous batch's fragments (or the previous tile) have been read
             for (int i = threadIdx.x; i < (R + colsP) * PC_HBS / 16; i += PC_NT)   // both count blocks, contiguous
                 reinterpret_cast<uint4*>(c_out)[i] = make_uint4(0u, 0u, 0u, 0u);
             __syncthreads();
+            // one atomic per lookup (a count is at most the bag's length); a wave per hot row
             for (int hx = wv; hx < PC_HB && hb + hx < nhot; hx += PC_NT / 64) {
                 const u32 r0 = recs[2 * (hb + hx)], r1 = recs[2 * (hb + hx) + 1];
                 const u32 inc = 1u << (8 * (hx & 3));
@@ -179,12 +171,9 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
 #pragma unroll
             for (int q = 0; q < PC_TPW; ++q) {
                 if (my_tr[q] >= 0) {
-#pragma unroll
-                    for (int ks = 0; ks < PC_HB / 16; ++ks) {
-                        const uint2 qa = *reinterpret_cast<const uint2*>(c_out + (my_tr[q] * 32 + ln) * PC_HBS + ks * 16 + h * 8);
-                        const uint2 qb = *reinterpret_cast<const uint2*>(c_in + (my_tc[q] * 32 + ln) * PC_HBS + ks * 16 + h * 8);
-                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pc_counts_to_bf16(qa), pc_counts_to_bf16(qb), acc[q], 0, 0, 0);
-                    }
+                    const pc_int4 qa = *reinterpret_cast<const pc_int4*>(c_out + (my_tr[q] * 32 + ln) * PC_HBS + h * 16);
+                    const pc_int4 qb = *reinterpret_cast<const pc_int4*>(c_in + (my_tc[q] * 32 + ln) * PC_HBS + h * 16);
+                    acc[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(qa, qb, acc[q], 0, 0, 0);
                 }
             }
         }
@@ -198,8 +187,8 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
                 uint8_t* col = tile + (size_t)(my_tc[q] * 32 + ln) * ldT + my_tr[q] * 32 + 4 * h;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const u32 b0 = (u32)fminf(acc[q][4 * g + 0], 255.f), b1 = (u32)fminf(acc[q][4 * g + 1], 255.f);
-                    const u32 b2 = (u32)fminf(acc[q][4 * g + 2], 255.f), b3 = (u32)fminf(acc[q][4 * g + 3], 255.f);
+                    const u32 b0 = min((u32)acc[q][4 * g + 0], 255u), b1 = min((u32)acc[q][4 * g + 1], 255u);
+                    const u32 b2 = min((u32)acc[q][4 * g + 2], 255u), b3 = min((u32)acc[q][4 * g + 3], 255u);
                     *reinterpret_cast<u32*>(col + 8 * g) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
                 }
             }
