@@ -364,6 +364,24 @@ def test_pair_counts_above_a_byte_fall_back(gm):
     ctx.close()
 
 
+def test_bags_longer_than_the_pair_path_allows(gm):
+    """Bags of up to 200 lookups: a (bag, row) count may not fit the pair-count kernel's signed 8-bit operands, so the
+    default choice takes the sparse kernel (and matches the oracle) and the forced pair path refuses."""
+    from paper_2401_04338_amd.binding import GMetaError
+    cfg = SMALL.with_(n_tasks=3, n_support=24, n_query=20, n_fields=3, emb_dim=32, rows_per_field=5000, bag_max=200,
+                      layer_dims=(3 * 32 + 13, 32, 16, 1), inner_lr=0.01)
+    sup, qry, params = _inputs(cfg)
+    lens = (sup.bag_offsets[1:] - sup.bag_offsets[:-1])
+    assert int(lens.max()) > 127
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+    _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_FP32, "long bags, auto")
+    ctx.configure("row_path", 2)
+    dev = ctx.device
+    with pytest.raises(GMetaError):
+        ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, 2, 2)
+    ctx.close()
+
+
 def test_mixed_row_paths_in_one_wave(gm):
     """configs[3]'s size mix in miniature (log-normal task sizes, task-private rows in the first fields): tasks above
     512 samples per set take the sparse kernel, the others the pair-count kernels, inside one wave of tasks."""
