@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
             ci_all[it] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (ok && has_mask) mk_all[it] = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
             if (ok && has_cin) ci_all[it] = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
-            if (ok && has_acc) ci_all[it] = *reinterpret_cast<const float4*>(Cacc + (int64_t)m * a.ldcacc + n);
+            if (ok && has_acc && !a.cacc_init) ci_all[it] = *reinterpret_cast<const float4*>(Cacc + (int64_t)m * a.ldcacc + n);
         }
 #pragma unroll
         for (int j = 0; j < NI; ++j)

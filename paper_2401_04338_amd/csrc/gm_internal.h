@@ -217,6 +217,7 @@ struct GemmBArgs {
     float* Cf; int64_t ldcf, gCf, rCf;     // fp32 output        (either may be null)
     bf16_t* Cb; int64_t ldcb, gCb, rCb;    // bf16 output
     float* Cacc; int64_t ldcacc, rCacc; float cacc;  // Cacc[(r0 + m)*ldcacc + n] += cacc * value (not with EPI_AXPBY + Cin)
+    int cacc_init;                                   // 1: Cacc is not read, = cacc * value (first term of a sum)
 };
 void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm);
 // same product with both operands stored contraction-slowest: A_p element (k, m) at A + g*gA + r0*rA + k*lda + m,

@@ -640,14 +640,14 @@ static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, con
 
 // out[rows, ld_{l-1}] = mask .* sum_p d_p[rows, ld_l] * W_p,l^T ; for l == 1: dX[rows, FD] fp32, no mask
 // dX (layer 1 only): the fp32 gradient w.r.t. the pooled input.  bf16 mode can also accumulate it, scaled, into
-// gx_acc (gx_acc += gx_scale * dX) in the same pass; with write_dx = false only that accumulation is stored.
+// gx_acc (gx_acc += gx_scale * dX, or = with gx_init) in the same pass; with write_dx = false only that is stored.
 static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, const Theta* th0, const Act* d1,
                      const Theta* th1, const Act* mask, Act* out, float* dX, float* gx_acc = nullptr, float gx_scale = 0.f,
-                     bool write_dx = true) {
+                     bool write_dx = true, bool gx_init = false) {
     const int K = c->ld[l], N = dX ? c->FD : c->ld[l - 1];
     if (N <= 0) return;
     const double esz = c->mlp_dtype ? 2.0 : 4.0;
-    double by = dX ? (double)g.rows * N * 4.0 * ((write_dx ? 1 : 0) + (gx_acc ? 2 : 0)) : (double)g.rows * N * esz;
+    double by = dX ? (double)g.rows * N * 4.0 * ((write_dx ? 1 : 0) + (gx_acc ? (gx_init ? 1 : 2) : 0)) : (double)g.rows * N * esz;
     if (mask) by += (double)g.rows * N * esz;
     for (int i = 0; i < np; ++i) {
         const Theta* t = i ? th1 : th0;
@@ -682,7 +682,7 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
         if (dX) {
             if (write_dx) { a.Cf = dX; a.ldcf = N; a.rCf = N; }
             a.epi = EPI_NONE;
-            if (gx_acc) { a.Cacc = gx_acc; a.ldcacc = N; a.rCacc = N; a.cacc = gx_scale; }
+            if (gx_acc) { a.Cacc = gx_acc; a.ldcacc = N; a.rCacc = N; a.cacc = gx_scale; a.cacc_init = gx_init ? 1 : 0; }
         } else {
             a.Cb = out->b; a.ldcb = N; a.rCb = N; a.epi = EPI_MASK; a.mask = mask->b; a.ld_mask = mask->ld;
         }
@@ -819,7 +819,7 @@ static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, Theta& out, const
 // gx_acc (bf16 mode): the support rows of the sparse-gradient buffer, which take -alpha * (tangent of dX) in the
 // layer-1 product itself; need_dx: the tangent of dX is also wanted in w.dX (for the row arithmetic of the next step)
 static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, float alpha, bool refresh_v_copies,
-                     float* gx_acc, bool need_dx) {
+                     float* gx_acc, bool need_dx, bool gx_init) {
     hipStream_t st = c->stream;
     const int L = c->L;
     Theta& v = w.v;
@@ -855,7 +855,7 @@ static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, f
     Theta vout = v;
     if (!refresh_v_copies) vout.b = nullptr;
     for (int l = L - 1; l >= 1; --l) {
-        if (l == 1) dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, nullptr, nullptr, w.dX, gx_acc, -alpha, need_dx || !gx_acc);
+        if (l == 1) dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, nullptr, nullptr, w.dX, gx_acc, -alpha, need_dx || !gx_acc, gx_init);
         else dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, &s.A[l - 1], &w.TD[l - 1], nullptr);
         const Act* ta_prev = l == 1 ? &w.TX : &w.TA[l - 1];
         const Act* a_prev = l == 1 ? &s.X : &s.A[l - 1];
@@ -1233,7 +1233,10 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                                    nullptr, 0);
     }
     launch_fill_f32(st, b.g_theta, nt, 0.f);
-    if (FD > 0 && !table) launch_fill_f32(st, b.GX, (Ps_tot + B.poff_q[T]) * (int64_t)FD, 0.f);
+    // Gradient w.r.t. the pooled inputs: the query rows are written whole by the outer backward pass; the support rows
+    // are the second-order chain's sum, which starts from zero unless its first product stores instead of adding.
+    const bool gxs_self_init = order == 2 && K > 0 && bf && L > 1;
+    if (FD > 0 && !table && !gxs_self_init) launch_fill_f32(st, b.GX, Ps_tot * (int64_t)FD, 0.f);
     float* task_loss = out->task_loss ? out->task_loss : b.task_loss;
 
     for (const WavePlan& wp : plans) {
@@ -1447,7 +1450,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         // gradient w.r.t. the pooled inputs: the wave's rows of the batch-wide buffer, or the wave's own buffer
         float* gxs = table ? w.GX : b.GX + wp.ps0 * (int64_t)FD;
         float* gxq = table ? w.GX + d.Ps * (int64_t)FD : b.GX + (Ps_tot + wp.pq0) * (int64_t)FD;
-        if (table && FD > 0) launch_fill_f32(st, w.GX, (d.Ps + d.Pq) * (int64_t)FD, 0.f);
+        if (table && FD > 0 && !gxs_self_init) launch_fill_f32(st, w.GX, d.Ps * (int64_t)FD, 0.f);
         Pass pq{&Xq, &w.Aq, &w.Dq, w.dLq, w.zq};
         forward_backward(c, gq, labels_q, pq, th, thf, thf_stride, w.loss_q, F > 0 ? gxq : nullptr);
         colsum_f32(c, gq, 1, w.loss_q, 1, task_loss + wp.t0, 1, nullptr, 0, 0.f, 1.f);
@@ -1465,7 +1468,8 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                 const StepState& s = w.steps[k];
                 // bf16 with hidden layers: the layer-1 product adds -alpha * dX to the gradient buffer itself
                 const bool fused_gx = bf && L > 1 && F > 0;
-                hvp_step(c, gs, s, w, alpha, k > 0, fused_gx ? gxs : nullptr, k > 0);
+                // (the chain's first step starts that sum: the buffer's support rows need no clearing)
+                hvp_step(c, gs, s, w, alpha, k > 0, fused_gx ? gxs : nullptr, k > 0, k == K - 1);
                 if (F > 0) {
                     if (!fused_gx) {
                         Prof p(c, "axpy_gx", 12.0 * d.Ps * FD, 0);
