@@ -208,6 +208,8 @@ __device__ __forceinline__ int load_tf_keys(u64* keys, int* sh_fill, const SetVi
 // positions.  Returns the buffer (one of the two) that holds the result.  At most TFR_ROUNDS * 64 keys per wave
 // and TFR_MAXS bags per task and set.
 #define TFR_ROUNDS 16
+#define TF_SMALL_N 1984    // lookups per set of a 'small' (task, field): its key buffer is 2048 + 64 keys
+#define TF_SMALL_MS 512    // samples per set of a 'small' task
 #define TFR_MAXS 2048
 struct TfRadixLds {
     u64* buf;               // [cap]: every pass holds all keys in registers between its read and its write
@@ -319,8 +321,11 @@ __device__ __forceinline__ u64* tf_radix_sorted(const TfRadixLds& L, const SetVi
 }
 
 // cap: key capacity of an LDS buffer (bitonic: a power of two); ms: most samples a task has in one set (radix)
+// cls: 0 = every (task, field); 1 = only the small ones (at most small_n lookups and small_ms samples per set);
+// 2 = only the others.  A launch is sized for its largest (task, field): with very uneven tasks the small ones get a
+// launch of their own, with workgroups and LDS that let several share a compute unit.
 template <bool LDS_UNIQ, bool RADIX>
-__global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms) {
+__global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms, int cls, int small_n, int small_ms) {
     extern __shared__ u64 sh_dyn[];  // bitonic: keys [cap] (+ u32 uniq[cap]); radix: two key buffers, uniq, bag tables, counters
     __shared__ int sh_scan[20];
     __shared__ int sh_fill;
@@ -341,6 +346,12 @@ __global__ void tf_sort_kernel(TfSortArgs a, int cap, int ms) {
     const u32 fb = (u32)a.field_base[f];
     const u32 n = a.cnt_sup[tf], B = a.base_sup[tf];
     const u32 nq = a.cnt_qry[tf], Bq = a.base_qry[tf];
+    if (cls) {
+        const int64_t ns_ = a.sup.task_offsets[a.t0 + t + 1] - a.sup.task_offsets[a.t0 + t];
+        const int64_t nq_ = a.qry.task_offsets[a.t0 + t + 1] - a.qry.task_offsets[a.t0 + t];
+        const bool small = (int)max(n, nq) <= small_n && max(ns_, nq_) <= (int64_t)small_ms;
+        if (small != (cls == 1)) return;
+    }
     u32* uniq = LDS_UNIQ ? (u32*)(sh_dyn + cap) : (a.slot_rows + B);
     int bits = 1;
     while (((int64_t)1 << bits) < a.field_base[f + 1] - a.field_base[f]) ++bits;
@@ -478,19 +489,31 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set
     int cap = 1024;
     while (cap < max_tf) cap <<= 1;
     if (max_set_rows <= TFR_MAXS) {   // radix sort in LDS
-        const int kcap = (max_tf + 63) / 64 * 64 + 64;                // keys in the buffer
-        const int ms = max_set_rows > 0 ? max_set_rows : 1;
-        int nt = cap / 8;                                             // at most 8 rounds of 64 keys per wave while the block
-        nt = nt < 256 ? 256 : (nt > 1024 ? 1024 : nt);                // allows (TFR_ROUNDS = 16 at the largest capacity)
-        const size_t fixed = (size_t)(2 * ms + 2) * 4 + (size_t)(nt / WAVE) * 256 * 2;
-        const bool lds_uniq = (size_t)kcap * 12 + fixed <= 80 * 1024;   // the row list in LDS while two workgroups fit a compute unit
-        const size_t shmem = (size_t)kcap * 8 + (lds_uniq ? (size_t)kcap * 4 : 0) + fixed;
-        if (lds_uniq) {
-            hipFuncSetAttribute((const void*)tf_sort_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-            hipLaunchKernelGGL((tf_sort_kernel<true, true>), grid, dim3(nt), shmem, st, a, kcap, ms);
+        auto launch = [&](int mtf, int mrows, int cls, int small_n, int small_ms) {
+            int cp = 1024;
+            while (cp < mtf) cp <<= 1;
+            const int kcap = (mtf + 63) / 64 * 64 + 64;                   // keys in the buffer
+            const int ms = mrows > 0 ? mrows : 1;
+            int nt = cp / 8;                                              // at most 8 rounds of 64 keys per wave while the block
+            nt = nt < 256 ? 256 : (nt > 1024 ? 1024 : nt);                // allows (TFR_ROUNDS = 16 at the largest capacity)
+            const size_t fixed = (size_t)(2 * ms + 2) * 4 + (size_t)(nt / WAVE) * 256 * 2;
+            const bool lds_uniq = (size_t)kcap * 12 + fixed <= 80 * 1024;   // the row list in LDS while two workgroups fit a compute unit
+            const size_t shmem = (size_t)kcap * 8 + (lds_uniq ? (size_t)kcap * 4 : 0) + fixed;
+            if (lds_uniq) {
+                hipFuncSetAttribute((const void*)tf_sort_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+                hipLaunchKernelGGL((tf_sort_kernel<true, true>), grid, dim3(nt), shmem, st, a, kcap, ms, cls, small_n, small_ms);
+            } else {
+                hipFuncSetAttribute((const void*)tf_sort_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+                hipLaunchKernelGGL((tf_sort_kernel<false, true>), grid, dim3(nt), shmem, st, a, kcap, ms, cls, small_n, small_ms);
+            }
+        };
+        // uneven tasks: the (task, field)s of at most TF_SMALL_N lookups and TF_SMALL_MS samples per set run in a launch
+        // of their own (every workgroup of either launch checks its class first)
+        if (max_tf > 2 * TF_SMALL_N && (int64_t)a.Tw * a.F >= 32) {
+            launch(TF_SMALL_N, max_set_rows < TF_SMALL_MS ? max_set_rows : TF_SMALL_MS, 1, TF_SMALL_N, TF_SMALL_MS);
+            launch(max_tf, max_set_rows, 2, TF_SMALL_N, TF_SMALL_MS);
         } else {
-            hipFuncSetAttribute((const void*)tf_sort_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-            hipLaunchKernelGGL((tf_sort_kernel<false, true>), grid, dim3(nt), shmem, st, a, kcap, ms);
+            launch(max_tf, max_set_rows, 0, 0, 0);
         }
         return;
     }
@@ -499,10 +522,10 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set
     const int nt = cap <= 1024 ? 256 : (cap <= 4096 ? 512 : 1024);
     if (lds_uniq) {
         hipFuncSetAttribute((const void*)tf_sort_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-        hipLaunchKernelGGL((tf_sort_kernel<true, false>), grid, dim3(nt), shmem, st, a, cap, 0);
+        hipLaunchKernelGGL((tf_sort_kernel<true, false>), grid, dim3(nt), shmem, st, a, cap, 0, 0, 0, 0);
     } else {
         hipFuncSetAttribute((const void*)tf_sort_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-        hipLaunchKernelGGL((tf_sort_kernel<false, false>), grid, dim3(nt), shmem, st, a, cap, 0);
+        hipLaunchKernelGGL((tf_sort_kernel<false, false>), grid, dim3(nt), shmem, st, a, cap, 0, 0, 0, 0);
     }
 }
 
