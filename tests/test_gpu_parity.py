@@ -9,7 +9,7 @@ import torch
 
 from oracle import maml_dlrm as O
 from synth import SMALL, TINY, make_batch, make_params
-from tests.helpers import oracle_model, rel_err, small_cfg
+from tests.helpers import compact_task, oracle_model, rel_err, small_cfg
 
 pytestmark = pytest.mark.gpu
 
@@ -406,6 +406,71 @@ def test_small_config_full_size(gm):
     sup, qry, params = _inputs(cfg)
     ctx = gm.from_config(cfg, workspace_bytes=4 << 30)
     _compare_step(cfg, ctx, sup, qry, params, cfg.inner_steps, cfg.order, TOL_FP32, "c2_small full size")
+    ctx.close()
+
+
+def test_coldstart_config_full_size_sampled_tasks(gm):
+    """configs[3] whole (2,048 tasks of log-normal size, 40 fields x 4 M rows x 64, MLP 2573-1024-512-256-1, bf16
+    operands, K=2, second order), as bench.py launches it.  Tasks are independent (Alg. 1): the loss of a sampled task
+    must equal the oracle's for that task alone (the oracle sees only the table rows the task looks up: the tables do
+    not fit a host copy).  The first fields draw from rows private to a task, so on those rows the batch's sparse
+    gradient IS the task's and is compared element by element.  Over all tasks: loss = sum of task losses, listed rows
+    = distinct rows looked up."""
+    from synth import COLDSTART
+    from synth.generate import task_sizes
+    cfg = COLDSTART
+    dev = torch.device("cuda", 0)
+    sup, qry = make_batch(cfg, 0, dev)
+    params = make_params(cfg, dev)
+    K, order = cfg.inner_steps, cfg.order
+    probe = gm.from_config(cfg, workspace_bytes=1 << 20)
+    need = probe.workspace_bytes(cfg.n_tasks, sup.n_samples, qry.n_samples, sup.nnz, qry.nnz, K, order)
+    probe.close()
+    ctx = gm.from_config(cfg, workspace_bytes=int(need * 1.02))
+    out = ctx.meta_step(sup, qry, params, cfg.inner_lr, K, order)
+    task_loss = out["task_loss"][: cfg.n_tasks].double().cpu().numpy()
+    loss = float(out["loss"].item())
+    assert abs(task_loss.sum() - loss) <= 1e-5 * abs(loss)
+    n = int(out["n_emb_rows"].item())
+    rows = out["emb_rows"][:n]
+    F = cfg.n_fields
+    want = []
+    for sd in (sup, qry):
+        lens = sd.bag_offsets[1:] - sd.bag_offsets[:-1]
+        field = (torch.arange(lens.numel(), device=dev) % F).repeat_interleave(lens)
+        want.append(sd.indices.long() + field * cfg.rows_per_field)
+    want = torch.unique(torch.cat(want))
+    assert n == want.numel() and torch.equal(rows, want), "listed rows != distinct rows looked up"
+    del want
+    sizes = task_sizes(cfg)[:, 0]
+    picks = [int(np.argmax(sizes)), int(np.argsort(sizes)[len(sizes) // 2]), int(np.argmin(sizes))]
+    print("c4 sampled tasks", picks, "support samples", [int(sizes[t]) for t in picks], flush=True)
+    assert sizes[picks[0]] > 512 >= sizes[picks[1]], "one sampled task per row path"
+    errs = []
+    for t in picks:
+        s1, q1 = make_batch(cfg, 0, "cpu", [t])
+        model, p_np, sd, qd, grows = compact_task(cfg, s1, q1, params.emb, params.W, params.b)
+        ref = O.meta_step(model, p_np, sd, qd, cfg.inner_lr, K, order, operand="bf16")
+        e = abs(task_loss[t] - ref["loss"]) / abs(ref["loss"])
+        # rows of the task-private fields: nobody else touches them
+        priv = ref["emb_rows"] < np.cumsum([0] + list(model.rows_per_field))[cfg.n_private_fields]
+        g_rows = torch.from_numpy(grows[ref["emb_rows"][priv]]).to(dev)
+        pos = torch.searchsorted(rows, g_rows)
+        assert torch.equal(rows[pos], g_rows)
+        got_g, ref_g = out["emb_grad"][pos].double().cpu().numpy(), ref["emb_grad"][priv]
+        row_err = np.linalg.norm(got_g - ref_g, axis=1) / np.linalg.norm(ref_g, axis=1).max()
+        q50, q90, q99 = np.quantile(row_err, [0.5, 0.9, 0.99])
+        print(f"c4 full size, task {t}: loss {task_loss[t]:.6f} vs oracle {ref['loss']:.6f} ({e:.2e}); "
+              f"{int(priv.sum())} private rows, row error median {q50:.1e}, 90% {q90:.1e}, 99% {q99:.1e}, "
+              f"max {row_err.max():.1e}", flush=True)
+        errs.append((e, q50, q90, row_err.max()))
+    # A ReLU decision on a pre-activation within float32 accumulation error of zero may fall differently than in the
+    # oracle's float64 accumulation (a few units in a million; seen here on 2 of one task's 62 samples).  That changes
+    # that sample's whole gradient, i.e. exactly the rows it looks up, and a task of a few dozen samples does not
+    # average it away.  The bar is therefore on the bulk of the rows: the median must sit far below bf16 resolution
+    # (the rounding points agree), 90 % within the bf16 tolerance, and the rest bounded by one sample's share.
+    for e, q50, q90, emax in errs:
+        assert e <= TOL_BF16 and q50 <= 1e-3 and q90 <= TOL_BF16 and emax <= 0.5
     ctx.close()
 
 
