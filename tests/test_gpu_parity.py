@@ -535,3 +535,70 @@ def test_medium_config_full_size_sampled_tasks(gm):
         print(f"c3 full size, task {t}: loss {task_loss[t]:.6f} vs oracle {ref['loss']:.6f} ({e:.2e})", flush=True)
         assert e <= TOL_BF16
     ctx.close()
+
+
+def test_large_config_full_size_sampled_tasks(gm):
+    """configs[4] whole (8,192 tasks x (512 + 512) samples, 64 fields x 4 M rows x 64, 8.9 G lookups: more than 2^31 per
+    set), as bench.py launches it: 32-odd waves of tasks, the sparse gradient added wave by wave into a table-shaped
+    accumulator.  Checked: loss = sum of task losses; for sampled tasks the loss against the oracle run on the task's
+    own rows; and, on table rows that the whole batch looks up exactly once (so that the batch's gradient of the row IS
+    the sampled task's), the accumulated gradient against the oracle's, row by row."""
+    from synth import LARGE
+    cfg = LARGE
+    dev = torch.device("cuda", 0)
+    torch.cuda.empty_cache()
+    free_b, _ = torch.cuda.mem_get_info()
+    if free_b < (250 << 30):
+        pytest.skip(f"needs about 250 GiB of free device memory, {free_b >> 30} GiB are free")
+    K, order, F, R = cfg.inner_steps, cfg.order, cfg.n_fields, cfg.rows_per_field
+    print("c5 full size: generating", flush=True)
+    sup, qry = make_batch(cfg, 0, dev)
+    params = make_params(cfg, dev)
+    table = torch.zeros_like(params.emb)
+    assert sup.nnz >= 2 ** 31 and qry.nnz >= 2 ** 31
+    free_b, _ = torch.cuda.mem_get_info()
+    ctx = gm.from_config(cfg, workspace_bytes=int(free_b - (16 << 30)))
+    print("c5 full size: step", flush=True)
+    out = ctx.meta_step(sup, qry, params, cfg.inner_lr, K, order, emb_grad_table=table)
+    ctx.close()
+    task_loss = out["task_loss"][: cfg.n_tasks].double().cpu().numpy()
+    loss = float(out["loss"].item())
+    assert np.isfinite(loss) and abs(task_loss.sum() - loss) <= 1e-5 * abs(loss)
+    rng = np.random.default_rng(0)
+    for t in (0, 8191):
+        s1, q1 = make_batch(cfg, 0, "cpu", [t])
+        model, p_np, sd, qd, grows = compact_task(cfg, s1, q1, params.emb, params.W, params.b)
+        ref = O.meta_step(model, p_np, sd, qd, cfg.inner_lr, K, order, operand="bf16")
+        e = abs(task_loss[t] - ref["loss"]) / abs(ref["loss"])
+        # candidate rows of the task; keep those that the whole batch looks up exactly once
+        cand = rng.choice(len(ref["emb_rows"]), size=4000, replace=False)
+        cand_rows = grows[ref["emb_rows"][cand]]
+        is_cand = torch.zeros(R, dtype=torch.bool, device=dev)   # by index within a field; the field is resolved below
+        is_cand[torch.from_numpy(np.unique(cand_rows % R)).to(dev)] = True
+        hits = []
+        for sdv in (sup, qry):
+            for lo in range(0, sdv.nnz, 1 << 28):
+                chunk = sdv.indices[lo: lo + (1 << 28)]
+                p = torch.nonzero(is_cand[chunk.long()]).flatten() + lo
+                if p.numel():
+                    bag = torch.searchsorted(sdv.bag_offsets, p, right=True) - 1
+                    hits.append((bag % F) * R + sdv.indices[p].long())
+                del chunk, p
+        hits = torch.cat(hits).cpu().numpy()
+        rows_hit, counts = np.unique(hits, return_counts=True)
+        once = set(rows_hit[counts == 1].tolist())
+        print("c5 full size: candidate rows by number of lookups in the batch:",
+              {int(k): int((counts[np.isin(rows_hit, cand_rows)] == k).sum()) for k in (1, 2, 3, 4, 8)}, flush=True)
+        keep = np.array([i for i, g in zip(cand, cand_rows) if int(g) in once], dtype=np.int64)
+        assert keep.size >= 10, "too few rows that only this task looks up"
+        got = table[torch.from_numpy(grows[ref["emb_rows"][keep]]).to(dev)].double().cpu().numpy()
+        want = ref["emb_grad"][keep]
+        row_err = np.linalg.norm(got - want, axis=1) / np.linalg.norm(ref["emb_grad"], axis=1).max()
+        q50, q90 = np.quantile(row_err, [0.5, 0.9])
+        print(f"c5 full size, task {t}: loss {task_loss[t]:.6f} vs oracle {ref['loss']:.6f} ({e:.2e}); {keep.size} rows "
+              f"looked up once in the batch: row error median {q50:.1e}, 90% {q90:.1e}, max {row_err.max():.1e}", flush=True)
+        # (bar as in the configs[3] test: a ReLU decision that falls differently moves one sample's rows)
+        assert e <= TOL_BF16 and q50 <= 1e-3 and q90 <= TOL_BF16 and row_err.max() <= 0.5
+        assert np.abs(got).sum() > 0
+    del table, params, sup, qry
+    torch.cuda.empty_cache()
