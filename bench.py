@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--batches", type=int, default=2, help="distinct pre-generated batches cycled through")
+    ap.add_argument("--configure", action="append", default=[], metavar="KEY=VALUE",
+                    help="gm_configure setting for the run (e.g. row_path=1, gemm_tile_n=256); may be repeated")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
                     help="also run one device copy of this size (a known transfer that calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -89,6 +91,9 @@ def main():
         ws = int(args.workspace_gib * 2 ** 30)
     ws = min(ws, int(free_b - out_bytes - (4 << 30)))
     ctx = GMeta.from_config(cfg, workspace_bytes=ws)
+    for kv in args.configure:
+        key, _, val = kv.partition("=")
+        ctx.configure(key, int(val))
     out = ctx.alloc_outputs(cfg.n_tasks, cap_rows)
 
     def step(i):
@@ -177,7 +182,7 @@ def main():
         "config": {"workload": cfg.name, "n_tasks": cfg.n_tasks, "samples_per_step": S, "lookups_per_step": nnz,
                    "n_fields": cfg.n_fields, "rows_per_field": cfg.rows_per_field, "emb_dim": cfg.emb_dim,
                    "mlp": list(cfg.layer_dims), "inner_steps": K, "order": order, "inner_lr": cfg.inner_lr,
-                   "sparse_out": sparse_out, "workspace_gib": ws / 2 ** 30, "batches_cycled": len(batches), "loss": loss,
+                   "sparse_out": sparse_out, "configure": args.configure, "workspace_gib": ws / 2 ** 30, "batches_cycled": len(batches), "loss": loss,
                    "input_generation_s": gen_s},
         "roofline": roof,
         "roofline_gemm": roof_gemm,

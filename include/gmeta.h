@@ -145,6 +145,10 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               sparse two-hop kernel; 2 = always per-(task, field) pair-count matrices on the matrix
  *               cores (gm_meta_step then returns GM_ERR_CAPACITY when a wave exceeds that path's limits:
  *               bags of at most 127 lookups, pair counts of at most 254, 16384 lookups per task, field and set).
+ *   "gemm_tile_n": column tile of the forward / backward grouped products when tasks get 256-row tiles:
+ *               0 = chosen by the library (128), 128, or 256 (eight waves per workgroup; identical results).
+ *   "pair_tile_rows": most out-rows of a pair-count matrix that the counting kernel holds in LDS at a time
+ *               (0 = as many as fit); identical results.
  * Unknown keys or values give GM_ERR_ARG. */
 int gm_configure(gm_ctx* ctx, const char* key, int64_t value);
 

@@ -22,9 +22,13 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 #define GK 64          // k extent of one LDS tile
 #define GLD (GK + 8)   // LDS row stride in elements: 144 bytes, an odd number of 16-byte units
 
+// Waves: 2 along m, BN / 128 * 2 along n -- 4 waves for 128-wide tiles, 8 for 256-wide ones, so that a wave's share
+// is at most 128 x 64 (128 accumulator registers) whatever the block tile.
 template <int BM, int BN, bool DB, bool KA, bool KB>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
-    constexpr int MI = BM / 64, NI = BN / 64;  // 32x32 blocks per wave in each direction (2x2 waves)
+__global__ __launch_bounds__(BN > 128 ? 2 * (BN / 64) * 64 : 256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
+    constexpr int WN = BN > 128 ? BN / 64 : 2;   // waves along n
+    constexpr int NT = 2 * WN * 64;              // threads
+    constexpr int MI = BM / 64, NI = BN / (32 * WN);  // 32x32 blocks per wave in each direction
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     constexpr int LDA_K = BM + 8, LDB_K = BN + 8;  // KM: LDS row strides of the [GK][BM] and [GK][BN] tiles
     constexpr int TILE = (KA ? GK * LDA_K : BM * GLD) + (KB ? GK * LDB_K : BN * GLD);  // elements of one operand stage
@@ -53,7 +57,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     const int n0 = ntile * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+    const int wm0 = (wave / WN) * (BM / 2), wn0 = (wave % WN) * (BN / WN);
     const int l32 = lane & 31, lhi = lane >> 5;
 
     f32x16 acc[MI][NI];
@@ -65,9 +69,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // global -> register staging: 16-byte chunks, 8 chunks per tile row
-    constexpr int CA = BM * 8 / 256, CB = BN * 8 / 256;  // chunks per thread
+    constexpr int CA = BM * 8 / NT, CB = BN * 8 / NT;  // chunks per thread
+    constexpr int CR = NT / 8;                          // tile rows covered by one chunk round
     uint4 ra[CA], rb[CB];
-    const int crow = tid >> 3, ccol = (tid & 7) * 8;     // chunk c = tid + 256*i: row = crow + 32*i, k = ccol
+    const int crow = tid >> 3, ccol = (tid & 7) * 8;     // chunk c = tid + NT*i: row = crow + CR*i, k = ccol
 
     const int kt_per_pair = (K + GK - 1) / GK;
     const int n_kt = kt_per_pair * a.n_pairs;
@@ -80,31 +85,31 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
         const bf16_t* B = a.B[pr] + (int64_t)g * a.gB[pr] + r0 * a.rB[pr];
         const int64_t lda = a.lda[pr], ldb = a.ldb[pr];
         const bool kok = k0 + ccol < K;
-        if constexpr (KA) {  // contraction slowest: 16-byte chunks along m, chunk c = tid + 256*i of row c / (BM/8)
+        if constexpr (KA) {  // contraction slowest: 16-byte chunks along m, chunk c = tid + NT*i of row c / (BM/8)
 #pragma unroll
             for (int i = 0; i < CA; ++i) {
-                const int ch = tid + 256 * i, kr = ch / (BM / 8), mc = (ch % (BM / 8)) * 8;
+                const int ch = tid + NT * i, kr = ch / (BM / 8), mc = (ch % (BM / 8)) * 8;
                 ra[i] = (k0 + kr < K && m0 + mc < M) ? *reinterpret_cast<const uint4*>(A + (int64_t)(k0 + kr) * lda + m0 + mc)
                                                      : make_uint4(0, 0, 0, 0);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < CA; ++i) {
-                const int m = m0 + crow + 32 * i;
+                const int m = m0 + crow + CR * i;
                 ra[i] = (kok && m < M) ? *reinterpret_cast<const uint4*>(A + (int64_t)m * lda + k0 + ccol) : make_uint4(0, 0, 0, 0);
             }
         }
         if constexpr (KB) {
 #pragma unroll
             for (int i = 0; i < CB; ++i) {
-                const int ch = tid + 256 * i, kr = ch / (BN / 8), nc = (ch % (BN / 8)) * 8;
+                const int ch = tid + NT * i, kr = ch / (BN / 8), nc = (ch % (BN / 8)) * 8;
                 rb[i] = (k0 + kr < K && n0 + nc < N) ? *reinterpret_cast<const uint4*>(B + (int64_t)(k0 + kr) * ldb + n0 + nc)
                                                      : make_uint4(0, 0, 0, 0);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < CB; ++i) {
-                const int n = n0 + crow + 32 * i;
+                const int n = n0 + crow + CR * i;
                 rb[i] = (kok && n < N) ? *reinterpret_cast<const uint4*>(B + (int64_t)n * ldb + k0 + ccol) : make_uint4(0, 0, 0, 0);
             }
         }
@@ -112,15 +117,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntile
     auto store_tile = [&](bf16_t* stage) {
 #pragma unroll
         for (int i = 0; i < CA; ++i) {
-            const int ch = tid + 256 * i;
+            const int ch = tid + NT * i;
             if constexpr (KA) *reinterpret_cast<uint4*>(stage + (ch / (BM / 8)) * LDA_K + (ch % (BM / 8)) * 8) = ra[i];
-            else *reinterpret_cast<uint4*>(stage + (crow + 32 * i) * GLD + ccol) = ra[i];
+            else *reinterpret_cast<uint4*>(stage + (crow + CR * i) * GLD + ccol) = ra[i];
         }
 #pragma unroll
         for (int i = 0; i < CB; ++i) {
-            const int ch = tid + 256 * i;
+            const int ch = tid + NT * i;
             if constexpr (KB) *reinterpret_cast<uint4*>(stage + A_ELEMS + (ch / (BN / 8)) * LDB_K + (ch % (BN / 8)) * 8) = rb[i];
-            else *reinterpret_cast<uint4*>(stage + A_ELEMS + (crow + 32 * i) * GLD + ccol) = rb[i];
+            else *reinterpret_cast<uint4*>(stage + A_ELEMS + (crow + CR * i) * GLD + ccol) = rb[i];
         }
     };
     // 8 contraction values of one column of a contraction-slowest tile, two per register
@@ -277,20 +282,23 @@ static void launch_variant(hipStream_t st, const GemmBArgs& a) {
     if (n_mtiles <= 0 || n_ntiles <= 0) return;
     const int64_t n_tiles = n_mtiles * n_ntiles;
     size_t shmem = ((KA ? (size_t)GK * (BM + 8) : (size_t)BM * GLD) + (KB ? (size_t)GK * (BN + 8) : (size_t)BN * GLD)) * sizeof(bf16_t) * (DB ? 2 : 1);
-    const size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);  // the epilogue's strips
+    constexpr int WN = BN > 128 ? BN / 64 : 2, NT = 2 * WN * 64;
+    const size_t epi = (size_t)(2 * WN) * 32 * (BN / WN + 4) * sizeof(float);  // the epilogue's strips, one per wave
     if (shmem < epi) shmem = epi;
     auto kern = gemm_bf16_kernel<BM, BN, DB, KA, KB>;
     if (shmem > 48 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
 }
 
 // bm: row tile the caller built its (tile_group, tile_m0) lists for (64, 128 or 256).  Measured on the
 // benchmark shapes: one LDS stage with register prefetch beats two stages (occupancy), and 256x128 beats
 // 128x128 and 256x256 when a task has enough rows; the weight-gradient set-up (fixed M, K = rows of a
 // task) is bound by the theta' it writes and keeps 128x128.
-void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm) {
+// bn: 128 or 256 (256 only with bm = 256: eight waves, for products that are bound by the matrix cores)
+void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm, int bn) {
     if (bm == 64) launch_variant<64, 128, false>(st, a);
+    else if (bm == 256 && bn == 256) launch_variant<256, 256, false>(st, a);
     else if (bm == 256) launch_variant<256, 128, false>(st, a);
     else launch_variant<128, 128, false>(st, a);
 }
@@ -299,8 +307,9 @@ void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm) {
 void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a) { launch_variant<128, 128, false, true, true>(st, a); }
 
 // Forward form with the weights as they are stored (B [K, N] = W [d_in, d_out]): no transposed copy of theta.
-void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm) {
+void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm, int bn) {
     if (bm == 64) launch_variant<64, 128, false, false, true>(st, a);
+    else if (bm == 256 && bn == 256) launch_variant<256, 256, false, false, true>(st, a);
     else if (bm == 256) launch_variant<256, 128, false, false, true>(st, a);
     else launch_variant<128, 128, false, false, true>(st, a);
 }

@@ -219,12 +219,12 @@ struct GemmBArgs {
     float* Cacc; int64_t ldcacc, rCacc; float cacc;  // Cacc[(r0 + m)*ldcacc + n] += cacc * value (not with EPI_AXPBY + Cin)
     int cacc_init;                                   // 1: Cacc is not read, = cacc * value (first term of a sum)
 };
-void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm);
+void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm, int bn = 128);
 // same product with both operands stored contraction-slowest: A_p element (k, m) at A + g*gA + r0*rA + k*lda + m,
 // B_p element (k, n) at B + g*gB + r0*rB + k*ldb + n
 void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a);
 // A contraction-contiguous as in launch_gemm_bf16, B stored contraction-slowest (element (k, n) at ... + k*ldb + n)
-void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm);
+void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm, int bn = 128);
 void launch_convert_weights(hipStream_t st, const float* src, int64_t g_src, int G, int rows, int cols, bf16_t* w,
                             bf16_t* wT, int64_t g_dst);
 

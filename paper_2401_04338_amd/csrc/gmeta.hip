@@ -68,6 +68,7 @@ struct gm_ctx {
     u32* d_status = nullptr;
     std::string err;
     int pair_tile_rows = 0;
+    int gemm_tile_n = 0;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
     // optional kernel timing
     bool prof_on = false;
@@ -482,6 +483,11 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
         c->pair_tile_rows = (int)value;
         return GM_OK;
     }
+    if (!strcmp(key, "gemm_tile_n")) {   // column tile of the forward / backward products with 256-row tiles (0: chosen by shape)
+        if (value != 0 && value != 128 && value != 256) return fail(c, GM_ERR_ARG, "gemm_tile_n must be 0, 128 or 256");
+        c->gemm_tile_n = (int)value;
+        return GM_OK;
+    }
     if (!strcmp(key, "row_path")) {
         if (value < 0 || value > 2) return fail(c, GM_ERR_ARG, "row_path must be 0, 1 or 2");
         c->row_path = (int)value;
@@ -595,6 +601,13 @@ struct Grp {  // grouping of one set's rows by task inside the wave
 };
 
 
+// column tile of a forward / backward product: 256 (eight waves) needs 256-row tiles and at least 256 columns
+static int gemm_bn(const gm_ctx* c, int bm, int N) {
+    if (bm != 256 || N < 256) return 128;
+    if (c->gemm_tile_n) return c->gemm_tile_n;
+    return 128;
+}
+
 // out[rows, ld_l] = epi( sum_p in_p[rows, ld_{l-1}] * W_p,l + bias )
 static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, const Theta* th0, const Act* in1,
                      const Theta* th1, const float* bias, int64_t bias_stride, const Act* mask, int epi, Act& out) {
@@ -634,7 +647,7 @@ static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, con
         a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
         a.epi = epi; a.bias = bias; a.gBias = bias_stride;
         if (mask) { a.mask = mask->b; a.ld_mask = mask->ld; }
-        launch_gemm_bf16_bkmajor(c->stream, a, g.bm);
+        launch_gemm_bf16_bkmajor(c->stream, a, g.bm, gemm_bn(c, g.bm, N));
     }
 }
 
@@ -686,7 +699,7 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
         } else {
             a.Cb = out->b; a.ldcb = N; a.rCb = N; a.epi = EPI_MASK; a.mask = mask->b; a.ld_mask = mask->ld;
         }
-        launch_gemm_bf16(c->stream, a, g.bm);
+        launch_gemm_bf16(c->stream, a, g.bm, gemm_bn(c, g.bm, N));
     }
 }
 

@@ -348,6 +348,26 @@ def test_row_paths_bf16_medium_shape(gm, path):
     ctx.close()
 
 
+def test_gemm_wide_tiles_give_the_same_result(gm):
+    """gm_configure("gemm_tile_n", 256): the forward / backward products in 256 x 256 tiles with eight waves.  Every
+    output element is accumulated in the same order as with 128-wide tiles, so the results are identical."""
+    from synth import MEDIUM
+    cfg = MEDIUM.with_(n_tasks=3, rows_per_field=20000, n_support=250, n_query=203)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=3 << 30)
+    dev = ctx.device
+    ds, dq, dp = _to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev)
+    a = ctx.meta_step(ds, dq, dp, cfg.inner_lr, 2, 2)
+    ctx.configure("gemm_tile_n", 256)
+    b = ctx.meta_step(ds, dq, dp, cfg.inner_lr, 2, 2)
+    n = int(a["n_emb_rows"].item())
+    assert torch.equal(a["loss"], b["loss"]) and torch.equal(a["emb_grad"][:n], b["emb_grad"][:n])
+    for l in range(3):
+        assert torch.equal(a["dW"][l], b["dW"][l]) and torch.equal(a["db"][l], b["db"][l])
+    _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_BF16, "bf16 medium3 ragged, 256-wide tiles", operand="bf16")
+    ctx.close()
+
+
 def test_pair_counts_above_a_byte_fall_back(gm):
     """One row per table: every pair of bags shares all its lookups, so counts reach bag_i * bag_j > 255.  The default
     choice must fall back to the sparse kernel (and still match the oracle); the forced pair path must refuse."""
