@@ -243,16 +243,34 @@ __device__ __forceinline__ u64* tf_radix_sorted(const TfRadixLds& L, const SetVi
         if (threadIdx.x == 0) L.sbase[ns] = (u32)n;
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < n; e += NT) {
-        int lo = 0, hi = ns;   // last bag whose first key is <= e (empty bags share their successor's first key)
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (L.sbase[mid] <= (u32)e) lo = mid;
-            else hi = mid;
+    // Every thread builds a run of consecutive keys: one bisection for the bag of its first key, then a walk along the
+    // bag table; the index loads of the run are all requested before the first key is assembled.
+    {
+        const int C = (n + NT - 1) / NT;   // at most TFR_ROUNDS + 1
+        const int e0 = min(n, (int)threadIdx.x * C), e1 = min(n, e0 + C);
+        int lo = 0;
+        if (e0 < e1) {
+            int hi = ns;   // last bag whose first key is <= e0 (empty bags share their successor's first key)
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (L.sbase[mid] <= (u32)e0) lo = mid;
+                else hi = mid;
+            }
         }
-        const int j = e - (int)L.sbase[lo];
-        const u32 idx = (u32)v.indices[v.lookup0 + L.sp0[lo] + j];
-        L.buf[e] = ((u64)(fb + idx) << 32) | ((u64)lo << 16) | (u64)j;
+        u32 meta[TFR_ROUNDS + 1], idx[TFR_ROUNDS + 1];
+#pragma unroll
+        for (int q = 0; q < TFR_ROUNDS + 1; ++q) {
+            const int e = e0 + q;
+            if (e < e1) {
+                while (L.sbase[lo + 1] <= (u32)e) ++lo;   // (the table ends with n: the walk stops)
+                const u32 j = (u32)e - L.sbase[lo];
+                meta[q] = ((u32)lo << 16) | j;
+                idx[q] = (u32)v.indices[v.lookup0 + L.sp0[lo] + j];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < TFR_ROUNDS + 1; ++q)
+            if (e0 + q < e1) L.buf[e0 + q] = ((u64)(fb + idx[q]) << 32) | (u64)meta[q];
     }
     const int passes = (bits + 7) / 8 > 0 ? (bits + 7) / 8 : 1;
     const int width = (bits + passes - 1) / passes > 0 ? (bits + passes - 1) / passes : 1;
