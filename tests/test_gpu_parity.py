@@ -228,6 +228,39 @@ def test_ragged_and_empty_tasks(gm):
     ctx.close()
 
 
+def test_degenerate_batches_in_both_output_shapes(gm):
+    """No tasks at all, and a batch whose bags are all empty (no lookup anywhere): both run, touch no table row and
+    list no row; the dense part of the all-empty-bags batch still matches the oracle."""
+    from synth.generate import SetData
+    cfg = small_cfg(n_tasks=3)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
+    dev = ctx.device
+    dp = _params_dev(params, dev)
+
+    def no_lookups(sd):
+        return SetData(sd.task_offsets, torch.zeros_like(sd.bag_offsets), sd.indices[:0], sd.dense, sd.labels)
+
+    def no_tasks(sd):
+        return SetData(np.zeros(1, dtype=np.int64), sd.bag_offsets[:1] * 0, sd.indices[:0], sd.dense[:0], sd.labels[:0])
+
+    table = torch.zeros_like(dp.emb)
+    for label, s2, q2 in (("no tasks", no_tasks(sup), no_tasks(qry)), ("empty bags", no_lookups(sup), no_lookups(qry))):
+        out = ctx.meta_step(_to_dev(s2, dev), _to_dev(q2, dev), dp, cfg.inner_lr, 2, 2)
+        assert int(out["n_emb_rows"].item()) == 0, label
+        ctx.meta_step(_to_dev(s2, dev), _to_dev(q2, dev), dp, cfg.inner_lr, 2, 2, emb_grad_table=table)
+        assert not table.any(), label
+        if label == "no tasks":
+            assert float(out["loss"].item()) == 0.0 and not out["dW"][0].any()
+        else:
+            ref = O.meta_step(oracle_model(cfg), params.numpy(), s2.numpy(), q2.numpy(), cfg.inner_lr, 2, 2)
+            assert len(ref["emb_rows"]) == 0
+            assert abs(float(out["loss"].item()) - ref["loss"]) <= TOL_FP32 * abs(ref["loss"])
+            for l in range(len(ref["dW"])):
+                assert max(rel_err(out["dW"][l].cpu().numpy(), ref["dW"][l])) <= TOL_FP32, (label, l)
+    ctx.close()
+
+
 def test_error_paths(gm):
     from paper_2401_04338_amd import GMetaError
     cfg = small_cfg(n_tasks=3)
