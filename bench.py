@@ -41,6 +41,7 @@ def main():
                     help="list: coalesced (rows, gradient) lists; table: added into a table-shaped accumulator wave by wave "
                          "(default: list while the call has fewer than 2^31 lookups per set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-outer-update", action="store_true", help="skip the separate timing of gm_scatter_add")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--batches", type=int, default=2, help="distinct pre-generated batches cycled through")
     ap.add_argument("--configure", action="append", default=[], metavar="KEY=VALUE",
@@ -161,6 +162,32 @@ def main():
                     frac=top["frac"], traffic=measured_traffic(cfg.name, top["kernel"]), ms_per_step=top["ms_per_step"],
                     avg_launch_ms=top["avg_launch_ms"])
 
+    # The outer update's sparse half (Alg. 1, global back-propagation on xi with the coalesced gradient): outside the
+    # step, timed on its own with HIP events around the call, on a copy of the tables
+    outer = None
+    if table is None and cfg.n_fields > 0 and not args.no_outer_update:
+        free_now, _ = torch.cuda.mem_get_info()
+        if free_now > params.emb.numel() * 4 + (2 << 30):
+            n_rows = int(out["n_emb_rows"].item())
+            tbl = params.emb.clone()
+            rows_v, grad_v = out["emb_rows"][:n_rows], out["emb_grad"][:n_rows]
+            ctx.scatter_add(tbl, rows_v, grad_v, -1e-3)   # warm-up
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 5
+            torch.cuda.synchronize()
+            ev0.record()
+            for _ in range(reps):
+                ctx.scatter_add(tbl, rows_v, grad_v, -1e-3)
+            ev1.record()
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / reps
+            by = n_rows * (3 * cfg.emb_dim * 4 + 8)   # row read + gradient read + row written + row id
+            pk, un = PEAK["hbm"]
+            outer = dict(kernel="scatter_add_kernel (gm_scatter_add, outside the step)", bound="hbm", rows=n_rows, ms=ms,
+                         achieved=by / (ms * 1e-3) / 1e9, peak=pk, unit=un, frac=by / (ms * 1e-3) / 1e9 / pk,
+                         algorithmic_bytes_per_launch=by)
+            del tbl
+
     if args.copy_probe_gib > 0:
         n = int(args.copy_probe_gib * 2 ** 30)
         src = torch.ones(n, dtype=torch.uint8, device=dev)
@@ -188,6 +215,7 @@ def main():
         "roofline_gemm": roof_gemm,
         "roofline_hbm": top_hbm,
         "kernels": fams,
+        "outer_update_sparse": outer,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
