@@ -133,10 +133,11 @@ struct PairCountArgs {
     uint8_t* mat;
     int want_ss, want_sq;
     int lds_bytes, n_max, max_tile_rows;      // set by the launcher
+    int cls, small_n;                         // set by the launcher: 0 all, 1 only small (task, field)s, 2 only the others
     u32* task_path;                           // [Tw] only tasks flagged 1 are counted; cleared when a count exceeds 254
     u32* status;
 };
-void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int max_tf, int max_rows, int max_tile_rows);
+void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int max_tf, int max_rows, int min_rows, int max_tile_rows);
 struct PairHopOut {
     int enabled;
     const int64_t* mat_off;                   // [Tw]

@@ -1285,12 +1285,15 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             pa.task_path = w.task_path;
             {
                 Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0);
-                int max_rows = 0;
+                int max_rows = 0, min_rows = 1 << 30;
                 for (int t = wp.t0; t < wp.t1; ++t)
-                    if (task_pair_ok(c, B, t, K))
-                        max_rows = std::max<int>(max_rows, (int)std::max(sup->task_offsets[t + 1] - sup->task_offsets[t],
-                                                                         qry->task_offsets[t + 1] - qry->task_offsets[t]));
-                launch_pair_count(st, pa, Tw, max_tf, max_rows, c->pair_tile_rows);
+                    if (task_pair_ok(c, B, t, K)) {
+                        const int r = (int)std::max(sup->task_offsets[t + 1] - sup->task_offsets[t],
+                                                    qry->task_offsets[t + 1] - qry->task_offsets[t]);
+                        max_rows = std::max(max_rows, r);
+                        min_rows = std::min(min_rows, r);
+                    }
+                launch_pair_count(st, pa, Tw, max_tf, max_rows, min_rows, c->pair_tile_rows);
             }
             u32 hs[ST_WORDS];
             if ((rc = read_status(c, hs))) return rc;

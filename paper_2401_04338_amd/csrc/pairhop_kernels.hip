@@ -43,8 +43,9 @@ __host__ __device__ __forceinline__ int pad64(int n) { return (n + 63) & ~63; }
 // row with pairs (hot: the bounds of its two lookup ranges; cold: packed starts and sizes).  After that
 // only LDS is read until the matrix is written out.
 // ------------------------------------------------------------------------------------------------
-#define PC_NT 1024
-#define PC_TPW (64 / (PC_NT / 64))   // MFMA tiles per wave: at most 64 tiles per row tile
+#define PC_TPW 4          // MFMA tiles per wave: a workgroup of NT threads covers NT / 16 tiles per row tile
+#define PC_SMALL_ROWS 128 // samples per set of a 'small' task: 16 tiles, four waves
+#define PC_SMALL_N 1984   // lookups per set of a 'small' (task, field)
 #define PC_HB 32     // hot rows per matrix-core batch (one MFMA contraction step)
 #define PC_HBS 48    // bytes per bag in a count block (16-byte fragment reads; 12 words spread them over the banks)
 #define PC_HOT 4     // a row is hot when one of the two sets looks it up at least this often
@@ -52,7 +53,8 @@ __host__ __device__ __forceinline__ int pad64(int n) { return (n + 63) & ~63; }
 typedef int pc_int4 __attribute__((ext_vector_type(4)));
 typedef int pc_int16 __attribute__((ext_vector_type(16)));
 
-__global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
+template <int NT>
+__global__ __launch_bounds__(NT) void pair_count_kernel(PairCountArgs a) {
     extern __shared__ __attribute__((aligned(16))) u32 pc_lds[];
     __shared__ int sh_nhot, sh_ncold;
     const int f = blockIdx.x, t = blockIdx.y;
@@ -69,6 +71,10 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     const int nu = (int)a.n_slots[tf];
     const int n_in_entries = a.slot_start[B + tf + nu] - (int)B;
     const int n_out_entries = qs ? (int)a.cnt_q[tf] : n_in_entries;
+    if (a.cls) {   // uneven tasks: the small (task, field)s have a launch of their own, with small workgroups
+        const bool small = max(ns, nq) <= PC_SMALL_ROWS && max(n_in_entries, n_out_entries) <= a.small_n;
+        if (small != (a.cls == 1)) return;
+    }
     // LDS, from the end (6 * n_max bytes): the bag of every out lookup and of every in lookup (16 bits each, in the
     // order of the row-sorted lists; one array when both sets are the support set), then the records: hot rows
     // from the front (two words: in range, out range), cold rows with pairs from the back (one word).
@@ -85,14 +91,14 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     {
         const int2* in_list = a.sup_sorted + B;   // {row, slot}, slot-sorted
         const int in_row0 = a.row_off_s[t];
-        for (int e = threadIdx.x; e < n_in_entries; e += PC_NT) in_rows[e] = (uint16_t)(in_list[e].x - in_row0);
+        for (int e = threadIdx.x; e < n_in_entries; e += NT) in_rows[e] = (uint16_t)(in_list[e].x - in_row0);
         if (qs) {
             const int2* out_list = a.qry_sorted + Bq;
             const int out_row0 = a.row_off_q[t];
-            for (int e = threadIdx.x; e < n_out_entries; e += PC_NT) out_rows[e] = (uint16_t)(out_list[e].x - out_row0);
+            for (int e = threadIdx.x; e < n_out_entries; e += NT) out_rows[e] = (uint16_t)(out_list[e].x - out_row0);
         }
     }
-    for (int u = threadIdx.x; u < nu; u += PC_NT) {
+    for (int u = threadIdx.x; u < nu; u += NT) {
         const int lo = a.slot_start[B + tf + u] - (int)B, hi = a.slot_start[B + tf + u + 1] - (int)B;
         int lo2 = lo, hi2 = hi;
         if (qs) { lo2 = a.qseg_lo[B + u] - (int)Bq; hi2 = a.qseg_hi[B + u] - (int)Bq; }
@@ -120,7 +126,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
     }
     const size_t budget = (size_t)a.lds_bytes - 6 * (size_t)nmax;
     int R = min(rowsP, a.max_tile_rows);   // at most 64 MFMA tiles per row tile
-    while (R > 32 && ((size_t)colsP * (R + 4) + (size_t)(R + colsP) * PC_HBS > budget || R * colsP > 65536)) R -= 32;
+    while (R > 32 && ((size_t)colsP * (R + 4) + (size_t)(R + colsP) * PC_HBS > budget || R * colsP > NT * 64)) R -= 32;
     if ((size_t)colsP * (R + 4) + (size_t)(R + colsP) * PC_HBS > budget) {   // not even 32 rows fit: sparse kernel
         if (threadIdx.x == 0) {
             a.task_path[t] = 0u;
@@ -153,11 +159,11 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
             for (int v = 0; v < 16; ++v) acc[q][v] = 0;
         for (int hb = 0; hb < nhot; hb += PC_HB) {
             __syncthreads();   // the previous batch's fragments (or the previous tile) have been read
-            for (int i = threadIdx.x; i < (R + colsP) * PC_HBS / 16; i += PC_NT)   // both count blocks, contiguous
+            for (int i = threadIdx.x; i < (R + colsP) * PC_HBS / 16; i += NT)   // both count blocks, contiguous
                 reinterpret_cast<uint4*>(c_out)[i] = make_uint4(0u, 0u, 0u, 0u);
             __syncthreads();
             // one atomic per lookup (a count is at most the bag's length); a wave per hot row
-            for (int hx = wv; hx < PC_HB && hb + hx < nhot; hx += PC_NT / 64) {
+            for (int hx = wv; hx < PC_HB && hb + hx < nhot; hx += NT / 64) {
                 const u32 r0 = recs[2 * (hb + hx)], r1 = recs[2 * (hb + hx) + 1];
                 const u32 inc = 1u << (8 * (hx & 3));
                 for (int e = (int)(r0 & 0xFFFFu) + lane; e < (int)(r0 >> 16); e += 64)
@@ -196,7 +202,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
         __syncthreads();
         // ---- the other rows, pair by pair; a cell that was at 254 or more before an increment may have
         //      wrapped: reported
-        for (int k = threadIdx.x; k < ncold; k += PC_NT) {
+        for (int k = threadIdx.x; k < ncold; k += NT) {
             const u32 r = recs[RW - 1 - k];
             const int lo = (int)(r & 0x3FFFu), lo2 = (int)((r >> 14) & 0x3FFFu), na = (int)((r >> 28) & 3u), nb = (int)(r >> 30);
             for (int y = 0; y < nb; ++y) {
@@ -213,7 +219,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
         __syncthreads();
         // ---- rows [i0, i0 + rows_here) of M: a thread gathers four consecutive columns of one row
         const int wpr = colsP / 4;
-        for (int w = threadIdx.x; w < rows_here * wpr; w += PC_NT) {
+        for (int w = threadIdx.x; w < rows_here * wpr; w += NT) {
             const int i = w / wpr, j4 = (w - i * wpr) * 4;
             const u32 c0 = tile[(j4 + 0) * ldT + i], c1 = tile[(j4 + 1) * ldT + i];
             const u32 c2 = tile[(j4 + 2) * ldT + i], c3 = tile[(j4 + 3) * ldT + i];
@@ -222,7 +228,7 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
         }
         if (Mt) {  // the transpose is the tile as it lies: row j holds columns [i0, i0 + rows_here)
             const int gpr = rows_here / 4;
-            for (int w = threadIdx.x; w < colsP * gpr; w += PC_NT) {
+            for (int w = threadIdx.x; w < colsP * gpr; w += NT) {
                 const int j = w / gpr, i4 = (w - j * gpr) * 4;
                 *reinterpret_cast<u32*>(Mt + (size_t)j * rowsP + i0 + i4) = *reinterpret_cast<const u32*>(tile + j * ldT + i4);
             }
@@ -236,18 +242,36 @@ __global__ __launch_bounds__(PC_NT) void pair_count_kernel(PairCountArgs a) {
 
 // max_tf: the most lookups any (task, field) of the wave has in one set; max_rows: the most samples any
 // counted task has in one set
-void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int max_tf, int max_rows, int max_tile_rows) {
-    if (Tw <= 0 || a.F <= 0) return;
+template <int NT>
+static void launch_pair_count_nt(hipStream_t st, PairCountArgs a, int Tw, int max_tf, int max_rows) {
     a.n_max = (max_tf + 7) / 8 * 8 + 8;
-    a.max_tile_rows = max_tile_rows > 0 ? (max_tile_rows + 31) / 32 * 32 : 1 << 20;
     // LDS: what the largest (task, field) needs for one tile of all its rows, or all there is
     const size_t P = (size_t)pad64(max_rows > 0 ? max_rows : 1);
     const size_t R = P < (size_t)a.max_tile_rows ? P : (size_t)a.max_tile_rows;
     size_t need = 6 * (size_t)a.n_max + P * (R + 4) + (R + P) * PC_HBS + 64;
     if (need > PAIR_LDS_BYTES) need = PAIR_LDS_BYTES;
     a.lds_bytes = (int)(need / 16 * 16);
-    (void)hipFuncSetAttribute((const void*)pair_count_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, PAIR_LDS_BYTES);
-    hipLaunchKernelGGL(pair_count_kernel, dim3(a.F, Tw, 2), dim3(PC_NT), (size_t)a.lds_bytes, st, a);
+    (void)hipFuncSetAttribute((const void*)pair_count_kernel<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, PAIR_LDS_BYTES);
+    hipLaunchKernelGGL(pair_count_kernel<NT>, dim3(a.F, Tw, 2), dim3(NT), (size_t)a.lds_bytes, st, a);
+}
+
+// max_rows / min_rows: the most / fewest samples any counted task has in one set (the larger of its two sets)
+void launch_pair_count(hipStream_t st, PairCountArgs a, int Tw, int max_tf, int max_rows, int min_rows, int max_tile_rows) {
+    if (Tw <= 0 || a.F <= 0) return;
+    a.max_tile_rows = max_tile_rows > 0 ? (max_tile_rows + 31) / 32 * 32 : 1 << 20;
+    a.small_n = PC_SMALL_N;
+    if (max_rows <= PC_SMALL_ROWS && max_tf <= PC_SMALL_N) {   // every task is small
+        a.cls = 0;
+        launch_pair_count_nt<256>(st, a, Tw, max_tf, max_rows);
+    } else if (max_rows > 2 * PC_SMALL_ROWS && min_rows <= PC_SMALL_ROWS && (int64_t)Tw * a.F >= 32) {   // uneven: two launches, each workgroup checks its class
+        a.cls = 1;
+        launch_pair_count_nt<256>(st, a, Tw, max_tf < PC_SMALL_N ? max_tf : PC_SMALL_N, PC_SMALL_ROWS);
+        a.cls = 2;
+        launch_pair_count_nt<1024>(st, a, Tw, max_tf, max_rows);
+    } else {
+        a.cls = 0;
+        launch_pair_count_nt<1024>(st, a, Tw, max_tf, max_rows);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
