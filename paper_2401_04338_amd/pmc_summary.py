@@ -53,7 +53,7 @@ def main():
     ap.add_argument("--workload", required=True)
     ap.add_argument("--steps", type=int, default=1, help="meta steps the profiled run made (timed + warm-up + 2 profiling)")
     ap.add_argument("--json", default=None)
-    ap.add_argument("--command", default="")
+    ap.add_argument("--bench-args", default="", help="bench.py arguments of the two profiled runs (for the header)")
     a = ap.parse_args()
     fetch, write = read(a.fetch, "FETCH_SIZE"), read(a.write, "WRITE_SIZE")
     known = a.copy_gib * 2 ** 30
@@ -69,8 +69,15 @@ def main():
     cf, cw = copy_reading(fetch), copy_reading(write)
     sf, sw = (known / cf if cf > 0 else 1.0), (known / cw if cw > 0 else 1.0)
     print(f"# HBM traffic per kernel family, workload {a.workload}")
-    if a.command:
-        print(f"# command: {a.command}")
+    ba = a.bench_args or "<bench arguments>"
+    print("# commands (from /tmp, TMPDIR=/tmp), one counter per run:")
+    print(f"#   rocprofv3 --pmc FETCH_SIZE --output-format csv -d <f> -o p -- python3 /root/repo/bench.py {ba}")
+    print(f"#   rocprofv3 --pmc WRITE_SIZE --output-format csv -d <w> -o p -- python3 /root/repo/bench.py {ba}")
+    print(f"#   python -m paper_2401_04338_amd.pmc_summary --fetch <f>/.../p_counter_collection.csv --write <w>/.../p_counter_collection.csv "
+          f"--copy-gib {a.copy_gib:g} --workload {a.workload} --steps {a.steps} --bench-args '{ba}' --json <json>")
+    print(f"# {a.steps} meta steps per run (timed + warm-up + 2 event-timed).  FETCH_SIZE / WRITE_SIZE are KiB per dispatch; the run's "
+          f"{a.copy_gib:g} GiB device copy (--copy-probe-gib) is the")
+    print("# transfer of known size that scales them.  \"bytes/launch\" is per kernel dispatch of the family.")
     print(f"# copy probe of {known:.0f} B read as FETCH_SIZE {cf:.0f} B, WRITE_SIZE {cw:.0f} B -> scale factors {sf:.3f}, {sw:.3f}")
     print(f"# {'family':24s} {'dispatches/step':>16s} {'fetch GB/step':>14s} {'write GB/step':>14s} {'bytes/launch':>14s}")
     out = {}

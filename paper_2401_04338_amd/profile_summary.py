@@ -1,8 +1,8 @@
 """Turns the rocpd database that `rocprofv3 --kernel-trace --stats` writes into a short text summary.
 
-Usage: python -m paper_2401_04338_amd.profile_summary <results.db> [top_n]
+Usage: python -m paper_2401_04338_amd.profile_summary <results.db> [top_n] [bench arguments of the profiled run]
 Only this package's kernels are listed by name; everything else (PyTorch's generator kernels that
-build the synthetic inputs) is summed into one line.
+build the synthetic inputs) is summed into one line.  The header states the command that made the trace.
 """
 import sqlite3
 import sys
@@ -27,4 +27,9 @@ def summarize(db_path: str, top_n: int = 40) -> str:
 
 
 if __name__ == "__main__":
-    print(summarize(sys.argv[1], int(sys.argv[2]) if len(sys.argv) > 2 else 40))
+    top = int(sys.argv[2]) if len(sys.argv) > 2 else 40
+    bench_args = " ".join(sys.argv[3:]) or "<bench arguments>"
+    print("# rocprofv3 kernel trace of gm_meta_step (per-kernel totals over the whole run: warm-up, timed and event-timed steps)")
+    print(f"# command (from /tmp, TMPDIR=/tmp): rocprofv3 --kernel-trace --stats -d <out> -o <name> -- python3 /root/repo/bench.py {bench_args}")
+    print(f"# summary made with: python -m paper_2401_04338_amd.profile_summary <out>/<name>_results.db {top} {bench_args}")
+    print(summarize(sys.argv[1], top))
