@@ -305,6 +305,22 @@ def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
                 emb_rows=emb_rows, emb_grad=emb_grad)
 
 
+def meta_train_step(model: Model, params, sup, qry, alpha: float, K: int, order: int, beta: float,
+                    operand: str = "fp64"):
+    """One whole iteration of Alg. 1 on one shard: the step above, then the two global back-propagation steps with
+    the outer step size beta (plain SGD on the summed meta-gradient): theta <- theta - beta * sum_t grad_theta and,
+    for every looked-up row, xi[row] <- xi[row] - beta * sum_t grad_xi[row].
+
+    Returns (new params dict (float64 copies; the input is not modified), loss of the step before the update).
+    """
+    r = meta_step(model, params, sup, qry, alpha, K, order, operand=operand)
+    emb = np.array(params["emb"], dtype=np.float64, copy=True)
+    emb[r["emb_rows"]] -= beta * r["emb_grad"]
+    W = [np.asarray(w, dtype=np.float64) - beta * g for w, g in zip(params["W"], r["dW"])]
+    b = [np.asarray(x, dtype=np.float64) - beta * g for x, g in zip(params["b"], r["db"])]
+    return dict(emb=emb, W=W, b=b), r["loss"]
+
+
 # --------------------------------------------------------------------------
 # integer side of the step: what the index preparation must produce, exactly
 # --------------------------------------------------------------------------

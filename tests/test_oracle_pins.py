@@ -452,3 +452,40 @@ def test_bf16_operands_stay_close_to_float64_where_no_mask_decides():
     assert abs(a["loss"] - b["loss"]) / a["loss"] < 5e-3
     assert abs(a["loss"] - b["loss"]) > 0.0
     assert np.array_equal(a["emb_rows"], b["emb_rows"])
+
+
+# ---------------------------------------------------------------- the outer update (Alg. 1, global back-propagation)
+@pytest.mark.parametrize("K", [0, 2])
+def test_train_step_descends_the_meta_objective_by_beta_times_the_squared_gradient(K):
+    """phi' = phi - beta * g with g the exact (second-order) meta-gradient: for small beta the objective must fall by
+    beta * |g|^2 to first order.  A wrong sign, a wrong scale, or an update landing on other rows than the gradient's
+    breaks the ratio."""
+    cfg = small_cfg(n_tasks=4, inner_lr=0.2)
+    model, params, sup, qry = oracle_inputs(cfg, emb_std=0.3)
+    alpha = cfg.inner_lr
+    g = O.meta_step(model, params, sup, qry, alpha, K, 2)
+    g2 = float((g["emb_grad"] ** 2).sum() + sum((w ** 2).sum() for w in g["dW"]) + sum((b ** 2).sum() for b in g["db"]))
+    assert g2 > 0
+    j0 = _objective(model, params, sup, qry, alpha, K)
+    for beta in (1e-5, 1e-6):
+        new, loss = O.meta_train_step(model, params, sup, qry, alpha, K, 2, beta)
+        assert loss == g["loss"] == j0
+        j1 = _objective(model, new, sup, qry, alpha, K)
+        ratio = (j0 - j1) / (beta * g2)
+        assert abs(ratio - 1.0) < 2e-3, (K, beta, ratio)
+
+
+def test_train_step_touches_only_looked_up_rows_and_is_the_identity_for_beta_zero():
+    cfg = small_cfg(n_tasks=3, rows_per_field=200)
+    model, params, sup, qry = oracle_inputs(cfg, emb_std=0.3)
+    new, _ = O.meta_train_step(model, params, sup, qry, cfg.inner_lr, 2, 2, 0.05)
+    g = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 2)
+    touched = np.zeros(params["emb"].shape[0], dtype=bool)
+    touched[g["emb_rows"]] = True
+    assert np.array_equal(new["emb"][~touched], params["emb"][~touched].astype(np.float64))
+    moved = np.abs(new["emb"] - params["emb"]).sum(axis=1) > 0
+    assert moved[touched].mean() > 0.5 and not moved[~touched].any()
+    same, _ = O.meta_train_step(model, params, sup, qry, cfg.inner_lr, 2, 2, 0.0)
+    assert np.array_equal(same["emb"], params["emb"].astype(np.float64))
+    for a, b in zip(same["W"] + same["b"], list(params["W"]) + list(params["b"])):
+        assert np.array_equal(a, np.asarray(b, dtype=np.float64))
