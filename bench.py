@@ -42,6 +42,9 @@ def main():
                          "(default: list while the call has fewer than 2^31 lookups per set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-outer-update", action="store_true", help="skip the separate timing of gm_scatter_add")
+    ap.add_argument("--train", type=float, default=None, metavar="OUTER_LR",
+                    help="time whole training iterations (gm_meta_train_step: the step and the outer update with this step "
+                         "size, parameters updated in place) instead of the step alone")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--batches", type=int, default=2, help="distinct pre-generated batches cycled through")
     ap.add_argument("--configure", action="append", default=[], metavar="KEY=VALUE",
@@ -88,6 +91,12 @@ def main():
     cap_rows = 0 if table is not None else min(nnz, cfg.total_rows)
     out_bytes = cap_rows * (cfg.emb_dim * 4 + 8)
     ws = int(need * 1.02)
+    if args.train is not None:   # the meta-gradient lists then live in the workspace, not in caller buffers
+        ws += out_bytes + (1 << 20)
+        if table is not None:
+            print("--train uses the row-list output (fewer than 2^31 lookups per set)", file=sys.stderr)
+            sys.exit(2)
+        cap_rows, out_bytes = 0, 0
     if args.workspace_gib is not None:
         ws = int(args.workspace_gib * 2 ** 30)
     ws = min(ws, int(free_b - out_bytes - (4 << 30)))
@@ -99,6 +108,9 @@ def main():
 
     def step(i):
         s, q = batches[i % len(batches)]
+        if args.train is not None:
+            ctx.meta_train_step(s, q, params, cfg.inner_lr, K, order, args.train, loss=out["loss"])
+            return out
         return ctx.meta_step(s, q, params, cfg.inner_lr, K, order, out=out, emb_grad_table=table)
 
     for i in range(args.warmup):
@@ -165,7 +177,7 @@ def main():
     # The outer update's sparse half (Alg. 1, global back-propagation on xi with the coalesced gradient): outside the
     # step, timed on its own with HIP events around the call, on a copy of the tables
     outer = None
-    if table is None and cfg.n_fields > 0 and not args.no_outer_update:
+    if table is None and cfg.n_fields > 0 and not args.no_outer_update and args.train is None:
         free_now, _ = torch.cuda.mem_get_info()
         if free_now > params.emb.numel() * 4 + (2 << 30):
             n_rows = int(out["n_emb_rows"].item())
@@ -209,6 +221,7 @@ def main():
         "config": {"workload": cfg.name, "n_tasks": cfg.n_tasks, "samples_per_step": S, "lookups_per_step": nnz,
                    "n_fields": cfg.n_fields, "rows_per_field": cfg.rows_per_field, "emb_dim": cfg.emb_dim,
                    "mlp": list(cfg.layer_dims), "inner_steps": K, "order": order, "inner_lr": cfg.inner_lr,
+                   "outer_update": None if args.train is None else {"fused": True, "outer_lr": args.train},
                    "sparse_out": sparse_out, "configure": args.configure, "workspace_gib": ws / 2 ** 30, "batches_cycled": len(batches), "loss": loss,
                    "input_generation_s": gen_s},
         "roofline": roof,

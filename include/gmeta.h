@@ -11,7 +11,7 @@
  *   gradients of L^Query w.r.t. the META parameters, summed over
  *   tasks: dense part (theta) and sparse part (xi)                   (Alg. 1, global back-propagation
  *                                                                     steps; Sec. 2.1.3 sum rule)
- * The beta update itself is gm_scatter_add (sparse) / the caller's (dense).
+ * The beta update: gm_meta_train_step (the step and the update in one call), or gm_scatter_add (sparse half alone).
  *
  * Model: x_s = concat_f( sum_{r in bag(s,f)} xi_f[r] ) || dense_s ; MLP d_0 -> ... -> d_L = 1 with
  * ReLU on hidden layers; loss = mean over a set's samples of the binary cross-entropy with logits.
@@ -115,6 +115,20 @@ size_t gm_workspace_bytes(const gm_model_desc* model, int32_t n_tasks, int64_t n
 int gm_meta_step(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_set* query,
                  const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
                  float* loss, gm_grads* out);
+
+/* One whole iteration of Alg. 1 on one shard: gm_meta_step, then the two global back-propagation steps
+ * applied with the outer step size beta (plain SGD on the summed meta-gradient), IN PLACE:
+ *   W_l -= outer_lr * dW_l,  b_l -= outer_lr * db_l,  emb[row, :] -= outer_lr * grad[row, :] for every row
+ *   that a support or query sample looks up.
+ * params: as for gm_meta_step, but the DEVICE arrays it points to are written (emb, every W_l, every b_l).
+ * loss: DEVICE scalar, the step's sum_t L^Query_t (before the update).  task_loss: DEVICE [T] or NULL.
+ * The meta-gradient lists live in the context's workspace (rows * (4 D + 8) bytes on top of what the step
+ * needs, rows = min(lookups, table rows); GM_ERR_WORKSPACE if that does not fit).  The row-list form of the
+ * sparse gradient is used, so each set must hold fewer than 2^31 lookups.  Errors as gm_meta_step; on an
+ * error nothing has been updated. */
+int gm_meta_train_step(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_set* query,
+                       const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
+                       float outer_lr, float* loss, float* task_loss);
 
 /* table[rows[i], :] += scale * grad[i, :]  (Alg. 1, global back-propagation on xi, on one shard,
  * with scale = -beta).  rows must be distinct (as gm_meta_step emits them).  All DEVICE. */

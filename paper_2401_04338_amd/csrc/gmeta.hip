@@ -1544,6 +1544,62 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     return GM_OK;
 }
 
+extern "C" int gm_meta_train_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set* qry, const gm_params* params,
+                                  float alpha, int32_t K, int32_t order, float beta, float* loss, float* task_loss) {
+    if (!c) return GM_ERR_ARG;
+    if (!sup || !qry || sup->nnz < 0 || qry->nnz < 0) return fail(c, GM_ERR_ARG, "null set / negative size");
+    if (!params || !params->W || !params->b) return fail(c, GM_ERR_ARG, "null params");
+    HIPCHK(c, hipSetDevice(c->device));
+    const int L = c->L, D = c->D;
+    // the meta-gradient of this iteration lives at the top of the workspace; the step gets what is below it
+    const int64_t capacity = c->F > 0 ? std::min<int64_t>(sup->nnz + qry->nnz, c->field_base[c->F]) : 0;
+    int64_t n_dense = 0;
+    for (int l = 0; l < L; ++l) n_dense += (int64_t)(c->dims[l] + 1) * c->dims[l + 1];
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t need = up((size_t)n_dense * 4) + up((size_t)capacity * 8) + up((size_t)capacity * std::max(D, 1) * 4) + 256;
+    if (need + c->persistent + (1 << 20) > c->ws_bytes)
+        return fail(c, GM_ERR_WORKSPACE, "workspace of %zu bytes cannot hold the meta-gradient (%zu bytes) beside the step", c->ws_bytes, need);
+    const size_t full = c->ws_bytes;
+    char* top = c->ws + (full - need) / 256 * 256;
+    float* dense = reinterpret_cast<float*>(top);
+    int64_t* rows = reinterpret_cast<int64_t*>(top + up((size_t)n_dense * 4));
+    float* grad = reinterpret_cast<float*>(reinterpret_cast<char*>(rows) + up((size_t)capacity * 8));
+    int64_t* n_rows = reinterpret_cast<int64_t*>(reinterpret_cast<char*>(grad) + up((size_t)capacity * std::max(D, 1) * 4));
+    std::vector<float*> dW(L), db(L);
+    {
+        float* p = dense;
+        for (int l = 0; l < L; ++l) {
+            dW[l] = p; p += (int64_t)c->dims[l] * c->dims[l + 1];
+            db[l] = p; p += c->dims[l + 1];
+        }
+    }
+    gm_grads out;
+    memset(&out, 0, sizeof out);
+    out.dW = dW.data(); out.db = db.data();
+    out.emb_rows = rows; out.emb_grad = grad; out.n_emb_rows = n_rows; out.emb_rows_capacity = capacity;
+    out.task_loss = task_loss;
+    c->ws_bytes = static_cast<size_t>(top - c->ws);
+    const int rc = gm_meta_step(c, T, sup, qry, params, alpha, K, order, loss, &out);
+    c->ws_bytes = full;
+    if (rc != GM_OK) return rc;
+    hipStream_t st = c->stream;
+    int64_t h_rows = 0;
+    HIPCHK(c, hipMemcpyAsync(&h_rows, n_rows, sizeof h_rows, hipMemcpyDeviceToHost, st));
+    for (int l = 0; l < L; ++l) {
+        launch_axpy(st, (int64_t)c->dims[l] * c->dims[l + 1], -beta, dW[l], const_cast<float*>(params->W[l]));
+        launch_axpy(st, c->dims[l + 1], -beta, db[l], const_cast<float*>(params->b[l]));
+    }
+    HIPCHK(c, hipStreamSynchronize(st));
+    if (c->F > 0 && h_rows > 0) {
+        Prof p(c, "scatter_add", (double)h_rows * (12.0 * D + 8), 0);
+        launch_scatter_add(st, D, const_cast<float*>(params->emb), rows, grad, h_rows, -beta);
+    }
+    HIPCHK(c, hipStreamSynchronize(st));
+    HIPCHK(c, hipGetLastError());
+    prof_drain(c);
+    return GM_OK;
+}
+
 extern "C" int gm_scatter_add(gm_ctx* c, float* table, const int64_t* rows, const float* grad, int64_t n_rows,
                               float scale) {
     if (!c) return GM_ERR_ARG;

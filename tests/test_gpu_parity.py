@@ -291,6 +291,41 @@ def test_error_paths(gm):
     ctx.close()
 
 
+@pytest.mark.parametrize("bf", [0, 1], ids=["fp32", "bf16"])
+def test_train_steps_follow_the_oracle(gm, bf):
+    """gm_meta_train_step: three iterations of Alg. 1 (a fresh batch each), parameters updated in place; losses and
+    parameters after every iteration against the oracle's meta_train_step run on its own copy."""
+    from synth.generate import Params
+    cfg = SMALL.with_(n_tasks=4, n_support=40, n_query=24, n_fields=5, emb_dim=32, rows_per_field=3000, bag_max=6,
+                      layer_dims=(5 * 32 + 13, 64, 32, 1), inner_lr=0.05, mlp_dtype=bf)
+    beta, K, order = 0.02, 2, 2
+    tol = TOL_BF16 if bf else TOL_FP32
+    params = make_params(cfg, "cpu", emb_std=0.1)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+    dev = ctx.device
+    dp = Params(params.emb.to(dev).clone(), [w.to(dev).clone() for w in params.W], [b.to(dev).clone() for b in params.b])
+    ref_p = params.numpy()
+    ref_p = dict(emb=ref_p["emb"].astype(np.float64), W=[w.astype(np.float64) for w in ref_p["W"]],
+                 b=[b.astype(np.float64) for b in ref_p["b"]])
+    for it in range(3):
+        sup, qry = make_batch(cfg, it, "cpu")
+        loss = ctx.meta_train_step(_to_dev(sup, dev), _to_dev(qry, dev), dp, cfg.inner_lr, K, order, beta)
+        ref_p, ref_loss = O.meta_train_step(oracle_model(cfg), ref_p, sup.numpy(), qry.numpy(), cfg.inner_lr, K, order, beta,
+                                            operand="bf16" if bf else "fp64")
+        e = {"loss": abs(float(loss.item()) - ref_loss) / abs(ref_loss),
+             "emb": max(rel_err(dp.emb.cpu().numpy(), ref_p["emb"]))}
+        for l in range(len(ref_p["W"])):
+            e[f"W{l}"] = max(rel_err(dp.W[l].cpu().numpy(), ref_p["W"][l]))
+            e[f"b{l}"] = max(rel_err(dp.b[l].cpu().numpy(), ref_p["b"][l]))
+        # what moved, against what the oracle moved (parameters are dominated by their initial values)
+        d_emb = max(rel_err(dp.emb.cpu().numpy().astype(np.float64) - params.emb.numpy(), ref_p["emb"] - params.emb.numpy()))
+        d_w0 = max(rel_err(dp.W[0].cpu().numpy().astype(np.float64) - params.W[0].numpy(), ref_p["W"][0] - params.W[0].numpy()))
+        print(f"train it {it} bf16={bf}", {k: f"{v:.1e}" for k, v in e.items()}, f"moved: emb {d_emb:.1e} W0 {d_w0:.1e}", flush=True)
+        assert all(v <= tol for v in e.values()), (it, e)
+        assert d_emb <= 5 * tol and d_w0 <= 5 * tol, (it, d_emb, d_w0)
+    ctx.close()
+
+
 def test_scatter_add_is_the_outer_update(gm):
     cfg = small_cfg(n_tasks=3)
     sup, qry, params = _inputs(cfg)
