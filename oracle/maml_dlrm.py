@@ -198,8 +198,14 @@ def hvp(acts, z, y, W, deltas, vW, vb, vx, q=_identity):
 # one task
 # --------------------------------------------------------------------------
 def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int, order: int,
-                   full_table: bool = False, operand: str = "fp64"):
+                   full_table: bool = False, operand: str = "fp64", adapt_rows: bool = True):
     """MAML for task t.  Returns (L^Query, gW, gb, rows, gxi[rows]) w.r.t. the META parameters.
+
+    adapt_rows=False is the variant that adapts the dense parameters only (the way the paper's framework
+    also hosts MeLU, Sec. 3.1: embeddings are meta-parameters that the inner loop reads but does not update):
+    phi_k = (theta_k, xi), theta_{k+1} = theta_k - alpha grad_theta L^Sup(theta_k, xi).  The meta-gradient
+    w.r.t. xi is then the query loss's own plus, for order 2, the path through every theta_k:
+    -alpha * d/dxi <grad_theta L^Sup(theta_k, xi), v_theta,k+1>.
 
     full_table=True copies the whole table into the task (brute force: phi_0 is
     all of xi); the default keeps only the rows the task looks up.  Both must agree.
@@ -240,8 +246,8 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
         acts, z = forward(x, W, b, q)
         dW, db, dx, deltas = backward(acts, z, ys, W, q)
         tape.append((acts, z, W, deltas))
-        gE = rows_grad(dx, loc_s, bag_s)
-        E = E - alpha * gE
+        if adapt_rows:
+            E = E - alpha * rows_grad(dx, loc_s, bag_s)
         W = [w - alpha * g for w, g in zip(W, dW)]
         b = [v - alpha * g for v, g in zip(b, db)]
 
@@ -255,7 +261,10 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
     # chain back through the inner steps: v_k = v_{k+1} - alpha * H_k v_{k+1}
     if order == 2:
         for acts_k, z_k, W_k, deltas_k in reversed(tape):
-            vx = np.concatenate([pool(model, vE, loc_s, bag_s, ns), np.zeros_like(dense_s)], axis=1)
+            if adapt_rows:
+                vx = np.concatenate([pool(model, vE, loc_s, bag_s, ns), np.zeros_like(dense_s)], axis=1)
+            else:   # xi is not a state of the inner loop: no direction on the inputs
+                vx = np.zeros((ns, FD + dense_s.shape[1]))
             hW, hb, hx = hvp(acts_k, z_k, ys, W_k, deltas_k, vW, vb, vx, q)
             hE = rows_grad(hx, loc_s, bag_s)
             vW = [v - alpha * h for v, h in zip(vW, hW)]
@@ -273,7 +282,8 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
 # the whole step
 # --------------------------------------------------------------------------
 def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
-              tasks: Optional[Sequence[int]] = None, full_table: bool = False, operand: str = "fp64"):
+              tasks: Optional[Sequence[int]] = None, full_table: bool = False, operand: str = "fp64",
+              adapt_rows: bool = True):
     """Sum of the per-task meta-gradients (Alg. 1, global back-propagation steps).
 
     Returns dict(loss, task_loss[T], dW[l], db[l], emb_rows (ascending unique
@@ -287,7 +297,8 @@ def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
     task_loss = np.zeros(len(tasks))
     parts_rows, parts_grad = [], []
     for i, t in enumerate(tasks):
-        lq, vW, vb, rows, vE = task_meta_grad(model, params, sup, qry, t, alpha, K, order, full_table, operand)
+        lq, vW, vb, rows, vE = task_meta_grad(model, params, sup, qry, t, alpha, K, order, full_table, operand,
+                                              adapt_rows)
         task_loss[i] = lq
         for l in range(L):
             gW[l] += vW[l]
@@ -306,14 +317,14 @@ def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
 
 
 def meta_train_step(model: Model, params, sup, qry, alpha: float, K: int, order: int, beta: float,
-                    operand: str = "fp64"):
+                    operand: str = "fp64", adapt_rows: bool = True):
     """One whole iteration of Alg. 1 on one shard: the step above, then the two global back-propagation steps with
     the outer step size beta (plain SGD on the summed meta-gradient): theta <- theta - beta * sum_t grad_theta and,
     for every looked-up row, xi[row] <- xi[row] - beta * sum_t grad_xi[row].
 
     Returns (new params dict (float64 copies; the input is not modified), loss of the step before the update).
     """
-    r = meta_step(model, params, sup, qry, alpha, K, order, operand=operand)
+    r = meta_step(model, params, sup, qry, alpha, K, order, operand=operand, adapt_rows=adapt_rows)
     emb = np.array(params["emb"], dtype=np.float64, copy=True)
     emb[r["emb_rows"]] -= beta * r["emb_grad"]
     W = [np.asarray(w, dtype=np.float64) - beta * g for w, g in zip(params["W"], r["dW"])]

@@ -22,9 +22,9 @@ def _full_grad(model, out):
     return g
 
 
-def _objective(model, params, sup, qry, alpha, K):
+def _objective(model, params, sup, qry, alpha, K, adapt_rows=True):
     """M(phi) = sum_t L^Query_t(phi_K(phi)): forward value only."""
-    return O.meta_step(model, params, sup, qry, alpha, K, 1)["loss"]
+    return O.meta_step(model, params, sup, qry, alpha, K, 1, adapt_rows=adapt_rows)["loss"]
 
 
 def _min_hidden_margin(model, params, sup, qry, alpha, K):
@@ -98,12 +98,12 @@ def test_zero_weights_give_log2():
 
 
 # ---------------------------------------------------------------- finite differences
-def _fd_check(cfg, K, n_coords=40, eps=1e-5, tol=2e-6, emb_std=0.3):
+def _fd_check(cfg, K, n_coords=40, eps=1e-5, tol=2e-6, emb_std=0.3, adapt_rows=True):
     model, params, sup, qry = oracle_inputs(cfg, emb_std=emb_std)
     params = {k: ([a.astype(np.float64) for a in v] if isinstance(v, list) else v.astype(np.float64))
               for k, v in params.items()}
     alpha = cfg.inner_lr
-    out = O.meta_step(model, params, sup, qry, alpha, K, 2)
+    out = O.meta_step(model, params, sup, qry, alpha, K, 2, adapt_rows=adapt_rows)
     gfull = _full_grad(model, out)
     rng = np.random.default_rng(1)
     checks = []
@@ -127,9 +127,9 @@ def _fd_check(cfg, K, n_coords=40, eps=1e-5, tol=2e-6, emb_std=0.3):
         arr = params["emb"] if kind == "emb" else params[kind][l]
         old = arr[i]
         arr[i] = old + eps
-        fp = _objective(model, params, sup, qry, alpha, K)
+        fp = _objective(model, params, sup, qry, alpha, K, adapt_rows)
         arr[i] = old - eps
-        fm = _objective(model, params, sup, qry, alpha, K)
+        fm = _objective(model, params, sup, qry, alpha, K, adapt_rows)
         arr[i] = old
         fd = (fp - fm) / (2 * eps)
         worst = max(worst, abs(fd - g) / scale)
@@ -489,3 +489,26 @@ def test_train_step_touches_only_looked_up_rows_and_is_the_identity_for_beta_zer
     assert np.array_equal(same["emb"], params["emb"].astype(np.float64))
     for a, b in zip(same["W"] + same["b"], list(params["W"]) + list(params["b"])):
         assert np.array_equal(a, np.asarray(b, dtype=np.float64))
+
+
+# ---------------------------------------------------------------- dense-only adaptation (embeddings read, not updated)
+@pytest.mark.parametrize("K", [1, 2])
+def test_dense_only_adaptation_by_central_differences(K):
+    """adapt_rows=False, order 2: the exact gradient of its own objective, theta and xi parts (the xi part includes
+    the path through the adapted theta)."""
+    _fd_check(small_cfg(inner_lr=0.3), K=K, adapt_rows=False)
+
+
+def test_dense_only_adaptation_differs_from_the_full_one_and_agrees_without_sparse_fields_or_steps():
+    cfg = small_cfg(inner_lr=0.3)
+    model, params, sup, qry = oracle_inputs(cfg, emb_std=0.3)
+    full = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 2)
+    dense = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 2, adapt_rows=False)
+    assert abs(full["loss"] - dense["loss"]) > 1e-6 * abs(full["loss"])          # the rows' adaptation matters here
+    assert np.array_equal(full["emb_rows"], dense["emb_rows"])
+    a = O.meta_step(model, params, sup, qry, cfg.inner_lr, 0, 2)
+    b = O.meta_step(model, params, sup, qry, cfg.inner_lr, 0, 2, adapt_rows=False)
+    assert a["loss"] == b["loss"] and np.array_equal(a["emb_grad"], b["emb_grad"])   # K = 0: nothing is adapted
+    # first order: support-only rows get exactly nothing either way, but the query side sees unadapted rows
+    d1 = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 1, adapt_rows=False)
+    assert abs(d1["loss"] - dense["loss"]) == 0.0
