@@ -211,7 +211,8 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, cfg_gen, K, order, args.cpu_seconds, params.numpy())
+        cpu = cpu_baseline(cfg, cfg_gen, K, order, args.cpu_seconds, params.numpy(),
+                           adapt_rows="adapt_rows=0" not in args.configure)
 
     line = {
         "metric": "meta-train samples/sec (support+query) on 1 GPU", "value": value, "unit": "samples/s",
@@ -245,7 +246,7 @@ def measured_traffic(workload, family):
         return None
 
 
-def cpu_baseline(cfg, cfg_gen, K, order, budget_s, params):
+def cpu_baseline(cfg, cfg_gen, K, order, budget_s, params, adapt_rows=True):
     """The CPU oracle, as it stands, on a task subset of the same workload (about budget_s of CPU work)."""
     import numpy as np
     from oracle import maml_dlrm as O
@@ -264,7 +265,7 @@ def cpu_baseline(cfg, cfg_gen, K, order, budget_s, params):
         tasks = list(range(done, min(cfg.n_tasks, done + n)))
         sup, qry = make_batch(cfg_gen, 0, "cpu", tasks)
         t0 = time.perf_counter()
-        O.meta_step(model, params, sup.numpy(), qry.numpy(), cfg.inner_lr, K, order, operand=operand)
+        O.meta_step(model, params, sup.numpy(), qry.numpy(), cfg.inner_lr, K, order, operand=operand, adapt_rows=adapt_rows)
         dt = time.perf_counter() - t0
         spent += dt
         samples += sup.n_samples + qry.n_samples

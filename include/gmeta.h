@@ -153,12 +153,18 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
                   int64_t* emb_rows, int64_t* seg_counts, int64_t* n_emb_rows,
                   int64_t emb_rows_capacity);
 
-/* Implementation choices that change results by rounding order only (for measurement and tests).
+/* Settings of a context.  All but "adapt_rows" are implementation choices that change results by rounding
+ * order only (for measurement and tests).
  *   "row_path": how the task-local row arithmetic (inner-loop row update, overlap update of Sec. 2.1.2 and
  *               their tangents) is carried out: 0 = chosen per wave of tasks (default); 1 = always the
  *               sparse two-hop kernel; 2 = always per-(task, field) pair-count matrices on the matrix
  *               cores (gm_meta_step then returns GM_ERR_CAPACITY when a wave exceeds that path's limits:
  *               bags of at most 127 lookups, pair counts of at most 254, 16384 lookups per task, field and set).
+ *   "adapt_rows": 1 (default) = the inner loop adapts the dense parameters and the looked-up embedding rows
+ *               (Alg. 1); 0 = it adapts the dense parameters only and reads the embeddings as they are (the
+ *               dense-only family of optimisation-based meta learners that Sec. 3.1 runs on the same
+ *               framework); the meta-gradient w.r.t. the embeddings then is the query loss's own plus, for
+ *               order 2, the path through the adapted dense parameters.  THIS ONE CHANGES WHAT IS COMPUTED.
  *   "gemm_tile_n": column tile of the forward / backward grouped products when tasks get 256-row tiles:
  *               0 = chosen by the library (128), 128, or 256 (eight waves per workgroup; identical results).
  *   "pair_tile_rows": most out-rows of a pair-count matrix that the counting kernel holds in LDS at a time

@@ -68,6 +68,7 @@ struct gm_ctx {
     u32* d_status = nullptr;
     std::string err;
     int pair_tile_rows = 0;
+    int adapt_rows = 1;   // 0: the inner loop adapts the dense parameters only (embedding rows are read, not updated)
     int gemm_tile_n = 0;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
     // optional kernel timing
@@ -488,6 +489,11 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
         c->gemm_tile_n = (int)value;
         return GM_OK;
     }
+    if (!strcmp(key, "adapt_rows")) {
+        if (value != 0 && value != 1) return fail(c, GM_ERR_ARG, "adapt_rows must be 0 or 1");
+        c->adapt_rows = (int)value;
+        return GM_OK;
+    }
     if (!strcmp(key, "row_path")) {
         if (value < 0 || value > 2) return fail(c, GM_ERR_ARG, "row_path must be 0, 1 or 2");
         c->row_path = (int)value;
@@ -832,7 +838,7 @@ static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, Theta& out, const
 // gx_acc (bf16 mode): the support rows of the sparse-gradient buffer, which take -alpha * (tangent of dX) in the
 // layer-1 product itself; need_dx: the tangent of dX is also wanted in w.dX (for the row arithmetic of the next step)
 static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, float alpha, bool refresh_v_copies,
-                     float* gx_acc, bool need_dx, bool gx_init) {
+                     float* gx_acc, bool need_dx, bool gx_init, bool tx) {
     hipStream_t st = c->stream;
     const int L = c->L;
     Theta& v = w.v;
@@ -840,7 +846,9 @@ static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, f
     const Act* tprev = &w.TX;
     const Act* prev = &s.X;
     for (int l = 1; l < L; ++l) {
-        dense_nn(c, g, l, 2, tprev, &s.th, prev, &v, v.f + c->offb[l], nt, &s.A[l], EPI_BIAS_MASK, w.TA[l]);
+        // (tx false: no direction on the inputs -- rows not adapted -- so layer 1 has one product only)
+        if (l == 1 && !tx) dense_nn(c, g, l, 1, prev, &v, nullptr, nullptr, v.f + c->offb[l], nt, &s.A[l], EPI_BIAS_MASK, w.TA[l]);
+        else dense_nn(c, g, l, 2, tprev, &s.th, prev, &v, v.f + c->offb[l], nt, &s.A[l], EPI_BIAS_MASK, w.TA[l]);
         tprev = &w.TA[l];
         prev = &s.A[l];
     }
@@ -872,7 +880,8 @@ static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, f
         else dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, &s.A[l - 1], &w.TD[l - 1], nullptr);
         const Act* ta_prev = l == 1 ? &w.TX : &w.TA[l - 1];
         const Act* a_prev = l == 1 ? &s.X : &s.A[l - 1];
-        dense_tn(c, g, l, 2, ta_prev, &s.Dl[l], a_prev, &w.TD[l], vout, v.f, nt, 1.f, -alpha);
+        if (l == 1 && !tx) dense_tn(c, g, l, 1, a_prev, &w.TD[l], nullptr, nullptr, vout, v.f, nt, 1.f, -alpha);
+        else dense_tn(c, g, l, 2, ta_prev, &s.Dl[l], a_prev, &w.TD[l], vout, v.f, nt, 1.f, -alpha);
         colsum(c, g, c->ld[l], &w.TD[l], nullptr, nullptr, nullptr, v.f + c->offb[l], nt, v.f + c->offb[l], nt, 1.f, -alpha);
     }
 }
@@ -950,6 +959,7 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
     if (cap_out) *cap_out = cap;
     if (max_bag_out) *max_bag_out = (int)hs[ST_MAX_BAG];
     if (max_tf_out) *max_tf_out = (int)hs[ST_MAX_TF];
+    if (!c->adapt_rows) return GM_OK;   // validated; no row arithmetic, so no per-(task, field) dictionaries
     if (cap > tf_sort_max_cap())
         return fail(c, GM_ERR_CAPACITY, "a (task, field) has %u lookups in one set; the limit is %d", hs[ST_MAX_TF],
                     tf_sort_max_cap());
@@ -1017,7 +1027,7 @@ static inline int64_t pad64(int64_t n) { return (n + 63) & ~(int64_t)63; }
 // n_out * n_in * D per (task, field) against lookups * D for the sparse kernel, on units that are far
 // faster, so it pays while the task is moderately small.
 static bool task_pair_ok(const gm_ctx* c, const Batch& B, int t, int K) {
-    if (c->row_path == 1 || K <= 0 || c->F == 0 || c->D % 32 != 0) return false;
+    if (c->row_path == 1 || K <= 0 || c->F == 0 || c->D % 32 != 0 || !c->adapt_rows) return false;
     const int64_t mx = std::max(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t], B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]);
     return mx > 0 && mx <= (c->row_path == 2 ? 1024 : 512);
 }
@@ -1269,6 +1279,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         if (rc != GM_OK) return rc;
         // pair-count matrices for the tasks that qualify, when the wave's bags and (task, field)s are within the
         // counting kernel's limits; a task with a count that does not fit a byte is handed to the sparse kernel
+        const bool adapt = c->adapt_rows != 0;
         bool pair = d.pair && tf_cap <= PAIR_MAX_CAP && max_bag <= PAIR_MAX_BAG;
         bool any_sparse = d.any_sparse || (d.pair && !pair);
         if (d.pair && !pair) launch_fill_u32(st, w.task_path, Tw, 0u);
@@ -1299,7 +1310,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             if ((rc = read_status(c, hs))) return rc;
             if (hs[ST_PAIR_OVF]) any_sparse = true;   // some task's flag was cleared on the device
         }
-        if (c->row_path == 2 && any_sparse)
+        if (c->row_path == 2 && any_sparse && adapt)
             return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a task, count, bag or (task, field) exceeds its limits");
         const int n_tf = Tw * F;
         const int32_t* rows_s = b.prow_s + wp.s0;
@@ -1432,7 +1443,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             const bool more = k + 1 < K;
             Act Xn;  // support input of step k+1
             if (more) Xn = second ? w.steps[k + 1].X : w.Xs_scratch;
-            if (F > 0) {
+            if (F > 0 && adapt) {
                 float* xs_next = nullptr;
                 if (more) {
                     xs_next = bf ? w.Xs0 : Xn.f;  // bf16: the fp32 master is updated in place
@@ -1447,7 +1458,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                     launch_copy_tail(st, FD, xs_cur, d.Ps, bf ? nullptr : (xs_next != xs_cur ? xs_next : nullptr), ld0, bf ? Xn.b : nullptr);
                     xs_cur = xs_next;
                 }
-            } else if (more) {  // no sparse fields: every step reads the same input
+            } else if (more) {  // no sparse fields, or rows not adapted: every step reads the same input
                 Xn = s.X;
             }
             if (more) {
@@ -1462,7 +1473,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             }
 
         // outer forward/backward on the query set with the adapted parameters
-        if (bf && K > 0) launch_copy_tail(st, F > 0 ? FD : 0, w.Xq0, d.Pq, nullptr, ld0, Xq.b);
+        if (bf && K > 0) launch_copy_tail(st, (F > 0 && adapt) ? FD : 0, w.Xq0, d.Pq, nullptr, ld0, Xq.b);
         // gradient w.r.t. the pooled inputs: the wave's rows of the batch-wide buffer, or the wave's own buffer
         float* gxs = table ? w.GX : b.GX + wp.ps0 * (int64_t)FD;
         float* gxq = table ? w.GX + d.Ps * (int64_t)FD : b.GX + (Ps_tot + wp.pq0) * (int64_t)FD;
@@ -1475,7 +1486,11 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         // second-order chain back through the inner steps: v_k = v_{k+1} - alpha H_k v_{k+1}
         if (second) {
             float* txf = bf ? w.TXf : w.TX.f;  // fp32 pooled direction (support rows); TX.b is its GEMM operand copy
-            if (F > 0) {
+            if (!adapt) {   // no direction on the inputs: whatever still reads it (a model without hidden layers) sees zeros
+                if (bf) zero_bf16(st, w.TX.b, d.Ps * ld0);
+                else launch_fill_f32(st, w.TX.f, d.Ps * ld0, 0.f);
+            }
+            if (F > 0 && adapt) {
                 // direction on the support rows = query gradient routed through the rows both sets share
                 TwoHopOut os = hop_out(true, nullptr, txf, w.TX.b, 1.f);
                 two_hop(false, gxq, &os, nullptr);
@@ -1485,13 +1500,13 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                 // bf16 with hidden layers: the layer-1 product adds -alpha * dX to the gradient buffer itself
                 const bool fused_gx = bf && L > 1 && F > 0;
                 // (the chain's first step starts that sum: the buffer's support rows need no clearing)
-                hvp_step(c, gs, s, w, alpha, k > 0, fused_gx ? gxs : nullptr, k > 0, k == K - 1);
+                hvp_step(c, gs, s, w, alpha, k > 0, fused_gx ? gxs : nullptr, k > 0 && adapt, k == K - 1, adapt);
                 if (F > 0) {
                     if (!fused_gx) {
                         Prof p(c, "axpy_gx", 12.0 * d.Ps * FD, 0);
                         launch_axpy(st, d.Ps * (int64_t)FD, -alpha, w.dX, gxs);
                     }
-                    if (k > 0) {
+                    if (k > 0 && adapt) {
                         TwoHopOut os = hop_out(true, txf, txf, w.TX.b, -alpha);
                         two_hop(true, w.dX, &os, nullptr);
                     }

@@ -326,6 +326,41 @@ def test_train_steps_follow_the_oracle(gm, bf):
     ctx.close()
 
 
+@pytest.mark.parametrize("bf,K,order", [(0, 1, 2), (0, 2, 2), (0, 3, 1), (1, 2, 2)])
+def test_dense_only_adaptation(gm, bf, K, order):
+    """gm_configure("adapt_rows", 0): the inner loop adapts theta only; every output against the oracle's
+    adapt_rows=False, and the fused training iteration in that mode."""
+    from synth.generate import Params
+    cfg = SMALL.with_(n_tasks=5, n_support=40, n_query=24, n_fields=5, emb_dim=32, rows_per_field=2000, bag_max=6,
+                      layer_dims=(5 * 32 + 13, 64, 32, 1), inner_lr=0.05, mlp_dtype=bf)
+    tol = TOL_BF16 if bf else TOL_FP32
+    sup, qry, params = _inputs(cfg, emb_std=0.2)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+    ctx.configure("adapt_rows", 0)
+    dev = ctx.device
+    out = ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, K, order)
+    ref = O.meta_step(oracle_model(cfg), params.numpy(), sup.numpy(), qry.numpy(), cfg.inner_lr, K, order,
+                      operand="bf16" if bf else "fp64", adapt_rows=False)
+    full = O.meta_step(oracle_model(cfg), params.numpy(), sup.numpy(), qry.numpy(), cfg.inner_lr, K, order)
+    assert abs(full["loss"] - ref["loss"]) > 1e-7 * abs(ref["loss"]), "the case must tell the two variants apart"
+    n = int(out["n_emb_rows"].item())
+    assert np.array_equal(out["emb_rows"][:n].cpu().numpy(), ref["emb_rows"])
+    e = {"loss": abs(float(out["loss"].item()) - ref["loss"]) / abs(ref["loss"]),
+         "emb_grad": max(rel_err(out["emb_grad"][:n].cpu().numpy(), ref["emb_grad"]))}
+    for l in range(len(ref["dW"])):
+        e[f"dW{l}"] = max(rel_err(out["dW"][l].cpu().numpy(), ref["dW"][l]))
+        e[f"db{l}"] = max(rel_err(out["db"][l].cpu().numpy(), ref["db"][l]))
+    print(f"dense-only bf16={bf} K={K} order={order}", {k: f"{v:.1e}" for k, v in e.items()}, flush=True)
+    assert all(v <= tol for v in e.values()), e
+    # one training iteration in this mode
+    dp = Params(params.emb.to(dev).clone(), [w.to(dev).clone() for w in params.W], [b.to(dev).clone() for b in params.b])
+    ctx.meta_train_step(_to_dev(sup, dev), _to_dev(qry, dev), dp, cfg.inner_lr, K, order, 0.02)
+    new, _ = O.meta_train_step(oracle_model(cfg), params.numpy(), sup.numpy(), qry.numpy(), cfg.inner_lr, K, order, 0.02,
+                               operand="bf16" if bf else "fp64", adapt_rows=False)
+    assert max(rel_err(dp.emb.cpu().numpy(), new["emb"])) <= tol and max(rel_err(dp.W[0].cpu().numpy(), new["W"][0])) <= tol
+    ctx.close()
+
+
 def test_scatter_add_is_the_outer_update(gm):
     cfg = small_cfg(n_tasks=3)
     sup, qry, params = _inputs(cfg)
