@@ -386,3 +386,52 @@ def gather_pool(model: Model, emb: np.ndarray, s) -> np.ndarray:
     rows, bag = lookup_rows(model, s, 0, n)
     x = pool(model, emb.astype(np.float64), rows, bag, n)
     return np.concatenate([x, s["dense"].astype(np.float64)], axis=1)
+
+
+# --------------------------------------------------------------------------
+# the step before the hot path: one-task batches out of a flat record stream (Sec. 2.2.2, Meta I/O pipeline)
+# --------------------------------------------------------------------------
+def group_batch(n_fields: int, task, batch_id, bag_offsets, indices, dense, labels, support_num: int, support_den: int):
+    """Assembles task batches from a flat stream of records: records with equal (task, batch_id) form one batch
+    (the paper's GroupBatchOp), and every batch is split into a support and a query set (Alg. 1, "Split T_i").
+
+    Readings where the paper is silent: batches come out in ascending (task, batch_id) order; inside a batch the
+    records keep their order in the stream; the first ceil(n * support_num / support_den) records of a batch of n are
+    its support set, the rest its query set.
+
+    Returns (support, query): dicts with task_offsets, bag_offsets, indices, dense, labels (the layout of the step).
+    """
+    task = np.asarray(task, dtype=np.int64)
+    batch_id = np.asarray(batch_id, dtype=np.int64)
+    bag_offsets = np.asarray(bag_offsets, dtype=np.int64)
+    n = task.shape[0]
+    order = sorted(range(n), key=lambda i: (int(task[i]), int(batch_id[i]), i))
+    groups = []
+    for i in order:
+        if groups and (task[groups[-1][0]], batch_id[groups[-1][0]]) == (task[i], batch_id[i]):
+            groups[-1].append(i)
+        else:
+            groups.append([i])
+
+    def build(parts):
+        toff, boff, idx, dn, lb = [0], [0], [], [], []
+        for recs in parts:
+            for i in recs:
+                for f in range(n_fields):
+                    p0, p1 = int(bag_offsets[i * n_fields + f]), int(bag_offsets[i * n_fields + f + 1])
+                    idx.extend(int(x) for x in indices[p0:p1])
+                    boff.append(len(idx))
+                dn.append(np.asarray(dense[i]))
+                lb.append(labels[i])
+            toff.append(toff[-1] + len(recs))
+        nd = np.asarray(dense).shape[1]
+        return dict(task_offsets=np.asarray(toff, dtype=np.int64), bag_offsets=np.asarray(boff, dtype=np.int64),
+                    indices=np.asarray(idx, dtype=np.int32),
+                    dense=np.asarray(dn, dtype=np.float32).reshape(len(dn), nd), labels=np.asarray(lb, dtype=np.float32))
+
+    sup_parts, qry_parts = [], []
+    for recs in groups:
+        k = (len(recs) * support_num + support_den - 1) // support_den
+        sup_parts.append(recs[:k])
+        qry_parts.append(recs[k:])
+    return build(sup_parts), build(qry_parts)
