@@ -42,6 +42,8 @@ def main():
                          "(default: list while the call has fewer than 2^31 lookups per set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-outer-update", action="store_true", help="skip the separate timing of gm_scatter_add")
+    ap.add_argument("--group-batch", action="store_true",
+                    help="also time gm_group_batch (the record-grouping step before the hot path) on this workload's records")
     ap.add_argument("--train", type=float, default=None, metavar="OUTER_LR",
                     help="time whole training iterations (gm_meta_train_step: the step and the outer update with this step "
                          "size, parameters updated in place) instead of the step alone")
@@ -200,6 +202,33 @@ def main():
                          algorithmic_bytes_per_launch=by)
             del tbl
 
+    # The step before the hot path: the batch's records as one flat stream (support records, then query records, each
+    # with its task id), regrouped into one-task batches and split again; wall time of the call (host ordering +
+    # device copies), outside the step
+    grouping = None
+    if args.group_batch:
+        F = cfg.n_fields
+        sizes_s, sizes_q = np.diff(sup0.task_offsets), np.diff(qry0.task_offsets)
+        task_of = np.concatenate([np.repeat(np.arange(cfg.n_tasks), sizes_s), np.repeat(np.arange(cfg.n_tasks), sizes_q)])
+        bo = torch.cat([sup0.bag_offsets, qry0.bag_offsets[1:] + sup0.bag_offsets[-1]])
+        idx = torch.cat([sup0.indices, qry0.indices])
+        dn, lb = torch.cat([sup0.dense, qry0.dense]), torch.cat([sup0.labels, qry0.labels])
+        num, den = int(sizes_s.sum()), int(sizes_s.sum() + sizes_q.sum())
+        ctx.group_batch(task_of, np.zeros_like(task_of), bo, idx, dn, lb, num, den)   # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 3
+        for _ in range(reps):
+            gs, gq = ctx.group_batch(task_of, np.zeros_like(task_of), bo, idx, dn, lb, num, den)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        same = bool(torch.equal(gs.indices, sup0.indices) and torch.equal(gq.bag_offsets, qry0.bag_offsets)) \
+            if np.all(sizes_s * den == (sizes_s + sizes_q) * num) else None
+        grouping = dict(op="gm_group_batch (outside the step; includes the binding's output allocation)", records=int(task_of.size),
+                        lookups=int(idx.numel()), ms=ms, records_per_s=task_of.size / (ms * 1e-3),
+                        reproduces_the_batch=same)
+        del bo, idx, dn, lb, gs, gq
+
     if args.copy_probe_gib > 0:
         n = int(args.copy_probe_gib * 2 ** 30)
         src = torch.ones(n, dtype=torch.uint8, device=dev)
@@ -230,6 +259,7 @@ def main():
         "roofline_hbm": top_hbm,
         "kernels": fams,
         "outer_update_sparse": outer,
+        "group_batch": grouping,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -130,6 +130,35 @@ int gm_meta_train_step(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, cons
                        const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
                        float outer_lr, float* loss, float* task_loss);
 
+/* Output buffers of gm_group_batch for one set.  Capacities are those of the whole stream (a set can at most
+ * hold every record): task_offsets n_records + 1, bag_offsets n_records * F + 1, indices nnz, dense
+ * n_records * n_dense, labels n_records.  n_samples and nnz are written by the call; afterwards the struct's
+ * arrays are exactly a gm_set. */
+typedef struct {
+    int64_t n_samples;     /* out */
+    int64_t nnz;           /* out */
+    int64_t* task_offsets; /* HOST   */
+    int64_t* bag_offsets;  /* DEVICE */
+    int32_t* indices;      /* DEVICE */
+    float* dense;          /* DEVICE */
+    float* labels;         /* DEVICE */
+} gm_set_buffers;
+
+/* The step before the hot path (Sec. 2.2.2, Meta I/O pipeline; Alg. 1 "Split T_i"): assembles one-task
+ * batches from a flat stream of records and splits each into its support and query set.  Records with equal
+ * (task, batch_id) form one batch (the paper's GroupBatchOp); batches come out in ascending (task, batch_id)
+ * order, records keep their stream order inside a batch, and the first ceil(n * support_num / support_den)
+ * records of a batch of n are its support set (the paper fixes none of the three; see the oracle).
+ * task, batch_id: HOST [n_records].  bag_offsets: DEVICE [n_records * F + 1] (sample-major, field-minor),
+ * indices: DEVICE [nnz], dense: DEVICE [n_records, n_dense], labels: DEVICE [n_records].
+ * *n_tasks: number of batches.  The stream must hold fewer than 2^31 records and 2^32 lookups.
+ * GM_ERR_INDEX if bag_offsets is not monotone from 0 to nnz.  Uses the context's workspace
+ * (about 12 bytes per bag). */
+int gm_group_batch(gm_ctx* ctx, int64_t n_records, int64_t nnz, const int64_t* task, const int64_t* batch_id,
+                   const int64_t* bag_offsets, const int32_t* indices, const float* dense, const float* labels,
+                   int32_t support_num, int32_t support_den, gm_set_buffers* support, gm_set_buffers* query,
+                   int32_t* n_tasks);
+
 /* table[rows[i], :] += scale * grad[i, :]  (Alg. 1, global back-propagation on xi, on one shard,
  * with scale = -beta).  rows must be distinct (as gm_meta_step emits them).  All DEVICE. */
 int gm_scatter_add(gm_ctx* ctx, float* table, const int64_t* rows, const float* grad,

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libgmeta.so")
 GM_OK, GM_ERR_ARG, GM_ERR_INDEX, GM_ERR_CAPACITY, GM_ERR_WORKSPACE, GM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["gm_create", "gm_destroy", "gm_last_error", "gm_workspace_bytes", "gm_meta_step",
-           "gm_meta_train_step", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report"]
+           "gm_meta_train_step", "gm_group_batch", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report"]
 
 
 class gm_model_desc(C.Structure):
@@ -42,6 +42,11 @@ class gm_grads(C.Structure):
     _fields_ = [("dW", C.POINTER(C.c_void_p)), ("db", C.POINTER(C.c_void_p)), ("emb_rows", C.c_void_p),
                 ("emb_grad", C.c_void_p), ("n_emb_rows", C.c_void_p), ("emb_rows_capacity", C.c_int64),
                 ("task_loss", C.c_void_p), ("emb_grad_table", C.c_void_p)]
+
+
+class gm_set_buffers(C.Structure):
+    _fields_ = [("n_samples", C.c_int64), ("nnz", C.c_int64), ("task_offsets", C.POINTER(C.c_int64)),
+                ("bag_offsets", C.c_void_p), ("indices", C.c_void_p), ("dense", C.c_void_p), ("labels", C.c_void_p)]
 
 
 class GMetaError(RuntimeError):
@@ -71,6 +76,10 @@ def load_library() -> C.CDLL:
     lib.gm_workspace_bytes.restype = C.c_size_t
     lib.gm_workspace_bytes.argtypes = [C.POINTER(gm_model_desc), C.c_int32, C.c_int64, C.c_int64, C.c_int64,
                                        C.c_int64, C.c_int32, C.c_int32]
+    lib.gm_group_batch.restype = C.c_int
+    lib.gm_group_batch.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_void_p,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(gm_set_buffers),
+                                   C.POINTER(gm_set_buffers), C.POINTER(C.c_int32)]
     lib.gm_meta_train_step.restype = C.c_int
     lib.gm_meta_train_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set), C.POINTER(gm_params),
                                        C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
@@ -224,6 +233,42 @@ class GMeta:
                                          int(inner_steps), int(order), float(outer_lr), _ptr(loss), _ptr(task_loss))
         self._check(rc)
         return loss
+
+    def group_batch(self, task, batch_id, bag_offsets: torch.Tensor, indices: torch.Tensor, dense: torch.Tensor,
+                    labels: torch.Tensor, support_num: int, support_den: int):
+        """gm_group_batch: task / batch_id host int64 arrays, the other arrays device tensors of the flat stream.
+        Returns (support, query) as SetData-like objects (host task_offsets, device tensors)."""
+        from types import SimpleNamespace
+        task = np.ascontiguousarray(np.asarray(task, dtype=np.int64))
+        batch_id = np.ascontiguousarray(np.asarray(batch_id, dtype=np.int64))
+        n, nnz, F, nd = int(task.shape[0]), int(indices.numel()), self.n_fields, self.n_dense
+        dev = self.device
+        outs, structs, toffs = [], [], []
+        for _ in range(2):
+            o = dict(bag_offsets=torch.empty(n * F + 1, dtype=torch.int64, device=dev),
+                     indices=torch.empty(max(nnz, 1), dtype=torch.int32, device=dev),
+                     dense=torch.empty(max(n, 1), max(nd, 1), dtype=torch.float32, device=dev),
+                     labels=torch.empty(max(n, 1), dtype=torch.float32, device=dev))
+            toff = np.zeros(n + 1, dtype=np.int64)
+            st = gm_set_buffers(0, 0, toff.ctypes.data_as(C.POINTER(C.c_int64)), _ptr(o["bag_offsets"]), _ptr(o["indices"]),
+                                _ptr(o["dense"]), _ptr(o["labels"]))
+            outs.append(o); structs.append(st); toffs.append(toff)
+        n_tasks = C.c_int32(0)
+        rc = self.lib.gm_group_batch(self._ctx, n, nnz, task.ctypes.data_as(C.POINTER(C.c_int64)),
+                                     batch_id.ctypes.data_as(C.POINTER(C.c_int64)), _ptr(bag_offsets), _ptr(indices), _ptr(dense),
+                                     _ptr(labels), int(support_num), int(support_den), C.byref(structs[0]), C.byref(structs[1]),
+                                     C.byref(n_tasks))
+        self._check(rc)
+        res = []
+        for o, st, toff in zip(outs, structs, toffs):
+            ns, nz, T = int(st.n_samples), int(st.nnz), int(n_tasks.value)
+            sd = SimpleNamespace(task_offsets=toff[: T + 1].copy(), bag_offsets=o["bag_offsets"][: ns * F + 1],
+                                 indices=o["indices"][:nz], dense=o["dense"][:ns, :nd], labels=o["labels"][:ns])
+            sd.numpy = (lambda d=sd: dict(task_offsets=d.task_offsets, bag_offsets=d.bag_offsets.cpu().numpy(),
+                                          indices=d.indices.cpu().numpy(), dense=d.dense.cpu().numpy(),
+                                          labels=d.labels.cpu().numpy()))
+            res.append(sd)
+        return res[0], res[1]
 
     def gather_pool(self, set_, emb: torch.Tensor) -> torch.Tensor:
         n_tasks = len(set_.task_offsets) - 1

@@ -1615,6 +1615,142 @@ extern "C" int gm_meta_train_step(gm_ctx* c, int32_t T, const gm_set* sup, const
     return GM_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// one-task batches out of a flat record stream
+// ------------------------------------------------------------------------------------------------
+// lens[d * F + f] = length of bag f of source record perm[d]; flags offsets that are not monotone inside [0, nnz]
+__global__ void group_lens_kernel(const int32_t* __restrict__ perm, int64_t n_dst, int F, const int64_t* __restrict__ bo,
+                                  int64_t nnz, u32* lens, u32* status) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_dst * F) return;
+    const int64_t d = i / F;
+    const int f = (int)(i - d * F);
+    const int64_t b = (int64_t)perm[d] * F + f;
+    const int64_t p0 = bo[b], p1 = bo[b + 1];
+    const bool bad = p0 < 0 || p1 < p0 || p1 > nnz;
+    if (bad) atomicOr(&status[ST_BAD_INDEX], 1u);
+    lens[i] = bad ? 0u : (u32)(p1 - p0);
+}
+// One workgroup per 256 destination bags: their lookups are one contiguous destination range; the bag of a lookup is
+// found by bisection of the staged offsets (as in build_keys_kernel).  Also widens the offsets to 64 bits.
+__global__ __launch_bounds__(256) void group_copy_kernel(const int32_t* __restrict__ perm, int64_t n_bags, int F,
+                                                         const int64_t* __restrict__ bo, const int32_t* __restrict__ idx_in,
+                                                         const u32* __restrict__ offs, int64_t* bo_out, int32_t* idx_out) {
+    __shared__ u32 so[257];
+    __shared__ int64_t src0[256];
+    const int64_t b0 = (int64_t)blockIdx.x * 256;
+    const int nb = (int)min<int64_t>(256, n_bags - b0);
+    for (int i = threadIdx.x; i <= nb; i += 256) {
+        so[i] = offs[b0 + i];
+        bo_out[b0 + i] = (int64_t)offs[b0 + i];
+    }
+    for (int i = threadIdx.x; i < nb; i += 256) {
+        const int64_t d = (b0 + i) / F;
+        src0[i] = bo[(int64_t)perm[d] * F + (b0 + i - d * F)];
+    }
+    __syncthreads();
+    const u32 p0 = so[0], p1 = so[nb];
+    for (u32 p = p0 + threadIdx.x; p < p1; p += 256) {
+        int lo = 0, hi = nb;   // last bag with so[bag] <= p
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (so[mid] <= p) lo = mid;
+            else hi = mid;
+        }
+        idx_out[p] = idx_in[src0[lo] + (p - so[lo])];
+    }
+}
+__global__ void group_rows_kernel(const int32_t* __restrict__ perm, int64_t n_dst, int nd, const float* __restrict__ dense,
+                                  const float* __restrict__ labels, float* dense_out, float* labels_out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_dst * (nd + 1)) return;
+    const int64_t d = i / (nd + 1);
+    const int k = (int)(i - d * (nd + 1));
+    const int64_t s = perm[d];
+    if (k < nd) dense_out[d * nd + k] = dense[s * nd + k];
+    else labels_out[d] = labels[s];
+}
+
+extern "C" int gm_group_batch(gm_ctx* c, int64_t n, int64_t nnz, const int64_t* task, const int64_t* batch_id,
+                              const int64_t* bag_offsets, const int32_t* indices, const float* dense, const float* labels,
+                              int32_t support_num, int32_t support_den, gm_set_buffers* sup, gm_set_buffers* qry,
+                              int32_t* n_tasks) {
+    if (!c) return GM_ERR_ARG;
+    if (n < 0 || nnz < 0 || !sup || !qry || !n_tasks) return fail(c, GM_ERR_ARG, "bad sizes / null outputs");
+    if (support_den <= 0 || support_num < 0 || support_num > support_den) return fail(c, GM_ERR_ARG, "support share must be in [0, 1]");
+    if (n >= ((int64_t)1 << 31) / std::max(c->F, 1) || nnz >= ((int64_t)1 << 32))
+        return fail(c, GM_ERR_ARG, "the stream must hold fewer than 2^31 bags and 2^32 lookups");
+    if (n > 0 && (!task || !batch_id || !bag_offsets || !labels || (c->n_dense > 0 && !dense) || (nnz > 0 && !indices)))
+        return fail(c, GM_ERR_ARG, "null stream array");
+    gm_set_buffers* outs[2] = {sup, qry};
+    for (gm_set_buffers* o : outs)
+        if (!o->task_offsets || (n > 0 && (!o->bag_offsets || !o->labels || (c->n_dense > 0 && !o->dense) || (nnz > 0 && !o->indices))))
+            return fail(c, GM_ERR_ARG, "null output buffer");
+    HIPCHK(c, hipSetDevice(c->device));
+    hipStream_t st = c->stream;
+    const int F = c->F, nd = c->n_dense;
+    // host: records in (task, batch_id) order, stream order inside a batch; batches and their split
+    std::vector<int32_t> order((size_t)n);
+    for (int64_t i = 0; i < n; ++i) order[(size_t)i] = (int32_t)i;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        return task[a] != task[b] ? task[a] < task[b] : batch_id[a] < batch_id[b];
+    });
+    std::vector<int32_t> perm[2];
+    sup->task_offsets[0] = qry->task_offsets[0] = 0;
+    int32_t T = 0;
+    for (int64_t i = 0; i < n;) {
+        int64_t j = i + 1;
+        while (j < n && task[order[j]] == task[order[i]] && batch_id[order[j]] == batch_id[order[i]]) ++j;
+        const int64_t m = j - i, k = (m * support_num + support_den - 1) / support_den;
+        for (int64_t r = i; r < j; ++r) perm[r - i < k ? 0 : 1].push_back(order[(size_t)r]);
+        ++T;
+        sup->task_offsets[T] = (int64_t)perm[0].size();
+        qry->task_offsets[T] = (int64_t)perm[1].size();
+        i = j;
+    }
+    *n_tasks = T;
+    launch_fill_u32(st, c->d_status, ST_WORDS, 0);
+    for (int w = 0; w < 2; ++w) {
+        gm_set_buffers* o = outs[w];
+        const int64_t nw = (int64_t)perm[w].size(), nbags = nw * F;
+        o->n_samples = nw;
+        o->nnz = 0;
+        Arena ar;
+        ar.base = c->ws; ar.cap = c->ws_bytes; ar.off = c->persistent;
+        int32_t* d_perm = ar.get<int32_t>(nw + 1);
+        u32* lens = ar.get<u32>(nbags + 2);
+        u32* scan_tmp = ar.get<u32>(scan_tmp_words(nbags + 1));
+        if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "workspace too small for the grouping (%zu bytes needed)", ar.off);
+        if (nw == 0) {
+            if (n > 0) HIPCHK(c, hipMemsetAsync(o->bag_offsets, 0, sizeof(int64_t), st));
+            continue;
+        }
+        HIPCHK(c, hipMemcpyAsync(d_perm, perm[w].data(), nw * sizeof(int32_t), hipMemcpyHostToDevice, st));
+        if (nbags > 0) {
+            hipLaunchKernelGGL(group_lens_kernel, dim3((unsigned)((nbags + 255) / 256)), dim3(256), 0, st, d_perm, nw, F,
+                               bag_offsets, nnz, lens, c->d_status);
+            launch_fill_u32(st, lens + nbags, 1, 0);   // so that the exclusive scan's last entry is the total
+            launch_scan_u32(st, lens, lens, nbags + 1, scan_tmp, nullptr);
+            u32 hs[ST_WORDS];
+            int rc = read_status(c, hs);   // (synchronises: the permutation vector may go, the offsets are trusted below)
+            if (rc != GM_OK) return rc;
+            if (hs[ST_BAD_INDEX]) return fail(c, GM_ERR_INDEX, "bag_offsets not monotone / beyond nnz");
+            u32 total = 0;
+            HIPCHK(c, hipMemcpy(&total, lens + nbags, sizeof total, hipMemcpyDeviceToHost));
+            o->nnz = (int64_t)total;
+            hipLaunchKernelGGL(group_copy_kernel, dim3((unsigned)((nbags + 255) / 256)), dim3(256), 0, st, d_perm, nbags, F,
+                               bag_offsets, indices, lens, o->bag_offsets, o->indices);
+        } else {
+            HIPCHK(c, hipMemsetAsync(o->bag_offsets, 0, sizeof(int64_t), st));
+        }
+        hipLaunchKernelGGL(group_rows_kernel, dim3((unsigned)((nw * (nd + 1) + 255) / 256)), dim3(256), 0, st, d_perm, nw, nd,
+                           dense, labels, o->dense, o->labels);
+        HIPCHK(c, hipStreamSynchronize(st));
+    }
+    HIPCHK(c, hipGetLastError());
+    return GM_OK;
+}
+
 extern "C" int gm_scatter_add(gm_ctx* c, float* table, const int64_t* rows, const float* grad, int64_t n_rows,
                               float scale) {
     if (!c) return GM_ERR_ARG;
