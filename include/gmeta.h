@@ -194,6 +194,9 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               dense-only family of optimisation-based meta learners that Sec. 3.1 runs on the same
  *               framework); the meta-gradient w.r.t. the embeddings then is the query loss's own plus, for
  *               order 2, the path through the adapted dense parameters.  THIS ONE CHANGES WHAT IS COMPUTED.
+ *   "overlap_sort": 1 = the ordering of the lookups by row (it depends on the indices only) runs on a second
+ *               stream of the context beside the dense phase and is joined before the segment reduction;
+ *               0 (default) = everything on the context's stream.  Identical results.
  *   "gemm_tile_n": column tile of the forward / backward grouped products when tasks get 256-row tiles:
  *               0 = chosen by the library (128), 128, or 256 (eight waves per workgroup; identical results).
  *   "pair_tile_rows": most out-rows of a pair-count matrix that the counting kernel holds in LDS at a time

@@ -66,6 +66,12 @@ struct gm_ctx {
     size_t persistent = 0;
     int64_t* d_field_base = nullptr;
     u32* d_status = nullptr;
+    u32* d_status_side = nullptr;   // status words of the work on the side stream
+    // The ordering of the lookups by row depends on the indices only: it runs on a stream of its own beside the dense
+    // computation (same priority) and is joined before the segment reduction.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_side = nullptr, ev_main = nullptr, ev_go = nullptr;
+    int overlap_sort = 0;   // measured: 1-1.5 % (both streams contend for the same memory system), so off unless asked for
     std::string err;
     int pair_tile_rows = 0;
     int adapt_rows = 1;   // 0: the inner loop adapts the dense parameters only (embedding rows are read, not updated)
@@ -100,7 +106,9 @@ struct Prof {
     gm_ctx* c;
     ProfPending p;
     bool on;
-    Prof(gm_ctx* c_, const char* name, double bytes, double flops) : c(c_), on(c_->prof_on) {
+    hipStream_t st;
+    Prof(gm_ctx* c_, const char* name, double bytes, double flops, hipStream_t st_ = nullptr, bool use_st = false)
+        : c(c_), on(c_->prof_on), st(use_st ? st_ : c_->stream) {
         if (!on) return;
         p.name = name;
         p.bytes = bytes;
@@ -114,11 +122,11 @@ struct Prof {
                 return;
             }
         }
-        (void)hipEventRecord(p.e0, c->stream);
+        (void)hipEventRecord(p.e0, st);
     }
     ~Prof() {
         if (!on) return;
-        (void)hipEventRecord(p.e1, c->stream);
+        (void)hipEventRecord(p.e1, st);
         c->prof_pending.push_back(p);
     }
 };
@@ -455,6 +463,11 @@ extern "C" int gm_create(gm_ctx** out, const gm_model_desc* model, int device, v
     ar.cap = c->ws_bytes;
     c->d_field_base = ar.get<int64_t>(c->F + 1);
     c->d_status = ar.get<u32>(ST_WORDS);
+    c->d_status_side = ar.get<u32>(ST_WORDS);
+    HIPCHK(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+    HIPCHK(c, hipEventCreateWithFlags(&c->ev_side, hipEventDisableTiming));
+    HIPCHK(c, hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming));
+    HIPCHK(c, hipEventCreateWithFlags(&c->ev_go, hipEventDisableTiming));
     c->persistent = ar.off;
     HIPCHK(c, hipMemcpy(c->d_field_base, c->field_base.data(), (c->F + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     return GM_OK;
@@ -469,6 +482,10 @@ extern "C" void gm_destroy(gm_ctx* c) {
             (void)hipEventDestroy(p.e1);
         }
         for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
+        if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
+        if (c->ev_side) (void)hipEventDestroy(c->ev_side);
+        if (c->ev_main) (void)hipEventDestroy(c->ev_main);
+        if (c->ev_go) (void)hipEventDestroy(c->ev_go);
         (void)hipFree(c->ws);
     }
     delete c;
@@ -492,6 +509,11 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
     if (!strcmp(key, "adapt_rows")) {
         if (value != 0 && value != 1) return fail(c, GM_ERR_ARG, "adapt_rows must be 0 or 1");
         c->adapt_rows = (int)value;
+        return GM_OK;
+    }
+    if (!strcmp(key, "overlap_sort")) {
+        if (value != 0 && value != 1) return fail(c, GM_ERR_ARG, "overlap_sort must be 0 or 1");
+        c->overlap_sort = (int)value;
         return GM_OK;
     }
     if (!strcmp(key, "row_path")) {
@@ -993,13 +1015,14 @@ struct SortRange {
 };
 
 static int global_order(gm_ctx* c, Batch& B, SortBufs& so, const SortRange& r, int64_t* emb_rows, int64_t* seg_counts,
-                        int64_t capacity, int64_t* n_rows) {
-    hipStream_t st = c->stream;
+                        int64_t capacity, int64_t* n_rows, bool on_side = false) {
+    hipStream_t st = on_side ? c->side : c->stream;
+    u32* status = on_side ? c->d_status_side : c->d_status;
     const int F = c->F;
     const gm_set *sup = B.sup, *qry = B.qry;
     BatchBufs& b = B.b;
     const int64_t n_s = r.ls1 - r.ls0, nnz = n_s + (r.lq1 - r.lq0);
-    Prof p(c, "global_sort", 0, 0);
+    Prof p(c, "global_sort", 0, 0, st, true);
     if (F > 0) {
         launch_build_keys(st, F, c->d_field_base, sup->bag_offsets + r.s0 * F, sup->indices, (r.s1 - r.s0) * F, r.ls0,
                           b.prow_s + r.s0, r.row0_s, so.keys, so.vals);
@@ -1013,7 +1036,7 @@ static int global_order(gm_ctx* c, Batch& B, SortBufs& so, const SortRange& r, i
         std::swap(so.vals, so.vals_tmp);
     }
     launch_segments(st, so.keys, nnz, so.keys_tmp, so.scan_tmp, emb_rows, so.seg_start, seg_counts, capacity, n_rows,
-                    c->d_status);
+                    status);
     return GM_OK;
 }
 
@@ -1246,6 +1269,12 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     rc = plan_waves(c, B, c->ws_bytes - ar.off, K, order, bm, plans);
     if (rc != GM_OK) return rc;
     const size_t wave_mark = ar.off;
+    struct SideGuard {   // whatever way this call ends, nothing of it is left running on the side stream
+        gm_ctx* c;
+        bool active = false;
+        ~SideGuard() { if (active) (void)hipStreamSynchronize(c->side); }
+    } side{c};
+    bool side_list = false;
 
     // meta theta in the padded internal layout (and its bf16 operand copies); accumulators
     for (int l = 1; l <= L; ++l) {
@@ -1348,6 +1377,30 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             launch_copy_tail(st, FD, nullptr, d.Ps, bf ? w.TXf : w.TX.f, ld0, w.TX.b);
         }
 
+        // The wave's offsets and indices are validated.  Ordering the lookups by row needs nothing else: it runs on the
+        // side stream from here on -- beside the dense phase, which is bound by memory traffic, not beside the index
+        // kernels above, which are bound by the same things as the sort -- and is joined before the segment reduction
+        // (row-list output: only when the batch is one wave, so that everything it reads has been validated).
+        if (c->overlap_sort && F > 0 && (table || plans.size() == 1)) {
+            HIPCHK(c, hipEventRecord(c->ev_go, st));
+            HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_go, 0));
+        }
+        const bool side_table = table && c->overlap_sort && F > 0;
+        if (side_table) {
+            if (side.active) HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_main, 0));   // the previous wave is done with this memory
+            side.active = true;
+            launch_fill_u32(c->side, c->d_status_side, ST_WORDS, 0);
+            const SortRange r{wp.s0, wp.s1, wp.q0, wp.q1, wp.ls0, wp.ls1, wp.lq0, wp.lq1,
+                              (u32)(0 - (uint64_t)wp.ps0), (u32)((uint64_t)d.Ps - (uint64_t)wp.pq0)};
+            global_order(c, B, w.so, r, nullptr, nullptr, d.nnz_s + d.nnz_q, w.n_rows, true);
+            HIPCHK(c, hipEventRecord(c->ev_side, c->side));
+        } else if (!table && c->overlap_sort && F > 0 && plans.size() == 1) {
+            side.active = true;
+            side_list = true;
+            launch_fill_u32(c->side, c->d_status_side, ST_WORDS, 0);
+            global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows, true);
+            HIPCHK(c, hipEventRecord(c->ev_side, c->side));
+        }
         // row arithmetic of one (task, field) at a time, through LDS (no row table in HBM)
         int max_bags = 0;
         for (int t = wp.t0; t < wp.t1; ++t)
@@ -1524,10 +1577,14 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             const SortRange r{wp.s0, wp.s1, wp.q0, wp.q1, wp.ls0, wp.ls1, wp.lq0, wp.lq1,
                               (u32)(0 - (uint64_t)wp.ps0), (u32)((uint64_t)d.Ps - (uint64_t)wp.pq0)};
             const int64_t nw = d.nnz_s + d.nnz_q;
-            global_order(c, B, w.so, r, nullptr, nullptr, nw, w.n_rows);
-            Prof p(c, "seg_reduce", (double)nw * (4.0 * D + 4), 0);
-            launch_seg_reduce(st, D, w.so.keys, w.so.keys_tmp, w.so.seg_start, w.n_rows, nw, nw, w.so.vals, w.GX, nullptr,
-                              w.so.seg_partial, table);
+            if (side_table) HIPCHK(c, hipStreamWaitEvent(st, c->ev_side, 0));
+            else global_order(c, B, w.so, r, nullptr, nullptr, nw, w.n_rows);
+            {
+                Prof p(c, "seg_reduce", (double)nw * (4.0 * D + 4), 0);
+                launch_seg_reduce(st, D, w.so.keys, w.so.keys_tmp, w.so.seg_start, w.n_rows, nw, nw, w.so.vals, w.GX, nullptr,
+                                  w.so.seg_partial, table);
+            }
+            if (side_table) HIPCHK(c, hipEventRecord(c->ev_main, st));
         }
     }
 
@@ -1541,7 +1598,8 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     if (table) {
         launch_fill_u32(st, reinterpret_cast<u32*>(out->n_emb_rows), 2, 0u);
     } else {
-        global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows);
+        if (side_list) HIPCHK(c, hipStreamWaitEvent(st, c->ev_side, 0));
+        else global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows);
         if (F > 0) {
             Prof p(c, "seg_reduce", (double)nnz * (4.0 * D + 4), 0);
             launch_seg_reduce(st, D, b.so.keys, b.so.keys_tmp, b.so.seg_start, out->n_emb_rows, capacity, nnz, b.so.vals,
@@ -1549,7 +1607,10 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         }
     }
     u32 hs[ST_WORDS];
-    rc = read_status(c, hs);
+    if (side_list)   // the ordering's own status words (the main stream has waited for it)
+        HIPCHK(c, hipMemcpyAsync(hs, c->d_status_side, ST_WORDS * sizeof(u32), hipMemcpyDeviceToHost, st));
+    rc = side_list ? (hipStreamSynchronize(st) == hipSuccess ? GM_OK : fail(c, GM_ERR_HIP, "stream synchronisation failed"))
+                   : read_status(c, hs);
     if (rc != GM_OK) return rc;
     HIPCHK(c, hipGetLastError());
     prof_drain(c);

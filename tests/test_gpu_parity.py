@@ -471,6 +471,32 @@ def test_gemm_wide_tiles_give_the_same_result(gm):
     ctx.close()
 
 
+@pytest.mark.parametrize("shape", ["list", "table"])
+def test_sort_on_the_side_stream_gives_the_same_result(gm, shape):
+    """gm_configure("overlap_sort", 1): the lookups are ordered by row on a second stream beside the dense phase.  Same
+    bits as without, in both shapes of the sparse output (the table one with several waves)."""
+    cfg = SMALL.with_(n_tasks=8)
+    sup, qry, params = _inputs(cfg)
+    probe = gm.from_config(cfg, workspace_bytes=2 << 30)
+    need = probe.workspace_bytes(8, sup.n_samples, qry.n_samples, sup.nnz, qry.nnz, 2, 2)
+    probe.close()
+    ctx = gm.from_config(cfg, workspace_bytes=(2 << 30) if shape == "list" else int(need * 0.3))
+    dev = ctx.device
+    ds, dq, dp = _to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev)
+    res = []
+    for on in (0, 1, 1):
+        ctx.configure("overlap_sort", on)
+        table = torch.zeros_like(dp.emb) if shape == "table" else None
+        out = ctx.meta_step(ds, dq, dp, cfg.inner_lr, 2, 2, emb_grad_table=table)
+        n = int(out["n_emb_rows"].item())
+        res.append((out["loss"].clone(), out["dW"][0].clone(), table if table is not None else out["emb_grad"][:n].clone(),
+                    out["emb_rows"][:n].clone()))
+    for r in res[1:]:
+        for a, b in zip(res[0], r):
+            assert torch.equal(a, b)
+    ctx.close()
+
+
 def test_pair_counts_above_a_byte_fall_back(gm):
     """One row per table: every pair of bags shares all its lookups, so counts reach bag_i * bag_j > 255.  The default
     choice must fall back to the sparse kernel (and still match the oracle); the forced pair path must refuse."""
