@@ -266,10 +266,13 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
+// lpr: lanes per row, a power of two (64: one row per wave; fewer when 8 columns per lane cover the row with less,
+// so that a wave takes 64 / lpr rows at once)
 template <typename T>
-__global__ void last_fwd_kernel(LastFwdArgs a) {
-    const int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 64;
-    const int lane = threadIdx.x & 63;
+__global__ void last_fwd_kernel(LastFwdArgs a, int lpr) {
+    const int64_t gt = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t s = gt / lpr;
+    const int lane = (int)(gt % lpr);
     if (s >= a.n) return;
     const int g = a.row_task[s];
     const int r_in = (int)(s - a.row_offsets[g]);
@@ -292,7 +295,7 @@ __global__ void last_fwd_kernel(LastFwdArgs a) {
         const bf16_t* xb = reinterpret_cast<const bf16_t*>(x);
         const bf16_t* txb = a.ta ? reinterpret_cast<const bf16_t*>(a.ta) + s * a.ld : nullptr;
         const float* tw = a.ta ? a.tw + (int64_t)g * a.gTW : nullptr;
-        for (int n = lane * 8; n < a.N; n += 512) {
+        for (int n = lane * 8; n < a.N; n += lpr * 8) {
             float xv[8], wv[8];
             load8(xb + n, xv);
             load8(w + n, wv);
@@ -314,7 +317,7 @@ __global__ void last_fwd_kernel(LastFwdArgs a) {
         const float* tw = a.tw + (int64_t)g * a.gTW;
         for (int n = lane; n < a.N; n += 64) acc += ldf(tx, n) * w[n] + ldf(x, n) * tw[n];
     }
-    acc = wave_sum(acc);
+    for (int d = lpr >> 1; d > 0; d >>= 1) acc += __shfl_xor(acc, d, 64);   // within the row's lanes
     if (lane != 0) return;
     const float inv_n = 1.f / (float)n_real;
     if (!a.ta) {
@@ -336,9 +339,15 @@ __global__ void last_fwd_kernel(LastFwdArgs a) {
 
 void launch_last_fwd(hipStream_t st, const LastFwdArgs& a) {
     if (a.n <= 0) return;
-    const dim3 grid((unsigned)((a.n * 64 + 255) / 256));
-    if (a.bf16) hipLaunchKernelGGL(last_fwd_kernel<bf16_t>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(last_fwd_kernel<float>, grid, dim3(256), 0, st, a);
+    int lpr = 64;
+    // the 16-byte path of the kernel (same conditions) reads 8 columns per lane: narrow rows need fewer lanes
+    if (a.bf16 && a.N % 8 == 0 && a.ld % 8 == 0 && a.gW % 4 == 0 && (!a.ta || a.gTW % 4 == 0) &&
+        reinterpret_cast<uintptr_t>(a.w) % 16 == 0 && (!a.ta || reinterpret_cast<uintptr_t>(a.tw) % 16 == 0)) {
+        while (lpr > 8 && (lpr / 2) * 8 >= a.N) lpr /= 2;
+    }
+    const dim3 grid((unsigned)((a.n * lpr + 255) / 256));
+    if (a.bf16) hipLaunchKernelGGL(last_fwd_kernel<bf16_t>, grid, dim3(256), 0, st, a, lpr);
+    else hipLaunchKernelGGL(last_fwd_kernel<float>, grid, dim3(256), 0, st, a, lpr);
 }
 
 template <typename T>
