@@ -123,6 +123,37 @@ __global__ void scan_block_kernel(const u32* in, u32* out, int64_t n, u32* block
     if (threadIdx.x == 0) block_sums[blockIdx.x] = (u32)total;
 }
 
+// first level of the scan of segment-head flags: the flag of key i (1 where a new row starts) is taken from the sorted
+// keys themselves, so no flag array is written and read back
+__global__ void scan_heads_block_kernel(const u32* __restrict__ keys, u32* out, int64_t n, u32* block_sums) {
+    __shared__ int sh[SCAN_NT / WAVE + 2];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    u32 k[SCAN_ITEMS + 1];
+    k[0] = (base > 0 && base < n) ? keys[base - 1] : 0u;
+    if (base + SCAN_ITEMS <= n) {   // (the buffers are 16-byte aligned and base is a multiple of 8)
+        const uint4 a = *reinterpret_cast<const uint4*>(keys + base), b = *reinterpret_cast<const uint4*>(keys + base + 4);
+        k[1] = a.x; k[2] = a.y; k[3] = a.z; k[4] = a.w; k[5] = b.x; k[6] = b.y; k[7] = b.z; k[8] = b.w;
+    } else {
+#pragma unroll
+        for (int i = 0; i < SCAN_ITEMS; ++i) k[i + 1] = (base + i < n) ? keys[base + i] : 0u;
+    }
+    u32 v[SCAN_ITEMS];
+    u32 sum = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        v[i] = (base + i < n && (base + i == 0 || k[i + 1] != k[i])) ? 1u : 0u;
+        sum += v[i];
+    }
+    int total;
+    u32 run = (u32)block_excl_scan((int)sum, sh, &total);
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        if (base + i < n) out[base + i] = run;
+        run += v[i];
+    }
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = (u32)total;
+}
+
 __global__ void scan_add_kernel(u32* out, int64_t n, const u32* block_offsets) {
     const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
     const u32 o = block_offsets[blockIdx.x];
@@ -740,11 +771,6 @@ int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* 
     return passes;
 }
 
-__global__ void seg_flags_kernel(const u32* keys, int64_t n, u32* flags) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) flags[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
-}
-
 __global__ void seg_emit_kernel(const u32* keys, int64_t n, const u32* scan, int64_t* emb_rows, u32* seg_start,
                                 int64_t capacity, int64_t* n_rows_out, u32* status) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -783,8 +809,15 @@ void launch_segments(hipStream_t st, const u32* sorted_keys, int64_t n, u32* fla
         return;
     }
     const unsigned nb = (unsigned)((n + 255) / 256);
-    hipLaunchKernelGGL(seg_flags_kernel, dim3(nb), dim3(256), 0, st, sorted_keys, n, flags_scan);
-    launch_scan_u32(st, flags_scan, flags_scan, n, scan_tmp, nullptr);
+    {   // exclusive scan of the segment-head flags (launch_scan_u32 with its first level reading the keys)
+        const int64_t nblk = (n + SCAN_TILE - 1) / SCAN_TILE;
+        hipLaunchKernelGGL(scan_heads_block_kernel, dim3((unsigned)nblk), dim3(SCAN_NT), 0, st, sorted_keys, flags_scan, n, scan_tmp);
+        if (nblk > 1) {
+            u32* next = scan_tmp + (nblk + 63) / 64 * 64;
+            launch_scan_u32(st, scan_tmp, scan_tmp, nblk, next, nullptr);
+            hipLaunchKernelGGL(scan_add_kernel, dim3((unsigned)nblk), dim3(SCAN_NT), 0, st, flags_scan, n, scan_tmp);
+        }
+    }
     hipLaunchKernelGGL(seg_emit_kernel, dim3(nb), dim3(256), 0, st, sorted_keys, n, flags_scan, emb_rows, seg_start,
                        capacity, n_rows_out, status);
     if (seg_counts) {
