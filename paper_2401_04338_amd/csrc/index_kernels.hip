@@ -103,22 +103,37 @@ void launch_tf_count(hipStream_t st, int F, int t0, int Tw, SetView sup, SetView
 #define SCAN_ITEMS 8
 #define SCAN_TILE (SCAN_NT * SCAN_ITEMS)
 
+// (a thread's 8 items are 32 contiguous bytes: two 16-byte accesses when the pointers allow and the items are all inside)
 __global__ void scan_block_kernel(const u32* in, u32* out, int64_t n, u32* block_sums) {
     __shared__ int sh[SCAN_NT / WAVE + 2];
     const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
+    const bool wide = base + SCAN_ITEMS <= n && ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
     u32 v[SCAN_ITEMS];
     u32 sum = 0;
+    if (wide) {
+        const uint4 a = *reinterpret_cast<const uint4*>(in + base), b = *reinterpret_cast<const uint4*>(in + base + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
 #pragma unroll
-    for (int i = 0; i < SCAN_ITEMS; ++i) {
-        v[i] = (base + i < n) ? in[base + i] : 0u;
-        sum += v[i];
+        for (int i = 0; i < SCAN_ITEMS; ++i) v[i] = (base + i < n) ? in[base + i] : 0u;
     }
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) sum += v[i];
     int total;
     u32 run = (u32)block_excl_scan((int)sum, sh, &total);
+    u32 o[SCAN_ITEMS];
 #pragma unroll
     for (int i = 0; i < SCAN_ITEMS; ++i) {
-        if (base + i < n) out[base + i] = run;
+        o[i] = run;
         run += v[i];
+    }
+    if (wide) {
+        *reinterpret_cast<uint4*>(out + base) = make_uint4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<uint4*>(out + base + 4) = make_uint4(o[4], o[5], o[6], o[7]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < SCAN_ITEMS; ++i)
+            if (base + i < n) out[base + i] = o[i];
     }
     if (threadIdx.x == 0) block_sums[blockIdx.x] = (u32)total;
 }
@@ -157,6 +172,14 @@ __global__ void scan_heads_block_kernel(const u32* __restrict__ keys, u32* out, 
 __global__ void scan_add_kernel(u32* out, int64_t n, const u32* block_offsets) {
     const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_ITEMS;
     const u32 o = block_offsets[blockIdx.x];
+    if (base + SCAN_ITEMS <= n && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+        uint4* p = reinterpret_cast<uint4*>(out + base);
+        uint4 a = p[0], b = p[1];
+        a.x += o; a.y += o; a.z += o; a.w += o; b.x += o; b.y += o; b.z += o; b.w += o;
+        p[0] = a;
+        p[1] = b;
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < SCAN_ITEMS; ++i)
         if (base + i < n) out[base + i] += o;
