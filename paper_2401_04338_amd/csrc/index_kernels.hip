@@ -569,7 +569,9 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set
             int nt = cp / 8;                                              // at most 8 rounds of 64 keys per wave while the block
             nt = nt < 256 ? 256 : (nt > 1024 ? 1024 : nt);                // allows (TFR_ROUNDS = 16 at the largest capacity)
             const size_t fixed = (size_t)(2 * ms + 2) * 4 + (size_t)(nt / WAVE) * 256 * 2;
-            const bool lds_uniq = (size_t)kcap * 12 + fixed <= 80 * 1024;   // the row list in LDS while two workgroups fit a compute unit
+            // the row list in LDS while two workgroups still fit a compute unit -- or when only one fits anyway
+            const bool lds_uniq = (size_t)kcap * 12 + fixed <= 80 * 1024 ||
+                                  ((size_t)kcap * 8 + fixed > 80 * 1024 && (size_t)kcap * 12 + fixed <= 158 * 1024);
             const size_t shmem = (size_t)kcap * 8 + (lds_uniq ? (size_t)kcap * 4 : 0) + fixed;
             if (lds_uniq) {
                 hipFuncSetAttribute((const void*)tf_sort_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
