@@ -361,6 +361,45 @@ def test_dense_only_adaptation(gm, bf, K, order):
     ctx.close()
 
 
+def test_error_paths_of_the_wider_entry_points(gm):
+    """gm_meta_train_step without room for the meta-gradient lists, gm_group_batch on offsets that are not monotone or a
+    share outside [0, 1], unknown settings: codes come back, nothing is updated, the context stays usable."""
+    from paper_2401_04338_amd.binding import GMetaError
+    from synth.generate import Params
+    cfg = small_cfg(n_tasks=3)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 26)
+    dev = ctx.device
+    dp = Params(params.emb.to(dev).clone(), [w.to(dev).clone() for w in params.W], [b.to(dev).clone() for b in params.b])
+    big = SMALL.with_(n_tasks=4)
+    ctx_big = gm.from_config(big, workspace_bytes=1 << 20)   # no room for the meta-gradient lists beside the step
+    sb, qb, pb = _inputs(big)
+    dpb = Params(pb.emb.to(dev).clone(), [w.to(dev).clone() for w in pb.W], [b.to(dev).clone() for b in pb.b])
+    before = dpb.emb.clone()
+    with pytest.raises(GMetaError) as e:
+        ctx_big.meta_train_step(_to_dev(sb, dev), _to_dev(qb, dev), dpb, 0.01, 1, 2, 0.1)
+    assert e.value.code == -4 and torch.equal(dpb.emb, before)
+    ctx_big.close()
+    with pytest.raises(GMetaError):
+        ctx.configure("no_such_setting", 1)
+    with pytest.raises(GMetaError):
+        ctx.configure("adapt_rows", 7)
+    n = sup.n_samples
+    task = np.zeros(n, dtype=np.int64)
+    bo = sup.bag_offsets.clone()
+    bo[5] = bo[7] + 3                                         # not monotone
+    with pytest.raises(GMetaError) as e:
+        ctx.group_batch(task, task, bo.to(dev), sup.indices.to(dev), sup.dense.to(dev), sup.labels.to(dev), 1, 2)
+    assert e.value.code == -2
+    with pytest.raises(GMetaError):
+        ctx.group_batch(task, task, sup.bag_offsets.to(dev), sup.indices.to(dev), sup.dense.to(dev), sup.labels.to(dev), 3, 2)
+    # still usable
+    gs, gq = ctx.group_batch(task, task, sup.bag_offsets.to(dev), sup.indices.to(dev), sup.dense.to(dev), sup.labels.to(dev), 1, 1)
+    assert gs.indices.numel() == sup.nnz and gq.indices.numel() == 0
+    ctx.meta_train_step(_to_dev(sup, dev), _to_dev(qry, dev), dp, 0.1, 1, 2, 0.1)
+    ctx.close()
+
+
 def test_scatter_add_is_the_outer_update(gm):
     cfg = small_cfg(n_tasks=3)
     sup, qry, params = _inputs(cfg)
