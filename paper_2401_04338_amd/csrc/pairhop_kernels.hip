@@ -89,14 +89,20 @@ __global__ __launch_bounds__(NT) void pair_count_kernel(PairCountArgs a) {
     if (threadIdx.x == 0) { sh_nhot = 0; sh_ncold = 0; }
     __syncthreads();
     {
-        const int2* in_list = a.sup_sorted + B;   // {row, slot}, slot-sorted
-        const int in_row0 = a.row_off_s[t];
-        for (int e = threadIdx.x; e < n_in_entries; e += NT) in_rows[e] = (uint16_t)(in_list[e].x - in_row0);
-        if (qs) {
-            const int2* out_list = a.qry_sorted + Bq;
-            const int out_row0 = a.row_off_q[t];
-            for (int e = threadIdx.x; e < n_out_entries; e += NT) out_rows[e] = (uint16_t)(out_list[e].x - out_row0);
-        }
+        // four loads in flight per thread and list: the workgroup has the compute unit to itself, so nothing else hides
+        // the latency of these first reads
+        auto stage_rows = [&](const int2* list, int n_entries, int row0, uint16_t* dst) {
+            for (int e0 = threadIdx.x; e0 < n_entries; e0 += 4 * NT) {
+                int r[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) r[q] = list[min(e0 + q * NT, n_entries - 1)].x;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (e0 + q * NT < n_entries) dst[e0 + q * NT] = (uint16_t)(r[q] - row0);
+            }
+        };
+        stage_rows(a.sup_sorted + B, n_in_entries, a.row_off_s[t], in_rows);   // {row, slot}, slot-sorted
+        if (qs) stage_rows(a.qry_sorted + Bq, n_out_entries, a.row_off_q[t], out_rows);
     }
     for (int u = threadIdx.x; u < nu; u += NT) {
         const int lo = a.slot_start[B + tf + u] - (int)B, hi = a.slot_start[B + tf + u + 1] - (int)B;
