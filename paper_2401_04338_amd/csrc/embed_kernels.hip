@@ -119,68 +119,98 @@ void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_row
 // ------------------------------------------------------------------------------------------------
 #define SEG_CH 64
 
-__global__ void seg_reduce_chunks_kernel(int D, int LG, const u32* __restrict__ keys, const u32* __restrict__ scan,
-                                         const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
-                                         int64_t capacity, int64_t n, const u32* __restrict__ sorted_vals,
-                                         const float* __restrict__ gx, float* emb_grad, float* partial, float* table) {
-    const int groups_per_block = blockDim.x / LG;
+// One lane group (LG = D/4 lanes, a float4 of the row each) walks one chunk.  The chunk's metadata is read LG positions
+// at a time, one position per lane (coalesced), and handed round the group by lane shuffles; the head flags of
+// the LG positions come back as one ballot word.  Whether a run began before the chunk or continues past it
+// follows from the head flags at the chunk's two borders, so no segment table is read here.
+template <int LG>
+__global__ void __launch_bounds__(256)
+seg_reduce_chunks_kernel(int D, const u32* __restrict__ keys, const u32* __restrict__ scan,
+                         const int64_t* __restrict__ n_rows, int64_t capacity, int64_t n,
+                         const u32* __restrict__ sorted_vals, const float* __restrict__ gx, float* emb_grad,
+                         float* partial, float* table) {
+    constexpr int GPB = 256 / LG;            // lane groups per workgroup
+    constexpr int U = LG < 8 ? LG : 8;       // row loads in flight per lane
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
-    if (g_in_block >= groups_per_block) return;
+    const int group_lane0 = (threadIdx.x % 64) / LG * LG;   // the group's first lane inside its wave
     const int64_t n_valid = min(*n_rows, capacity);
     const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
-    const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
+    const int64_t n_groups = (int64_t)gridDim.x * GPB;
     const float4* gx4 = reinterpret_cast<const float4*>(gx);
-    for (int64_t c = (int64_t)blockIdx.x * groups_per_block + g_in_block; c < n_chunks; c += n_groups) {
-        const int64_t cb = c * SEG_CH, ce = min(n, cb + SEG_CH);
+    for (int64_t c = (int64_t)blockIdx.x * GPB + g_in_block; c < n_chunks; c += n_groups) {
+        const int64_t cb = c * SEG_CH;
+        const int cnt = (int)min((int64_t)SEG_CH, n - cb);
+        // borders: does the chunk's last run go on in the next chunk; which segment does position cb lie in
+        const bool goes_on = (cb + cnt < n) && keys[cb + cnt] == keys[cb + cnt - 1];
+        int64_t seg = table ? 0 : (int64_t)scan[cb] - 1;     // + 1 at every head, the one at cb included
+        u32 v_next = 0, k_next = 0;
+        bool h_next = false;
+        auto load_meta = [&](int p0) {       // positions cb + p0 + l of the chunk
+            const int p = p0 + l;
+            v_next = 0, k_next = 0, h_next = false;
+            if (p < cnt) {
+                const int64_t i = cb + p;
+                v_next = sorted_vals[i];
+                k_next = keys[i];
+                h_next = (i == 0) || keys[i - 1] != k_next;
+            }
+        };
+        load_meta(0);
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        int64_t run_begin = cb;
-        int64_t cur = -1;
-        auto flush = [&](int64_t seg, int64_t a, int64_t b) {
-            if (seg < 0 || seg >= n_valid) return;
-            const int64_t s0 = seg_start[seg], s1 = seg_start[seg + 1];
+        bool began_before = false;           // the current run began in an earlier chunk
+        u32 run_key = 0;
+        auto flush = [&](bool continues) {
             float* dst;
-            if (a == s0 && b == s1) {                                               // whole segment in this chunk
-                if (table) {   // table-shaped output: added to the segment's row (rows of one call are distinct)
-                    float4* tp = reinterpret_cast<float4*>(table + (int64_t)keys[s0] * D + l * 4);
-                    *tp = add4(*tp, acc);
-                    return;
-                }
+            if (began_before) dst = partial + (c * 2 + 0) * D;
+            else if (continues) dst = partial + (c * 2 + 1) * D;
+            else if (table) {  // table-shaped output: added to the segment's row (rows of one call are distinct)
+                float4* tp = reinterpret_cast<float4*>(table + (int64_t)run_key * D + l * 4);
+                *tp = add4(*tp, acc);
+                return;
+            } else {
+                if (seg >= n_valid) return;
                 dst = emb_grad + seg * D;
-            } else if (s0 < a) dst = partial + (c * 2 + 0) * D;                     // began in an earlier chunk
-            else dst = partial + (c * 2 + 1) * D;                                   // continues in a later chunk
+            }
             *reinterpret_cast<float4*>(dst + l * 4) = acc;
         };
-        for (int64_t i0 = cb; i0 < ce; i0 += 4) {
-            u32 v[4];
-            int64_t sg[4];
-            float4 x[4];
+        for (int p0 = 0; p0 < cnt; p0 += LG) {
+            const u32 v = v_next, k = k_next;
+            const unsigned long long heads = (__ballot(h_next) >> group_lane0);
+            if (p0 + LG < cnt) load_meta(p0 + LG);
+            const int m = min(LG, cnt - p0);
+            for (int s0 = 0; s0 < m; s0 += U) {
+                u32 vv[U], kk[U];
+                float4 x[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t i = i0 + u;
-                if (i < ce) {
-                    v[u] = sorted_vals[i];
-                    const bool head = (i == 0) || (keys[i] != keys[i - 1]);
-                    sg[u] = (int64_t)scan[i] + (head ? 1 : 0) - 1;
+                for (int u = 0; u < U; ++u) {
+                    vv[u] = __shfl(v, s0 + u, LG);          // lanes past cnt hold row 0: a valid, unused read
+                    kk[u] = __shfl(k, s0 + u, LG);
                 }
-            }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (i0 + u < ce) x[u] = gx4[(int64_t)v[u] * LG + l];
+                for (int u = 0; u < U; ++u) x[u] = gx4[(int64_t)vv[u] * LG + l];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t i = i0 + u;
-                if (i >= ce) break;
-                if (sg[u] != cur) {
-                    flush(cur, run_begin, i);
-                    cur = sg[u];
-                    run_begin = i;
-                    acc = x[u];
-                } else {
-                    acc = add4(acc, x[u]);
+                for (int u = 0; u < U; ++u) {
+                    const int s = s0 + u;
+                    if (s >= m) break;
+                    const bool head = (heads >> s) & 1;
+                    if (p0 + s == 0) {
+                        began_before = !head;
+                        seg += head ? 1 : 0;
+                        run_key = kk[u];
+                        acc = x[u];
+                    } else if (head) {
+                        flush(false);
+                        began_before = false;
+                        seg += 1;
+                        run_key = kk[u];
+                        acc = x[u];
+                    } else {
+                        acc = add4(acc, x[u]);
+                    }
                 }
             }
         }
-        flush(cur, run_begin, ce);
+        flush(goes_on);
     }
 }
 
@@ -234,8 +264,17 @@ void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, 
     if (n <= 0 || capacity <= 0) return;
     const int LG = D / 4;
     const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
-    hipLaunchKernelGGL(seg_reduce_chunks_kernel, dim3(pool_grid(n_chunks, 256 / LG)), dim3(256), 0, st, D, LG, keys, scan,
-                       seg_start, n_rows, capacity, n, sorted_vals, gx, emb_grad, partial, table);
+    const dim3 grid(pool_grid(n_chunks, 256 / LG));
+#define SEG_CHUNKS(LG_)                                                                                              \
+    case LG_:                                                                                                        \
+        hipLaunchKernelGGL(seg_reduce_chunks_kernel<LG_>, grid, dim3(256), 0, st, D, keys, scan, n_rows, capacity, n, \
+                           sorted_vals, gx, emb_grad, partial, table);                                               \
+        break;
+    switch (LG) {
+        SEG_CHUNKS(1) SEG_CHUNKS(2) SEG_CHUNKS(4) SEG_CHUNKS(8) SEG_CHUNKS(16) SEG_CHUNKS(32) SEG_CHUNKS(64)
+        default: return;   // emb_dim is a power of two in 4..256 (checked when the context is made)
+    }
+#undef SEG_CHUNKS
     hipLaunchKernelGGL(seg_reduce_join_kernel, dim3(pool_grid(n_chunks, 256 / LG)), dim3(256), 0, st, D, LG, keys, scan,
                        seg_start, n_rows, capacity, n, partial, emb_grad, table);
 }
