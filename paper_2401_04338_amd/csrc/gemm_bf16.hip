@@ -5,13 +5,12 @@
 //     C_g[M, N] = sum_p  A_p,g[M, K] * B_p,g[K, N]          (p = 1 or 2 products)
 // A lane's MFMA fragment is 8 consecutive contraction values.  An operand stored contraction-contiguous
 // delivers them as one 16-byte LDS read; an operand stored with the contraction index slowest (template
-// flags KA / KB) goes to LDS row by row as it lies in memory and the lane collects its 8 values with eight
-// 2-byte LDS reads.  Every matrix therefore exists once, in the orientation it was produced in:
+// flags KA / KB) goes to LDS row by row as it lies in memory and the lane collects its 8 values with two
+// transposing LDS reads (ds_read_b64_tr_b16).  Every matrix therefore exists once, in the orientation it
+// was produced in:
 //   forward      A = activations [rows, d_in]  (contiguous),  B = W [d_in, d_out]          (KB)
 //   backward dA  A = deltas      [rows, d_out] (contiguous),  B = W [d_in, d_out] read as [n][k] (contiguous)
 //   weight grad  A = activations [rows, d_in]  (KA),          B = deltas [rows, d_out]     (KB), K = rows of the task
-// The eightfold LDS instruction count of the slow-index form is affordable where it is used: the forward
-// product and the weight gradient are bound by the per-task weights they stream, not by LDS issue.
 // A group is a task: its rows are [row_offsets[g], row_offsets[g+1]) and, once theta has been adapted,
 // its weights are its own (group stride != 0).
 #include "gm_internal.h"
@@ -21,6 +20,10 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 #define GK 64          // k extent of one LDS tile
 #define GLD (GK + 8)   // LDS row stride in elements: 144 bytes, an odd number of 16-byte units
+#define GPADK 32       // pad of a contraction-slowest tile's rows: four consecutive rows start 16 banks apart
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 // Waves: 2 along m, BN / 128 * 2 along n -- 4 waves for 128-wide tiles, 8 for 256-wide ones, so that a wave's share
 // is at most 128 x 64 (128 accumulator registers) whatever the block tile.
@@ -30,7 +33,7 @@ __global__ __launch_bounds__(BN > 128 ? 2 * (BN / 64) * 64 : 256) void gemm_bf16
     constexpr int NT = 2 * WN * 64;              // threads
     constexpr int MI = BM / 64, NI = BN / (32 * WN);  // 32x32 blocks per wave in each direction
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    constexpr int LDA_K = BM + 8, LDB_K = BN + 8;  // KM: LDS row strides of the [GK][BM] and [GK][BN] tiles
+    constexpr int LDA_K = BM + GPADK, LDB_K = BN + GPADK;  // KM: LDS row strides of the [GK][BM] and [GK][BN] tiles
     constexpr int TILE = (KA ? GK * LDA_K : BM * GLD) + (KB ? GK * LDB_K : BN * GLD);  // elements of one operand stage
 
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Re-number them so that
@@ -128,12 +131,16 @@ __global__ __launch_bounds__(BN > 128 ? 2 * (BN / 64) * 64 : 256) void gemm_bf16
             else *reinterpret_cast<uint4*>(stage + A_ELEMS + (crow + CR * i) * GLD + ccol) = rb[i];
         }
     };
-    // 8 contraction values of one column of a contraction-slowest tile, two per register
-    auto frag = [&](const bf16_t* col, int ld, int k) {
-        u32 w[4];
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) w[jj] = (u32)col[(k + 2 * jj) * ld] | ((u32)col[(k + 2 * jj + 1) * ld] << 16);
-        return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    // 8 contraction values of one column of a contraction-slowest tile: two transposing LDS reads
+    // (ds_read_b64_tr_b16).  Such a read serves 16 lanes at a time: lane s of the 16 points at 4 consecutive
+    // columns (s % 4) * 4.. of row s / 4, and lane i receives column i of those 4 rows.
+    const int tr_off_row = lhi * 8 + ((lane & 15) >> 2), tr_off_col = (lane & 16) + (lane & 3) * 4;
+    auto frag = [&](const bf16_t* tile, int ld, int c0, int k) {
+        const bf16_t* p = tile + (k + tr_off_row) * ld + c0 + tr_off_col;
+        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * ld));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
     auto compute = [&](const bf16_t* stage) {
         const bf16_t* As = stage;
@@ -143,12 +150,12 @@ __global__ __launch_bounds__(BN > 128 ? 2 * (BN / 64) * 64 : 256) void gemm_bf16
             bf16x8 af[MI], bfr[NI];
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
-                if constexpr (KA) af[i] = frag(As + wm0 + i * 32 + l32, LDA_K, kk * 16 + lhi * 8);
+                if constexpr (KA) af[i] = frag(As, LDA_K, wm0 + i * 32, kk * 16);
                 else af[i] = *reinterpret_cast<const bf16x8*>(As + (wm0 + i * 32 + l32) * GLD + kk * 16 + lhi * 8);
             }
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
-                if constexpr (KB) bfr[j] = frag(Bs + wn0 + j * 32 + l32, LDB_K, kk * 16 + lhi * 8);
+                if constexpr (KB) bfr[j] = frag(Bs, LDB_K, wn0 + j * 32, kk * 16);
                 else bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + (wn0 + j * 32 + l32) * GLD + kk * 16 + lhi * 8);
             }
 #pragma unroll
@@ -281,7 +288,7 @@ static void launch_variant(hipStream_t st, const GemmBArgs& a) {
     }
     if (n_mtiles <= 0 || n_ntiles <= 0) return;
     const int64_t n_tiles = n_mtiles * n_ntiles;
-    size_t shmem = ((KA ? (size_t)GK * (BM + 8) : (size_t)BM * GLD) + (KB ? (size_t)GK * (BN + 8) : (size_t)BN * GLD)) * sizeof(bf16_t) * (DB ? 2 : 1);
+    size_t shmem = ((KA ? (size_t)GK * (BM + GPADK) : (size_t)BM * GLD) + (KB ? (size_t)GK * (BN + GPADK) : (size_t)BN * GLD)) * sizeof(bf16_t) * (DB ? 2 : 1);
     constexpr int WN = BN > 128 ? BN / 64 : 2, NT = 2 * WN * 64;
     const size_t epi = (size_t)(2 * WN) * 32 * (BN / WN + 4) * sizeof(float);  // the epilogue's strips, one per wave
     if (shmem < epi) shmem = epi;
