@@ -133,7 +133,7 @@ seg_reduce_chunks_kernel(int D, const u32* __restrict__ keys, const u32* __restr
     constexpr int U = LG < 8 ? LG : 8;       // row loads in flight per lane
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
     const int group_lane0 = (threadIdx.x % 64) / LG * LG;   // the group's first lane inside its wave
-    const int64_t n_valid = min(*n_rows, capacity);
+    const int64_t n_valid = table ? 0 : min(*n_rows, capacity);
     const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
     const int64_t n_groups = (int64_t)gridDim.x * GPB;
     const float4* gx4 = reinterpret_cast<const float4*>(gx);
@@ -214,31 +214,44 @@ seg_reduce_chunks_kernel(int D, const u32* __restrict__ keys, const u32* __restr
     }
 }
 
-// One lane group per CHUNK: if a segment starts inside the chunk and runs past its end, this group adds its
-// partial sums in chunk order (every such segment is the last one of exactly one chunk).
+// One lane group per CHUNK: if the chunk's last run begins inside the chunk and goes on past it, this group adds
+// the pieces the following chunks left (each of them starts with the same key) in chunk order.  Every such
+// segment is the last one of exactly one chunk.
 __global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ keys, const u32* __restrict__ scan,
-                                       const u32* __restrict__ seg_start, const int64_t* __restrict__ n_rows,
-                                       int64_t capacity, int64_t n, const float* __restrict__ partial, float* emb_grad,
-                                       float* table) {
+                                       const int64_t* __restrict__ n_rows, int64_t capacity, int64_t n,
+                                       const float* __restrict__ partial, float* emb_grad, float* table) {
     const int groups_per_block = blockDim.x / LG;
     const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
     if (g_in_block >= groups_per_block) return;
-    const int64_t n_valid = min(*n_rows, capacity);
+    const int64_t n_valid = table ? 0 : min(*n_rows, capacity);
     const int64_t n_chunks = (n + SEG_CH - 1) / SEG_CH;
     const int64_t n_groups = (int64_t)gridDim.x * groups_per_block;
     for (int64_t c = (int64_t)blockIdx.x * groups_per_block + g_in_block; c + 1 < n_chunks; c += n_groups) {
-        const int64_t cb = c * SEG_CH, ce = cb + SEG_CH;   // not the last chunk, so it is full
-        const int64_t i = ce - 1;
-        const bool head = (i == 0) || (keys[i] != keys[i - 1]);
-        const int64_t seg = (int64_t)scan[i] + (head ? 1 : 0) - 1;
-        if (seg >= n_valid) continue;
-        const int64_t s0 = seg_start[seg], s1 = seg_start[seg + 1];
-        if (s0 < cb || s1 <= ce) continue;                 // began earlier, or ends inside this chunk
-        const int64_t c1 = (s1 - 1) / SEG_CH;
+        const int64_t cb = c * SEG_CH, ce = cb + SEG_CH;   // not the last chunk, so it is full and ce < n
+        const u32 key = keys[ce - 1];
+        if (keys[ce] != key) continue;                     // the run ends with the chunk
+        if (cb > 0 && keys[cb - 1] == key) continue;       // began in an earlier chunk, which adds it up
+        int64_t seg = 0;
+        if (!table) {
+            seg = (int64_t)scan[ce - 1] + (keys[ce - 2] != key ? 1 : 0) - 1;
+            if (seg >= n_valid) continue;
+        }
+        // c1: the last chunk that starts with the key.  Most segments end in chunk c + 1, a hot row's spans
+        // thousands: gallop forward in doubling steps, then bisect (the keys are sorted).
+        auto starts_with_key = [&](int64_t cc) { return cc < n_chunks && keys[cc * SEG_CH] == key; };
+        int64_t c1 = c + 1, step = 1;
+        while (starts_with_key(c1 + step)) {
+            c1 += step;
+            step *= 2;
+        }
+        for (int64_t hi = c1 + step; hi - c1 > 1;) {       // chunk c1 starts with the key, chunk hi does not
+            const int64_t mid = c1 + (hi - c1) / 2;
+            if (starts_with_key(mid)) c1 = mid;
+            else hi = mid;
+        }
         float4 acc = *reinterpret_cast<const float4*>(partial + (c * 2 + 1) * D + l * 4);
-        // a hot row's segment spans thousands of chunks: keep 8 independent loads in flight, add in chunk order
         int64_t cc = c + 1;
-        for (; cc + 8 <= c1 + 1; cc += 8) {
+        for (; cc + 8 <= c1 + 1; cc += 8) {       // 8 independent loads in flight, added in chunk order
             float4 x[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) x[u] = *reinterpret_cast<const float4*>(partial + ((cc + u) * 2 + 0) * D + l * 4);
@@ -248,7 +261,7 @@ __global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ ke
         for (; cc <= c1; ++cc)
             acc = add4(acc, *reinterpret_cast<const float4*>(partial + (cc * 2 + 0) * D + l * 4));
         if (table) {
-            float4* tp = reinterpret_cast<float4*>(table + (int64_t)keys[s0] * D + l * 4);
+            float4* tp = reinterpret_cast<float4*>(table + (int64_t)key * D + l * 4);
             *tp = add4(*tp, acc);
         } else {
             *reinterpret_cast<float4*>(emb_grad + seg * D + l * 4) = acc;
@@ -258,8 +271,7 @@ __global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ ke
 
 size_t seg_reduce_partial_floats(int64_t n, int D) { return (size_t)((n + SEG_CH - 1) / SEG_CH) * 2 * D + 16; }
 
-void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const u32* seg_start,
-                       const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
+void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
                        float* emb_grad, float* partial, float* table) {
     if (n <= 0 || capacity <= 0) return;
     const int LG = D / 4;
@@ -276,7 +288,7 @@ void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, 
     }
 #undef SEG_CHUNKS
     hipLaunchKernelGGL(seg_reduce_join_kernel, dim3(pool_grid(n_chunks, 256 / LG)), dim3(256), 0, st, D, LG, keys, scan,
-                       seg_start, n_rows, capacity, n, partial, emb_grad, table);
+                       n_rows, capacity, n, partial, emb_grad, table);
 }
 
 __global__ void scatter_add_kernel(int D, int LG, float* table, const int64_t* __restrict__ rows,

@@ -160,9 +160,10 @@ struct PairHopArgs {
 void launch_pair_hop(hipStream_t st, PairHopArgs a, int Tw, int max_out_rows);
 void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_rows, float* x_out, int ldx, bf16_t* x_bf);
 
-// keys: the sorted row keys; scan: exclusive scan of their segment-head flags (both as launch_segments left them)
-void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const u32* seg_start,
-                       const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
+// keys: the sorted row keys; scan: exclusive scan of their segment-head flags and n_rows: the number of segments
+// (both as launch_segments left them; neither is read when the output is table-shaped)
+void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const int64_t* n_rows,
+                       int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
                        float* emb_grad, float* partial /* seg_reduce_partial_floats(n, D) */,
                        float* table /* null, or [all rows, D]: every segment is ADDED to its row instead of listed */);
 size_t seg_reduce_partial_floats(int64_t n, int D);

@@ -1035,8 +1035,10 @@ static int global_order(gm_ctx* c, Batch& B, SortBufs& so, const SortRange& r, i
         std::swap(so.keys, so.keys_tmp);   // an odd number of passes leaves the result in the second pair of buffers
         std::swap(so.vals, so.vals_tmp);
     }
-    launch_segments(st, so.keys, nnz, so.keys_tmp, so.scan_tmp, emb_rows, so.seg_start, seg_counts, capacity, n_rows,
-                    status);
+    // the table-shaped output adds every segment to the row its key names: no segment numbers, no row list
+    if (n_rows)
+        launch_segments(st, so.keys, nnz, so.keys_tmp, so.scan_tmp, emb_rows, so.seg_start, seg_counts, capacity, n_rows,
+                        status);
     return GM_OK;
 }
 
@@ -1392,7 +1394,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             launch_fill_u32(c->side, c->d_status_side, ST_WORDS, 0);
             const SortRange r{wp.s0, wp.s1, wp.q0, wp.q1, wp.ls0, wp.ls1, wp.lq0, wp.lq1,
                               (u32)(0 - (uint64_t)wp.ps0), (u32)((uint64_t)d.Ps - (uint64_t)wp.pq0)};
-            global_order(c, B, w.so, r, nullptr, nullptr, d.nnz_s + d.nnz_q, w.n_rows, true);
+            global_order(c, B, w.so, r, nullptr, nullptr, d.nnz_s + d.nnz_q, nullptr, true);
             HIPCHK(c, hipEventRecord(c->ev_side, c->side));
         } else if (!table && c->overlap_sort && F > 0 && plans.size() == 1) {
             side.active = true;
@@ -1578,10 +1580,10 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                               (u32)(0 - (uint64_t)wp.ps0), (u32)((uint64_t)d.Ps - (uint64_t)wp.pq0)};
             const int64_t nw = d.nnz_s + d.nnz_q;
             if (side_table) HIPCHK(c, hipStreamWaitEvent(st, c->ev_side, 0));
-            else global_order(c, B, w.so, r, nullptr, nullptr, nw, w.n_rows);
+            else global_order(c, B, w.so, r, nullptr, nullptr, nw, nullptr);
             {
                 Prof p(c, "seg_reduce", (double)nw * (4.0 * D + 4), 0);
-                launch_seg_reduce(st, D, w.so.keys, w.so.keys_tmp, w.so.seg_start, w.n_rows, nw, nw, w.so.vals, w.GX, nullptr,
+                launch_seg_reduce(st, D, w.so.keys, w.so.keys_tmp, nullptr, nw, nw, w.so.vals, w.GX, nullptr,
                                   w.so.seg_partial, table);
             }
             if (side_table) HIPCHK(c, hipEventRecord(c->ev_main, st));
@@ -1602,7 +1604,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         else global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows);
         if (F > 0) {
             Prof p(c, "seg_reduce", (double)nnz * (4.0 * D + 4), 0);
-            launch_seg_reduce(st, D, b.so.keys, b.so.keys_tmp, b.so.seg_start, out->n_emb_rows, capacity, nnz, b.so.vals,
+            launch_seg_reduce(st, D, b.so.keys, b.so.keys_tmp, out->n_emb_rows, capacity, nnz, b.so.vals,
                               b.GX, out->emb_grad, b.so.seg_partial, nullptr);
         }
     }
