@@ -662,6 +662,26 @@ def test_coldstart_config_full_size_sampled_tasks(gm):
     ctx.close()
 
 
+@pytest.mark.parametrize("D", [8, 16, 128, 256])
+def test_embedding_widths(gm, D):
+    """Every embedding width has its own lane-group shape in the gather, the segmented reduction and the scatter
+    (D / 4 lanes per row): widths the five configs do not use, hot rows whose segments span many 64-lookup chunks
+    (zipf over 300 rows), both shapes of the sparse output."""
+    cfg = SMALL.with_(n_tasks=3, n_support=48, n_query=40, n_fields=3, emb_dim=D, rows_per_field=300, bag_max=9,
+                      layer_dims=(3 * D + 13, 32, 1), inner_lr=0.05, zipf_s=1.2)
+    sup, qry, params = _inputs(cfg, emb_std=0.2)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+    dev = ctx.device
+    out, ref = _compare_step(cfg, ctx, sup, qry, params, 1, 2, TOL_FP32, f"D={D}")
+    table = torch.zeros(cfg.total_rows, D, dtype=torch.float32, device=dev)
+    ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, 1, 2, emb_grad_table=table)
+    n = int(out["n_emb_rows"].item())
+    want = torch.zeros_like(table)
+    want[out["emb_rows"][:n]] = out["emb_grad"][:n]
+    assert torch.equal(table, want)
+    ctx.close()
+
+
 def test_large_config_shape(gm):
     """configs[4]'s shapes on two of its tasks (64 fields, bags of 1-32, 512 + 512 samples per task, MLP
     4109-1024-512-256-1, bf16 operands, K=1, second order) over smaller tables (2^16 rows per field, so that the oracle's
