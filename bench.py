@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--batches", type=int, default=2, help="distinct pre-generated batches cycled through")
     ap.add_argument("--configure", action="append", default=[], metavar="KEY=VALUE",
                     help="gm_configure setting for the run (e.g. row_path=1, gemm_tile_n=256); may be repeated")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="also time the vendor library (torch.bmm, bf16) on the first layer's forward product of this workload: "
+                         "what a grouped GEMM with per-task weights reaches on this GPU with the same shapes and random values")
     ap.add_argument("--copy-probe-gib", type=float, default=0.0,
                     help="also run one device copy of this size (a known transfer that calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -238,6 +241,26 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    vendor = None
+    if args.vendor_gemm and cfg.mlp_dtype:
+        # context for roofline_gemm, not part of the path: per-task weights [d0, d1], one set's rows per task
+        Tg = min(cfg.n_tasks, 256)
+        rows, d0, d1 = int(cfg.n_support), -(-int(cfg.layer_dims[0]) // 32) * 32, int(cfg.layer_dims[1])
+        xa = torch.randn(Tg, rows, d0, device=dev, dtype=torch.bfloat16)
+        wb = torch.randn(Tg, d0, d1, device=dev, dtype=torch.bfloat16)
+        best = None
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            torch.bmm(xa, wb)
+            e1.record()
+            torch.cuda.synchronize()
+            best = e0.elapsed_time(e1) if best is None else min(best, e0.elapsed_time(e1))
+        fl = 2.0 * Tg * rows * d0 * d1
+        vendor = dict(op="torch.bmm bf16 (vendor library), first layer forward", tasks=Tg, m=rows, k=d0, n=d1, ms=best,
+                      achieved=fl / (best * 1e-3) / 1e12, unit="TFLOP/s", frac_of_mfma_peak=fl / (best * 1e-3) / 2.5e15)
+        del xa, wb
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, cfg_gen, K, order, args.cpu_seconds, params.numpy(),
@@ -260,6 +283,7 @@ def main():
         "kernels": fams,
         "outer_update_sparse": outer,
         "group_batch": grouping,
+        "vendor_gemm": vendor,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
