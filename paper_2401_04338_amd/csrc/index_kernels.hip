@@ -642,7 +642,7 @@ void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const i
 }
 
 #define RS_NT 256
-#define RS_ITEMS 16
+#define RS_ITEMS 8
 #define RS_TILE (RS_NT * RS_ITEMS)
 #define RS_WAVES (RS_NT / WAVE)
 
