@@ -255,7 +255,8 @@ void launch_last_fwd(hipStream_t st, const LastFwdArgs& a);
 void launch_last_bwd(hipStream_t st, int bf16, int64_t n, int N, int64_t ld_a, int64_t ld_d, const int32_t* row_task,
                      const float* dl, const float* w, int64_t gW, const float* dl2, const float* w2, int64_t gW2,
                      const void* act, void* d, float* d_f32);
-void launch_reduce_tasks(hipStream_t st, const float* v, int64_t ld, int G, int64_t n, float* out, int accumulate);
+void launch_reduce_tasks(hipStream_t st, const float* v, int64_t ld, int G, int64_t n, float* out, int accumulate,
+                         float scale = 1.f);
 void launch_fill_sample_task(hipStream_t st, const int32_t* row_offsets, int G, int32_t* sample_task);
 void launch_pack_weights(hipStream_t st, const float* W, int din, int dout, int ld_in, int ld_out, float* dst);
 void launch_unpack_weights(hipStream_t st, const float* src, int din, int dout, int ld_out, float* W);

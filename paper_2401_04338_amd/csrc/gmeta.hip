@@ -231,6 +231,8 @@ struct SortBufs {
     float* seg_partial = nullptr;
 };
 
+enum { COARSE_GROUPS = 16 };
+
 struct WaveBufs {
     int32_t *row_off_s, *row_off_q, *real_off_s, *real_off_q;
     int32_t *sample_task_s, *sample_task_q, *row_task_s, *row_task_q;
@@ -241,6 +243,10 @@ struct WaveBufs {
     int2 *sup_sorted, *qry_sorted;
     float *Xs0, *Xq0, *TXf, *dX, *loss_q;
     Theta v;  // direction / query gradient w.r.t. theta'
+    // the last weight-gradient products of a call are only ever summed over the tasks: they are taken over COARSE_GROUPS
+    // runs of consecutive tasks instead (row offsets of the runs, one sum per run)
+    int32_t *coarse_off_s, *coarse_off_q;
+    Theta vsum;
     Act Xs_scratch;
     std::vector<StepState> steps;
     std::vector<Theta> thetas;
@@ -344,6 +350,9 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
     w.dX = ar.get<float>(std::max(d.Ps, d.Pq) * (int64_t)std::max(c->FD, 1) + 4);
     w.loss_q = ar.get<float>(d.Pq + 1);
     w.v = alloc_theta(c, ar, d.Tw, true);
+    w.coarse_off_s = ar.get<int32_t>(COARSE_GROUPS + 1);
+    w.coarse_off_q = ar.get<int32_t>(COARSE_GROUPS + 1);
+    w.vsum = Theta{ar.get<float>((int64_t)COARSE_GROUPS * c->n_theta), c->n_theta, nullptr, 0};
     if (!second) w.v.b = nullptr;  // the direction is a GEMM operand only in the second-order pass
     w.Xs_scratch = Act();
     if (K > 1 && !second) {
@@ -835,14 +844,18 @@ static void forward_backward(gm_ctx* c, const Grp& g, const float* labels, const
     }
 }
 
-// out = c0*in + c1 * (gradient of the pass w.r.t. theta), per task; out.b (if any) gets the bf16 operand copies
+// out = c0*in + c1 * (gradient of the pass w.r.t. theta), per task; out.b (if any) gets the bf16 operand copies.
+// coarse / coarse_out: the hidden layers' weight matrices are summed over runs of tasks instead (c1 times the gradient,
+// nothing added), for a caller that only wants their sum over the tasks; biases and the last layer stay per task.
 static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, Theta& out, const float* in, int64_t in_stride, float c0,
-                       float c1, float* wL_copy, bool write_f32 = true) {
+                       float c1, float* wL_copy, bool write_f32 = true, const Grp* coarse = nullptr,
+                       Theta* coarse_out = nullptr) {
     const int L = c->L;
     const int64_t nt = out.sf;
     for (int l = 1; l < L; ++l) {
         const Act* prev = l == 1 ? p.X : &(*p.A)[l - 1];
-        dense_tn(c, g, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, out, in, in_stride, c0, c1, write_f32);
+        if (coarse) dense_tn(c, *coarse, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, *coarse_out, nullptr, 0, 0.f, c1);
+        else dense_tn(c, g, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, out, in, in_stride, c0, c1, write_f32);
         colsum(c, g, c->ld[l], &(*p.Dl)[l], nullptr, nullptr, nullptr, out.f + c->offb[l], nt, in ? in + c->offb[l] : nullptr,
                in_stride, c0, c1);
     }
@@ -859,8 +872,10 @@ static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, Theta& out, const
 // (tangent pass through the forward and the backward pass of step s, direction (v, TX))
 // gx_acc (bf16 mode): the support rows of the sparse-gradient buffer, which take -alpha * (tangent of dX) in the
 // layer-1 product itself; need_dx: the tangent of dX is also wanted in w.dX (for the row arithmetic of the next step)
+// coarse (the chain's last step): the weight matrices' part of H v is not folded into every task's v but summed over
+// runs of tasks into w.vsum (unscaled); the caller adds -alpha times their sum to the reduced v
 static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, float alpha, bool refresh_v_copies,
-                     float* gx_acc, bool need_dx, bool gx_init, bool tx) {
+                     float* gx_acc, bool need_dx, bool gx_init, bool tx, const Grp* coarse = nullptr) {
     hipStream_t st = c->stream;
     const int L = c->L;
     Theta& v = w.v;
@@ -902,7 +917,10 @@ static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, f
         else dense_nt(c, g, l, 2, &w.TD[l], &s.th, &s.Dl[l], &v, &s.A[l - 1], &w.TD[l - 1], nullptr);
         const Act* ta_prev = l == 1 ? &w.TX : &w.TA[l - 1];
         const Act* a_prev = l == 1 ? &s.X : &s.A[l - 1];
-        if (l == 1 && !tx) dense_tn(c, g, l, 1, a_prev, &w.TD[l], nullptr, nullptr, vout, v.f, nt, 1.f, -alpha);
+        if (coarse) {
+            if (l == 1 && !tx) dense_tn(c, *coarse, l, 1, a_prev, &w.TD[l], nullptr, nullptr, w.vsum, nullptr, 0, 0.f, 1.f);
+            else dense_tn(c, *coarse, l, 2, ta_prev, &s.Dl[l], a_prev, &w.TD[l], w.vsum, nullptr, 0, 0.f, 1.f);
+        } else if (l == 1 && !tx) dense_tn(c, g, l, 1, a_prev, &w.TD[l], nullptr, nullptr, vout, v.f, nt, 1.f, -alpha);
         else dense_tn(c, g, l, 2, ta_prev, &s.Dl[l], a_prev, &w.TD[l], vout, v.f, nt, 1.f, -alpha);
         colsum(c, g, c->ld[l], &w.TD[l], nullptr, nullptr, nullptr, v.f + c->offb[l], nt, v.f + c->offb[l], nt, 1.f, -alpha);
     }
@@ -1207,7 +1225,16 @@ static int setup_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, int bm, int
         re_s.push_back((int32_t)(B.sup->task_offsets[t] - wp.s0));
         re_q.push_back((int32_t)(B.qry->task_offsets[t] - wp.q0));
     }
+    // runs of consecutive tasks for the products that are only summed over the tasks
+    std::vector<int32_t> co_s, co_q;
+    const int n_coarse = std::min<int>(d.Tw, COARSE_GROUPS);
+    for (int i = 0; i <= n_coarse; ++i) {
+        const int t = (int)((int64_t)i * d.Tw / n_coarse);
+        co_s.push_back(ro_s[t]);
+        co_q.push_back(ro_q[t]);
+    }
     int rc;
+    if ((rc = upload_i32(c, w.coarse_off_s, co_s)) || (rc = upload_i32(c, w.coarse_off_q, co_q))) return rc;
     if ((rc = upload_i32(c, w.row_off_s, ro_s)) || (rc = upload_i32(c, w.row_off_q, ro_q)) ||
         (rc = upload_i32(c, w.real_off_s, re_s)) || (rc = upload_i32(c, w.real_off_q, re_q)) ||
         (rc = upload_i32(c, w.tile_g_s, tg_s)) || (rc = upload_i32(c, w.tile_m_s, tm_s)) ||
@@ -1536,7 +1563,14 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         Pass pq{&Xq, &w.Aq, &w.Dq, w.dLq, w.zq};
         forward_backward(c, gq, labels_q, pq, th, thf, thf_stride, w.loss_q, F > 0 ? gxq : nullptr);
         colsum_f32(c, gq, 1, w.loss_q, 1, task_loss + wp.t0, 1, nullptr, 0, 0.f, 1.f);
-        theta_grad(c, gq, pq, w.v, nullptr, 0, 0.f, 1.f, nullptr);
+        // The query gradient w.r.t. theta' per task starts the second-order chain; without a chain it is only summed
+        // over the tasks, so it is taken over runs of tasks straight away.
+        const int n_coarse = std::min<int>(Tw, COARSE_GROUPS);
+        Grp gs_coarse = gs, gq_coarse = gq;
+        gs_coarse.row_off = w.coarse_off_s; gs_coarse.G = n_coarse;
+        gq_coarse.row_off = w.coarse_off_q; gq_coarse.G = n_coarse;
+        if (second) theta_grad(c, gq, pq, w.v, nullptr, 0, 0.f, 1.f, nullptr);
+        else theta_grad(c, gq, pq, w.v, nullptr, 0, 0.f, 1.f, nullptr, true, &gq_coarse, &w.vsum);
 
         // second-order chain back through the inner steps: v_k = v_{k+1} - alpha H_k v_{k+1}
         if (second) {
@@ -1555,7 +1589,8 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                 // bf16 with hidden layers: the layer-1 product adds -alpha * dX to the gradient buffer itself
                 const bool fused_gx = bf && L > 1 && F > 0;
                 // (the chain's first step starts that sum: the buffer's support rows need no clearing)
-                hvp_step(c, gs, s, w, alpha, k > 0, fused_gx ? gxs : nullptr, k > 0 && adapt, k == K - 1, adapt);
+                hvp_step(c, gs, s, w, alpha, k > 0, fused_gx ? gxs : nullptr, k > 0 && adapt, k == K - 1, adapt,
+                         k == 0 ? &gs_coarse : nullptr);
                 if (F > 0) {
                     if (!fused_gx) {
                         Prof p(c, "axpy_gx", 12.0 * d.Ps * FD, 0);
@@ -1570,8 +1605,21 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         }
         // cross-task reduction of the dense part (tasks of the wave in order, waves in order)
         {
-            Prof p(c, "reduce_tasks", 4.0 * Tw * nt, 0);
-            launch_reduce_tasks(st, w.v.f, nt, Tw, nt, b.g_theta, 1);
+            Prof p(c, "reduce_tasks", 4.0 * (second ? Tw : n_coarse) * nt, 0);
+            if (second) {
+                launch_reduce_tasks(st, w.v.f, nt, Tw, nt, b.g_theta, 1, 1.f);
+                for (int l = 1; l < L; ++l)   // the last step's weight-matrix part, summed over runs of tasks
+                    launch_reduce_tasks(st, w.vsum.f + c->offW[l], nt, n_coarse, (int64_t)c->ld[l - 1] * c->ld[l],
+                                        b.g_theta + c->offW[l], 1, -alpha);
+            } else {   // weight matrices of the hidden layers from the runs of tasks, the rest from the tasks
+                for (int l = 1; l < L; ++l) {
+                    launch_reduce_tasks(st, w.vsum.f + c->offW[l], nt, n_coarse, c->offb[l] - c->offW[l],
+                                        b.g_theta + c->offW[l], 1, 1.f);
+                    launch_reduce_tasks(st, w.v.f + c->offb[l], nt, Tw, c->offW[l + 1] - c->offb[l], b.g_theta + c->offb[l], 1,
+                                        1.f);
+                }
+                launch_reduce_tasks(st, w.v.f + c->offW[L], nt, Tw, nt - c->offW[L], b.g_theta + c->offW[L], 1, 1.f);
+            }
         }
         // table-shaped sparse output: the wave's lookups are ordered by row and every row's sum is added to its row of
         // the table (rows are distinct within a wave; waves follow each other on the stream)

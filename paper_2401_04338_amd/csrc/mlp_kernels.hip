@@ -424,21 +424,31 @@ void launch_last_bwd(hipStream_t st, int bf16, int64_t n, int N, int64_t ld_a, i
 
 // ------------------------------------------------------------------------------------------------
 // cross-task reduction of the dense meta-gradient (Alg. 1, global back-propagation on theta; Sec. 2.1.3):
-// out[j] (+)= sum_g v[g, j], tasks added in task order
+// out[j] (+)= sum_g v[g, j], tasks added in task order; with a scale other than 1: out[j] (+)= scale * (sum_g v[g, j])
 // ------------------------------------------------------------------------------------------------
 __global__ void reduce_tasks_kernel(const float* __restrict__ v, int64_t ld, int G, int64_t n, float* out,
-                                    int accumulate) {
+                                    int accumulate, float scale) {
     const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= n) return;
-    float acc = accumulate ? out[j] : 0.f;
-    for (int g = 0; g < G; ++g) acc += v[(int64_t)g * ld + j];
-    out[j] = acc;
+    // eight tasks' values are requested before the first is added (the order of the sum stays the task order)
+    float acc = (accumulate && scale == 1.f) ? out[j] : 0.f;
+    int g = 0;
+    for (; g + 8 <= G; g += 8) {
+        float x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = v[(int64_t)(g + u) * ld + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += x[u];
+    }
+    for (; g < G; ++g) acc += v[(int64_t)g * ld + j];
+    out[j] = scale == 1.f ? acc : (accumulate ? out[j] : 0.f) + scale * acc;
 }
 
-void launch_reduce_tasks(hipStream_t st, const float* v, int64_t ld, int G, int64_t n, float* out, int accumulate) {
+void launch_reduce_tasks(hipStream_t st, const float* v, int64_t ld, int G, int64_t n, float* out, int accumulate,
+                         float scale) {
     if (n <= 0) return;
     hipLaunchKernelGGL(reduce_tasks_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, v, ld, G, n, out,
-                       accumulate);
+                       accumulate, scale);
 }
 
 __global__ void fill_sample_task_kernel(const int32_t* row_offsets, int32_t* sample_task) {
