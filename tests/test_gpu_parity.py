@@ -662,6 +662,22 @@ def test_coldstart_config_full_size_sampled_tasks(gm):
     ctx.close()
 
 
+@pytest.mark.parametrize("bf,K,order", [(0, 2, 2), (0, 1, 1), (1, 2, 2), (1, 0, 2)])
+def test_more_tasks_than_coarse_runs(gm, bf, K, order):
+    """The weight-gradient products that only feed the sum over the tasks (last step of the second-order chain; the
+    query gradient when there is no chain) are taken over 16 runs of consecutive tasks.  37 tasks of log-normal size:
+    runs of two and three tasks with ragged row counts, every output against the oracle."""
+    from synth.generate import task_sizes
+    cfg = small_cfg(n_tasks=37, inner_lr=0.1, mlp_dtype=bf).with_(lognormal_sizes=True, size_median=9, size_sigma=0.8,
+                                                                   size_max=40)
+    sup, qry, params = _inputs(cfg, emb_std=0.3)
+    assert len(set(task_sizes(cfg)[:, 0])) > 3, "the case must have ragged tasks"
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 29)
+    _compare_step(cfg, ctx, sup, qry, params, K, order, TOL_BF16 if bf else TOL_FP32, f"37 tasks bf16={bf} K={K} order={order}",
+                  operand="bf16" if bf else "fp64")
+    ctx.close()
+
+
 @pytest.mark.parametrize("D", [8, 16, 128, 256])
 def test_embedding_widths(gm, D):
     """Every embedding width has its own lane-group shape in the gather, the segmented reduction and the scatter
