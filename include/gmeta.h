@@ -197,6 +197,10 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *   "overlap_sort": 1 = the ordering of the lookups by row (it depends on the indices only) runs on a second
  *               stream of the context beside the dense phase and is joined before the segment reduction;
  *               0 (default) = everything on the context's stream.  Identical results.
+ *   "overlap_pairs": 1 = the pair-count matrices (they depend on the indices only) are counted on the second
+ *               stream beside the prefetch and the first forward / backward pass and joined before the first
+ *               row hop; 0 (default) = on the context's stream.  Identical results; ignored while
+ *               "overlap_sort" is 1.
  *   "gemm_tile_n": column tile of the forward / backward grouped products when tasks get 256-row tiles:
  *               0 = chosen by the library (128), 128, or 256 (eight waves per workgroup; identical results).
  *   "pair_tile_rows": most out-rows of a pair-count matrix that the counting kernel holds in LDS at a time

@@ -71,6 +71,11 @@ struct gm_ctx {
     // computation (same priority) and is joined before the segment reduction.
     hipStream_t side = nullptr;
     hipEvent_t ev_side = nullptr, ev_main = nullptr, ev_go = nullptr;
+    // The pair-count matrices depend on the indices only and are first read by the first row hop: counting them on the
+    // side stream lets the prefetch and the first forward / backward pass (bound by memory traffic) run beside a kernel
+    // that is bound by latency and instruction issue.
+    hipEvent_t ev_pairs_go = nullptr, ev_pairs = nullptr;
+    int overlap_pairs = 0;
     int overlap_sort = 0;   // measured: 1-1.5 % (both streams contend for the same memory system), so off unless asked for
     std::string err;
     int pair_tile_rows = 0;
@@ -477,6 +482,8 @@ extern "C" int gm_create(gm_ctx** out, const gm_model_desc* model, int device, v
     HIPCHK(c, hipEventCreateWithFlags(&c->ev_side, hipEventDisableTiming));
     HIPCHK(c, hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming));
     HIPCHK(c, hipEventCreateWithFlags(&c->ev_go, hipEventDisableTiming));
+    HIPCHK(c, hipEventCreateWithFlags(&c->ev_pairs_go, hipEventDisableTiming));
+    HIPCHK(c, hipEventCreateWithFlags(&c->ev_pairs, hipEventDisableTiming));
     c->persistent = ar.off;
     HIPCHK(c, hipMemcpy(c->d_field_base, c->field_base.data(), (c->F + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     return GM_OK;
@@ -495,6 +502,8 @@ extern "C" void gm_destroy(gm_ctx* c) {
         if (c->ev_side) (void)hipEventDestroy(c->ev_side);
         if (c->ev_main) (void)hipEventDestroy(c->ev_main);
         if (c->ev_go) (void)hipEventDestroy(c->ev_go);
+        if (c->ev_pairs_go) (void)hipEventDestroy(c->ev_pairs_go);
+        if (c->ev_pairs) (void)hipEventDestroy(c->ev_pairs);
         (void)hipFree(c->ws);
     }
     delete c;
@@ -518,6 +527,11 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
     if (!strcmp(key, "adapt_rows")) {
         if (value != 0 && value != 1) return fail(c, GM_ERR_ARG, "adapt_rows must be 0 or 1");
         c->adapt_rows = (int)value;
+        return GM_OK;
+    }
+    if (!strcmp(key, "overlap_pairs")) {   // (ignored while overlap_sort is on: one side stream, one set of status words)
+        if (value != 0 && value != 1) return fail(c, GM_ERR_ARG, "overlap_pairs must be 0 or 1");
+        c->overlap_pairs = (int)value;
         return GM_OK;
     }
     if (!strcmp(key, "overlap_sort")) {
@@ -1340,6 +1354,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         const bool adapt = c->adapt_rows != 0;
         bool pair = d.pair && tf_cap <= PAIR_MAX_CAP && max_bag <= PAIR_MAX_BAG;
         bool any_sparse = d.any_sparse || (d.pair && !pair);
+        bool pairs_on_side = false;
         if (d.pair && !pair) launch_fill_u32(st, w.task_path, Tw, 0u);
         if (pair) {
             PairCountArgs pa;
@@ -1352,8 +1367,17 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             pa.off_ss = w.pair_off_ss; pa.off_qs = w.pair_off_qs; pa.off_sq = w.pair_off_sq;
             pa.mat = w.pair_mat; pa.want_ss = d.pair_ss; pa.want_sq = d.pair_sq; pa.status = c->d_status;
             pa.task_path = w.task_path;
+            pairs_on_side = c->overlap_pairs && !c->overlap_sort;
+            hipStream_t pst = pairs_on_side ? c->side : st;
+            if (pairs_on_side) {   // everything the kernel reads is in place once the main stream gets here
+                HIPCHK(c, hipEventRecord(c->ev_pairs_go, st));
+                HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_pairs_go, 0));
+                side.active = true;
+                launch_fill_u32(c->side, c->d_status_side, ST_WORDS, 0);
+                pa.status = c->d_status_side;
+            }
             {
-                Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0);
+                Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0, pst, true);
                 int max_rows = 0, min_rows = 1 << 30;
                 for (int t = wp.t0; t < wp.t1; ++t)
                     if (task_pair_ok(c, B, t, K)) {
@@ -1362,13 +1386,31 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                         max_rows = std::max(max_rows, r);
                         min_rows = std::min(min_rows, r);
                     }
-                launch_pair_count(st, pa, Tw, max_tf, max_rows, min_rows, c->pair_tile_rows);
+                launch_pair_count(pst, pa, Tw, max_tf, max_rows, min_rows, c->pair_tile_rows);
             }
-            u32 hs[ST_WORDS];
-            if ((rc = read_status(c, hs))) return rc;
-            if (hs[ST_PAIR_OVF]) any_sparse = true;   // some task's flag was cleared on the device
+            if (pairs_on_side) {
+                HIPCHK(c, hipEventRecord(c->ev_pairs, c->side));
+            } else {
+                u32 hs[ST_WORDS];
+                if ((rc = read_status(c, hs))) return rc;
+                if (hs[ST_PAIR_OVF]) any_sparse = true;   // some task's flag was cleared on the device
+            }
         }
-        if (c->row_path == 2 && any_sparse && adapt)
+        // joins the counting on the side stream: the host learns whether a task fell back to the sparse kernel, the main
+        // stream waits for the matrices (called before the first row hop, which is their first reader)
+        auto join_pairs = [&]() -> int {
+            if (!pairs_on_side) return GM_OK;
+            pairs_on_side = false;
+            u32 hs[ST_WORDS];
+            HIPCHK(c, hipMemcpyAsync(hs, c->d_status_side, ST_WORDS * sizeof(u32), hipMemcpyDeviceToHost, c->side));
+            HIPCHK(c, hipStreamSynchronize(c->side));
+            HIPCHK(c, hipStreamWaitEvent(st, c->ev_pairs, 0));
+            if (hs[ST_PAIR_OVF]) any_sparse = true;
+            if (c->row_path == 2 && any_sparse && adapt)
+                return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a task, count, bag or (task, field) exceeds its limits");
+            return GM_OK;
+        };
+        if (!pairs_on_side && c->row_path == 2 && any_sparse && adapt)
             return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a task, count, bag or (task, field) exceeds its limits");
         const int n_tf = Tw * F;
         const int32_t* rows_s = b.prow_s + wp.s0;
@@ -1526,6 +1568,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
             Act Xn;  // support input of step k+1
             if (more) Xn = second ? w.steps[k + 1].X : w.Xs_scratch;
             if (F > 0 && adapt) {
+                if ((rc = join_pairs())) return rc;
                 float* xs_next = nullptr;
                 if (more) {
                     xs_next = bf ? w.Xs0 : Xn.f;  // bf16: the fp32 master is updated in place
@@ -1554,6 +1597,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                 w.steps[k].wL_stride = c->ld[L - 1];
             }
 
+        if ((rc = join_pairs())) return rc;   // (no inner step took a row hop)
         // outer forward/backward on the query set with the adapted parameters
         if (bf && K > 0) launch_copy_tail(st, (F > 0 && adapt) ? FD : 0, w.Xq0, d.Pq, nullptr, ld0, Xq.b);
         // gradient w.r.t. the pooled inputs: the wave's rows of the batch-wide buffer, or the wave's own buffer

@@ -536,6 +536,39 @@ def test_sort_on_the_side_stream_gives_the_same_result(gm, shape):
     ctx.close()
 
 
+@pytest.mark.parametrize("waves", [1, 3], ids=["one_wave", "several_waves"])
+def test_pair_counting_on_the_side_stream_gives_the_same_result(gm, waves):
+    """gm_configure("overlap_pairs", 1): the pair-count matrices are counted on a second stream beside the prefetch and
+    the first forward / backward pass and joined before the first row hop.  Same bits as without, with one wave and
+    with several; the overflow fall-back (counts above a byte, found by the kernel on the side stream) still works."""
+    cfg = SMALL.with_(n_tasks=8)
+    sup, qry, params = _inputs(cfg)
+    probe = gm.from_config(cfg, workspace_bytes=2 << 30)
+    need = probe.workspace_bytes(8, sup.n_samples, qry.n_samples, sup.nnz, qry.nnz, 2, 2)
+    probe.close()
+    ctx = gm.from_config(cfg, workspace_bytes=(2 << 30) if waves == 1 else int(need * 0.5))
+    dev = ctx.device
+    ds, dq, dp = _to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev)
+    res = []
+    for on in (0, 1, 1):
+        ctx.configure("overlap_pairs", on)
+        out = ctx.meta_step(ds, dq, dp, cfg.inner_lr, 2, 2)
+        n = int(out["n_emb_rows"].item())
+        res.append((out["loss"].clone(), out["dW"][0].clone(), out["emb_grad"][:n].clone(), out["emb_rows"][:n].clone()))
+    for r in res[1:]:
+        for a, b in zip(res[0], r):
+            assert torch.equal(a, b)
+    ctx.close()
+    if waves == 1:
+        cfg = SMALL.with_(n_tasks=3, n_support=40, n_query=30, n_fields=4, emb_dim=32, rows_per_field=1, bag_max=24,
+                          layer_dims=(4 * 32 + 13, 32, 16, 1), inner_lr=0.01)
+        sup, qry, params = _inputs(cfg)
+        ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+        ctx.configure("overlap_pairs", 1)
+        _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_FP32, "pair overflow found on the side stream")
+        ctx.close()
+
+
 def test_pair_counts_above_a_byte_fall_back(gm):
     """One row per table: every pair of bags shares all its lookups, so counts reach bag_i * bag_j > 255.  The default
     choice must fall back to the sparse kernel (and still match the oracle); the forced pair path must refuse."""
