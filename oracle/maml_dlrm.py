@@ -43,6 +43,20 @@ wherever a pre-activation sits within rounding distance of zero.  Both sides
 must take that decision in the same precision; the rounding below is the only
 place where the oracle departs from float64, and q = identity recovers it.
 
+ReLU decisions given from outside (relu_masks).  The mode above rounds operands
+throughout, so a comparison against it cannot tell whether the rounding points
+themselves are right.  relu_masks="bf16" therefore separates the two things:
+the task is first run once in the bf16-operand mode only to record the ReLU
+gates of every forward pass (each inner step's support pass, the query pass);
+then ALL arithmetic runs in float64, with no rounding anywhere, using those
+gates as given 0/1 factors (a_l = z_l * m_l; the backward and tangent passes
+gate with the same m_l).  This is the reference a reduced-precision path is
+held against at the bf16 tolerance: the yes/no decisions are taken where such a
+path takes them, and every rounding it makes has to fit inside the tolerance by
+itself.  relu_masks may also be an explicit list of masks per forward pass
+(tests freeze the gates that way and take central differences of the
+frozen-gate objective).
+
 Pins (tests/test_oracle_*.py): central finite differences of the loss and of
 the meta-objective, K=0 and alpha=0 identities, the K=1 relation
 order2 = (I - alpha*H) order1 with H pinned by differences of the gradient,
@@ -137,23 +151,28 @@ def _w(W, l, q):
     return q(W[l]) if l < len(W) - 1 else W[l]
 
 
-def forward(x: np.ndarray, W: List[np.ndarray], b: List[np.ndarray], q=_identity):
-    """a_0 = x; z_l = a_{l-1} W_l + b_l; a_l = relu(z_l) for l < L.  Returns ([a_0..a_{L-1}], z_L)."""
+def forward(x: np.ndarray, W: List[np.ndarray], b: List[np.ndarray], q=_identity, masks=None):
+    """a_0 = x; z_l = a_{l-1} W_l + b_l; a_l = z_l * m_l for l < L, with m_l = [z_l > 0] (ReLU) unless the
+    gates are given (masks[l-1] for hidden layer l).  Returns ([a_0..a_{L-1}], z_L, [m_1..m_{L-1}])."""
     acts = [q(x)]
+    used = []
     L = len(W)
     for l in range(L):
         z = acts[-1] @ _w(W, l, q) + b[l]
         if l < L - 1:
-            acts.append(q(np.where(z > 0.0, z, 0.0)))
-    return acts, z[:, 0]
+            m = (z > 0.0) if masks is None else np.asarray(masks[l], dtype=bool)
+            used.append(m)
+            acts.append(q(np.where(m, z, 0.0)))
+    return acts, z[:, 0], used
 
 
 def set_loss(z: np.ndarray, y: np.ndarray) -> float:
     return float(np.mean(bce_with_logits(z, y))) if len(y) else 0.0
 
 
-def backward(acts, z, y, W, q=_identity):
-    """Gradient of the mean BCE w.r.t. W_l, b_l and the input x.  Also returns the deltas."""
+def backward(acts, z, y, W, masks, q=_identity):
+    """Gradient of the mean BCE w.r.t. W_l, b_l and the input x (masks: the gates of the forward pass).
+    Also returns the deltas."""
     n = len(y)
     L = len(W)
     delta = ((sigmoid(z) - y) / max(n, 1))[:, None]
@@ -164,11 +183,11 @@ def backward(acts, z, y, W, q=_identity):
         db[l] = delta.sum(axis=0)
         da = delta @ _w(W, l, q).T
         if l > 0:
-            delta = q(da * (acts[l] > 0.0))
+            delta = q(da * masks[l - 1])
     return dW, db, da, deltas
 
 
-def hvp(acts, z, y, W, deltas, vW, vb, vx, q=_identity):
+def hvp(acts, z, y, W, deltas, masks, vW, vb, vx, q=_identity):
     """Hessian of the mean BCE (w.r.t. W, b and the input x) times (vW, vb, vx).
 
     Tangent (forward) pass through the forward AND the backward pass of the
@@ -182,7 +201,7 @@ def hvp(acts, z, y, W, deltas, vW, vb, vx, q=_identity):
     for l in range(L):
         tz = ta[-1] @ _w(W, l, q) + acts[l] @ _w(vW, l, q) + vb[l]
         if l < L - 1:
-            ta.append(q(tz * (acts[l + 1] > 0.0)))
+            ta.append(q(tz * masks[l]))
     tdelta = (sg * (1.0 - sg) * tz[:, 0] / max(n, 1))[:, None]
     hW, hb = [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
@@ -190,7 +209,7 @@ def hvp(acts, z, y, W, deltas, vW, vb, vx, q=_identity):
         hb[l] = tdelta.sum(axis=0)
         tda = tdelta @ _w(W, l, q).T + deltas[l] @ _w(vW, l, q).T
         if l > 0:
-            tdelta = q(tda * (acts[l] > 0.0))
+            tdelta = q(tda * masks[l - 1])
     return hW, hb, tda
 
 
@@ -198,7 +217,8 @@ def hvp(acts, z, y, W, deltas, vW, vb, vx, q=_identity):
 # one task
 # --------------------------------------------------------------------------
 def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int, order: int,
-                   full_table: bool = False, operand: str = "fp64", adapt_rows: bool = True):
+                   full_table: bool = False, operand: str = "fp64", adapt_rows: bool = True,
+                   relu_masks=None, masks_out: Optional[list] = None):
     """MAML for task t.  Returns (L^Query, gW, gb, rows, gxi[rows]) w.r.t. the META parameters.
 
     adapt_rows=False is the variant that adapts the dense parameters only (the way the paper's framework
@@ -209,10 +229,21 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
 
     full_table=True copies the whole table into the task (brute force: phi_0 is
     all of xi); the default keeps only the rows the task looks up.  Both must agree.
+
+    relu_masks: None -- every forward pass decides its own ReLU gates (z > 0); "bf16" -- the gates are those of a
+    run of the task with operand="bf16", recorded first, while the arithmetic itself follows `operand`; a list of
+    K + 1 entries (the K support passes, then the query pass), each the list of hidden
+    layers' boolean masks -- gates given from outside.  masks_out, if a list, receives the gates used, in that form.
     """
     F, D = model.n_fields, model.emb_dim
     FD = F * D
     q = quantizer(operand)
+    if isinstance(relu_masks, str):
+        if relu_masks != "bf16":
+            raise ValueError("relu_masks must be None, 'bf16' or a list of masks")
+        recorded: list = []
+        task_meta_grad(model, params, sup, qry, t, alpha, K, 1, full_table, "bf16", adapt_rows, None, recorded)
+        relu_masks = recorded
     s_lo, s_hi = int(sup["task_offsets"][t]), int(sup["task_offsets"][t + 1])
     q_lo, q_hi = int(qry["task_offsets"][t]), int(qry["task_offsets"][t + 1])
     ns, nq = s_hi - s_lo, q_hi - q_lo
@@ -239,13 +270,20 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
         np.add.at(g, loc, dx[:, :FD].reshape(-1, D)[bag])
         return g
 
+    def gated_forward(x, W, b, i):
+        """Forward pass number i of the task (support passes 0..K-1, query pass K) with its gates."""
+        acts, z, used = forward(x, W, b, q, None if relu_masks is None else relu_masks[i])
+        if masks_out is not None:
+            masks_out.append(used)
+        return acts, z, used
+
     # inner loop on the support set
     tape = []
-    for _ in range(K):
+    for k in range(K):
         x = np.concatenate([pool(model, E, loc_s, bag_s, ns), dense_s], axis=1)
-        acts, z = forward(x, W, b, q)
-        dW, db, dx, deltas = backward(acts, z, ys, W, q)
-        tape.append((acts, z, W, deltas))
+        acts, z, masks = gated_forward(x, W, b, k)
+        dW, db, dx, deltas = backward(acts, z, ys, W, masks, q)
+        tape.append((acts, z, W, deltas, masks))
         if adapt_rows:
             E = E - alpha * rows_grad(dx, loc_s, bag_s)
         W = [w - alpha * g for w, g in zip(W, dW)]
@@ -253,19 +291,19 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
 
     # outer forward/backward on the query set with the adapted parameters
     xq = np.concatenate([pool(model, E, loc_q, bag_q, nq), dense_q], axis=1)
-    acts, z = forward(xq, W, b, q)
+    acts, z, masks = gated_forward(xq, W, b, K)
     loss_q = set_loss(z, yq)
-    vW, vb, dx, _ = backward(acts, z, yq, W, q)
+    vW, vb, dx, _ = backward(acts, z, yq, W, masks, q)
     vE = rows_grad(dx, loc_q, bag_q)
 
     # chain back through the inner steps: v_k = v_{k+1} - alpha * H_k v_{k+1}
     if order == 2:
-        for acts_k, z_k, W_k, deltas_k in reversed(tape):
+        for acts_k, z_k, W_k, deltas_k, masks_k in reversed(tape):
             if adapt_rows:
                 vx = np.concatenate([pool(model, vE, loc_s, bag_s, ns), np.zeros_like(dense_s)], axis=1)
             else:   # xi is not a state of the inner loop: no direction on the inputs
                 vx = np.zeros((ns, FD + dense_s.shape[1]))
-            hW, hb, hx = hvp(acts_k, z_k, ys, W_k, deltas_k, vW, vb, vx, q)
+            hW, hb, hx = hvp(acts_k, z_k, ys, W_k, deltas_k, masks_k, vW, vb, vx, q)
             hE = rows_grad(hx, loc_s, bag_s)
             vW = [v - alpha * h for v, h in zip(vW, hW)]
             vb = [v - alpha * h for v, h in zip(vb, hb)]
@@ -283,8 +321,11 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
 # --------------------------------------------------------------------------
 def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
               tasks: Optional[Sequence[int]] = None, full_table: bool = False, operand: str = "fp64",
-              adapt_rows: bool = True):
+              adapt_rows: bool = True, relu_masks=None, masks_out: Optional[dict] = None):
     """Sum of the per-task meta-gradients (Alg. 1, global back-propagation steps).
+
+    relu_masks: None, "bf16", or {task: list of masks per forward pass} (see task_meta_grad); masks_out, if a
+    dict, receives {task: gates used}.
 
     Returns dict(loss, task_loss[T], dW[l], db[l], emb_rows (ascending unique
     global rows looked up by any sample), emb_grad[len(emb_rows), D]).
@@ -297,8 +338,12 @@ def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
     task_loss = np.zeros(len(tasks))
     parts_rows, parts_grad = [], []
     for i, t in enumerate(tasks):
+        rec = [] if masks_out is not None else None
         lq, vW, vb, rows, vE = task_meta_grad(model, params, sup, qry, t, alpha, K, order, full_table, operand,
-                                              adapt_rows)
+                                              adapt_rows, relu_masks[t] if isinstance(relu_masks, dict) else relu_masks,
+                                              rec)
+        if masks_out is not None:
+            masks_out[t] = rec
         task_loss[i] = lq
         for l in range(L):
             gW[l] += vW[l]
@@ -317,14 +362,15 @@ def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
 
 
 def meta_train_step(model: Model, params, sup, qry, alpha: float, K: int, order: int, beta: float,
-                    operand: str = "fp64", adapt_rows: bool = True):
+                    operand: str = "fp64", adapt_rows: bool = True, relu_masks=None):
     """One whole iteration of Alg. 1 on one shard: the step above, then the two global back-propagation steps with
     the outer step size beta (plain SGD on the summed meta-gradient): theta <- theta - beta * sum_t grad_theta and,
     for every looked-up row, xi[row] <- xi[row] - beta * sum_t grad_xi[row].
 
     Returns (new params dict (float64 copies; the input is not modified), loss of the step before the update).
     """
-    r = meta_step(model, params, sup, qry, alpha, K, order, operand=operand, adapt_rows=adapt_rows)
+    r = meta_step(model, params, sup, qry, alpha, K, order, operand=operand, adapt_rows=adapt_rows,
+                  relu_masks=relu_masks)
     emb = np.array(params["emb"], dtype=np.float64, copy=True)
     emb[r["emb_rows"]] -= beta * r["emb_grad"]
     W = [np.asarray(w, dtype=np.float64) - beta * g for w, g in zip(params["W"], r["dW"])]

@@ -11,18 +11,18 @@ from tests.helpers import small_cfg
 from tests.test_oracle_pins import _fd_check
 
 
-def _drop_cross_term(acts, z, y, W, deltas, vW, vb, vx, q=None):
-    hW, hb, hx = _ORIG(acts, z, y, W, deltas, vW, vb, vx)
+def _drop_cross_term(acts, z, y, W, deltas, masks, vW, vb, vx, q=None):
+    hW, hb, hx = _ORIG(acts, z, y, W, deltas, masks, vW, vb, vx)
     return hW, hb, hx * 0.0 + (hx - deltas[0] @ vW[0].T)      # drop delta * vW^T at the input
 
 
-def _wrong_sign(acts, z, y, W, deltas, vW, vb, vx, q=None):
-    hW, hb, hx = _ORIG(acts, z, y, W, deltas, vW, vb, vx)
+def _wrong_sign(acts, z, y, W, deltas, masks, vW, vb, vx, q=None):
+    hW, hb, hx = _ORIG(acts, z, y, W, deltas, masks, vW, vb, vx)
     return [-h for h in hW], hb, hx
 
 
-def _no_bias_tangent(acts, z, y, W, deltas, vW, vb, vx, q=None):
-    return _ORIG(acts, z, y, W, deltas, vW, [np.zeros_like(v) for v in vb], vx)
+def _no_bias_tangent(acts, z, y, W, deltas, masks, vW, vb, vx, q=None):
+    return _ORIG(acts, z, y, W, deltas, masks, vW, [np.zeros_like(v) for v in vb], vx)
 
 
 _ORIG = O.hvp
@@ -51,8 +51,8 @@ def test_transposed_pool_is_caught(monkeypatch):
 def test_dense_only_chain_without_its_cross_term_is_caught(monkeypatch):
     """adapt_rows=False: dropping the path from the adapted theta back to the embeddings (the input part of the
     Hessian-vector product) must break the finite-difference pin of that variant."""
-    def no_input_part(acts, z, y, W, deltas, vW, vb, vx, q=None):
-        hW, hb, hx = _ORIG(acts, z, y, W, deltas, vW, vb, vx)
+    def no_input_part(acts, z, y, W, deltas, masks, vW, vb, vx, q=None):
+        hW, hb, hx = _ORIG(acts, z, y, W, deltas, masks, vW, vb, vx)
         return hW, hb, hx * 0.0
     monkeypatch.setattr(O, "hvp", no_input_part)
     with pytest.raises(AssertionError):
@@ -119,3 +119,19 @@ def test_grouping_with_a_wrong_split_or_order_is_caught(monkeypatch):
     monkeypatch.setattr(O, "group_batch", reversed_inside)
     with pytest.raises(AssertionError):
         G.test_grouping_recovers_the_generators_sets()
+
+
+@pytest.mark.parametrize("where", ["backward", "hvp"])
+def test_given_gates_ignored_by_a_pass_is_caught(monkeypatch, where):
+    """A backward or tangent pass that re-derives its gates from the activations instead of applying the given ones
+    must break the frozen-gate finite-difference pin."""
+    from tests.test_oracle_pins import test_frozen_gate_meta_gradient_by_central_differences as pin
+    if where == "backward":
+        orig = O.backward
+        monkeypatch.setattr(O, "backward", lambda acts, z, y, W, masks, q=O._identity:
+                            orig(acts, z, y, W, [a > 0.0 for a in acts[1:]], q))
+    else:
+        monkeypatch.setattr(O, "hvp", lambda acts, z, y, W, deltas, masks, vW, vb, vx, q=O._identity:
+                            _ORIG(acts, z, y, W, deltas, [a > 0.0 for a in acts[1:]], vW, vb, vx, q))
+    with pytest.raises(AssertionError):
+        pin(2)

@@ -66,7 +66,7 @@ def test_forward_loss_against_python_loops():
     st = dict(task_offsets=np.array([0, 3]), bag_offsets=np.array(offs, dtype=np.int64),
               indices=np.array(indices, dtype=np.int32), dense=dense, labels=y)
     x = O.gather_pool(model, emb, st)
-    acts, z = O.forward(x, W, b)
+    acts, z, _ = O.forward(x, W, b)
     got = O.set_loss(z, y)
     # scalar loops
     total = 0.0
@@ -512,3 +512,86 @@ def test_dense_only_adaptation_differs_from_the_full_one_and_agrees_without_spar
     # first order: support-only rows get exactly nothing either way, but the query side sees unadapted rows
     d1 = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 1, adapt_rows=False)
     assert abs(d1["loss"] - dense["loss"]) == 0.0
+
+
+# ---------------------------------------------------------------- ReLU gates given from outside (relu_masks)
+def _flipped_gates(model, params, sup, qry, alpha, K, share, seed):
+    """The gates of a plain run with a share of them flipped at random: gates that no forward pass would choose."""
+    rec = {}
+    O.meta_step(model, params, sup, qry, alpha, K, 1, masks_out=rec)
+    rng = np.random.default_rng(seed)
+    return {t: [[np.logical_xor(m, rng.random(m.shape) < share) for m in one_pass] for one_pass in passes]
+            for t, passes in rec.items()}
+
+
+def test_recorded_gates_given_back_reproduce_the_plain_run():
+    cfg = small_cfg(inner_lr=0.3)
+    model, params, sup, qry = oracle_inputs(cfg, emb_std=0.3)
+    rec = {}
+    a = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 2, masks_out=rec)
+    assert sorted(rec) == [0, 1, 2] and all(len(p) == 3 and len(p[0]) == model.n_layers - 1 for p in rec.values())
+    b = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 2, relu_masks=rec)
+    assert a["loss"] == b["loss"] and np.array_equal(a["emb_grad"], b["emb_grad"])
+    assert all(np.array_equal(x, y) for x, y in zip(a["dW"] + a["db"], b["dW"] + b["db"]))
+
+
+@pytest.mark.parametrize("K", [1, 2])
+def test_frozen_gate_meta_gradient_by_central_differences(K):
+    """With the gates given (here: a plain run's gates with 15 % flipped, so that they really come from outside),
+    the step must be the exact gradient of the frozen-gate objective: a_l = z_l * m_l is smooth in the parameters, so
+    central differences of that objective pin every place where the backward and tangent passes apply a gate."""
+    cfg = small_cfg(inner_lr=0.3)
+    model, params, sup, qry = oracle_inputs(cfg, emb_std=0.3)
+    params = {k: ([a.astype(np.float64) for a in v] if isinstance(v, list) else v.astype(np.float64))
+              for k, v in params.items()}
+    alpha = cfg.inner_lr
+    gates = _flipped_gates(model, params, sup, qry, alpha, K, 0.15, 5)
+    out = O.meta_step(model, params, sup, qry, alpha, K, 2, relu_masks=gates)
+    plain = O.meta_step(model, params, sup, qry, alpha, K, 2)
+    assert max(rel_err(out["dW"][0], plain["dW"][0])) > 0.05, "the flipped gates must matter"
+    gfull = _full_grad(model, out)
+    rng = np.random.default_rng(2)
+    checks = []
+    for l in range(model.n_layers):
+        for _ in range(10):
+            i = tuple(rng.integers(0, s) for s in params["W"][l].shape)
+            checks.append((params["W"][l], i, out["dW"][l][i]))
+        j = (int(rng.integers(0, params["b"][l].shape[0])),)
+        checks.append((params["b"][l], j, out["db"][l][j]))
+    for r in rng.choice(out["emb_rows"], size=25, replace=False):
+        c = int(rng.integers(0, model.emb_dim))
+        checks.append((params["emb"], (int(r), c), gfull[int(r), c]))
+    scale = max(np.abs(gfull).max(), max(np.abs(g).max() for g in out["dW"]))
+    eps, worst = 1e-5, 0.0
+    for arr, i, g in checks:
+        old = arr[i]
+        arr[i] = old + eps
+        fp = O.meta_step(model, params, sup, qry, alpha, K, 1, relu_masks=gates)["loss"]
+        arr[i] = old - eps
+        fm = O.meta_step(model, params, sup, qry, alpha, K, 1, relu_masks=gates)["loss"]
+        arr[i] = old
+        worst = max(worst, abs((fp - fm) / (2 * eps) - g) / scale)
+    assert worst < 2e-6, worst
+
+
+def test_bf16_gates_with_float64_arithmetic_sit_between_the_two_modes():
+    """relu_masks="bf16": float64 arithmetic on the gates of the bf16-operand run.  On configs[1]'s model shape with
+    small ragged tasks: against the bf16-operand mode only rounding is left (well inside the bf16 tolerance of 2e-2 on
+    every output), while against the plain float64 run whole gradient terms differ (gates that fall differently) --
+    which is why a reduced-precision path is held against THIS reference and not against the plain one."""
+    from synth import SMALL, make_batch, make_params
+    cfg = SMALL.with_(n_tasks=6, n_support=50, n_query=37, mlp_dtype=1, rows_per_field=5000, inner_lr=0.05)
+    sup, qry = make_batch(cfg, 0, "cpu")
+    params, model = make_params(cfg, "cpu").numpy(), oracle_model(cfg)
+    sup, qry = sup.numpy(), qry.numpy()
+    rounded = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 2, operand="bf16")
+    gated = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 2, relu_masks="bf16")
+    plain = O.meta_step(model, params, sup, qry, cfg.inner_lr, 2, 2)
+
+    def dist(a, b):
+        e = [abs(a["loss"] - b["loss"]) / abs(b["loss"]), max(rel_err(a["emb_grad"], b["emb_grad"]))]
+        e += [max(rel_err(x, y)) for x, y in zip(a["dW"] + a["db"], b["dW"] + b["db"])]
+        return max(e)
+    assert dist(rounded, gated) < 1e-2, dist(rounded, gated)
+    assert dist(gated, plain) > 2e-2, dist(gated, plain)
+    assert abs(gated["loss"] - plain["loss"]) / plain["loss"] < 1e-4     # the loss itself hardly feels a gate near zero
