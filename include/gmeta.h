@@ -116,6 +116,21 @@ int gm_meta_step(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_s
                  const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
                  float* loss, gm_grads* out);
 
+/* gm_meta_step for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): same arguments, same results, but every intermediate buffer lives in a static
+ * device array of GM_STATIC_SCRATCH_MIB MiB that is part of the library's code object (each GPU the library runs on
+ * holds its copy until the process ends) instead of the context's workspace, and the call allocates and frees
+ * nothing on the device.  The caller still passes inputs and outputs; ctx must have been created before (gm_create
+ * is where the array is located on the device).  Tasks run in waves as in gm_meta_step when the scratch does not
+ * hold them all at once; a call whose batch-level buffers plus one task do not fit returns GM_ERR_WORKSPACE and says
+ * so.  All calls on one GPU -- of any context -- share that GPU's array: calls that overlap in time on one GPU race,
+ * and nothing in it survives from one call to the next (every call initialises what it reads).  Kernel timing
+ * (gm_profile) is suspended for the call. */
+#define GM_STATIC_SCRATCH_MIB 64
+int gm_meta_step_static(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_set* query,
+                        const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
+                        float* loss, gm_grads* out);
+
 /* One whole iteration of Alg. 1 on one shard: gm_meta_step, then the two global back-propagation steps
  * applied with the outer step size beta (plain SGD on the summed meta-gradient), IN PLACE:
  *   W_l -= outer_lr * dW_l,  b_l -= outer_lr * db_l,  emb[row, :] -= outer_lr * grad[row, :] for every row

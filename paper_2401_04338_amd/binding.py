@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libgmeta.so")
 
 GM_OK, GM_ERR_ARG, GM_ERR_INDEX, GM_ERR_CAPACITY, GM_ERR_WORKSPACE, GM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ["gm_create", "gm_destroy", "gm_last_error", "gm_workspace_bytes", "gm_meta_step",
+EXPORTS = ["gm_create", "gm_destroy", "gm_last_error", "gm_workspace_bytes", "gm_meta_step", "gm_meta_step_static",
            "gm_meta_train_step", "gm_group_batch", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report"]
 
 
@@ -87,6 +87,8 @@ def load_library() -> C.CDLL:
     lib.gm_meta_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set),
                                  C.POINTER(gm_params), C.c_float, C.c_int32, C.c_int32, C.c_void_p,
                                  C.POINTER(gm_grads)]
+    lib.gm_meta_step_static.restype = C.c_int
+    lib.gm_meta_step_static.argtypes = lib.gm_meta_step.argtypes
     lib.gm_scatter_add.restype = C.c_int
     lib.gm_scatter_add.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float]
     lib.gm_gather_pool.restype = C.c_int
@@ -185,10 +187,11 @@ class GMeta:
 
     def meta_step(self, support, query, params, inner_lr: float, inner_steps: int, order: int,
                   out: Optional[Dict[str, object]] = None, emb_rows_capacity: Optional[int] = None,
-                  emb_grad_table: Optional[torch.Tensor] = None):
+                  emb_grad_table: Optional[torch.Tensor] = None, static_scratch: bool = False):
         """gm_meta_step.  support/query: SetData-like; params: object with emb, W[], b[] device tensors.
         emb_grad_table: a float32 device tensor shaped like params.emb that the sparse gradient is added to
-        (then no row list is produced)."""
+        (then no row list is produced).  static_scratch: call gm_meta_step_static instead (the library's static
+        scratch array in place of the context's workspace; pass `out` to keep the call itself free of allocations)."""
         n_tasks = len(support.task_offsets) - 1
         if emb_grad_table is not None:
             if (emb_grad_table.dtype != torch.float32 or not emb_grad_table.is_contiguous()
@@ -212,8 +215,9 @@ class GMeta:
         gs = gm_grads(dWp, dbp, _ptr(out["emb_rows"]), _ptr(out["emb_grad"]), _ptr(out["n_emb_rows"]),
                       int(out["capacity"]), _ptr(out["task_loss"]),
                       _ptr(emb_grad_table) if emb_grad_table is not None else None)
-        rc = self.lib.gm_meta_step(self._ctx, n_tasks, C.byref(ss), C.byref(qs), C.byref(ps), float(inner_lr),
-                                   int(inner_steps), int(order), _ptr(out["loss"]), C.byref(gs))
+        entry = self.lib.gm_meta_step_static if static_scratch else self.lib.gm_meta_step
+        rc = entry(self._ctx, n_tasks, C.byref(ss), C.byref(qs), C.byref(ps), float(inner_lr),
+                   int(inner_steps), int(order), _ptr(out["loss"]), C.byref(gs))
         self._check(rc)
         return out
 

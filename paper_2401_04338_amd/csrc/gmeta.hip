@@ -82,6 +82,7 @@ struct gm_ctx {
     int adapt_rows = 1;   // 0: the inner loop adapts the dense parameters only (embedding rows are read, not updated)
     int gemm_tile_n = 0;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
+    char* static_scratch = nullptr;   // this device's copy of the static scratch array (gm_meta_step_static)
     // optional kernel timing
     bool prof_on = false;
     std::vector<ProfPending> prof_pending;
@@ -89,6 +90,14 @@ struct gm_ctx {
     std::map<std::string, ProfEntry> prof;
     std::string prof_text;
 };
+
+// Scratch of gm_meta_step_static: one array per GPU, part of the loaded code object (held until the process ends).
+// Host code never passes the array's name to a kernel: the device address is looked up once per device at gm_create
+// (hipGetSymbolAddress) and only that pointer is used.
+#define GM_STATIC_SCRATCH_BYTES ((size_t)GM_STATIC_SCRATCH_MIB << 20)
+static __device__ __align__(256) unsigned char scratch[GM_STATIC_SCRATCH_BYTES];
+enum { GM_MAX_DEVICES = 64 };
+static char* g_scratch_ptr[GM_MAX_DEVICES];   // device address of `scratch` on each GPU (null: not looked up yet)
 
 static int fail(gm_ctx* c, int code, const char* fmt, ...) {
     char buf[512];
@@ -470,6 +479,13 @@ extern "C" int gm_create(gm_ctx** out, const gm_model_desc* model, int device, v
     c->device = device;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
     HIPCHK(c, hipSetDevice(device));
+    if (device < 0 || device >= GM_MAX_DEVICES) return fail(c, GM_ERR_ARG, "device must be in [0, %d)", (int)GM_MAX_DEVICES);
+    if (!g_scratch_ptr[device]) {   // once per device, with that device current: every GPU holds its own copy
+        void* p = nullptr;
+        HIPCHK(c, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[device] = static_cast<char*>(p);
+    }
+    c->static_scratch = g_scratch_ptr[device];
     c->ws_bytes = std::max<size_t>(workspace_bytes, 1 << 20);
     HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&c->ws), c->ws_bytes));
     Arena ar;
@@ -1712,6 +1728,33 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         return fail(c, GM_ERR_CAPACITY, "emb_rows_capacity %lld is smaller than the %u rows touched", (long long)capacity,
                     hs[ST_NROWS]);
     return GM_OK;
+}
+
+// The same step with every intermediate buffer in the static scratch array instead of the context's workspace: no
+// device memory is allocated or freed anywhere below (the persistent words -- table bases, status -- stay where
+// gm_create put them).  Kernel timing is off for the call: its events would have to be created.
+extern "C" int gm_meta_step_static(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set* qry, const gm_params* params,
+                                   float alpha, int32_t K, int32_t order, float* loss, gm_grads* out) {
+    if (!c) return GM_ERR_ARG;
+    if (!c->static_scratch) return fail(c, GM_ERR_HIP, "the static scratch array was not located at gm_create");
+    char* const ws = c->ws;
+    const size_t ws_bytes = c->ws_bytes, persistent = c->persistent;
+    const bool prof_on = c->prof_on;
+    c->ws = c->static_scratch;
+    c->ws_bytes = GM_STATIC_SCRATCH_BYTES;
+    c->persistent = 0;
+    c->prof_on = false;
+    const int rc = gm_meta_step(c, T, sup, qry, params, alpha, K, order, loss, out);
+    c->ws = ws;
+    c->ws_bytes = ws_bytes;
+    c->persistent = persistent;
+    c->prof_on = prof_on;
+    if (rc == GM_ERR_WORKSPACE) {
+        const std::string why = c->err;
+        return fail(c, GM_ERR_WORKSPACE, "the call does not fit the %d MiB of static scratch of gm_meta_step_static (%s); "
+                    "use gm_meta_step with a workspace", (int)GM_STATIC_SCRATCH_MIB, why.c_str());
+    }
+    return rc;
 }
 
 extern "C" int gm_meta_train_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set* qry, const gm_params* params,
