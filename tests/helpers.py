@@ -44,32 +44,12 @@ def rel_err(a, b):
 
 
 def compact_task(cfg: Config, sup_t, qry_t, emb_dev, W, b):
-    """One task's oracle inputs over only the table rows the task looks up (the oracle's result depends on no other
-    row): returns (Model with per-field row counts, params dict, sup dict, qry dict, global_rows) where
-    global_rows[i] is the full-size table row behind compact row i.  Lets the oracle check a task of a configuration
-    whose tables do not fit host-side copies.  Pure re-indexing: none of the method's arithmetic."""
-    import torch
-    F, R = cfg.n_fields, cfg.rows_per_field
-    sd, qd = sup_t.numpy(), qry_t.numpy()
-
-    def fields_of(d):
-        lens = d["bag_offsets"][1:] - d["bag_offsets"][:-1]
-        return np.repeat(np.arange(lens.size, dtype=np.int64) % F, lens)
-
-    fs, fq = fields_of(sd), fields_of(qd)
-    counts, rows_all, new_s, new_q = [], [], np.empty_like(sd["indices"]), np.empty_like(qd["indices"])
-    for f in range(F):
-        ms, mq = fs == f, fq == f
-        u = np.unique(np.concatenate([sd["indices"][ms], qd["indices"][mq]]).astype(np.int64))
-        if u.size == 0:
-            u = np.zeros(1, dtype=np.int64)
-        new_s[ms] = np.searchsorted(u, sd["indices"][ms]).astype(new_s.dtype)
-        new_q[mq] = np.searchsorted(u, qd["indices"][mq]).astype(new_q.dtype)
-        counts.append(int(u.size))
-        rows_all.append(u + f * R)
-    global_rows = np.concatenate(rows_all)
-    emb = emb_dev[torch.from_numpy(global_rows).to(emb_dev.device)].cpu().numpy()
-    sd["indices"], qd["indices"] = new_s, new_q
+    """Oracle inputs of a task subset over only the table rows it looks up (synth.compact_tasks does the re-indexing):
+    returns (Model with per-field row counts, params dict, sup dict, qry dict, global_rows) where global_rows[i] is the
+    full-size table row behind compact row i.  Lets the oracle check tasks of a configuration whose tables do not fit
+    host-side copies."""
+    from synth import compact_tasks
+    counts, emb, sd, qd, global_rows = compact_tasks(cfg, sup_t, qry_t, emb_dev)
     model = Model(rows_per_field=counts, emb_dim=cfg.emb_dim, n_dense=cfg.n_dense, layer_dims=list(cfg.layer_dims))
     params = dict(emb=emb, W=[w.cpu().numpy() for w in W], b=[x.cpu().numpy() for x in b])
     return model, params, sd, qd, global_rows

@@ -65,13 +65,14 @@ def _compare_step(cfg, ctx, sup, qry, params, K, order, tol, label, operand="fp6
     model = model or oracle_model(cfg)
     p_np, s_np, q_np = params.numpy(), sup.numpy(), qry.numpy()
     out = ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, K, order)
-    ref = O.meta_step(model, p_np, s_np, q_np, cfg.inner_lr, K, order, operand=operand, adapt_rows=adapt_rows)
+    rec = {} if operand != "fp64" else None
+    ref = O.meta_step(model, p_np, s_np, q_np, cfg.inner_lr, K, order, operand=operand, adapt_rows=adapt_rows, masks_out=rec)
     n = int(out["n_emb_rows"].item())
     assert n == len(ref["emb_rows"]), label
     assert np.array_equal(out["emb_rows"][:n].cpu().numpy(), ref["emb_rows"]), label
     T = len(sup.task_offsets) - 1
     if operand != "fp64":
-        gated = O.meta_step(model, p_np, s_np, q_np, cfg.inner_lr, K, order, relu_masks="bf16", adapt_rows=adapt_rows)
+        gated = O.meta_step(model, p_np, s_np, q_np, cfg.inner_lr, K, order, relu_masks=rec, adapt_rows=adapt_rows)
         eg = _errors(out, gated, n, T)
         print(label, "vs float64 arithmetic on bf16 gates:", {k: f"{v:.2e}" for k, v in eg.items()}, flush=True)
         for k, v in eg.items():
@@ -879,3 +880,101 @@ def test_large_config_full_size_sampled_tasks(gm):
         assert np.abs(got).sum() > 0
     del table, params, sup, qry
     torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------- the three large configurations: every output on a task subset at
+# full table size
+def _subset_case(name):
+    from synth import COLDSTART, LARGE, MEDIUM
+    from synth.generate import task_sizes
+    if name == "c3":
+        return MEDIUM, [0, 31, 64, 101, 128, 170, 201, 255, 256, 300, 333, 384, 420, 457, 500, 511], 6
+    if name == "c4":
+        sizes = task_sizes(COLDSTART)[:, 0]
+        by_size = np.argsort(sizes, kind="stable")
+        # stratified over the size distribution: the smallest and the largest task, the tasks nearest to 512 samples per
+        # set from both sides (one per row path), and quantiles in between
+        above = [int(t) for t in by_size if sizes[t] > 512]
+        below = [int(t) for t in by_size if sizes[t] <= 512]
+        picks = {below[0], below[-1], above[0], above[-1]}
+        for q in np.linspace(0.05, 0.95, 12):
+            picks.add(int(by_size[int(q * (len(by_size) - 1))]))
+        tasks = sorted(picks)
+        assert len(tasks) >= 16 or len(tasks) == len(picks)
+        return COLDSTART, tasks, 6
+    return LARGE, [0, 2741, 5555, 8191], 2
+
+
+@pytest.mark.parametrize("name", ["c3", "c4", "c5"])
+def test_large_configs_task_subset_at_full_table_size(gm, name):
+    """configs[2], [3], [4]: a GPU run restricted to a subset of the configuration's tasks -- the full batch's values for
+    those tasks (the generator's streams are per task), tables at FULL size, the launch configuration bench.py uses,
+    several waves of tasks -- against the oracle on the same subset (which sees the rows the subset looks up,
+    re-indexed): loss, every task's loss, every dW and db, the listed rows and the whole sparse gradient.  c3: 16
+    tasks; c4: the smallest and the largest task, both row paths, quantiles of the size distribution; c5: 4 tasks."""
+    cfg, tasks, per_wave = _subset_case(name)
+    dev = torch.device("cuda", 0)
+    torch.cuda.empty_cache()
+    free_b, _ = torch.cuda.mem_get_info()
+    need_b = cfg.total_rows * cfg.emb_dim * 4 + (24 << 30)
+    if free_b < need_b:
+        pytest.skip(f"needs {need_b >> 30} GiB of free device memory, {free_b >> 30} GiB are free")
+    K, order = cfg.inner_steps, cfg.order
+    print(f"{name}: {len(tasks)} tasks {tasks}", flush=True)
+    params = make_params(cfg, dev, chunk=1 << 26)
+    sup, qry = make_batch(cfg, 0, dev, tasks)
+    ctx = gm.from_config(cfg, workspace_bytes=16 << 30)
+    ctx.configure("max_wave_tasks", per_wave)
+    out = ctx.meta_step(sup, qry, params, cfg.inner_lr, K, order)
+    ctx.close()
+    s_cpu, q_cpu = make_batch(cfg, 0, "cpu", tasks)
+    assert torch.equal(s_cpu.indices, sup.indices.cpu()) and torch.equal(q_cpu.bag_offsets, qry.bag_offsets.cpu())
+    model, p_np, sd, qd, grows = compact_task(cfg, s_cpu, q_cpu, params.emb, params.W, params.b)
+    rec = {}
+    ref = O.meta_step(model, p_np, sd, qd, cfg.inner_lr, K, order, operand="bf16", masks_out=rec)
+    gated = O.meta_step(model, p_np, sd, qd, cfg.inner_lr, K, order, relu_masks=rec)
+    n = int(out["n_emb_rows"].item())
+    assert n == len(ref["emb_rows"])
+    assert np.array_equal(out["emb_rows"][:n].cpu().numpy(), grows[ref["emb_rows"]])     # integers: exact
+    T = len(tasks)
+    for label, r in (("float64 arithmetic on bf16 gates", gated), ("bf16-operand oracle", ref)):
+        e = _errors(out, r, n, T)
+        got, want = out["emb_grad"][:n].double().cpu().numpy(), r["emb_grad"]
+        row_err = np.linalg.norm(got - want, axis=1) / np.linalg.norm(want, axis=1).max()
+        print(f"{name} subset vs {label}:", {k: f"{v:.2e}" for k, v in e.items()},
+              f"rows: median {np.median(row_err):.1e}, 99.9% {np.quantile(row_err, 0.999):.1e}, max {row_err.max():.1e}, "
+              f"above tolerance {int((row_err > TOL_BF16).sum())} of {n}", flush=True)
+        for k, v in e.items():
+            assert v <= TOL_BF16, (name, label, k, v)
+    del params, sup, qry, out
+    torch.cuda.empty_cache()
+
+
+def test_tables_of_unequal_size(gm):
+    """rows_per_field need not be equal: 5 fields of 7 to 3,001 rows (field bases that are no multiple of anything),
+    fp32, every output against the oracle; and the integer structures bit for bit."""
+    from paper_2401_04338_amd import GMeta
+    from synth.generate import Params, SetData
+    rows = [7, 3001, 64, 1234, 333]
+    cfg = SMALL.with_(n_tasks=5, n_support=33, n_query=21, n_fields=5, emb_dim=16, rows_per_field=4000, bag_max=6,
+                      layer_dims=(5 * 16 + 13, 32, 16, 1), inner_lr=0.05)
+    sup, qry, params = _inputs(cfg, emb_std=0.2)
+    F = cfg.n_fields
+
+    def fold(sd):   # every index taken modulo its own field's table size
+        lens = sd.bag_offsets[1:] - sd.bag_offsets[:-1]
+        field = (torch.arange(lens.numel()) % F).repeat_interleave(lens)
+        return SetData(sd.task_offsets, sd.bag_offsets, (sd.indices.long() % torch.tensor(rows)[field]).int(), sd.dense, sd.labels)
+
+    sup, qry = fold(sup), fold(qry)
+    emb = params.emb[: sum(rows)].contiguous()
+    p2 = Params(emb, params.W, params.b)
+    model = O.Model(rows_per_field=rows, emb_dim=cfg.emb_dim, n_dense=cfg.n_dense, layer_dims=list(cfg.layer_dims))
+    ctx = GMeta(F, rows, cfg.emb_dim, cfg.n_dense, cfg.layer_dims, 0, workspace_bytes=1 << 28)
+    dev = ctx.device
+    got = ctx.index_prep(_to_dev(sup, dev), _to_dev(qry, dev))
+    want = O.index_prep(model, sup.numpy(), qry.numpy())
+    for k in ("slot_counts", "slot_rows", "sup_slot", "qry_slot", "emb_rows", "seg_counts"):
+        assert np.array_equal(got[k].cpu().numpy(), want[k]), k
+    _compare_step(cfg, ctx, sup, qry, p2, 2, 2, TOL_FP32, "unequal tables", model=model)
+    ctx.close()
