@@ -218,6 +218,8 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               "overlap_sort" is 1.
  *   "gemm_tile_n": column tile of the forward / backward grouped products when tasks get 256-row tiles:
  *               0 = chosen by the library (128), 128, or 256 (eight waves per workgroup; identical results).
+ *   "max_wave_tasks": most tasks processed at a time (0 = as many as the workspace holds).  Tasks are independent
+ *               (Alg. 1): a call runs them in waves of nearly equal size, the fewest that fit the workspace.
  *   "pair_tile_rows": most out-rows of a pair-count matrix that the counting kernel holds in LDS at a time
  *               (0 = as many as fit); identical results.
  * Unknown keys or values give GM_ERR_ARG. */
@@ -229,6 +231,14 @@ int gm_configure(gm_ctx* ctx, const char* key, int64_t value);
  * algorithmic_flops".  Enabling clears the accumulated figures. */
 int gm_profile(gm_ctx* ctx, int enable);
 const char* gm_profile_report(gm_ctx* ctx);
+
+/* On-box ceilings for measurement harnesses (not part of the method): a streaming copy (bytes read + written per
+ * second), a streaming read and a register-resident v_mfma_f32_32x32x16_bf16 loop, each run by a kernel of the
+ * library's own on the context's workspace (at least 130 MiB; up to 2 GiB per buffer are used) and timed with HIP
+ * events: the best of several repetitions.  Outputs are HOST: GB/s, GB/s, TFLOP/s, and (if not NULL) the bytes of one
+ * buffer -- every stream_copy_kernel dispatch of the call reads that many bytes and writes as many, which gives
+ * profiler byte counters a transfer of known size to be scaled by. */
+int gm_ceilings(gm_ctx* ctx, double* copy_gbs, double* read_gbs, double* mfma_tflops, int64_t* buffer_bytes);
 
 #ifdef __cplusplus
 }

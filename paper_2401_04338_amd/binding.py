@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libgmeta.so")
 GM_OK, GM_ERR_ARG, GM_ERR_INDEX, GM_ERR_CAPACITY, GM_ERR_WORKSPACE, GM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["gm_create", "gm_destroy", "gm_last_error", "gm_workspace_bytes", "gm_meta_step", "gm_meta_step_static",
-           "gm_meta_train_step", "gm_group_batch", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report"]
+           "gm_meta_train_step", "gm_group_batch", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report", "gm_ceilings"]
 
 
 class gm_model_desc(C.Structure):
@@ -101,6 +101,9 @@ def load_library() -> C.CDLL:
     lib.gm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.gm_profile_report.restype = C.c_char_p
     lib.gm_profile_report.argtypes = [C.c_void_p]
+    lib.gm_ceilings.restype = C.c_int
+    lib.gm_ceilings.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                C.POINTER(C.c_int64)]
     _lib = lib
     return lib
 
@@ -318,6 +321,13 @@ class GMeta:
             name, n, ms, by, fl = line.split()
             out[name] = dict(launches=int(n), ms=float(ms), bytes=float(by), flops=float(fl))
         return out
+
+    def ceilings(self) -> Dict[str, float]:
+        """gm_ceilings: {"copy_GBps", "read_GBps", "mfma_bf16_TFLOPs", "copy_buffer_bytes"} measured on this GPU with the
+        library's own kernels."""
+        a, b, m, n = C.c_double(0), C.c_double(0), C.c_double(0), C.c_int64(0)
+        self._check(self.lib.gm_ceilings(self._ctx, C.byref(a), C.byref(b), C.byref(m), C.byref(n)))
+        return {"copy_GBps": a.value, "read_GBps": b.value, "mfma_bf16_TFLOPs": m.value, "copy_buffer_bytes": n.value}
 
     def scatter_add(self, table: torch.Tensor, rows: torch.Tensor, grad: torch.Tensor, scale: float):
         self._check(self.lib.gm_scatter_add(self._ctx, _ptr(table), _ptr(rows), _ptr(grad), int(rows.numel()),

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgmeta.so")
 SOURCES = ["gmeta.hip", "index_kernels.hip", "embed_kernels.hip", "mlp_kernels.hip", "gemm_bf16.hip", "twohop_kernels.hip",
-           "pairhop_kernels.hip"]
+           "pairhop_kernels.hip", "ceiling_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-Wno-unused-value", "-Wno-unknown-warning-option"]

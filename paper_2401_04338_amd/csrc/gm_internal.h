@@ -264,3 +264,8 @@ void launch_axpy(hipStream_t st, int64_t n, float a, const float* x, float* y); 
 void launch_sum_to_scalar(hipStream_t st, const float* x, int n, float* out, int accumulate);
 void launch_fill_u32(hipStream_t st, u32* p, int64_t n, u32 v);
 void launch_fill_f32(hipStream_t st, float* p, int64_t n, float v);
+
+// ------------------------------------------------------------------ on-box ceilings (measurement only)
+void launch_stream_copy(hipStream_t st, const void* src, void* dst, int64_t bytes);
+void launch_stream_read(hipStream_t st, const void* src, int64_t bytes, u32* sink);
+double launch_mfma_loop(hipStream_t st, int iters, float* sink);   // returns the flops of the launch

@@ -82,6 +82,7 @@ struct gm_ctx {
     int adapt_rows = 1;   // 0: the inner loop adapts the dense parameters only (embedding rows are read, not updated)
     int gemm_tile_n = 0;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
+    int max_wave_tasks = 0;   // 0: as many tasks per wave as the workspace holds
     char* static_scratch = nullptr;   // this device's copy of the static scratch array (gm_meta_step_static)
     // optional kernel timing
     bool prof_on = false;
@@ -555,6 +556,11 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
         c->overlap_sort = (int)value;
         return GM_OK;
     }
+    if (!strcmp(key, "max_wave_tasks")) {
+        if (value < 0 || value > 32768) return fail(c, GM_ERR_ARG, "max_wave_tasks must be in [0, 32768]");
+        c->max_wave_tasks = (int)value;
+        return GM_OK;
+    }
     if (!strcmp(key, "row_path")) {
         if (value < 0 || value > 2) return fail(c, GM_ERR_ARG, "row_path must be 0, 1 or 2");
         c->row_path = (int)value;
@@ -580,6 +586,56 @@ extern "C" const char* gm_profile_report(gm_ctx* c) {
         c->prof_text += line;
     }
     return c->prof_text.c_str();
+}
+
+// Streaming and matrix-core ceilings of this GPU, measured with kernels of the library's own on the context's
+// workspace (whose contents are scratch between calls anyway).
+extern "C" int gm_ceilings(gm_ctx* c, double* copy_gbs, double* read_gbs, double* mfma_tflops, int64_t* buffer_bytes) {
+    if (!c) return GM_ERR_ARG;
+    if (!copy_gbs || !read_gbs || !mfma_tflops) return fail(c, GM_ERR_ARG, "null outputs");
+    HIPCHK(c, hipSetDevice(c->device));
+    hipStream_t st = c->stream;
+    const size_t avail = (c->ws_bytes - c->persistent) / 2 / 4096 * 4096;
+    const int64_t bytes = (int64_t)std::min<size_t>(avail, (size_t)2 << 30);
+    if (bytes < (64 << 20)) return fail(c, GM_ERR_WORKSPACE, "gm_ceilings needs a workspace of at least 130 MiB");
+    char* a = c->ws + (c->persistent + 4095) / 4096 * 4096;
+    char* b = a + bytes;
+    if (buffer_bytes) *buffer_bytes = bytes;
+    hipEvent_t e0, e1;
+    HIPCHK(c, hipEventCreate(&e0));
+    HIPCHK(c, hipEventCreate(&e1));
+    auto timed = [&](auto&& launch, int reps, float* best) -> int {
+        *best = 1e30f;
+        for (int r = 0; r < reps + 1; ++r) {   // the first repetition warms up
+            HIPCHK(c, hipEventRecord(e0, st));
+            launch();
+            HIPCHK(c, hipEventRecord(e1, st));
+            HIPCHK(c, hipEventSynchronize(e1));
+            float ms = 0.f;
+            HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+            if (r > 0) *best = std::min(*best, ms);
+        }
+        return GM_OK;
+    };
+    launch_fill_u32(st, reinterpret_cast<u32*>(a), bytes / 4, 0x3f800000u);
+    float ms = 0.f;
+    int rc = timed([&] { launch_stream_copy(st, a, b, bytes); }, 5, &ms);
+    if (rc == GM_OK) {
+        *copy_gbs = 2.0 * bytes / (ms * 1e-3) / 1e9;
+        rc = timed([&] { launch_stream_read(st, a, bytes, reinterpret_cast<u32*>(b)); }, 5, &ms);
+    }
+    if (rc == GM_OK) {
+        *read_gbs = (double)bytes / (ms * 1e-3) / 1e9;
+        double flops = 0.0;
+        rc = timed([&] { flops = launch_mfma_loop(st, 20000, reinterpret_cast<float*>(b)); }, 3, &ms);
+        if (rc == GM_OK) *mfma_tflops = flops / (ms * 1e-3) / 1e12;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != GM_OK) return rc;
+    HIPCHK(c, hipStreamSynchronize(st));
+    HIPCHK(c, hipGetLastError());
+    return GM_OK;
 }
 
 static int64_t padded_upper(const gm_ctx* c, int64_t n, int T) { return n + (int64_t)T * (c->row_pad - 1); }
@@ -813,7 +869,9 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
 
 static void colsum(gm_ctx* c, const Grp& g, int N, const Act* X1, const float* w1, const Act* X2, const float* w2,
                    float* out, int64_t g_out, const float* in, int64_t g_in, float c0, float c1) {
-    Prof p(c, "task_colsum", 0, 0);
+    // algorithmic bytes: every operand row once (and its per-row weights), one output row per task (read back when updated)
+    Prof p(c, "task_colsum", (double)g.rows * N * (c->mlp_dtype ? 2.0 : 4.0) * (X2 ? 2 : 1) + 4.0 * g.rows * ((w1 ? 1 : 0) + (w2 ? 1 : 0)) +
+                                 4.0 * g.G * N * (in ? 2 : 1), 0);
     if (c->mlp_dtype == 0)
         launch_task_colsum(c->stream, g.G, g.row_off, N, X1->f, w1, X2 ? X2->f : nullptr, w2, X1->ld, out, g_out, in, g_in,
                            c0, c1);
@@ -823,7 +881,7 @@ static void colsum(gm_ctx* c, const Grp& g, int N, const Act* X1, const float* w
 }
 static void colsum_f32(gm_ctx* c, const Grp& g, int N, const float* X1, int64_t ldx, float* out, int64_t g_out,
                        const float* in, int64_t g_in, float c0, float c1) {
-    Prof p(c, "task_colsum", 0, 0);
+    Prof p(c, "task_colsum", 4.0 * g.rows * N + 4.0 * g.G * N * (in ? 2 : 1), 0);
     launch_task_colsum(c->stream, g.G, g.row_off, N, X1, nullptr, nullptr, nullptr, ldx, out, g_out, in, g_in, c0, c1);
 }
 
@@ -849,7 +907,10 @@ static void forward_backward(gm_ctx* c, const Grp& g, const float* labels, const
     }
     const float* wL = thf + c->offW[L];
     {
-        Prof pr(c, "last_layer", 0, 0);
+        // algorithmic bytes: the last hidden activations read twice (logit; mask of the backward pass), the delta of the
+        // last hidden layer written, 20 bytes of per-row scalars (label, logit, delta, loss, task)
+        const double esz_l = c->mlp_dtype ? 2.0 : 4.0;
+        Prof pr(c, "last_layer", (double)g.rows * c->ld[L - 1] * esz_l * (L > 1 ? 3 : 1) + 20.0 * g.rows + (L == 1 && dX ? 4.0 * g.rows * c->FD : 0.0), 0);
         LastFwdArgs f;
         memset(&f, 0, sizeof f);
         f.n = g.rows; f.N = c->ld[L - 1]; f.ld = c->ld[L - 1]; f.bf16 = c->mlp_dtype;
@@ -921,7 +982,9 @@ static void hvp_step(gm_ctx* c, const Grp& g, const StepState& s, WaveBufs& w, f
     }
     const float* vwL = v.f + c->offW[L];
     {
-        Prof pr(c, "last_layer", 0, 0);
+        // (tangent pass: activations and their tangents read, the mask read, the tangent delta written)
+        const double esz_l = c->mlp_dtype ? 2.0 : 4.0;
+        Prof pr(c, "last_layer", (double)g.rows * c->ld[L - 1] * esz_l * (L > 1 ? 4 : 2) + 24.0 * g.rows + (L == 1 ? 4.0 * g.rows * c->FD : 0.0), 0);
         LastFwdArgs f;
         memset(&f, 0, sizeof f);
         f.n = g.rows; f.N = c->ld[L - 1]; f.ld = c->ld[L - 1]; f.bf16 = c->mlp_dtype;
@@ -1079,7 +1142,12 @@ static int global_order(gm_ctx* c, Batch& B, SortBufs& so, const SortRange& r, i
     }
     int bits = 1;
     while (((int64_t)1 << bits) < c->field_base[c->F]) ++bits;
-    if (launch_radix_sort(st, so.keys, so.vals, so.keys_tmp, so.vals_tmp, nnz, bits, so.hist) & 1) {
+    const int passes = launch_radix_sort(st, so.keys, so.vals, so.keys_tmp, so.vals_tmp, nnz, bits, so.hist);
+    // algorithmic bytes: keys built from the lookups (4 B index read, 8 B of key and value written, 8 B of offsets per bag),
+    // 20 B per key and radix pass (the key read for the digit counts; key and value read and written by the scatter),
+    // the sorted keys read once more for the segments
+    p.p.bytes = (double)nnz * (12.0 + 20.0 * passes + (n_rows ? 4.0 : 0.0)) + 8.0 * F * ((r.s1 - r.s0) + (r.q1 - r.q0));
+    if (passes & 1) {
         std::swap(so.keys, so.keys_tmp);   // an odd number of passes leaves the result in the second pair of buffers
         std::swap(so.vals, so.vals_tmp);
     }
@@ -1181,8 +1249,13 @@ static int plan_waves(gm_ctx* c, Batch& B, size_t avail, int K, int order, int b
         have_offsets = true;
         return GM_OK;
     };
-    int per = std::min(std::max(T, 1), 32768);  // a wave's tasks are one grid dimension of several kernels
+    // Waves of (nearly) equal numbers of tasks: the fewest waves whose every wave fits.  A wave's tasks are one grid
+    // dimension of several kernels, hence the cap.
+    int max_per = std::min(std::max(T, 1), 32768);
+    if (c->max_wave_tasks > 0) max_per = std::min(max_per, c->max_wave_tasks);
+    int n_waves = (std::max(T, 1) + max_per - 1) / max_per;
     while (true) {
+        const int per = (std::max(T, 1) + n_waves - 1) / n_waves;
         plans.clear();
         bool fits = true;
         if (per < T) {
@@ -1212,7 +1285,7 @@ static int plan_waves(gm_ctx* c, Batch& B, size_t avail, int K, int order, int b
         }
         if (fits) return GM_OK;
         if (per == 1) return fail(c, GM_ERR_WORKSPACE, "workspace of %zu bytes cannot hold one task", c->ws_bytes);
-        per = (per + 1) / 2;
+        n_waves = std::min(std::max(T, 1), std::max(n_waves + 1, n_waves + n_waves / 16));
     }
 }
 
