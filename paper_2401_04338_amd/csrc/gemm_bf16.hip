@@ -13,6 +13,8 @@
 //   weight grad  A = activations [rows, d_in]  (KA),          B = deltas [rows, d_out]     (KB), K = rows of the task
 // A group is a task: its rows are [row_offsets[g], row_offsets[g+1]) and, once theta has been adapted,
 // its weights are its own (group stride != 0).
+#include <algorithm>
+
 #include "gm_internal.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -25,11 +27,196 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
+// What an epilogue does is fixed at compile time for the launches the step makes (EP >= 0: bits 0-2 the fused
+// operation, then whether the fp32 output, the bf16 output, the accumulate-into output and the added input exist), so
+// that the per-element code is straight-line; EP < 0 reads the same facts from the arguments at run time (any other
+// combination).  With everything decided per element at run time the epilogue of a 256 x 256 tile ran to some 14,000
+// instructions -- as long as twelve k-tiles of its main loop.
+enum { EP_CF = 8, EP_CB = 16, EP_CACC = 32, EP_CIN = 64, EP_RUNTIME = -1 };
+static int ep_of(const GemmBArgs& a) {
+    const bool cin = a.epi == EPI_AXPBY && a.Cin;
+    return a.epi | (a.Cf ? EP_CF : 0) | (a.Cb ? EP_CB : 0) | ((a.Cacc && !cin) ? EP_CACC : 0) | (cin ? EP_CIN : 0);
+}
+template <int EP>
+struct EpiFlags {
+    int epi;
+    bool cf, cb, cacc, cin;
+    __device__ __forceinline__ explicit EpiFlags(const GemmBArgs& a) {
+        if constexpr (EP >= 0) {
+            epi = EP & 7; cf = (EP & EP_CF) != 0; cb = (EP & EP_CB) != 0; cacc = (EP & EP_CACC) != 0; cin = (EP & EP_CIN) != 0;
+        } else {
+            epi = a.epi; cf = a.Cf != nullptr; cb = a.Cb != nullptr;
+            cin = a.epi == EPI_AXPBY && a.Cin != nullptr; cacc = a.Cacc != nullptr && !cin;
+        }
+    }
+};
+
+// Epilogue shared by the GEMM kernels.  A lane holds column l32 of each 32x32 block and rows 8*(v/4) + 4*lhi + v%4,
+// which would give 2-byte scattered stores; instead every wave passes its accumulators through LDS one 32-row strip at
+// a time, applies the fused operation on 4 consecutive columns per lane and writes whole row segments.
+template <int BM, int BN, int MI, int NI, int EP>
+__device__ __forceinline__ void gemm_epilogue(const GemmBArgs& a, f32x16 (&acc)[MI][NI], bf16_t* smem, int g, int64_t r0, int m0,
+                                              int n0, int M, int N, int wm0, int wn0, int lane, int wave) {
+    const EpiFlags<EP> fl(a);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const bool has_bias = (fl.epi == EPI_BIAS_RELU || fl.epi == EPI_BIAS_MASK) && a.bias;
+    const bool has_mask = fl.epi == EPI_BIAS_MASK || fl.epi == EPI_MASK;
+    const bool has_cin = fl.cin, has_acc = fl.cacc;
+    const float* bias = has_bias ? a.bias + (int64_t)g * a.gBias : nullptr;
+    const bf16_t* mask = has_mask ? a.mask + r0 * a.ld_mask : nullptr;
+    const float* Cin = has_cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
+    float* Cf = fl.cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
+    float* Cacc = has_acc ? a.Cacc + r0 * a.rCacc : nullptr;
+    bf16_t* Cb = fl.cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
+    constexpr int SW = NI * 32, ELD = SW + 4;      // strip width, LDS row stride (floats)
+    constexpr int LPR = SW / 4, RPI = 64 / LPR;    // lanes per strip row, rows per pass
+    float* E = reinterpret_cast<float*>(smem) + wave * (32 * ELD);
+    const int er = lane / LPR, ec = (lane % LPR) * 4;
+    const int n = n0 + wn0 + ec;
+    const bool nok = n < N;
+    float4 bn = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (has_bias && nok) bn = *reinterpret_cast<const float4*>(bias + n);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        // What the strip reads from memory is requested before anything of it is stored: the outputs may alias
+        // the inputs (an in-place update), which would otherwise chain every load behind the previous store.
+        uint2 mk_all[32 / RPI];
+        float4 ci_all[32 / RPI];
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int m = m0 + wm0 + i * 32 + it * RPI + er;
+            const bool ok = nok && m < M;
+            mk_all[it] = make_uint2(0u, 0u);
+            ci_all[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ok && has_mask) mk_all[it] = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
+            if (ok && has_cin) ci_all[it] = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
+            if (ok && has_acc && !a.cacc_init) ci_all[it] = *reinterpret_cast<const float4*>(Cacc + (int64_t)m * a.ldcacc + n);
+        }
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) E[(8 * (v >> 2) + 4 * lhi + (v & 3)) * ELD + j * 32 + l32] = acc[i][j][v];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the strip is this wave's own: LDS order within the wave suffices
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int rr = it * RPI + er;
+            const int m = m0 + wm0 + i * 32 + rr;
+            if (!nok || m >= M) continue;
+            float4 x = *reinterpret_cast<const float4*>(E + rr * ELD + ec);
+            if (fl.epi == EPI_BIAS_RELU) {
+                x = make_float4(fmaxf(x.x + bn.x, 0.f), fmaxf(x.y + bn.y, 0.f), fmaxf(x.z + bn.z, 0.f), fmaxf(x.w + bn.w, 0.f));
+            } else if (has_mask) {
+                const uint2 mk = mk_all[it];
+                if (fl.epi == EPI_BIAS_MASK) x = make_float4(x.x + bn.x, x.y + bn.y, x.z + bn.z, x.w + bn.w);
+                // a bf16 is positive iff it is neither zero nor has its sign bit set
+                const u32 h0 = mk.x & 0xffffu, h1 = mk.x >> 16, h2 = mk.y & 0xffffu, h3 = mk.y >> 16;
+                x.x = (h0 != 0 && h0 < 0x8000u) ? x.x : 0.f;
+                x.y = (h1 != 0 && h1 < 0x8000u) ? x.y : 0.f;
+                x.z = (h2 != 0 && h2 < 0x8000u) ? x.z : 0.f;
+                x.w = (h3 != 0 && h3 < 0x8000u) ? x.w : 0.f;
+            } else if (fl.epi == EPI_AXPBY) {
+                x = make_float4(a.c1 * x.x, a.c1 * x.y, a.c1 * x.z, a.c1 * x.w);
+                if (has_cin) {
+                    const float4 ci = ci_all[it];
+                    x = make_float4(x.x + a.c0 * ci.x, x.y + a.c0 * ci.y, x.z + a.c0 * ci.z, x.w + a.c0 * ci.w);
+                }
+            }
+            if (fl.cf) *reinterpret_cast<float4*>(Cf + (int64_t)m * a.ldcf + n) = x;
+            if (has_acc) {
+                const float4 ci = ci_all[it];
+                *reinterpret_cast<float4*>(Cacc + (int64_t)m * a.ldcacc + n) =
+                    make_float4(ci.x + a.cacc * x.x, ci.y + a.cacc * x.y, ci.z + a.cacc * x.z, ci.w + a.cacc * x.w);
+            }
+            if (fl.cb) {
+                uint2 pk;
+                pk.x = f2bf2(x.x, x.y);
+                pk.y = f2bf2(x.z, x.w);
+                *reinterpret_cast<uint2*>(Cb + (int64_t)m * a.ldcb + n) = pk;
+            }
+        }
+        asm volatile("" ::: "memory");   // (no block barrier: it would also wait for the strip's global stores to land)
+    }
+}
+
+// Epilogue for accumulators computed with the operand roles swapped (first MFMA operand = B fragment, second = A
+// fragment): the 32 x 32 block then sits transposed in the registers -- a lane holds ONE output row m (lane % 32) and,
+// per group of four accumulator registers, four consecutive output columns n = 8 q + 4 (lane / 32) + (0..3) -- so every
+// fused operation and every store works on 8- or 16-byte pieces of a row straight from the registers, without a
+// pass through LDS.  Same arithmetic per element as gemm_epilogue.
+template <int MI, int NI, int EP>
+__device__ __forceinline__ void gemm_epilogue_direct(const GemmBArgs& a, f32x16 (&acc)[MI][NI], int g, int64_t r0, int m0, int n0,
+                                                     int M, int N, int wm0, int wn0, int lane) {
+    const EpiFlags<EP> fl(a);
+    const int l32 = lane & 31, lhi = lane >> 5;
+    const bool has_bias = (fl.epi == EPI_BIAS_RELU || fl.epi == EPI_BIAS_MASK) && a.bias;
+    const bool has_mask = fl.epi == EPI_BIAS_MASK || fl.epi == EPI_MASK;
+    const bool has_cin = fl.cin, has_acc = fl.cacc;
+    const float* bias = has_bias ? a.bias + (int64_t)g * a.gBias : nullptr;
+    const bf16_t* mask = has_mask ? a.mask + r0 * a.ld_mask : nullptr;
+    const float* Cin = has_cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
+    float* Cf = fl.cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
+    float* Cacc = has_acc ? a.Cacc + r0 * a.rCacc : nullptr;
+    bf16_t* Cb = fl.cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int m = m0 + wm0 + i * 32 + l32;
+        const bool mok = m < M;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            // everything this block reads from memory is requested before anything of it is stored
+            uint2 mk[4];
+            float4 ci[4], bn[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn0 + j * 32 + 8 * q + 4 * lhi;
+                const bool ok = mok && n < N;
+                mk[q] = make_uint2(0u, 0u);
+                ci[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                bn[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (has_bias && n < N) bn[q] = *reinterpret_cast<const float4*>(bias + n);
+                if (ok && has_mask) mk[q] = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
+                if (ok && has_cin) ci[q] = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
+                if (ok && has_acc && !a.cacc_init) ci[q] = *reinterpret_cast<const float4*>(Cacc + (int64_t)m * a.ldcacc + n);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn0 + j * 32 + 8 * q + 4 * lhi;
+                if (!mok || n >= N) continue;
+                float4 x = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                if (fl.epi == EPI_BIAS_RELU) {
+                    x = make_float4(fmaxf(x.x + bn[q].x, 0.f), fmaxf(x.y + bn[q].y, 0.f), fmaxf(x.z + bn[q].z, 0.f), fmaxf(x.w + bn[q].w, 0.f));
+                } else if (has_mask) {
+                    if (fl.epi == EPI_BIAS_MASK) x = make_float4(x.x + bn[q].x, x.y + bn[q].y, x.z + bn[q].z, x.w + bn[q].w);
+                    // a bf16 is positive iff it is neither zero nor has its sign bit set
+                    const u32 h0 = mk[q].x & 0xffffu, h1 = mk[q].x >> 16, h2 = mk[q].y & 0xffffu, h3 = mk[q].y >> 16;
+                    x.x = (h0 != 0 && h0 < 0x8000u) ? x.x : 0.f;
+                    x.y = (h1 != 0 && h1 < 0x8000u) ? x.y : 0.f;
+                    x.z = (h2 != 0 && h2 < 0x8000u) ? x.z : 0.f;
+                    x.w = (h3 != 0 && h3 < 0x8000u) ? x.w : 0.f;
+                } else if (fl.epi == EPI_AXPBY) {
+                    x = make_float4(a.c1 * x.x, a.c1 * x.y, a.c1 * x.z, a.c1 * x.w);
+                    if (has_cin) x = make_float4(x.x + a.c0 * ci[q].x, x.y + a.c0 * ci[q].y, x.z + a.c0 * ci[q].z, x.w + a.c0 * ci[q].w);
+                }
+                if (fl.cf) *reinterpret_cast<float4*>(Cf + (int64_t)m * a.ldcf + n) = x;
+                if (has_acc)
+                    *reinterpret_cast<float4*>(Cacc + (int64_t)m * a.ldcacc + n) =
+                        make_float4(ci[q].x + a.cacc * x.x, ci[q].y + a.cacc * x.y, ci[q].z + a.cacc * x.z, ci[q].w + a.cacc * x.w);
+                if (fl.cb) {
+                    uint2 pk;
+                    pk.x = f2bf2(x.x, x.y);
+                    pk.y = f2bf2(x.z, x.w);
+                    *reinterpret_cast<uint2*>(Cb + (int64_t)m * a.ldcb + n) = pk;
+                }
+            }
+        }
+    }
+}
+
 // Waves: 2 along m, BN / 128 * 2 along n -- 4 waves for 128-wide tiles, 8 for 256-wide ones, so that a wave's share
 // is at most 128 x 64 (128 accumulator registers) whatever the block tile.
-template <int BM, int BN, bool DB, bool KA, bool KB>
-__global__ __launch_bounds__(BN > 128 ? 2 * (BN / 64) * 64 : 256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
-    constexpr int WN = BN > 128 ? BN / 64 : 2;   // waves along n
+template <int BM, int BN, bool DB, bool KA, bool KB, int EP>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
+    constexpr int WN = 2;   // waves along n
     constexpr int NT = 2 * WN * 64;              // threads
     constexpr int MI = BM / 64, NI = BN / (32 * WN);  // 32x32 blocks per wave in each direction
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
@@ -193,133 +380,318 @@ __global__ __launch_bounds__(BN > 128 ? 2 * (BN / 64) * 64 : 256) void gemm_bf16
         __syncthreads();  // every wave is done with the operand tiles
     }
 
-    // epilogue.  A lane holds column l32 of each 32x32 block and rows 8*(v/4) + 4*lhi + v%4, which would give
-    // 2-byte scattered stores; instead every wave passes its accumulators through LDS one 32-row strip at a
-    // time, applies the fused operation on 4 consecutive columns per lane and writes whole row segments.
-    const float* bias = a.bias ? a.bias + (int64_t)g * a.gBias : nullptr;
-    const bf16_t* mask = a.mask ? a.mask + r0 * a.ld_mask : nullptr;
-    const float* Cin = a.Cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
-    float* Cf = a.Cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
-    float* Cacc = a.Cacc ? a.Cacc + r0 * a.rCacc : nullptr;
-    bf16_t* Cb = a.Cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
-    constexpr int SW = NI * 32, ELD = SW + 4;      // strip width, LDS row stride (floats)
-    constexpr int LPR = SW / 4, RPI = 64 / LPR;    // lanes per strip row, rows per pass
-    float* E = reinterpret_cast<float*>(smem) + wave * (32 * ELD);
-    const int er = lane / LPR, ec = (lane % LPR) * 4;
-    const int n = n0 + wn0 + ec;
-    const bool nok = n < N;
-    float4 bn = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (bias && nok) bn = *reinterpret_cast<const float4*>(bias + n);
-    const bool has_mask = a.epi == EPI_BIAS_MASK || a.epi == EPI_MASK;
-    const bool has_cin = a.epi == EPI_AXPBY && Cin;
-    const bool has_acc = Cacc && !has_cin;   // the accumulate-into output shares the registers of Cin
+    gemm_epilogue<BM, BN, MI, NI, EP>(a, acc, smem, g, r0, m0, n0, M, N, wm0, wn0, lane, wave);
+}
+
+// ------------------------------------------------------------------------------------------------
+// 256 x 256 tiles for products that are bound by the matrix cores (forward and backward products of tasks with
+// hundreds of rows).  Four waves, each owning a 128 x 128 block of the tile (16 accumulator blocks = 256 registers):
+// per contraction step a wave reads 8 operand fragments from LDS for 16 MFMAs, half the LDS traffic per flop of a
+// 128 x 64 block, which is what the smaller tiles are bound by.  One wave per SIMD, so nothing but the instruction
+// order hides latencies: two LDS stages, fragments double-buffered in registers, and within each k-tile
+//   step 0: fragments of step 1 requested, first half of the NEXT tile parked in the other stage, first half of the
+//           tile after it requested from memory, MFMAs of step 0
+//   step 1: the same with the second halves
+//   step 2: fragments of step 3 requested, MFMAs of step 2
+//   step 3: barrier (everyone has read this stage and written the other), fragments of the next tile's step 0
+//           requested, MFMAs of step 3
+// Operand tiles come through buffer loads: a row, column or whole tile outside the operand reads as zero without a
+// branch, so the loop body is straight-line code.  A is stored contraction-contiguous; B either way (KB).
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+
+#ifdef GEMM_TIMING
+__device__ unsigned long long g_gemm_ts[4 * 16384];
+void gemm_timing_fetch(unsigned long long* host, int n) { (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_gemm_ts), sizeof(unsigned long long) * n); }
+#endif
+template <bool KB, int EP, bool TIMED = false>
+__global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
+    constexpr int BM = 256, BN = 256, MI = 4, NI = 4, NT = 256;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    constexpr int LDB_K = BN + GPADK;
+    constexpr int A_ELEMS = BM * GLD;
+    constexpr int TILE = A_ELEMS + (KB ? GK * LDB_K : BN * GLD);
+
+    const int per_xcd = gridDim.x >> 3;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= n_tiles) return;
+    const int ntile = tile % n_ntiles;
+    const int mtile = tile / n_ntiles;
+    int g, m0;
+    if (a.tile_group) {
+        g = a.tile_group[mtile];
+        m0 = a.tile_m0[mtile];
+    } else {
+        g = mtile / mt_per_group;
+        m0 = (mtile % mt_per_group) * BM;
+    }
+    const int64_t r0 = a.row_offsets[g];
+    const int rows_g = (int)(a.row_offsets[g + 1] - r0);
+    const int M = a.M < 0 ? rows_g : a.M;
+    const int K = a.K < 0 ? rows_g : a.K;
+    const int N = a.N;
+    const int n0 = ntile * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 128;
+    const int l32 = lane & 31, lhi = lane >> 5;
+
+    f32x16 acc[MI][NI];
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
-        // What the strip reads from memory is requested before anything of it is stored: the outputs may alias
-        // the inputs (an in-place update), which would otherwise chain every load behind the previous store.
-        uint2 mk_all[32 / RPI];
-        float4 ci_all[32 / RPI];
-#pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int m = m0 + wm0 + i * 32 + it * RPI + er;
-            const bool ok = nok && m < M;
-            mk_all[it] = make_uint2(0u, 0u);
-            ci_all[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ok && has_mask) mk_all[it] = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
-            if (ok && has_cin) ci_all[it] = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
-            if (ok && has_acc && !a.cacc_init) ci_all[it] = *reinterpret_cast<const float4*>(Cacc + (int64_t)m * a.ldcacc + n);
-        }
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) E[(8 * (v >> 2) + 4 * lhi + (v & 3)) * ELD + j * 32 + l32] = acc[i][j][v];
-        __syncthreads();
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int kt_per_pair = (K + GK - 1) / GK;
+    const int n_kt = kt_per_pair * a.n_pairs;
+
+    // operands of the (up to two) products as buffer resources: an access past the group's matrix returns zero
+    const u32 OOB = 0x7ffffff0u;
+    __amdgpu_buffer_rsrc_t rsA[2], rsB[2];
+    u32 ldA2[2], ldB2[2];
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int rr = it * RPI + er;
-            const int m = m0 + wm0 + i * 32 + rr;
-            if (!nok || m >= M) continue;
-            float4 x = *reinterpret_cast<const float4*>(E + rr * ELD + ec);
-            if (a.epi == EPI_BIAS_RELU) {
-                x = make_float4(fmaxf(x.x + bn.x, 0.f), fmaxf(x.y + bn.y, 0.f), fmaxf(x.z + bn.z, 0.f), fmaxf(x.w + bn.w, 0.f));
-            } else if (has_mask) {
-                const uint2 mk = mk_all[it];
-                if (a.epi == EPI_BIAS_MASK) x = make_float4(x.x + bn.x, x.y + bn.y, x.z + bn.z, x.w + bn.w);
-                // a bf16 is positive iff it is neither zero nor has its sign bit set
-                const u32 h0 = mk.x & 0xffffu, h1 = mk.x >> 16, h2 = mk.y & 0xffffu, h3 = mk.y >> 16;
-                x.x = (h0 != 0 && h0 < 0x8000u) ? x.x : 0.f;
-                x.y = (h1 != 0 && h1 < 0x8000u) ? x.y : 0.f;
-                x.z = (h2 != 0 && h2 < 0x8000u) ? x.z : 0.f;
-                x.w = (h3 != 0 && h3 < 0x8000u) ? x.w : 0.f;
-            } else if (a.epi == EPI_AXPBY) {
-                x = make_float4(a.c1 * x.x, a.c1 * x.y, a.c1 * x.z, a.c1 * x.w);
-                if (Cin) {
-                    const float4 ci = ci_all[it];
-                    x = make_float4(x.x + a.c0 * ci.x, x.y + a.c0 * ci.y, x.z + a.c0 * ci.z, x.w + a.c0 * ci.w);
-                }
-            }
-            if (Cf) *reinterpret_cast<float4*>(Cf + (int64_t)m * a.ldcf + n) = x;
-            if (has_acc) {
-                const float4 ci = ci_all[it];
-                *reinterpret_cast<float4*>(Cacc + (int64_t)m * a.ldcacc + n) =
-                    make_float4(ci.x + a.cacc * x.x, ci.y + a.cacc * x.y, ci.z + a.cacc * x.z, ci.w + a.cacc * x.w);
-            }
-            if (Cb) {
-                uint2 pk;
-                pk.x = f2bf2(x.x, x.y);
-                pk.y = f2bf2(x.z, x.w);
-                *reinterpret_cast<uint2*>(Cb + (int64_t)m * a.ldcb + n) = pk;
-            }
-        }
-        __syncthreads();
+    for (int p2 = 0; p2 < 2; ++p2) {
+        const int pr = p2 < a.n_pairs ? p2 : 0;
+        const bf16_t* A = a.A[pr] + (int64_t)g * a.gA[pr] + r0 * a.rA[pr];
+        const bf16_t* B = a.B[pr] + (int64_t)g * a.gB[pr] + r0 * a.rB[pr];
+        ldA2[p2] = (u32)a.lda[pr] * 2u;
+        ldB2[p2] = (u32)a.ldb[pr] * 2u;
+        rsA[p2] = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)((u32)M * ldA2[p2]), 0x00020000);
+        rsB[p2] = __builtin_amdgcn_make_buffer_rsrc((void*)B, 0, (int)((u32)(KB ? K : N) * ldB2[p2]), 0x00020000);
     }
+    // chunk c = tid + 256 i of a tile: A (and B stored like A): row c / 8, 16 bytes at k = (c % 8) * 8;
+    // B stored contraction-slowest: k-row c / 32, 16 bytes at n = (c % 32) * 8
+    const int crow = tid >> 3, ccol = (tid & 7) * 8;
+    const int kbrow = tid >> 5, kbcol = (tid & 31) * 8;
+    u32x4 ra[8], rb[8];
+    auto gload_half = [&](int h, int lt) {   // chunks 4h .. 4h+3 of tile lt (a tile past the end reads as zero)
+        const int pr = (lt >= kt_per_pair && a.n_pairs > 1) ? 1 : 0;
+        const int k0 = (lt - pr * kt_per_pair) * GK;
+        const __amdgpu_buffer_rsrc_t rA = pr ? rsA[1] : rsA[0];
+        const __amdgpu_buffer_rsrc_t rB = pr ? rsB[1] : rsB[0];
+        const u32 la = pr ? ldA2[1] : ldA2[0], lb = pr ? ldB2[1] : ldB2[0];
+        const bool kok = k0 + ccol < K;
+        const u32 a0 = kok ? (u32)(m0 + crow) * la + (u32)(k0 + ccol) * 2u : OOB;
+#pragma unroll
+        for (int i = 4 * h; i < 4 * h + 4; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rA, (int)(a0 + (kok ? (u32)(32 * i) * la : 0u)), 0, 0);
+        if constexpr (KB) {
+            const u32 b0 = (u32)(k0 + kbrow) * lb + (u32)(n0 + kbcol) * 2u;
+#pragma unroll
+            for (int i = 4 * h; i < 4 * h + 4; ++i) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rB, (int)(b0 + (u32)(8 * i) * lb), 0, 0);
+        } else {
+            const u32 b0 = kok ? (u32)(n0 + crow) * lb + (u32)(k0 + ccol) * 2u : OOB;
+#pragma unroll
+            for (int i = 4 * h; i < 4 * h + 4; ++i) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rB, (int)(b0 + (kok ? (u32)(32 * i) * lb : 0u)), 0, 0);
+        }
+    };
+    auto store_half = [&](bf16_t* stage, int h) {
+#pragma unroll
+        for (int i = 4 * h; i < 4 * h + 4; ++i) *reinterpret_cast<u32x4*>(stage + (crow + 32 * i) * GLD + ccol) = ra[i];
+#pragma unroll
+        for (int i = 4 * h; i < 4 * h + 4; ++i) {
+            if constexpr (KB) *reinterpret_cast<u32x4*>(stage + A_ELEMS + (kbrow + 8 * i) * LDB_K + kbcol) = rb[i];
+            else *reinterpret_cast<u32x4*>(stage + A_ELEMS + (crow + 32 * i) * GLD + ccol) = rb[i];
+        }
+    };
+    const int tr_off_row = lhi * 8 + ((lane & 15) >> 2), tr_off_col = (lane & 16) + (lane & 3) * 4;
+    auto frag_tr = [&](const bf16_t* tile_, int c0, int k) {
+        const bf16_t* p = tile_ + (k + tr_off_row) * LDB_K + c0 + tr_off_col;
+        typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * LDB_K));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto read_frags = [&](const bf16_t* stage, int kk, bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const bf16x8*>(stage + (wm0 + i * 32 + l32) * GLD + kk * 16 + lhi * 8);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            if constexpr (KB) bfr[j] = frag_tr(stage + A_ELEMS, wn0 + j * 32, kk * 16);
+            else bfr[j] = *reinterpret_cast<const bf16x8*>(stage + A_ELEMS + (wn0 + j * 32 + l32) * GLD + kk * 16 + lhi * 8);
+        }
+    };
+    auto mfmas = [&](const bf16x8 (&af)[MI], const bf16x8 (&bfr)[NI]) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);   // transposed block
+    };
+
+    bf16x8 fa0[MI], fb0[NI], fa1[MI], fb1[NI];
+#ifdef GEMM_TIMING
+    unsigned long long ts0 = 0, ts1 = 0, ts2 = 0;
+    if (TIMED) ts0 = __builtin_readcyclecounter();
+#endif
+    gload_half(0, 0);
+    gload_half(1, 0);
+    store_half(smem, 0);
+    store_half(smem, 1);
+    gload_half(0, 1);
+    gload_half(1, 1);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    read_frags(smem, 0, fa0, fb0);
+#ifdef GEMM_TIMING
+    if (TIMED) ts1 = __builtin_readcyclecounter();
+#endif
+    for (int kt = 0; kt < n_kt; ++kt) {
+        bf16_t* cur = smem + (kt & 1) * TILE;
+        bf16_t* nxt = smem + ((kt + 1) & 1) * TILE;
+        // instruction order of a step: the fragment reads first, then one LDS write or one memory request in the
+        // shadow of every MFMA (0x100 LDS read, 0x200 LDS write, 0x020 memory read, 0x008 MFMA)
+        constexpr int NR = KB ? 12 : 8;   // LDS reads of one set of fragments
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(cur, 1, fa1, fb1);
+        mfmas(fa0, fb0);
+        store_half(nxt, 0);
+        gload_half(0, kt + 2);
+        __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(cur, 2, fa0, fb0);
+        mfmas(fa1, fb1);
+        store_half(nxt, 1);
+        gload_half(1, kt + 2);
+        __builtin_amdgcn_sched_group_barrier(0x100, NR, 1);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 1);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(cur, 3, fa1, fb1);
+        mfmas(fa0, fb0);
+        __builtin_amdgcn_sched_group_barrier(0x100, NR, 2);
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        read_frags(nxt, 0, fa0, fb0);
+        mfmas(fa1, fb1);
+        __builtin_amdgcn_sched_group_barrier(0x100, NR, 3);
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 3);
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();   // every wave is done with the operand stages (the epilogue reuses them)
+#ifdef GEMM_TIMING
+    if (TIMED) ts2 = __builtin_readcyclecounter();
+#endif
+    gemm_epilogue_direct<MI, NI, EP>(a, acc, g, r0, m0, n0, M, N, wm0, wn0, lane);
+#ifdef GEMM_TIMING
+    if (TIMED && tid == 0 && tile < 16384) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        g_gemm_ts[4 * tile] = ts0; g_gemm_ts[4 * tile + 1] = ts1; g_gemm_ts[4 * tile + 2] = ts2;
+        g_gemm_ts[4 * tile + 3] = __builtin_readcyclecounter();
+    }
+#endif
 }
 
-template <int BM, int BN, bool DB, bool KA = false, bool KB = false>
-static void launch_variant(hipStream_t st, const GemmBArgs& a) {
-    const int n_ntiles = (a.N + BN - 1) / BN;
+static void tile_counts(const GemmBArgs& a, int BM, int BN, int& n_ntiles, int& mt_per_group, int64_t& n_tiles) {
+    n_ntiles = (a.N + BN - 1) / BN;
     int64_t n_mtiles;
-    int mt_per_group = 1;
+    mt_per_group = 1;
     if (a.tile_group) {
         n_mtiles = a.n_mtiles;
     } else {
         mt_per_group = (a.M + BM - 1) / BM;
         n_mtiles = (int64_t)mt_per_group * a.G;
     }
-    if (n_mtiles <= 0 || n_ntiles <= 0) return;
-    const int64_t n_tiles = n_mtiles * n_ntiles;
-    size_t shmem = ((KA ? (size_t)GK * (BM + GPADK) : (size_t)BM * GLD) + (KB ? (size_t)GK * (BN + GPADK) : (size_t)BN * GLD)) * sizeof(bf16_t) * (DB ? 2 : 1);
-    constexpr int WN = BN > 128 ? BN / 64 : 2, NT = 2 * WN * 64;
-    const size_t epi = (size_t)(2 * WN) * 32 * (BN / WN + 4) * sizeof(float);  // the epilogue's strips, one per wave
-    if (shmem < epi) shmem = epi;
-    auto kern = gemm_bf16_kernel<BM, BN, DB, KA, KB>;
-    if (shmem > 48 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
-    const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
+    n_tiles = (n_mtiles <= 0 || n_ntiles <= 0) ? 0 : n_mtiles * n_ntiles;
 }
 
-// bm: row tile the caller built its (tile_group, tile_m0) lists for (64, 128 or 256).  Measured on the
-// benchmark shapes: one LDS stage with register prefetch beats two stages (occupancy), and 256x128 beats
-// 128x128 and 256x256 when a task has enough rows; the weight-gradient set-up (fixed M, K = rows of a
-// task) is bound by the theta' it writes and keeps 128x128.
-// bn: 128 or 256 (256 only with bm = 256: eight waves, for products that are bound by the matrix cores)
+template <bool KB, int EP, bool TIMED = false>
+static void launch_pipe(hipStream_t st, const GemmBArgs& a) {
+    constexpr int BM = 256, BN = 256;
+    int n_ntiles, mt_per_group;
+    int64_t n_tiles;
+    tile_counts(a, BM, BN, n_ntiles, mt_per_group, n_tiles);
+    if (n_tiles <= 0) return;
+    const size_t shmem = ((size_t)BM * GLD + (KB ? (size_t)GK * (BN + GPADK) : (size_t)BN * GLD)) * sizeof(bf16_t) * 2;
+    auto kern = gemm_bf16_pipe_kernel<KB, EP, TIMED>;
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
+}
+
+template <int BM, int BN, bool KA, bool KB, int EP>
+static void launch_variant(hipStream_t st, const GemmBArgs& a) {
+    int n_ntiles, mt_per_group;
+    int64_t n_tiles;
+    tile_counts(a, BM, BN, n_ntiles, mt_per_group, n_tiles);
+    if (n_tiles <= 0) return;
+    size_t shmem = ((KA ? (size_t)GK * (BM + GPADK) : (size_t)BM * GLD) + (KB ? (size_t)GK * (BN + GPADK) : (size_t)BN * GLD)) * sizeof(bf16_t);
+    const size_t epi = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);  // the epilogue's strips, one per wave
+    if (shmem < epi) shmem = epi;
+    auto kern = gemm_bf16_kernel<BM, BN, false, KA, KB, EP>;
+    if (shmem > 48 * 1024) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+    const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
+}
+
+// Tile shapes of one operand form.  bm: row tile the caller built its (tile_group, tile_m0) lists for (64, 128 or
+// 256); bn: 128, or 256 (with bm = 256: the pipelined 256 x 256 kernel).  Measured on the benchmark shapes: one LDS
+// stage with register prefetch beats two stages for the smaller tiles (occupancy); the weight-gradient form (fixed M,
+// K = rows of a task) is bound by the theta' it writes and keeps 128 x 128.
+template <bool KB, int EP>
+static void launch_rows_form(hipStream_t st, const GemmBArgs& a, int bm, int bn) {
+    if (bm == 256 && bn == 256) launch_pipe<KB, EP>(st, a);
+    else if (bm == 256) launch_variant<256, 128, false, KB, EP>(st, a);
+    else if (bm == 128) launch_variant<128, 128, false, KB, EP>(st, a);
+    else launch_variant<64, 128, false, KB, EP_RUNTIME>(st, a);
+}
+
+// backward form: both operands contraction-contiguous
 void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm, int bn) {
-    if (bm == 64) launch_variant<64, 128, false>(st, a);
-    else if (bm == 256 && bn == 256) launch_variant<256, 256, false>(st, a);
-    else if (bm == 256) launch_variant<256, 128, false>(st, a);
-    else launch_variant<128, 128, false>(st, a);
+    switch (ep_of(a)) {
+        case EPI_MASK | EP_CB: launch_rows_form<false, EPI_MASK | EP_CB>(st, a, bm, bn); break;
+        case EPI_NONE | EP_CF: launch_rows_form<false, EPI_NONE | EP_CF>(st, a, bm, bn); break;
+        case EPI_NONE | EP_CF | EP_CACC: launch_rows_form<false, EPI_NONE | EP_CF | EP_CACC>(st, a, bm, bn); break;
+        case EPI_NONE | EP_CACC: launch_rows_form<false, EPI_NONE | EP_CACC>(st, a, bm, bn); break;
+        default: launch_rows_form<false, EP_RUNTIME>(st, a, bm, bn); break;
+    }
 }
 
 // Weight-gradient form: both operands stored with the contraction index slowest (A [K, M], B [K, N]).
-void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a) { launch_variant<128, 128, false, true, true>(st, a); }
+void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a) {
+    switch (ep_of(a)) {
+        case EPI_AXPBY | EP_CF: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CF>(st, a); break;
+        case EPI_AXPBY | EP_CF | EP_CB: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CF | EP_CB>(st, a); break;
+        case EPI_AXPBY | EP_CF | EP_CIN: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CF | EP_CIN>(st, a); break;
+        case EPI_AXPBY | EP_CF | EP_CB | EP_CIN: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CF | EP_CB | EP_CIN>(st, a); break;
+        case EPI_AXPBY | EP_CB | EP_CIN: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CB | EP_CIN>(st, a); break;
+        default: launch_variant<128, 128, true, true, EP_RUNTIME>(st, a); break;
+    }
+}
 
 // Forward form with the weights as they are stored (B [K, N] = W [d_in, d_out]): no transposed copy of theta.
 void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm, int bn) {
-    if (bm == 64) launch_variant<64, 128, false, false, true>(st, a);
-    else if (bm == 256 && bn == 256) launch_variant<256, 256, false, false, true>(st, a);
-    else if (bm == 256) launch_variant<256, 128, false, false, true>(st, a);
-    else launch_variant<128, 128, false, false, true>(st, a);
+    switch (ep_of(a)) {
+        case EPI_BIAS_RELU | EP_CB: launch_rows_form<true, EPI_BIAS_RELU | EP_CB>(st, a, bm, bn); break;
+        case EPI_BIAS_MASK | EP_CB: launch_rows_form<true, EPI_BIAS_MASK | EP_CB>(st, a, bm, bn); break;
+        default: launch_rows_form<true, EP_RUNTIME>(st, a, bm, bn); break;
+    }
 }
+
+#ifdef GEMM_TIMING
+void launch_gemm_bf16_timed(hipStream_t st, const GemmBArgs& a, bool kb) {   // development: per-phase cycle counts of the pipelined kernel
+    if (kb) launch_pipe<true, EPI_BIAS_RELU | EP_CB, true>(st, a);
+    else launch_pipe<false, EPI_MASK | EP_CB, true>(st, a);
+}
+#endif
 
 // fp32 padded weights [rows, cols] -> bf16 W [rows, cols] and W^T [cols, rows], per group
 __global__ void convert_weights_kernel(const float* __restrict__ src, int64_t g_src, int rows, int cols, bf16_t* w,

@@ -221,7 +221,7 @@ struct GemmBArgs {
     float* Cacc; int64_t ldcacc, rCacc; float cacc;  // Cacc[(r0 + m)*ldcacc + n] += cacc * value (not with EPI_AXPBY + Cin)
     int cacc_init;                                   // 1: Cacc is not read, = cacc * value (first term of a sum)
 };
-void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm, int bn = 128);
+void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm, int bn = 128);   // bn = 256 (with bm = 256): the pipelined 256 x 256 kernel
 // same product with both operands stored contraction-slowest: A_p element (k, m) at A + g*gA + r0*rA + k*lda + m,
 // B_p element (k, n) at B + g*gB + r0*rB + k*ldb + n
 void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a);

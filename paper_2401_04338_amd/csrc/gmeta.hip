@@ -724,11 +724,13 @@ struct Grp {  // grouping of one set's rows by task inside the wave
 };
 
 
-// column tile of a forward / backward product: 256 (eight waves) needs 256-row tiles and at least 256 columns
-static int gemm_bn(const gm_ctx* c, int bm, int N) {
-    if (bm != 256 || N < 256) return 128;
+// column tile of a forward / backward product.  256 selects the pipelined 256 x 256 kernel (256-row tiles, a multiple of
+// 256 columns): it wins where the contraction is long enough to pay for its unhidden prologue and epilogue (one
+// workgroup per compute unit), measured from about 2,048 on; results are identical either way.
+static int gemm_bn(const gm_ctx* c, int bm, int N, int K) {
+    if (bm != 256 || N < 256 || N % 256 != 0) return 128;
     if (c->gemm_tile_n) return c->gemm_tile_n;
-    return 128;
+    return K >= 2048 ? 256 : 128;
 }
 
 // out[rows, ld_l] = epi( sum_p in_p[rows, ld_{l-1}] * W_p,l + bias )
@@ -770,7 +772,7 @@ static void dense_nn(gm_ctx* c, const Grp& g, int l, int np, const Act* in0, con
         a.tile_group = g.tile_g; a.tile_m0 = g.tile_m; a.n_mtiles = g.n_mtiles;
         a.epi = epi; a.bias = bias; a.gBias = bias_stride;
         if (mask) { a.mask = mask->b; a.ld_mask = mask->ld; }
-        launch_gemm_bf16_bkmajor(c->stream, a, g.bm, gemm_bn(c, g.bm, N));
+        launch_gemm_bf16_bkmajor(c->stream, a, g.bm, gemm_bn(c, g.bm, N, K * np));
     }
 }
 
@@ -822,7 +824,7 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
         } else {
             a.Cb = out->b; a.ldcb = N; a.rCb = N; a.epi = EPI_MASK; a.mask = mask->b; a.ld_mask = mask->ld;
         }
-        launch_gemm_bf16(c->stream, a, g.bm, gemm_bn(c, g.bm, N));
+        launch_gemm_bf16(c->stream, a, g.bm, gemm_bn(c, g.bm, N, K * np));
     }
 }
 
