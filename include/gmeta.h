@@ -111,7 +111,14 @@ size_t gm_workspace_bytes(const gm_model_desc* model, int32_t n_tasks, int64_t n
                           int32_t inner_steps, int32_t order);
 
 /* The whole step (Alg. 1 from the prefetch step to the two global back-propagation steps, without
- * the beta update).  loss: DEVICE scalar = sum_t L^Query_t.  order in {1,2}; inner_steps >= 0. */
+ * the beta update).  loss: DEVICE scalar = sum_t L^Query_t.  order in {1,2}; inner_steps >= 0.
+ * Size limits of a well-formed call (each reported as GM_ERR_CAPACITY with its own message, never as GM_ERR_INDEX):
+ *   a bag holds at most 65,535 lookups and a task at most 65,536 samples per set;
+ *   with the row-list output each set holds fewer than 2^31 lookups (any number with emb_grad_table);
+ *   when the inner loop adapts embedding rows (inner_steps > 0, "adapt_rows" = 1, at least one field): a (task,
+ *   field) holds at most 16,384 lookups per set, and a task at most 2,048 samples per set (rounded up to a
+ *   multiple of 8 with bf16 operands);
+ *   all tables together hold fewer than 2^32 rows, and one call fewer than 2^31 (sample, field) bags per set. */
 int gm_meta_step(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_set* query,
                  const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
                  float* loss, gm_grads* out);

@@ -120,8 +120,20 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
-def _set_struct(s) -> gm_set:
+def _checked(t: torch.Tensor, dtype, name: str, device=None) -> torch.Tensor:
+    """The library reads raw pointers: a tensor of another type, layout or device would be misread silently."""
+    if t.dtype != dtype or not t.is_contiguous() or not t.is_cuda or (device is not None and t.device != device):
+        raise ValueError(f"{name} must be a contiguous {dtype} tensor on {device or 'the GPU'} "
+                         f"(got {t.dtype}, contiguous={t.is_contiguous()}, device={t.device})")
+    return t
+
+
+def _set_struct(s, device=None) -> gm_set:
     """s: an object with task_offsets (host numpy int64), bag_offsets, indices, dense, labels (device tensors)."""
+    _checked(s.bag_offsets, torch.int64, "bag_offsets", device)
+    _checked(s.indices, torch.int32, "indices", device)
+    _checked(s.dense, torch.float32, "dense", device)
+    _checked(s.labels, torch.float32, "labels", device)
     toff = np.ascontiguousarray(np.asarray(s.task_offsets, dtype=np.int64))
     st = gm_set(int(toff[-1]), int(s.indices.numel()), toff.ctypes.data_as(C.POINTER(C.c_int64)),
                 _ptr(s.bag_offsets), _ptr(s.indices), _ptr(s.dense), _ptr(s.labels))
@@ -175,6 +187,20 @@ class GMeta:
         if rc != GM_OK:
             raise GMetaError(rc, self.lib.gm_last_error(self._ctx).decode())
 
+    def _check_params(self, params):
+        L = len(self.layer_dims) - 1
+        if self.n_fields > 0:
+            _checked(params.emb, torch.float32, "params.emb", self.device)
+            if tuple(params.emb.shape) != (int(sum(self.rows_per_field)), self.emb_dim):
+                raise ValueError("params.emb must be [sum rows_per_field, emb_dim]")
+        if len(params.W) != L or len(params.b) != L:
+            raise ValueError("params.W / params.b must hold one tensor per layer")
+        for l in range(L):
+            _checked(params.W[l], torch.float32, f"params.W[{l}]", self.device)
+            _checked(params.b[l], torch.float32, f"params.b[{l}]", self.device)
+            if tuple(params.W[l].shape) != (self.layer_dims[l], self.layer_dims[l + 1]) or params.b[l].numel() != self.layer_dims[l + 1]:
+                raise ValueError(f"layer {l}: W must be [{self.layer_dims[l]}, {self.layer_dims[l + 1]}] and b [{self.layer_dims[l + 1]}]")
+
     # ------------------------------------------------------------------ entry points
     def alloc_outputs(self, n_tasks: int, emb_rows_capacity: int) -> Dict[str, object]:
         dev, L = self.device, len(self.layer_dims) - 1
@@ -209,7 +235,8 @@ class GMeta:
                 cap = min(int(support.indices.numel() + query.indices.numel()), int(sum(self.rows_per_field)))
             out = self.alloc_outputs(n_tasks, cap)
         L = len(self.layer_dims) - 1
-        ss, qs = _set_struct(support), _set_struct(query)
+        ss, qs = _set_struct(support, self.device), _set_struct(query, self.device)
+        self._check_params(params)
         Wp = (C.c_void_p * L)(*[w.data_ptr() for w in params.W])
         bp = (C.c_void_p * L)(*[x.data_ptr() for x in params.b])
         ps = gm_params(_ptr(params.emb), Wp, bp)
@@ -232,7 +259,8 @@ class GMeta:
         L = len(self.layer_dims) - 1
         if loss is None:
             loss = torch.empty(1, dtype=torch.float32, device=self.device)
-        ss, qs = _set_struct(support), _set_struct(query)
+        ss, qs = _set_struct(support, self.device), _set_struct(query, self.device)
+        self._check_params(params)
         Wp = (C.c_void_p * L)(*[w.data_ptr() for w in params.W])
         bp = (C.c_void_p * L)(*[x.data_ptr() for x in params.b])
         ps = gm_params(_ptr(params.emb), Wp, bp)
@@ -279,14 +307,15 @@ class GMeta:
 
     def gather_pool(self, set_, emb: torch.Tensor) -> torch.Tensor:
         n_tasks = len(set_.task_offsets) - 1
-        st = _set_struct(set_)
+        st = _set_struct(set_, self.device)
+        _checked(emb, torch.float32, "emb", self.device)
         x = torch.empty(max(st.n_samples, 1), self.layer_dims[0], dtype=torch.float32, device=self.device)
         self._check(self.lib.gm_gather_pool(self._ctx, n_tasks, C.byref(st), _ptr(emb), _ptr(x)))
         return x[: st.n_samples]
 
     def index_prep(self, support, query, emb_rows_capacity: Optional[int] = None):
         n_tasks = len(support.task_offsets) - 1
-        ss, qs = _set_struct(support), _set_struct(query)
+        ss, qs = _set_struct(support, self.device), _set_struct(query, self.device)
         dev, F = self.device, self.n_fields
         cap = emb_rows_capacity
         if cap is None:

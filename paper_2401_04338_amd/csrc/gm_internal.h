@@ -22,7 +22,7 @@ __device__ __forceinline__ float bf2f(bf16_t h) { return __builtin_bit_cast(floa
 #endif
 
 // Device-side status word indices (ctx->d_status).
-enum { ST_BAD_INDEX = 0, ST_CAPACITY = 1, ST_MAX_TF = 2, ST_NROWS = 3, ST_MAX_BAG = 4, ST_PAIR_OVF = 5, ST_WORDS = 8 };
+enum { ST_BAD_INDEX = 0, ST_CAPACITY = 1, ST_MAX_TF = 2, ST_NROWS = 3, ST_MAX_BAG = 4, ST_PAIR_OVF = 5, ST_TOO_LARGE = 6, ST_WORDS = 8 };
 
 // ------------------------------------------------------------------ index kernels
 // Per-wave geometry handed to the index kernels (all device pointers).

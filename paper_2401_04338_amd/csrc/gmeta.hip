@@ -1089,6 +1089,8 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
     int rc = read_status(c, hs);
     if (rc != GM_OK) return rc;
     if (hs[ST_BAD_INDEX]) return fail(c, GM_ERR_INDEX, "index outside its table, or bag_offsets not monotone / beyond nnz");
+    if (hs[ST_TOO_LARGE])
+        return fail(c, GM_ERR_CAPACITY, "a bag has more than 65535 lookups, or a task more than 65536 samples in one set");
     int cap = 1024;
     while (cap < (int)hs[ST_MAX_TF]) cap <<= 1;
     if (cap_out) *cap_out = cap;
@@ -2070,6 +2072,8 @@ extern "C" int gm_gather_pool(gm_ctx* c, int32_t T, const gm_set* set, const flo
     rc = read_status(c, hs);
     if (rc != GM_OK) return rc;
     if (hs[ST_BAD_INDEX]) return fail(c, GM_ERR_INDEX, "index outside its table, or bag_offsets not monotone / beyond nnz");
+    if (hs[ST_TOO_LARGE])
+        return fail(c, GM_ERR_CAPACITY, "a bag has more than 65535 lookups, or a task more than 65536 samples in one set");
     // process in chunks of samples that fit the workspace
     const size_t mark = ar.off;
     const int ld0 = c->ld[0], d0 = c->dims[0];

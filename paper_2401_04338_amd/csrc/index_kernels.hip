@@ -41,26 +41,33 @@ __device__ __forceinline__ int block_excl_scan(int v, int* sh, int* total) {
 // ------------------------------------------------------------------------------------------------
 // validation + per-(task, field) lookup counts
 // ------------------------------------------------------------------------------------------------
+// One task per blockIdx.x, its bags dealt to gridDim.y workgroups; cnt_sup / cnt_qry must be zero on entry.
+// A well-formed input that exceeds a size limit of the index kernels (a bag of more than 65,535 lookups, a task of more
+// than 65,536 samples in one set) raises ST_TOO_LARGE, not ST_BAD_INDEX.
 __global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const int64_t* field_base,
                                 int64_t nnz_sup, int64_t nnz_qry, u32* cnt_sup, u32* cnt_qry, u32* status) {
     extern __shared__ u32 sh_cnt[];  // [2F]
     const int t = blockIdx.x;
     for (int i = threadIdx.x; i < 2 * F; i += blockDim.x) sh_cnt[i] = 0;
     __syncthreads();
-    bool bad = false;
+    bool bad = false, too_large = false;
     u32 longest = 0;
     for (int set = 0; set < 2; ++set) {
         const SetView& v = set ? qry : sup;
         const int64_t nnz = set ? nnz_qry : nnz_sup;
         const int64_t s_lo = v.task_offsets[t0 + t], s_hi = v.task_offsets[t0 + t + 1];
-        if (s_hi - s_lo > 65536) bad = true;
+        if (s_hi - s_lo > 65536) too_large = true;
         const int64_t n = (s_hi - s_lo) * F;
-        for (int64_t i = threadIdx.x; i < n; i += blockDim.x) {
+        for (int64_t i = (int64_t)blockIdx.y * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.y * blockDim.x) {
             const int64_t bag = s_lo * F + i;
             const int f = (int)(i % F);
             const int64_t p0 = v.bag_offsets[bag], p1 = v.bag_offsets[bag + 1];
-            if (p0 < 0 || p1 < p0 || p1 > nnz || p1 - p0 > 65535) {
+            if (p0 < 0 || p1 < p0 || p1 > nnz) {
                 bad = true;
+                continue;
+            }
+            if (p1 - p0 > 65535) {
+                too_large = true;
                 continue;
             }
             const int64_t R = field_base[f + 1] - field_base[f];
@@ -72,27 +79,31 @@ __global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const i
             longest = max(longest, (u32)(p1 - p0));
         }
     }
-    if (t == 0 && threadIdx.x == 0) {  // the ends of both offset arrays
+    if (t == 0 && blockIdx.y == 0 && threadIdx.x == 0) {  // the ends of both offset arrays
         if (sup.bag_offsets[0] != 0 || sup.bag_offsets[sup.n_samples * F] != nnz_sup) bad = true;
         if (qry.bag_offsets[0] != 0 || qry.bag_offsets[qry.n_samples * F] != nnz_qry) bad = true;
     }
     __syncthreads();
-    u32 mx = 0;
     for (int i = threadIdx.x; i < 2 * F; i += blockDim.x) {
         const u32 c = sh_cnt[i];
-        if (i < F) cnt_sup[(size_t)t * F + i] = c;
-        else cnt_qry[(size_t)t * F + (i - F)] = c;
-        mx = max(mx, c);
+        if (!c) continue;
+        u32* dst = i < F ? &cnt_sup[(size_t)t * F + i] : &cnt_qry[(size_t)t * F + (i - F)];
+        const u32 whole = atomicAdd(dst, c) + c;     // the (task, field)'s count so far: the last adder sees the total
+        atomicMax(&status[ST_MAX_TF], whole);
     }
-    if (mx) atomicMax(&status[ST_MAX_TF], mx);
     if (longest) atomicMax(&status[ST_MAX_BAG], longest);
     if (bad) atomicOr(&status[ST_BAD_INDEX], 1u);
+    if (too_large) atomicOr(&status[ST_TOO_LARGE], 1u);
 }
 
 void launch_tf_count(hipStream_t st, int F, int t0, int Tw, SetView sup, SetView qry, const int64_t* field_base,
                      int64_t nnz_sup, int64_t nnz_qry, u32* cnt_sup, u32* cnt_qry, u32* status) {
     if (Tw <= 0) return;
-    hipLaunchKernelGGL(tf_count_kernel, dim3(Tw), dim3(256), 2 * F * sizeof(u32), st, F, t0, sup, qry, field_base,
+    launch_fill_u32(st, cnt_sup, (int64_t)Tw * F, 0u);
+    if (cnt_qry != cnt_sup) launch_fill_u32(st, cnt_qry, (int64_t)Tw * F, 0u);
+    // enough workgroups to fill the chip whatever the number of tasks in the wave
+    const int split = Tw >= 2048 ? 1 : (Tw >= 512 ? 4 : 8);
+    hipLaunchKernelGGL(tf_count_kernel, dim3(Tw, split), dim3(256), 2 * F * sizeof(u32), st, F, t0, sup, qry, field_base,
                        nnz_sup, nnz_qry, cnt_sup, cnt_qry, status);
 }
 

@@ -307,6 +307,25 @@ def test_error_paths(gm):
     with pytest.raises(GMetaError) as e:
         ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), p, 0.1, 1, 3)
     assert e.value.code == -1
+    # a well-formed input beyond a size limit is a capacity error, not an index error: one bag of 70,000 lookups
+    from synth.generate import SetData
+    big = _to_dev(sup, dev)
+    extra = 70000
+    offs = big.bag_offsets.clone()
+    offs[1:] += extra
+    big = SetData(big.task_offsets, offs, torch.cat([torch.zeros(extra, dtype=torch.int32, device=dev), big.indices]),
+                  big.dense, big.labels)
+    with pytest.raises(GMetaError) as e:
+        ctx.meta_step(big, _to_dev(qry, dev), p, 0.1, 1, 2)
+    assert e.value.code == -3 and "65535" in str(e.value)
+    # tensors of another type or layout are refused by the binding before the library would misread them
+    wrong = _to_dev(sup, dev)
+    wrong.indices = wrong.indices.long()
+    with pytest.raises(ValueError):
+        ctx.meta_step(wrong, _to_dev(qry, dev), p, 0.1, 1, 2)
+    from synth.generate import Params
+    with pytest.raises(ValueError):
+        ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), Params(p.emb.t().contiguous().t(), p.W, p.b), 0.1, 1, 2)
     # the context still works after errors
     _compare_step(cfg, ctx, sup, qry, params, 1, 2, TOL_FP32, "after-errors")
     ctx.close()
