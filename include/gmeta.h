@@ -240,12 +240,15 @@ int gm_profile(gm_ctx* ctx, int enable);
 const char* gm_profile_report(gm_ctx* ctx);
 
 /* On-box ceilings for measurement harnesses (not part of the method): a streaming copy (bytes read + written per
- * second), a streaming read and a register-resident v_mfma_f32_32x32x16_bf16 loop, each run by a kernel of the
- * library's own on the context's workspace (at least 130 MiB; up to 2 GiB per buffer are used) and timed with HIP
- * events: the best of several repetitions.  Outputs are HOST: GB/s, GB/s, TFLOP/s, and (if not NULL) the bytes of one
+ * second), a streaming read, and a register-resident v_mfma_f32_32x32x16_bf16 loop with constant operands and with
+ * operands that change from one instruction to the next (pseudo-random values of the magnitude of activations and
+ * weights: the rate the matrix cores sustain on real data), each run by a kernel of the library's own on the
+ * context's workspace (at least 130 MiB; up to 2 GiB per buffer are used) and timed with HIP events: the best of
+ * several repetitions.  Outputs are HOST: GB/s, GB/s, TFLOP/s, TFLOP/s, and (if not NULL) the bytes of one
  * buffer -- every stream_copy_kernel dispatch of the call reads that many bytes and writes as many, which gives
  * profiler byte counters a transfer of known size to be scaled by. */
-int gm_ceilings(gm_ctx* ctx, double* copy_gbs, double* read_gbs, double* mfma_tflops, int64_t* buffer_bytes);
+int gm_ceilings(gm_ctx* ctx, double* copy_gbs, double* read_gbs, double* mfma_tflops, double* mfma_random_tflops,
+                int64_t* buffer_bytes);
 
 #ifdef __cplusplus
 }

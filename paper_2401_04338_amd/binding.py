@@ -103,7 +103,7 @@ def load_library() -> C.CDLL:
     lib.gm_profile_report.argtypes = [C.c_void_p]
     lib.gm_ceilings.restype = C.c_int
     lib.gm_ceilings.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
-                                C.POINTER(C.c_int64)]
+                                C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _lib = lib
     return lib
 
@@ -352,11 +352,12 @@ class GMeta:
         return out
 
     def ceilings(self) -> Dict[str, float]:
-        """gm_ceilings: {"copy_GBps", "read_GBps", "mfma_bf16_TFLOPs", "copy_buffer_bytes"} measured on this GPU with the
-        library's own kernels."""
-        a, b, m, n = C.c_double(0), C.c_double(0), C.c_double(0), C.c_int64(0)
-        self._check(self.lib.gm_ceilings(self._ctx, C.byref(a), C.byref(b), C.byref(m), C.byref(n)))
-        return {"copy_GBps": a.value, "read_GBps": b.value, "mfma_bf16_TFLOPs": m.value, "copy_buffer_bytes": n.value}
+        """gm_ceilings: streaming copy / read rates and the register-resident bf16 MFMA rate (constant operands, and
+        operands that toggle like real data) measured on this GPU with the library's own kernels."""
+        a, b, m, r, n = C.c_double(0), C.c_double(0), C.c_double(0), C.c_double(0), C.c_int64(0)
+        self._check(self.lib.gm_ceilings(self._ctx, C.byref(a), C.byref(b), C.byref(m), C.byref(r), C.byref(n)))
+        return {"copy_GBps": a.value, "read_GBps": b.value, "mfma_bf16_TFLOPs": m.value,
+                "mfma_bf16_TFLOPs_toggling_operands": r.value, "copy_buffer_bytes": n.value}
 
     def scatter_add(self, table: torch.Tensor, rows: torch.Tensor, grad: torch.Tensor, scale: float):
         self._check(self.lib.gm_scatter_add(self._ctx, _ptr(table), _ptr(rows), _ptr(grad), int(rows.numel()),

@@ -269,3 +269,4 @@ void launch_fill_f32(hipStream_t st, float* p, int64_t n, float v);
 void launch_stream_copy(hipStream_t st, const void* src, void* dst, int64_t bytes);
 void launch_stream_read(hipStream_t st, const void* src, int64_t bytes, u32* sink);
 double launch_mfma_loop(hipStream_t st, int iters, float* sink);   // returns the flops of the launch
+double launch_mfma_loop_random(hipStream_t st, int iters, float* sink);

@@ -590,9 +590,10 @@ extern "C" const char* gm_profile_report(gm_ctx* c) {
 
 // Streaming and matrix-core ceilings of this GPU, measured with kernels of the library's own on the context's
 // workspace (whose contents are scratch between calls anyway).
-extern "C" int gm_ceilings(gm_ctx* c, double* copy_gbs, double* read_gbs, double* mfma_tflops, int64_t* buffer_bytes) {
+extern "C" int gm_ceilings(gm_ctx* c, double* copy_gbs, double* read_gbs, double* mfma_tflops, double* mfma_random_tflops,
+                           int64_t* buffer_bytes) {
     if (!c) return GM_ERR_ARG;
-    if (!copy_gbs || !read_gbs || !mfma_tflops) return fail(c, GM_ERR_ARG, "null outputs");
+    if (!copy_gbs || !read_gbs || !mfma_tflops || !mfma_random_tflops) return fail(c, GM_ERR_ARG, "null outputs");
     HIPCHK(c, hipSetDevice(c->device));
     hipStream_t st = c->stream;
     const size_t avail = (c->ws_bytes - c->persistent) / 2 / 4096 * 4096;
@@ -628,7 +629,11 @@ extern "C" int gm_ceilings(gm_ctx* c, double* copy_gbs, double* read_gbs, double
         *read_gbs = (double)bytes / (ms * 1e-3) / 1e9;
         double flops = 0.0;
         rc = timed([&] { flops = launch_mfma_loop(st, 20000, reinterpret_cast<float*>(b)); }, 3, &ms);
-        if (rc == GM_OK) *mfma_tflops = flops / (ms * 1e-3) / 1e12;
+        if (rc == GM_OK) {
+            *mfma_tflops = flops / (ms * 1e-3) / 1e12;
+            rc = timed([&] { flops = launch_mfma_loop_random(st, 40000, reinterpret_cast<float*>(b)); }, 3, &ms);
+            if (rc == GM_OK) *mfma_random_tflops = flops / (ms * 1e-3) / 1e12;
+        }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
