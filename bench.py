@@ -160,8 +160,8 @@ def main():
     cap_rows = 0 if table is not None else min(nnz, cfg.total_rows)
     out_bytes = cap_rows * (cfg.emb_dim * 4 + 8)
     ws = int(need * 1.02)
-    if args.train is not None:   # the meta-gradient lists then live in the workspace, not in caller buffers
-        ws += out_bytes + (1 << 20)
+    if args.train is not None:   # the meta-gradient lists and a second set of index structures then live in the workspace
+        ws += 2 * out_bytes + int(need * 0.35) + (64 << 20)
         if table is not None:
             print("--train uses the row-list output (fewer than 2^31 lookups per set)", file=sys.stderr)
             sys.exit(2)
@@ -186,12 +186,22 @@ def main():
             return out
         return ctx.meta_step(s, q, params, cfg.inner_lr, K, order, out=out, emb_grad_table=table)
 
-    for i in range(args.warmup):
-        step(i)
+    def train_loop(n):   # n iterations of Alg. 1 in one call (gm_meta_train), cycling through the batches
+        losses = ctx.meta_train([batches[i % len(batches)] for i in range(n)], params, cfg.inner_lr, K, order, args.train)
+        out["loss"][:1] = losses[-1:]
+
+    if args.train is not None:
+        train_loop(max(args.warmup, 1))
+    else:
+        for i in range(args.warmup):
+            step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    if args.train is not None:
+        train_loop(args.steps)
+    else:
+        for i in range(args.steps):
+            step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
@@ -307,7 +317,8 @@ def main():
         "config": {"workload": cfg.name, "n_tasks": cfg.n_tasks, "samples_per_step": S, "lookups_per_step": nnz,
                    "n_fields": cfg.n_fields, "rows_per_field": cfg.rows_per_field, "emb_dim": cfg.emb_dim,
                    "mlp": list(cfg.layer_dims), "inner_steps": K, "order": order, "inner_lr": cfg.inner_lr,
-                   "outer_update": None if args.train is None else {"fused": True, "outer_lr": args.train},
+                   "outer_update": None if args.train is None else {"fused": True, "outer_lr": args.train,
+                                                                     "loop": "gm_meta_train: one call per timed region"},
                    "sparse_out": sparse_out, "configure": args.configure, "workspace_gib": ctx_ws / 2 ** 30,
                    "tasks_per_wave": tasks_per_wave, "batches_cycled": len(batches), "loss": loss,
                    "input_generation_s": gen_s, "inputs": "loaded" if args.load_inputs else "generated"},

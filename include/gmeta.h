@@ -152,6 +152,23 @@ int gm_meta_train_step(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, cons
                        const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
                        float outer_lr, float* loss, float* task_loss);
 
+/* n_iters iterations of Alg. 1 on one shard in one call: iteration i is gm_meta_train_step on (support[i], query[i]),
+ * and the parameters after the call are bit for bit those of n_iters such calls in a row.  What the call adds is the
+ * overlap of Alg. 1's outer loop as a sustained training loop: everything of batch i+1 that depends on its indices
+ * only (validation, per-(task, field) row dictionaries and overlap join of Sec. 2.1.2, pair-count matrices, the order
+ * of all lookups by row for the sparse gradient) is prepared on the context's second stream while batch i computes,
+ * and the step itself then runs without a host synchronisation.
+ * n_tasks: HOST [n_iters]; support, query: HOST arrays of n_iters gm_set (each as for gm_meta_step, row-list form:
+ * fewer than 2^31 lookups per batch); params: updated in place; losses: DEVICE [n_iters], the loss of every step
+ * before its update; n_done: HOST, iterations applied when the call returns (all of them on GM_OK; on an error the
+ * failing iteration and the ones after it have not been applied), or NULL.
+ * The overlap needs every batch to run as one wave of tasks and the workspace to hold, beside the dense buffers of
+ * one batch, the index structures of two batches and the meta-gradient lists; otherwise the iterations simply run one
+ * after the other (same results).  The "overlap_sort" / "overlap_pairs" settings are ignored during the call. */
+int gm_meta_train(gm_ctx* ctx, int32_t n_iters, const int32_t* n_tasks, const gm_set* support, const gm_set* query,
+                  const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order, float outer_lr,
+                  float* losses, int32_t* n_done);
+
 /* Output buffers of gm_group_batch for one set.  Capacities are those of the whole stream (a set can at most
  * hold every record): task_offsets n_records + 1, bag_offsets n_records * F + 1, indices nnz, dense
  * n_records * n_dense, labels n_records.  n_samples and nnz are written by the call; afterwards the struct's

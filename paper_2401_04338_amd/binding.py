@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libgmeta.so")
 GM_OK, GM_ERR_ARG, GM_ERR_INDEX, GM_ERR_CAPACITY, GM_ERR_WORKSPACE, GM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["gm_create", "gm_destroy", "gm_last_error", "gm_workspace_bytes", "gm_meta_step", "gm_meta_step_static",
-           "gm_meta_train_step", "gm_group_batch", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report", "gm_ceilings"]
+           "gm_meta_train_step", "gm_meta_train", "gm_group_batch", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report", "gm_ceilings"]
 
 
 class gm_model_desc(C.Structure):
@@ -83,6 +83,10 @@ def load_library() -> C.CDLL:
     lib.gm_meta_train_step.restype = C.c_int
     lib.gm_meta_train_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set), C.POINTER(gm_params),
                                        C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
+    lib.gm_meta_train.restype = C.c_int
+    lib.gm_meta_train.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(gm_set), C.POINTER(gm_set),
+                                  C.POINTER(gm_params), C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
+                                  C.POINTER(C.c_int32)]
     lib.gm_meta_step.restype = C.c_int
     lib.gm_meta_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set),
                                  C.POINTER(gm_params), C.c_float, C.c_int32, C.c_int32, C.c_void_p,
@@ -268,6 +272,36 @@ class GMeta:
                                          int(inner_steps), int(order), float(outer_lr), _ptr(loss), _ptr(task_loss))
         self._check(rc)
         return loss
+
+    def meta_train(self, batches, params, inner_lr: float, inner_steps: int, order: int, outer_lr: float,
+                   losses: Optional[torch.Tensor] = None):
+        """gm_meta_train: one iteration per (support, query) pair of `batches`, parameters updated in place, the index
+        side of each batch prepared while the previous one computes.  Returns the device tensor of the steps' losses."""
+        n = len(batches)
+        L = len(self.layer_dims) - 1
+        if losses is None:
+            losses = torch.empty(max(n, 1), dtype=torch.float32, device=self.device)
+        self._check_params(params)
+        sup = (gm_set * max(n, 1))()
+        qry = (gm_set * max(n, 1))()
+        keep = []
+        nt = (C.c_int32 * max(n, 1))()
+        for i, (s, q) in enumerate(batches):
+            ss, qs = _set_struct(s, self.device), _set_struct(q, self.device)
+            keep.append((ss, qs))
+            for f, _t in gm_set._fields_:
+                setattr(sup[i], f, getattr(ss, f))
+                setattr(qry[i], f, getattr(qs, f))
+            nt[i] = len(s.task_offsets) - 1
+        Wp = (C.c_void_p * L)(*[w.data_ptr() for w in params.W])
+        bp = (C.c_void_p * L)(*[x.data_ptr() for x in params.b])
+        ps = gm_params(_ptr(params.emb), Wp, bp)
+        done = C.c_int32(0)
+        rc = self.lib.gm_meta_train(self._ctx, n, nt, sup, qry, C.byref(ps), float(inner_lr), int(inner_steps), int(order),
+                                    float(outer_lr), _ptr(losses), C.byref(done))
+        self.iterations_done = int(done.value)
+        self._check(rc)
+        return losses[:n]
 
     def group_batch(self, task, batch_id, bag_offsets: torch.Tensor, indices: torch.Tensor, dense: torch.Tensor,
                     labels: torch.Tensor, support_num: int, support_den: int):

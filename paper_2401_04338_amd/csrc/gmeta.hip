@@ -327,9 +327,10 @@ static void alloc_sort(const gm_ctx* c, Arena& ar, SortBufs& so, int64_t nnz, in
     so.seg_partial = need_gx ? ar.get<float>(seg_reduce_partial_floats(nnz, c->D)) : nullptr;
 }
 
-static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& d, int K, int order) {
-    const int L = c->L, F = c->F, D = c->D;
-    const bool bf = c->mlp_dtype != 0;
+// What depends on the indices only (row dictionaries, overlap join, pair-count matrices, and with the table-shaped
+// output the wave's own sort buffers): a batch's can be prepared while another batch computes.
+static void alloc_wave_index(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& d) {
+    const int F = c->F;
     const int64_t TF = (int64_t)d.Tw * F;
     w.row_off_s = ar.get<int32_t>(d.Tw + 1);
     w.row_off_q = ar.get<int32_t>(d.Tw + 1);
@@ -357,6 +358,23 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
     w.qry_sorted = ar.get<int2>(d.nnz_q + 1);
     w.qseg_lo = ar.get<int32_t>(d.nnz_s + 1);
     w.qseg_hi = ar.get<int32_t>(d.nnz_s + 1);
+    w.coarse_off_s = ar.get<int32_t>(COARSE_GROUPS + 1);
+    w.coarse_off_q = ar.get<int32_t>(COARSE_GROUPS + 1);
+    w.pair_mat = nullptr;
+    w.pair_off_ss = w.pair_off_qs = w.pair_off_sq = nullptr;
+    w.task_path = ar.get<u32>(d.Tw + 1);
+    if (d.pair) {
+        w.pair_off_ss = ar.get<int64_t>(d.Tw + 1);
+        w.pair_off_qs = ar.get<int64_t>(d.Tw + 1);
+        w.pair_off_sq = ar.get<int64_t>(d.Tw + 1);
+        w.pair_mat = ar.get<uint8_t>(d.pair_bytes + 64);
+    }
+}
+
+// activations, per-task parameters and gradient buffers of a wave
+static void alloc_wave_dense(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& d, int K, int order) {
+    const int L = c->L;
+    const bool bf = c->mlp_dtype != 0;
     const int ld0 = c->ld[0];
     w.Xs0 = ar.get<float>(d.Ps * ld0);
     w.Xq0 = ar.get<float>(d.Pq * ld0);
@@ -365,8 +383,6 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
     w.dX = ar.get<float>(std::max(d.Ps, d.Pq) * (int64_t)std::max(c->FD, 1) + 4);
     w.loss_q = ar.get<float>(d.Pq + 1);
     w.v = alloc_theta(c, ar, d.Tw, true);
-    w.coarse_off_s = ar.get<int32_t>(COARSE_GROUPS + 1);
-    w.coarse_off_q = ar.get<int32_t>(COARSE_GROUPS + 1);
     w.vsum = Theta{ar.get<float>((int64_t)COARSE_GROUPS * c->n_theta), c->n_theta, nullptr, 0};
     if (!second) w.v.b = nullptr;  // the direction is a GEMM operand only in the second-order pass
     w.Xs_scratch = Act();
@@ -404,7 +420,6 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
         }
     }
     w.Xq = alloc_act(c, ar, d.Pq, ld0);
-    if (!bf && K == 0) { /* fp32 without adaptation reads Xq0 directly */ }
     w.Aq.assign(L, Act());
     w.Dq.assign(L, Act());
     for (int l = 1; l < L; ++l) {
@@ -425,20 +440,16 @@ static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& 
         }
         w.tdL = ar.get<float>(d.Ps + 1);
     }
-    w.pair_mat = nullptr;
-    w.pair_off_ss = w.pair_off_qs = w.pair_off_sq = nullptr;
-    w.task_path = ar.get<u32>(d.Tw + 1);
-    if (d.pair) {
-        w.pair_off_ss = ar.get<int64_t>(d.Tw + 1);
-        w.pair_off_qs = ar.get<int64_t>(d.Tw + 1);
-        w.pair_off_sq = ar.get<int64_t>(d.Tw + 1);
-        w.pair_mat = ar.get<uint8_t>(d.pair_bytes + 64);
-    }
     if (d.table) {
         w.GX = ar.get<float>((d.Ps + d.Pq) * (int64_t)std::max(c->FD, 1) + 4);
         w.n_rows = ar.get<int64_t>(2);
         alloc_sort(c, ar, w.so, d.nnz_s + d.nnz_q, c->field_base[c->F], 0, true);
     }
+}
+
+static void alloc_wave(const gm_ctx* c, Arena& ar, WaveBufs& w, const WaveDims& d, int K, int order) {
+    alloc_wave_index(c, ar, w, d);
+    alloc_wave_dense(c, ar, w, d, K, order);
 }
 
 struct BatchBufs {
@@ -449,22 +460,31 @@ struct BatchBufs {
     SortBufs so;
 };
 
-static void alloc_batch(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t Ss, int64_t Sq, int64_t Ps, int64_t Pq,
-                        int64_t nnz, int64_t capacity, bool need_gx) {
+// per batch, from the indices only: device copies of the task offsets, the row of every sample in the activation
+// buffers, and the buffers of the batch-wide sort
+static void alloc_batch_index(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t Ss, int64_t Sq, int64_t nnz,
+                              int64_t capacity, bool need_gx) {
     b.toff_s = ar.get<int64_t>(T + 1);
     b.toff_q = ar.get<int64_t>(T + 1);
     b.prow_off_s = ar.get<int32_t>(T + 1);
     b.prow_off_q = ar.get<int32_t>(T + 1);
     b.prow_s = ar.get<int32_t>(Ss + 1);
     b.prow_q = ar.get<int32_t>(Sq + 1);
+    // the histogram area doubles as the scratch of the per-task lookup offsets (2 (T+1) 64-bit words) before any sort
+    alloc_sort(c, ar, b.so, nnz, capacity, 2 * (size_t)(T + 1) * 2, need_gx);
+}
+static void alloc_batch_dense(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t Ps, int64_t Pq, bool need_gx) {
     b.GX = need_gx ? ar.get<float>((Ps + Pq) * (int64_t)std::max(c->FD, 1) + 4) : nullptr;
     b.theta0 = Theta();
     b.theta0.f = ar.get<float>(c->n_theta);
     if (c->mlp_dtype) b.theta0.b = ar.get<bf16_t>(c->n_theta_b);
     b.g_theta = ar.get<float>(c->n_theta);
     b.task_loss = ar.get<float>(T + 1);
-    // the histogram area doubles as the scratch of the per-task lookup offsets (2 (T+1) 64-bit words) before any sort
-    alloc_sort(c, ar, b.so, nnz, capacity, 2 * (size_t)(T + 1) * 2, need_gx);
+}
+static void alloc_batch(const gm_ctx* c, Arena& ar, BatchBufs& b, int T, int64_t Ss, int64_t Sq, int64_t Ps, int64_t Pq,
+                        int64_t nnz, int64_t capacity, bool need_gx) {
+    alloc_batch_index(c, ar, b, T, Ss, Sq, nnz, capacity, need_gx);
+    alloc_batch_dense(c, ar, b, T, Ps, Pq, need_gx);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1299,7 +1319,8 @@ static int plan_waves(gm_ctx* c, Batch& B, size_t avail, int K, int order, int b
 }
 
 // batch-level set-up shared by gm_meta_step and gm_index_prep
-static int begin_batch(gm_ctx* c, Batch& B, Arena& ar, int64_t capacity, bool need_gx) {
+// ar: where the index-side buffers go; dense_ar: where the batch's dense buffers go (null: the caller places them)
+static int begin_batch(gm_ctx* c, Batch& B, Arena& ar, int64_t capacity, bool need_gx, Arena* dense_ar) {
     const int T = B.T, pad = c->row_pad;
     B.poff_s.assign(T + 1, 0);
     B.poff_q.assign(T + 1, 0);
@@ -1310,9 +1331,10 @@ static int begin_batch(gm_ctx* c, Batch& B, Arena& ar, int64_t capacity, bool ne
     if ((B.poff_s[T] + B.poff_q[T]) * (int64_t)std::max(c->F, 1) >= ((int64_t)1 << 32))
         return fail(c, GM_ERR_ARG, "more than 2^32 (row, field) pairs in one call");
     // (no batch-wide sort when every wave reduces its own lookups into a table)
-    alloc_batch(c, ar, B.b, T, B.sup->n_samples, B.qry->n_samples, B.poff_s[T], B.poff_q[T],
-                B.table ? 0 : B.sup->nnz + B.qry->nnz, capacity, need_gx);
-    if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "workspace too small for the batch-level buffers (%zu needed)", ar.off);
+    alloc_batch_index(c, ar, B.b, T, B.sup->n_samples, B.qry->n_samples, B.table ? 0 : B.sup->nnz + B.qry->nnz, capacity, need_gx);
+    if (dense_ar) alloc_batch_dense(c, *dense_ar, B.b, T, B.poff_s[T], B.poff_q[T], need_gx);
+    if (ar.overflow || (dense_ar && dense_ar->overflow))
+        return fail(c, GM_ERR_WORKSPACE, "workspace too small for the batch-level buffers (%zu needed)", ar.off);
     hipStream_t st = c->stream;
     HIPCHK(c, hipMemcpyAsync(B.b.toff_s, B.sup->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
     HIPCHK(c, hipMemcpyAsync(B.b.toff_q, B.qry->task_offsets, (T + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
@@ -1372,8 +1394,81 @@ static int setup_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, int bm, int
     return GM_OK;
 }
 
-extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set* qry, const gm_params* params,
-                            float alpha, int32_t K, int32_t order, float* loss, gm_grads* out) {
+// Pair-count matrices for the tasks that qualify, when the wave's bags and (task, field)s are within the counting
+// kernel's limits; a task with a count that does not fit a byte is handed to the sparse kernel (its flag is cleared on
+// the device).  allow_side: the counting may run on the second stream (gm_configure "overlap_pairs"); the caller then
+// joins it before the first row hop.
+static int count_pairs(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBufs& w, const WaveDims& d, int K, int tf_cap,
+                       int max_bag, int max_tf, bool allow_side, bool& pair, bool& any_sparse, bool& pairs_on_side) {
+    hipStream_t st = c->stream;
+    const int F = c->F, Tw = wp.t1 - wp.t0;
+    const gm_set *sup = B.sup, *qry = B.qry;
+    pair = d.pair && tf_cap <= PAIR_MAX_CAP && max_bag <= PAIR_MAX_BAG;
+    any_sparse = d.any_sparse || (d.pair && !pair);
+    pairs_on_side = false;
+    if (d.pair && !pair) launch_fill_u32(st, w.task_path, Tw, 0u);
+    if (!pair) return GM_OK;
+    PairCountArgs pa;
+    memset(&pa, 0, sizeof pa);
+    pa.F = F;
+    pa.real_off_s = w.real_off_s; pa.real_off_q = w.real_off_q; pa.row_off_s = w.row_off_s; pa.row_off_q = w.row_off_q;
+    pa.base_s = w.base_s; pa.base_q = w.base_q; pa.cnt_q = w.cnt_q; pa.n_slots = w.n_slots;
+    pa.slot_start = w.slot_start; pa.qseg_lo = w.qseg_lo; pa.qseg_hi = w.qseg_hi;
+    pa.sup_sorted = w.sup_sorted; pa.qry_sorted = w.qry_sorted;
+    pa.off_ss = w.pair_off_ss; pa.off_qs = w.pair_off_qs; pa.off_sq = w.pair_off_sq;
+    pa.mat = w.pair_mat; pa.want_ss = d.pair_ss; pa.want_sq = d.pair_sq; pa.status = c->d_status;
+    pa.task_path = w.task_path;
+    pairs_on_side = allow_side && c->overlap_pairs && !c->overlap_sort;
+    hipStream_t pst = pairs_on_side ? c->side : st;
+    if (pairs_on_side) {   // everything the kernel reads is in place once the main stream gets here
+        HIPCHK(c, hipEventRecord(c->ev_pairs_go, st));
+        HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_pairs_go, 0));
+        launch_fill_u32(c->side, c->d_status_side, ST_WORDS, 0);
+        pa.status = c->d_status_side;
+    }
+    {
+        Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0, pst, true);
+        int max_rows = 0, min_rows = 1 << 30;
+        for (int t = wp.t0; t < wp.t1; ++t)
+            if (task_pair_ok(c, B, t, K)) {
+                const int r = (int)std::max(sup->task_offsets[t + 1] - sup->task_offsets[t],
+                                            qry->task_offsets[t + 1] - qry->task_offsets[t]);
+                max_rows = std::max(max_rows, r);
+                min_rows = std::min(min_rows, r);
+            }
+        launch_pair_count(pst, pa, Tw, max_tf, max_rows, min_rows, c->pair_tile_rows);
+    }
+    if (pairs_on_side) {
+        HIPCHK(c, hipEventRecord(c->ev_pairs, c->side));
+    } else {
+        u32 hs[ST_WORDS];
+        int rc = read_status(c, hs);
+        if (rc != GM_OK) return rc;
+        if (hs[ST_PAIR_OVF]) any_sparse = true;   // some task's flag was cleared on the device
+    }
+    return GM_OK;
+}
+
+// Everything of a one-wave batch with the row-list output that depends on its indices only, prepared ahead of the step
+// (by gm_meta_train, on the second stream, while the previous batch computes): validated offsets and indices, padded
+// row numbers, tile lists, per-(task, field) dictionaries and overlap join, pair-count matrices, the batch-wide order
+// of the lookups by row and its segments.  The buffers live in an arena of their own.
+struct Prepared {
+    Batch B;
+    WavePlan wp;
+    WaveDims d;
+    WaveBufs w;        // index part only
+    Grp gs, gq;
+    int bm = 64;
+    int tf_cap = 0, max_bag = 0, max_tf = 0;
+    bool pair = false, any_sparse = false;
+};
+
+// The step.  pre: null, or the batch's index side prepared beforehand (one wave, row-list output); no_sync: return with
+// the work enqueued and the stream not drained (the caller synchronises and reads nothing from the host side but the
+// stream's error state; only with pre).
+static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set* qry, const gm_params* params, float alpha,
+                          int32_t K, int32_t order, float* loss, gm_grads* out, Prepared* pre, bool no_sync) {
     if (!c) return GM_ERR_ARG;
     if (T < 0 || K < 0 || (order != 1 && order != 2)) return fail(c, GM_ERR_ARG, "bad n_tasks / inner_steps / order");
     if (!out) return fail(c, GM_ERR_ARG, "null outputs");
@@ -1396,19 +1491,29 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
     const int64_t nnz = sup->nnz + qry->nnz;
     const int64_t capacity = table ? 0 : out->emb_rows_capacity;
 
+    if (pre && table) return fail(c, GM_ERR_ARG, "internal: a prepared batch uses the row-list output");
     Arena ar;
     ar.base = c->ws; ar.cap = c->ws_bytes; ar.off = c->persistent;
-    Batch B;
-    B.T = T; B.sup = sup; B.qry = qry;
-    B.table = table != nullptr;
-    rc = begin_batch(c, B, ar, capacity, !B.table);
-    if (rc != GM_OK) return rc;
+    Batch local_batch;
+    Batch& B = pre ? pre->B : local_batch;
+    std::vector<WavePlan> plans;
+    int bm;
+    if (pre) {   // the index side exists already; the dense buffers of the batch go to this call's arena
+        alloc_batch_dense(c, ar, B.b, T, B.poff_s[T], B.poff_q[T], true);
+        if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "workspace too small for the batch-level buffers (%zu needed)", ar.off);
+        bm = pre->bm;
+        plans.push_back(pre->wp);
+    } else {
+        B.T = T; B.sup = sup; B.qry = qry;
+        B.table = table != nullptr;
+        rc = begin_batch(c, B, ar, capacity, !B.table, &ar);
+        if (rc != GM_OK) return rc;
+        bm = pick_bm(c, B);
+        rc = plan_waves(c, B, c->ws_bytes - ar.off, K, order, bm, plans);
+        if (rc != GM_OK) return rc;
+    }
     BatchBufs& b = B.b;
     const int64_t Ps_tot = B.poff_s[T];
-    const int bm = pick_bm(c, B);
-    std::vector<WavePlan> plans;
-    rc = plan_waves(c, B, c->ws_bytes - ar.off, K, order, bm, plans);
-    if (rc != GM_OK) return rc;
     const size_t wave_mark = ar.off;
     struct SideGuard {   // whatever way this call ends, nothing of it is left running on the side stream
         gm_ctx* c;
@@ -1437,62 +1542,26 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         const int Tw = wp.t1 - wp.t0;
         if (Tw == 0) continue;
         WaveBufs w;
-        const WaveDims d = wave_dims(c, B, wp, bm, K, order);
-        alloc_wave(c, ar, w, d, K, order);
+        if (pre) w = pre->w;
+        const WaveDims d = pre ? pre->d : wave_dims(c, B, wp, bm, K, order);
+        if (!pre) alloc_wave_index(c, ar, w, d);
+        alloc_wave_dense(c, ar, w, d, K, order);
         if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "internal: wave does not fit");
         Grp gs, gq;
-        if ((rc = setup_wave(c, B, wp, bm, K, w, d, gs, gq))) return rc;
-
-        // a0: row dictionaries and the overlap join
-        int tf_cap = 0, max_bag = 0, max_tf = 0;
-        rc = run_index_wave(c, B, wp, w, &tf_cap, &max_bag, &max_tf);
-        if (rc != GM_OK) return rc;
-        // pair-count matrices for the tasks that qualify, when the wave's bags and (task, field)s are within the
-        // counting kernel's limits; a task with a count that does not fit a byte is handed to the sparse kernel
         const bool adapt = c->adapt_rows != 0;
-        bool pair = d.pair && tf_cap <= PAIR_MAX_CAP && max_bag <= PAIR_MAX_BAG;
-        bool any_sparse = d.any_sparse || (d.pair && !pair);
-        bool pairs_on_side = false;
-        if (d.pair && !pair) launch_fill_u32(st, w.task_path, Tw, 0u);
-        if (pair) {
-            PairCountArgs pa;
-            memset(&pa, 0, sizeof pa);
-            pa.F = F;
-            pa.real_off_s = w.real_off_s; pa.real_off_q = w.real_off_q; pa.row_off_s = w.row_off_s; pa.row_off_q = w.row_off_q;
-            pa.base_s = w.base_s; pa.base_q = w.base_q; pa.cnt_q = w.cnt_q; pa.n_slots = w.n_slots;
-            pa.slot_start = w.slot_start; pa.qseg_lo = w.qseg_lo; pa.qseg_hi = w.qseg_hi;
-            pa.sup_sorted = w.sup_sorted; pa.qry_sorted = w.qry_sorted;
-            pa.off_ss = w.pair_off_ss; pa.off_qs = w.pair_off_qs; pa.off_sq = w.pair_off_sq;
-            pa.mat = w.pair_mat; pa.want_ss = d.pair_ss; pa.want_sq = d.pair_sq; pa.status = c->d_status;
-            pa.task_path = w.task_path;
-            pairs_on_side = c->overlap_pairs && !c->overlap_sort;
-            hipStream_t pst = pairs_on_side ? c->side : st;
-            if (pairs_on_side) {   // everything the kernel reads is in place once the main stream gets here
-                HIPCHK(c, hipEventRecord(c->ev_pairs_go, st));
-                HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_pairs_go, 0));
-                side.active = true;
-                launch_fill_u32(c->side, c->d_status_side, ST_WORDS, 0);
-                pa.status = c->d_status_side;
-            }
-            {
-                Prof p(c, "pair_count", 8.0 * (d.nnz_s + d.nnz_q) + (double)d.pair_bytes, 0, pst, true);
-                int max_rows = 0, min_rows = 1 << 30;
-                for (int t = wp.t0; t < wp.t1; ++t)
-                    if (task_pair_ok(c, B, t, K)) {
-                        const int r = (int)std::max(sup->task_offsets[t + 1] - sup->task_offsets[t],
-                                                    qry->task_offsets[t + 1] - qry->task_offsets[t]);
-                        max_rows = std::max(max_rows, r);
-                        min_rows = std::min(min_rows, r);
-                    }
-                launch_pair_count(pst, pa, Tw, max_tf, max_rows, min_rows, c->pair_tile_rows);
-            }
-            if (pairs_on_side) {
-                HIPCHK(c, hipEventRecord(c->ev_pairs, c->side));
-            } else {
-                u32 hs[ST_WORDS];
-                if ((rc = read_status(c, hs))) return rc;
-                if (hs[ST_PAIR_OVF]) any_sparse = true;   // some task's flag was cleared on the device
-            }
+        int tf_cap = 0, max_bag = 0, max_tf = 0;
+        bool pair = false, any_sparse = false, pairs_on_side = false;
+        if (pre) {
+            gs = pre->gs; gq = pre->gq;
+            tf_cap = pre->tf_cap; max_bag = pre->max_bag; max_tf = pre->max_tf;
+            pair = pre->pair; any_sparse = pre->any_sparse;
+        } else {
+            if ((rc = setup_wave(c, B, wp, bm, K, w, d, gs, gq))) return rc;
+            // a0: row dictionaries and the overlap join
+            rc = run_index_wave(c, B, wp, w, &tf_cap, &max_bag, &max_tf);
+            if (rc != GM_OK) return rc;
+            if ((rc = count_pairs(c, B, wp, w, d, K, tf_cap, max_bag, max_tf, true, pair, any_sparse, pairs_on_side))) return rc;
+            if (pairs_on_side) side.active = true;
         }
         // joins the counting on the side stream: the host learns whether a task fell back to the sparse kernel, the main
         // stream waits for the matrices (called before the first row hop, which is their first reader)
@@ -1550,7 +1619,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         // side stream from here on -- beside the dense phase, which is bound by memory traffic, not beside the index
         // kernels above, which are bound by the same things as the sort -- and is joined before the segment reduction
         // (row-list output: only when the batch is one wave, so that everything it reads has been validated).
-        if (c->overlap_sort && F > 0 && (table || plans.size() == 1)) {
+        if (!pre && c->overlap_sort && F > 0 && (table || plans.size() == 1)) {
             HIPCHK(c, hipEventRecord(c->ev_go, st));
             HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_go, 0));
         }
@@ -1563,7 +1632,7 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
                               (u32)(0 - (uint64_t)wp.ps0), (u32)((uint64_t)d.Ps - (uint64_t)wp.pq0)};
             global_order(c, B, w.so, r, nullptr, nullptr, d.nnz_s + d.nnz_q, nullptr, true);
             HIPCHK(c, hipEventRecord(c->ev_side, c->side));
-        } else if (!table && c->overlap_sort && F > 0 && plans.size() == 1) {
+        } else if (!pre && !table && c->overlap_sort && F > 0 && plans.size() == 1) {
             side.active = true;
             side_list = true;
             launch_fill_u32(c->side, c->d_status_side, ST_WORDS, 0);
@@ -1786,19 +1855,27 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         launch_unpack_weights(st, b.g_theta + c->offb[l], 1, c->dims[l], c->dims[l], out->db[l - 1]);
     }
     launch_sum_to_scalar(st, task_loss, T, loss, 0);
-    launch_fill_u32(st, c->d_status, ST_WORDS, 0);
+    if (!pre) launch_fill_u32(st, c->d_status, ST_WORDS, 0);
     if (table) {
         launch_fill_u32(st, reinterpret_cast<u32*>(out->n_emb_rows), 2, 0u);
     } else {
         if (side_list) HIPCHK(c, hipStreamWaitEvent(st, c->ev_side, 0));
-        else global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows);
+        else if (!pre) global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows);
         if (F > 0) {
             Prof p(c, "seg_reduce", (double)nnz * (4.0 * D + 4), 0);
             launch_seg_reduce(st, D, b.so.keys, b.so.keys_tmp, out->n_emb_rows, capacity, nnz, b.so.vals,
                               b.GX, out->emb_grad, b.so.seg_partial, nullptr);
         }
     }
+    if (pre && no_sync) return GM_OK;   // the caller drains the stream; a prepared batch has passed every check already
     u32 hs[ST_WORDS];
+    memset(hs, 0, sizeof hs);
+    if (pre) {
+        HIPCHK(c, hipStreamSynchronize(st));
+        HIPCHK(c, hipGetLastError());
+        prof_drain(c);
+        return GM_OK;
+    }
     if (side_list)   // the ordering's own status words (the main stream has waited for it)
         HIPCHK(c, hipMemcpyAsync(hs, c->d_status_side, ST_WORDS * sizeof(u32), hipMemcpyDeviceToHost, st));
     rc = side_list ? (hipStreamSynchronize(st) == hipSuccess ? GM_OK : fail(c, GM_ERR_HIP, "stream synchronisation failed"))
@@ -1810,6 +1887,11 @@ extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_se
         return fail(c, GM_ERR_CAPACITY, "emb_rows_capacity %lld is smaller than the %u rows touched", (long long)capacity,
                     hs[ST_NROWS]);
     return GM_OK;
+}
+
+extern "C" int gm_meta_step(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set* qry, const gm_params* params,
+                            float alpha, int32_t K, int32_t order, float* loss, gm_grads* out) {
+    return meta_step_impl(c, T, sup, qry, params, alpha, K, order, loss, out, nullptr, false);
 }
 
 // The same step with every intermediate buffer in the static scratch array instead of the context's workspace: no
@@ -1888,6 +1970,212 @@ extern "C" int gm_meta_train_step(gm_ctx* c, int32_t T, const gm_set* sup, const
     if (c->F > 0 && h_rows > 0) {
         Prof p(c, "scatter_add", (double)h_rows * (12.0 * D + 8), 0);
         launch_scatter_add(st, D, const_cast<float*>(params->emb), rows, grad, h_rows, -beta);
+    }
+    HIPCHK(c, hipStreamSynchronize(st));
+    HIPCHK(c, hipGetLastError());
+    prof_drain(c);
+    return GM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// several iterations of Alg. 1 in one call, the index side of batch i+1 prepared while batch i computes
+// ------------------------------------------------------------------------------------------------
+static void host_layout(const gm_ctx* c, Batch& B, int T, const gm_set* sup, const gm_set* qry) {
+    B.T = T; B.sup = sup; B.qry = qry; B.table = false;
+    B.poff_s.assign(T + 1, 0);
+    B.poff_q.assign(T + 1, 0);
+    for (int t = 0; t < T; ++t) {
+        B.poff_s[t + 1] = B.poff_s[t] + round_up64(sup->task_offsets[t + 1] - sup->task_offsets[t], c->row_pad);
+        B.poff_q[t + 1] = B.poff_q[t] + round_up64(qry->task_offsets[t + 1] - qry->task_offsets[t], c->row_pad);
+    }
+}
+static WavePlan whole_batch_plan(const Batch& B) {
+    WavePlan p;
+    const int T = B.T;
+    p.t0 = 0; p.t1 = T;
+    p.s0 = 0; p.s1 = B.sup->n_samples; p.q0 = 0; p.q1 = B.qry->n_samples;
+    p.ps0 = 0; p.ps1 = B.poff_s[T]; p.pq0 = 0; p.pq1 = B.poff_q[T];
+    p.ls0 = 0; p.ls1 = B.sup->nnz; p.lq0 = 0; p.lq1 = B.qry->nnz;
+    return p;
+}
+// bytes of the index side and of the dense side of a batch run as ONE wave of tasks
+static void one_wave_bytes(const gm_ctx* c, int T, const gm_set* sup, const gm_set* qry, int K, int order, int64_t capacity,
+                           size_t* index_bytes, size_t* dense_bytes) {
+    Batch B;
+    host_layout(c, B, T, sup, qry);
+    const WavePlan p = whole_batch_plan(B);
+    const WaveDims d = wave_dims(c, B, p, pick_bm(c, B), K, order);
+    Arena ia, da;
+    ia.cap = da.cap = ~(size_t)0 >> 1;
+    BatchBufs b;
+    WaveBufs w;
+    alloc_batch_index(c, ia, b, T, sup->n_samples, qry->n_samples, sup->nnz + qry->nnz, capacity, true);
+    alloc_wave_index(c, ia, w, d);
+    alloc_batch_dense(c, da, b, T, B.poff_s[T], B.poff_q[T], true);
+    alloc_wave_dense(c, da, w, d, K, order);
+    *index_bytes = ia.off;
+    *dense_bytes = da.off;
+}
+
+// The index side of one batch, on the context's current stream, into the arena `ia`.
+static int prepare_batch(gm_ctx* c, Arena& ia, int32_t T, const gm_set* sup, const gm_set* qry, int K, int order,
+                         int64_t capacity, int64_t* emb_rows, int64_t* n_rows, Prepared& P) {
+    int rc = check_set(c, sup, T, "support");
+    if (rc != GM_OK) return rc;
+    rc = check_set(c, qry, T, "query");
+    if (rc != GM_OK) return rc;
+    P = Prepared();
+    Batch& B = P.B;
+    B.T = T; B.sup = sup; B.qry = qry; B.table = false;
+    if ((rc = begin_batch(c, B, ia, capacity, true, nullptr))) return rc;
+    P.bm = pick_bm(c, B);
+    P.wp = whole_batch_plan(B);
+    if (sup->nnz + qry->nnz >= ((int64_t)1 << 31)) return fail(c, GM_ERR_WORKSPACE, "the batch does not run as one wave of tasks");
+    P.d = wave_dims(c, B, P.wp, P.bm, K, order);
+    alloc_wave_index(c, ia, P.w, P.d);
+    if (ia.overflow) return fail(c, GM_ERR_WORKSPACE, "the batch's index structures do not fit their arena");
+    if (T > 0) {
+        if ((rc = setup_wave(c, B, P.wp, P.bm, K, P.w, P.d, P.gs, P.gq))) return rc;
+        if ((rc = run_index_wave(c, B, P.wp, P.w, &P.tf_cap, &P.max_bag, &P.max_tf))) return rc;
+        bool on_side = false;
+        if ((rc = count_pairs(c, B, P.wp, P.w, P.d, K, P.tf_cap, P.max_bag, P.max_tf, false, P.pair, P.any_sparse, on_side))) return rc;
+        if (c->row_path == 2 && P.any_sparse && c->adapt_rows)
+            return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a task, count, bag or (task, field) exceeds its limits");
+    }
+    launch_fill_u32(c->stream, c->d_status, ST_WORDS, 0);
+    global_order(c, B, B.b.so, whole_batch_range(B), emb_rows, nullptr, capacity, n_rows);
+    u32 hs[ST_WORDS];
+    if ((rc = read_status(c, hs))) return rc;
+    HIPCHK(c, hipGetLastError());
+    if (hs[ST_CAPACITY])
+        return fail(c, GM_ERR_CAPACITY, "internal: %u rows touched exceed the list capacity %lld", hs[ST_NROWS], (long long)capacity);
+    return GM_OK;
+}
+
+extern "C" int gm_meta_train(gm_ctx* c, int32_t n_iters, const int32_t* n_tasks, const gm_set* support, const gm_set* query,
+                             const gm_params* params, float alpha, int32_t K, int32_t order, float beta, float* losses,
+                             int32_t* n_done) {
+    if (!c) return GM_ERR_ARG;
+    if (n_done) *n_done = 0;
+    if (n_iters < 0 || (n_iters > 0 && (!n_tasks || !support || !query || !losses)))
+        return fail(c, GM_ERR_ARG, "bad iteration count / null arrays");
+    if (K < 0 || (order != 1 && order != 2)) return fail(c, GM_ERR_ARG, "bad inner_steps / order");
+    if (!params || !params->W || !params->b || (c->F > 0 && !params->emb)) return fail(c, GM_ERR_ARG, "null params");
+    for (int l = 0; l < c->L; ++l)
+        if (!params->W[l] || !params->b[l]) return fail(c, GM_ERR_ARG, "null layer pointer");
+    if (n_iters == 0) return GM_OK;
+    HIPCHK(c, hipSetDevice(c->device));
+    const int L = c->L, D = c->D;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    // what the overlapped loop needs: two index arenas, the meta-gradient lists (row lists twice: the next batch's is
+    // written while this batch's is still being applied), and the dense side of the largest batch
+    bool overlapped = true;
+    int64_t cap_max = 0;
+    size_t idx_max = 0, dense_max = 0;
+    for (int i = 0; i < n_iters; ++i) {
+        const gm_set *s = &support[i], *q = &query[i];
+        if (n_tasks[i] < 0 || !s->task_offsets || !q->task_offsets || s->nnz < 0 || q->nnz < 0 || s->n_samples < 0 || q->n_samples < 0 ||
+            s->task_offsets[n_tasks[i]] != s->n_samples || q->task_offsets[n_tasks[i]] != q->n_samples ||
+            s->nnz + q->nnz >= ((int64_t)1 << 31)) {
+            overlapped = false;   // (the per-iteration call reports what is wrong)
+            break;
+        }
+        const int64_t cap = c->F > 0 ? std::min<int64_t>(s->nnz + q->nnz, c->field_base[c->F]) : 0;
+        cap_max = std::max(cap_max, cap);
+        size_t ib, db;
+        one_wave_bytes(c, n_tasks[i], s, q, K, order, cap, &ib, &db);
+        idx_max = std::max(idx_max, up(ib) + 4096);
+        dense_max = std::max(dense_max, db);
+    }
+    int64_t n_dense = 0;
+    for (int l = 0; l < L; ++l) n_dense += (int64_t)(c->dims[l] + 1) * c->dims[l + 1];
+    const size_t top = up((size_t)n_dense * 4) + 2 * up((size_t)cap_max * 8) + up((size_t)cap_max * std::max(D, 1) * 4) + 2 * 256 + 256;
+    if (overlapped && c->persistent + dense_max + 2 * idx_max + top + (1 << 20) > c->ws_bytes) overlapped = false;
+    if (!overlapped) {   // one iteration after the other (several waves of tasks, or a workspace for one batch only)
+        for (int i = 0; i < n_iters; ++i) {
+            const int rc = gm_meta_train_step(c, n_tasks[i], &support[i], &query[i], params, alpha, K, order, beta, losses + i, nullptr);
+            if (rc != GM_OK) return rc;
+            if (n_done) *n_done = i + 1;
+        }
+        return GM_OK;
+    }
+    const size_t full = c->ws_bytes;
+    char* const top_p = c->ws + (full - top) / 256 * 256;
+    float* dense = reinterpret_cast<float*>(top_p);
+    int64_t* rows[2];
+    rows[0] = reinterpret_cast<int64_t*>(top_p + up((size_t)n_dense * 4));
+    rows[1] = reinterpret_cast<int64_t*>(reinterpret_cast<char*>(rows[0]) + up((size_t)cap_max * 8));
+    float* grad = reinterpret_cast<float*>(reinterpret_cast<char*>(rows[1]) + up((size_t)cap_max * 8));
+    int64_t* n_rows[2];
+    n_rows[0] = reinterpret_cast<int64_t*>(reinterpret_cast<char*>(grad) + up((size_t)cap_max * std::max(D, 1) * 4));
+    n_rows[1] = n_rows[0] + 32;
+    char* const idx_p[2] = {top_p - 2 * idx_max, top_p - idx_max};
+    const size_t dense_end = static_cast<size_t>(idx_p[0] - c->ws);
+    std::vector<float*> dW(L), db(L);
+    {
+        float* p = dense;
+        for (int l = 0; l < L; ++l) {
+            dW[l] = p; p += (int64_t)c->dims[l] * c->dims[l + 1];
+            db[l] = p; p += c->dims[l + 1];
+        }
+    }
+    // the side-stream settings of single steps do not apply here: the second stream belongs to the preparation
+    const int keep_sort = c->overlap_sort, keep_pairs = c->overlap_pairs;
+    c->overlap_sort = c->overlap_pairs = 0;
+    struct Restore {
+        gm_ctx* c; size_t full; int s, p;
+        ~Restore() { c->ws_bytes = full; c->overlap_sort = s; c->overlap_pairs = p; (void)hipStreamSynchronize(c->side); }
+    } restore{c, full, keep_sort, keep_pairs};
+    hipStream_t st = c->stream;
+    Prepared P[2];
+    auto prepare = [&](int i, bool on_side) -> int {
+        Arena ia;
+        ia.base = idx_p[i & 1]; ia.cap = idx_max; ia.off = 0;
+        const int64_t cap = c->F > 0 ? std::min<int64_t>(support[i].nnz + query[i].nnz, c->field_base[c->F]) : 0;
+        if (on_side) { std::swap(c->stream, c->side); std::swap(c->d_status, c->d_status_side); }
+        const int rc = prepare_batch(c, ia, n_tasks[i], &support[i], &query[i], K, order, cap, rows[i & 1], n_rows[i & 1], P[i & 1]);
+        if (on_side) { std::swap(c->stream, c->side); std::swap(c->d_status, c->d_status_side); }
+        return rc;
+    };
+    int rc = prepare(0, false);
+    if (rc != GM_OK) return rc;
+    for (int i = 0; i < n_iters; ++i) {
+        gm_grads out;
+        memset(&out, 0, sizeof out);
+        out.dW = dW.data(); out.db = db.data();
+        out.emb_rows = rows[i & 1]; out.emb_grad = grad; out.n_emb_rows = n_rows[i & 1];
+        out.emb_rows_capacity = c->F > 0 ? std::min<int64_t>(support[i].nnz + query[i].nnz, c->field_base[c->F]) : 0;
+        c->ws_bytes = dense_end;
+        rc = meta_step_impl(c, n_tasks[i], &support[i], &query[i], params, alpha, K, order, losses + i, &out, &P[i & 1], true);
+        c->ws_bytes = full;
+        if (rc != GM_OK) { (void)hipStreamSynchronize(st); return rc; }
+        int64_t h_rows = 0;
+        HIPCHK(c, hipMemcpyAsync(&h_rows, n_rows[i & 1], sizeof h_rows, hipMemcpyDeviceToHost, st));
+        // the next batch's index side, on the second stream, while this batch computes; its row list replaces the one of
+        // batch i-1, whose update (enqueued before this batch's step) must have been applied: ev_main marks that point
+        int rc_next = GM_OK;
+        if (i + 1 < n_iters) {
+            HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_main, 0));
+            rc_next = prepare(i + 1, true);
+        }
+        HIPCHK(c, hipStreamSynchronize(st));
+        HIPCHK(c, hipGetLastError());
+        prof_drain(c);
+        // the two global back-propagation steps with the outer step size (Alg. 1), in place
+        for (int l = 0; l < L; ++l) {
+            launch_axpy(st, (int64_t)c->dims[l] * c->dims[l + 1], -beta, dW[l], const_cast<float*>(params->W[l]));
+            launch_axpy(st, c->dims[l + 1], -beta, db[l], const_cast<float*>(params->b[l]));
+        }
+        if (c->F > 0 && h_rows > 0) {
+            Prof p(c, "scatter_add", (double)h_rows * (12.0 * D + 8), 0);
+            launch_scatter_add(st, D, const_cast<float*>(params->emb), rows[i & 1], grad, h_rows, -beta);
+        }
+        HIPCHK(c, hipEventRecord(c->ev_main, st));
+        if (n_done) *n_done = i + 1;
+        if (rc_next != GM_OK) {
+            (void)hipStreamSynchronize(st);
+            return rc_next;
+        }
     }
     HIPCHK(c, hipStreamSynchronize(st));
     HIPCHK(c, hipGetLastError());
@@ -2133,7 +2421,7 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
     ar.base = c->ws; ar.cap = c->ws_bytes; ar.off = c->persistent;
     Batch B;
     B.T = T; B.sup = sup; B.qry = qry;
-    rc = begin_batch(c, B, ar, capacity, false);
+    rc = begin_batch(c, B, ar, capacity, false, &ar);
     if (rc != GM_OK) return rc;
     std::vector<WavePlan> plans;
     rc = plan_waves(c, B, c->ws_bytes - ar.off, 1, 2, 64, plans);
