@@ -49,6 +49,75 @@ __global__ void gather_pool_kernel(int F, int D, int LG, const int64_t* __restri
     }
 }
 
+// The same pooling with the fields dealt to the 8 XCDs: workgroup b runs on XCD b % 8 and pools one eighth of the
+// (field, sample) pairs in field-major order, i.e. about F / 8 consecutive fields (a field may be shared by two
+// neighbours, so that the shares are equal whatever F is).  Under Zipf skew most lookups of a field hit a few thousand
+// hot rows; with an eighth of the fields per XCD the hot rows of "its" fields fit that XCD's L2 (8 fields x 1000 rows
+// x 256 B = 2 MB of 4 MB), so they stop travelling over the fabric for every lookup -- the fabric, not HBM, is what
+// this kernel is bound by.  (The lookups of a bag are summed in two interleaved chains of four, a fixed order.)
+__global__ void gather_pool_xcd_kernel(int F, int D, int LG, const int64_t* __restrict__ field_base,
+                                       const int64_t* __restrict__ bag_offsets, const int32_t* __restrict__ indices,
+                                       const float* __restrict__ emb, int64_t sample0, int64_t n_samples,
+                                       const int32_t* __restrict__ row_map, int32_t row_base, float* x, int ldx,
+                                       bf16_t* x_bf) {
+    const int groups_per_block = blockDim.x / LG;
+    const int g_in_block = threadIdx.x / LG, l = threadIdx.x % LG;
+    if (g_in_block >= groups_per_block) return;
+    const int xcd = blockIdx.x & 7, bi = blockIdx.x >> 3, nbx = gridDim.x >> 3;
+    const float4* emb4 = reinterpret_cast<const float4*>(emb);
+    // work items of this XCD: pairs [lo, hi) of the field-major list (pair = field * n_samples + sample)
+    const int64_t n_pairs = n_samples * F;
+    const int64_t lo = n_pairs * xcd / 8, hi = n_pairs * (xcd + 1) / 8;
+    const int64_t stride = (int64_t)nbx * groups_per_block;
+    // A bag is a chain of dependent reads (offsets -> indices -> rows).  The chain of the NEXT bag is started before
+    // the rows of this one are summed: its offsets and its first LG indices (one per lane of the group, handed round
+    // by lane shuffles) are in registers when its turn comes, and up to 8 row reads are in flight per lane.
+    int64_t it = lo + (int64_t)bi * groups_per_block + g_in_block;
+    int64_t p0 = 0, p1 = 0;
+    int32_t idx_l = 0;
+    if (it < hi) {
+        const int f = (int)(it / n_samples);
+        const int64_t gb = (sample0 + (it - (int64_t)f * n_samples)) * F + f;
+        p0 = bag_offsets[gb]; p1 = bag_offsets[gb + 1];
+        if (p0 + l < p1) idx_l = indices[p0 + l];
+    }
+    for (; it < hi; it += stride) {
+        const int f = (int)(it / n_samples);
+        const int64_t s = it - (int64_t)f * n_samples;
+        const int64_t fb = field_base[f];
+        const int64_t c0 = p0, c1 = p1;
+        int32_t cur_idx = idx_l;
+        // next bag's offsets and first indices
+        const int64_t itn = it + stride;
+        if (itn < hi) {
+            const int fn = (int)(itn / n_samples);
+            const int64_t gbn = (sample0 + (itn - (int64_t)fn * n_samples)) * F + fn;
+            p0 = bag_offsets[gbn]; p1 = bag_offsets[gbn + 1];
+            idx_l = (p0 + l < p1) ? indices[p0 + l] : 0;
+        }
+        float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
+        for (int64_t base = c0; base < c1; base += LG) {
+            if (base > c0) cur_idx = (base + l < c1) ? indices[base + l] : 0;
+            const int m = (int)min<int64_t>(LG, c1 - base);
+            for (int j0 = 0; j0 < m; j0 += 8) {
+                float4 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int jj = j0 + j;
+                    const int32_t r = __shfl(cur_idx, jj < LG ? jj : 0, LG);
+                    v[j] = jj < m ? emb4[(fb + r) * LG + l] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+                acc0 = add4(add4(add4(add4(acc0, v[0]), v[1]), v[2]), v[3]);
+                acc1 = add4(add4(add4(add4(acc1, v[4]), v[5]), v[6]), v[7]);
+            }
+        }
+        const float4 acc = add4(acc0, acc1);
+        const int64_t o = (int64_t)(row_map[s] - row_base) * ldx + (int64_t)f * D + l * 4;
+        if (x) *reinterpret_cast<float4*>(x + o) = acc;
+        if (x_bf) store_bf4(x_bf + o, acc);
+    }
+}
+
 // dense features and zero padding behind the pooled fields
 __global__ void dense_tail_kernel(int FD, int n_dense, const float* __restrict__ dense, int64_t sample0,
                                   int64_t n_samples, const int32_t* __restrict__ row_map, int32_t row_base, float* x,
@@ -79,7 +148,11 @@ void launch_gather_pool(hipStream_t st, int F, int D, int n_dense, const int64_t
     if (n_samples <= 0) return;
     const int LG = D / 4;
     const int64_t n_bags = n_samples * F;
-    if (n_bags > 0)
+    if (n_bags > 0 && F >= 8 && n_bags >= (1 << 14)) {
+        const unsigned grid = pool_grid(n_bags, 256 / LG) / 8 * 8;
+        hipLaunchKernelGGL(gather_pool_xcd_kernel, dim3(grid), dim3(256), 0, st, F, D, LG, field_base, bag_offsets,
+                           indices, emb, sample0, n_samples, row_map, row_base, x, ldx, x_bf);
+    } else if (n_bags > 0)
         hipLaunchKernelGGL(gather_pool_kernel, dim3(pool_grid(n_bags, 256 / LG)), dim3(256), 0, st, F, D, LG, field_base,
                            bag_offsets, indices, emb, sample0, n_bags, row_map, row_base, x, ldx, x_bf);
     const int64_t nt = n_samples * (ldx - F * D);
