@@ -18,27 +18,29 @@ import argparse
 import collections
 import csv
 import json
+import re
 import sqlite3
 
-# kernel-name fragments of each kernel family that bench.py reports (launches of one family are averaged)
+# regular expressions over kernel names for each kernel family that bench.py reports (launches of one family are averaged)
 FAMILIES = {
-    "pair_hop": ["pair_hop_kernel"],
-    "pair_count": ["pair_count_kernel"],
-    "two_hop": ["two_hop_kernel"],
-    "seg_reduce": ["seg_reduce_chunks_kernel", "seg_reduce_join_kernel"],
-    "gather_pool": ["gather_pool_kernel", "dense_tail_kernel"],
-    "tf_sort": ["tf_sort_kernel"],
-    "tf_count": ["tf_count_kernel"],
-    "global_sort": ["build_keys_kernel", "radix_hist_kernel", "radix_scatter_kernel", "seg_flags_kernel", "seg_emit_kernel"],
-    "task_colsum": ["task_colsum_kernel"],
-    "reduce_tasks": ["reduce_tasks_kernel"],
-    "axpy_gx": ["axpy_kernel"],
-    "last_layer": ["last_fwd_kernel", "last_bwd_kernel"],
-    # template flags of gemm_bf16_kernel<BM, BN, DB, KA, KB>: which operand is read contraction-slowest
-    "gemm_wgrad": ["false, true, true>"],
-    "gemm_fwd": ["false, false, true>"],
-    "gemm_bwd": ["false, false, false>"],
-    "gemm_f32 (all launches)": ["gemm_f32_kernel"],
+    "pair_hop": r"pair_hop_kernel",
+    "pair_count": r"pair_count_kernel",
+    "two_hop": r"two_hop_kernel",
+    "seg_reduce": r"seg_reduce_(chunks|join)_kernel",
+    "gather_pool": r"gather_pool(_xcd)?_kernel|dense_tail_kernel",
+    "tf_sort": r"tf_sort_kernel",
+    "tf_count": r"tf_count_kernel",
+    "global_sort": r"build_keys_kernel|radix_hist_kernel|radix_scatter_kernel|seg_flags_kernel|seg_emit_kernel",
+    "task_colsum": r"task_colsum_kernel",
+    "reduce_tasks": r"reduce_tasks_kernel",
+    "axpy_gx": r"axpy_kernel",
+    "last_layer": r"last_fwd_kernel|last_bwd",
+    # gemm_bf16_kernel<BM, BN, DB, KA, KB, EP>: which operand is read contraction-slowest tells the product's kind;
+    # gemm_bf16_pipe_kernel<KB, EP, ..>: the pipelined 256 x 256 kernel (forward products have KB = true)
+    "gemm_wgrad": r"gemm_bf16_kernel<\d+, \d+, false, true, true",
+    "gemm_fwd": r"gemm_bf16_kernel<\d+, \d+, false, false, true|gemm_bf16_pipe_kernel<true",
+    "gemm_bwd": r"gemm_bf16_kernel<\d+, \d+, false, false, false|gemm_bf16_pipe_kernel<false",
+    "gemm_f32 (all launches)": r"gemm_f32_kernel",
 }
 
 
@@ -49,11 +51,14 @@ def _is_framework(name: str) -> bool:
 def trace(a):
     con = sqlite3.connect(a.db)
     rows = list(con.execute("select name, total_calls, total_duration, average, percentage from top_kernels"))
-    ours, other_ns, other_calls = [], 0.0, 0
+    ours, other_ns, other_calls, probe_ns, probe_calls = [], 0.0, 0, 0.0, 0
     for name, calls, total, avg, _pct in rows:
         if _is_framework(name):
             other_ns += total
             other_calls += calls
+        elif re.search(r"mfma_loop(_random)?_kernel|stream_copy_kernel|stream_read_kernel", name):
+            probe_ns += total      # bench.py --ceilings: the on-box ceiling probes, not part of the step
+            probe_calls += calls
         else:
             ours.append((name.split("(")[0].replace("void ", ""), calls, total, avg))
     tot = sum(r[2] for r in ours)
@@ -64,6 +69,7 @@ def trace(a):
     print(f"{'kernel':56s} {'calls':>6s} {'total_us':>10s} {'avg_us':>10s}   share_of_library_time")
     for name, calls, total, avg in ours[:a.top]:
         print(f"{name[:56]:56s} {calls:6d} {total:10.1f} {avg:10.2f} {100.0 * total / tot:8.2f}%")
+    print(f"(ceiling probes of bench.py --ceilings: {probe_calls} calls, {probe_ns:.1f} us)")
     print(f"(input generation and other framework kernels: {other_calls} calls, {other_ns:.1f} us)")
 
 
@@ -106,15 +112,16 @@ def hbm(a):
     print(f"# copy probe of {known:.0f} B read as FETCH_SIZE {cf:.0f} B, WRITE_SIZE {cw:.0f} B -> scale factors {sf:.3f}, {sw:.3f}")
     print(f"# {'family':24s} {'dispatches/step':>16s} {'fetch GB/step':>14s} {'write GB/step':>14s} {'bytes/launch':>14s}")
     out, per_step = {}, {}
-    for fam, frags in FAMILIES.items():
+    for fam, pattern in FAMILIES.items():
         fb = wb = 0.0
         n = 0
+        rx = re.compile(pattern)
         for k, v in fetch.items():
-            if any(x in k for x in frags):
+            if rx.search(k):
                 fb += sum(v) * sf
                 n += len(v)
         for k, v in write.items():
-            if any(x in k for x in frags):
+            if rx.search(k):
                 wb += sum(v) * sw
         if n == 0:
             continue
@@ -152,8 +159,9 @@ def mfma(a):
         rows.append((sum(act), k.split("(")[0].replace("void ", ""), n, ma, mb, 100.0 * mb / (ma / 8 * 1024) if ma > 0 else 0.0, ops))
     for _, k, n, ma, mb, pct, ops in sorted(rows, reverse=True):
         print(f"  {k[:60]:60s} {n:10d} {ma:14.4g} {mb:16.4g} {pct:11.1f} {ops:14.4g}")
-    print("# gemm_bf16_kernel<BM,BN,false,false,true>: forward products; <..,false,false,false>: backward (dA) products;")
-    print("# <128,128,false,true,true>: per-task weight gradients.")
+    print("# gemm_bf16_kernel<BM,BN,false,KA,KB,EP>: KA,KB = false,true forward products; false,false backward (dA) products;")
+    print("# true,true per-task weight gradients.  gemm_bf16_pipe_kernel<KB,EP,..>: the pipelined 256 x 256 kernel (KB = true:")
+    print("# forward products, false: backward products).  EP encodes the fused epilogue of the launch.")
 
 
 def main():
