@@ -228,6 +228,12 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               sparse two-hop kernel; 2 = always per-(task, field) pair-count matrices on the matrix
  *               cores (gm_meta_step then returns GM_ERR_CAPACITY when a wave exceeds that path's limits:
  *               bags of at most 127 lookups, pair counts of at most 254, 16384 lookups per task, field and set).
+ *   "index_path": how the per-(task, field) row dictionaries, lookup lists and the overlap join of Sec. 2.1.2 are
+ *               built: 0 = chosen per wave of tasks (default); 1 = every (task, field) sorted by itself; 2 = read
+ *               off the row order of the wave's lookups (the order the sparse meta-gradient of Alg. 1 needs anyway,
+ *               followed by one stable pass by task; GM_ERR_CAPACITY when that order is not the wave's own -- a
+ *               row-list output over several waves -- or a gradient-buffer row, a field number and a position in a
+ *               bag do not fit 32 bits together).  Identical integer structures, identical results.
  *   "adapt_rows": 1 (default) = the inner loop adapts the dense parameters and the looked-up embedding rows
  *               (Alg. 1); 0 = it adapts the dense parameters only and reads the embeddings as they are (the
  *               dense-only family of optimisation-based meta learners that Sec. 3.1 runs on the same

@@ -151,9 +151,11 @@ def _w(W, l, q):
     return q(W[l]) if l < len(W) - 1 else W[l]
 
 
-def forward(x: np.ndarray, W: List[np.ndarray], b: List[np.ndarray], q=_identity, masks=None):
+def forward(x: np.ndarray, W: List[np.ndarray], b: List[np.ndarray], q=_identity, masks=None, pre_out=None):
     """a_0 = x; z_l = a_{l-1} W_l + b_l; a_l = z_l * m_l for l < L, with m_l = [z_l > 0] (ReLU) unless the
-    gates are given (masks[l-1] for hidden layer l).  Returns ([a_0..a_{L-1}], z_L, [m_1..m_{L-1}])."""
+    gates are given (masks[l-1] for hidden layer l).  Returns ([a_0..a_{L-1}], z_L, [m_1..m_{L-1}]).
+    pre_out, if a list, receives the hidden layers' pre-activations [z_1..z_{L-1}] (what the gates were decided
+    on: a test can tell from them which gates sit within rounding distance of zero)."""
     acts = [q(x)]
     used = []
     L = len(W)
@@ -162,6 +164,8 @@ def forward(x: np.ndarray, W: List[np.ndarray], b: List[np.ndarray], q=_identity
         if l < L - 1:
             m = (z > 0.0) if masks is None else np.asarray(masks[l], dtype=bool)
             used.append(m)
+            if pre_out is not None:
+                pre_out.append(z.copy())
             acts.append(q(np.where(m, z, 0.0)))
     return acts, z[:, 0], used
 
@@ -218,7 +222,7 @@ def hvp(acts, z, y, W, deltas, masks, vW, vb, vx, q=_identity):
 # --------------------------------------------------------------------------
 def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int, order: int,
                    full_table: bool = False, operand: str = "fp64", adapt_rows: bool = True,
-                   relu_masks=None, masks_out: Optional[list] = None):
+                   relu_masks=None, masks_out: Optional[list] = None, pre_out: Optional[list] = None):
     """MAML for task t.  Returns (L^Query, gW, gb, rows, gxi[rows]) w.r.t. the META parameters.
 
     adapt_rows=False is the variant that adapts the dense parameters only (the way the paper's framework
@@ -233,7 +237,8 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
     relu_masks: None -- every forward pass decides its own ReLU gates (z > 0); "bf16" -- the gates are those of a
     run of the task with operand="bf16", recorded first, while the arithmetic itself follows `operand`; a list of
     K + 1 entries (the K support passes, then the query pass), each the list of hidden
-    layers' boolean masks -- gates given from outside.  masks_out, if a list, receives the gates used, in that form.
+    layers' boolean masks -- gates given from outside.  masks_out, if a list, receives the gates used, in that form;
+    pre_out, if a list, the pre-activations those gates belong to (same form).
     """
     F, D = model.n_fields, model.emb_dim
     FD = F * D
@@ -272,9 +277,12 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
 
     def gated_forward(x, W, b, i):
         """Forward pass number i of the task (support passes 0..K-1, query pass K) with its gates."""
-        acts, z, used = forward(x, W, b, q, None if relu_masks is None else relu_masks[i])
+        pre = [] if pre_out is not None else None
+        acts, z, used = forward(x, W, b, q, None if relu_masks is None else relu_masks[i], pre)
         if masks_out is not None:
             masks_out.append(used)
+        if pre_out is not None:
+            pre_out.append(pre)
         return acts, z, used
 
     # inner loop on the support set
@@ -321,11 +329,12 @@ def task_meta_grad(model: Model, params, sup, qry, t: int, alpha: float, K: int,
 # --------------------------------------------------------------------------
 def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
               tasks: Optional[Sequence[int]] = None, full_table: bool = False, operand: str = "fp64",
-              adapt_rows: bool = True, relu_masks=None, masks_out: Optional[dict] = None):
+              adapt_rows: bool = True, relu_masks=None, masks_out: Optional[dict] = None,
+              pre_out: Optional[dict] = None):
     """Sum of the per-task meta-gradients (Alg. 1, global back-propagation steps).
 
     relu_masks: None, "bf16", or {task: list of masks per forward pass} (see task_meta_grad); masks_out, if a
-    dict, receives {task: gates used}.
+    dict, receives {task: gates used}; pre_out, if a dict, {task: the pre-activations they were decided on}.
 
     Returns dict(loss, task_loss[T], dW[l], db[l], emb_rows (ascending unique
     global rows looked up by any sample), emb_grad[len(emb_rows), D]).
@@ -339,11 +348,14 @@ def meta_step(model: Model, params, sup, qry, alpha: float, K: int, order: int,
     parts_rows, parts_grad = [], []
     for i, t in enumerate(tasks):
         rec = [] if masks_out is not None else None
+        pre = [] if pre_out is not None else None
         lq, vW, vb, rows, vE = task_meta_grad(model, params, sup, qry, t, alpha, K, order, full_table, operand,
                                               adapt_rows, relu_masks[t] if isinstance(relu_masks, dict) else relu_masks,
-                                              rec)
+                                              rec, pre)
         if masks_out is not None:
             masks_out[t] = rec
+        if pre_out is not None:
+            pre_out[t] = pre
         task_loss[i] = lq
         for l in range(L):
             gW[l] += vW[l]

@@ -33,15 +33,18 @@ __global__ void gather_pool_kernel(int F, int D, int LG, const int64_t* __restri
         const int64_t gb = sample0 * F + bag;
         const int64_t p0 = bag_offsets[gb], p1 = bag_offsets[gb + 1];
         const int64_t fb = field_base[f];
+        // the order of the sums is gather_pool_xcd_kernel's, bit for bit: eight lookups at a time, the first four into
+        // one chain and the next four into the other (one chain when a lane group is narrower than eight lanes)
         float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
-        int64_t p = p0;
-        for (; p + 4 <= p1; p += 4) {
-            const int64_t r0 = fb + indices[p], r1 = fb + indices[p + 1], r2 = fb + indices[p + 2], r3 = fb + indices[p + 3];
-            const float4 v0 = emb4[r0 * LG + l], v1 = emb4[r1 * LG + l], v2 = emb4[r2 * LG + l], v3 = emb4[r3 * LG + l];
-            acc0 = add4(add4(acc0, v0), v1);   // fixed order: the bag's lookups left to right in two lanes of sums
-            acc1 = add4(add4(acc1, v2), v3);
+        const float4 zero = acc0;
+        for (int64_t p = p0; p < p1; p += 8) {
+            float4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = p + j < p1 ? emb4[(fb + indices[p + j]) * LG + l] : zero;
+            acc0 = add4(add4(add4(add4(acc0, v[0]), v[1]), v[2]), v[3]);
+            if (LG >= 8) acc1 = add4(add4(add4(add4(acc1, v[4]), v[5]), v[6]), v[7]);
+            else acc0 = add4(add4(add4(add4(acc0, v[4]), v[5]), v[6]), v[7]);
         }
-        for (; p < p1; ++p) acc0 = add4(acc0, emb4[(fb + indices[p]) * LG + l]);
         const float4 acc = add4(acc0, acc1);
         const int64_t o = (int64_t)(row_map[s] - row_base) * ldx + (int64_t)f * D + l * 4;
         if (x) *reinterpret_cast<float4*>(x + o) = acc;
@@ -198,7 +201,7 @@ void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_row
 // follows from the head flags at the chunk's two borders, so no segment table is read here.
 template <int LG>
 __global__ void __launch_bounds__(256)
-seg_reduce_chunks_kernel(int D, const u32* __restrict__ keys, const u32* __restrict__ scan,
+seg_reduce_chunks_kernel(int D, int F, ValEnc enc, const u32* __restrict__ keys, const u32* __restrict__ scan,
                          const int64_t* __restrict__ n_rows, int64_t capacity, int64_t n,
                          const u32* __restrict__ sorted_vals, const float* __restrict__ gx, float* emb_grad,
                          float* partial, float* table) {
@@ -224,6 +227,8 @@ seg_reduce_chunks_kernel(int D, const u32* __restrict__ keys, const u32* __restr
             if (p < cnt) {
                 const int64_t i = cb + p;
                 v_next = sorted_vals[i];
+                // (bit-field values: the bag's place in the gradient buffer is row * F + field)
+                if (enc.rshift) v_next = (v_next >> enc.rshift) * (u32)F + ((v_next >> enc.pshift) & enc.fmask);
                 k_next = keys[i];
                 h_next = (i == 0) || keys[i - 1] != k_next;
             }
@@ -344,7 +349,7 @@ __global__ void seg_reduce_join_kernel(int D, int LG, const u32* __restrict__ ke
 
 size_t seg_reduce_partial_floats(int64_t n, int D) { return (size_t)((n + SEG_CH - 1) / SEG_CH) * 2 * D + 16; }
 
-void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
+void launch_seg_reduce(hipStream_t st, int D, int F, ValEnc enc, const u32* keys, const u32* scan, const int64_t* n_rows, int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
                        float* emb_grad, float* partial, float* table) {
     if (n <= 0 || capacity <= 0) return;
     const int LG = D / 4;
@@ -352,7 +357,7 @@ void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, 
     const dim3 grid(pool_grid(n_chunks, 256 / LG));
 #define SEG_CHUNKS(LG_)                                                                                              \
     case LG_:                                                                                                        \
-        hipLaunchKernelGGL(seg_reduce_chunks_kernel<LG_>, grid, dim3(256), 0, st, D, keys, scan, n_rows, capacity, n, \
+        hipLaunchKernelGGL(seg_reduce_chunks_kernel<LG_>, grid, dim3(256), 0, st, D, F, enc, keys, scan, n_rows, capacity, n, \
                            sorted_vals, gx, emb_grad, partial, table);                                               \
         break;
     switch (LG) {

@@ -68,9 +68,46 @@ struct TfSortArgs {
 void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set_rows);
 int tf_sort_max_cap();
 
+// How the value that travels with a lookup's row key names the lookup's bag in the gradient buffer.
+// rshift == 0: value = (row of the sample) * F + field.  Otherwise bit fields: row << rshift | field << pshift |
+// position of the lookup in its bag -- the form the per-(task, field) join needs (it finds every lookup's number again).
+struct ValEnc {
+    int rshift, pshift;
+    u32 fmask;      // (1 << bits of a field number) - 1
+};
 void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
-                       const int32_t* indices, int64_t n_bags, int64_t lookup0, const int32_t* row_map, u32 row0, u32* keys,
-                       u32* vals);
+                       const int32_t* indices, int64_t n_bags, int64_t lookup0, const int32_t* row_map, u32 row0, ValEnc enc,
+                       u32* keys, u32* vals);
+// Task of a bit-field value's sample: gradient-buffer rows below n_sup_rows are the wave's support rows, the others its
+// query rows; row_task_* give the task (within the wave) of every padded row of a set.
+struct TaskOf {
+    const int32_t *row_task_s, *row_task_q;
+    u32 n_sup_rows, n_rows;   // support rows; support + query rows
+    int rshift;
+    int uniform_shift;        // >= 0: every task has 1 << uniform_shift padded rows in each set (the tables are not read)
+};
+// (keys, vals) in (field, row) order -> (out_keys, out_vals) in (task, field, row) order, stable; the input is kept.
+// (mid_keys, mid_vals) are needed when task_sort_passes(n_tasks) is 2.
+void launch_task_sort(hipStream_t st, const u32* keys, const u32* vals, u32* mid_keys, u32* mid_vals, u32* out_keys,
+                      u32* out_vals, int64_t n, int n_tasks, const TaskOf& tk, u32* hist /* radix_hist_words(n) */);
+int task_sort_passes(int n_tasks);
+// The outputs of launch_tf_sort, read off the (task, field, row)-ordered list instead of sorted per (task, field).
+struct TfJoinArgs {
+    int F, Tw;
+    const u32 *keys, *vals;                        // the ordered list (bit-field values)
+    const u32 *cnt_s, *base_s, *cnt_q, *base_q;    // per (task, field): lookups of each set and their exclusive scans
+    int rshift, pshift;
+    u32 n_sup_rows;
+    u32* n_slots; u32* slot_rows; int32_t* slot_start;
+    int2 *sup_sorted, *qry_sorted;
+    int32_t *qseg_lo, *qseg_hi;
+    int32_t *sup_slot, *qry_slot;                  // both null: the slot of every lookup is not written
+    const int64_t *bag_s, *bag_q;                  // bag offsets of the two sets (whole sets)
+    int64_t sample0_s, sample0_q, lookup0_s, lookup0_q;   // the wave's first sample / lookup in each set
+    int64_t n_lookups_s, n_lookups_q;                     // the wave's lookups in each set
+    const int32_t *row_off_s, *row_off_q, *real_off_s, *real_off_q;   // [Tw + 1] first padded row / first sample of each task
+};
+void launch_tf_join(hipStream_t st, const TfJoinArgs& a);
 // Stable LSD radix sort of (key, val) pairs on the low `bits` bits.  Returns the number of passes: after an odd
 // number the result is in (keys_tmp, vals_tmp), else in (keys, vals).
 int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n,
@@ -162,7 +199,7 @@ void launch_copy_tail(hipStream_t st, int FD, const float* x_base, int64_t n_row
 
 // keys: the sorted row keys; scan: exclusive scan of their segment-head flags and n_rows: the number of segments
 // (both as launch_segments left them; neither is read when the output is table-shaped)
-void launch_seg_reduce(hipStream_t st, int D, const u32* keys, const u32* scan, const int64_t* n_rows,
+void launch_seg_reduce(hipStream_t st, int D, int F, ValEnc enc, const u32* keys, const u32* scan, const int64_t* n_rows,
                        int64_t capacity, int64_t n, const u32* sorted_vals, const float* gx,
                        float* emb_grad, float* partial /* seg_reduce_partial_floats(n, D) */,
                        float* table /* null, or [all rows, D]: every segment is ADDED to its row instead of listed */);

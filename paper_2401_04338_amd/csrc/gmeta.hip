@@ -82,6 +82,7 @@ struct gm_ctx {
     int adapt_rows = 1;   // 0: the inner loop adapts the dense parameters only (embedding rows are read, not updated)
     int gemm_tile_n = 0;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
+    int index_path = 0; // per-(task, field) dictionaries: 0 = choose per wave, 1 = sorted per (task, field) in LDS, 2 = read off the wave's (task, field, row) order
     int max_wave_tasks = 0;   // 0: as many tasks per wave as the workspace holds
     char* static_scratch = nullptr;   // this device's copy of the static scratch array (gm_meta_step_static)
     // optional kernel timing
@@ -256,6 +257,8 @@ struct WaveBufs {
     u32* slot_rows;
     int32_t *slot_start, *sup_slot, *qry_slot, *qseg_lo, *qseg_hi;
     int2 *sup_sorted, *qry_sorted;
+    u32 *tmid_keys = nullptr, *tmid_vals = nullptr;   // more than 512 tasks: the first of the two passes that order the lookups by task
+    bool slots_written = true;   // sup_slot / qry_slot hold the slot of every lookup (only the sparse row kernel reads them)
     float *Xs0, *Xq0, *TXf, *dX, *loss_q;
     Theta v;  // direction / query gradient w.r.t. theta'
     // the last weight-gradient products of a call are only ever summed over the tasks: they are taken over COARSE_GROUPS
@@ -358,6 +361,11 @@ static void alloc_wave_index(const gm_ctx* c, Arena& ar, WaveBufs& w, const Wave
     w.qry_sorted = ar.get<int2>(d.nnz_q + 1);
     w.qseg_lo = ar.get<int32_t>(d.nnz_s + 1);
     w.qseg_hi = ar.get<int32_t>(d.nnz_s + 1);
+    w.tmid_keys = w.tmid_vals = nullptr;
+    if (F > 0 && c->adapt_rows && c->index_path != 1 && task_sort_passes(d.Tw) > 1) {
+        w.tmid_keys = ar.get<u32>(d.nnz_s + d.nnz_q + 1);
+        w.tmid_vals = ar.get<u32>(d.nnz_s + d.nnz_q + 1);
+    }
     w.coarse_off_s = ar.get<int32_t>(COARSE_GROUPS + 1);
     w.coarse_off_q = ar.get<int32_t>(COARSE_GROUPS + 1);
     w.pair_mat = nullptr;
@@ -584,6 +592,11 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
     if (!strcmp(key, "row_path")) {
         if (value < 0 || value > 2) return fail(c, GM_ERR_ARG, "row_path must be 0, 1 or 2");
         c->row_path = (int)value;
+        return GM_OK;
+    }
+    if (!strcmp(key, "index_path")) {
+        if (value < 0 || value > 2) return fail(c, GM_ERR_ARG, "index_path must be 0, 1 or 2");
+        c->index_path = (int)value;
         return GM_OK;
     }
     return fail(c, GM_ERR_ARG, "unknown key '%s'", key);
@@ -1098,10 +1111,109 @@ struct Batch {  // host-side description of one call
     BatchBufs b;
 };
 
-static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBufs& w, int* cap_out = nullptr,
-                          int* max_bag_out = nullptr, int* max_tf_out = nullptr) {
+// The lookups of samples [s0, s1) of the support set and [q0, q1) of the query set, ordered by global row and cut into
+// one segment per distinct row.  Gradient-buffer rows are row0_* + the batch-wide padded row of the sample (mod 2^32).
+struct SortRange {
+    int64_t s0, s1, q0, q1;      // samples
+    int64_t ls0, ls1, lq0, lq1;  // their lookups
+    u32 row0_s, row0_q;
+};
+
+static const ValEnc kPlainVals{0, 0, 0u};
+
+enum { ORDER_SORT = 1, ORDER_SEGMENTS = 2, ORDER_ALL = 3 };
+
+// parts: the sort (keys built, ordered by row: left in so.keys / so.vals), the segments (one per distinct row, from
+// the sorted keys), or both
+static int global_order(gm_ctx* c, Batch& B, SortBufs& so, const SortRange& r, int64_t* emb_rows, int64_t* seg_counts,
+                        int64_t capacity, int64_t* n_rows, bool on_side = false, ValEnc enc = kPlainVals, int parts = ORDER_ALL) {
+    hipStream_t st = on_side ? c->side : c->stream;
+    u32* status = on_side ? c->d_status_side : c->d_status;
+    const int F = c->F;
+    const gm_set *sup = B.sup, *qry = B.qry;
+    BatchBufs& b = B.b;
+    const int64_t n_s = r.ls1 - r.ls0, nnz = n_s + (r.lq1 - r.lq0);
+    Prof p(c, "global_sort", 0, 0, st, true);
+    if (parts & ORDER_SORT) {
+        if (F > 0) {
+            launch_build_keys(st, F, c->d_field_base, sup->bag_offsets + r.s0 * F, sup->indices, (r.s1 - r.s0) * F, r.ls0,
+                              b.prow_s + r.s0, r.row0_s, enc, so.keys, so.vals);
+            launch_build_keys(st, F, c->d_field_base, qry->bag_offsets + r.q0 * F, qry->indices, (r.q1 - r.q0) * F, r.lq0,
+                              b.prow_q + r.q0, r.row0_q, enc, so.keys + n_s, so.vals + n_s);
+        }
+        int bits = 1;
+        while (((int64_t)1 << bits) < c->field_base[c->F]) ++bits;
+        const int passes = launch_radix_sort(st, so.keys, so.vals, so.keys_tmp, so.vals_tmp, nnz, bits, so.hist);
+        // algorithmic bytes: keys built from the lookups (4 B index read, 8 B of key and value written, 8 B of offsets per bag),
+        // 20 B per key and radix pass (the key read for the digit counts; key and value read and written by the scatter)
+        p.p.bytes += (double)nnz * (12.0 + 20.0 * passes) + 8.0 * F * ((r.s1 - r.s0) + (r.q1 - r.q0));
+        if (passes & 1) {
+            std::swap(so.keys, so.keys_tmp);   // an odd number of passes leaves the result in the second pair of buffers
+            std::swap(so.vals, so.vals_tmp);
+        }
+    }
+    // the table-shaped output adds every segment to the row its key names: no segment numbers, no row list
+    if ((parts & ORDER_SEGMENTS) && n_rows) {
+        p.p.bytes += 4.0 * (double)nnz;   // the sorted keys read once more
+        launch_segments(st, so.keys, nnz, so.keys_tmp, so.scan_tmp, emb_rows, so.seg_start, seg_counts, capacity, n_rows,
+                        status);
+    }
+    return GM_OK;
+}
+
+// Asks run_index_wave to take the wave's per-(task, field) dictionaries from the (field, row) order of its lookups --
+// the order the sparse meta-gradient needs anyway -- instead of sorting every (task, field) by itself: the wave's
+// lookups are ordered by row first (left in `so` for the segment reduction), one more stable pass orders them by task,
+// and the dictionaries, the lookup lists and the overlap join are read off that list.  Applies when the sort's range is
+// exactly the wave and a gradient-buffer row, a field number and a position in a bag fit 32 bits together.
+struct JoinReq {
+    SortBufs* so = nullptr;
+    SortRange range{};
+    int64_t* emb_rows = nullptr;     // row-list output: the segments are cut right after the sort (n_rows null: table-shaped output)
+    int64_t* seg_counts = nullptr;
+    int64_t capacity = 0;
+    int64_t* n_rows = nullptr;
+    int64_t n_sup_rows = 0, n_qry_rows = 0;   // padded rows of the wave's two sets (gradient-buffer rows: support first)
+    bool slots = false;              // the slot of every lookup is wanted whatever the row path
+    bool pair_only = false;          // every task of the wave is planned for the pair-count matrices (which do not read those slots)
+    bool used = false;               // out: the wave's lookups are ordered, `enc` says how their values read
+    ValEnc enc = kPlainVals;
+};
+
+static int bits_for(int64_t n) {   // bits that hold every value below n
+    int b = 0;
+    while (((int64_t)1 << b) < n) ++b;
+    return b;
+}
+
+// The per-(task, field) dictionaries, lookup lists and overlap join of a wave, every (task, field) sorted by itself in LDS
+// (w.cnt_* / w.base_* are in place).
+static void sort_task_fields(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBufs& w, int max_tf) {
+    const int F = c->F, Tw = wp.t1 - wp.t0;
+    TfSortArgs a;
+    a.F = F; a.t0 = wp.t0; a.Tw = Tw;
+    a.sup = make_view(B.sup, B.b.toff_s, wp.s0, wp.ls0); a.qry = make_view(B.qry, B.b.toff_q, wp.q0, wp.lq0);
+    a.field_base = c->d_field_base;
+    a.cnt_sup = w.cnt_s; a.base_sup = w.base_s; a.cnt_qry = w.cnt_q; a.base_qry = w.base_q;
+    a.n_slots = w.n_slots; a.slot_rows = w.slot_rows; a.slot_start = w.slot_start;
+    a.sup_sorted = w.sup_sorted; a.sup_slot = w.sup_slot; a.qry_slot = w.qry_slot;
+    a.qry_sorted = w.qry_sorted; a.qseg_lo = w.qseg_lo; a.qseg_hi = w.qseg_hi; a.status = c->d_status;
+    a.sup_rows = B.b.prow_s; a.sup_row_base = (int32_t)wp.ps0;
+    a.qry_rows = B.b.prow_q; a.qry_row_base = (int32_t)wp.pq0;
+    Prof p(c, "tf_sort", 12.0 * ((wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0)), 0);
+    int64_t max_set_rows = 0;
+    for (int t = wp.t0; t < wp.t1; ++t)
+        max_set_rows = std::max(max_set_rows, std::max(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t],
+                                                       B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]));
+    launch_tf_sort(c->stream, a, max_tf, (int)std::min<int64_t>(max_set_rows, 1 << 30));
+    w.slots_written = true;
+}
+
+static int run_index_wave(gm_ctx* c, Batch& B, const WavePlan& wp, WaveBufs& w, int* cap_out = nullptr,
+                          int* max_bag_out = nullptr, int* max_tf_out = nullptr, JoinReq* jr = nullptr) {
     hipStream_t st = c->stream;
     const int F = c->F, Tw = wp.t1 - wp.t0;
+    if (jr) jr->used = false;
     if (F == 0 || Tw == 0) return GM_OK;
     const int64_t TF = (int64_t)Tw * F;
     SetView vs = make_view(B.sup, B.b.toff_s, wp.s0, wp.ls0), vq = make_view(B.qry, B.b.toff_q, wp.q0, wp.lq0);
@@ -1127,63 +1239,62 @@ static int run_index_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBuf
                     tf_sort_max_cap());
     launch_scan_u32(st, w.cnt_s, w.base_s, TF, w.scan_tmp, nullptr);
     launch_scan_u32(st, w.cnt_q, w.base_q, TF, w.scan_tmp, nullptr);
-    TfSortArgs a;
-    a.F = F; a.t0 = wp.t0; a.Tw = Tw; a.sup = vs; a.qry = vq; a.field_base = c->d_field_base;
-    a.cnt_sup = w.cnt_s; a.base_sup = w.base_s; a.cnt_qry = w.cnt_q; a.base_qry = w.base_q;
-    a.n_slots = w.n_slots; a.slot_rows = w.slot_rows; a.slot_start = w.slot_start;
-    a.sup_sorted = w.sup_sorted; a.sup_slot = w.sup_slot; a.qry_slot = w.qry_slot;
-    a.qry_sorted = w.qry_sorted; a.qseg_lo = w.qseg_lo; a.qseg_hi = w.qseg_hi; a.status = c->d_status;
-    a.sup_rows = B.b.prow_s; a.sup_row_base = (int32_t)wp.ps0;
-    a.qry_rows = B.b.prow_q; a.qry_row_base = (int32_t)wp.pq0;
-    {
-        Prof p(c, "tf_sort", 12.0 * ((wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0)), 0);
-        int64_t max_set_rows = 0;
-        for (int t = wp.t0; t < wp.t1; ++t)
-            max_set_rows = std::max(max_set_rows, std::max(B.sup->task_offsets[t + 1] - B.sup->task_offsets[t],
-                                                           B.qry->task_offsets[t + 1] - B.qry->task_offsets[t]));
-        launch_tf_sort(st, a, (int)hs[ST_MAX_TF], (int)std::min<int64_t>(max_set_rows, 1 << 30));
+    const double tf_bytes = 12.0 * ((wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0));
+    // ---- the dictionaries read off the row order of the wave's lookups
+    bool join = jr && jr->so && c->index_path != 1;
+    ValEnc enc = kPlainVals;
+    if (join) {
+        const int pbits = bits_for((int64_t)hs[ST_MAX_BAG]), fbits = bits_for(F);
+        const int rbits = bits_for(jr->n_sup_rows + jr->n_qry_rows);
+        if (rbits + fbits + pbits > 32 || (task_sort_passes(Tw) > 1 && !w.tmid_keys)) join = false;
+        else enc = ValEnc{fbits + pbits > 0 ? fbits + pbits : 1, pbits, (1u << fbits) - 1u};
+        if (join && enc.rshift + rbits > 32) join = false;   // (no field and no position bits: the shift of 1 marks the form)
     }
-    return GM_OK;
-}
-
-// The lookups of samples [s0, s1) of the support set and [q0, q1) of the query set, ordered by global row and cut into
-// one segment per distinct row.  Gradient-buffer rows are row0_* + the batch-wide padded row of the sample (mod 2^32).
-struct SortRange {
-    int64_t s0, s1, q0, q1;      // samples
-    int64_t ls0, ls1, lq0, lq1;  // their lookups
-    u32 row0_s, row0_q;
-};
-
-static int global_order(gm_ctx* c, Batch& B, SortBufs& so, const SortRange& r, int64_t* emb_rows, int64_t* seg_counts,
-                        int64_t capacity, int64_t* n_rows, bool on_side = false) {
-    hipStream_t st = on_side ? c->side : c->stream;
-    u32* status = on_side ? c->d_status_side : c->d_status;
-    const int F = c->F;
-    const gm_set *sup = B.sup, *qry = B.qry;
-    BatchBufs& b = B.b;
-    const int64_t n_s = r.ls1 - r.ls0, nnz = n_s + (r.lq1 - r.lq0);
-    Prof p(c, "global_sort", 0, 0, st, true);
-    if (F > 0) {
-        launch_build_keys(st, F, c->d_field_base, sup->bag_offsets + r.s0 * F, sup->indices, (r.s1 - r.s0) * F, r.ls0,
-                          b.prow_s + r.s0, r.row0_s, so.keys, so.vals);
-        launch_build_keys(st, F, c->d_field_base, qry->bag_offsets + r.q0 * F, qry->indices, (r.q1 - r.q0) * F, r.lq0,
-                          b.prow_q + r.q0, r.row0_q, so.keys + n_s, so.vals + n_s);
+    if (jr && c->index_path == 2 && !join)
+        return fail(c, GM_ERR_CAPACITY, "index_path 2: the wave's lookups cannot be ordered as one list of 32-bit bit-field values");
+    if (join) {
+        SortBufs& so = *jr->so;
+        global_order(c, B, so, jr->range, nullptr, nullptr, jr->capacity, nullptr, false, enc, ORDER_SORT);
+        {
+            Prof p(c, "tf_sort", tf_bytes, 0);
+            const int64_t nw = (wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0);
+            int uniform_shift = -1;   // all tasks of the wave of one power-of-two size (padded rows, both sets alike)?
+            {
+                const int64_t r0 = B.poff_s[wp.t0 + 1] - B.poff_s[wp.t0];
+                bool same = r0 > 0 && (r0 & (r0 - 1)) == 0;
+                for (int t = wp.t0; t < wp.t1 && same; ++t)
+                    same = B.poff_s[t + 1] - B.poff_s[t] == r0 && B.poff_q[t + 1] - B.poff_q[t] == r0;
+                if (same) uniform_shift = bits_for(r0);
+            }
+            TaskOf tk{w.row_task_s, w.row_task_q, (u32)jr->n_sup_rows, (u32)(jr->n_sup_rows + jr->n_qry_rows), enc.rshift, uniform_shift};
+            launch_task_sort(st, so.keys, so.vals, w.tmid_keys, w.tmid_vals, so.keys_tmp, so.vals_tmp, nw, Tw, tk, so.hist);
+            TfJoinArgs a;
+            memset(&a, 0, sizeof a);
+            a.F = F; a.Tw = Tw; a.keys = so.keys_tmp; a.vals = so.vals_tmp;
+            a.cnt_s = w.cnt_s; a.base_s = w.base_s; a.cnt_q = w.cnt_q; a.base_q = w.base_q;
+            a.rshift = enc.rshift; a.pshift = enc.pshift; a.n_sup_rows = (u32)jr->n_sup_rows;
+            a.n_slots = w.n_slots; a.slot_rows = w.slot_rows; a.slot_start = w.slot_start;
+            a.sup_sorted = w.sup_sorted; a.qry_sorted = w.qry_sorted; a.qseg_lo = w.qseg_lo; a.qseg_hi = w.qseg_hi;
+            // the slot of every lookup (scattered 4-byte writes) only where the sparse row kernel may read it
+            const bool write_slots = jr->slots || !jr->pair_only || cap > PAIR_MAX_CAP || (int)hs[ST_MAX_BAG] > PAIR_MAX_BAG;
+            a.sup_slot = write_slots ? w.sup_slot : nullptr;
+            a.qry_slot = write_slots ? w.qry_slot : nullptr;
+            w.slots_written = write_slots;
+            a.bag_s = B.sup->bag_offsets; a.bag_q = B.qry->bag_offsets;
+            a.sample0_s = wp.s0; a.sample0_q = wp.q0; a.lookup0_s = wp.ls0; a.lookup0_q = wp.lq0;
+            a.n_lookups_s = wp.ls1 - wp.ls0; a.n_lookups_q = wp.lq1 - wp.lq0;
+            a.row_off_s = w.row_off_s; a.row_off_q = w.row_off_q; a.real_off_s = w.real_off_s; a.real_off_q = w.real_off_q;
+            launch_tf_join(st, a);
+        }
+        // (the list in task order is done with: the second pair of buffers is free for the segment scan)
+        if (jr->n_rows)
+            global_order(c, B, so, jr->range, jr->emb_rows, jr->seg_counts, jr->capacity, jr->n_rows, false, enc, ORDER_SEGMENTS);
+        jr->used = true;
+        jr->enc = enc;
+        return GM_OK;
     }
-    int bits = 1;
-    while (((int64_t)1 << bits) < c->field_base[c->F]) ++bits;
-    const int passes = launch_radix_sort(st, so.keys, so.vals, so.keys_tmp, so.vals_tmp, nnz, bits, so.hist);
-    // algorithmic bytes: keys built from the lookups (4 B index read, 8 B of key and value written, 8 B of offsets per bag),
-    // 20 B per key and radix pass (the key read for the digit counts; key and value read and written by the scatter),
-    // the sorted keys read once more for the segments
-    p.p.bytes = (double)nnz * (12.0 + 20.0 * passes + (n_rows ? 4.0 : 0.0)) + 8.0 * F * ((r.s1 - r.s0) + (r.q1 - r.q0));
-    if (passes & 1) {
-        std::swap(so.keys, so.keys_tmp);   // an odd number of passes leaves the result in the second pair of buffers
-        std::swap(so.vals, so.vals_tmp);
-    }
-    // the table-shaped output adds every segment to the row its key names: no segment numbers, no row list
-    if (n_rows)
-        launch_segments(st, so.keys, nnz, so.keys_tmp, so.scan_tmp, emb_rows, so.seg_start, seg_counts, capacity, n_rows,
-                        status);
+    w.slots_written = true;
+    sort_task_fields(c, B, wp, w, (int)hs[ST_MAX_TF]);
     return GM_OK;
 }
 
@@ -1445,6 +1556,8 @@ static int count_pairs(gm_ctx* c, const Batch& B, const WavePlan& wp, WaveBufs& 
         int rc = read_status(c, hs);
         if (rc != GM_OK) return rc;
         if (hs[ST_PAIR_OVF]) any_sparse = true;   // some task's flag was cleared on the device
+        // the sparse kernel reads the slot of every lookup: written now if the wave was planned without it
+        if (any_sparse && !w.slots_written) sort_task_fields(c, B, wp, w, max_tf);
     }
     return GM_OK;
 }
@@ -1462,6 +1575,7 @@ struct Prepared {
     int bm = 64;
     int tf_cap = 0, max_bag = 0, max_tf = 0;
     bool pair = false, any_sparse = false;
+    ValEnc enc = kPlainVals;   // how the values of the ordered lookups name their bags
 };
 
 // The step.  pre: null, or the batch's index side prepared beforehand (one wave, row-list output); no_sync: return with
@@ -1521,6 +1635,8 @@ static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set*
         ~SideGuard() { if (active) (void)hipStreamSynchronize(c->side); }
     } side{c};
     bool side_list = false;
+    bool list_ordered = false;   // row-list output: the batch's lookups were ordered and cut into segments inside its (only) wave
+    ValEnc enc = kPlainVals;     // how the values that travel with the row keys name their bags
 
     // meta theta in the padded internal layout (and its bf16 operand copies); accumulators
     for (int l = 1; l <= L; ++l) {
@@ -1551,15 +1667,29 @@ static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set*
         const bool adapt = c->adapt_rows != 0;
         int tf_cap = 0, max_bag = 0, max_tf = 0;
         bool pair = false, any_sparse = false, pairs_on_side = false;
+        bool ordered = false;   // this wave's lookups are in row order already (its dictionaries were read off that order)
         if (pre) {
+            enc = pre->enc;
             gs = pre->gs; gq = pre->gq;
             tf_cap = pre->tf_cap; max_bag = pre->max_bag; max_tf = pre->max_tf;
             pair = pre->pair; any_sparse = pre->any_sparse;
         } else {
             if ((rc = setup_wave(c, B, wp, bm, K, w, d, gs, gq))) return rc;
-            // a0: row dictionaries and the overlap join
-            rc = run_index_wave(c, B, wp, w, &tf_cap, &max_bag, &max_tf);
+            // a0: row dictionaries and the overlap join -- read off the row order of the wave's lookups when that order
+            // is the one the sparse gradient needs (table-shaped output: every wave's own; row list: a batch of one wave)
+            JoinReq jr;
+            if (F > 0 && !c->overlap_sort && (table || plans.size() == 1)) {
+                jr.so = table ? &w.so : &b.so;
+                jr.range = table ? SortRange{wp.s0, wp.s1, wp.q0, wp.q1, wp.ls0, wp.ls1, wp.lq0, wp.lq1,
+                                             (u32)(0 - (uint64_t)wp.ps0), (u32)((uint64_t)d.Ps - (uint64_t)wp.pq0)}
+                                 : whole_batch_range(B);
+                jr.n_sup_rows = d.Ps; jr.n_qry_rows = d.Pq;
+                if (!table) { jr.emb_rows = out->emb_rows; jr.capacity = capacity; jr.n_rows = out->n_emb_rows; }
+                jr.pair_only = d.pair && !d.any_sparse;
+            }
+            rc = run_index_wave(c, B, wp, w, &tf_cap, &max_bag, &max_tf, &jr);
             if (rc != GM_OK) return rc;
+            if (jr.used) { ordered = true; enc = jr.enc; }
             if ((rc = count_pairs(c, B, wp, w, d, K, tf_cap, max_bag, max_tf, true, pair, any_sparse, pairs_on_side))) return rc;
             if (pairs_on_side) side.active = true;
         }
@@ -1575,6 +1705,7 @@ static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set*
             if (hs[ST_PAIR_OVF]) any_sparse = true;
             if (c->row_path == 2 && any_sparse && adapt)
                 return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a task, count, bag or (task, field) exceeds its limits");
+            if (any_sparse && !w.slots_written) sort_task_fields(c, B, wp, w, max_tf);
             return GM_OK;
         };
         if (!pairs_on_side && c->row_path == 2 && any_sparse && adapt)
@@ -1839,13 +1970,15 @@ static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set*
                               (u32)(0 - (uint64_t)wp.ps0), (u32)((uint64_t)d.Ps - (uint64_t)wp.pq0)};
             const int64_t nw = d.nnz_s + d.nnz_q;
             if (side_table) HIPCHK(c, hipStreamWaitEvent(st, c->ev_side, 0));
-            else global_order(c, B, w.so, r, nullptr, nullptr, nw, nullptr);
+            else if (!ordered) global_order(c, B, w.so, r, nullptr, nullptr, nw, nullptr);
             {
                 Prof p(c, "seg_reduce", (double)nw * (4.0 * D + 4), 0);
-                launch_seg_reduce(st, D, w.so.keys, w.so.keys_tmp, nullptr, nw, nw, w.so.vals, w.GX, nullptr,
-                                  w.so.seg_partial, table);
+                launch_seg_reduce(st, D, F, ordered ? enc : kPlainVals, w.so.keys, w.so.keys_tmp, nullptr, nw, nw, w.so.vals, w.GX,
+                                  nullptr, w.so.seg_partial, table);
             }
             if (side_table) HIPCHK(c, hipEventRecord(c->ev_main, st));
+        } else if (ordered) {
+            list_ordered = true;
         }
     }
 
@@ -1855,16 +1988,17 @@ static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set*
         launch_unpack_weights(st, b.g_theta + c->offb[l], 1, c->dims[l], c->dims[l], out->db[l - 1]);
     }
     launch_sum_to_scalar(st, task_loss, T, loss, 0);
-    if (!pre) launch_fill_u32(st, c->d_status, ST_WORDS, 0);
+    // (a batch whose segments were cut inside its wave keeps the status words of that: the row count, the capacity flag)
+    if (!pre && !list_ordered) launch_fill_u32(st, c->d_status, ST_WORDS, 0);
     if (table) {
         launch_fill_u32(st, reinterpret_cast<u32*>(out->n_emb_rows), 2, 0u);
     } else {
         if (side_list) HIPCHK(c, hipStreamWaitEvent(st, c->ev_side, 0));
-        else if (!pre) global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows);
+        else if (!pre && !list_ordered) global_order(c, B, b.so, whole_batch_range(B), out->emb_rows, nullptr, capacity, out->n_emb_rows);
         if (F > 0) {
             Prof p(c, "seg_reduce", (double)nnz * (4.0 * D + 4), 0);
-            launch_seg_reduce(st, D, b.so.keys, b.so.keys_tmp, out->n_emb_rows, capacity, nnz, b.so.vals,
-                              b.GX, out->emb_grad, b.so.seg_partial, nullptr);
+            launch_seg_reduce(st, D, F, (pre || list_ordered) ? enc : kPlainVals, b.so.keys, b.so.keys_tmp, out->n_emb_rows, capacity, nnz,
+                              b.so.vals, b.GX, out->emb_grad, b.so.seg_partial, nullptr);
         }
     }
     if (pre && no_sync) return GM_OK;   // the caller drains the stream; a prepared batch has passed every check already
@@ -2025,6 +2159,7 @@ static int prepare_batch(gm_ctx* c, Arena& ia, int32_t T, const gm_set* sup, con
     rc = check_set(c, qry, T, "query");
     if (rc != GM_OK) return rc;
     P = Prepared();
+    JoinReq jr;
     Batch& B = P.B;
     B.T = T; B.sup = sup; B.qry = qry; B.table = false;
     if ((rc = begin_batch(c, B, ia, capacity, true, nullptr))) return rc;
@@ -2036,14 +2171,24 @@ static int prepare_batch(gm_ctx* c, Arena& ia, int32_t T, const gm_set* sup, con
     if (ia.overflow) return fail(c, GM_ERR_WORKSPACE, "the batch's index structures do not fit their arena");
     if (T > 0) {
         if ((rc = setup_wave(c, B, P.wp, P.bm, K, P.w, P.d, P.gs, P.gq))) return rc;
-        if ((rc = run_index_wave(c, B, P.wp, P.w, &P.tf_cap, &P.max_bag, &P.max_tf))) return rc;
+        if (c->F > 0) {
+            jr.so = &B.b.so;
+            jr.range = whole_batch_range(B);
+            jr.n_sup_rows = P.d.Ps; jr.n_qry_rows = P.d.Pq;
+            jr.emb_rows = emb_rows; jr.capacity = capacity; jr.n_rows = n_rows;
+            jr.pair_only = P.d.pair && !P.d.any_sparse;
+        }
+        if ((rc = run_index_wave(c, B, P.wp, P.w, &P.tf_cap, &P.max_bag, &P.max_tf, &jr))) return rc;
+        if (jr.used) P.enc = jr.enc;
         bool on_side = false;
         if ((rc = count_pairs(c, B, P.wp, P.w, P.d, K, P.tf_cap, P.max_bag, P.max_tf, false, P.pair, P.any_sparse, on_side))) return rc;
         if (c->row_path == 2 && P.any_sparse && c->adapt_rows)
             return fail(c, GM_ERR_CAPACITY, "pair-count path forced, but a task, count, bag or (task, field) exceeds its limits");
     }
-    launch_fill_u32(c->stream, c->d_status, ST_WORDS, 0);
-    global_order(c, B, B.b.so, whole_batch_range(B), emb_rows, nullptr, capacity, n_rows);
+    if (!jr.used) {
+        launch_fill_u32(c->stream, c->d_status, ST_WORDS, 0);
+        global_order(c, B, B.b.so, whole_batch_range(B), emb_rows, nullptr, capacity, n_rows);
+    }
     u32 hs[ST_WORDS];
     if ((rc = read_status(c, hs))) return rc;
     HIPCHK(c, hipGetLastError());
@@ -2428,6 +2573,7 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
     if (rc != GM_OK) return rc;
     const size_t mark = ar.off;
     int64_t packed0 = 0;
+    bool ordered = false;
     for (const WavePlan& wp : plans) {
         ar.off = mark;
         const int Tw = wp.t1 - wp.t0;
@@ -2435,8 +2581,20 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
         WaveBufs w;
         const WaveDims d = wave_dims(c, B, wp, 64, 0, 1);
         alloc_wave(c, ar, w, d, 1, 2);
-        rc = run_index_wave(c, B, wp, w);
+        if (ar.overflow) return fail(c, GM_ERR_WORKSPACE, "internal: wave does not fit");
+        Grp gs, gq;
+        if ((rc = setup_wave(c, B, wp, 64, 0, w, d, gs, gq))) return rc;
+        JoinReq jr;
+        if (plans.size() == 1) {   // the batch-wide order is this wave's: both come out of one sort
+            jr.so = &B.b.so;
+            jr.range = whole_batch_range(B);
+            jr.n_sup_rows = d.Ps; jr.n_qry_rows = d.Pq;
+            jr.emb_rows = emb_rows; jr.seg_counts = seg_counts; jr.capacity = capacity; jr.n_rows = n_emb_rows;
+            jr.slots = true;
+        }
+        rc = run_index_wave(c, B, wp, w, nullptr, nullptr, nullptr, &jr);
         if (rc != GM_OK) return rc;
+        ordered = jr.used;
         const int64_t TF = (int64_t)Tw * F;
         hipLaunchKernelGGL(widen_u32_kernel, dim3((unsigned)((TF + 255) / 256)), dim3(256), 0, st, w.n_slots, TF,
                            slot_counts + (int64_t)wp.t0 * F);
@@ -2451,8 +2609,10 @@ extern "C" int gm_index_prep(gm_ctx* c, int32_t T, const gm_set* sup, const gm_s
         HIPCHK(c, hipStreamSynchronize(st));
         packed0 += h_total;
     }
-    launch_fill_u32(st, c->d_status, ST_WORDS, 0);
-    global_order(c, B, B.b.so, whole_batch_range(B), emb_rows, seg_counts, capacity, n_emb_rows);
+    if (!ordered) {
+        launch_fill_u32(st, c->d_status, ST_WORDS, 0);
+        global_order(c, B, B.b.so, whole_batch_range(B), emb_rows, seg_counts, capacity, n_emb_rows);
+    }
     u32 hs[ST_WORDS];
     rc = read_status(c, hs);
     if (rc != GM_OK) return rc;

@@ -619,9 +619,12 @@ void launch_tf_sort(hipStream_t st, const TfSortArgs& a, int max_tf, int max_set
 // ------------------------------------------------------------------------------------------------
 // One workgroup per 256 consecutive bags: their lookups are one contiguous range, walked by all lanes with
 // coalesced reads and writes; the bag of a lookup is found by bisection of the 257 staged offsets.
+// The value of a lookup names its bag in the gradient buffer: (row of the sample) * F + field when enc.rshift is 0, else
+// the bit fields row << rshift | field << pshift | position of the lookup in its bag (ValEnc).
 __global__ __launch_bounds__(256) void build_keys_kernel(int F, const int64_t* field_base, const int64_t* bag_offsets,
                                                          const int32_t* indices, int64_t n_bags, int64_t lookup0,
-                                                         const int32_t* __restrict__ row_map, u32 row0, u32* keys, u32* vals) {
+                                                         const int32_t* __restrict__ row_map, u32 row0, ValEnc enc, u32* keys,
+                                                         u32* vals) {
     __shared__ int64_t offs[257];
     const int64_t b0 = (int64_t)blockIdx.x * 256;
     const int nb = (int)min<int64_t>(256, n_bags - b0);
@@ -637,19 +640,20 @@ __global__ __launch_bounds__(256) void build_keys_kernel(int F, const int64_t* f
         }
         const int64_t b = b0 + lo;
         const int f = (int)(b % F);
+        const u32 row = row0 + (u32)row_map[b / F];   // row of the sample in the gradient buffer
         keys[p - lookup0] = (u32)field_base[f] + (u32)indices[p];
-        vals[p - lookup0] = (row0 + (u32)row_map[b / F]) * (u32)F + (u32)f;  // (row of the sample, field) in the gradient buffer
+        vals[p - lookup0] = enc.rshift ? (row << enc.rshift) | ((u32)f << enc.pshift) | (u32)(p - offs[lo]) : row * (u32)F + (u32)f;
     }
 }
 
 // bag_offsets / row_map point at the first bag / sample of the range (a multiple of F bags); lookup0 is the range's first
 // lookup: keys and vals are numbered from it
 void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const int64_t* bag_offsets,
-                       const int32_t* indices, int64_t n_bags, int64_t lookup0, const int32_t* row_map, u32 row0, u32* keys,
-                       u32* vals) {
+                       const int32_t* indices, int64_t n_bags, int64_t lookup0, const int32_t* row_map, u32 row0, ValEnc enc,
+                       u32* keys, u32* vals) {
     if (n_bags <= 0) return;
     hipLaunchKernelGGL(build_keys_kernel, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, st, F, field_base,
-                       bag_offsets, indices, n_bags, lookup0, row_map, row0, keys, vals);
+                       bag_offsets, indices, n_bags, lookup0, row_map, row0, enc, keys, vals);
 }
 
 #define RS_NT 256
@@ -665,8 +669,17 @@ __device__ __forceinline__ int rs_tile_of_block(int nblk) {
     return (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
 }
 
-template <int BITS>
-__global__ void radix_hist_kernel(const u32* keys, int64_t n, int shift, u32* hist, int nblk) {
+// What a pass sorts by: a digit of the key, or (BYTASK) a digit of the task that the value's sample belongs to --
+// the stable pass that turns the (field, row) order of a wave's lookups into (task, field, row) order.
+__device__ __forceinline__ u32 rs_task_of(const TaskOf& m, u32 val) {
+    const u32 r = min(val >> m.rshift, m.n_rows - 1u);   // (every value names a row of the wave; the bound keeps any other inside the tables)
+    // tasks of one size (a power of two of padded rows in both sets): the task is a shift of the row, no table read
+    if (m.uniform_shift >= 0) return (r < m.n_sup_rows ? r : r - m.n_sup_rows) >> m.uniform_shift;
+    return (u32)(r < m.n_sup_rows ? m.row_task_s[r] : m.row_task_q[r - m.n_sup_rows]);
+}
+
+template <int BITS, bool BYTASK>
+__global__ void radix_hist_kernel(const u32* src, int64_t n, int shift, u32* hist, int nblk, TaskOf tk) {
     constexpr int NB = 1 << BITS;
     __shared__ u32 h[NB];
     const int tile = rs_tile_of_block(nblk);
@@ -674,10 +687,25 @@ __global__ void radix_hist_kernel(const u32* keys, int64_t n, int shift, u32* hi
     for (int i = threadIdx.x; i < NB; i += RS_NT) h[i] = 0;
     __syncthreads();
     const int64_t base = (int64_t)tile * RS_TILE;
+    const int lane = threadIdx.x & (WAVE - 1);
 #pragma unroll
     for (int i = 0; i < RS_ITEMS; ++i) {
         const int64_t idx = base + i * RS_NT + threadIdx.x;
-        if (idx < n) atomicAdd(&h[(keys[idx] >> shift) & (NB - 1)], 1u);
+        if (BYTASK) {
+            // Inside a row the lookups are in input order, i.e. by task: a hot row gives long runs of one digit, which
+            // as one atomic per lane would all queue on one counter.  One atomic per run of equal digits in the wave.
+            const bool valid = idx < n;
+            const u32 d = valid ? (rs_task_of(tk, src[idx]) >> shift) & (NB - 1) : 0xFFFFFFFFu;
+            const u32 dp = __shfl_up(d, 1, WAVE);
+            const u64 heads = __ballot(lane == 0 || d != dp);
+            if (valid && (lane == 0 || d != dp)) {
+                const u64 later = lane == 63 ? 0ull : (heads >> (lane + 1));   // heads after this lane
+                const int run = later ? __ffsll((unsigned long long)later) : 64 - lane;
+                atomicAdd(&h[d], (u32)run);
+            }
+        } else if (idx < n) {
+            atomicAdd(&h[(src[idx] >> shift) & (NB - 1)], 1u);
+        }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < NB; i += RS_NT) hist[(size_t)i * nblk + tile] = h[i];
@@ -685,14 +713,15 @@ __global__ void radix_hist_kernel(const u32* keys, int64_t n, int shift, u32* hi
 
 // Stable scatter: every wave owns a contiguous 1/4 of the tile and ranks its keys round by round (64
 // consecutive keys per round) with ballot matching, so equal digits keep their input order.
-template <int BITS>
+template <int BITS, bool BYTASK>
 __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, u32* vout, const u32* gofs,
-                                     int64_t n, int shift, int nblk) {
+                                     int64_t n, int shift, int nblk, TaskOf tk) {
     constexpr int NB = 1 << BITS, DPT = NB / RS_NT;   // digits per thread in the per-digit phase
     __shared__ u32 cnt[RS_WAVES][NB];
     __shared__ u32 digstart[NB];
     __shared__ u32 skeys[RS_TILE];
     __shared__ u32 svals[RS_TILE];
+    __shared__ uint16_t sdig[BYTASK ? RS_TILE : 1];   // the digit of every staged pair (a key names its own)
     __shared__ int sh_scan[RS_WAVES + 2];
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
     const int tile = rs_tile_of_block(nblk);
@@ -700,7 +729,7 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
     for (int i = threadIdx.x; i < RS_WAVES * NB; i += RS_NT) (&cnt[0][0])[i] = 0;
     __syncthreads();
     const int64_t tile0 = (int64_t)tile * RS_TILE;
-    u32 key[RS_ITEMS], val[RS_ITEMS], rank[RS_ITEMS];
+    u32 key[RS_ITEMS], val[RS_ITEMS], rank[RS_ITEMS], dig[RS_ITEMS];
     const u64 lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
     for (int r = 0; r < RS_ITEMS; ++r) {
@@ -708,7 +737,8 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
         const bool valid = idx < n;
         key[r] = valid ? kin[idx] : 0xFFFFFFFFu;
         val[r] = valid ? vin[idx] : 0u;
-        const u32 d = (key[r] >> shift) & (NB - 1);
+        const u32 d = ((BYTASK ? (valid ? rs_task_of(tk, val[r]) : 0u) : key[r]) >> shift) & (NB - 1);
+        dig[r] = d;
         u64 peers = __ballot(valid);
 #pragma unroll
         for (int b = 0; b < BITS; ++b) {
@@ -754,10 +784,11 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
     for (int r = 0; r < RS_ITEMS; ++r) {
         const int64_t idx = tile0 + (int64_t)w * (WAVE * RS_ITEMS) + r * WAVE + lane;
         if (idx < n) {
-            const u32 d = (key[r] >> shift) & (NB - 1);
+            const u32 d = dig[r];
             const u32 pos = digstart[d] + cnt[w][d] + rank[r];
             skeys[pos] = key[r];
             svals[pos] = val[r];
+            if (BYTASK) sdig[pos] = (uint16_t)d;
         }
     }
     __syncthreads();
@@ -766,7 +797,7 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
         const int pos = i * RS_NT + threadIdx.x;
         if (pos < tile_count) {
             const u32 k = skeys[pos];
-            const u32 d = (k >> shift) & (NB - 1);
+            const u32 d = BYTASK ? (u32)sdig[pos] : (k >> shift) & (NB - 1);
             const size_t dst = (size_t)gofs[(size_t)d * nblk + tile] + (pos - digstart[d]);
             kout[dst] = k;
             vout[dst] = svals[pos];
@@ -779,32 +810,228 @@ size_t radix_hist_words(int64_t n) {
     return (size_t)(512 * nblk + 64) + scan_tmp_words(512 * nblk);
 }
 
+template <int BITS, bool BYTASK>
+static void radix_pass(hipStream_t st, const u32* ki, const u32* vi, u32* ko, u32* vo, int64_t n, int shift, u32* hist,
+                       const TaskOf& tk) {
+    const int nblk = (int)((n + RS_TILE - 1) / RS_TILE);
+    u32* scan_tmp = hist + ((size_t)512 * nblk + 63) / 64 * 64;
+    const dim3 grid((nblk + 7) / 8 * 8);
+    hipLaunchKernelGGL((radix_hist_kernel<BITS, BYTASK>), grid, dim3(RS_NT), 0, st, BYTASK ? vi : ki, n, shift, hist, nblk, tk);
+    launch_scan_u32(st, hist, hist, (int64_t)(1 << BITS) * nblk, scan_tmp, nullptr);
+    hipLaunchKernelGGL((radix_scatter_kernel<BITS, BYTASK>), grid, dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk, tk);
+}
+
 // Returns the number of passes made: after an odd number the result is in (keys_tmp, vals_tmp).
 int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n, int bits,
                       u32* hist) {
     if (n <= 0) return 0;
-    const int nblk = (int)((n + RS_TILE - 1) / RS_TILE);
-    u32* scan_tmp = hist + ((size_t)512 * nblk + 63) / 64 * 64;
     if (bits < 1) bits = 1;
     if (bits > 32) bits = 32;
     const int p8 = (bits + 7) / 8, p9 = (bits + 8) / 9;
     const int width = p9 < p8 ? 9 : 8, passes = p9 < p8 ? p9 : p8;
+    const TaskOf none{nullptr, nullptr, 0u, 0u, 0, -1};
     u32 *ki = keys, *vi = vals, *ko = keys_tmp, *vo = vals_tmp;
     for (int p = 0; p < passes; ++p) {
-        const int shift = width * p;
-        if (width == 9) {
-            hipLaunchKernelGGL(radix_hist_kernel<9>, dim3((nblk + 7) / 8 * 8), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
-            launch_scan_u32(st, hist, hist, (int64_t)512 * nblk, scan_tmp, nullptr);
-            hipLaunchKernelGGL(radix_scatter_kernel<9>, dim3((nblk + 7) / 8 * 8), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk);
-        } else {
-            hipLaunchKernelGGL(radix_hist_kernel<8>, dim3((nblk + 7) / 8 * 8), dim3(RS_NT), 0, st, ki, n, shift, hist, nblk);
-            launch_scan_u32(st, hist, hist, (int64_t)256 * nblk, scan_tmp, nullptr);
-            hipLaunchKernelGGL(radix_scatter_kernel<8>, dim3((nblk + 7) / 8 * 8), dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk);
-        }
+        if (width == 9) radix_pass<9, false>(st, ki, vi, ko, vo, n, width * p, hist, none);
+        else radix_pass<8, false>(st, ki, vi, ko, vo, n, width * p, hist, none);
         u32* t = ki; ki = ko; ko = t;
         t = vi; vi = vo; vo = t;
     }
     return passes;
+}
+
+// The pairs of (keys, vals), which are in (field, row) order, stably re-ordered by the task of their sample: the result
+// is in (task, field, row) order, support lookups before query lookups inside a row, each in input order.  One pass
+// for up to 512 tasks into (out_keys, out_vals); two passes of at most 8 bits beyond that, the first into
+// (mid_keys, mid_vals).  The input is left as it is.
+void launch_task_sort(hipStream_t st, const u32* keys, const u32* vals, u32* mid_keys, u32* mid_vals, u32* out_keys,
+                      u32* out_vals, int64_t n, int n_tasks, const TaskOf& tk, u32* hist) {
+    if (n <= 0) return;
+    int bits = 1;
+    while ((1 << bits) < n_tasks) ++bits;
+    if (bits <= 8) {
+        radix_pass<8, true>(st, keys, vals, out_keys, out_vals, n, 0, hist, tk);
+    } else if (bits == 9) {
+        radix_pass<9, true>(st, keys, vals, out_keys, out_vals, n, 0, hist, tk);
+    } else {   // (the second pass masks with 8 bits: bits <= 16)
+        radix_pass<8, true>(st, keys, vals, mid_keys, mid_vals, n, 0, hist, tk);
+        radix_pass<8, true>(st, mid_keys, mid_vals, out_keys, out_vals, n, 8, hist, tk);
+    }
+}
+int task_sort_passes(int n_tasks) { return n_tasks > 512 ? 2 : 1; }
+
+// ------------------------------------------------------------------------------------------------
+// per-(task, field) dictionaries and overlap join read off the (task, field, row) order of the wave's lookups
+// ------------------------------------------------------------------------------------------------
+// One workgroup per (task, field): its lookups are one contiguous run of the ordered list, support lookups before
+// query lookups inside every row.  The run is walked 1024 entries at a time (four consecutive entries per thread);
+// what the entries need from before them -- how many support lookups, how many distinct support rows, and the slot of
+// the row they belong to (none when the support set does not look the row up) -- comes from one block-wide sum scan of
+// two packed counters and one segmented copy scan, carried from one 1024-entry piece to the next.  Writes exactly what
+// tf_sort_kernel writes, for (task, field)s of any size.
+template <bool SLOTS>
+__global__ __launch_bounds__(256) void tf_join_kernel(TfJoinArgs a) {
+    __shared__ int sh_scan[8];
+    __shared__ u32 sh_wstate[4];
+    const int f = blockIdx.x, t = blockIdx.y;
+    const size_t tf = (size_t)t * a.F + f;
+    const u32 ns = a.cnt_s[tf], nq = a.cnt_q[tf], B = a.base_s[tf], Bq = a.base_q[tf];
+    const u32 n = ns + nq;
+    // The run is read four entries per thread as 16-byte words, from the 16-byte boundary at or before its start: the
+    // `mis` entries in front belong to the (task, field) before and count as absent.
+    const size_t S = (size_t)B + Bq;
+    const u32 mis = (u32)(S & 3);
+    const u32* K = a.keys + (S - mis);
+    const u32* V = a.vals + (S - mis);
+    const u32 n_al = n + mis;
+    const int64_t readable = (a.n_lookups_s + a.n_lookups_q) - (int64_t)(S - mis);   // entries of the list from K on
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const u32 FLAG = 0x80000000u;
+    const u32 posmask = (1u << a.pshift) - 1u;
+    u32 a_carry = 0, u_carry = 0, st_carry = 0;   // the same on every thread
+    for (u32 c0 = 0; c0 < n_al; c0 += 1024) {
+        const u32 j0 = c0 + threadIdx.x * 4;   // position in the aligned run; entry i of the (task, field) is position i + mis
+        u32 k[6], v[5];   // k[0]: the entry before the thread's four, k[5] / v[4]: the one after
+        if ((int64_t)j0 + 4 <= readable) {
+            const uint4 kq = *reinterpret_cast<const uint4*>(K + j0), vq = *reinterpret_cast<const uint4*>(V + j0);
+            k[1] = kq.x; k[2] = kq.y; k[3] = kq.z; k[4] = kq.w;
+            v[0] = vq.x; v[1] = vq.y; v[2] = vq.z; v[3] = vq.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                k[e + 1] = (int64_t)j0 + e < readable ? K[j0 + e] : 0u;
+                v[e] = (int64_t)j0 + e < readable ? V[j0 + e] : 0u;
+            }
+        }
+        // neighbours across threads by lane shuffles; the wave's first and last lanes read theirs
+        k[0] = __shfl_up(k[4], 1, 64);
+        k[5] = __shfl_down(k[1], 1, 64);
+        v[4] = __shfl_down(v[0], 1, 64);
+        if (lane == 0) k[0] = (j0 > 0 && j0 <= n_al) ? K[j0 - 1] : 0u;
+        if (lane == 63) {
+            k[5] = j0 + 4 < n_al ? K[j0 + 4] : 0u;
+            v[4] = j0 + 4 < n_al ? V[j0 + 4] : 0u;
+        }
+        const u32 i0 = j0 - mis;   // (wraps for positions in front of the run: `in` below is false for them)
+        bool in[5];
+#pragma unroll
+        for (int e = 0; e < 5; ++e) in[e] = j0 + e >= mis && j0 + e < n_al;
+        bool sup[5], head[4];
+        int n_sup = 0, n_sh = 0;
+#pragma unroll
+        for (int e = 0; e < 5; ++e) sup[e] = in[e] && (v[e] >> a.rshift) < a.n_sup_rows;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            head[e] = in[e] && (i0 + e == 0 || k[e + 1] != k[e]);
+            n_sup += sup[e] ? 1 : 0;
+            n_sh += (head[e] && sup[e]) ? 1 : 0;
+        }
+        int total;
+        const int excl = block_excl_scan(n_sup | (n_sh << 16), sh_scan, &total);
+        u32 aex = a_carry + ((u32)excl & 0xFFFFu);        // support lookups before the thread's first entry
+        u32 uex = u_carry + ((u32)excl >> 16);            // distinct support rows before it
+        // state of an entry: slot + 1 of its row, 0 when the support set does not look the row up; set at the head of a
+        // run of equal keys and copied along the run
+        u32 stt[4];
+        u32 cur = 0;
+        bool any_head = false;
+        {
+            u32 u = uex;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (head[e]) {
+                    any_head = true;
+                    cur = sup[e] ? u + 1u : 0u;
+                    u += sup[e] ? 1u : 0u;
+                }
+                stt[e] = cur;   // valid from the thread's first head on; before it the incoming state applies
+            }
+        }
+        u32 x = any_head ? (FLAG | cur) : 0u;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const u32 y = __shfl_up(x, d, 64);
+            if (lane >= d && !(x & FLAG)) x = y;
+        }
+        if (lane == 63) sh_wstate[wv] = x;
+        u32 inc = __shfl_up(x, 1, 64);
+        if (lane == 0) inc = 0u;
+        __syncthreads();
+        u32 wave_in = FLAG | st_carry, all = FLAG | st_carry;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) {
+            const u32 s = sh_wstate[ww];
+            if (s & FLAG) {
+                all = s;
+                if (ww < wv) wave_in = s;
+            }
+        }
+        if (!(inc & FLAG)) inc = wave_in;
+        inc &= ~FLAG;
+        {
+            bool seen = false;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                seen = seen || head[e];
+                if (!seen) stt[e] = inc;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const u32 i = i0 + e;
+            if (in[e]) {
+                const u32 key = k[e + 1], val = v[e];
+                const u32 row = val >> a.rshift;
+                const bool next_same = in[e + 1] && k[e + 2] == key;
+                const int32_t slot = (int32_t)stt[e] - 1;
+                // (every index below is in range when the list is in the stated order; the checks keep a list that is
+                //  not -- a defect elsewhere -- from writing outside the (task, field)'s own ranges)
+                if (sup[e]) {
+                    if (slot >= 0 && (u32)slot < ns && aex < ns) {
+                        a.sup_sorted[B + aex] = make_int2((int)row, slot);
+                        if (head[e]) {
+                            a.slot_rows[B + slot] = key;
+                            a.slot_start[B + tf + slot] = (int32_t)(B + aex);
+                        }
+                        if (!(next_same && sup[e + 1])) a.qseg_lo[B + slot] = (int32_t)(Bq + (i - aex));
+                        if (SLOTS) {
+                            const int rel = (int)row - a.row_off_s[t];
+                            if (rel >= 0 && rel < a.real_off_s[t + 1] - a.real_off_s[t]) {
+                                const int64_t lk = a.bag_s[(a.sample0_s + a.real_off_s[t] + rel) * a.F + f] - a.lookup0_s + (val & posmask);
+                                if (lk >= 0 && lk < a.n_lookups_s) a.sup_slot[lk] = slot;
+                            }
+                        }
+                    }
+                } else if (i - aex < nq) {
+                    const u32 rq = row - a.n_sup_rows;
+                    a.qry_sorted[Bq + (i - aex)] = make_int2((int)rq, slot);
+                    if (SLOTS) {
+                        const int rel = (int)rq - a.row_off_q[t];
+                        if (rel >= 0 && rel < a.real_off_q[t + 1] - a.real_off_q[t]) {
+                            const int64_t lk = a.bag_q[(a.sample0_q + a.real_off_q[t] + rel) * a.F + f] - a.lookup0_q + (val & posmask);
+                            if (lk >= 0 && lk < a.n_lookups_q) a.qry_slot[lk] = slot;
+                        }
+                    }
+                }
+                if (!next_same && slot >= 0 && (u32)slot < ns) a.qseg_hi[B + slot] = (int32_t)(Bq + (i + 1) - (aex + (sup[e] ? 1u : 0u)));
+                aex += sup[e] ? 1u : 0u;
+            }
+        }
+        a_carry += (u32)total & 0xFFFFu;
+        u_carry += (u32)total >> 16;
+        st_carry = all & ~FLAG;
+    }
+    if (threadIdx.x == 0) {
+        const u32 nu = min(u_carry, ns);
+        a.n_slots[tf] = nu;
+        a.slot_start[B + tf + nu] = (int32_t)(B + ns);
+    }
+}
+
+void launch_tf_join(hipStream_t st, const TfJoinArgs& a) {
+    if (a.Tw <= 0 || a.F <= 0) return;
+    if (a.sup_slot) hipLaunchKernelGGL(tf_join_kernel<true>, dim3(a.F, a.Tw), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(tf_join_kernel<false>, dim3(a.F, a.Tw), dim3(256), 0, st, a);
 }
 
 __global__ void seg_emit_kernel(const u32* keys, int64_t n, const u32* scan, int64_t* emb_rows, u32* seg_start,
