@@ -234,6 +234,9 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               followed by one stable pass by task; GM_ERR_CAPACITY when that order is not the wave's own -- a
  *               row-list output over several waves -- or a gradient-buffer row, a field number and a position in a
  *               bag do not fit 32 bits together).  Identical integer structures, identical results.
+ *   "sort_fields": with the row order of "index_path": 1 (default) = the wave's row keys are laid out field after field
+ *               (the per-(task, field) counts give every lookup its place) and every field's range is sorted by
+ *               its row bits alone, in fewer radix passes; 0 = one sort on (field, row).  The same order either way.
  *   "adapt_rows": 1 (default) = the inner loop adapts the dense parameters and the looked-up embedding rows
  *               (Alg. 1); 0 = it adapts the dense parameters only and reads the embeddings as they are (the
  *               dense-only family of optimisation-based meta learners that Sec. 3.1 runs on the same

@@ -108,11 +108,37 @@ struct TfJoinArgs {
     const int32_t *row_off_s, *row_off_q, *real_off_s, *real_off_q;   // [Tw + 1] first padded row / first sample of each task
 };
 void launch_tf_join(hipStream_t st, const TfJoinArgs& a);
-// Stable LSD radix sort of (key, val) pairs on the low `bits` bits.  Returns the number of passes: after an odd
-// number the result is in (keys_tmp, vals_tmp), else in (keys, vals).
+// Independent ranges of one list that a radix pass sorts side by side (device arrays of n_seg + 1 words): range i holds
+// the keys at positions [key_base_pos[i], key_base_pos[i + 1]) in tiles [tile_base[i], tile_base[i + 1]), and its
+// digits are taken from key - key_sub[i].  n_seg == 0: the whole list is one range.
+struct SegTab {
+    int n_seg;
+    const u32 *tile_base, *key_base_pos, *key_sub;
+};
+#define RS_TILE_KEYS 2048   // keys per tile of a radix pass
+// Stable LSD radix sort of (key, val) pairs on the low `bits` bits (of key - key_sub with ranges: every range by
+// itself).  Returns the number of passes: after an odd number the result is in (keys_tmp, vals_tmp), else in (keys, vals).
 int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n,
-                      int bits, u32* hist /* radix_hist_words(n) */);
-size_t radix_hist_words(int64_t n);
+                      int bits, u32* hist /* radix_hist_words(n, ranges) */, const SegTab* seg = nullptr);
+size_t radix_hist_words(int64_t n, int extra_tiles);
+// The keys and bit-field values of a wave's lookups written field after field (a field's support lookups, then its
+// query lookups, each in input order) from the per-(task, field) counts; `tables` (field_table_words(F) words) receives
+// the fields' ranges, which field_seg_tab hands to the radix passes.
+struct FieldKeysArgs {
+    int F, t0, Tw;
+    SetView sup, qry;
+    const int64_t* field_base;
+    const u32 *cnt_s, *cnt_q;        // [Tw * F]
+    u32 *fm_off_s, *fm_off_q;        // [Tw * F] scratch: a (task, field)'s place inside its field's range, per set
+    const int32_t *prow_s, *prow_q;  // padded row of every sample (whole sets)
+    u32 row0_s, row0_q;              // added to it: the row in the gradient buffer
+    ValEnc enc;                      // bit-field form (rshift != 0)
+    u32 *keys, *vals;
+    const u32 *key_pos, *tot;        // set by the launcher
+};
+void launch_build_keys_by_field(hipStream_t st, FieldKeysArgs a, u32* tables);
+SegTab field_seg_tab(int F, u32* tables);
+size_t field_table_words(int F);
 void launch_segments(hipStream_t st, const u32* sorted_keys, int64_t n, u32* flags_scan, u32* scan_tmp,
                      int64_t* emb_rows, u32* seg_start, int64_t* seg_counts /* may be null */,
                      int64_t capacity, int64_t* n_rows_out, u32* status);

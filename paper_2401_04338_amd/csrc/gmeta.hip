@@ -82,6 +82,7 @@ struct gm_ctx {
     int adapt_rows = 1;   // 0: the inner loop adapts the dense parameters only (embedding rows are read, not updated)
     int gemm_tile_n = 0;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
+    int sort_fields = 1; // with index_path's row order: 1 = the keys are laid out field after field and every field's range sorted by row alone (fewer radix passes), 0 = one sort on (field, row)
     int index_path = 0; // per-(task, field) dictionaries: 0 = choose per wave, 1 = sorted per (task, field) in LDS, 2 = read off the wave's (task, field, row) order
     int max_wave_tasks = 0;   // 0: as many tasks per wave as the workspace holds
     char* static_scratch = nullptr;   // this device's copy of the static scratch array (gm_meta_step_static)
@@ -257,6 +258,7 @@ struct WaveBufs {
     u32* slot_rows;
     int32_t *slot_start, *sup_slot, *qry_slot, *qseg_lo, *qseg_hi;
     int2 *sup_sorted, *qry_sorted;
+    u32 *fm_off_s = nullptr, *fm_off_q = nullptr, *field_tab = nullptr;   // keys laid out field after field: places and ranges
     u32 *tmid_keys = nullptr, *tmid_vals = nullptr;   // more than 512 tasks: the first of the two passes that order the lookups by task
     bool slots_written = true;   // sup_slot / qry_slot hold the slot of every lookup (only the sparse row kernel reads them)
     float *Xs0, *Xq0, *TXf, *dX, *loss_q;
@@ -324,7 +326,7 @@ static void alloc_sort(const gm_ctx* c, Arena& ar, SortBufs& so, int64_t nnz, in
     so.vals = ar.get<u32>(nnz + 1);
     so.keys_tmp = ar.get<u32>(nnz + 1);
     so.vals_tmp = ar.get<u32>(nnz + 1);
-    so.hist = ar.get<u32>(radix_hist_words(nnz) + extra_hist_words);
+    so.hist = ar.get<u32>(radix_hist_words(nnz, c->F) + extra_hist_words);
     so.scan_tmp = ar.get<u32>(scan_tmp_words(nnz));
     so.seg_start = ar.get<u32>(std::min(nnz, max_segs) + 2);
     so.seg_partial = need_gx ? ar.get<float>(seg_reduce_partial_floats(nnz, c->D)) : nullptr;
@@ -361,6 +363,9 @@ static void alloc_wave_index(const gm_ctx* c, Arena& ar, WaveBufs& w, const Wave
     w.qry_sorted = ar.get<int2>(d.nnz_q + 1);
     w.qseg_lo = ar.get<int32_t>(d.nnz_s + 1);
     w.qseg_hi = ar.get<int32_t>(d.nnz_s + 1);
+    w.fm_off_s = ar.get<u32>(TF + 1);
+    w.fm_off_q = ar.get<u32>(TF + 1);
+    w.field_tab = ar.get<u32>(field_table_words(F));
     w.tmid_keys = w.tmid_vals = nullptr;
     if (F > 0 && c->adapt_rows && c->index_path != 1 && task_sort_passes(d.Tw) > 1) {
         w.tmid_keys = ar.get<u32>(d.nnz_s + d.nnz_q + 1);
@@ -592,6 +597,11 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
     if (!strcmp(key, "row_path")) {
         if (value < 0 || value > 2) return fail(c, GM_ERR_ARG, "row_path must be 0, 1 or 2");
         c->row_path = (int)value;
+        return GM_OK;
+    }
+    if (!strcmp(key, "sort_fields")) {
+        if (value != 0 && value != 1) return fail(c, GM_ERR_ARG, "sort_fields must be 0 or 1");
+        c->sort_fields = (int)value;
         return GM_OK;
     }
     if (!strcmp(key, "index_path")) {
@@ -1254,7 +1264,30 @@ static int run_index_wave(gm_ctx* c, Batch& B, const WavePlan& wp, WaveBufs& w, 
         return fail(c, GM_ERR_CAPACITY, "index_path 2: the wave's lookups cannot be ordered as one list of 32-bit bit-field values");
     if (join) {
         SortBufs& so = *jr->so;
-        global_order(c, B, so, jr->range, nullptr, nullptr, jr->capacity, nullptr, false, enc, ORDER_SORT);
+        if (c->sort_fields) {
+            // the keys field after field (the per-(task, field) counts give every lookup its place), then every field's
+            // range sorted by its row bits alone
+            const int64_t nw = (wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0);
+            Prof p(c, "global_sort", 0, 0, st, true);
+            FieldKeysArgs fa;
+            memset(&fa, 0, sizeof fa);
+            fa.F = F; fa.t0 = wp.t0; fa.Tw = Tw; fa.sup = vs; fa.qry = vq; fa.field_base = c->d_field_base;
+            fa.cnt_s = w.cnt_s; fa.cnt_q = w.cnt_q; fa.fm_off_s = w.fm_off_s; fa.fm_off_q = w.fm_off_q;
+            fa.prow_s = B.b.prow_s; fa.prow_q = B.b.prow_q; fa.row0_s = jr->range.row0_s; fa.row0_q = jr->range.row0_q;
+            fa.enc = enc; fa.keys = so.keys; fa.vals = so.vals;
+            launch_build_keys_by_field(st, fa, w.field_tab);
+            int64_t max_rows = 1;
+            for (int f = 0; f < F; ++f) max_rows = std::max(max_rows, c->field_base[f + 1] - c->field_base[f]);
+            const SegTab seg = field_seg_tab(F, w.field_tab);
+            const int passes = launch_radix_sort(st, so.keys, so.vals, so.keys_tmp, so.vals_tmp, nw, std::max(1, bits_for(max_rows)), so.hist, &seg);
+            p.p.bytes += (double)nw * (12.0 + 20.0 * passes) + 8.0 * F * ((wp.s1 - wp.s0) + (wp.q1 - wp.q0));
+            if (passes & 1) {
+                std::swap(so.keys, so.keys_tmp);
+                std::swap(so.vals, so.vals_tmp);
+            }
+        } else {
+            global_order(c, B, so, jr->range, nullptr, nullptr, jr->capacity, nullptr, false, enc, ORDER_SORT);
+        }
         {
             Prof p(c, "tf_sort", tf_bytes, 0);
             const int64_t nw = (wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0);

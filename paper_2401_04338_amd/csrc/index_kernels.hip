@@ -656,9 +656,153 @@ void launch_build_keys(hipStream_t st, int F, const int64_t* field_base, const i
                        bag_offsets, indices, n_bags, lookup0, row_map, row0, enc, keys, vals);
 }
 
+// ------------------------------------------------------------------------------------------------
+// the same keys laid out field after field (support lookups of a field first, then its query lookups, each in input
+// order): the field needs no sorting then -- every field's range is sorted by row alone, in fewer radix passes
+// ------------------------------------------------------------------------------------------------
+// One workgroup per field: fm_off_*[t * F + f] = lookups of field f in the tasks before t (per set), tot[f] / tot[F + f]
+// = the field's support / query lookups in the wave.
+__global__ __launch_bounds__(256) void field_offsets_kernel(int F, int Tw, const u32* cnt_s, const u32* cnt_q, u32* fm_off_s,
+                                                            u32* fm_off_q, u32* tot) {
+    __shared__ int sh[8];
+    const int f = blockIdx.x;
+    for (int set = 0; set < 2; ++set) {
+        const u32* cnt = set ? cnt_q : cnt_s;
+        u32* off = set ? fm_off_q : fm_off_s;
+        u32 run = 0;
+        for (int t0 = 0; t0 < Tw; t0 += 256) {
+            const int t = t0 + threadIdx.x;
+            const u32 c = t < Tw ? cnt[(size_t)t * F + f] : 0u;
+            int total;
+            const u32 ex = (u32)block_excl_scan((int)c, sh, &total);
+            if (t < Tw) off[(size_t)t * F + f] = run + ex;
+            run += (u32)total;
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) tot[set * F + f] = run;
+    }
+}
+
+// first key and first tile of every field's range, and what a key of the field has in front of its row number
+__global__ void field_table_kernel(int F, const u32* tot, const int64_t* field_base, int tile_keys, u32* key_pos, u32* tile_base,
+                                   u32* key_sub) {
+    if (threadIdx.x || blockIdx.x) return;
+    u32 k = 0, tl = 0;
+    for (int f = 0; f < F; ++f) {
+        key_pos[f] = k;
+        tile_base[f] = tl;
+        key_sub[f] = (u32)field_base[f];
+        const u32 nf = tot[f] + tot[F + f];
+        k += nf;
+        tl += (nf + (u32)tile_keys - 1) / (u32)tile_keys;
+    }
+    key_pos[F] = k;
+    tile_base[F] = tl;
+    key_sub[F] = 0u;
+}
+
+#define BKF_CH 1024   // bags of a task staged at a time
+// One workgroup per (field, task, set): the bags (sample, field) of the task, BKF_CH at a time -- their lengths are
+// scanned into LDS, then every lane takes lookups of the piece in order (coalesced writes), finding a lookup's bag
+// by bisection of the staged table.
+__global__ __launch_bounds__(256) void build_keys_fm_kernel(FieldKeysArgs a) {
+    __shared__ u32 sbase[BKF_CH + 1];
+    __shared__ u32 sp0[BKF_CH];
+    __shared__ int sh[8];
+    const int f = blockIdx.x, t = blockIdx.y, set = blockIdx.z;
+    const SetView& v = set ? a.qry : a.sup;
+    const size_t tf = (size_t)t * a.F + f;
+    const u32 n_tf = (set ? a.cnt_q : a.cnt_s)[tf];
+    if (n_tf == 0) return;
+    const int64_t s_lo = v.task_offsets[a.t0 + t], s_hi = v.task_offsets[a.t0 + t + 1];
+    const int32_t* prow = set ? a.prow_q : a.prow_s;
+    const u32 row0 = set ? a.row0_q : a.row0_s;
+    const u32 fb = (u32)a.field_base[f];
+    size_t dest = (size_t)a.key_pos[f] + (set ? a.tot[f] : 0u) + (set ? a.fm_off_q : a.fm_off_s)[tf];
+    for (int64_t c0 = s_lo; c0 < s_hi; c0 += BKF_CH) {
+        const int nb = (int)min<int64_t>(BKF_CH, s_hi - c0);
+        __syncthreads();   // the table of the piece before has been read
+        {
+            const int b0 = (int)threadIdx.x * 4;   // four consecutive bags per thread
+            u32 len[4], p0r[4];
+            u32 sum = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                len[q] = 0; p0r[q] = 0;
+                if (b0 + q < nb) {
+                    const int64_t bag = (c0 + b0 + q) * a.F + f;
+                    const int64_t p0 = v.bag_offsets[bag];
+                    len[q] = (u32)(v.bag_offsets[bag + 1] - p0);
+                    p0r[q] = (u32)(p0 - v.lookup0);
+                }
+                sum += len[q];
+            }
+            int total;
+            u32 run = (u32)block_excl_scan((int)sum, sh, &total);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (b0 + q < nb) {
+                    sbase[b0 + q] = run;
+                    sp0[b0 + q] = p0r[q];
+                    run += len[q];
+                }
+            if (threadIdx.x == 0) sbase[nb] = (u32)total;
+        }
+        __syncthreads();
+        const u32 total = sbase[nb];
+        for (u32 e0 = threadIdx.x; e0 < total; e0 += 4 * 256) {
+            int bag[4];
+            u32 j[4], idx[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u32 e = e0 + q * 256;
+                bag[q] = 0; j[q] = 0; idx[q] = 0;
+                if (e < total) {
+                    int lo = 0, hi = nb;   // last bag whose first lookup is <= e (empty bags share their successor's)
+                    while (hi - lo > 1) {
+                        const int mid = (lo + hi) >> 1;
+                        if (sbase[mid] <= e) lo = mid;
+                        else hi = mid;
+                    }
+                    bag[q] = lo;
+                    j[q] = e - sbase[lo];
+                    idx[q] = (u32)v.indices[v.lookup0 + sp0[lo] + j[q]];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u32 e = e0 + q * 256;
+                if (e < total) {
+                    const u32 row = row0 + (u32)prow[c0 + bag[q]];
+                    a.keys[dest + e] = fb + idx[q];
+                    a.vals[dest + e] = (row << a.enc.rshift) | ((u32)f << a.enc.pshift) | j[q];
+                }
+            }
+        }
+        dest += total;
+    }
+}
+
+// tables: 3 (F + 1) words (key_pos, tile_base, key_sub), then 2 F words of totals
+void launch_build_keys_by_field(hipStream_t st, FieldKeysArgs a, u32* tables) {
+    if (a.F <= 0 || a.Tw <= 0) return;
+    u32* key_pos = tables;
+    u32* tile_base = key_pos + (a.F + 1);
+    u32* key_sub = tile_base + (a.F + 1);
+    u32* tot = key_sub + (a.F + 1);
+    hipLaunchKernelGGL(field_offsets_kernel, dim3(a.F), dim3(256), 0, st, a.F, a.Tw, a.cnt_s, a.cnt_q, a.fm_off_s, a.fm_off_q, tot);
+    hipLaunchKernelGGL(field_table_kernel, dim3(1), dim3(64), 0, st, a.F, tot, a.field_base, RS_TILE_KEYS, key_pos, tile_base, key_sub);
+    a.key_pos = key_pos;
+    a.tot = tot;
+    hipLaunchKernelGGL(build_keys_fm_kernel, dim3(a.F, a.Tw, 2), dim3(256), 0, st, a);
+}
+SegTab field_seg_tab(int F, u32* tables) { return SegTab{F, tables + (F + 1), tables, tables + 2 * (F + 1)}; }
+size_t field_table_words(int F) { return (size_t)5 * (F + 1); }
+
 #define RS_NT 256
 #define RS_ITEMS 8
 #define RS_TILE (RS_NT * RS_ITEMS)
+static_assert(RS_TILE == RS_TILE_KEYS, "tile size");
 #define RS_WAVES (RS_NT / WAVE)
 
 // Digits are BITS wide (8 or 9): 25-bit row keys sort in three 9-bit passes instead of four 8-bit ones.
@@ -678,15 +822,57 @@ __device__ __forceinline__ u32 rs_task_of(const TaskOf& m, u32 val) {
     return (u32)(r < m.n_sup_rows ? m.row_task_s[r] : m.row_task_q[r - m.n_sup_rows]);
 }
 
+// A pass may sort several independent ranges of the list at once (SegTab: the fields of a wave's lookups, each range
+// holding one field's keys).  Tiles then never straddle two ranges: tile numbers run range after range, a range's
+// share of the digit-count table is laid out [digit][tile of the range] behind the shares of the ranges before it, so
+// that ONE exclusive scan over the whole table still yields every (range, digit, tile)'s place in the output; the
+// digit is taken from the key minus the range's key base.  seg.n_seg == 0: one range, the whole list.
+struct RsTile {
+    int64_t k0, k1;      // keys of the tile
+    u32 key_base;        // subtracted from a key before its digit is taken
+    size_t h0;           // count-table index of (digit 0, this tile)
+    size_t hstride;      // ... and the distance between digits
+    bool any;
+};
+__device__ __forceinline__ RsTile rs_tile(const SegTab& seg, int tile, int nblk, int64_t n, int nb) {
+    RsTile t;
+    if (seg.n_seg == 0) {
+        t.k0 = (int64_t)tile * RS_TILE;
+        t.k1 = min(n, t.k0 + RS_TILE);
+        t.key_base = 0u;
+        t.h0 = (size_t)tile;
+        t.hstride = (size_t)nblk;
+        t.any = tile < nblk;
+        return t;
+    }
+    int lo = 0, hi = seg.n_seg;   // last range whose first tile is <= tile
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (seg.tile_base[mid] <= (u32)tile) lo = mid;
+        else hi = mid;
+    }
+    const u32 tb = seg.tile_base[lo], te = seg.tile_base[lo + 1];
+    t.any = (u32)tile < te;       // (tiles past the last range's: nothing to do)
+    t.k0 = (int64_t)seg.key_base_pos[lo] + (int64_t)((u32)tile - tb) * RS_TILE;
+    t.k1 = min((int64_t)seg.key_base_pos[lo + 1], t.k0 + RS_TILE);
+    t.key_base = seg.key_sub[lo];
+    t.hstride = (size_t)(te - tb);
+    t.h0 = (size_t)nb * tb + ((u32)tile - tb);
+    return t;
+}
+
 template <int BITS, bool BYTASK>
-__global__ void radix_hist_kernel(const u32* src, int64_t n, int shift, u32* hist, int nblk, TaskOf tk) {
+__global__ void radix_hist_kernel(const u32* src, int64_t n, int shift, u32* hist, int nblk, TaskOf tk, SegTab seg) {
     constexpr int NB = 1 << BITS;
     __shared__ u32 h[NB];
     const int tile = rs_tile_of_block(nblk);
     if (tile >= nblk) return;
+    const RsTile T = rs_tile(seg, tile, nblk, n, NB);
+    if (!T.any) return;
     for (int i = threadIdx.x; i < NB; i += RS_NT) h[i] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)tile * RS_TILE;
+    const int64_t base = T.k0;
+    const int64_t n_end = T.k1;
     const int lane = threadIdx.x & (WAVE - 1);
 #pragma unroll
     for (int i = 0; i < RS_ITEMS; ++i) {
@@ -694,7 +880,7 @@ __global__ void radix_hist_kernel(const u32* src, int64_t n, int shift, u32* his
         if (BYTASK) {
             // Inside a row the lookups are in input order, i.e. by task: a hot row gives long runs of one digit, which
             // as one atomic per lane would all queue on one counter.  One atomic per run of equal digits in the wave.
-            const bool valid = idx < n;
+            const bool valid = idx < n_end;
             const u32 d = valid ? (rs_task_of(tk, src[idx]) >> shift) & (NB - 1) : 0xFFFFFFFFu;
             const u32 dp = __shfl_up(d, 1, WAVE);
             const u64 heads = __ballot(lane == 0 || d != dp);
@@ -703,19 +889,19 @@ __global__ void radix_hist_kernel(const u32* src, int64_t n, int shift, u32* his
                 const int run = later ? __ffsll((unsigned long long)later) : 64 - lane;
                 atomicAdd(&h[d], (u32)run);
             }
-        } else if (idx < n) {
-            atomicAdd(&h[(src[idx] >> shift) & (NB - 1)], 1u);
+        } else if (idx < n_end) {
+            atomicAdd(&h[((src[idx] - T.key_base) >> shift) & (NB - 1)], 1u);
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < NB; i += RS_NT) hist[(size_t)i * nblk + tile] = h[i];
+    for (int i = threadIdx.x; i < NB; i += RS_NT) hist[T.h0 + (size_t)i * T.hstride] = h[i];
 }
 
 // Stable scatter: every wave owns a contiguous 1/4 of the tile and ranks its keys round by round (64
 // consecutive keys per round) with ballot matching, so equal digits keep their input order.
 template <int BITS, bool BYTASK>
 __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, u32* vout, const u32* gofs,
-                                     int64_t n, int shift, int nblk, TaskOf tk) {
+                                     int64_t n_all, int shift, int nblk, TaskOf tk, SegTab seg) {
     constexpr int NB = 1 << BITS, DPT = NB / RS_NT;   // digits per thread in the per-digit phase
     __shared__ u32 cnt[RS_WAVES][NB];
     __shared__ u32 digstart[NB];
@@ -726,9 +912,11 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
     const int tile = rs_tile_of_block(nblk);
     if (tile >= nblk) return;
+    const RsTile T = rs_tile(seg, tile, nblk, n_all, NB);
+    if (!T.any) return;
     for (int i = threadIdx.x; i < RS_WAVES * NB; i += RS_NT) (&cnt[0][0])[i] = 0;
     __syncthreads();
-    const int64_t tile0 = (int64_t)tile * RS_TILE;
+    const int64_t tile0 = T.k0, n = T.k1;
     u32 key[RS_ITEMS], val[RS_ITEMS], rank[RS_ITEMS], dig[RS_ITEMS];
     const u64 lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
@@ -737,7 +925,7 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
         const bool valid = idx < n;
         key[r] = valid ? kin[idx] : 0xFFFFFFFFu;
         val[r] = valid ? vin[idx] : 0u;
-        const u32 d = ((BYTASK ? (valid ? rs_task_of(tk, val[r]) : 0u) : key[r]) >> shift) & (NB - 1);
+        const u32 d = ((BYTASK ? (valid ? rs_task_of(tk, val[r]) : 0u) : key[r] - T.key_base) >> shift) & (NB - 1);
         dig[r] = d;
         u64 peers = __ballot(valid);
 #pragma unroll
@@ -797,34 +985,39 @@ __global__ void radix_scatter_kernel(const u32* kin, const u32* vin, u32* kout, 
         const int pos = i * RS_NT + threadIdx.x;
         if (pos < tile_count) {
             const u32 k = skeys[pos];
-            const u32 d = BYTASK ? (u32)sdig[pos] : (k >> shift) & (NB - 1);
-            const size_t dst = (size_t)gofs[(size_t)d * nblk + tile] + (pos - digstart[d]);
+            const u32 d = BYTASK ? (u32)sdig[pos] : ((k - T.key_base) >> shift) & (NB - 1);
+            const size_t dst = (size_t)gofs[T.h0 + (size_t)d * T.hstride] + (pos - digstart[d]);
             kout[dst] = k;
             vout[dst] = svals[pos];
         }
     }
 }
 
-size_t radix_hist_words(int64_t n) {
-    const int64_t nblk = (n + RS_TILE - 1) / RS_TILE;
+// extra_tiles: tiles beyond ceil(n / tile) that a pass over several ranges may need (one per range)
+size_t radix_hist_words(int64_t n, int extra_tiles) {
+    const int64_t nblk = (n + RS_TILE - 1) / RS_TILE + extra_tiles;
     return (size_t)(512 * nblk + 64) + scan_tmp_words(512 * nblk);
 }
 
 template <int BITS, bool BYTASK>
 static void radix_pass(hipStream_t st, const u32* ki, const u32* vi, u32* ko, u32* vo, int64_t n, int shift, u32* hist,
-                       const TaskOf& tk) {
-    const int nblk = (int)((n + RS_TILE - 1) / RS_TILE);
+                       const TaskOf& tk, const SegTab& seg) {
+    // ranges: at most one partly filled tile per range beyond the tiles of the whole list; the count table is cleared
+    // first, since the tiles past the last range's write nothing into it
+    const int nblk = (int)((n + RS_TILE - 1) / RS_TILE) + seg.n_seg;
     u32* scan_tmp = hist + ((size_t)512 * nblk + 63) / 64 * 64;
     const dim3 grid((nblk + 7) / 8 * 8);
-    hipLaunchKernelGGL((radix_hist_kernel<BITS, BYTASK>), grid, dim3(RS_NT), 0, st, BYTASK ? vi : ki, n, shift, hist, nblk, tk);
+    if (seg.n_seg) launch_fill_u32(st, hist, (int64_t)(1 << BITS) * nblk, 0u);
+    hipLaunchKernelGGL((radix_hist_kernel<BITS, BYTASK>), grid, dim3(RS_NT), 0, st, BYTASK ? vi : ki, n, shift, hist, nblk, tk, seg);
     launch_scan_u32(st, hist, hist, (int64_t)(1 << BITS) * nblk, scan_tmp, nullptr);
-    hipLaunchKernelGGL((radix_scatter_kernel<BITS, BYTASK>), grid, dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk, tk);
+    hipLaunchKernelGGL((radix_scatter_kernel<BITS, BYTASK>), grid, dim3(RS_NT), 0, st, ki, vi, ko, vo, hist, n, shift, nblk, tk, seg);
 }
 
 // Returns the number of passes made: after an odd number the result is in (keys_tmp, vals_tmp).
 int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* vals_tmp, int64_t n, int bits,
-                      u32* hist) {
+                      u32* hist, const SegTab* seg_in) {
     if (n <= 0) return 0;
+    const SegTab seg = seg_in ? *seg_in : SegTab{0, nullptr, nullptr, nullptr};
     if (bits < 1) bits = 1;
     if (bits > 32) bits = 32;
     const int p8 = (bits + 7) / 8, p9 = (bits + 8) / 9;
@@ -832,8 +1025,8 @@ int launch_radix_sort(hipStream_t st, u32* keys, u32* vals, u32* keys_tmp, u32* 
     const TaskOf none{nullptr, nullptr, 0u, 0u, 0, -1};
     u32 *ki = keys, *vi = vals, *ko = keys_tmp, *vo = vals_tmp;
     for (int p = 0; p < passes; ++p) {
-        if (width == 9) radix_pass<9, false>(st, ki, vi, ko, vo, n, width * p, hist, none);
-        else radix_pass<8, false>(st, ki, vi, ko, vo, n, width * p, hist, none);
+        if (width == 9) radix_pass<9, false>(st, ki, vi, ko, vo, n, width * p, hist, none, seg);
+        else radix_pass<8, false>(st, ki, vi, ko, vo, n, width * p, hist, none, seg);
         u32* t = ki; ki = ko; ko = t;
         t = vi; vi = vo; vo = t;
     }
@@ -849,13 +1042,14 @@ void launch_task_sort(hipStream_t st, const u32* keys, const u32* vals, u32* mid
     if (n <= 0) return;
     int bits = 1;
     while ((1 << bits) < n_tasks) ++bits;
+    const SegTab one{0, nullptr, nullptr, nullptr};
     if (bits <= 8) {
-        radix_pass<8, true>(st, keys, vals, out_keys, out_vals, n, 0, hist, tk);
+        radix_pass<8, true>(st, keys, vals, out_keys, out_vals, n, 0, hist, tk, one);
     } else if (bits == 9) {
-        radix_pass<9, true>(st, keys, vals, out_keys, out_vals, n, 0, hist, tk);
+        radix_pass<9, true>(st, keys, vals, out_keys, out_vals, n, 0, hist, tk, one);
     } else {   // (the second pass masks with 8 bits: bits <= 16)
-        radix_pass<8, true>(st, keys, vals, mid_keys, mid_vals, n, 0, hist, tk);
-        radix_pass<8, true>(st, mid_keys, mid_vals, out_keys, out_vals, n, 8, hist, tk);
+        radix_pass<8, true>(st, keys, vals, mid_keys, mid_vals, n, 0, hist, tk, one);
+        radix_pass<8, true>(st, mid_keys, mid_vals, out_keys, out_vals, n, 8, hist, tk, one);
     }
 }
 int task_sort_passes(int n_tasks) { return n_tasks > 512 ? 2 : 1; }

@@ -1,6 +1,7 @@
 """The two ways the HIP path builds the per-(task, field) row dictionaries, lookup lists and the overlap join of
 Sec. 2.1.2: every (task, field) sorted by itself (gm_configure("index_path", 1)), or read off the row order of the wave's
-lookups plus one stable pass by task ("index_path", 2).  Both must give the oracle's integer structures bit for bit,
+lookups plus one stable pass by task ("index_path", 2; that row order from one sort on (field, row) or, "sort_fields",
+from the fields' ranges sorted by row alone).  All must give the oracle's integer structures bit for bit,
 and a meta step must come out identical whichever built them.
 """
 import numpy as np
@@ -15,18 +16,20 @@ from tests.test_gpu_parity import TOL_FP32, _compare_step, _inputs, _params_dev,
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("path", [1, 2], ids=["per_task_field", "row_order"])
+@pytest.mark.parametrize("path,by_field", [(1, 1), (2, 0), (2, 1)], ids=["per_task_field", "row_order", "row_order_by_field"])
 @pytest.mark.parametrize("cfg", [small_cfg(n_tasks=5, rows_per_field=12, bag_max=5), TINY, SMALL.with_(n_tasks=6),
                                  small_cfg(n_tasks=1, n_fields=1, rows_per_field=3, bag_max=1, n_support=9, n_query=4),
                                  small_cfg(n_tasks=700, n_fields=2, rows_per_field=9, bag_max=3, n_support=3, n_query=2)],
                          ids=["mini", "tiny", "small6", "one_field_one_lookup", "700_tasks"])
-def test_index_prep_bit_exact_on_both_paths(gm, cfg, path):
+def test_index_prep_bit_exact_on_both_paths(gm, cfg, path, by_field):
     """Slots, row lists, the slot of every lookup and the batch-wide segments against the oracle.  "700_tasks" needs two
-    passes to order the lookups by task (more than 512 tasks); "one_field_one_lookup" has no field or position bits."""
-    print("index_prep", cfg.name, "index_path", path, flush=True)
+    passes to order the lookups by task (more than 512 tasks); "one_field_one_lookup" has no field or position bits.
+    The row order itself is made either by one sort on (field, row) or ("sort_fields", the default) field by field."""
+    print("index_prep", cfg.name, "index_path", path, "sort_fields", by_field, flush=True)
     sup, qry, _ = _inputs(cfg)
     ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
     ctx.configure("index_path", path)
+    ctx.configure("sort_fields", by_field)
     got = ctx.index_prep(_to_dev(sup, ctx.device), _to_dev(qry, ctx.device))
     ref = O.index_prep(oracle_model(cfg), sup.numpy(), qry.numpy())
     for k in ("slot_counts", "slot_rows", "sup_slot", "qry_slot", "emb_rows", "seg_counts"):
@@ -77,16 +80,17 @@ def test_step_is_identical_on_both_index_paths(gm, case):
     dev = ctx.device
     ds, dq, dp = _to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev)
     res, tables = [], []
-    for path in (1, 2, 0):
+    for path, by_field in ((1, 1), (2, 1), (2, 0), (0, 1)):
         ctx.configure("index_path", path)
+        ctx.configure("sort_fields", by_field)
         t = torch.zeros_like(dp.emb) if table else None
         out = ctx.meta_step(ds, dq, dp, cfg.inner_lr, K, order, emb_grad_table=t)
         res.append({k: (v.clone() if torch.is_tensor(v) else [x.clone() for x in v] if isinstance(v, (list, tuple)) else v)
                     for k, v in out.items()})
         tables.append(t)
     nl = len(cfg.layer_dims) - 1
-    _same_bits(res[0], res[1], nl, tables[0], tables[1])
-    _same_bits(res[0], res[2], nl, tables[0], tables[2])
+    for i in (1, 2, 3):
+        _same_bits(res[0], res[i], nl, tables[0], tables[i])
     if not table and cfg.mlp_dtype == 0:
         ctx.configure("index_path", 2)
         _compare_step(cfg, ctx, sup, qry, params, K, order, TOL_FP32, f"{case} index_path=2")
