@@ -35,8 +35,9 @@ struct SetView {
     int64_t n_samples;           // samples of the whole set
 };
 
+// uniform_rows: the number of rows every table has, or -1 when the tables differ in size
 void launch_tf_count(hipStream_t st, int F, int t0, int Tw, SetView sup, SetView qry, const int64_t* field_base,
-                     int64_t nnz_sup, int64_t nnz_qry, u32* cnt_sup, u32* cnt_qry, u32* status);
+                     int64_t nnz_sup, int64_t nnz_qry, int64_t uniform_rows, u32* cnt_sup, u32* cnt_qry, u32* status);
 void launch_scan_u32(hipStream_t st, const u32* in, u32* out, int64_t n, u32* tmp /* >= n/1024+2048 */,
                      u32* total /* may be null */);
 size_t scan_tmp_words(int64_t n);

@@ -1190,6 +1190,12 @@ struct JoinReq {
     ValEnc enc = kPlainVals;
 };
 
+static int64_t uniform_rows(const gm_ctx* c) {   // rows of every table when they are all of one size, else -1
+    for (int f = 1; f < c->F; ++f)
+        if (c->rows[f] != c->rows[0]) return -1;
+    return c->F > 0 ? c->rows[0] : -1;
+}
+
 static int bits_for(int64_t n) {   // bits that hold every value below n
     int b = 0;
     while (((int64_t)1 << b) < n) ++b;
@@ -1230,7 +1236,7 @@ static int run_index_wave(gm_ctx* c, Batch& B, const WavePlan& wp, WaveBufs& w, 
     launch_fill_u32(st, c->d_status, ST_WORDS, 0);
     {
         Prof p(c, "tf_count", 8.0 * ((wp.s1 - wp.s0) + (wp.q1 - wp.q0)) * F + 4.0 * ((wp.ls1 - wp.ls0) + (wp.lq1 - wp.lq0)), 0);
-        launch_tf_count(st, F, wp.t0, Tw, vs, vq, c->d_field_base, B.sup->nnz, B.qry->nnz, w.cnt_s, w.cnt_q, c->d_status);
+        launch_tf_count(st, F, wp.t0, Tw, vs, vq, c->d_field_base, B.sup->nnz, B.qry->nnz, uniform_rows(c), w.cnt_s, w.cnt_q, c->d_status);
     }
     u32 hs[ST_WORDS];
     int rc = read_status(c, hs);
@@ -2538,7 +2544,7 @@ extern "C" int gm_gather_pool(gm_ctx* c, int32_t T, const gm_set* set, const flo
     launch_fill_u32(st, c->d_status, ST_WORDS, 0);
     SetView v = make_view(set, toff, 0, 0);
     if (c->F > 0 && T > 0)
-        launch_tf_count(st, c->F, 0, T, v, v, c->d_field_base, set->nnz, set->nnz, cnt, cnt + (int64_t)T * c->F + 1, c->d_status);
+        launch_tf_count(st, c->F, 0, T, v, v, c->d_field_base, set->nnz, set->nnz, uniform_rows(c), cnt, cnt + (int64_t)T * c->F + 1, c->d_status);
     u32 hs[ST_WORDS];
     rc = read_status(c, hs);
     if (rc != GM_OK) return rc;

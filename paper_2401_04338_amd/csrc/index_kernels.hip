@@ -44,8 +44,10 @@ __device__ __forceinline__ int block_excl_scan(int v, int* sh, int* total) {
 // One task per blockIdx.x, its bags dealt to gridDim.y workgroups; cnt_sup / cnt_qry must be zero on entry.
 // A well-formed input that exceeds a size limit of the index kernels (a bag of more than 65,535 lookups, a task of more
 // than 65,536 samples in one set) raises ST_TOO_LARGE, not ST_BAD_INDEX.
+// uniform_rows >= 0: every table has that many rows, so an index is checked without knowing its field: the task's
+// lookups, one contiguous range, are then read by all lanes in order instead of bag by bag.
 __global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const int64_t* field_base,
-                                int64_t nnz_sup, int64_t nnz_qry, u32* cnt_sup, u32* cnt_qry, u32* status) {
+                                int64_t nnz_sup, int64_t nnz_qry, int64_t uniform_rows, u32* cnt_sup, u32* cnt_qry, u32* status) {
     extern __shared__ u32 sh_cnt[];  // [2F]
     const int t = blockIdx.x;
     for (int i = threadIdx.x; i < 2 * F; i += blockDim.x) sh_cnt[i] = 0;
@@ -70,13 +72,22 @@ __global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const i
                 too_large = true;
                 continue;
             }
-            const int64_t R = field_base[f + 1] - field_base[f];
-            for (int64_t p = p0; p < p1; ++p) {
-                const int32_t r = v.indices[p];
-                if (r < 0 || r >= R) bad = true;
+            if (uniform_rows < 0) {
+                const int64_t R = field_base[f + 1] - field_base[f];
+                for (int64_t p = p0; p < p1; ++p) {
+                    const int32_t r = v.indices[p];
+                    if (r < 0 || r >= R) bad = true;
+                }
             }
             atomicAdd(&sh_cnt[set * F + f], (u32)(p1 - p0));
             longest = max(longest, (u32)(p1 - p0));
+        }
+        if (uniform_rows >= 0 && n > 0) {   // (offsets outside [0, nnz] are flagged above; the range read here is clamped)
+            const int64_t q0 = min(max(v.bag_offsets[s_lo * F], (int64_t)0), nnz), q1 = min(max(v.bag_offsets[s_hi * F], q0), nnz);
+            for (int64_t p = q0 + (int64_t)blockIdx.y * blockDim.x + threadIdx.x; p < q1; p += (int64_t)gridDim.y * blockDim.x) {
+                const int32_t r = v.indices[p];
+                if (r < 0 || r >= uniform_rows) bad = true;
+            }
         }
     }
     if (t == 0 && blockIdx.y == 0 && threadIdx.x == 0) {  // the ends of both offset arrays
@@ -97,14 +108,14 @@ __global__ void tf_count_kernel(int F, int t0, SetView sup, SetView qry, const i
 }
 
 void launch_tf_count(hipStream_t st, int F, int t0, int Tw, SetView sup, SetView qry, const int64_t* field_base,
-                     int64_t nnz_sup, int64_t nnz_qry, u32* cnt_sup, u32* cnt_qry, u32* status) {
+                     int64_t nnz_sup, int64_t nnz_qry, int64_t uniform_rows, u32* cnt_sup, u32* cnt_qry, u32* status) {
     if (Tw <= 0) return;
     launch_fill_u32(st, cnt_sup, (int64_t)Tw * F, 0u);
     if (cnt_qry != cnt_sup) launch_fill_u32(st, cnt_qry, (int64_t)Tw * F, 0u);
     // enough workgroups to fill the chip whatever the number of tasks in the wave
     const int split = Tw >= 2048 ? 1 : (Tw >= 512 ? 4 : 8);
     hipLaunchKernelGGL(tf_count_kernel, dim3(Tw, split), dim3(256), 2 * F * sizeof(u32), st, F, t0, sup, qry, field_base,
-                       nnz_sup, nnz_qry, cnt_sup, cnt_qry, status);
+                       nnz_sup, nnz_qry, uniform_rows, cnt_sup, cnt_qry, status);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -877,20 +888,19 @@ __global__ void radix_hist_kernel(const u32* src, int64_t n, int shift, u32* his
 #pragma unroll
     for (int i = 0; i < RS_ITEMS; ++i) {
         const int64_t idx = base + i * RS_NT + threadIdx.x;
-        if (BYTASK) {
-            // Inside a row the lookups are in input order, i.e. by task: a hot row gives long runs of one digit, which
-            // as one atomic per lane would all queue on one counter.  One atomic per run of equal digits in the wave.
-            const bool valid = idx < n_end;
-            const u32 d = valid ? (rs_task_of(tk, src[idx]) >> shift) & (NB - 1) : 0xFFFFFFFFu;
-            const u32 dp = __shfl_up(d, 1, WAVE);
-            const u64 heads = __ballot(lane == 0 || d != dp);
-            if (valid && (lane == 0 || d != dp)) {
-                const u64 later = lane == 63 ? 0ull : (heads >> (lane + 1));   // heads after this lane
-                const int run = later ? __ffsll((unsigned long long)later) : 64 - lane;
-                atomicAdd(&h[d], (u32)run);
-            }
-        } else if (idx < n_end) {
-            atomicAdd(&h[((src[idx] - T.key_base) >> shift) & (NB - 1)], 1u);
+        // One atomic per run of equal digits in the wave instead of one per lane.  By task: inside a row the lookups
+        // are in input order, i.e. by task, so a hot row gives long runs of one digit, which as one atomic per lane
+        // would all queue on one counter.  By key: from the second pass on the keys of a hot row lie next to each
+        // other (they share every digit sorted so far), and LDS atomics retire about one lane per cycle.
+        const bool valid = idx < n_end;
+        u32 d = 0xFFFFFFFFu;
+        if (valid) d = ((BYTASK ? rs_task_of(tk, src[idx]) : src[idx] - T.key_base) >> shift) & (NB - 1);
+        const u32 dp = __shfl_up(d, 1, WAVE);
+        const u64 heads = __ballot(lane == 0 || d != dp);
+        if (valid && (lane == 0 || d != dp)) {
+            const u64 later = lane == 63 ? 0ull : (heads >> (lane + 1));   // heads after this lane
+            const int run = later ? __ffsll((unsigned long long)later) : 64 - lane;
+            atomicAdd(&h[d], (u32)run);
         }
     }
     __syncthreads();

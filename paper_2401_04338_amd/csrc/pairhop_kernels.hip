@@ -89,36 +89,47 @@ __global__ __launch_bounds__(NT) void pair_count_kernel(PairCountArgs a) {
     if (threadIdx.x == 0) { sh_nhot = 0; sh_ncold = 0; }
     __syncthreads();
     {
-        // four loads in flight per thread and list: the workgroup has the compute unit to itself, so nothing else hides
+        // eight loads in flight per thread and list: the workgroup has the compute unit to itself, so nothing else hides
         // the latency of these first reads
         auto stage_rows = [&](const int2* list, int n_entries, int row0, uint16_t* dst) {
-            for (int e0 = threadIdx.x; e0 < n_entries; e0 += 4 * NT) {
-                int r[4];
+            for (int e0 = threadIdx.x; e0 < n_entries; e0 += 8 * NT) {
+                int r[8];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) r[q] = list[min(e0 + q * NT, n_entries - 1)].x;
+                for (int q = 0; q < 8; ++q) r[q] = list[min(e0 + q * NT, n_entries - 1)].x;
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < 8; ++q)
                     if (e0 + q * NT < n_entries) dst[e0 + q * NT] = (uint16_t)(r[q] - row0);
             }
         };
         stage_rows(a.sup_sorted + B, n_in_entries, a.row_off_s[t], in_rows);   // {row, slot}, slot-sorted
         if (qs) stage_rows(a.qry_sorted + Bq, n_out_entries, a.row_off_q[t], out_rows);
     }
-    for (int u = threadIdx.x; u < nu; u += NT) {
-        const int lo = a.slot_start[B + tf + u] - (int)B, hi = a.slot_start[B + tf + u + 1] - (int)B;
-        int lo2 = lo, hi2 = hi;
-        if (qs) { lo2 = a.qseg_lo[B + u] - (int)Bq; hi2 = a.qseg_hi[B + u] - (int)Bq; }
-        const int na = hi - lo, nb = hi2 - lo2;
-        if (na <= 0 || nb <= 0) continue;
-        if (na >= PC_HOT || nb >= PC_HOT) {
-            const int k = atomicAdd(&sh_nhot, 1);
-            if (2 * k + 1 < RW) {
-                recs[2 * k] = (u32)lo | ((u32)hi << 16);
-                recs[2 * k + 1] = (u32)lo2 | ((u32)hi2 << 16);
+    for (int u0 = threadIdx.x; u0 < nu; u0 += 4 * NT) {   // (the loads of four rows in flight per thread)
+        int lo_[4], hi_[4], lo2_[4], hi2_[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int u = min(u0 + q * NT, nu - 1);
+            lo_[q] = a.slot_start[B + tf + u] - (int)B;
+            hi_[q] = a.slot_start[B + tf + u + 1] - (int)B;
+            lo2_[q] = lo_[q]; hi2_[q] = hi_[q];
+            if (qs) { lo2_[q] = a.qseg_lo[B + u] - (int)Bq; hi2_[q] = a.qseg_hi[B + u] - (int)Bq; }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (u0 + q * NT >= nu) continue;
+            const int lo = lo_[q], hi = hi_[q], lo2 = lo2_[q], hi2 = hi2_[q];
+            const int na = hi - lo, nb = hi2 - lo2;
+            if (na <= 0 || nb <= 0) continue;
+            if (na >= PC_HOT || nb >= PC_HOT) {
+                const int k = atomicAdd(&sh_nhot, 1);
+                if (2 * k + 1 < RW) {
+                    recs[2 * k] = (u32)lo | ((u32)hi << 16);
+                    recs[2 * k + 1] = (u32)lo2 | ((u32)hi2 << 16);
+                }
+            } else {
+                const int k = atomicAdd(&sh_ncold, 1);
+                if (k < RW) recs[RW - 1 - k] = (u32)lo | ((u32)lo2 << 14) | ((u32)na << 28) | ((u32)nb << 30);
             }
-        } else {
-            const int k = atomicAdd(&sh_ncold, 1);
-            if (k < RW) recs[RW - 1 - k] = (u32)lo | ((u32)lo2 << 14) | ((u32)na << 28) | ((u32)nb << 30);
         }
     }
     __syncthreads();
@@ -223,14 +234,31 @@ __global__ __launch_bounds__(NT) void pair_count_kernel(PairCountArgs a) {
             }
         }
         __syncthreads();
-        // ---- rows [i0, i0 + rows_here) of M: a thread gathers four consecutive columns of one row
-        const int wpr = colsP / 4;
-        for (int w = threadIdx.x; w < rows_here * wpr; w += NT) {
-            const int i = w / wpr, j4 = (w - i * wpr) * 4;
-            const u32 c0 = tile[(j4 + 0) * ldT + i], c1 = tile[(j4 + 1) * ldT + i];
-            const u32 c2 = tile[(j4 + 2) * ldT + i], c3 = tile[(j4 + 3) * ldT + i];
-            ovf |= (c0 == 255u) | (c1 == 255u) | (c2 == 255u) | (c3 == 255u);
-            *reinterpret_cast<u32*>(M + (size_t)(i0 + i) * colsP + j4) = c0 | (c1 << 8) | (c2 << 16) | (c3 << 24);
+        // ---- rows [i0, i0 + rows_here) of M.  A thread takes a 4 x 4 block of cells: four words of the transposed tile
+        //      (four rows of one column each), turned in registers into four words of M (four columns of one row each).
+        //      Of a wave, 16 lanes lie along the columns and 4 along the rows: the tile reads then spread over all
+        //      banks (a column step moves 4 banks, a row step 1), and every row gets 64 contiguous bytes per store.
+        {
+            const int jl = lane & 15, il = lane >> 4;
+            const int pj_n = colsP / 64, n_patches = pj_n * (rows_here / 16);
+            for (int wq = wv; wq < n_patches; wq += NT / 64) {
+                const int pj = wq % pj_n, pi = wq / pj_n;
+                const int j4 = (pj * 16 + jl) * 4, i4 = (pi * 4 + il) * 4;
+                const u32 ca = *reinterpret_cast<const u32*>(tile + (j4 + 0) * ldT + i4), cb = *reinterpret_cast<const u32*>(tile + (j4 + 1) * ldT + i4);
+                const u32 cc = *reinterpret_cast<const u32*>(tile + (j4 + 2) * ldT + i4), cd = *reinterpret_cast<const u32*>(tile + (j4 + 3) * ldT + i4);
+                // a byte of 255: some byte of the complement is zero
+                const u32 na_ = ~ca, nb_ = ~cb, nc_ = ~cc, nd_ = ~cd;
+                ovf |= (((na_ - 0x01010101u) & ca & 0x80808080u) | ((nb_ - 0x01010101u) & cb & 0x80808080u) |
+                        ((nc_ - 0x01010101u) & cc & 0x80808080u) | ((nd_ - 0x01010101u) & cd & 0x80808080u)) != 0u;
+                const u32 t0 = __builtin_amdgcn_perm(cb, ca, 0x05010400u), t1 = __builtin_amdgcn_perm(cb, ca, 0x07030602u);
+                const u32 u0 = __builtin_amdgcn_perm(cd, cc, 0x05010400u), u1 = __builtin_amdgcn_perm(cd, cc, 0x07030602u);
+                u32* dst = reinterpret_cast<u32*>(M + (size_t)(i0 + i4) * colsP + j4);
+                const size_t rw = (size_t)colsP / 4;
+                dst[0] = __builtin_amdgcn_perm(u0, t0, 0x05040100u);
+                dst[rw] = __builtin_amdgcn_perm(u0, t0, 0x07060302u);
+                dst[2 * rw] = __builtin_amdgcn_perm(u1, t1, 0x05040100u);
+                dst[3 * rw] = __builtin_amdgcn_perm(u1, t1, 0x07060302u);
+            }
         }
         if (Mt) {  // the transpose is the tile as it lies: row j holds columns [i0, i0 + rows_here)
             const int gpr = rows_here / 4;
