@@ -28,9 +28,11 @@ FAMILIES = {
     "two_hop": r"two_hop_kernel",
     "seg_reduce": r"seg_reduce_(chunks|join)_kernel",
     "gather_pool": r"gather_pool(_xcd)?_kernel|dense_tail_kernel",
-    "tf_sort": r"tf_sort_kernel",
+    # radix_*_kernel<BITS, BYTASK>: the pass by task belongs to the per-(task, field) dictionaries (with the join that reads
+    # them off the ordered list), the passes by row key to the ordering of the lookups by row
+    "tf_sort": r"tf_sort_kernel|tf_join_kernel|radix_(hist|scatter)_kernel<\d+, true>",
     "tf_count": r"tf_count_kernel",
-    "global_sort": r"build_keys_kernel|radix_hist_kernel|radix_scatter_kernel|seg_flags_kernel|seg_emit_kernel",
+    "global_sort": r"build_keys_kernel|build_keys_fm_kernel|field_(offsets|table)_kernel|radix_(hist|scatter)_kernel<\d+, false>|seg_flags_kernel|seg_emit_kernel",
     "task_colsum": r"task_colsum_kernel",
     "reduce_tasks": r"reduce_tasks_kernel",
     "axpy_gx": r"axpy_kernel",
