@@ -250,7 +250,16 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               row hop; 0 (default) = on the context's stream.  Identical results; ignored while
  *               "overlap_sort" is 1.
  *   "gemm_tile_n": column tile of the forward / backward grouped products when tasks get 256-row tiles:
- *               0 = chosen by the library (128), 128, or 256 (eight waves per workgroup; identical results).
+ *               0 = chosen by shape (256, the software-pipelined 256 x 256 tiles, when the contraction is at least
+ *               2048 long and the width a multiple of 256; else 128), 128, or 256.  Identical results.
+ *   "wgrad_wide": 1 (default) = the weight-gradient products that are only ever summed over tasks (they run over runs
+ *               of consecutive tasks) take the pipelined 256 x 256 tiles when a run has thousands of rows, the layer
+ *               is at least 1024 wide on the input side and a multiple of 256 on the output side, and the tiles fill
+ *               the device at least twice; 0 = always 128 x 128 tiles.  Identical results over the same runs.
+ *   "coarse_groups": number of runs of consecutive tasks for those products: 0 (default) = 16, or, when the first
+ *               layer's product takes the wide tiles, the count in [12, 16] whose tiles fill the device's last round
+ *               best; 1..32 = that many.  Another grouping adds the same per-task terms in another order
+ *               (fp32 rounding).
  *   "max_wave_tasks": most tasks processed at a time (0 = as many as the workspace holds).  Tasks are independent
  *               (Alg. 1): a call runs them in waves of nearly equal size, the fewest that fit the workspace.
  *   "pair_tile_rows": most out-rows of a pair-count matrix that the counting kernel holds in LDS at a time

@@ -212,8 +212,7 @@ __device__ __forceinline__ void gemm_epilogue_direct(const GemmBArgs& a, f32x16 
     }
 }
 
-// Waves: 2 along m, BN / 128 * 2 along n -- 4 waves for 128-wide tiles, 8 for 256-wide ones, so that a wave's share
-// is at most 128 x 64 (128 accumulator registers) whatever the block tile.
+// Four waves, 2 along m and 2 along n: a wave's share of a BM x BN tile is BM / 2 x BN / 2.
 template <int BM, int BN, bool DB, bool KA, bool KB, int EP>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
     constexpr int WN = 2;   // waves along n
@@ -403,12 +402,12 @@ typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 __device__ unsigned long long g_gemm_ts[4 * 16384];
 void gemm_timing_fetch(unsigned long long* host, int n) { (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_gemm_ts), sizeof(unsigned long long) * n); }
 #endif
-template <bool KB, int EP, bool TIMED = false>
+template <bool KA, bool KB, int EP, bool TIMED = false>
 __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmBArgs a, int n_ntiles, int mt_per_group, int n_tiles) {
     constexpr int BM = 256, BN = 256, MI = 4, NI = 4, NT = 256;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-    constexpr int LDB_K = BN + GPADK;
-    constexpr int A_ELEMS = BM * GLD;
+    constexpr int LDB_K = BN + GPADK;   // (also the row stride of a contraction-slowest A tile: BM = BN)
+    constexpr int A_ELEMS = KA ? GK * LDB_K : BM * GLD;
     constexpr int TILE = A_ELEMS + (KB ? GK * LDB_K : BN * GLD);
 
     const int per_xcd = gridDim.x >> 3;
@@ -456,7 +455,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmBArgs a, int n_
         const bf16_t* B = a.B[pr] + (int64_t)g * a.gB[pr] + r0 * a.rB[pr];
         ldA2[p2] = (u32)a.lda[pr] * 2u;
         ldB2[p2] = (u32)a.ldb[pr] * 2u;
-        rsA[p2] = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)((u32)M * ldA2[p2]), 0x00020000);
+        rsA[p2] = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)((u32)(KA ? K : M) * ldA2[p2]), 0x00020000);
         rsB[p2] = __builtin_amdgcn_make_buffer_rsrc((void*)B, 0, (int)((u32)(KB ? K : N) * ldB2[p2]), 0x00020000);
     }
     // chunk c = tid + 256 i of a tile: A (and B stored like A): row c / 8, 16 bytes at k = (c % 8) * 8;
@@ -471,9 +470,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmBArgs a, int n_
         const __amdgpu_buffer_rsrc_t rB = pr ? rsB[1] : rsB[0];
         const u32 la = pr ? ldA2[1] : ldA2[0], lb = pr ? ldB2[1] : ldB2[0];
         const bool kok = k0 + ccol < K;
-        const u32 a0 = kok ? (u32)(m0 + crow) * la + (u32)(k0 + ccol) * 2u : OOB;
+        if constexpr (KA) {   // (a column past M would read on into the next row: such a chunk is sent out of bounds)
+            const bool mok = m0 + kbcol < M;
+            const u32 a0 = mok ? (u32)(k0 + kbrow) * la + (u32)(m0 + kbcol) * 2u : OOB;
 #pragma unroll
-        for (int i = 4 * h; i < 4 * h + 4; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rA, (int)(a0 + (kok ? (u32)(32 * i) * la : 0u)), 0, 0);
+            for (int i = 4 * h; i < 4 * h + 4; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rA, (int)(a0 + (mok ? (u32)(8 * i) * la : 0u)), 0, 0);
+        } else {
+            const u32 a0 = kok ? (u32)(m0 + crow) * la + (u32)(k0 + ccol) * 2u : OOB;
+#pragma unroll
+            for (int i = 4 * h; i < 4 * h + 4; ++i) ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rA, (int)(a0 + (kok ? (u32)(32 * i) * la : 0u)), 0, 0);
+        }
         if constexpr (KB) {
             const u32 b0 = (u32)(k0 + kbrow) * lb + (u32)(n0 + kbcol) * 2u;
 #pragma unroll
@@ -486,7 +492,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmBArgs a, int n_
     };
     auto store_half = [&](bf16_t* stage, int h) {
 #pragma unroll
-        for (int i = 4 * h; i < 4 * h + 4; ++i) *reinterpret_cast<u32x4*>(stage + (crow + 32 * i) * GLD + ccol) = ra[i];
+        for (int i = 4 * h; i < 4 * h + 4; ++i) {
+            if constexpr (KA) *reinterpret_cast<u32x4*>(stage + (kbrow + 8 * i) * LDB_K + kbcol) = ra[i];
+            else *reinterpret_cast<u32x4*>(stage + (crow + 32 * i) * GLD + ccol) = ra[i];
+        }
 #pragma unroll
         for (int i = 4 * h; i < 4 * h + 4; ++i) {
             if constexpr (KB) *reinterpret_cast<u32x4*>(stage + A_ELEMS + (kbrow + 8 * i) * LDB_K + kbcol) = rb[i];
@@ -503,7 +512,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmBArgs a, int n_
     };
     auto read_frags = [&](const bf16_t* stage, int kk, bf16x8 (&af)[MI], bf16x8 (&bfr)[NI]) {
 #pragma unroll
-        for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const bf16x8*>(stage + (wm0 + i * 32 + l32) * GLD + kk * 16 + lhi * 8);
+        for (int i = 0; i < MI; ++i) {
+            if constexpr (KA) af[i] = frag_tr(stage, wm0 + i * 32, kk * 16);
+            else af[i] = *reinterpret_cast<const bf16x8*>(stage + (wm0 + i * 32 + l32) * GLD + kk * 16 + lhi * 8);
+        }
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             if constexpr (KB) bfr[j] = frag_tr(stage + A_ELEMS, wn0 + j * 32, kk * 16);
@@ -539,7 +551,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmBArgs a, int n_
         bf16_t* nxt = smem + ((kt + 1) & 1) * TILE;
         // instruction order of a step: the fragment reads first, then one LDS write or one memory request in the
         // shadow of every MFMA (0x100 LDS read, 0x200 LDS write, 0x020 memory read, 0x008 MFMA)
-        constexpr int NR = KB ? 12 : 8;   // LDS reads of one set of fragments
+        constexpr int NR = 8 + (KA ? 4 : 0) + (KB ? 4 : 0);   // LDS reads of one set of fragments
         __builtin_amdgcn_sched_barrier(0);
         read_frags(cur, 1, fa1, fb1);
         mfmas(fa0, fb0);
@@ -613,15 +625,15 @@ static void tile_counts(const GemmBArgs& a, int BM, int BN, int& n_ntiles, int& 
     n_tiles = (n_mtiles <= 0 || n_ntiles <= 0) ? 0 : n_mtiles * n_ntiles;
 }
 
-template <bool KB, int EP, bool TIMED = false>
+template <bool KA, bool KB, int EP, bool TIMED = false>
 static void launch_pipe(hipStream_t st, const GemmBArgs& a) {
     constexpr int BM = 256, BN = 256;
     int n_ntiles, mt_per_group;
     int64_t n_tiles;
     tile_counts(a, BM, BN, n_ntiles, mt_per_group, n_tiles);
     if (n_tiles <= 0) return;
-    const size_t shmem = ((size_t)BM * GLD + (KB ? (size_t)GK * (BN + GPADK) : (size_t)BN * GLD)) * sizeof(bf16_t) * 2;
-    auto kern = gemm_bf16_pipe_kernel<KB, EP, TIMED>;
+    const size_t shmem = ((KA ? (size_t)GK * (BM + GPADK) : (size_t)BM * GLD) + (KB ? (size_t)GK * (BN + GPADK) : (size_t)BN * GLD)) * sizeof(bf16_t) * 2;
+    auto kern = gemm_bf16_pipe_kernel<KA, KB, EP, TIMED>;
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     const unsigned grid = (unsigned)((n_tiles + 7) / 8 * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), shmem, st, a, n_ntiles, mt_per_group, (int)n_tiles);
@@ -648,7 +660,7 @@ static void launch_variant(hipStream_t st, const GemmBArgs& a) {
 // K = rows of a task) is bound by the theta' it writes and keeps 128 x 128.
 template <bool KB, int EP>
 static void launch_rows_form(hipStream_t st, const GemmBArgs& a, int bm, int bn) {
-    if (bm == 256 && bn == 256) launch_pipe<KB, EP>(st, a);
+    if (bm == 256 && bn == 256) launch_pipe<false, KB, EP>(st, a);
     else if (bm == 256) launch_variant<256, 128, false, KB, EP>(st, a);
     else if (bm == 128) launch_variant<128, 128, false, KB, EP>(st, a);
     else launch_variant<64, 128, false, KB, EP_RUNTIME>(st, a);
@@ -665,14 +677,22 @@ void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm, int bn) {
     }
 }
 
-// Weight-gradient form: both operands stored with the contraction index slowest (A [K, M], B [K, N]).
-void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a) {
+// Weight-gradient form: both operands stored with the contraction index slowest (A [K, M], B [K, N]).  tile: 128, or 256
+// (the pipelined 256 x 256 kernel; N a multiple of 256): worth it when the contraction is thousands of rows long -- per
+// task (K = a task's rows, every task writing its own [M, N]) the product is bound by what it writes, and more
+// workgroups per compute unit hide that better than wider tiles.
+template <int EP>
+static void launch_kmajor_tile(hipStream_t st, const GemmBArgs& a, int tile) {
+    if (tile == 256) launch_pipe<true, true, EP>(st, a);
+    else launch_variant<128, 128, true, true, EP>(st, a);
+}
+void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a, int tile) {
     switch (ep_of(a)) {
-        case EPI_AXPBY | EP_CF: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CF>(st, a); break;
-        case EPI_AXPBY | EP_CF | EP_CB: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CF | EP_CB>(st, a); break;
-        case EPI_AXPBY | EP_CF | EP_CIN: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CF | EP_CIN>(st, a); break;
-        case EPI_AXPBY | EP_CF | EP_CB | EP_CIN: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CF | EP_CB | EP_CIN>(st, a); break;
-        case EPI_AXPBY | EP_CB | EP_CIN: launch_variant<128, 128, true, true, EPI_AXPBY | EP_CB | EP_CIN>(st, a); break;
+        case EPI_AXPBY | EP_CF: launch_kmajor_tile<EPI_AXPBY | EP_CF>(st, a, tile); break;
+        case EPI_AXPBY | EP_CF | EP_CB: launch_kmajor_tile<EPI_AXPBY | EP_CF | EP_CB>(st, a, tile); break;
+        case EPI_AXPBY | EP_CF | EP_CIN: launch_kmajor_tile<EPI_AXPBY | EP_CF | EP_CIN>(st, a, tile); break;
+        case EPI_AXPBY | EP_CF | EP_CB | EP_CIN: launch_kmajor_tile<EPI_AXPBY | EP_CF | EP_CB | EP_CIN>(st, a, tile); break;
+        case EPI_AXPBY | EP_CB | EP_CIN: launch_kmajor_tile<EPI_AXPBY | EP_CB | EP_CIN>(st, a, tile); break;
         default: launch_variant<128, 128, true, true, EP_RUNTIME>(st, a); break;
     }
 }
@@ -688,8 +708,8 @@ void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm, int bn
 
 #ifdef GEMM_TIMING
 void launch_gemm_bf16_timed(hipStream_t st, const GemmBArgs& a, bool kb) {   // development: per-phase cycle counts of the pipelined kernel
-    if (kb) launch_pipe<true, EPI_BIAS_RELU | EP_CB, true>(st, a);
-    else launch_pipe<false, EPI_MASK | EP_CB, true>(st, a);
+    if (kb) launch_pipe<false, true, EPI_BIAS_RELU | EP_CB, true>(st, a);
+    else launch_pipe<false, false, EPI_MASK | EP_CB, true>(st, a);
 }
 #endif
 

@@ -288,7 +288,7 @@ struct GemmBArgs {
 void launch_gemm_bf16(hipStream_t st, const GemmBArgs& a, int bm, int bn = 128);   // bn = 256 (with bm = 256): the pipelined 256 x 256 kernel
 // same product with both operands stored contraction-slowest: A_p element (k, m) at A + g*gA + r0*rA + k*lda + m,
 // B_p element (k, n) at B + g*gB + r0*rB + k*ldb + n
-void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a);
+void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a, int tile = 128);   // tile: 128, or 256 (N % 256 == 0)
 // A contraction-contiguous as in launch_gemm_bf16, B stored contraction-slowest (element (k, n) at ... + k*ldb + n)
 void launch_gemm_bf16_bkmajor(hipStream_t st, const GemmBArgs& a, int bm, int bn = 128);
 void launch_convert_weights(hipStream_t st, const float* src, int64_t g_src, int G, int rows, int cols, bf16_t* w,

@@ -81,6 +81,9 @@ struct gm_ctx {
     int pair_tile_rows = 0;
     int adapt_rows = 1;   // 0: the inner loop adapts the dense parameters only (embedding rows are read, not updated)
     int gemm_tile_n = 0;
+    int wgrad_wide = 1;      // weight gradients over runs of tasks in 256 x 256 tiles where the shape allows
+    int coarse_groups = 0;   // runs of tasks for the products only summed over tasks (0: chosen by shape)
+    int n_cus = 256;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
     int sort_fields = 1; // with index_path's row order: 1 = the keys are laid out field after field and every field's range sorted by row alone (fewer radix passes), 0 = one sort on (field, row)
     int index_path = 0; // per-(task, field) dictionaries: 0 = choose per wave, 1 = sorted per (task, field) in LDS, 2 = read off the wave's (task, field, row) order
@@ -248,7 +251,7 @@ struct SortBufs {
     float* seg_partial = nullptr;
 };
 
-enum { COARSE_GROUPS = 16 };
+enum { COARSE_GROUPS = 32 };   // most runs of tasks (gm_configure "coarse_groups" says how many are used)
 
 struct WaveBufs {
     int32_t *row_off_s, *row_off_q, *real_off_s, *real_off_q;
@@ -396,7 +399,7 @@ static void alloc_wave_dense(const gm_ctx* c, Arena& ar, WaveBufs& w, const Wave
     w.dX = ar.get<float>(std::max(d.Ps, d.Pq) * (int64_t)std::max(c->FD, 1) + 4);
     w.loss_q = ar.get<float>(d.Pq + 1);
     w.v = alloc_theta(c, ar, d.Tw, true);
-    w.vsum = Theta{ar.get<float>((int64_t)COARSE_GROUPS * c->n_theta), c->n_theta, nullptr, 0};
+    w.vsum = Theta{ar.get<float>((int64_t)std::max(16, c->coarse_groups) * c->n_theta), c->n_theta, nullptr, 0};
     if (!second) w.v.b = nullptr;  // the direction is a GEMM operand only in the second-order pass
     w.Xs_scratch = Act();
     if (K > 1 && !second) {
@@ -513,6 +516,10 @@ extern "C" int gm_create(gm_ctx** out, const gm_model_desc* model, int device, v
     c->device = device;
     c->stream = reinterpret_cast<hipStream_t>(hip_stream);
     HIPCHK(c, hipSetDevice(device));
+    {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && n > 0) c->n_cus = n;
+    }
     if (device < 0 || device >= GM_MAX_DEVICES) return fail(c, GM_ERR_ARG, "device must be in [0, %d)", (int)GM_MAX_DEVICES);
     if (!g_scratch_ptr[device]) {   // once per device, with that device current: every GPU holds its own copy
         void* p = nullptr;
@@ -572,6 +579,16 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
     if (!strcmp(key, "gemm_tile_n")) {   // column tile of the forward / backward products with 256-row tiles (0: chosen by shape)
         if (value != 0 && value != 128 && value != 256) return fail(c, GM_ERR_ARG, "gemm_tile_n must be 0, 128 or 256");
         c->gemm_tile_n = (int)value;
+        return GM_OK;
+    }
+    if (!strcmp(key, "wgrad_wide")) {
+        if (value != 0 && value != 1) return fail(c, GM_ERR_ARG, "wgrad_wide must be 0 or 1");
+        c->wgrad_wide = (int)value;
+        return GM_OK;
+    }
+    if (!strcmp(key, "coarse_groups")) {
+        if (value < 0 || value > COARSE_GROUPS) return fail(c, GM_ERR_ARG, "coarse_groups must be in [0, 32]");
+        c->coarse_groups = (int)value;
         return GM_OK;
     }
     if (!strcmp(key, "adapt_rows")) {
@@ -876,6 +893,32 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
     }
 }
 
+// Weight gradient [M, N] of G groups over `rows` rows in all: the pipelined 256 x 256 tiles pay once the contraction of a
+// group is thousands of rows long and the tiles fill the device several times over.
+static bool wgrad_wide_ok(const gm_ctx* c, int M, int N, int64_t rows, int G) {
+    return c->wgrad_wide && c->mlp_dtype && M >= 1024 && N % 256 == 0 && G > 0 && rows / G >= 2048 &&
+           (int64_t)((M + 255) / 256) * (N / 256) * G >= 2 * (int64_t)c->n_cus;
+}
+
+// Runs of consecutive tasks that the products only summed over tasks are taken over.  16, unless the first layer's
+// product then runs in 256 x 256 tiles, one workgroup per compute unit: the count in [12, 16] whose tiles fill the
+// last round over the compute units best (the larger count on a tie).
+static int coarse_group_count(const gm_ctx* c, int Tw, int64_t rows) {
+    if (c->coarse_groups) return std::min(Tw, c->coarse_groups);
+    int n = std::min(Tw, 16);
+    if (n < 16 || c->L < 1) return n;
+    const int M = c->ld[0], N = c->ld[1];
+    if (!wgrad_wide_ok(c, M, N, rows, 16)) return n;
+    const int64_t per = (int64_t)((M + 255) / 256) * (N / 256);
+    double best = -1.0;
+    for (int k = 12; k <= 16; ++k) {
+        const int64_t tiles = per * k, rounds = (tiles + c->n_cus - 1) / c->n_cus;
+        const double fill = (double)tiles / (double)(rounds * c->n_cus);
+        if (fill >= best) { best = fill; n = k; }
+    }
+    return n;
+}
+
 // out_g[ld_{l-1}, ld_l] = c0*in_g + c1 * sum_p a_p[rows_g, ld_{l-1}]^T d_p[rows_g, ld_l]  (and its bf16 copies)
 static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, const Act* d0, const Act* a1, const Act* d1,
                      Theta& out, const float* in, int64_t in_stride, float c0, float c1, bool write_f32 = true) {
@@ -912,7 +955,7 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
                 a.Cb = out.b + c->offWb[l]; a.ldcb = N; a.gCb = out.sb;
             }
             a.epi = EPI_AXPBY; a.Cin = in ? in + c->offW[l] : nullptr; a.gCin = in_stride; a.ldcin = N; a.c0 = c0; a.c1 = c1;
-            launch_gemm_bf16_kmajor(c->stream, a);
+            launch_gemm_bf16_kmajor(c->stream, a, wgrad_wide_ok(c, M, N, g.rows, g.G) ? 256 : 128);
         }
     }
 }
@@ -1511,7 +1554,7 @@ static int setup_wave(gm_ctx* c, const Batch& B, const WavePlan& wp, int bm, int
     }
     // runs of consecutive tasks for the products that are only summed over the tasks
     std::vector<int32_t> co_s, co_q;
-    const int n_coarse = std::min<int>(d.Tw, COARSE_GROUPS);
+    const int n_coarse = coarse_group_count(c, d.Tw, std::min(d.Ps, d.Pq));
     for (int i = 0; i <= n_coarse; ++i) {
         const int t = (int)((int64_t)i * d.Tw / n_coarse);
         co_s.push_back(ro_s[t]);
@@ -1946,7 +1989,7 @@ static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set*
         colsum_f32(c, gq, 1, w.loss_q, 1, task_loss + wp.t0, 1, nullptr, 0, 0.f, 1.f);
         // The query gradient w.r.t. theta' per task starts the second-order chain; without a chain it is only summed
         // over the tasks, so it is taken over runs of tasks straight away.
-        const int n_coarse = std::min<int>(Tw, COARSE_GROUPS);
+        const int n_coarse = coarse_group_count(c, Tw, std::min(d.Ps, d.Pq));
         Grp gs_coarse = gs, gq_coarse = gq;
         gs_coarse.row_off = w.coarse_off_s; gs_coarse.G = n_coarse;
         gq_coarse.row_off = w.coarse_off_q; gq_coarse.G = n_coarse;

@@ -590,7 +590,7 @@ def test_row_paths_bf16_medium_shape(gm, path):
 
 
 def test_gemm_wide_tiles_give_the_same_result(gm):
-    """gm_configure("gemm_tile_n", 256): the forward / backward products in 256 x 256 tiles with eight waves.  Every
+    """gm_configure("gemm_tile_n", 256): the forward / backward products in the pipelined 256 x 256 tiles.  Every
     output element is accumulated in the same order as with 128-wide tiles, so the results are identical."""
     from synth import MEDIUM
     cfg = MEDIUM.with_(n_tasks=3, rows_per_field=20000, n_support=250, n_query=203)
@@ -606,6 +606,34 @@ def test_gemm_wide_tiles_give_the_same_result(gm):
     for l in range(3):
         assert torch.equal(a["dW"][l], b["dW"][l]) and torch.equal(a["db"][l], b["db"][l])
     _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_BF16, "bf16 medium3 ragged, 256-wide tiles", operand="bf16")
+    ctx.close()
+
+
+def test_weight_gradient_over_runs_of_tasks_in_wide_tiles(gm):
+    """The weight-gradient products that are only ever summed over tasks run over runs of tasks; with thousands of rows
+    per run and a first layer wide enough to fill the device they take the pipelined 256 x 256 tiles, both operands read
+    contraction-slowest (gm_configure("wgrad_wide"), on by default).  Every element is accumulated in the same order as
+    in 128 x 128 tiles: over the same runs of tasks the results are identical; then the whole step against the oracle
+    with the number of runs the library picks for the wide tiles."""
+    from synth import MEDIUM
+    cfg = MEDIUM.with_(n_tasks=40, n_fields=34, rows_per_field=3000, n_support=900, n_query=37, bag_max=3,
+                       layer_dims=(34 * 64 + 13, 1024, 64, 1))
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=6 << 30)
+    dev = ctx.device
+    ds, dq, dp = _to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev)
+    res = []
+    for wide in (0, 1):
+        ctx.configure("wgrad_wide", wide)
+        ctx.configure("coarse_groups", 16)
+        r = ctx.meta_step(ds, dq, dp, cfg.inner_lr, 1, 2)
+        res.append({"loss": r["loss"].clone(), "dW": [x.clone() for x in r["dW"]], "db": [x.clone() for x in r["db"]]})
+    a, b = res
+    assert torch.equal(a["loss"], b["loss"])
+    for l in range(3):
+        assert torch.equal(a["dW"][l], b["dW"][l]) and torch.equal(a["db"][l], b["db"][l]), l
+    ctx.configure("coarse_groups", 0)
+    _compare_step(cfg, ctx, sup, qry, params, 1, 2, TOL_BF16, "bf16, weight gradient in 256 x 256 tiles", operand="bf16")
     ctx.close()
 
 
