@@ -251,7 +251,7 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               "overlap_sort" is 1.
  *   "gemm_tile_n": column tile of the forward / backward grouped products when tasks get 256-row tiles:
  *               0 = chosen by shape (256, the software-pipelined 256 x 256 tiles, when the contraction is at least
- *               2048 long and the width a multiple of 256; else 128), 128, or 256.  Identical results.
+ *               1024 long and the width a multiple of 256; else 128), 128, or 256.  Identical results.
  *   "wgrad_wide": 1 (default) = the weight-gradient products that are only ever summed over tasks (they run over runs
  *               of consecutive tasks) take the pipelined 256 x 256 tiles when a run has thousands of rows, the layer
  *               is at least 1024 wide on the input side and a multiple of 256 on the output side, and the tiles fill

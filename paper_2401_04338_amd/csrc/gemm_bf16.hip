@@ -53,8 +53,12 @@ struct EpiFlags {
 
 // Epilogue shared by the GEMM kernels.  A lane holds column l32 of each 32x32 block and rows 8*(v/4) + 4*lhi + v%4,
 // which would give 2-byte scattered stores; instead every wave passes its accumulators through LDS one 32-row strip at
-// a time, applies the fused operation on 4 consecutive columns per lane and writes whole row segments.
-template <int BM, int BN, int MI, int NI, int EP>
+// a time, applies the fused operation on 4 consecutive columns per lane and writes whole row segments.  TRANSPOSED: the
+// accumulators were computed with the operand roles swapped (first MFMA operand = B fragment), so a lane holds ROW l32
+// and four consecutive columns per group of four registers; stored straight from the registers that is 16 bytes per
+// lane in 32 different rows per instruction, which the memory pipeline takes several times longer over than whole
+// row segments (measured on the 256 x 256 tiles: epilogue 32 -> 26 thousand cycles forward, 56 -> 33 backward).
+template <int BM, int BN, int MI, int NI, int EP, bool TRANSPOSED = false>
 __device__ __forceinline__ void gemm_epilogue(const GemmBArgs& a, f32x16 (&acc)[MI][NI], bf16_t* smem, int g, int64_t r0, int m0,
                                               int n0, int M, int N, int wm0, int wn0, int lane, int wave) {
     const EpiFlags<EP> fl(a);
@@ -92,10 +96,19 @@ __device__ __forceinline__ void gemm_epilogue(const GemmBArgs& a, f32x16 (&acc)[
             if (ok && has_cin) ci_all[it] = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
             if (ok && has_acc && !a.cacc_init) ci_all[it] = *reinterpret_cast<const float4*>(Cacc + (int64_t)m * a.ldcacc + n);
         }
+        if constexpr (TRANSPOSED) {   // (operand roles swapped in the MFMA: the lane holds row l32, four consecutive columns per q)
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
+            for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) E[(8 * (v >> 2) + 4 * lhi + (v & 3)) * ELD + j * 32 + l32] = acc[i][j][v];
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<float4*>(E + l32 * ELD + j * 32 + 8 * q + 4 * lhi) =
+                        make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) E[(8 * (v >> 2) + 4 * lhi + (v & 3)) * ELD + j * 32 + l32] = acc[i][j][v];
+        }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the strip is this wave's own: LDS order within the wave suffices
 #pragma unroll
         for (int it = 0; it < 32 / RPI; ++it) {
@@ -135,80 +148,6 @@ __device__ __forceinline__ void gemm_epilogue(const GemmBArgs& a, f32x16 (&acc)[
             }
         }
         asm volatile("" ::: "memory");   // (no block barrier: it would also wait for the strip's global stores to land)
-    }
-}
-
-// Epilogue for accumulators computed with the operand roles swapped (first MFMA operand = B fragment, second = A
-// fragment): the 32 x 32 block then sits transposed in the registers -- a lane holds ONE output row m (lane % 32) and,
-// per group of four accumulator registers, four consecutive output columns n = 8 q + 4 (lane / 32) + (0..3) -- so every
-// fused operation and every store works on 8- or 16-byte pieces of a row straight from the registers, without a
-// pass through LDS.  Same arithmetic per element as gemm_epilogue.
-template <int MI, int NI, int EP>
-__device__ __forceinline__ void gemm_epilogue_direct(const GemmBArgs& a, f32x16 (&acc)[MI][NI], int g, int64_t r0, int m0, int n0,
-                                                     int M, int N, int wm0, int wn0, int lane) {
-    const EpiFlags<EP> fl(a);
-    const int l32 = lane & 31, lhi = lane >> 5;
-    const bool has_bias = (fl.epi == EPI_BIAS_RELU || fl.epi == EPI_BIAS_MASK) && a.bias;
-    const bool has_mask = fl.epi == EPI_BIAS_MASK || fl.epi == EPI_MASK;
-    const bool has_cin = fl.cin, has_acc = fl.cacc;
-    const float* bias = has_bias ? a.bias + (int64_t)g * a.gBias : nullptr;
-    const bf16_t* mask = has_mask ? a.mask + r0 * a.ld_mask : nullptr;
-    const float* Cin = has_cin ? a.Cin + (int64_t)g * a.gCin : nullptr;
-    float* Cf = fl.cf ? a.Cf + (int64_t)g * a.gCf + r0 * a.rCf : nullptr;
-    float* Cacc = has_acc ? a.Cacc + r0 * a.rCacc : nullptr;
-    bf16_t* Cb = fl.cb ? a.Cb + (int64_t)g * a.gCb + r0 * a.rCb : nullptr;
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-        const int m = m0 + wm0 + i * 32 + l32;
-        const bool mok = m < M;
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            // everything this block reads from memory is requested before anything of it is stored
-            uint2 mk[4];
-            float4 ci[4], bn[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn0 + j * 32 + 8 * q + 4 * lhi;
-                const bool ok = mok && n < N;
-                mk[q] = make_uint2(0u, 0u);
-                ci[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                bn[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (has_bias && n < N) bn[q] = *reinterpret_cast<const float4*>(bias + n);
-                if (ok && has_mask) mk[q] = *reinterpret_cast<const uint2*>(mask + (int64_t)m * a.ld_mask + n);
-                if (ok && has_cin) ci[q] = *reinterpret_cast<const float4*>(Cin + (int64_t)m * a.ldcin + n);
-                if (ok && has_acc && !a.cacc_init) ci[q] = *reinterpret_cast<const float4*>(Cacc + (int64_t)m * a.ldcacc + n);
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn0 + j * 32 + 8 * q + 4 * lhi;
-                if (!mok || n >= N) continue;
-                float4 x = make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                if (fl.epi == EPI_BIAS_RELU) {
-                    x = make_float4(fmaxf(x.x + bn[q].x, 0.f), fmaxf(x.y + bn[q].y, 0.f), fmaxf(x.z + bn[q].z, 0.f), fmaxf(x.w + bn[q].w, 0.f));
-                } else if (has_mask) {
-                    if (fl.epi == EPI_BIAS_MASK) x = make_float4(x.x + bn[q].x, x.y + bn[q].y, x.z + bn[q].z, x.w + bn[q].w);
-                    // a bf16 is positive iff it is neither zero nor has its sign bit set
-                    const u32 h0 = mk[q].x & 0xffffu, h1 = mk[q].x >> 16, h2 = mk[q].y & 0xffffu, h3 = mk[q].y >> 16;
-                    x.x = (h0 != 0 && h0 < 0x8000u) ? x.x : 0.f;
-                    x.y = (h1 != 0 && h1 < 0x8000u) ? x.y : 0.f;
-                    x.z = (h2 != 0 && h2 < 0x8000u) ? x.z : 0.f;
-                    x.w = (h3 != 0 && h3 < 0x8000u) ? x.w : 0.f;
-                } else if (fl.epi == EPI_AXPBY) {
-                    x = make_float4(a.c1 * x.x, a.c1 * x.y, a.c1 * x.z, a.c1 * x.w);
-                    if (has_cin) x = make_float4(x.x + a.c0 * ci[q].x, x.y + a.c0 * ci[q].y, x.z + a.c0 * ci[q].z, x.w + a.c0 * ci[q].w);
-                }
-                if (fl.cf) *reinterpret_cast<float4*>(Cf + (int64_t)m * a.ldcf + n) = x;
-                if (has_acc)
-                    *reinterpret_cast<float4*>(Cacc + (int64_t)m * a.ldcacc + n) =
-                        make_float4(ci[q].x + a.cacc * x.x, ci[q].y + a.cacc * x.y, ci[q].z + a.cacc * x.z, ci[q].w + a.cacc * x.w);
-                if (fl.cb) {
-                    uint2 pk;
-                    pk.x = f2bf2(x.x, x.y);
-                    pk.y = f2bf2(x.z, x.w);
-                    *reinterpret_cast<uint2*>(Cb + (int64_t)m * a.ldcb + n) = pk;
-                }
-            }
-        }
     }
 }
 
@@ -602,7 +541,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_pipe_kernel(GemmBArgs a, int n_
 #ifdef GEMM_TIMING
     if (TIMED) ts2 = __builtin_readcyclecounter();
 #endif
-    gemm_epilogue_direct<MI, NI, EP>(a, acc, g, r0, m0, n0, M, N, wm0, wn0, lane);
+    gemm_epilogue<BM, BN, MI, NI, EP, true>(a, acc, smem, g, r0, m0, n0, M, N, wm0, wn0, lane, wave);
 #ifdef GEMM_TIMING
     if (TIMED && tid == 0 && tile < 16384) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -795,7 +795,7 @@ struct Grp {  // grouping of one set's rows by task inside the wave
 static int gemm_bn(const gm_ctx* c, int bm, int N, int K) {
     if (bm != 256 || N < 256 || N % 256 != 0) return 128;
     if (c->gemm_tile_n) return c->gemm_tile_n;
-    return K >= 2048 ? 256 : 128;
+    return K >= 1024 ? 256 : 128;
 }
 
 // out[rows, ld_l] = epi( sum_p in_p[rows, ld_{l-1}] * W_p,l + bias )
