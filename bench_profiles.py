@@ -38,10 +38,10 @@ FAMILIES = {
     "axpy_gx": r"axpy_kernel",
     "last_layer": r"last_fwd_kernel|last_bwd",
     # gemm_bf16_kernel<BM, BN, DB, KA, KB, EP>: which operand is read contraction-slowest tells the product's kind;
-    # gemm_bf16_pipe_kernel<KB, EP, ..>: the pipelined 256 x 256 kernel (forward products have KB = true)
-    "gemm_wgrad": r"gemm_bf16_kernel<\d+, \d+, false, true, true",
-    "gemm_fwd": r"gemm_bf16_kernel<\d+, \d+, false, false, true|gemm_bf16_pipe_kernel<true",
-    "gemm_bwd": r"gemm_bf16_kernel<\d+, \d+, false, false, false|gemm_bf16_pipe_kernel<false",
+    # gemm_bf16_pipe_kernel<KA, KB, EP, ..>: the pipelined 256 x 256 kernel, the same two flags
+    "gemm_wgrad": r"gemm_bf16_kernel<\d+, \d+, false, true, true|gemm_bf16_pipe_kernel<true, true",
+    "gemm_fwd": r"gemm_bf16_kernel<\d+, \d+, false, false, true|gemm_bf16_pipe_kernel<false, true",
+    "gemm_bwd": r"gemm_bf16_kernel<\d+, \d+, false, false, false|gemm_bf16_pipe_kernel<false, false",
     "gemm_f32 (all launches)": r"gemm_f32_kernel",
 }
 
@@ -162,8 +162,8 @@ def mfma(a):
     for _, k, n, ma, mb, pct, ops in sorted(rows, reverse=True):
         print(f"  {k[:60]:60s} {n:10d} {ma:14.4g} {mb:16.4g} {pct:11.1f} {ops:14.4g}")
     print("# gemm_bf16_kernel<BM,BN,false,KA,KB,EP>: KA,KB = false,true forward products; false,false backward (dA) products;")
-    print("# true,true per-task weight gradients.  gemm_bf16_pipe_kernel<KB,EP,..>: the pipelined 256 x 256 kernel (KB = true:")
-    print("# forward products, false: backward products).  EP encodes the fused epilogue of the launch.")
+    print("# true,true weight gradients.  gemm_bf16_pipe_kernel<KA,KB,EP,..>: the pipelined 256 x 256 kernel, the same two flags.")
+    print("# EP encodes the fused epilogue of the launch.")
 
 
 def main():
