@@ -252,10 +252,11 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *   "gemm_tile_n": column tile of the forward / backward grouped products when tasks get 256-row tiles:
  *               0 = chosen by shape (256, the software-pipelined 256 x 256 tiles, when the contraction is at least
  *               1024 long and the width a multiple of 256; else 128), 128, or 256.  Identical results.
- *   "wgrad_wide": 1 (default) = the weight-gradient products that are only ever summed over tasks (they run over runs
- *               of consecutive tasks) take the pipelined 256 x 256 tiles when a run has thousands of rows, the layer
- *               is at least 1024 wide on the input side and a multiple of 256 on the output side, and the tiles fill
- *               the device at least twice; 0 = always 128 x 128 tiles.  Identical results over the same runs.
+ *   "wgrad_wide": 1 (default) = weight-gradient products take the pipelined 256 x 256 tiles when a group (a task, or
+ *               a run of consecutive tasks for the products that are only ever summed over tasks) has at least 512
+ *               rows, the layer is at least 1024 wide on the input side and a multiple of 256 on the output side, and
+ *               the tiles fill the device at least twice; 0 = always 128 x 128 tiles.  Identical results over the
+ *               same groups.
  *   "coarse_groups": number of runs of consecutive tasks for those products: 0 (default) = 16, or, when the first
  *               layer's product takes the wide tiles, the count in [12, 16] whose tiles fill the device's last round
  *               best; 1..32 = that many.  Another grouping adds the same per-task terms in another order

@@ -894,9 +894,9 @@ static void dense_nt(gm_ctx* c, const Grp& g, int l, int np, const Act* d0, cons
 }
 
 // Weight gradient [M, N] of G groups over `rows` rows in all: the pipelined 256 x 256 tiles pay once the contraction of a
-// group is thousands of rows long and the tiles fill the device several times over.
+// group is at least 512 rows long (clearly so from thousands of rows on) and the tiles fill the device several times over.
 static bool wgrad_wide_ok(const gm_ctx* c, int M, int N, int64_t rows, int G) {
-    return c->wgrad_wide && c->mlp_dtype && M >= 1024 && N % 256 == 0 && G > 0 && rows / G >= 2048 &&
+    return c->wgrad_wide && c->mlp_dtype && M >= 1024 && N % 256 == 0 && G > 0 && rows / G >= 512 &&
            (int64_t)((M + 255) / 256) * (N / 256) * G >= 2 * (int64_t)c->n_cus;
 }
 
@@ -908,7 +908,7 @@ static int coarse_group_count(const gm_ctx* c, int Tw, int64_t rows) {
     int n = std::min(Tw, 16);
     if (n < 16 || c->L < 1) return n;
     const int M = c->ld[0], N = c->ld[1];
-    if (!wgrad_wide_ok(c, M, N, rows, 16)) return n;
+    if (!wgrad_wide_ok(c, M, N, rows, 16) || rows / 16 < 2048) return n;
     const int64_t per = (int64_t)((M + 255) / 256) * (N / 256);
     double best = -1.0;
     for (int k = 12; k <= 16; ++k) {
