@@ -838,6 +838,26 @@ def test_more_tasks_than_coarse_runs(gm, bf, K, order):
     ctx.close()
 
 
+@pytest.mark.parametrize("runs", [1, 7, 32])
+def test_other_numbers_of_task_runs(gm, runs):
+    """gm_configure("coarse_groups"): the products only summed over tasks taken over another number of runs of tasks --
+    the same per-task terms added in another order: against the oracle, and within fp32 rounding of the default."""
+    from paper_2401_04338_amd.binding import GMetaError
+    cfg = small_cfg(n_tasks=37, inner_lr=0.1).with_(lognormal_sizes=True, size_median=9, size_sigma=0.8, size_max=40)
+    sup, qry, params = _inputs(cfg, emb_std=0.3)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 29)
+    dev = ctx.device
+    a = ctx.meta_step(_to_dev(sup, dev), _to_dev(qry, dev), _params_dev(params, dev), cfg.inner_lr, 2, 2)
+    a = [x.clone() for x in a["dW"]]
+    ctx.configure("coarse_groups", runs)
+    out, _ = _compare_step(cfg, ctx, sup, qry, params, 2, 2, TOL_FP32, f"37 tasks in {runs} runs")
+    for l in range(len(a)):
+        assert max(rel_err(out["dW"][l].cpu().numpy(), a[l].cpu().numpy())) <= 1e-5
+    with pytest.raises(GMetaError):
+        ctx.configure("coarse_groups", 33)
+    ctx.close()
+
+
 @pytest.mark.parametrize("D", [8, 16, 128, 256])
 def test_embedding_widths(gm, D):
     """Every embedding width has its own lane-group shape in the gather, the segmented reduction and the scatter
