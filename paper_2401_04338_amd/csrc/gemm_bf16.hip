@@ -595,8 +595,7 @@ static void launch_variant(hipStream_t st, const GemmBArgs& a) {
 
 // Tile shapes of one operand form.  bm: row tile the caller built its (tile_group, tile_m0) lists for (64, 128 or
 // 256); bn: 128, or 256 (with bm = 256: the pipelined 256 x 256 kernel).  Measured on the benchmark shapes: one LDS
-// stage with register prefetch beats two stages for the smaller tiles (occupancy); the weight-gradient form (fixed M,
-// K = rows of a task) is bound by the theta' it writes and keeps 128 x 128.
+// stage with register prefetch beats two stages for the smaller tiles (occupancy).
 template <bool KB, int EP>
 static void launch_rows_form(hipStream_t st, const GemmBArgs& a, int bm, int bn) {
     if (bm == 256 && bn == 256) launch_pipe<false, KB, EP>(st, a);
