@@ -285,24 +285,26 @@ def test_determinism(gm):
 
 
 # ---------------------------------------------------------------- edge cases and error paths
+def _drop_task_samples(cfg, sd, t):
+    """The set without the samples of task t (the task stays, empty)."""
+    from synth.generate import SetData
+    F = cfg.n_fields
+    lo, hi = int(sd.task_offsets[t]), int(sd.task_offsets[t + 1])
+    p0, p1 = int(sd.bag_offsets[lo * F]), int(sd.bag_offsets[hi * F])
+    offs = torch.cat([sd.bag_offsets[: lo * F], sd.bag_offsets[hi * F:] - (p1 - p0)])
+    toff = sd.task_offsets.copy()
+    toff[t + 1:] -= hi - lo
+    keep = torch.ones(sd.n_samples, dtype=torch.bool)
+    keep[lo:hi] = False
+    return SetData(toff, offs, torch.cat([sd.indices[:p0], sd.indices[p1:]]), sd.dense[keep], sd.labels[keep])
+
+
 def test_ragged_and_empty_tasks(gm):
     """Variable task sizes including a task with no support samples and empty bags."""
-    from synth.generate import SetData
     cfg = small_cfg(n_tasks=4, inner_lr=0.2)
     sup, qry, params = _inputs(cfg, emb_std=0.3)
 
-    def drop_task_samples(sd, t):   # remove all samples of task t
-        F = cfg.n_fields
-        lo, hi = int(sd.task_offsets[t]), int(sd.task_offsets[t + 1])
-        p0, p1 = int(sd.bag_offsets[lo * F]), int(sd.bag_offsets[hi * F])
-        offs = torch.cat([sd.bag_offsets[: lo * F], sd.bag_offsets[hi * F:] - (p1 - p0)])
-        toff = sd.task_offsets.copy()
-        toff[t + 1:] -= hi - lo
-        keep = torch.ones(sd.n_samples, dtype=torch.bool)
-        keep[lo:hi] = False
-        return SetData(toff, offs, torch.cat([sd.indices[:p0], sd.indices[p1:]]), sd.dense[keep], sd.labels[keep])
-
-    sup2 = drop_task_samples(sup, 1)
+    sup2 = _drop_task_samples(cfg, sup, 1)
     ctx = gm.from_config(cfg, workspace_bytes=1 << 28)
     _compare_step(cfg, ctx, sup2, qry, params, 2, 2, TOL_FP32, "empty-support-task")
     ctx.close()
@@ -634,6 +636,10 @@ def test_weight_gradient_over_runs_of_tasks_in_wide_tiles(gm):
         assert torch.equal(a["dW"][l], b["dW"][l]) and torch.equal(a["db"][l], b["db"][l]), l
     ctx.configure("coarse_groups", 0)
     _compare_step(cfg, ctx, sup, qry, params, 1, 2, TOL_BF16, "bf16, weight gradient in 256 x 256 tiles", operand="bf16")
+    # a task without support samples (a group with an empty contraction: its tiles hold the old weights alone) and one
+    # without query samples
+    _compare_step(cfg, ctx, _drop_task_samples(cfg, sup, 3), _drop_task_samples(cfg, qry, 17), params, 1, 2, TOL_BF16,
+                  "bf16, wide weight-gradient tiles, empty tasks", operand="bf16")
     ctx.close()
 
 
