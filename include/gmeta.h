@@ -257,6 +257,12 @@ int gm_index_prep(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_
  *               rows, the layer is at least 1024 wide on the input side and a multiple of 256 on the output side, and
  *               the tiles fill the device at least twice; 0 = always 128 x 128 tiles.  Identical results over the
  *               same groups.
+ *   "theta_from_meta": bf16 operands, second order, 2 to 4 inner steps: 1 (default) = the weight matrices of inner step k
+ *               are written as theta - alpha * (the gradients of steps 0..k), one product per step accumulated on the
+ *               matrix cores, straight from the meta parameters (every step's activations and deltas are kept for the
+ *               second-order chain anyway): no per-task fp32 copy of a weight matrix is written or read; 0 = every
+ *               step updates a per-task fp32 master (theta_{k+1} = theta_k - alpha * gradient_k).  The same values up
+ *               to fp32 rounding before the bf16 operand copy is taken.
  *   "coarse_groups": number of runs of consecutive tasks for those products: 0 (default) = 16, or, when the first
  *               layer's product takes the wide tiles, the count in [12, 16] whose tiles fill the device's last round
  *               best; 1..32 = that many.  Another grouping adds the same per-task terms in another order

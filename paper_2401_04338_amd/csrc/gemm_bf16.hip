@@ -625,6 +625,7 @@ static void launch_kmajor_tile(hipStream_t st, const GemmBArgs& a, int tile) {
     else launch_variant<128, 128, true, true, EP>(st, a);
 }
 void launch_gemm_bf16_kmajor(hipStream_t st, const GemmBArgs& a, int tile) {
+    if (a.n_pairs > 2) tile = 128;   // (the pipelined kernel keeps two operand descriptors)
     switch (ep_of(a)) {
         case EPI_AXPBY | EP_CF: launch_kmajor_tile<EPI_AXPBY | EP_CF>(st, a, tile); break;
         case EPI_AXPBY | EP_CF | EP_CB: launch_kmajor_tile<EPI_AXPBY | EP_CF | EP_CB>(st, a, tile); break;

@@ -263,11 +263,12 @@ struct GemmArgs {
 void launch_gemm_f32(hipStream_t st, const GemmArgs& a);
 
 // bf16 operands, both stored contraction-contiguous: C[M,N] = sum_p A_p[M,K] * Bt_p[N,K]^T
+#define GEMM_MAX_PAIRS 4   // products accumulated into one output (the pipelined kernel takes at most two)
 struct GemmBArgs {
-    const bf16_t* A[2];
-    const bf16_t* B[2];
-    int64_t lda[2], gA[2], rA[2];   // element (m,k) of group g: A + g*gA + r0(g)*rA + m*lda + k
-    int64_t ldb[2], gB[2], rB[2];   // element (n,k) of group g: B + g*gB + r0(g)*rB + n*ldb + k
+    const bf16_t* A[GEMM_MAX_PAIRS];
+    const bf16_t* B[GEMM_MAX_PAIRS];
+    int64_t lda[GEMM_MAX_PAIRS], gA[GEMM_MAX_PAIRS], rA[GEMM_MAX_PAIRS];   // element (m,k) of group g: A + g*gA + r0(g)*rA + m*lda + k
+    int64_t ldb[GEMM_MAX_PAIRS], gB[GEMM_MAX_PAIRS], rB[GEMM_MAX_PAIRS];   // element (n,k) of group g: B + g*gB + r0(g)*rB + n*ldb + k
     int n_pairs;
     int M, N, K;                    // -1: rows of the group
     const int32_t* row_offsets;     // [G+1]

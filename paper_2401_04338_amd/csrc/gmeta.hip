@@ -82,6 +82,7 @@ struct gm_ctx {
     int adapt_rows = 1;   // 0: the inner loop adapts the dense parameters only (embedding rows are read, not updated)
     int gemm_tile_n = 0;
     int wgrad_wide = 1;      // weight gradients over runs of tasks in 256 x 256 tiles where the shape allows
+    int theta_from_meta = 1; // bf16, second order, several inner steps: a step's weights from theta and all steps' gradients
     int coarse_groups = 0;   // runs of tasks for the products only summed over tasks (0: chosen by shape)
     int n_cus = 256;
     int row_path = 0;   // task-local row arithmetic: 0 = choose per wave, 1 = sparse two-hop kernel, 2 = pair-count matrices
@@ -586,6 +587,11 @@ extern "C" int gm_configure(gm_ctx* c, const char* key, int64_t value) {
         c->wgrad_wide = (int)value;
         return GM_OK;
     }
+    if (!strcmp(key, "theta_from_meta")) {
+        if (value != 0 && value != 1) return fail(c, GM_ERR_ARG, "theta_from_meta must be 0 or 1");
+        c->theta_from_meta = (int)value;
+        return GM_OK;
+    }
     if (!strcmp(key, "coarse_groups")) {
         if (value < 0 || value > COARSE_GROUPS) return fail(c, GM_ERR_ARG, "coarse_groups must be in [0, 32]");
         c->coarse_groups = (int)value;
@@ -920,11 +926,9 @@ static int coarse_group_count(const gm_ctx* c, int Tw, int64_t rows) {
 }
 
 // out_g[ld_{l-1}, ld_l] = c0*in_g + c1 * sum_p a_p[rows_g, ld_{l-1}]^T d_p[rows_g, ld_l]  (and its bf16 copies)
-static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, const Act* d0, const Act* a1, const Act* d1,
-                     Theta& out, const float* in, int64_t in_stride, float c0, float c1, bool write_f32 = true) {
+static void dense_tn_n(gm_ctx* c, const Grp& g, int l, int np, const Act* const* as, const Act* const* ds, Theta& out,
+                       const float* in, int64_t in_stride, float c0, float c1, bool write_f32 = true) {
     const int M = c->ld[l - 1], N = c->ld[l];
-    const Act* as[2] = {a0, a1};
-    const Act* ds[2] = {d0, d1};
     {
         const double esz = c->mlp_dtype ? 2.0 : 4.0;
         const double out_b = c->mlp_dtype ? ((write_f32 || !out.b) ? 4.0 : 0.0) + (out.b ? 2.0 : 0.0) : 4.0;
@@ -958,6 +962,13 @@ static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, cons
             launch_gemm_bf16_kmajor(c->stream, a, wgrad_wide_ok(c, M, N, g.rows, g.G) ? 256 : 128);
         }
     }
+}
+
+static void dense_tn(gm_ctx* c, const Grp& g, int l, int np, const Act* a0, const Act* d0, const Act* a1, const Act* d1,
+                     Theta& out, const float* in, int64_t in_stride, float c0, float c1, bool write_f32 = true) {
+    const Act* as[2] = {a0, a1};
+    const Act* ds[2] = {d0, d1};
+    dense_tn_n(c, g, l, np, as, ds, out, in, in_stride, c0, c1, write_f32);
 }
 
 static void colsum(gm_ctx* c, const Grp& g, int N, const Act* X1, const float* w1, const Act* X2, const float* w2,
@@ -1031,15 +1042,29 @@ static void forward_backward(gm_ctx* c, const Grp& g, const float* labels, const
 // out = c0*in + c1 * (gradient of the pass w.r.t. theta), per task; out.b (if any) gets the bf16 operand copies.
 // coarse / coarse_out: the hidden layers' weight matrices are summed over runs of tasks instead (c1 times the gradient,
 // nothing added), for a caller that only wants their sum over the tasks; biases and the last layer stay per task.
+// hist / in0 (bf16 operands, an inner step of a second-order call): the passes of all inner steps so far, this one
+// last, and the meta parameters.  The step's weight matrices are then written as theta - alpha * (sum of the steps'
+// gradients), one product per step accumulated in the matrix cores, from the shared fp32 theta: no per-task fp32
+// master of a weight matrix is written or read (it was most of what a step of small tasks moved); biases and the
+// last layer keep their per-task fp32 chain (in, in_stride).
 static void theta_grad(gm_ctx* c, const Grp& g, const Pass& p, Theta& out, const float* in, int64_t in_stride, float c0,
                        float c1, float* wL_copy, bool write_f32 = true, const Grp* coarse = nullptr,
-                       Theta* coarse_out = nullptr) {
+                       Theta* coarse_out = nullptr, const std::vector<Pass>* hist = nullptr, const float* in0 = nullptr) {
     const int L = c->L;
     const int64_t nt = out.sf;
     for (int l = 1; l < L; ++l) {
         const Act* prev = l == 1 ? p.X : &(*p.A)[l - 1];
         if (coarse) dense_tn(c, *coarse, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, *coarse_out, nullptr, 0, 0.f, c1);
-        else dense_tn(c, g, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, out, in, in_stride, c0, c1, write_f32);
+        else if (hist) {
+            const Act* as[GEMM_MAX_PAIRS];
+            const Act* ds[GEMM_MAX_PAIRS];
+            const int np = (int)hist->size();
+            for (int j = 0; j < np; ++j) {
+                as[j] = l == 1 ? (*hist)[j].X : &(*(*hist)[j].A)[l - 1];
+                ds[j] = &(*(*hist)[j].Dl)[l];
+            }
+            dense_tn_n(c, g, l, np, as, ds, out, in0, 0, c0, c1, false);
+        } else dense_tn(c, g, l, 1, prev, &(*p.Dl)[l], nullptr, nullptr, out, in, in_stride, c0, c1, write_f32);
         colsum(c, g, c->ld[l], &(*p.Dl)[l], nullptr, nullptr, nullptr, out.f + c->offb[l], nt, in ? in + c->offb[l] : nullptr,
                in_stride, c0, c1);
     }
@@ -1926,6 +1951,11 @@ static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set*
         const float* xs_cur = w.Xs0;    // fp32 support input of the current step
         Act Xq = w.Xq;                  // query input as the GEMMs read it
         if (!bf) Xq.f = w.Xq0;          // fp32: the prefetched buffer, updated in place by the overlap update
+        // bf16, second order, 2..GEMM_MAX_PAIRS inner steps: every step's weights straight from the meta parameters
+        // and the gradients of all steps so far (their activations and deltas are kept for the chain anyway)
+        const bool from_theta0 = bf && second && K >= 2 && K <= GEMM_MAX_PAIRS && c->theta_from_meta;
+        const float* thf0 = thf;
+        std::vector<Pass> passes;
         for (int k = 0; k < K; ++k) {
             StepState& s = w.steps[second ? k : 0];
             if (k == 0) s.X = X0s;
@@ -1938,7 +1968,10 @@ static int meta_step_impl(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set*
             Theta& next = w.thetas[second ? k : 0];
             float* wl_copy = (bf && second && k + 1 < K) ? w.steps[k + 1].wL_copy : nullptr;
             // bf16: after the last inner step only the operand copies of W' are read again, not its fp32 master
-            theta_grad(c, gs, p, next, thf, thf_stride, 1.f, -alpha, wl_copy, !(bf && k + 1 == K));
+            if (from_theta0) {
+                passes.push_back(p);
+                theta_grad(c, gs, p, next, thf, thf_stride, 1.f, -alpha, wl_copy, false, nullptr, nullptr, &passes, thf0);
+            } else theta_grad(c, gs, p, next, thf, thf_stride, 1.f, -alpha, wl_copy, !(bf && k + 1 == K));
             th = next;
             thf = next.f;
             thf_stride = nt;

@@ -844,6 +844,25 @@ def test_more_tasks_than_coarse_runs(gm, bf, K, order):
     ctx.close()
 
 
+@pytest.mark.parametrize("K", [2, 3, 4])
+def test_inner_step_weights_from_the_meta_parameters(gm, K):
+    """bf16, second order, several inner steps: by default a step's weight matrices are theta - alpha * (all steps'
+    gradients so far) in one accumulation; gm_configure("theta_from_meta", 0) keeps a per-task fp32 master updated step by
+    step.  Both against the oracle; the two agree far inside the bf16 tolerance (they differ by fp32 rounding before the
+    operand copy is rounded)."""
+    cfg = SMALL.with_(n_tasks=5, n_support=70, n_query=40, n_fields=4, emb_dim=32, rows_per_field=400, bag_max=5,
+                      layer_dims=(4 * 32 + 13, 96, 48, 1), mlp_dtype=1, inner_lr=0.05)
+    sup, qry, params = _inputs(cfg)
+    ctx = gm.from_config(cfg, workspace_bytes=1 << 30)
+    out_a, _ = _compare_step(cfg, ctx, sup, qry, params, K, 2, TOL_BF16, f"K={K}, weights from the meta parameters", operand="bf16")
+    a = [x.clone() for x in out_a["dW"]]
+    ctx.configure("theta_from_meta", 0)
+    out_b, _ = _compare_step(cfg, ctx, sup, qry, params, K, 2, TOL_BF16, f"K={K}, per-task fp32 master", operand="bf16")
+    for l in range(len(a)):
+        assert max(rel_err(out_b["dW"][l].cpu().numpy(), a[l].cpu().numpy())) <= 5e-3
+    ctx.close()
+
+
 @pytest.mark.parametrize("runs", [1, 7, 32])
 def test_other_numbers_of_task_runs(gm, runs):
     """gm_configure("coarse_groups"): the products only summed over tasks taken over another number of runs of tasks --
