@@ -160,11 +160,8 @@ def main():
     cap_rows = 0 if table is not None else min(nnz, cfg.total_rows)
     out_bytes = cap_rows * (cfg.emb_dim * 4 + 8)
     ws = int(need * 1.02)
-    if args.train is not None:   # the meta-gradient lists and a second set of index structures then live in the workspace
+    if args.train is not None and table is None:   # the meta-gradient lists and a second set of index structures then live in the workspace
         ws += 2 * out_bytes + int(need * 0.35) + (64 << 20)
-        if table is not None:
-            print("--train uses the row-list output (fewer than 2^31 lookups per set)", file=sys.stderr)
-            sys.exit(2)
         cap_rows, out_bytes = 0, 0
     if args.workspace_gib is not None:
         ws = int(args.workspace_gib * 2 ** 30)
@@ -181,12 +178,19 @@ def main():
 
     def step(i):
         s, q = batches[i % len(batches)]
+        if args.train is not None and table is not None:   # (the table-shaped accumulator is cleared by the update)
+            ctx.meta_train_step_table(s, q, params, cfg.inner_lr, K, order, args.train, table, loss=out["loss"])
+            return out
         if args.train is not None:
             ctx.meta_train_step(s, q, params, cfg.inner_lr, K, order, args.train, loss=out["loss"])
             return out
         return ctx.meta_step(s, q, params, cfg.inner_lr, K, order, out=out, emb_grad_table=table)
 
     def train_loop(n):   # n iterations of Alg. 1 in one call (gm_meta_train), cycling through the batches
+        if table is not None:   # batches beyond the row-list form: one call per iteration
+            for i in range(n):
+                step(i)
+            return
         losses = ctx.meta_train([batches[i % len(batches)] for i in range(n)], params, cfg.inner_lr, K, order, args.train)
         out["loss"][:1] = losses[-1:]
 
@@ -318,7 +322,8 @@ def main():
                    "n_fields": cfg.n_fields, "rows_per_field": cfg.rows_per_field, "emb_dim": cfg.emb_dim,
                    "mlp": list(cfg.layer_dims), "inner_steps": K, "order": order, "inner_lr": cfg.inner_lr,
                    "outer_update": None if args.train is None else {"fused": True, "outer_lr": args.train,
-                                                                     "loop": "gm_meta_train: one call per timed region"},
+                                                                     "loop": "gm_meta_train: one call per timed region" if table is None
+                                                                     else "gm_meta_train_step_table: one call per iteration"},
                    "sparse_out": sparse_out, "configure": args.configure, "workspace_gib": ctx_ws / 2 ** 30,
                    "tasks_per_wave": tasks_per_wave, "batches_cycled": len(batches), "loss": loss,
                    "input_generation_s": gen_s, "inputs": "loaded" if args.load_inputs else "generated"},

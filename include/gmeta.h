@@ -152,6 +152,16 @@ int gm_meta_train_step(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, cons
                        const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
                        float outer_lr, float* loss, float* task_loss);
 
+/* gm_meta_train_step for batches of any size (the row-list form holds fewer than 2^31 lookups per set): the sparse
+ * meta-gradient is accumulated, wave of tasks by wave of tasks, in emb_grad_table -- DEVICE [all table rows, D]
+ * fp32, 16-byte aligned, ALL ZERO on entry -- and then applied to the tables in one streaming pass
+ * (emb -= outer_lr * table) that also clears the buffer: it is all zero again on return, ready for the next
+ * iteration.  Everything else as gm_meta_train_step (Alg. 1: the step, then both global back-propagation steps
+ * applied with step size beta); the workspace only has to hold the dense meta-gradient beside the step. */
+int gm_meta_train_step_table(gm_ctx* ctx, int32_t n_tasks, const gm_set* support, const gm_set* query,
+                             const gm_params* params, float inner_lr, int32_t inner_steps, int32_t order,
+                             float outer_lr, float* loss, float* task_loss, float* emb_grad_table);
+
 /* n_iters iterations of Alg. 1 on one shard in one call: iteration i is gm_meta_train_step on (support[i], query[i]),
  * and the parameters after the call are bit for bit those of n_iters such calls in a row.  What the call adds is the
  * overlap of Alg. 1's outer loop as a sustained training loop: everything of batch i+1 that depends on its indices

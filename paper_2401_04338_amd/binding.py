@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libgmeta.so")
 GM_OK, GM_ERR_ARG, GM_ERR_INDEX, GM_ERR_CAPACITY, GM_ERR_WORKSPACE, GM_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["gm_create", "gm_destroy", "gm_last_error", "gm_workspace_bytes", "gm_meta_step", "gm_meta_step_static",
-           "gm_meta_train_step", "gm_meta_train", "gm_group_batch", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report", "gm_ceilings"]
+           "gm_meta_train_step", "gm_meta_train_step_table", "gm_meta_train", "gm_group_batch", "gm_scatter_add", "gm_gather_pool", "gm_index_prep", "gm_configure", "gm_profile", "gm_profile_report", "gm_ceilings"]
 
 
 class gm_model_desc(C.Structure):
@@ -83,6 +83,9 @@ def load_library() -> C.CDLL:
     lib.gm_meta_train_step.restype = C.c_int
     lib.gm_meta_train_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set), C.POINTER(gm_params),
                                        C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
+    lib.gm_meta_train_step_table.restype = C.c_int
+    lib.gm_meta_train_step_table.argtypes = [C.c_void_p, C.c_int32, C.POINTER(gm_set), C.POINTER(gm_set), C.POINTER(gm_params),
+                                             C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gm_meta_train.restype = C.c_int
     lib.gm_meta_train.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(gm_set), C.POINTER(gm_set),
                                   C.POINTER(gm_params), C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_void_p,
@@ -270,6 +273,27 @@ class GMeta:
         ps = gm_params(_ptr(params.emb), Wp, bp)
         rc = self.lib.gm_meta_train_step(self._ctx, n_tasks, C.byref(ss), C.byref(qs), C.byref(ps), float(inner_lr),
                                          int(inner_steps), int(order), float(outer_lr), _ptr(loss), _ptr(task_loss))
+        self._check(rc)
+        return loss
+
+    def meta_train_step_table(self, support, query, params, inner_lr: float, inner_steps: int, order: int, outer_lr: float,
+                              emb_grad_table: torch.Tensor, loss: Optional[torch.Tensor] = None,
+                              task_loss: Optional[torch.Tensor] = None):
+        """gm_meta_train_step_table: the step with the table-shaped sparse meta-gradient (all zero on entry and again on
+        return) and the outer update; params.emb / W[] / b[] are updated in place.  Returns the device scalar of the loss."""
+        n_tasks = len(support.task_offsets) - 1
+        L = len(self.layer_dims) - 1
+        if loss is None:
+            loss = torch.empty(1, dtype=torch.float32, device=self.device)
+        ss, qs = _set_struct(support, self.device), _set_struct(query, self.device)
+        self._check_params(params)
+        assert emb_grad_table.dtype == torch.float32 and emb_grad_table.is_contiguous() and emb_grad_table.shape == params.emb.shape
+        Wp = (C.c_void_p * L)(*[w.data_ptr() for w in params.W])
+        bp = (C.c_void_p * L)(*[x.data_ptr() for x in params.b])
+        ps = gm_params(_ptr(params.emb), Wp, bp)
+        rc = self.lib.gm_meta_train_step_table(self._ctx, n_tasks, C.byref(ss), C.byref(qs), C.byref(ps), float(inner_lr),
+                                               int(inner_steps), int(order), float(outer_lr), _ptr(loss), _ptr(task_loss),
+                                               _ptr(emb_grad_table))
         self._check(rc)
         return loss
 

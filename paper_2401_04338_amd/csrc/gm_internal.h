@@ -326,6 +326,7 @@ void launch_fill_sample_task(hipStream_t st, const int32_t* row_offsets, int G, 
 void launch_pack_weights(hipStream_t st, const float* W, int din, int dout, int ld_in, int ld_out, float* dst);
 void launch_unpack_weights(hipStream_t st, const float* src, int din, int dout, int ld_out, float* W);
 void launch_axpy(hipStream_t st, int64_t n, float a, const float* x, float* y);  // y += a*x
+void launch_axpy_clear(hipStream_t st, int64_t n, float a, float* x, float* y);  // y += a*x, x = 0 (n % 4 == 0, 16-byte aligned)
 void launch_sum_to_scalar(hipStream_t st, const float* x, int n, float* out, int accumulate);
 void launch_fill_u32(hipStream_t st, u32* p, int64_t n, u32 v);
 void launch_fill_f32(hipStream_t st, float* p, int64_t n, float v);

@@ -2226,6 +2226,61 @@ extern "C" int gm_meta_train_step(gm_ctx* c, int32_t T, const gm_set* sup, const
     return GM_OK;
 }
 
+// The same iteration with the sparse meta-gradient accumulated in a table-shaped buffer of the caller's (any number of
+// lookups, tasks in waves) and applied to the tables in one streaming pass that clears the buffer again.
+extern "C" int gm_meta_train_step_table(gm_ctx* c, int32_t T, const gm_set* sup, const gm_set* qry, const gm_params* params,
+                                        float alpha, int32_t K, int32_t order, float beta, float* loss, float* task_loss,
+                                        float* emb_grad_table) {
+    if (!c) return GM_ERR_ARG;
+    if (!sup || !qry || sup->nnz < 0 || qry->nnz < 0) return fail(c, GM_ERR_ARG, "null set / negative size");
+    if (!params || !params->W || !params->b) return fail(c, GM_ERR_ARG, "null params");
+    if (c->F > 0 && (!emb_grad_table || !params->emb)) return fail(c, GM_ERR_ARG, "null emb_grad_table / emb");
+    if ((reinterpret_cast<uintptr_t>(emb_grad_table) | reinterpret_cast<uintptr_t>(params->emb)) & 15)
+        return fail(c, GM_ERR_ARG, "emb_grad_table and emb must be 16-byte aligned");
+    HIPCHK(c, hipSetDevice(c->device));
+    const int L = c->L, D = c->D;
+    int64_t n_dense = 0;
+    for (int l = 0; l < L; ++l) n_dense += (int64_t)(c->dims[l] + 1) * c->dims[l + 1];
+    const size_t dense_bytes = ((size_t)n_dense * 4 + 255) & ~(size_t)255;
+    const size_t need = dense_bytes + 512;   // the dense meta-gradient and the row counter, at the top of the workspace
+    if (need + c->persistent + (1 << 20) > c->ws_bytes)
+        return fail(c, GM_ERR_WORKSPACE, "workspace of %zu bytes cannot hold the dense meta-gradient (%zu bytes) beside the step", c->ws_bytes, need);
+    const size_t full = c->ws_bytes;
+    char* top = c->ws + (full - need) / 256 * 256;
+    std::vector<float*> dW(L), db(L);
+    {
+        float* p = reinterpret_cast<float*>(top);
+        for (int l = 0; l < L; ++l) {
+            dW[l] = p; p += (int64_t)c->dims[l] * c->dims[l + 1];
+            db[l] = p; p += c->dims[l + 1];
+        }
+    }
+    gm_grads out;
+    memset(&out, 0, sizeof out);
+    out.dW = dW.data(); out.db = db.data();
+    out.emb_grad_table = emb_grad_table;
+    out.n_emb_rows = reinterpret_cast<int64_t*>(top + dense_bytes);   // (0 with the table-shaped output)
+    out.task_loss = task_loss;
+    c->ws_bytes = static_cast<size_t>(top - c->ws);
+    const int rc = gm_meta_step(c, T, sup, qry, params, alpha, K, order, loss, &out);
+    c->ws_bytes = full;
+    if (rc != GM_OK) return rc;
+    hipStream_t st = c->stream;
+    for (int l = 0; l < L; ++l) {
+        launch_axpy(st, (int64_t)c->dims[l] * c->dims[l + 1], -beta, dW[l], const_cast<float*>(params->W[l]));
+        launch_axpy(st, c->dims[l + 1], -beta, db[l], const_cast<float*>(params->b[l]));
+    }
+    if (c->F > 0) {
+        const int64_t n = c->field_base[c->F] * (int64_t)D;   // (D is a multiple of 4)
+        Prof p(c, "table_update", 16.0 * n, 0);
+        launch_axpy_clear(st, n, -beta, emb_grad_table, const_cast<float*>(params->emb));
+    }
+    HIPCHK(c, hipStreamSynchronize(st));
+    HIPCHK(c, hipGetLastError());
+    prof_drain(c);
+    return GM_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // several iterations of Alg. 1 in one call, the index side of batch i+1 prepared while batch i computes
 // ------------------------------------------------------------------------------------------------

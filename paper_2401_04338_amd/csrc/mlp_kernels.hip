@@ -2,6 +2,8 @@
 // forward with the task's adapted theta', and the tangent passes of the second-order term.  Every
 // product is a GROUPED GEMM: one group per task, each group with its own rows and (when theta has been
 // adapted) its own weights.
+#include <algorithm>
+
 #include "gm_internal.h"
 
 // ------------------------------------------------------------------------------------------------
@@ -488,6 +490,25 @@ void launch_unpack_weights(hipStream_t st, const float* src, int din, int dout, 
 __global__ void axpy_kernel(int64_t n, float a, const float* __restrict__ x, float* y) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
         y[i] += a * x[i];
+}
+// y += a * x and x = 0 in one pass (the table-shaped sparse meta-gradient applied to the tables and cleared for the next
+// iteration); 16 bytes per lane
+__global__ void axpy_clear_kernel(int64_t n4, float a, float4* x, float4* y) {
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (int64_t)gridDim.x * blockDim.x) {
+        const float4 g = x[i];
+        if (g.x == 0.f && g.y == 0.f && g.z == 0.f && g.w == 0.f) continue;   // (rows nobody looked up: nothing to read or write)
+        float4 v = y[i];
+        v.x += a * g.x; v.y += a * g.y; v.z += a * g.z; v.w += a * g.w;
+        y[i] = v;
+        x[i] = zero;
+    }
+}
+void launch_axpy_clear(hipStream_t st, int64_t n, float a, float* x, float* y) {   // n a multiple of 4, both 16-byte aligned
+    if (n <= 0) return;
+    const int64_t n4 = n / 4;
+    const unsigned grid = (unsigned)std::min<int64_t>((n4 + 255) / 256, 256 * 64);
+    hipLaunchKernelGGL(axpy_clear_kernel, dim3(grid), dim3(256), 0, st, n4, a, reinterpret_cast<float4*>(x), reinterpret_cast<float4*>(y));
 }
 void launch_axpy(hipStream_t st, int64_t n, float a, const float* x, float* y) {
     if (n <= 0) return;

@@ -427,6 +427,44 @@ def test_train_steps_follow_the_oracle(gm, bf):
     ctx.close()
 
 
+@pytest.mark.parametrize("waves", [1, 3], ids=["one_wave", "several_waves"])
+def test_train_steps_with_a_table_shaped_gradient(gm, waves):
+    """gm_meta_train_step_table: three iterations of Alg. 1 with the sparse meta-gradient accumulated in a table-shaped
+    buffer (all zero before and after every call) and applied in one pass: losses and parameters after every iteration
+    against the oracle's meta_train_step, tasks in one wave and in several."""
+    from synth.generate import Params
+    cfg = SMALL.with_(n_tasks=6, n_support=40, n_query=24, n_fields=5, emb_dim=32, rows_per_field=3000, bag_max=6,
+                      layer_dims=(5 * 32 + 13, 64, 32, 1), inner_lr=0.05)
+    beta, K, order = 0.02, 2, 2
+    params = make_params(cfg, "cpu", emb_std=0.1)
+    sup0, qry0 = make_batch(cfg, 0, "cpu")
+    probe = gm.from_config(cfg, workspace_bytes=1 << 30)
+    need = probe.workspace_bytes(cfg.n_tasks, sup0.n_samples, qry0.n_samples, sup0.nnz, qry0.nnz, K, order)
+    probe.close()
+    ctx = gm.from_config(cfg, workspace_bytes=(1 << 30) if waves == 1 else int(need * 0.45))
+    dev = ctx.device
+    dp = Params(params.emb.to(dev).clone(), [w.to(dev).clone() for w in params.W], [b.to(dev).clone() for b in params.b])
+    table = torch.zeros_like(dp.emb)
+    ref_p = params.numpy()
+    ref_p = dict(emb=ref_p["emb"].astype(np.float64), W=[w.astype(np.float64) for w in ref_p["W"]],
+                 b=[b.astype(np.float64) for b in ref_p["b"]])
+    for it in range(3):
+        sup, qry = make_batch(cfg, it, "cpu")
+        loss = ctx.meta_train_step_table(_to_dev(sup, dev), _to_dev(qry, dev), dp, cfg.inner_lr, K, order, beta, table)
+        assert float(table.abs().max()) == 0.0, "the accumulator is cleared by the update"
+        ref_p, ref_loss = O.meta_train_step(oracle_model(cfg), ref_p, sup.numpy(), qry.numpy(), cfg.inner_lr, K, order, beta)
+        e = {"loss": abs(float(loss.item()) - ref_loss) / abs(ref_loss),
+             "emb": max(rel_err(dp.emb.cpu().numpy(), ref_p["emb"]))}
+        for l in range(len(ref_p["W"])):
+            e[f"W{l}"] = max(rel_err(dp.W[l].cpu().numpy(), ref_p["W"][l]))
+            e[f"b{l}"] = max(rel_err(dp.b[l].cpu().numpy(), ref_p["b"][l]))
+        d_emb = max(rel_err(dp.emb.cpu().numpy().astype(np.float64) - params.emb.numpy(), ref_p["emb"] - params.emb.numpy()))
+        print(f"table train it {it} waves={waves}", {k: f"{v:.1e}" for k, v in e.items()}, f"moved: emb {d_emb:.1e}", flush=True)
+        assert all(v <= TOL_FP32 for v in e.values()), (it, e)
+        assert d_emb <= 5 * TOL_FP32, (it, d_emb)
+    ctx.close()
+
+
 @pytest.mark.parametrize("bf,K,order", [(0, 1, 2), (0, 2, 2), (0, 3, 1), (1, 2, 2)])
 def test_dense_only_adaptation(gm, bf, K, order):
     """gm_configure("adapt_rows", 0): the inner loop adapts theta only; every output against the oracle's
